@@ -1,0 +1,119 @@
+"""MetaSD generation loop of the oracle: Alg. 1 (generic loop), Alg. 2 (UCB policy) and one
+speculative-sampling round per Alg. 3, written step by step on top of the C primitives.
+
+TEST INFRASTRUCTURE ONLY (see the package docstring).
+
+Bookkeeping.  ``hist[0:l]`` are the committed tokens.  The target's KV cache holds positions
+``[0, l-1)``: the last committed token has no KV yet, it is row 0 of the next verification
+block.  Drafter k's KV cache holds positions ``[0, c[k])`` with ``c[k] <= l-1``; when drafter k
+is selected it first consumes every committed token it has not seen (App. "Switching costs":
+the missing KV entries are recomputed when a drafter is switched in).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+
+@dataclass
+class SdState:
+    hist: np.ndarray                 # int32 [max_ctx]
+    l: int                           # number of committed tokens
+    c: list                          # per-drafter number of positions already in its KV cache
+    t: int = 0                       # completed rounds (Alg. 2's t)
+    log: list = field(default_factory=list)
+
+
+def sd_round(target, drafter, k: int, st: SdState, gamma: int, T: float, seed: int, seq: int = 0) -> dict:
+    """One draft -> verify -> accept round (Alg. 3 body) with drafter ``k``; commits the result."""
+    from . import STREAM_ACCEPT, STREAM_DRAFT, STREAM_RESIDUAL, accept, sample, uniform
+
+    l = st.l
+    V = target.desc["vocab"]
+    Q = np.empty((gamma, V), np.float32)
+    d = np.empty(gamma, np.int32)
+    draft_margin = np.empty(gamma, np.float64)
+    # --- draft: catch-up block (ends with the last committed token), then gamma-1 single steps
+    Q[0] = drafter.forward(st.hist[st.c[k]: l], st.c[k], "last")
+    for j in range(gamma):
+        if j > 0:
+            Q[j] = drafter.forward(st.hist[l + j - 1: l + j], l + j - 1, "last")
+        u = uniform(seed, seq, st.t, j, STREAM_DRAFT)
+        d[j], draft_margin[j] = sample(Q[j], T, u, with_margin=True)
+        st.hist[l + j] = d[j]
+    # --- verify: one target pass over [x_last, d_1 .. d_gamma]
+    P = target.forward(st.hist[l - 1: l + gamma], l - 1, "all")
+    # --- accept
+    u_acc = np.array([uniform(seed, seq, st.t, j, STREAM_ACCEPT) for j in range(gamma)], np.float32)
+    u_res = uniform(seed, seq, st.t, 0, STREAM_RESIDUAL)
+    r = accept(P, Q, d, T, u_acc, u_res)
+    n = r["n_acc"]
+    # --- commit: d_1..d_n stay, the emitted token follows them
+    st.hist[l + n] = r["token"]
+    st.l = l + n + 1
+    st.c[k] = min(l + n, l + gamma - 1)
+    out = dict(k=k, round=st.t, l_before=l, d=d.copy(), P=P, Q=Q, u_acc=u_acc, u_res=u_res,
+               draft_margin=draft_margin, **r)
+    st.t += 1
+    return out
+
+
+def generate(target, drafters, prompt, n_new: int, gamma: int, T: float, seed: int, beta: float,
+             reward: str = "BE", seq: int = 0, kv_prefilled: bool = False, policy=None,
+             before_round=None, keep_logits: bool = False) -> dict:
+    """MetaSD-UCB generation (Alg. 2).  Stops when ``n_new`` tokens beyond the prompt exist
+    (the check ``l < B`` is made before every round, also during the initial sweep); the
+    output is truncated to exactly ``n_new`` new tokens.
+
+    policy: optional callable(round_index) -> arm overriding the bandit's choice (the bandit is
+    still updated), used to test single-drafter runs.
+    before_round: optional callable(state) run before each round (e.g. to swap drafter heads).
+    """
+    from . import Ucb, reward_bd, reward_be
+
+    prompt = np.asarray(prompt, np.int32)
+    l0 = int(prompt.shape[0])
+    B = l0 + n_new
+    hist = np.zeros(target.max_ctx, np.int32)
+    hist[:l0] = prompt
+    st = SdState(hist=hist, l=l0, c=[0] * len(drafters))
+    if kv_prefilled:
+        st.c = [l0 - 1] * len(drafters)
+    elif l0 > 1:
+        target.forward(prompt[: l0 - 1], 0, None)
+    bandit = Ucb(len(drafters), beta)
+    rounds = []
+    while st.l < B:
+        if before_round is not None:
+            before_round(st)
+        k, scores = bandit.select(with_scores=True)
+        if policy is not None:
+            k = int(policy(st.t))
+        r = sd_round(target, drafters[k], k, st, gamma, T, seed, seq)
+        rew = reward_be(r["n_acc"], gamma) if reward == "BE" else reward_bd(r["bd"])
+        bandit.update(k, rew)
+        r["reward"] = rew
+        r["scores"] = scores
+        if not keep_logits:
+            r.pop("P"), r.pop("Q")
+        rounds.append(r)
+    return dict(tokens=st.hist[l0:B].copy(), total_len=st.l, rounds=rounds, state=st,
+                mu=bandit.mu, n=bandit.n, t=bandit.t)
+
+
+def ar_decode(target, prompt, n_new: int, T: float = 0.0, seed: int = 0, seq: int = 0) -> np.ndarray:
+    """Plain autoregressive decoding with the target alone: one token per forward pass.
+    T == 0 is greedy; T > 0 draws with the residual-stream uniform of round i."""
+    from . import STREAM_RESIDUAL, sample, uniform
+
+    prompt = np.asarray(prompt, np.int32)
+    l0 = int(prompt.shape[0])
+    out = np.empty(n_new, np.int32)
+    logits = target.forward(prompt, 0, "last")
+    for i in range(n_new):
+        u = uniform(seed, seq, i, 0, STREAM_RESIDUAL)
+        out[i] = sample(logits, T, u)
+        if i + 1 < n_new:
+            logits = target.forward(out[i: i + 1], l0 + i, "last")
+    return out

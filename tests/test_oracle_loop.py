@@ -1,0 +1,72 @@
+"""The oracle's MetaSD loop (Alg. 1 / Alg. 2 around Alg. 3 rounds) on the tiny configuration."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+
+
+@pytest.fixture(scope="module")
+def c1():
+    cfg = W.config1()
+    td, tw = cfg["target"]
+    cfg["tw_np"] = W.to_numpy(tw)
+    cfg["dw_np"] = [W.to_numpy(dw) for _, dw in cfg["drafters"]]
+    return cfg
+
+
+def models(cfg):
+    td, _ = cfg["target"]
+    T = oracle.Model(td, cfg["tw_np"], cfg["max_ctx"])
+    D = [oracle.Model(dd, w, cfg["max_ctx"]) for (dd, _), w in zip(cfg["drafters"], cfg["dw_np"])]
+    return T, D
+
+
+def test_greedy_sd_equals_target_only_greedy(c1):
+    """Speculative decoding is lossless (Sec. 2.1, Alg. 3): with T = 0 every drafter, also a
+    badly aligned one, must reproduce plain greedy decoding of the target token for token."""
+    T, _ = models(c1)
+    ref = oracle.ar_decode(T, c1["prompt"], c1["n_new"], T=0.0)
+    accs = []
+    for pol in (None, 0, 1, 2):
+        T, D = models(c1)
+        out = oracle.generate(T, D, c1["prompt"], c1["n_new"], c1["gamma"], 0.0, c1["seed"], c1["beta"],
+                              policy=None if pol is None else (lambda t, a=pol: a))
+        assert np.array_equal(out["tokens"], ref), pol
+        # accounting: B = tau + sum N_acc (proof of the stopping-time lemma), before truncation
+        tau = len(out["rounds"])
+        assert out["total_len"] - len(c1["prompt"]) == tau + sum(r["n_acc"] for r in out["rounds"])
+        assert out["t"] == tau and out["n"].sum() == tau
+        accs.append(np.mean([r["n_acc"] for r in out["rounds"]]))
+    # drafter 0 is the exact early exit; drafter 2 carries the largest head noise
+    assert accs[1] >= accs[3]
+
+
+def test_initial_sweep_visits_arms_in_order(c1):
+    T, D = models(c1)
+    out = oracle.generate(T, D, c1["prompt"], 24, c1["gamma"], 1.0, c1["seed"], c1["beta"])
+    assert [r["k"] for r in out["rounds"][:3]] == [0, 1, 2]
+    assert all(np.isnan(r["scores"]).all() for r in out["rounds"][:3])
+    assert all(0 <= r["reward"] <= 1 for r in out["rounds"])
+    assert len(out["tokens"]) == 24 and out["tokens"].min() >= 0 and out["tokens"].max() < 512
+
+
+def test_sampling_run_is_reproducible_and_seed_dependent(c1):
+    outs = []
+    for seed in (1, 1, 2):
+        T, D = models(c1)
+        outs.append(oracle.generate(T, D, c1["prompt"], 32, c1["gamma"], 1.0, seed, c1["beta"], reward="BD")["tokens"])
+    assert np.array_equal(outs[0], outs[1]) and not np.array_equal(outs[0], outs[2])
+
+
+def test_drafter_catch_up_after_switch(c1):
+    """A drafter that sat out several rounds first consumes the tokens it missed: its logits for
+    the next position equal those of a fresh copy fed the whole committed sequence."""
+    T, D = models(c1)
+    out = oracle.generate(T, D, c1["prompt"], 20, c1["gamma"], 0.0, c1["seed"], c1["beta"],
+                          policy=lambda t: 0 if t < 4 else 1, keep_logits=True)
+    st = out["state"]
+    r = next(r for r in out["rounds"] if r["k"] == 1)
+    fresh = oracle.Model(c1["drafters"][1][0], c1["dw_np"][1], c1["max_ctx"])
+    want = fresh.forward(st.hist[: r["l_before"]], 0, "last")
+    assert np.abs(want - r["Q"][0]).max() < 1e-5
