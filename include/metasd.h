@@ -1,0 +1,201 @@
+/*
+ * metasd.h - C ABI of the MI355X (gfx950) MetaSD hot-path library.
+ *
+ * One round of MetaSD (Alg. 1 of the paper) is
+ *     k = metasd_bandit_select()            Alg. 2, selection line / initial sweep
+ *     metasd_draft(k, gamma)                Alg. 3, drafting loop: gamma tokens from drafter k
+ *     metasd_verify(gamma)                  Alg. 3, "in parallel compute E+1 sets of logits"
+ *     metasd_accept(gamma, ...)             Alg. 3, accept test / residual resample / bonus token
+ *     metasd_bandit_update(k, n_acc, ...)   Alg. 2, mean update with the BE (or BD, Def. 2) reward
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative METASD_E_* code; nothing is thrown or
+ *     aborted across this boundary.  metasd_last_error() gives a message for the last failure.
+ *   - "device" pointers are HIP device memory owned by the CALLER (weights, KV caches,
+ *     workspace); the library never allocates or frees device memory.  "host" pointers are
+ *     ordinary host memory.  The library owns only its host-side context and one small
+ *     pinned host buffer for results.
+ *   - All device work is enqueued on the HIP stream given to metasd_create (NULL = default
+ *     stream); draft and verify are asynchronous, accept synchronises the stream.
+ *   - This version runs one sequence per context (config.batch must be 1) for draft / verify;
+ *     metasd_accept_logits and metasd_sample_logits take any number of rows.
+ *
+ * Model weights.  A model is described by metasd_model_desc and a table of device pointers in
+ * this order: embed [V][d]; per layer: attn_norm [d], wq [H*hd][d], wk [KH*hd][d],
+ * wv [KH*hd][d], wo [d][H*hd], ffn_norm [d], w_gate [f][d] (NULL when act == GELU),
+ * w_up [f][d], w_down [d][f]; then final_norm [d], lm_head [V][d].  hd = d / H.
+ *   dtype METASD_F32: every tensor is float, matrices row-major [out][in].
+ *   dtype METASD_BF16: every tensor is bf16; embed and the norm gains are plain row-major, every
+ *     matrix (wq .. w_down, lm_head) must be in the library's streaming-tile order produced by
+ *     metasd_pack_weight (same byte size as the row-major matrix).
+ *
+ * KV cache of a model (device, caller-owned): element type = model dtype, layout
+ *     [layer][2 (K, V)][kv_head][max_ctx][hd],  bytes = metasd_kv_bytes().
+ */
+#ifndef METASD_H
+#define METASD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define METASD_OK 0
+#define METASD_E_INVALID (-1)   /* bad argument: NULL, k out of range, gamma out of range, unsupported shape */
+#define METASD_E_OVERFLOW (-2)  /* the KV cache / token history would exceed max_ctx */
+#define METASD_E_ORDER (-3)     /* call-order violation (e.g. verify before draft) */
+#define METASD_E_HIP (-4)       /* a HIP call failed; message retained */
+#define METASD_E_WORKSPACE (-5) /* workspace too small; required size in the message */
+
+#define METASD_GELU 0
+#define METASD_SWIGLU 1
+#define METASD_F32 0
+#define METASD_BF16 1
+#define METASD_REWARD_BE 0 /* block efficiency  N_acc / N_max */
+#define METASD_REWARD_BD 1 /* block divergence, Def. 2 */
+#define METASD_MAX_GAMMA 15 /* a verification block is gamma+1 <= 16 rows */
+#define METASD_MAX_K 64
+
+typedef struct metasd_ctx metasd_ctx; /* opaque; freed by metasd_destroy */
+
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab;
+    int32_t act;   /* METASD_GELU | METASD_SWIGLU */
+    int32_t dtype; /* METASD_F32 | METASD_BF16 */
+    float rms_eps, rope_theta;
+} metasd_model_desc;
+
+typedef struct {
+    int32_t K;          /* number of drafters, 1..METASD_MAX_K */
+    int32_t gamma_max;  /* largest draft length N_max that will be used, 1..METASD_MAX_GAMMA */
+    int32_t batch;      /* must be 1 */
+    int32_t max_ctx;    /* capacity of the token history and of every KV cache, in positions */
+    float temperature;  /* 0 => greedy; otherwise p = softmax(logits / T) for target and drafter */
+    int32_t reward;     /* METASD_REWARD_BE | METASD_REWARD_BD (used by metasd_bandit_update) */
+    double ucb_beta;    /* exploration strength beta of Alg. 2 */
+    uint64_t seed;      /* Philox key of all uniforms */
+} metasd_config;
+
+/* ---- sizes -------------------------------------------------------------------------------- */
+
+/* Bytes of one model's KV cache for max_ctx positions. */
+int32_t metasd_kv_bytes(const metasd_model_desc* m, int32_t max_ctx, size_t* bytes_out);
+
+/* Bytes of device workspace metasd_create needs for this configuration. */
+int32_t metasd_workspace_bytes(const metasd_config* cfg, const metasd_model_desc* target,
+                               const metasd_model_desc* drafters /*[K]*/, size_t* bytes_out);
+
+/* Re-order a row-major bf16 matrix W[n_out][n_in] (device) into streaming-tile order (device,
+ * n_out*n_in*2 bytes, must not alias src): 1 KiB tiles of 16 output rows x 32 inputs, tile
+ * (t, c) at ((t * n_in/32) + c) KiB, lane l of a wavefront owning bytes [16 l, 16 l + 16) =
+ * W[16 t + l%16][32 c + 8 (l/16) .. +8].  Requires n_out % 16 == 0 and n_in % 32 == 0.
+ * Asynchronous on `hip_stream`. */
+int32_t metasd_pack_weight(void* dst, const void* src, int32_t n_out, int32_t n_in, void* hip_stream);
+
+/* ---- context ------------------------------------------------------------------------------ */
+
+/* Create a context.  Descriptors and pointer tables are copied; the device memory they point
+ * to stays owned by the caller and must outlive the context.  target_kv / drafter_kv[k] are
+ * KV caches of metasd_kv_bytes() each; workspace is >= metasd_workspace_bytes() and 256-byte
+ * aligned.  Errors: INVALID (NULL, unsupported shape: see metasd_last_error), WORKSPACE, HIP. */
+int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_model_desc* target,
+                      const metasd_model_desc* drafters /*[K]*/, const void* const* target_weights,
+                      const void* const* const* drafter_weights /*[K] tables*/, void* target_kv,
+                      void* const* drafter_kv /*[K]*/, void* workspace, size_t workspace_bytes, void* hip_stream);
+int32_t metasd_destroy(metasd_ctx*);
+
+/* Start a new query (Alg. 1 input "initial prompt x^{1:l}"): upload n >= 1 prompt tokens (host),
+ * reset the round counter and the bandit (the bandit is re-initialised for every query).
+ * kv_prefilled == 0: the target prefills positions [0, n-1) now (asynchronously); drafters start
+ *   empty and catch up the first time they are selected.
+ * kv_prefilled != 0: the caller has already written the KV entries of positions [0, n-1) of
+ *   the target and of every drafter (synthetic or externally computed context).
+ * Errors: INVALID, OVERFLOW (n + gamma_max + 1 > max_ctx), HIP. */
+int32_t metasd_set_context(metasd_ctx*, int32_t seq, const int32_t* tokens, int32_t n, int32_t kv_prefilled);
+
+/* Replace entry `index` of the weight table of model `model` (-1 = target, k = drafter k) with
+ * another device pointer of the same shape and layout (e.g. a drafter's LM head). */
+int32_t metasd_swap_weight(metasd_ctx*, int32_t model, int32_t index, const void* dev_ptr);
+
+/* ---- bandit (host, fp64; Alg. 2) ------------------------------------------------------------ */
+
+/* Arm for the next round: arms 0..K-1 once each in index order, afterwards
+ * argmax_i mu_i + beta * sqrt(2 ln t / n_i), t = completed rounds, lowest index on ties. */
+int32_t metasd_bandit_select(metasd_ctx*, int32_t seq, int32_t* k_out);
+/* Feed back the round's reward to arm k: BE reward n_acc / gamma, or, when the context was
+ * created with METASD_REWARD_BD, bd_reward (the value metasd_accept reported).  mu_k becomes
+ * (mu_k n_k + r)/(n_k + 1), n_k and t advance.  Errors: INVALID. */
+int32_t metasd_bandit_update(metasd_ctx*, int32_t seq, int32_t k, int32_t n_acc, int32_t gamma, double bd_reward);
+/* Copy out mu[K], n[K], t (any pointer may be NULL). */
+int32_t metasd_bandit_state(const metasd_ctx*, int32_t seq, double* mu, int32_t* n, int32_t* t);
+
+/* ---- one speculative-sampling round (Alg. 3) -------------------------------------------------- */
+
+/* Draft gamma tokens with drafter k[0]: the drafter first consumes the committed tokens it has
+ * not processed yet (ending with the last committed token), then runs gamma-1 single-token steps.
+ * Token j is argmax (T = 0) or the inverse-CDF draw of softmax(logits/T) with the Philox uniform
+ * at (seq, round, j, stream 2).  Draft tokens and drafter logits stay on the device.
+ * Errors: INVALID (k, gamma), OVERFLOW, ORDER (no context set / round already drafted), HIP. */
+int32_t metasd_draft(metasd_ctx*, const int32_t* k /*[batch] host*/, int32_t gamma);
+
+/* Target forward over the gamma+1 rows [last committed token, d_1 .. d_gamma] at positions
+ * l-1 .. l-1+gamma against the KV cache (causal inside the block); appends their K/V and leaves
+ * fp32 logits [gamma+1][V] on the device.  Errors: INVALID, ORDER (draft not done), HIP. */
+int32_t metasd_verify(metasd_ctx*, int32_t gamma);
+
+/* Accept test u_j < min(1, p_j(d_j)/q_j(d_j)) for j < gamma with the uniform at (seq, round, j,
+ * stream 0); N_acc = index of the first failure (gamma if none); the emitted token is drawn by
+ * inverse CDF with the uniform at (seq, round, 0, stream 1) from norm(max(0, p_n - q_n)) if
+ * n < gamma, else from p_gamma (greedy: accept iff d_j == argmax, emit argmax).  Synchronises,
+ * then commits: history, KV lengths, round counter.  Outputs are host arrays of `batch` entries
+ * (mask_out: bit j = raw test j; bd_out: mean over j of sum_v min(p_j, q_j)); any may be NULL.
+ * Errors: INVALID, ORDER (verify not done), HIP. */
+int32_t metasd_accept(metasd_ctx*, int32_t gamma, int32_t* n_acc_out, int32_t* token_out, uint32_t* mask_out,
+                      double* bd_out);
+
+/* ---- stand-alone kernels on caller-supplied logits (device) ------------------------------------ */
+
+/* Accept step on rows of logits: P [rows][gamma+1][V], Q [rows][gamma][V] fp32, d [rows][gamma]
+ * int32, all device.  Row b uses the uniforms of sequence id seq0 + b at `round`.  Outputs
+ * (device, any of mask/bd may be NULL): n_acc [rows], token [rows], mask [rows] (bit j), bd
+ * [rows][gamma] doubles (sum_v min(p_j, q_j)).  scratch: device, rows*(gamma+1)*16 bytes.
+ * Requires V % 4 == 0 and V <= 32768.  Asynchronous on hip_stream. */
+int32_t metasd_accept_logits(const float* P, const float* Q, const int32_t* d, int32_t rows, int32_t gamma,
+                             int32_t V, float temperature, uint64_t seed, uint32_t round, uint32_t seq0,
+                             int32_t* n_acc, int32_t* token, uint32_t* mask, double* bd, void* scratch,
+                             void* hip_stream);
+
+/* Token draw per row of logits [rows][V] (device): argmax for T = 0, else inverse CDF of
+ * softmax(logits/T) with the uniform at (seq0 + row, round, pos, stream 2).  tok [rows] device. */
+int32_t metasd_sample_logits(const float* logits, int32_t rows, int32_t V, float temperature, uint64_t seed,
+                             uint32_t round, uint32_t pos, uint32_t seq0, int32_t* tok, void* hip_stream);
+
+/* Raw Philox4x32-10 output words for counters (c0_start + i, c1, c2, c3), i < n, key = seed:
+ * out [n][4] uint32 device.  Used to check the generator against another implementation. */
+int32_t metasd_philox_words(uint64_t seed, uint32_t c0_start, int32_t n, uint32_t c1, uint32_t c2, uint32_t c3,
+                            uint32_t* out, void* hip_stream);
+
+/* ---- introspection ---------------------------------------------------------------------------- */
+
+#define METASD_PEEK_P 0     /* float [gamma_max+1][V]  target logits of the last verify */
+#define METASD_PEEK_Q 1     /* float [gamma_max][V]    drafter logits of the last draft */
+#define METASD_PEEK_HIST 2  /* int32 [max_ctx]         token history (committed + speculative) */
+#define METASD_PEEK_BD 3    /* double [gamma_max]      sum_v min(p_j, q_j) of the last accept */
+#define METASD_PEEK_DRAFT 4 /* int32 [gamma_max]       draft tokens d_1..d_gamma of the last draft */
+/* Device pointer and byte size of an internal buffer (valid until metasd_destroy). */
+int32_t metasd_peek(metasd_ctx*, int32_t what, void** dev_ptr_out, size_t* bytes_out);
+
+/* Committed length l, number of positions in the KV cache of model (-1 target, k drafter),
+ * completed rounds.  Any pointer may be NULL. */
+int32_t metasd_state(const metasd_ctx*, int32_t model, int32_t* l_out, int32_t* kv_len_out, int32_t* round_out);
+
+/* Message of the last error on this context (ctx == NULL: of the last context-free call on
+ * this thread).  Never NULL. */
+const char* metasd_last_error(const metasd_ctx*);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* METASD_H */

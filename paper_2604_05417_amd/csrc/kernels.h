@@ -1,0 +1,794 @@
+// Device kernels of the MetaSD hot path for gfx950 (CDNA4): wave64, MFMA, LDS.
+//
+// Every kernel here is launched by metasd.hip; shapes are validated on the host before launch
+// (see check_model / the asserts next to each launcher), kernels themselves only guard ragged tails.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace msd {
+
+typedef uint16_t bf16_t;  // raw bf16 bit pattern
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ------------------------------------------------------------------------------------------
+// element conversion
+
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even float -> bf16 (inf / nan pass through by truncation)
+__device__ __forceinline__ bf16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7f800000u) != 0x7f800000u) u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct El;
+template <> struct El<float> {
+    static __device__ __forceinline__ float ld(float v) { return v; }
+    static __device__ __forceinline__ float st(float v) { return v; }
+};
+template <> struct El<bf16_t> {
+    static __device__ __forceinline__ float ld(bf16_t v) { return bf2f(v); }
+    static __device__ __forceinline__ bf16_t st(float v) { return f2bf(v); }
+};
+
+// ------------------------------------------------------------------------------------------
+// wavefront (64 lanes) reductions
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+// inclusive prefix sum over the lanes of a wavefront
+__device__ __forceinline__ double wave_scan_incl(double v, int lane) {
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        double t = __shfl_up(v, o, 64);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC'11)
+// counter (c0..c3), key = 64-bit seed; ten rounds, Weyl-sequence key schedule.
+
+__device__ __forceinline__ void philox4x32_10(uint64_t seed, uint32_t& c0, uint32_t& c1, uint32_t& c2, uint32_t& c3) {
+    uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+}
+
+// uniform in [0,1): top 24 bits of word 0 at counter (seq, round, pos, stream)
+__device__ __forceinline__ float philox_uniform(uint64_t seed, uint32_t seq, uint32_t round, uint32_t pos, uint32_t stream) {
+    uint32_t c0 = seq, c1 = round, c2 = pos, c3 = stream;
+    philox4x32_10(seed, c0, c1, c2, c3);
+    return (float)(c0 >> 8) * (1.0f / 16777216.0f);
+}
+
+__global__ void philox_words_kernel(uint64_t seed, uint32_t c0_start, int n, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t* out) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    uint32_t a = c0_start + (uint32_t)i, b = c1, c = c2, d = c3;
+    philox4x32_10(seed, a, b, c, d);
+    out[4 * i + 0] = a; out[4 * i + 1] = b; out[4 * i + 2] = c; out[4 * i + 3] = d;
+}
+
+// ------------------------------------------------------------------------------------------
+// embedding gather: h[r][:] = E[tok[r]][:]          grid (m), block 256
+
+template <typename T>
+__global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restrict__ E, int d, float* __restrict__ h) {
+    const int r = blockIdx.x;
+    const size_t t = (size_t)tok[r];
+    for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)r * d + i] = El<T>::ld(E[t * d + i]);
+}
+
+// ------------------------------------------------------------------------------------------
+// residual add of split-K partial sums + RMSNorm:      grid (m), block 256
+//   h[r] += sum_s part[s][r]   (skipped when nsplit == 0)
+//   xn[r] = T( h[r] / sqrt(mean(h[r]^2) + eps) * gain )
+
+template <typename T>
+__global__ __launch_bounds__(256) void addnorm_kernel(float* __restrict__ h, const float* __restrict__ part, int nsplit,
+                                                      size_t sstride, int d, const T* __restrict__ gain, float eps,
+                                                      T* __restrict__ xn) {
+    __shared__ float red[4];
+    const int r = blockIdx.x;
+    float* hr = h + (size_t)r * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float v = hr[i];
+        if (nsplit > 0) {
+            float y = 0.f;
+            for (int s = 0; s < nsplit; ++s) y += part[(size_t)s * sstride + (size_t)r * d + i];
+            v += y;
+            hr[i] = v;
+        }
+        ss += v * v;
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = (red[0] + red[1]) + (red[2] + red[3]);
+    const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+    if (xn)
+        for (int i = threadIdx.x; i < d; i += 256) xn[(size_t)r * d + i] = El<T>::st(hr[i] * inv * El<T>::ld(gain[i]));
+}
+
+// out[i] = sum_s part[s][i]                         (only for logits when the head GEMM is split)
+__global__ void sum_partials_kernel(const float* __restrict__ part, int nsplit, size_t sstride, size_t n, float* __restrict__ out) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float y = 0.f;
+    for (int s = 0; s < nsplit; ++s) y += part[(size_t)s * sstride + i];
+    out[i] = y;
+}
+
+// ------------------------------------------------------------------------------------------
+// fp32 skinny GEMM (fp32 models): one wavefront per output feature, lanes stride over K.
+//   out[r][n] = sum_k x[r][k] * W[n][k],  r < m <= 16,  W row-major [n][K], K % 4 == 0.
+// Up to three matrices are concatenated along n (boundaries n0 <= n1 <= N).     grid ceil(N/4), block 256
+
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ x, int ldx, int m, int K,
+                                                       const float* __restrict__ W0, const float* __restrict__ W1,
+                                                       const float* __restrict__ W2, int n0, int n1, int N,
+                                                       float* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= N) return;
+    const float* w = n < n0 ? W0 + (size_t)n * K : (n < n1 ? W1 + (size_t)(n - n0) * K : W2 + (size_t)(n - n1) * K);
+    float acc[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int k = lane * 4; k < K; k += 256) {
+        const float4 wv = *reinterpret_cast<const float4*>(w + k);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            if (r < m) {
+                const float4 xv = *reinterpret_cast<const float4*>(x + (size_t)r * ldx + k);
+                acc[r] += wv.x * xv.x + wv.y * xv.y + wv.z * xv.z + wv.w * xv.w;
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        if (r < m) {
+            const float s = wave_sum(acc[r]);
+            if (lane == 0) out[(size_t)r * N + n] = s;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// bf16 skinny GEMM on MFMA with weights streamed from HBM in tile order.
+//
+// Weights are in streaming-tile order (see pack_weight_kernel): tile (t, c) is 1 KiB holding
+// output features 16t..16t+15 and inputs 32c..32c+31; lane l owns 16 bytes = 8 consecutive inputs
+// 32c + 8(l/16).. of feature 16t + l%16 - exactly the A operand of v_mfma_f32_16x16x32_bf16, so
+// one wavefront load instruction reads one contiguous KiB.  The activations (m <= 16 rows) are
+// the B operand, staged once per workgroup in LDS.  D[i][j] = sum_k A[i][k] B[k][j]: lane l gets
+// D[4(l/16)+v][l%16], v = 0..3, i.e. 4 consecutive output features of activation row l%16.
+//
+// Work split: workgroup = (tile group tg, k-split ks); its 4 wavefronts take tiles
+// tg*tpb + wave, +4, ...; the k-split covers chunks [ks*cps, ks*cps + cps).  Partial sums go to
+// out[ks][r][n] (row stride N, split stride m*N) and are added by the consumer kernel.
+// Up to three matrices are concatenated along n at tile boundaries t0 <= t1 <= ntiles.
+//   grid (ceil(ntiles/tpb) * ksplit), block 256, dynamic LDS m * (cps*4 + 1) * 16 bytes.
+
+constexpr int GEMM_U = 8;  // tiles in flight per wavefront (8 KiB)
+
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ x, int ldx, int m, int K,
+                                                        const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
+                                                        const bf16_t* __restrict__ W2, int t0, int t1, int ntiles,
+                                                        float* __restrict__ out, int N, int ksplit, int cps, int tpb) {
+    extern __shared__ uint4 xs[];
+    const int kchunks = K >> 5;
+    const int ks = blockIdx.x % ksplit, tg = blockIdx.x / ksplit;
+    const int c0 = ks * cps;
+    const int nc = min(cps, kchunks - c0);
+    const int rs = cps * 4 + 1;  // LDS row stride in 16-byte units (+1 pads away bank conflicts)
+    for (int idx = threadIdx.x; idx < m * nc * 4; idx += 256) {
+        const int r = idx / (nc * 4), c = idx - r * (nc * 4);
+        xs[r * rs + c] = *reinterpret_cast<const uint4*>(x + (size_t)r * ldx + (size_t)c0 * 32 + (size_t)c * 8);
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = lane & 15, g = lane >> 4;
+    const bool rowok = row < m;
+    const uint4* xa = xs + (rowok ? row : 0) * rs + g;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    for (int tt = wave; tt < tpb; tt += 4) {
+        const int t = tg * tpb + tt;
+        if (t >= ntiles) break;
+        const bf16_t* W;
+        int tl;
+        if (t < t0) { W = W0; tl = t; }
+        else if (t < t1) { W = W1; tl = t - t0; }
+        else { W = W2; tl = t - t1; }
+        const u32x4* wp = reinterpret_cast<const u32x4*>(W) + ((size_t)tl * kchunks + c0) * 64 + lane;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        int c = 0;
+        for (; c + GEMM_U <= nc; c += GEMM_U) {
+            u32x4 w[GEMM_U];
+#pragma unroll
+            for (int u = 0; u < GEMM_U; ++u) w[u] = __builtin_nontemporal_load(wp + (size_t)(c + u) * 64);
+#pragma unroll
+            for (int u = 0; u < GEMM_U; ++u) {
+                uint4 a = xa[(c + u) * 4];
+                if (!rowok) a = zero;
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, a), acc, 0, 0, 0);
+            }
+        }
+        for (; c < nc; ++c) {
+            const u32x4 w = __builtin_nontemporal_load(wp + (size_t)c * 64);
+            uint4 a = xa[c * 4];
+            if (!rowok) a = zero;
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, a), acc, 0, 0, 0);
+        }
+        if (rowok) {
+            float* o = out + (size_t)ks * m * N + (size_t)row * N + (size_t)t * 16 + g * 4;
+            *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        }
+    }
+}
+
+// Row-major bf16 W[n_out][n_in] -> streaming-tile order.  One thread per 16-byte piece.
+__global__ void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int n_out, int n_in) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // index of a 16-byte piece in dst
+    const size_t total = (size_t)n_out * n_in / 8;
+    if (i >= total) return;
+    const int kchunks = n_in >> 5;
+    const int lane = (int)(i & 63);
+    const size_t tile = i >> 6;
+    const int c = (int)(tile % kchunks);
+    const size_t t = tile / kchunks;
+    const size_t rowi = t * 16 + (lane & 15);
+    const size_t col = (size_t)c * 32 + (size_t)(lane >> 4) * 8;
+    dst[i] = src[(rowi * n_in + col) / 8];
+}
+
+// ------------------------------------------------------------------------------------------
+// RoPE (rotate-half pairing, angle = pos * theta^(-2i/hd)) on q and k, K/V cache append.
+//   part: split-K partials of the fused q|k|v projection, [s][r][N], N = (H + 2 KH) * hd.
+//   q out [m][H*hd]; cache planes [kv_head][max_ctx][hd].     grid (H + 2KH, m), block 64
+
+template <typename T>
+__global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int N, int pos0, int H, int KH,
+                               int hd, float theta, T* __restrict__ q, T* __restrict__ kc, T* __restrict__ vc, int max_ctx) {
+    const int head = blockIdx.x, r = blockIdx.y, i = threadIdx.x, half = hd >> 1;
+    if (i >= half) return;
+    const size_t col = (size_t)r * N + (size_t)head * hd + i;
+    float a = 0.f, b = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+        a += part[(size_t)s * sstride + col];
+        b += part[(size_t)s * sstride + col + half];
+    }
+    const int pos = pos0 + r;
+    if (head < H + KH) {
+        const double freq = pow((double)theta, -2.0 * (double)i / (double)hd);
+        double sn, cs;
+        sincos((double)pos * freq, &sn, &cs);
+        const float ra = (float)((double)a * cs - (double)b * sn);
+        const float rb = (float)((double)a * sn + (double)b * cs);
+        a = ra; b = rb;
+    }
+    T* dst;
+    if (head < H) dst = q + (size_t)r * H * hd + (size_t)head * hd;
+    else if (head < H + KH) dst = kc + ((size_t)(head - H) * max_ctx + pos) * hd;
+    else dst = vc + ((size_t)(head - H - KH) * max_ctx + pos) * hd;
+    dst[i] = El<T>::st(a);
+    dst[i + half] = El<T>::st(b);
+}
+
+// ------------------------------------------------------------------------------------------
+// Decode attention over the KV cache for a block of m <= 16 query rows at positions pos0..pos0+m-1
+// (row r sees positions 0..pos0+r), split along the KV length in chunks of 128 positions.
+// K and V chunks are staged in LDS with coalesced 16-byte loads; scores, softmax and PV in fp32.
+//   partial kernel: grid (nchunks, H), block 256 -> part[h][c][16][HD+2] = (o[HD], max, sum)
+//   combine kernel: grid (H, m), block HD        -> out[r][h*HD + :] = T( sum_c o_c e^{m_c-M} / sum_c l_c e^{m_c-M} )
+
+constexpr int ATT_CH = 128;
+
+template <typename T, int HD>
+__global__ __launch_bounds__(256) void attn_partial_kernel(const T* __restrict__ q, const T* __restrict__ kc,
+                                                           const T* __restrict__ vc, int m, int pos0, int H, int KH,
+                                                           int max_ctx, float scale, float* __restrict__ part, int nchunks) {
+    constexpr int EPV = 16 / (int)sizeof(T);     // elements per 16-byte piece
+    constexpr int RS = HD + EPV;                 // padded LDS row stride (elements)
+    constexpr int VPR = HD / EPV;                // 16-byte pieces per row
+    constexpr int KVB = ATT_CH * RS * (int)sizeof(T);
+    constexpr int REDB = 256 * 16 * 4;
+    __shared__ __align__(16) unsigned char kvraw[KVB > REDB ? KVB : REDB];
+    __shared__ float qs[16 * HD];
+    __shared__ float ss[16 * ATT_CH];
+    __shared__ float mrow[16], lrow[16];
+    T* kv = reinterpret_cast<T*>(kvraw);
+
+    const int c = blockIdx.x, h = blockIdx.y, kh = h / (H / KH);
+    const int L = pos0 + m;
+    const int p0 = c * ATT_CH;
+    const int np = min(ATT_CH, L - p0);
+    const int tid = threadIdx.x;
+
+    for (int idx = tid; idx < m * HD; idx += 256) {
+        const int r = idx / HD, i = idx - r * HD;
+        qs[idx] = El<T>::ld(q[(size_t)r * H * HD + (size_t)h * HD + i]);
+    }
+    const T* kbase = kc + ((size_t)kh * max_ctx + p0) * HD;
+    for (int idx = tid; idx < np * VPR; idx += 256) {
+        const int p = idx / VPR, v = idx - p * VPR;
+        *reinterpret_cast<uint4*>(kv + p * RS + v * EPV) = *reinterpret_cast<const uint4*>(kbase + (size_t)p * HD + v * EPV);
+    }
+    __syncthreads();
+
+    {   // scores: thread = (position p, row half rh); 8 rows per thread
+        const int p = tid & (ATT_CH - 1), rh = tid >> 7;
+        const int rbeg = rh * 8;
+        if (rbeg < m) {
+            float acc[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+            if (p < np) {
+                for (int i = 0; i < HD; i += 8) {
+                    float kf[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) kf[e] = El<T>::ld(kv[p * RS + i + e]);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        if (rbeg + j < m) {
+                            const float* qq = qs + (rbeg + j) * HD + i;
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) acc[j] += kf[e] * qq[e];
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int r = rbeg + j;
+                if (r < m) ss[r * ATT_CH + p] = (p < np && p0 + p <= pos0 + r) ? acc[j] * scale : -INFINITY;
+            }
+        }
+    }
+    __syncthreads();
+
+    {   // chunk-local softmax numerators and statistics; wave w takes rows w, w+4, ...
+        const int wave = tid >> 6, lane = tid & 63;
+        for (int r = wave; r < m; r += 4) {
+            const float a = ss[r * ATT_CH + lane], b = ss[r * ATT_CH + lane + 64];
+            const float mx = wave_max(fmaxf(a, b));
+            const float ea = (mx == -INFINITY) ? 0.f : expf(a - mx);
+            const float eb = (mx == -INFINITY) ? 0.f : expf(b - mx);
+            const float sum = wave_sum(ea + eb);
+            ss[r * ATT_CH + lane] = ea;
+            ss[r * ATT_CH + lane + 64] = eb;
+            if (lane == 0) { mrow[r] = mx; lrow[r] = sum; }
+        }
+    }
+    __syncthreads();   // all reads of the K tile are done
+
+    const T* vbase = vc + ((size_t)kh * max_ctx + p0) * HD;
+    for (int idx = tid; idx < np * VPR; idx += 256) {
+        const int p = idx / VPR, v = idx - p * VPR;
+        *reinterpret_cast<uint4*>(kv + p * RS + v * EPV) = *reinterpret_cast<const uint4*>(vbase + (size_t)p * HD + v * EPV);
+    }
+    __syncthreads();
+
+    constexpr int G = 256 / HD;   // position groups
+    const int col = tid % HD, g = tid / HD;
+    float o[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[r] = 0.f;
+    for (int p = g; p < np; p += G) {
+        const float v = El<T>::ld(kv[p * RS + col]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (r < m) o[r] += ss[r * ATT_CH + p] * v;
+    }
+    __syncthreads();   // all reads of the V tile are done: reuse it for the cross-group reduction
+    float* red = reinterpret_cast<float*>(kvraw);
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        if (r < m) red[(g * 16 + r) * HD + col] = o[r];
+    __syncthreads();
+    float* dst = part + ((size_t)h * nchunks + c) * 16 * (HD + 2);
+    for (int idx = tid; idx < m * HD; idx += 256) {
+        const int r = idx / HD, cc = idx - r * HD;
+        float s = 0.f;
+#pragma unroll
+        for (int gg = 0; gg < G; ++gg) s += red[(gg * 16 + r) * HD + cc];
+        dst[r * (HD + 2) + cc] = s;
+    }
+    if (tid < m) {
+        dst[tid * (HD + 2) + HD] = mrow[tid];
+        dst[tid * (HD + 2) + HD + 1] = lrow[tid];
+    }
+}
+
+template <typename T, int HD>
+__global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks, int H, T* __restrict__ out) {
+    const int h = blockIdx.x, r = blockIdx.y, col = threadIdx.x;
+    const float* base = part + ((size_t)h * nchunks * 16 + r) * (HD + 2);
+    const size_t cs = (size_t)16 * (HD + 2);
+    float M = -INFINITY;
+    for (int c = 0; c < nchunks; ++c) M = fmaxf(M, base[c * cs + HD]);
+    float Lsum = 0.f, o = 0.f;
+    for (int c = 0; c < nchunks; ++c) {
+        const float mc = base[c * cs + HD];
+        if (mc == -INFINITY) continue;
+        const float w = expf(mc - M);
+        Lsum += base[c * cs + HD + 1] * w;
+        o += base[c * cs + col] * w;
+    }
+    out[(size_t)r * H * HD + (size_t)h * HD + col] = El<T>::st(o / Lsum);
+}
+
+// ------------------------------------------------------------------------------------------
+// FFN activation on split-K partials:  SwiGLU  out = silu(gate) * up  (part columns: gate | up),
+//                                      GELU    out = 0.5 u (1 + erf(u / sqrt 2)).
+
+template <typename T>
+__global__ void ffn_act_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int m, int f, int act,
+                               T* __restrict__ out) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)m * f) return;
+    const int r = (int)(idx / f), i = (int)(idx - (size_t)r * f);
+    if (act == 1) {
+        float g = 0.f, u = 0.f;
+        for (int s = 0; s < nsplit; ++s) {
+            g += part[(size_t)s * sstride + (size_t)r * 2 * f + i];
+            u += part[(size_t)s * sstride + (size_t)r * 2 * f + f + i];
+        }
+        out[idx] = El<T>::st(g / (1.0f + expf(-g)) * u);
+    } else {
+        float u = 0.f;
+        for (int s = 0; s < nsplit; ++s) u += part[(size_t)s * sstride + (size_t)r * f + i];
+        out[idx] = El<T>::st(0.5f * u * (1.0f + erff(u * 0.70710678118654752f)));
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Vocab-wide softmax + accept test + residual / bonus inverse-CDF draw, one workgroup of 1024
+// threads per (sequence row, block position).  The logits of the position (target row and, for
+// j < gamma, drafter row) are read from HBM exactly once into registers: wavefront w owns the
+// contiguous vocabulary segment [2048 w, 2048 w + 2048), lane l the float4 at 256 c + 4 l of
+// chunk c = 0..7.  exp() is evaluated in fp32, every sum and the CDF in fp64.
+
+constexpr int AK_NT = 1024, AK_WAVES = 16, AK_CH = 8, AK_SEG = AK_CH * 256;  // V <= 32768
+
+struct AkShared {
+    float fmx[AK_WAVES];
+    double dsum[AK_WAVES];
+    int ival[AK_WAVES];
+    int token;
+};
+
+__device__ __forceinline__ float ak_block_max(float v, AkShared& sm, int wave, int lane) {
+    v = wave_max(v);
+    __syncthreads();
+    if (lane == 0) sm.fmx[wave] = v;
+    __syncthreads();
+    float r = sm.fmx[0];
+#pragma unroll
+    for (int w = 1; w < AK_WAVES; ++w) r = fmaxf(r, sm.fmx[w]);
+    return r;
+}
+
+__device__ __forceinline__ double ak_block_sum(double v, AkShared& sm, int wave, int lane) {
+    v = wave_sum(v);
+    __syncthreads();
+    if (lane == 0) sm.dsum[wave] = v;
+    __syncthreads();
+    double r = 0.0;
+#pragma unroll
+    for (int w = 0; w < AK_WAVES; ++w) r += sm.dsum[w];
+    return r;
+}
+
+__device__ __forceinline__ void ak_load(const float* __restrict__ row, int V, int wave, int lane, float (&x)[AK_CH][4]) {
+#pragma unroll
+    for (int c = 0; c < AK_CH; ++c) {
+        const int idx = wave * AK_SEG + c * 256 + lane * 4;
+        if (idx < V) {
+            const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(row + idx));
+            x[c][0] = v[0]; x[c][1] = v[1]; x[c][2] = v[2]; x[c][3] = v[3];
+        } else {
+            x[c][0] = x[c][1] = x[c][2] = x[c][3] = -INFINITY;
+        }
+    }
+}
+
+// x <- exp((x - max) / T) in place (fp32 exp of an fp64-scaled argument); returns the block sum.
+__device__ __forceinline__ double ak_exp_sum(float (&x)[AK_CH][4], float mx, double invT, AkShared& sm, int wave, int lane) {
+    double s = 0.0;
+#pragma unroll
+    for (int c = 0; c < AK_CH; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float v = expf((float)(((double)x[c][e] - (double)mx) * invT));
+            x[c][e] = v;
+            s += (double)v;
+        }
+    return ak_block_sum(s, sm, wave, lane);
+}
+
+// Weight of element (c, e) for the draw: mode 0 = max(0, p - q), mode 1 = p (unnormalised exp).
+__device__ __forceinline__ double ak_weight(const float (&ep)[AK_CH][4], const float (&eq)[AK_CH][4], int c, int e,
+                                            double ipz, double iqz, int mode) {
+    if (mode == 1) return (double)ep[c][e];
+    const double dlt = (double)ep[c][e] * ipz - (double)eq[c][e] * iqz;
+    return dlt > 0.0 ? dlt : 0.0;
+}
+
+// Inverse CDF in ascending vocabulary order: smallest v with sum_{w<=v} weight_w > u * Z.
+// Returns the token in every thread.  *z_out = Z.
+__device__ int ak_inverse_cdf(const float (&ep)[AK_CH][4], const float (&eq)[AK_CH][4], double ipz, double iqz, int mode,
+                              float u, int V, AkShared& sm, int wave, int lane, double* z_out) {
+    double s[AK_CH];
+    double lt = 0.0;
+#pragma unroll
+    for (int c = 0; c < AK_CH; ++c) {
+        s[c] = 0.0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[c] += ak_weight(ep, eq, c, e, ipz, iqz, mode);
+        lt += s[c];
+    }
+    const double wt = wave_sum(lt);
+    __syncthreads();
+    if (lane == 0) sm.dsum[wave] = wt;
+    if (threadIdx.x == 0) sm.token = -1;
+    __syncthreads();
+    double Z = 0.0;
+#pragma unroll
+    for (int w = 0; w < AK_WAVES; ++w) Z += sm.dsum[w];
+    *z_out = Z;
+    if (!(Z > 0.0)) return -1;
+    const double target = (double)u * Z;
+    // wavefront holding the target; if rounding leaves none, the last one with weight
+    int wstar = -1, wlast = 0;
+    double base = 0.0, run = 0.0;
+#pragma unroll
+    for (int w = 0; w < AK_WAVES; ++w) {
+        const double ww = sm.dsum[w];
+        if (ww > 0.0) wlast = w;
+        if (wstar < 0) {
+            if (run + ww > target) { wstar = w; base = run; }
+            else run += ww;
+        }
+    }
+    bool take_last = false;
+    if (wstar < 0) { wstar = wlast; take_last = true; }
+    if (wave == wstar) {   // wave-uniform branch
+        int cstar = -1, clast = -1;
+        double cb = base;
+#pragma unroll
+        for (int c = 0; c < AK_CH; ++c) {
+            const double ct = wave_sum(s[c]);
+            if (ct > 0.0) clast = c;
+            if (cstar < 0 && !take_last) {
+                if (cb + ct > target) cstar = c;
+                else cb += ct;
+            }
+        }
+        if (cstar < 0) { cstar = clast < 0 ? 0 : clast; take_last = true; }
+        double sc = 0.0;
+#pragma unroll
+        for (int c = 0; c < AK_CH; ++c)
+            if (c == cstar) sc = s[c];
+        const double incl = wave_scan_incl(sc, lane);
+        unsigned long long bal = __ballot(take_last ? (sc > 0.0) : (cb + incl > target));
+        if (bal == 0ull) { take_last = true; bal = __ballot(sc > 0.0); }
+        int lstar;
+        if (bal == 0ull) lstar = 0;
+        else lstar = take_last ? (63 - __clzll((long long)bal)) : (__ffsll((long long)bal) - 1);
+        if (lane == lstar) {
+            double acc = cb + incl - sc;
+            int tok = -1, lastpos = -1;
+            const int idx0 = wave * AK_SEG + cstar * 256 + lane * 4;
+#pragma unroll
+            for (int c = 0; c < AK_CH; ++c) {
+                if (c == cstar) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const double w = ak_weight(ep, eq, c, e, ipz, iqz, mode);
+                        acc += w;
+                        if (w > 0.0) lastpos = idx0 + e;
+                        if (tok < 0 && !take_last && acc > target) tok = idx0 + e;
+                    }
+                }
+            }
+            if (tok < 0) tok = lastpos >= 0 ? lastpos : min(idx0, V - 1);
+            sm.token = tok;
+        }
+    }
+    __syncthreads();
+    return sm.token;
+}
+
+// argmax with lowest index on ties; returns the index in every thread
+__device__ int ak_argmax(const float (&x)[AK_CH][4], AkShared& sm, int wave, int lane) {
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int c = 0; c < AK_CH; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int idx = wave * AK_SEG + c * 256 + lane * 4 + e;
+            if (x[c][e] > bv) { bv = x[c][e]; bi = idx; }   // ascending c, e within a lane
+        }
+    // lanes of one chunk interleave, so order by (value desc, index asc)
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    __syncthreads();
+    if (lane == 0) { sm.fmx[wave] = bv; sm.ival[wave] = bi; }
+    __syncthreads();
+    float rv = sm.fmx[0];
+    int ri = sm.ival[0];
+#pragma unroll
+    for (int w = 1; w < AK_WAVES; ++w) {
+        const float ov = sm.fmx[w];
+        const int oi = sm.ival[w];
+        if (ov > rv || (ov == rv && oi < ri)) { rv = ov; ri = oi; }
+    }
+    return ri;
+}
+
+// One (row b, position j) of the accept step.  cand[(b*(gamma+1)+j)] = (candidate token, test result).
+//   j < gamma : test u_acc < min(1, p(d)/q(d)); candidate = draw from norm(max(0, p - q)) (from p if p == q)
+//   j == gamma: candidate = draw from p (bonus token); test result unused (1)
+//   T == 0    : test = [d == argmax P_j], candidate = argmax P_j
+__global__ __launch_bounds__(AK_NT) void accept_rows_kernel(const float* __restrict__ P, const float* __restrict__ Q,
+                                                            const int32_t* __restrict__ d, int gamma, int V, float T,
+                                                            uint64_t seed, uint32_t round, uint32_t seq0,
+                                                            int2* __restrict__ cand, double* __restrict__ bd) {
+    __shared__ AkShared sm;
+    const int j = blockIdx.x, b = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float* Prow = P + ((size_t)b * (gamma + 1) + j) * V;
+    const bool has_q = j < gamma;
+    const float* Qrow = has_q ? Q + ((size_t)b * gamma + j) * V : nullptr;
+    const int dtok = has_q ? min(max(d[(size_t)b * gamma + j], 0), V - 1) : -1;   // clamped: stays in bounds for any input
+    float xp[AK_CH][4], xq[AK_CH][4];
+    ak_load(Prow, V, wave, lane, xp);
+    if (T <= 0.f) {
+        const int am = ak_argmax(xp, sm, wave, lane);
+        if (threadIdx.x == 0) {
+            cand[(size_t)b * (gamma + 1) + j] = make_int2(am, has_q ? (dtok == am) : 1);
+            if (has_q && bd) bd[(size_t)b * gamma + j] = (dtok == am) ? 1.0 : 0.0;
+        }
+        return;
+    }
+    const double invT = 1.0 / (double)T;
+    if (has_q) ak_load(Qrow, V, wave, lane, xq);
+    else {
+#pragma unroll
+        for (int c = 0; c < AK_CH; ++c) xq[c][0] = xq[c][1] = xq[c][2] = xq[c][3] = -INFINITY;
+    }
+    float lm = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < AK_CH; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) lm = fmaxf(lm, xp[c][e]);
+    const float mp = ak_block_max(lm, sm, wave, lane);
+    const double Zp = ak_exp_sum(xp, mp, invT, sm, wave, lane);
+    const double ipz = 1.0 / Zp;
+    const float u_res = philox_uniform(seed, seq0 + (uint32_t)b, round, 0u, 1u);
+    int accept = 1, token;
+    double Z;
+    if (has_q) {
+        lm = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < AK_CH; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) lm = fmaxf(lm, xq[c][e]);
+        const float mq = ak_block_max(lm, sm, wave, lane);
+        const double Zq = ak_exp_sum(xq, mq, invT, sm, wave, lane);
+        const double iqz = 1.0 / Zq;
+        double mn = 0.0;
+#pragma unroll
+        for (int c = 0; c < AK_CH; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const double pv = (double)xp[c][e] * ipz, qv = (double)xq[c][e] * iqz;
+                mn += pv < qv ? pv : qv;
+            }
+        const double bdj = ak_block_sum(mn, sm, wave, lane);
+        const float epd = expf((float)(((double)Prow[dtok] - (double)mp) * invT));
+        const float eqd = expf((float)(((double)Qrow[dtok] - (double)mq) * invT));
+        const double qd = (double)eqd * iqz;
+        if (qd > 0.0) {
+            const double ratio = ((double)epd * ipz) / qd;
+            const float u_acc = philox_uniform(seed, seq0 + (uint32_t)b, round, (uint32_t)j, 0u);
+            accept = (double)u_acc < (ratio < 1.0 ? ratio : 1.0);
+        }
+        token = ak_inverse_cdf(xp, xq, ipz, iqz, 0, u_res, V, sm, wave, lane, &Z);
+        if (token < 0) token = ak_inverse_cdf(xp, xq, ipz, iqz, 1, u_res, V, sm, wave, lane, &Z);   // p == q
+        if (threadIdx.x == 0 && bd) bd[(size_t)b * gamma + j] = bdj;
+    } else {
+        token = ak_inverse_cdf(xp, xq, ipz, 0.0, 1, u_res, V, sm, wave, lane, &Z);
+    }
+    if (threadIdx.x == 0) cand[(size_t)b * (gamma + 1) + j] = make_int2(token, accept);
+}
+
+// Per row: N_acc = first failed test, emitted token = candidate of that position, mask bits.
+// hist (optional): hist[b*hist_stride + l + n] = token  (commit of the emitted token).
+__global__ void accept_finalize_kernel(const int2* __restrict__ cand, int rows, int gamma, int32_t* __restrict__ n_acc,
+                                       int32_t* __restrict__ token, uint32_t* __restrict__ mask, int32_t* __restrict__ hist,
+                                       int l) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= rows) return;
+    int n = gamma;
+    uint32_t mk = 0;
+    for (int j = gamma - 1; j >= 0; --j) {
+        const int a = cand[(size_t)b * (gamma + 1) + j].y;
+        if (a) mk |= 1u << j;
+        else n = j;
+    }
+    const int tok = cand[(size_t)b * (gamma + 1) + n].x;
+    n_acc[b] = n;
+    token[b] = tok;
+    if (mask) mask[b] = mk;
+    if (hist) hist[l + n] = tok;
+}
+
+// Token draw from one row of logits: argmax (T = 0) or inverse CDF of softmax(logits / T) with the
+// stream-2 uniform at (seq0 + row, round, pos).  grid (rows), block 1024.  tok[row * tok_stride]
+// (and tok_copy[row] when given).
+__global__ __launch_bounds__(AK_NT) void sample_rows_kernel(const float* __restrict__ logits, int V, float T, uint64_t seed,
+                                                            uint32_t round, uint32_t pos, uint32_t seq0,
+                                                            int32_t* __restrict__ tok, int tok_stride,
+                                                            int32_t* __restrict__ tok_copy) {
+    __shared__ AkShared sm;
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float xp[AK_CH][4];
+    ak_load(logits + (size_t)b * V, V, wave, lane, xp);
+    int token;
+    if (T <= 0.f) {
+        token = ak_argmax(xp, sm, wave, lane);
+    } else {
+        float lm = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < AK_CH; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) lm = fmaxf(lm, xp[c][e]);
+        const float mp = ak_block_max(lm, sm, wave, lane);
+        const double Zp = ak_exp_sum(xp, mp, 1.0 / (double)T, sm, wave, lane);
+        const float u = philox_uniform(seed, seq0 + (uint32_t)b, round, pos, 2u);
+        double Z;
+        token = ak_inverse_cdf(xp, xp, 1.0 / Zp, 0.0, 1, u, V, sm, wave, lane, &Z);
+    }
+    if (threadIdx.x == 0) {
+        tok[(size_t)b * tok_stride] = token;
+        if (tok_copy) tok_copy[b] = token;
+    }
+}
+
+}  // namespace msd

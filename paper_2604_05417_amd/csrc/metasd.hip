@@ -1,0 +1,702 @@
+// Host side of the MetaSD hot-path library: C ABI (include/metasd.h), launch plans, bandit.
+// Device memory is never allocated here; every buffer comes from the caller.
+#include "../../include/metasd.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace msd;
+
+namespace {
+
+thread_local std::string g_err = "";
+
+int fail_global(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+constexpr int PER_LAYER = 9;
+constexpr int MAX_ROWS = 16;
+constexpr size_t ALIGN = 256;
+constexpr int LDS_BUDGET = 60 * 1024;
+
+size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+size_t elem_size(const metasd_model_desc& d) { return d.dtype == METASD_BF16 ? 2 : 4; }
+
+struct Model {
+    metasd_model_desc d{};
+    std::vector<const void*> w;
+    void* kv = nullptr;
+    int hd = 0;
+    int kv_len = 0;  // positions valid in the KV cache
+    const void* layer_w(int L, int i) const { return w[1 + PER_LAYER * L + i]; }
+    const void* final_norm() const { return w[1 + PER_LAYER * d.n_layers]; }
+    const void* lm_head() const { return w[2 + PER_LAYER * d.n_layers]; }
+};
+
+// split of one GEMM launch
+struct Split {
+    int ksplit, cps, tpb;
+    size_t lds;
+};
+
+Split choose_split(int m, int ntiles, int kchunks) {
+    const int cps_max = std::max(1, ((LDS_BUDGET / 16 / m) - 1) / 4);
+    int want = (2048 + ntiles / 2) / ntiles;                      // aim for about 2048 wavefront work units
+    want = std::max(1, std::min(want, 8));
+    want = std::min(want, std::max(1, kchunks / 8));              // at least 8 chunks per slice
+    int ks = std::max(want, (kchunks + cps_max - 1) / cps_max);   // LDS capacity wins
+    int cps = (kchunks + ks - 1) / ks;
+    ks = (kchunks + cps - 1) / cps;
+    Split s;
+    s.ksplit = ks;
+    s.cps = cps;
+    s.tpb = 4;
+    s.lds = (size_t)m * (cps * 4 + 1) * 16;
+    return s;
+}
+
+const char* check_model(const metasd_model_desc& d, const char* who, char* buf, size_t n) {
+    auto bad = [&](const char* what) { snprintf(buf, n, "%s: %s", who, what); return buf; };
+    if (d.n_layers < 1 || d.d_model < 1 || d.n_heads < 1 || d.n_kv_heads < 1 || d.d_ffn < 1 || d.vocab < 1) return bad("non-positive dimension");
+    if (d.d_model % d.n_heads) return bad("d_model not divisible by n_heads");
+    if (d.n_heads % d.n_kv_heads) return bad("n_heads not divisible by n_kv_heads");
+    const int hd = d.d_model / d.n_heads;
+    if (hd != 32 && hd != 64 && hd != 128) return bad("head_dim must be 32, 64 or 128");
+    if (d.act != METASD_GELU && d.act != METASD_SWIGLU) return bad("act");
+    if (d.dtype != METASD_F32 && d.dtype != METASD_BF16) return bad("dtype");
+    if (d.dtype == METASD_F32 && hd > 64) return bad("fp32 models support head_dim <= 64");
+    if (d.vocab % 4 || d.vocab > AK_WAVES * AK_SEG) return bad("vocab must be a multiple of 4 and <= 32768");
+    if (d.dtype == METASD_BF16) {
+        if (d.d_model % 32 || d.d_ffn % 32) return bad("bf16: d_model and d_ffn must be multiples of 32");
+        if (d.vocab % 16) return bad("bf16: vocab must be a multiple of 16");
+    } else if (d.d_model % 4 || d.d_ffn % 4) return bad("fp32: d_model and d_ffn must be multiples of 4");
+    if (!(d.rms_eps > 0.f) || !(d.rope_theta > 0.f)) return bad("rms_eps / rope_theta must be positive");
+    return nullptr;
+}
+
+// Workspace layout shared by metasd_workspace_bytes and metasd_create.
+struct Layout {
+    size_t hist, h, xn, part, q, ao, act, apart, P, Q, cand, bd, res, draft, total;
+};
+
+Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const metasd_model_desc* dr) {
+    int dmax = t.d_model, fmax = t.d_ffn, vmax = t.vocab, hmax = t.n_heads, hdmax = t.d_model / t.n_heads;
+    size_t partmax = 0;
+    auto acc = [&](const metasd_model_desc& d) {
+        dmax = std::max(dmax, d.d_model); fmax = std::max(fmax, d.d_ffn); vmax = std::max(vmax, d.vocab);
+        hmax = std::max(hmax, d.n_heads); hdmax = std::max(hdmax, d.d_model / d.n_heads);
+        const int hd = d.d_model / d.n_heads;
+        const int ns[5] = {(d.n_heads + 2 * d.n_kv_heads) * hd, d.d_model, (d.act == METASD_SWIGLU ? 2 : 1) * d.d_ffn, d.d_model, d.vocab};
+        const int ks[5] = {d.d_model, d.d_model, d.d_model, d.d_ffn, d.d_model};
+        for (int i = 0; i < 5; ++i) {
+            int ksplit = 1;
+            if (d.dtype == METASD_BF16) ksplit = choose_split(MAX_ROWS, ns[i] / 16, ks[i] / 32).ksplit;
+            // a smaller m never needs more splits for LDS, but may use up to 8 for parallelism
+            ksplit = std::max(ksplit, 8);
+            partmax = std::max(partmax, (size_t)ksplit * MAX_ROWS * ns[i] * sizeof(float));
+        }
+    };
+    acc(t);
+    for (int k = 0; k < c.K; ++k) acc(dr[k]);
+    const int nchunks = (c.max_ctx + ATT_CH - 1) / ATT_CH;
+    Layout L{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes); return at; };
+    L.hist = take((size_t)c.max_ctx * 4);
+    L.h = take((size_t)MAX_ROWS * dmax * 4);
+    L.xn = take((size_t)MAX_ROWS * dmax * 4);
+    L.part = take(partmax);
+    L.q = take((size_t)MAX_ROWS * dmax * 4);
+    L.ao = take((size_t)MAX_ROWS * dmax * 4);
+    L.act = take((size_t)MAX_ROWS * fmax * 4);
+    L.apart = take((size_t)hmax * nchunks * 16 * (hdmax + 2) * 4);
+    L.P = take((size_t)(c.gamma_max + 1) * vmax * 4);
+    L.Q = take((size_t)c.gamma_max * vmax * 4);
+    L.cand = take((size_t)(c.gamma_max + 1) * sizeof(int2));
+    L.bd = take((size_t)c.gamma_max * sizeof(double));
+    L.res = take(64);
+    L.draft = take(64);
+    L.total = o;
+    return L;
+}
+
+struct Bandit {
+    int K = 0, t = 0;
+    double beta = 1.0;
+    std::vector<double> mu;
+    std::vector<int> n;
+    void reset() { t = 0; std::fill(mu.begin(), mu.end(), 0.0); std::fill(n.begin(), n.end(), 0); }
+};
+
+struct HostResult {   // pinned host mirror of one accept
+    int32_t n_acc, token;
+    uint32_t mask;
+    int32_t pad;
+    int32_t d[16];
+    double bd[16];
+};
+
+enum Phase { PH_NONE = 0, PH_READY, PH_DRAFTED, PH_VERIFIED };
+
+}  // namespace
+
+struct metasd_ctx {
+    metasd_config cfg{};
+    Model target;
+    std::vector<Model> drafters;
+    hipStream_t stream = nullptr;
+    char* ws = nullptr;
+    Layout lay{};
+    std::vector<int32_t> hist;   // host mirror of committed tokens
+    int l = 0;                   // committed tokens
+    int round = 0;
+    int cur_k = -1, cur_gamma = 0;
+    Phase phase = PH_NONE;
+    Bandit bandit;
+    HostResult* hres = nullptr;
+    std::string err;
+
+    int32_t* d_hist() const { return reinterpret_cast<int32_t*>(ws + lay.hist); }
+    float* d_h() const { return reinterpret_cast<float*>(ws + lay.h); }
+    void* d_xn() const { return ws + lay.xn; }
+    float* d_part() const { return reinterpret_cast<float*>(ws + lay.part); }
+    void* d_q() const { return ws + lay.q; }
+    void* d_ao() const { return ws + lay.ao; }
+    void* d_act() const { return ws + lay.act; }
+    float* d_apart() const { return reinterpret_cast<float*>(ws + lay.apart); }
+    float* d_P() const { return reinterpret_cast<float*>(ws + lay.P); }
+    float* d_Q() const { return reinterpret_cast<float*>(ws + lay.Q); }
+    int2* d_cand() const { return reinterpret_cast<int2*>(ws + lay.cand); }
+    double* d_bd() const { return reinterpret_cast<double*>(ws + lay.bd); }
+    int32_t* d_res() const { return reinterpret_cast<int32_t*>(ws + lay.res); }
+    int32_t* d_draft() const { return reinterpret_cast<int32_t*>(ws + lay.draft); }
+
+    int fail(int code, const char* fmt, ...) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        err = buf;
+        return code;
+    }
+};
+
+namespace {
+
+#define HIP_TRY(ctx, expr)                                                                              \
+    do {                                                                                                \
+        hipError_t e_ = (expr);                                                                         \
+        if (e_ != hipSuccess) return (ctx)->fail(METASD_E_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+#define LAUNCH_CHECK(ctx, name)                                                                              \
+    do {                                                                                                     \
+        hipError_t e_ = hipGetLastError();                                                                   \
+        if (e_ != hipSuccess) return (ctx)->fail(METASD_E_HIP, "launch %s: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+// ---- GEMM launcher: out[.][r][n] over up to three matrices concatenated along n.
+// Returns the number of split-K partials written to `part` (their split stride is m*N);
+// when direct_out != nullptr the summed result is written there instead and 0 is returned.
+template <typename T>
+int gemm(metasd_ctx* c, const void* x, int ldx, int m, int K, const void* W0, int n0, const void* W1, int n1,
+         const void* W2, int n2, float* direct_out, int* nsplit_out);
+
+template <>
+int gemm<float>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void* W0, int n0, const void* W1, int n1,
+                const void* W2, int n2, float* direct_out, int* nsplit_out) {
+    const int N = n0 + n1 + n2;
+    float* out = direct_out ? direct_out : c->d_part();
+    hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 3) / 4), dim3(256), 0, c->stream, (const float*)x, ldx, m, K,
+                       (const float*)W0, (const float*)W1, (const float*)W2, n0, n0 + n1, N, out);
+    LAUNCH_CHECK(c, "gemm_f32");
+    *nsplit_out = direct_out ? 0 : 1;
+    return 0;
+}
+
+template <>
+int gemm<bf16_t>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void* W0, int n0, const void* W1, int n1,
+                 const void* W2, int n2, float* direct_out, int* nsplit_out) {
+    const int N = n0 + n1 + n2;
+    const int ntiles = N / 16, kchunks = K / 32;
+    const Split s = choose_split(m, ntiles, kchunks);
+    float* out = (direct_out && s.ksplit == 1) ? direct_out : c->d_part();
+    const int groups = (ntiles + s.tpb - 1) / s.tpb;
+    hipLaunchKernelGGL(gemm_bf16_kernel, dim3(groups * s.ksplit), dim3(256), s.lds, c->stream, (const bf16_t*)x, ldx, m, K,
+                       (const bf16_t*)W0, (const bf16_t*)W1, (const bf16_t*)W2, n0 / 16, (n0 + n1) / 16, ntiles, out, N,
+                       s.ksplit, s.cps, s.tpb);
+    LAUNCH_CHECK(c, "gemm_bf16");
+    if (direct_out && s.ksplit > 1) {
+        const size_t n = (size_t)m * N;
+        hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->d_part(),
+                           s.ksplit, n, n, direct_out);
+        LAUNCH_CHECK(c, "sum_partials");
+    }
+    *nsplit_out = direct_out ? 0 : s.ksplit;
+    return 0;
+}
+
+template <typename T, int HD>
+int attention_hd(metasd_ctx* c, const Model& M, int L, int pos0, int m) {
+    const metasd_model_desc& d = M.d;
+    const size_t plane = (size_t)d.n_kv_heads * c->cfg.max_ctx * HD;
+    const T* kc = (const T*)M.kv + (size_t)L * 2 * plane;
+    const T* vc = kc + plane;
+    const int nchunks = (pos0 + m + ATT_CH - 1) / ATT_CH;
+    const float scale = 1.0f / sqrtf((float)HD);
+    hipLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(nchunks, d.n_heads), dim3(256), 0, c->stream, (const T*)c->d_q(), kc,
+                       vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale, c->d_apart(), nchunks);
+    LAUNCH_CHECK(c, "attn_partial");
+    hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3(d.n_heads, m), dim3(HD), 0, c->stream, c->d_apart(), nchunks,
+                       d.n_heads, (T*)c->d_ao());
+    LAUNCH_CHECK(c, "attn_combine");
+    return 0;
+}
+
+template <typename T>
+int attention(metasd_ctx* c, const Model& M, int L, int pos0, int m) {
+    switch (M.hd) {
+        case 32: return attention_hd<T, 32>(c, M, L, pos0, m);
+        case 64: return attention_hd<T, 64>(c, M, L, pos0, m);
+        default:
+            if constexpr (sizeof(T) == 2) return attention_hd<T, 128>(c, M, L, pos0, m);
+            return c->fail(METASD_E_INVALID, "fp32 head_dim 128 unsupported");
+    }
+}
+
+// Forward of m <= 16 rows whose tokens are hist[pos0 .. pos0+m) at positions pos0..; appends K/V.
+// logits: nullptr = none; otherwise rows [first_row, m) of the block get logits, written
+// consecutively to `logits` (row stride V).
+template <typename T>
+int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int first_row) {
+    const metasd_model_desc& d = M.d;
+    const int D = d.d_model, H = d.n_heads, KH = d.n_kv_heads, hd = M.hd, F = d.d_ffn, V = d.vocab;
+    const int DQ = H * hd, DKV = KH * hd;
+    hipStream_t st = c->stream;
+    float* h = c->d_h();
+    T* xn = (T*)c->d_xn();
+    float* part = c->d_part();
+    int ns = 0, rc;
+    hipLaunchKernelGGL(embed_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, h);
+    LAUNCH_CHECK(c, "embed");
+    for (int L = 0; L < d.n_layers; ++L) {
+        // h += previous FFN output (split partials); xn = norm(h)
+        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(256), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.layer_w(L, 0),
+                           d.rms_eps, xn);
+        LAUNCH_CHECK(c, "addnorm");
+        if ((rc = gemm<T>(c, xn, D, m, D, M.layer_w(L, 1), DQ, M.layer_w(L, 2), DKV, M.layer_w(L, 3), DKV, nullptr, &ns))) return rc;
+        const int NQKV = DQ + 2 * DKV;
+        const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
+        T* kc = (T*)M.kv + (size_t)L * 2 * plane;
+        hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, part, ns, (size_t)m * NQKV, NQKV, pos0, H, KH,
+                           hd, d.rope_theta, (T*)c->d_q(), kc, kc + plane, c->cfg.max_ctx);
+        LAUNCH_CHECK(c, "rope_kv");
+        if ((rc = attention<T>(c, M, L, pos0, m))) return rc;
+        if ((rc = gemm<T>(c, c->d_ao(), DQ, m, DQ, M.layer_w(L, 4), D, nullptr, 0, nullptr, 0, nullptr, &ns))) return rc;
+        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(256), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.layer_w(L, 5),
+                           d.rms_eps, xn);
+        LAUNCH_CHECK(c, "addnorm");
+        if (d.act == METASD_SWIGLU) {
+            if ((rc = gemm<T>(c, xn, D, m, D, M.layer_w(L, 6), F, M.layer_w(L, 7), F, nullptr, 0, nullptr, &ns))) return rc;
+        } else {
+            if ((rc = gemm<T>(c, xn, D, m, D, M.layer_w(L, 7), F, nullptr, 0, nullptr, 0, nullptr, &ns))) return rc;
+        }
+        const size_t nact = (size_t)m * F;
+        const int NF = (d.act == METASD_SWIGLU ? 2 : 1) * F;
+        hipLaunchKernelGGL(ffn_act_kernel<T>, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)m * NF, m, F,
+                           d.act, (T*)c->d_act());
+        LAUNCH_CHECK(c, "ffn_act");
+        if ((rc = gemm<T>(c, c->d_act(), F, m, F, M.layer_w(L, 8), D, nullptr, 0, nullptr, 0, nullptr, &ns))) return rc;
+    }
+    if (logits) {
+        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(256), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.final_norm(),
+                           d.rms_eps, xn);
+        LAUNCH_CHECK(c, "addnorm");
+        int dummy;
+        if ((rc = gemm<T>(c, xn + (size_t)first_row * D, D, m - first_row, D, M.lm_head(), V, nullptr, 0, nullptr, 0, logits, &dummy)))
+            return rc;
+    }
+    return 0;
+}
+
+// Forward over tokens hist[pos0 .. pos0+n) in blocks of <= 16 rows (later blocks see the KV of
+// earlier ones).  logits (optional): want_all ? all n rows (n <= 16) : the last row only.
+int forward(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool want_all) {
+    if (pos0 + n > c->cfg.max_ctx) return c->fail(METASD_E_OVERFLOW, "positions %d..%d exceed max_ctx %d", pos0, pos0 + n, c->cfg.max_ctx);
+    int done = 0;
+    while (done < n) {
+        const int m = std::min(MAX_ROWS, n - done);
+        const bool last = done + m == n;
+        float* lg = (last && logits) ? logits : nullptr;
+        const int first_row = want_all ? 0 : m - 1;
+        int rc = M.d.dtype == METASD_BF16 ? forward_rows<bf16_t>(c, M, pos0 + done, m, lg, first_row)
+                                          : forward_rows<float>(c, M, pos0 + done, m, lg, first_row);
+        if (rc) return rc;
+        done += m;
+    }
+    M.kv_len = pos0 + n;
+    return 0;
+}
+
+int launch_sample(hipStream_t st, const float* logits, int rows, int V, float T, uint64_t seed, uint32_t round, uint32_t pos,
+                  uint32_t seq0, int32_t* tok, int stride, int32_t* tok_copy) {
+    hipLaunchKernelGGL(sample_rows_kernel, dim3(rows), dim3(AK_NT), 0, st, logits, V, T, seed, round, pos, seq0, tok, stride,
+                       tok_copy);
+    return hipGetLastError() == hipSuccess ? 0 : METASD_E_HIP;
+}
+
+int launch_accept(hipStream_t st, const float* P, const float* Q, const int32_t* d, int rows, int gamma, int V, float T,
+                  uint64_t seed, uint32_t round, uint32_t seq0, int2* cand, double* bd, int32_t* n_acc, int32_t* token,
+                  uint32_t* mask, int32_t* hist, int l) {
+    hipLaunchKernelGGL(accept_rows_kernel, dim3(gamma + 1, rows), dim3(AK_NT), 0, st, P, Q, d, gamma, V, T, seed, round, seq0,
+                       cand, bd);
+    if (hipGetLastError() != hipSuccess) return METASD_E_HIP;
+    hipLaunchKernelGGL(accept_finalize_kernel, dim3((rows + 63) / 64), dim3(64), 0, st, cand, rows, gamma, n_acc, token, mask,
+                       hist, l);
+    return hipGetLastError() == hipSuccess ? 0 : METASD_E_HIP;
+}
+
+bool valid_vocab(int V) { return V >= 4 && V % 4 == 0 && V <= AK_WAVES * AK_SEG; }
+
+}  // namespace
+
+// ================================================================================================ C ABI
+
+extern "C" {
+
+const char* metasd_last_error(const metasd_ctx* c) { return c ? c->err.c_str() : g_err.c_str(); }
+
+int32_t metasd_kv_bytes(const metasd_model_desc* m, int32_t max_ctx, size_t* bytes_out) {
+    if (!m || !bytes_out || max_ctx < 1) return fail_global(METASD_E_INVALID, "metasd_kv_bytes: bad argument");
+    char buf[256];
+    if (const char* e = check_model(*m, "model", buf, sizeof buf)) return fail_global(METASD_E_INVALID, "%s", e);
+    *bytes_out = (size_t)m->n_layers * 2 * m->n_kv_heads * (size_t)max_ctx * (m->d_model / m->n_heads) * elem_size(*m);
+    return METASD_OK;
+}
+
+static int check_config(const metasd_config* cfg, const metasd_model_desc* target, const metasd_model_desc* drafters) {
+    if (!cfg || !target || !drafters) return fail_global(METASD_E_INVALID, "NULL config or descriptor");
+    if (cfg->K < 1 || cfg->K > METASD_MAX_K) return fail_global(METASD_E_INVALID, "K must be in 1..%d", METASD_MAX_K);
+    if (cfg->gamma_max < 1 || cfg->gamma_max > METASD_MAX_GAMMA) return fail_global(METASD_E_INVALID, "gamma_max must be in 1..%d", METASD_MAX_GAMMA);
+    if (cfg->batch != 1) return fail_global(METASD_E_INVALID, "batch must be 1 in this version");
+    if (cfg->max_ctx < cfg->gamma_max + 2) return fail_global(METASD_E_INVALID, "max_ctx too small");
+    if (!(cfg->temperature >= 0.f)) return fail_global(METASD_E_INVALID, "temperature must be >= 0");
+    if (cfg->reward != METASD_REWARD_BE && cfg->reward != METASD_REWARD_BD) return fail_global(METASD_E_INVALID, "reward");
+    if (!(cfg->ucb_beta >= 0.0)) return fail_global(METASD_E_INVALID, "ucb_beta must be >= 0");
+    char buf[256];
+    if (const char* e = check_model(*target, "target", buf, sizeof buf)) return fail_global(METASD_E_INVALID, "%s", e);
+    for (int k = 0; k < cfg->K; ++k) {
+        char who[32];
+        snprintf(who, sizeof who, "drafter %d", k);
+        if (const char* e = check_model(drafters[k], who, buf, sizeof buf)) return fail_global(METASD_E_INVALID, "%s", e);
+        if (drafters[k].vocab != target->vocab) return fail_global(METASD_E_INVALID, "%s: vocab differs from the target's", who);
+    }
+    return METASD_OK;
+}
+
+int32_t metasd_workspace_bytes(const metasd_config* cfg, const metasd_model_desc* target, const metasd_model_desc* drafters,
+                               size_t* bytes_out) {
+    if (!bytes_out) return fail_global(METASD_E_INVALID, "NULL bytes_out");
+    if (int rc = check_config(cfg, target, drafters)) return rc;
+    *bytes_out = make_layout(*cfg, *target, drafters).total;
+    return METASD_OK;
+}
+
+int32_t metasd_pack_weight(void* dst, const void* src, int32_t n_out, int32_t n_in, void* hip_stream) {
+    if (!dst || !src || dst == src) return fail_global(METASD_E_INVALID, "metasd_pack_weight: NULL or aliased pointers");
+    if (n_out < 16 || n_in < 32 || n_out % 16 || n_in % 32) return fail_global(METASD_E_INVALID, "metasd_pack_weight: n_out %% 16 and n_in %% 32 must be 0");
+    const size_t total = (size_t)n_out * n_in / 8;
+    hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)hip_stream,
+                       (const uint4*)src, (uint4*)dst, n_out, n_in);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_global(METASD_E_HIP, "pack_weight: %s", hipGetErrorString(e));
+    return METASD_OK;
+}
+
+int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_model_desc* target,
+                      const metasd_model_desc* drafters, const void* const* target_weights,
+                      const void* const* const* drafter_weights, void* target_kv, void* const* drafter_kv, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+    if (!out) return fail_global(METASD_E_INVALID, "NULL out");
+    *out = nullptr;
+    if (int rc = check_config(cfg, target, drafters)) return rc;
+    if (!target_weights || !drafter_weights || !target_kv || !drafter_kv || !workspace) return fail_global(METASD_E_INVALID, "NULL pointer argument");
+    if ((uintptr_t)workspace % ALIGN) return fail_global(METASD_E_INVALID, "workspace must be 256-byte aligned");
+    const Layout lay = make_layout(*cfg, *target, drafters);
+    if (workspace_bytes < lay.total) return fail_global(METASD_E_WORKSPACE, "workspace too small: need %zu bytes, got %zu", lay.total, workspace_bytes);
+    auto fill = [&](Model& M, const metasd_model_desc& d, const void* const* w, void* kv, const char* who) -> int {
+        M.d = d;
+        M.hd = d.d_model / d.n_heads;
+        M.kv = kv;
+        const int nw = 1 + PER_LAYER * d.n_layers + 2;
+        M.w.assign(w, w + nw);
+        for (int i = 0; i < nw; ++i) {
+            const bool gate = i >= 1 && i < nw - 2 && (i - 1) % PER_LAYER == 6;
+            if (!M.w[i] && !(gate && d.act == METASD_GELU)) return fail_global(METASD_E_INVALID, "%s: weight %d is NULL", who, i);
+            if ((uintptr_t)M.w[i] % 16) return fail_global(METASD_E_INVALID, "%s: weight %d is not 16-byte aligned", who, i);
+        }
+        if (!kv || (uintptr_t)kv % 16) return fail_global(METASD_E_INVALID, "%s: KV cache NULL or misaligned", who);
+        return 0;
+    };
+    metasd_ctx* c = new (std::nothrow) metasd_ctx();
+    if (!c) return fail_global(METASD_E_INVALID, "out of host memory");
+    c->cfg = *cfg;
+    c->stream = (hipStream_t)hip_stream;
+    c->ws = (char*)workspace;
+    c->lay = lay;
+    int rc = fill(c->target, *target, target_weights, target_kv, "target");
+    c->drafters.resize(cfg->K);
+    for (int k = 0; k < cfg->K && !rc; ++k) {
+        if (!drafter_weights[k]) rc = fail_global(METASD_E_INVALID, "drafter %d: NULL weight table", k);
+        else {
+            char who[32];
+            snprintf(who, sizeof who, "drafter %d", k);
+            rc = fill(c->drafters[k], drafters[k], drafter_weights[k], drafter_kv[k], who);
+        }
+    }
+    if (rc) { delete c; return rc; }
+    c->hist.assign(cfg->max_ctx, 0);
+    c->bandit.K = cfg->K;
+    c->bandit.beta = cfg->ucb_beta;
+    c->bandit.mu.assign(cfg->K, 0.0);
+    c->bandit.n.assign(cfg->K, 0);
+    hipError_t e = hipHostMalloc((void**)&c->hres, sizeof(HostResult), hipHostMallocDefault);
+    if (e != hipSuccess) {
+        rc = fail_global(METASD_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e));
+        delete c;
+        return rc;
+    }
+    *out = c;
+    return METASD_OK;
+}
+
+int32_t metasd_destroy(metasd_ctx* c) {
+    if (!c) return METASD_OK;
+    if (c->hres) (void)hipHostFree(c->hres);
+    delete c;
+    return METASD_OK;
+}
+
+int32_t metasd_set_context(metasd_ctx* c, int32_t seq, const int32_t* tokens, int32_t n, int32_t kv_prefilled) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (seq != 0 || !tokens || n < 1) return c->fail(METASD_E_INVALID, "set_context: bad seq / tokens / n");
+    if (n + c->cfg.gamma_max + 1 > c->cfg.max_ctx) return c->fail(METASD_E_OVERFLOW, "set_context: n + gamma_max + 1 = %d exceeds max_ctx %d", n + c->cfg.gamma_max + 1, c->cfg.max_ctx);
+    for (int i = 0; i < n; ++i)
+        if (tokens[i] < 0 || tokens[i] >= c->target.d.vocab) return c->fail(METASD_E_INVALID, "set_context: token %d out of range at %d", tokens[i], i);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    std::copy(tokens, tokens + n, c->hist.begin());
+    HIP_TRY(c, hipMemcpyAsync(c->d_hist(), c->hist.data(), (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->l = n;
+    c->round = 0;
+    c->bandit.reset();
+    c->phase = PH_READY;
+    if (kv_prefilled) {
+        c->target.kv_len = n - 1;
+        for (auto& d : c->drafters) d.kv_len = n - 1;
+    } else {
+        c->target.kv_len = 0;
+        for (auto& d : c->drafters) d.kv_len = 0;
+        if (n > 1)
+            if (int rc = forward(c, c->target, 0, n - 1, nullptr, false)) return rc;
+    }
+    return METASD_OK;
+}
+
+int32_t metasd_swap_weight(metasd_ctx* c, int32_t model, int32_t index, const void* dev_ptr) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (model < -1 || model >= c->cfg.K) return c->fail(METASD_E_INVALID, "swap_weight: model %d out of range", model);
+    Model& M = model < 0 ? c->target : c->drafters[model];
+    if (index < 0 || index >= (int)M.w.size() || !dev_ptr || (uintptr_t)dev_ptr % 16) return c->fail(METASD_E_INVALID, "swap_weight: bad index or pointer");
+    M.w[index] = dev_ptr;
+    return METASD_OK;
+}
+
+// ---- bandit
+
+int32_t metasd_bandit_select(metasd_ctx* c, int32_t seq, int32_t* k_out) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (seq != 0 || !k_out) return c->fail(METASD_E_INVALID, "bandit_select: bad argument");
+    const Bandit& b = c->bandit;
+    if (b.t < b.K) { *k_out = b.t; return METASD_OK; }
+    int best = 0;
+    double bs = -INFINITY;
+    for (int i = 0; i < b.K; ++i) {
+        const double s = b.mu[i] + b.beta * std::sqrt(2.0 * std::log((double)b.t) / (double)b.n[i]);
+        if (s > bs) { bs = s; best = i; }
+    }
+    *k_out = best;
+    return METASD_OK;
+}
+
+int32_t metasd_bandit_update(metasd_ctx* c, int32_t seq, int32_t k, int32_t n_acc, int32_t gamma, double bd_reward) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (seq != 0 || k < 0 || k >= c->cfg.K || gamma < 1 || n_acc < 0 || n_acc > gamma) return c->fail(METASD_E_INVALID, "bandit_update: bad argument");
+    double r = (double)n_acc / (double)gamma;
+    if (c->cfg.reward == METASD_REWARD_BD) {
+        if (!(bd_reward >= 0.0 && bd_reward <= 1.0 + 1e-9)) return c->fail(METASD_E_INVALID, "bandit_update: BD reward %g not in [0,1]", bd_reward);
+        r = bd_reward;
+    }
+    Bandit& b = c->bandit;
+    b.mu[k] = (b.mu[k] * (double)b.n[k] + r) / (double)(b.n[k] + 1);
+    b.n[k] += 1;
+    b.t += 1;
+    return METASD_OK;
+}
+
+int32_t metasd_bandit_state(const metasd_ctx* c, int32_t seq, double* mu, int32_t* n, int32_t* t) {
+    if (!c || seq != 0) return fail_global(METASD_E_INVALID, "bandit_state: bad argument");
+    if (mu) std::copy(c->bandit.mu.begin(), c->bandit.mu.end(), mu);
+    if (n) std::copy(c->bandit.n.begin(), c->bandit.n.end(), n);
+    if (t) *t = c->bandit.t;
+    return METASD_OK;
+}
+
+// ---- round
+
+int32_t metasd_draft(metasd_ctx* c, const int32_t* k, int32_t gamma) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (!k || k[0] < 0 || k[0] >= c->cfg.K) return c->fail(METASD_E_INVALID, "draft: drafter index out of range");
+    if (gamma < 1 || gamma > c->cfg.gamma_max) return c->fail(METASD_E_INVALID, "draft: gamma %d not in 1..%d", gamma, c->cfg.gamma_max);
+    if (c->phase != PH_READY) return c->fail(METASD_E_ORDER, "draft: call set_context first / finish the previous round with accept");
+    if (c->l + gamma + 1 > c->cfg.max_ctx) return c->fail(METASD_E_OVERFLOW, "draft: l + gamma + 1 = %d exceeds max_ctx %d", c->l + gamma + 1, c->cfg.max_ctx);
+    Model& D = c->drafters[k[0]];
+    const int V = D.d.vocab, l = c->l;
+    const float T = c->cfg.temperature;
+    for (int j = 0; j < gamma; ++j) {
+        float* Qj = c->d_Q() + (size_t)j * V;
+        int rc;
+        if (j == 0) rc = forward(c, D, D.kv_len, l - D.kv_len, Qj, false);   // catch-up, ends with the last committed token
+        else rc = forward(c, D, l + j - 1, 1, Qj, false);
+        if (rc) return rc;
+        if (launch_sample(c->stream, Qj, 1, V, T, c->cfg.seed, (uint32_t)c->round, (uint32_t)j, 0u, c->d_hist() + l + j, 1,
+                          c->d_draft() + j))
+            return c->fail(METASD_E_HIP, "launch sample_rows failed");
+    }
+    c->cur_k = k[0];
+    c->cur_gamma = gamma;
+    c->phase = PH_DRAFTED;
+    return METASD_OK;
+}
+
+int32_t metasd_verify(metasd_ctx* c, int32_t gamma) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (c->phase != PH_DRAFTED) return c->fail(METASD_E_ORDER, "verify: draft has not been run for this round");
+    if (gamma != c->cur_gamma) return c->fail(METASD_E_INVALID, "verify: gamma %d differs from the drafted %d", gamma, c->cur_gamma);
+    if (int rc = forward(c, c->target, c->l - 1, gamma + 1, c->d_P(), true)) return rc;
+    c->phase = PH_VERIFIED;
+    return METASD_OK;
+}
+
+int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t* token_out, uint32_t* mask_out, double* bd_out) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (c->phase != PH_VERIFIED) return c->fail(METASD_E_ORDER, "accept: verify has not been run for this round");
+    if (gamma != c->cur_gamma) return c->fail(METASD_E_INVALID, "accept: gamma %d differs from the drafted %d", gamma, c->cur_gamma);
+    const int V = c->target.d.vocab, l = c->l;
+    int32_t* res = c->d_res();
+    if (launch_accept(c->stream, c->d_P(), c->d_Q(), c->d_hist() + l, 1, gamma, V, c->cfg.temperature, c->cfg.seed,
+                      (uint32_t)c->round, 0u, c->d_cand(), c->d_bd(), res, res + 1, (uint32_t*)(res + 2), c->d_hist(), l))
+        return c->fail(METASD_E_HIP, "launch accept kernels failed");
+    HostResult* hr = c->hres;
+    HIP_TRY(c, hipMemcpyAsync(&hr->n_acc, res, 12, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(hr->d, c->d_draft(), (size_t)gamma * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(hr->bd, c->d_bd(), (size_t)gamma * 8, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    const int n = hr->n_acc;
+    if (n < 0 || n > gamma || hr->token < 0 || hr->token >= V) return c->fail(METASD_E_HIP, "accept: device returned n_acc %d token %d", n, hr->token);
+    for (int j = 0; j < n; ++j) c->hist[l + j] = hr->d[j];
+    c->hist[l + n] = hr->token;
+    // commit: rows 0..n of the verification block stay in the target's cache; the drafter keeps
+    // the committed prefix it has processed (it never saw d_gamma)
+    c->l = l + n + 1;
+    c->target.kv_len = l + n;
+    c->drafters[c->cur_k].kv_len = std::min(l + n, l + gamma - 1);
+    c->round += 1;
+    c->phase = PH_READY;
+    if (n_acc_out) *n_acc_out = n;
+    if (token_out) *token_out = hr->token;
+    if (mask_out) *mask_out = hr->mask;
+    if (bd_out) {
+        double s = 0.0;
+        for (int j = 0; j < gamma; ++j) s += hr->bd[j];
+        *bd_out = s / (double)gamma;
+    }
+    return METASD_OK;
+}
+
+// ---- stand-alone kernels
+
+int32_t metasd_accept_logits(const float* P, const float* Q, const int32_t* d, int32_t rows, int32_t gamma, int32_t V,
+                             float temperature, uint64_t seed, uint32_t round, uint32_t seq0, int32_t* n_acc, int32_t* token,
+                             uint32_t* mask, double* bd, void* scratch, void* hip_stream) {
+    if (!P || !Q || !d || !n_acc || !token || !scratch) return fail_global(METASD_E_INVALID, "accept_logits: NULL pointer");
+    if (rows < 1 || rows > 65535 || gamma < 1 || gamma > 31 || !valid_vocab(V) || !(temperature >= 0.f))
+        return fail_global(METASD_E_INVALID, "accept_logits: rows 1..65535, gamma 1..31, V %% 4 == 0, V <= 32768, T >= 0");
+    if (launch_accept((hipStream_t)hip_stream, P, Q, d, rows, gamma, V, temperature, seed, round, seq0, (int2*)scratch, bd, n_acc,
+                      token, mask, nullptr, 0))
+        return fail_global(METASD_E_HIP, "accept_logits: launch failed");
+    return METASD_OK;
+}
+
+int32_t metasd_sample_logits(const float* logits, int32_t rows, int32_t V, float temperature, uint64_t seed, uint32_t round,
+                             uint32_t pos, uint32_t seq0, int32_t* tok, void* hip_stream) {
+    if (!logits || !tok) return fail_global(METASD_E_INVALID, "sample_logits: NULL pointer");
+    if (rows < 1 || !valid_vocab(V) || !(temperature >= 0.f)) return fail_global(METASD_E_INVALID, "sample_logits: rows >= 1, V %% 4 == 0, V <= 32768, T >= 0");
+    if (launch_sample((hipStream_t)hip_stream, logits, rows, V, temperature, seed, round, pos, seq0, tok, 1, nullptr))
+        return fail_global(METASD_E_HIP, "sample_logits: launch failed");
+    return METASD_OK;
+}
+
+int32_t metasd_philox_words(uint64_t seed, uint32_t c0_start, int32_t n, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t* out,
+                            void* hip_stream) {
+    if (!out || n < 1) return fail_global(METASD_E_INVALID, "philox_words: bad argument");
+    hipLaunchKernelGGL(philox_words_kernel, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)hip_stream, seed, c0_start, n, c1, c2,
+                       c3, out);
+    if (hipGetLastError() != hipSuccess) return fail_global(METASD_E_HIP, "philox_words: launch failed");
+    return METASD_OK;
+}
+
+// ---- introspection
+
+int32_t metasd_peek(metasd_ctx* c, int32_t what, void** dev_ptr_out, size_t* bytes_out) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (!dev_ptr_out || !bytes_out) return c->fail(METASD_E_INVALID, "peek: NULL output");
+    const size_t V = (size_t)c->target.d.vocab;
+    switch (what) {
+        case METASD_PEEK_P: *dev_ptr_out = c->d_P(); *bytes_out = (size_t)(c->cfg.gamma_max + 1) * V * 4; break;
+        case METASD_PEEK_Q: *dev_ptr_out = c->d_Q(); *bytes_out = (size_t)c->cfg.gamma_max * V * 4; break;
+        case METASD_PEEK_HIST: *dev_ptr_out = c->d_hist(); *bytes_out = (size_t)c->cfg.max_ctx * 4; break;
+        case METASD_PEEK_BD: *dev_ptr_out = c->d_bd(); *bytes_out = (size_t)c->cfg.gamma_max * 8; break;
+        case METASD_PEEK_DRAFT: *dev_ptr_out = c->d_draft(); *bytes_out = (size_t)c->cfg.gamma_max * 4; break;
+        default: return c->fail(METASD_E_INVALID, "peek: unknown buffer %d", what);
+    }
+    return METASD_OK;
+}
+
+int32_t metasd_state(const metasd_ctx* c, int32_t model, int32_t* l_out, int32_t* kv_len_out, int32_t* round_out) {
+    if (!c || model < -1 || model >= c->cfg.K) return fail_global(METASD_E_INVALID, "state: bad argument");
+    if (l_out) *l_out = c->l;
+    if (kv_len_out) *kv_len_out = model < 0 ? c->target.kv_len : c->drafters[model].kv_len;
+    if (round_out) *round_out = c->round;
+    return METASD_OK;
+}
+
+}  // extern "C"
