@@ -1,0 +1,109 @@
+"""GPU parity of the bf16 path (MFMA skinny GEMMs on packed weights, bf16 KV cache) against the
+oracle: odd shapes spanning several tiles / attention chunks with ragged tails, then the
+1B-shape and 7B-shape configurations at full size on a synthetic KV prefix."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_05417_amd as M
+import workloads as W
+from lockstep import LockStep
+
+pytestmark = pytest.mark.gpu
+TOL = 3e-2
+
+
+def oracle_models(cfg):
+    td, tw = cfg["target"]
+    tw_np = W.to_numpy(tw)
+    cache = {id(t): a for t, a in zip(tw, tw_np) if t is not None}
+    ot = oracle.Model(td, tw_np, cfg["max_ctx"])
+    od = []
+    for dd, dw in cfg["drafters"]:
+        arrs = [None if t is None else (cache[id(t)] if id(t) in cache else W.to_numpy([t])[0]) for t in dw]
+        od.append(oracle.Model(dd, arrs, cfg["max_ctx"]))
+    return ot, od
+
+
+def fill_kv(cfg, g, ot, od, ctx, device):
+    """Same seeded synthetic KV prefix on both sides (positions [0, ctx))."""
+    models = [(cfg["target"][0], g.kv_target, ot)] + [(dd, g.kv_drafters[k], od[k]) for k, (dd, _) in enumerate(cfg["drafters"])]
+    for i, (desc, kv_gpu, om) in enumerate(models):
+        k, v = W.kv_fill(desc, ctx, cfg["kv_seed"] + i, device=device)
+        kv_gpu[:, 0, :, :ctx] = k.to(kv_gpu.device)
+        kv_gpu[:, 1, :, :ctx] = v.to(kv_gpu.device)
+        om.kv(0)[:, :, :ctx] = k.float().cpu().numpy()
+        om.kv(1)[:, :, :ctx] = v.float().cpu().numpy()
+
+
+def run_lockstep(cfg, T, rounds, kv_prefilled, device="cpu", swap_heads=False):
+    td, tw = cfg["target"]
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=cfg["gamma"], max_ctx=cfg["max_ctx"], temperature=T, seed=cfg["seed"],
+                 ucb_beta=cfg["beta"])
+    ot, od = oracle_models(cfg)
+    if kv_prefilled:
+        fill_kv(cfg, g, ot, od, len(cfg["prompt"]) - 1, device)
+    g.set_context(cfg["prompt"], kv_prefilled=kv_prefilled)
+    ls = LockStep(g, ot, od, cfg["prompt"], cfg["gamma"], T, cfg["seed"], cfg["beta"], logit_tol=TOL, kv_prefilled=kv_prefilled)
+    for r in range(rounds):
+        if swap_heads and r == rounds // 2:                # second half: the next head variant of every drafter
+            for k, (dd, dw) in enumerate(cfg["drafters"]):
+                hk = cfg["heads"][k][1]
+                g.swap_weight(k, 2 + 9 * dd["n_layers"], M.pack_weight(hk.cuda().contiguous()))
+                old = od[k]
+                od[k] = oracle.Model(dd, W.to_numpy(dw[:-1]) + W.to_numpy([hk]), cfg["max_ctx"])
+                od[k].kv(0)[:] = old.kv(0)                 # the head does not enter the KV cache
+                od[k].kv(1)[:] = old.kv(1)
+        ls.round()
+    g.close()
+    return ls.stats
+
+
+SMALL = [
+    # (target d, heads, kv heads, ffn, layers, vocab, prompt, gamma): head_dim 64/32/128, GQA, ragged everything
+    dict(d_model=256, n_heads=4, d_ffn=736, n_layers=2, vocab=1040, prompt=45, gamma=5, dd_model=128, dn_heads=2, dd_ffn=160),
+    dict(d_model=192, n_heads=6, d_ffn=352, n_layers=3, vocab=528, prompt=150, gamma=3, dd_model=96, dn_heads=3, dd_ffn=96),
+    dict(d_model=512, n_heads=4, d_ffn=1056, n_layers=2, vocab=2000 + 16, prompt=270, gamma=7, dd_model=256, dn_heads=2, dd_ffn=288),
+]
+
+
+@pytest.mark.parametrize("i", range(len(SMALL)))
+@pytest.mark.parametrize("T", [0.0, 1.0])
+def test_small_bf16_models_real_prefill(i, T):
+    s = SMALL[i]
+    cfg = W.config4(n_layers=s["n_layers"], ctx=s["prompt"], n_new=64, K=2, d_model=s["d_model"], n_heads=s["n_heads"],
+                    d_ffn=s["d_ffn"], vocab=s["vocab"], dd_model=s["dd_model"], dn_heads=s["dn_heads"], dd_ffn=s["dd_ffn"])
+    cfg["gamma"] = s["gamma"]
+    cfg["max_ctx"] = s["prompt"] + 80
+    st = run_lockstep(cfg, T, rounds=6, kv_prefilled=False, swap_heads=True)
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL, st
+    assert st["ties_shared"] <= 1, st
+
+
+def test_gqa_early_exit_drafters_real_prefill():
+    """1B-shape structure (GQA 4:1, SwiGLU, early-exit drafters sharing the target's tensors), reduced width."""
+    td = W.model_desc(4, 256, 8, 2, 512, 1024, W.SWIGLU, W.BF16)
+    tw = W.gen_weights(td, 0)
+    drafters = [W.early_exit_drafter(td, tw, e, 0.01, 100 + k) for k, e in enumerate((1, 2, 3))]
+    cfg = dict(target=(td, tw), drafters=drafters, gamma=5, prompt=W.prompt_tokens(131, 1024, 3), beta=1.0, seed=1,
+               max_ctx=131 + 64)
+    st = run_lockstep(cfg, 1.0, rounds=6, kv_prefilled=False)
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+
+
+def test_config3_1b_shape_full_size():
+    """1B-shape target at full size (16 layers, d 2048, 32/8 heads, FFN 8192, vocab 32000), K = 4
+    early-exit drafters; 512-position synthetic KV prefix instead of a CPU prefill; 3 rounds, T = 1."""
+    cfg = W.config3(device="cuda")
+    cfg["kv_seed"] = 7
+    st = run_lockstep(cfg, 1.0, rounds=3, kv_prefilled=True, device="cuda")
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+
+
+def test_config4_7b_shape_full_size():
+    """7B-shape target at full size (32 layers, d 4096, FFN 11008, vocab 32000, KV context 2048),
+    K = 5 two-layer drafters; the launch configuration bench.py times; 2 rounds, T = 1."""
+    cfg = W.config4(device="cuda")
+    st = run_lockstep(cfg, 1.0, rounds=2, kv_prefilled=True, device="cuda")
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
