@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""MetaSD hot-path benchmark on one MI355X.
+
+A step is one MetaSD round - bandit select, draft (gamma tokens from the chosen drafter), verify
+(one target pass over gamma+1 rows against the KV cache), accept, commit, bandit update - on the
+7B-shape configuration: bf16 target (32 layers, d 4096, FFN 11008, vocab 32000, KV context 2048),
+K = 5 two-layer drafters with segment-switching heads, gamma = 5, batch 1, T = 1.  All inputs are
+seeded synthetic tensors resident in HBM before the timed region.
+
+Prints ONE JSON line: verified tokens/s (sum of N_acc + 1 over the timed rounds / wall clock),
+the roofline of the dominant kernel (the bf16 weight-streaming GEMM: algorithmic bytes per launch
+/ mean launch duration from HIP events on the library's stream), and the CPU oracle timed on a
+bounded sample of the same workload on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def read_traffic():
+    """HBM bytes per GEMM launch from the committed rocprofv3 counter summary, if present."""
+    path = os.path.join(ROOT, "profiles", "gemm_bf16_c4_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get("hbm_bytes_per_launch")
+    except Exception:
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--ctx", type=int, default=2048)
+    ap.add_argument("--layers", type=int, default=32, help="target layers (32 = the 7B shape; fewer is NOT the benchmark)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rounds", type=int, default=3)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU (one process, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU available; the MetaSD library has no CPU path")
+    import paper_2604_05417_amd as M
+    import workloads as W
+
+    K_steps, Wm = args.steps, args.warmup
+    gamma = 5
+    dev = "cuda"
+    t0 = time.time()
+    cfg = W.config4(device=dev, n_layers=args.layers, ctx=args.ctx)
+    total_rounds = 2 * K_steps + Wm                              # timed pass + instrumented pass
+    cfg["max_ctx"] = args.ctx + (gamma + 1) * total_rounds + 16
+    td, tw = cfg["target"]
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=gamma, max_ctx=cfg["max_ctx"], temperature=cfg["T"],
+                 seed=cfg["seed"], ucb_beta=cfg["beta"])
+    heads = [[M.pack_weight(h.contiguous()) for h in hk] for hk in cfg["heads"]]
+    head_index = 2 + 9 * cfg["drafters"][0][0]["n_layers"]
+
+    def fill_kv(ctx):
+        models = [(td, g.kv_target)] + [(dd, g.kv_drafters[k]) for k, (dd, _) in enumerate(cfg["drafters"])]
+        for i, (desc, kv) in enumerate(models):
+            k, v = W.kv_fill(desc, ctx, cfg["kv_seed"] + i, device=dev)
+            kv[:, 0, :, :ctx] = k
+            kv[:, 1, :, :ctx] = v
+
+    fill_kv(args.ctx - 1)
+    g.set_context(cfg["prompt"], kv_prefilled=True)
+    torch.cuda.synchronize()
+    log(f"[bench] setup {time.time() - t0:.1f}s; weights {sum(t.numel() * 2 for t in tw if t is not None) / 1e9:.2f} GB")
+
+    state = dict(seg=0, new_tokens=0)
+
+    def one_round():
+        seg = (state["new_tokens"] // cfg["seg_len"]) % 4       # non-stationary drafters: head variant per segment
+        if seg != state["seg"]:
+            for k in range(g.K):
+                g.swap_weight(k, head_index, heads[k][seg])
+            state["seg"] = seg
+        k = g.bandit_select()
+        g.draft(k, gamma)
+        g.verify(gamma)
+        n, tok, mask, bd = g.accept(gamma)
+        g.bandit_update(k, n, gamma, bd)
+        state["new_tokens"] += n + 1
+        return k, n, bd
+
+    for _ in range(Wm):
+        one_round()
+    torch.cuda.synchronize()
+    # ---- timed region: exactly K steps
+    t1 = time.perf_counter()
+    toks, accs, bds, arms = 0, [], [], []
+    for _ in range(K_steps):
+        k, n, bd = one_round()
+        toks += n + 1
+        accs.append(n); bds.append(bd); arms.append(k)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t1
+    value = toks / dt
+    ms_per_step = dt / K_steps * 1e3
+
+    # ---- instrumented pass over the same kind of steps: HIP events around every launch of the
+    # bandwidth-bound kernels (library stream) and around the three phases
+    g.profile(4096 * 4)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K_steps)]
+    for i in range(K_steps):
+        k = g.bandit_select()
+        ev[i][0].record(); g.draft(k, gamma)
+        ev[i][1].record(); g.verify(gamma)
+        ev[i][2].record(); n, tok, mask, bd = g.accept(gamma)
+        ev[i][3].record()
+        g.bandit_update(k, n, gamma, bd)
+    torch.cuda.synchronize()
+    phase = [float(np.median([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(K_steps)])) for j in range(3)]
+    pg, pa, pc = g.profile_read("gemm"), g.profile_read("attn"), g.profile_read("accept")
+    g.profile(0)
+
+    def roof(p):
+        if not p["launches"]:
+            return None
+        per_launch_bytes = p["bytes"] / p["launches"]
+        avg_ms = p["ms"] / p["launches"]
+        gbs = per_launch_bytes / (avg_ms * 1e-3) / 1e9
+        return dict(launches=p["launches"], avg_us=avg_ms * 1e3, bytes_per_launch=per_launch_bytes, GBs=gbs)
+
+    rg, ra, rc = roof(pg), roof(pa), roof(pc)
+    roofline = {"bound": "hbm", "kernel": "gemm_bf16_kernel", "achieved": rg["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": rg["GBs"] / HBM_PEAK_GBS, "traffic": read_traffic(),
+                "avg_launch_us": rg["avg_us"], "algorithmic_bytes_per_launch": rg["bytes_per_launch"],
+                "launches_per_step": rg["launches"] / K_steps}
+    # verify pass as a whole against its algorithmic bytes (weights once + KV read + KV write + logits)
+    n_params = sum(t.numel() for i, t in enumerate(tw) if t is not None and i != 0)
+    kv_tok = 2 * td["n_layers"] * td["n_kv_heads"] * (td["d_model"] // td["n_heads"]) * 2
+    l_mid = args.ctx + (Wm + 1.5 * K_steps) * (np.mean(accs) + 1)
+    verify_bytes = n_params * 2 + kv_tok * l_mid + kv_tok * (gamma + 1) + (gamma + 1) * td["vocab"] * 4
+    extra = {
+        "verify_ms": phase[1], "draft_ms": phase[0], "accept_ms": phase[2],
+        "verify_hbm_frac": verify_bytes / (phase[1] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "verify_algorithmic_GB": verify_bytes / 1e9,
+        "attn_kernel": ra, "accept_kernel": rc,
+        "mean_n_acc": float(np.mean(accs)), "alpha_mean_bd": float(np.mean(bds)),
+        "arm_counts": [int(x) for x in np.bincount(arms, minlength=g.K)],
+    }
+
+    # ---- CPU oracle on a bounded sample of the same workload (same seeded tensors, same host)
+    cpu = None
+    if not args.no_cpu_baseline:
+        try:
+            cpu = cpu_baseline(cfg, args, gamma, W)
+        except Exception as e:       # the baseline is context; it never blocks the GPU result
+            log(f"[bench] cpu_baseline failed: {e!r}")
+    out = {
+        "metric": "verified tokens/sec @1 GPU (7B-shape, gamma=5)", "value": value, "unit": "tokens/s", "n_gpus": 1,
+        "steps": K_steps, "warmup": Wm, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"C4: 7B-shape bf16 target ({td['n_layers']} layers, d {td['d_model']}, FFN {td['d_ffn']}, "
+                               f"vocab {td['vocab']}), KV context {args.ctx}, K=5 two-layer d=768 drafters with "
+                               "segment-switching heads, gamma=5, batch 1, T=1, UCB beta=1, BE reward",
+                   "gamma": gamma, "batch": 1, "ctx": args.ctx, "K": g.K},
+        "roofline": roofline, "cpu_baseline": cpu, "detail": extra,
+    }
+    g.close()
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(cfg, args, gamma, W):
+    """The oracle as it stands, timed on this host for a few rounds of the same configuration."""
+    import numpy as np
+    import oracle
+    t0 = time.time()
+    td, tw = cfg["target"]
+    ctx = args.ctx
+    max_ctx = ctx + (gamma + 1) * (args.cpu_rounds + 1) + 8
+    ot = oracle.Model(td, W.to_numpy(tw), max_ctx)
+    od = [oracle.Model(dd, W.to_numpy(dw), max_ctx) for dd, dw in cfg["drafters"]]
+    models = [(td, ot)] + [(dd, od[k]) for k, (dd, _) in enumerate(cfg["drafters"])]
+    for i, (desc, om) in enumerate(models):
+        k, v = W.kv_fill(desc, ctx - 1, cfg["kv_seed"] + i, device="cuda")
+        om.kv(0)[:, :, : ctx - 1] = k.float().cpu().numpy()
+        om.kv(1)[:, :, : ctx - 1] = v.float().cpu().numpy()
+    log(f"[bench] cpu_baseline setup {time.time() - t0:.1f}s")
+    K = len(od)
+    hist = np.zeros(max_ctx, np.int32)
+    hist[:ctx] = cfg["prompt"]
+    st = oracle.SdState(hist=hist, l=ctx, c=[ctx - 1] * K)
+    bandit = oracle.Ucb(K, cfg["beta"])
+    t1 = time.perf_counter()
+    toks = 0
+    for _ in range(args.cpu_rounds):
+        k = bandit.select()
+        r = oracle.sd_round(ot, od[k], k, st, gamma, cfg["T"], cfg["seed"])
+        bandit.update(k, oracle.reward_be(r["n_acc"], gamma))
+        toks += r["n_acc"] + 1
+    dt = time.perf_counter() - t1
+    return {"value": toks / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{args.cpu_rounds} MetaSD rounds of the same C4 workload (same seeded weights and KV prefix): "
+                      f"{toks} tokens in {dt:.1f} s"}
+
+
+if __name__ == "__main__":
+    main()

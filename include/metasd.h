@@ -177,6 +177,20 @@ int32_t metasd_sample_logits(const float* logits, int32_t rows, int32_t V, float
 int32_t metasd_philox_words(uint64_t seed, uint32_t c0_start, int32_t n, uint32_t c1, uint32_t c2, uint32_t c3,
                             uint32_t* out, void* hip_stream);
 
+/* ---- per-kernel timing (measurement aid) ------------------------------------------------------ */
+
+#define METASD_PROF_GEMM 0   /* bf16 weight-streaming GEMM launches */
+#define METASD_PROF_ATTN 1   /* KV-cache attention (partial) launches */
+#define METASD_PROF_ACCEPT 2 /* accept step launches of metasd_accept */
+/* max_records > 0: from now on bracket every launch of the three bandwidth-bound kernels with a
+ * pair of HIP events on the context's stream (at most max_records launches are recorded; the
+ * pool is created here, not in the hot path) and reset the record count; 0: stop recording. */
+int32_t metasd_profile(metasd_ctx*, int32_t max_records);
+/* Synchronise and sum over the recorded launches of one kind: elapsed milliseconds, number of
+ * launches, algorithmic bytes (weights / KV / logits each counted once per launch, plus the
+ * small activation traffic).  Any output may be NULL. */
+int32_t metasd_profile_read(metasd_ctx*, int32_t kind, double* ms_total, int64_t* launches, double* bytes_total);
+
 /* ---- introspection ---------------------------------------------------------------------------- */
 
 #define METASD_PEEK_P 0     /* float [gamma_max+1][V]  target logits of the last verify */

@@ -18,10 +18,13 @@
  *                     GPU library can draw the same numbers from its own implementation.
  *
  * Precision: values are stored as float; every reduction (dot products, softmax sums, CDFs,
- * bandit means) accumulates in double.  For dtype == 1 ("bf16 model") weights are stored as
- * bf16 bit patterns and GEMM operands (normed activations, q/k/v, attention output, FFN
- * activation) are rounded to bf16 (round-to-nearest-even); the residual stream and logits stay
- * float.  These rounding points are part of the model definition, not an optimisation.
+ * bandit means) accumulates in double.  For dtype == 1 ("bf16 model") the weights and the KV
+ * cache are bf16 (K and V are rounded to nearest-even when they are written to the cache);
+ * activations, the residual stream and logits are float.  The paper does not fix an
+ * activation precision (it mentions float16 only for the memory footprint); rounding every GEMM
+ * operand to bf16 as well would make any two implementations diverge by about one bf16 ulp per
+ * element after a few layers (a single flipped rounding perturbs all later roundings), which
+ * leaves nothing tight to compare.
  *
  * Parity pins: see the header of oracle/__init__.py for which test pins which function.
  *   om_philox: parity unpinned with respect to the published generator's known-answer vectors
@@ -115,14 +118,14 @@ static void matmul(const om_desc *d, const float *x, int m, int K, const void *W
     }
 }
 
-/* out[r][:] = rnd( h[r][:] / sqrt(mean(h[r]^2) + eps) * g[:] ) */
+/* out[r][:] = h[r][:] / sqrt(mean(h[r]^2) + eps) * g[:] */
 static void rmsnorm(const om_desc *d, const float *h, int m, int D, const void *g, float *out) {
     for (int r = 0; r < m; ++r) {
         double ss = 0.0;
         for (int i = 0; i < D; ++i) ss += (double)h[(size_t)r * D + i] * (double)h[(size_t)r * D + i];
         double inv = 1.0 / sqrt(ss / (double)D + (double)d->rms_eps);
         for (int i = 0; i < D; ++i)
-            out[(size_t)r * D + i] = rnd(d, (double)h[(size_t)r * D + i] * inv * wget(d, g, (size_t)i));
+            out[(size_t)r * D + i] = (float)((double)h[(size_t)r * D + i] * inv * wget(d, g, (size_t)i));
     }
 }
 
@@ -206,7 +209,6 @@ int om_forward(om_model *M, const int32_t *tokens, int m, int pos0, float *logit
             for (int hh = 0; hh < H; ++hh) {
                 float *qv = q + (size_t)r * DQ + (size_t)hh * hd;
                 om_rope(qv, hd, pos0 + r, d->rope_theta);
-                for (int i = 0; i < hd; ++i) qv[i] = rnd(d, qv[i]);
             }
             for (int kh = 0; kh < KH; ++kh) {
                 float *kv = k + (size_t)r * DKV + (size_t)kh * hd;
@@ -244,7 +246,7 @@ int om_forward(om_model *M, const int32_t *tokens, int m, int pos0, float *logit
                     double pw = s[p] / Z;
                     for (int i = 0; i < hd; ++i) acc[i] += pw * (double)Vc[(size_t)p * hd + i];
                 }
-                for (int i = 0; i < hd; ++i) o[(size_t)r * DQ + (size_t)hh * hd + i] = rnd(d, acc[i]);
+                for (int i = 0; i < hd; ++i) o[(size_t)r * DQ + (size_t)hh * hd + i] = (float)acc[i];
             }
             free(s); free(acc);
         }
@@ -255,9 +257,9 @@ int om_forward(om_model *M, const int32_t *tokens, int m, int pos0, float *logit
         matmul(d, a, m, D, w[7], F, u);
         if (d->act == 1) {
             matmul(d, a, m, D, w[6], F, g);
-            for (size_t i = 0; i < (size_t)m * F; ++i) u[i] = rnd(d, silu((double)g[i]) * (double)u[i]);
+            for (size_t i = 0; i < (size_t)m * F; ++i) u[i] = (float)(silu((double)g[i]) * (double)u[i]);
         } else {
-            for (size_t i = 0; i < (size_t)m * F; ++i) u[i] = rnd(d, gelu_erf((double)u[i]));
+            for (size_t i = 0; i < (size_t)m * F; ++i) u[i] = (float)gelu_erf((double)u[i]);
         }
         matmul(d, u, m, F, w[8], D, y);
         for (size_t i = 0; i < (size_t)m * D; ++i) h[i] = (float)((double)h[i] + (double)y[i]);

@@ -14,7 +14,7 @@ MATRIX_SLOTS = (1, 2, 3, 4, 6, 7, 8)          # wq wk wv wo w_gate w_up w_down w
 EXPORTS = ["metasd_kv_bytes", "metasd_workspace_bytes", "metasd_pack_weight", "metasd_create", "metasd_destroy",
            "metasd_set_context", "metasd_swap_weight", "metasd_bandit_select", "metasd_bandit_update",
            "metasd_bandit_state", "metasd_draft", "metasd_verify", "metasd_accept", "metasd_accept_logits",
-           "metasd_sample_logits", "metasd_philox_words", "metasd_peek", "metasd_state", "metasd_last_error"]
+           "metasd_sample_logits", "metasd_philox_words", "metasd_profile", "metasd_profile_read", "metasd_peek", "metasd_state", "metasd_last_error"]
 
 
 class MetaSDError(RuntimeError):
@@ -69,6 +69,8 @@ def load_library():
         "metasd_accept_logits": [vp, vp, vp, i32, i32, i32, f32, u64, u32, u32, vp, vp, vp, vp, vp, vp],
         "metasd_sample_logits": [vp, i32, i32, f32, u64, u32, u32, u32, vp, vp],
         "metasd_philox_words": [u64, u32, i32, u32, u32, u32, vp, vp],
+        "metasd_profile": [vp, i32],
+        "metasd_profile_read": [vp, i32, C.POINTER(f64), C.POINTER(C.c_int64), C.POINTER(f64)],
         "metasd_peek": [vp, i32, C.POINTER(vp), C.POINTER(sz)],
         "metasd_state": [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)],
     }
@@ -248,6 +250,14 @@ class MetaSD:
         if what in ("hist", "draft"):
             return raw.view(torch.int32)
         return raw.view(torch.float64)
+
+    def profile(self, max_records: int):
+        _check(self.L.metasd_profile(self._h, max_records), self._h)
+
+    def profile_read(self, kind: str) -> dict:
+        ms, n, by = C.c_double(0), C.c_int64(0), C.c_double(0)
+        _check(self.L.metasd_profile_read(self._h, {"gemm": 0, "attn": 1, "accept": 2}[kind], C.byref(ms), C.byref(n), C.byref(by)), self._h)
+        return dict(ms=ms.value, launches=n.value, bytes=by.value)
 
     def state(self, model: int = -1):
         l, kv, r = C.c_int32(0), C.c_int32(0), C.c_int32(0)

@@ -109,12 +109,12 @@ __global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restric
 // ------------------------------------------------------------------------------------------
 // residual add of split-K partial sums + RMSNorm:      grid (m), block 256
 //   h[r] += sum_s part[s][r]   (skipped when nsplit == 0)
-//   xn[r] = T( h[r] / sqrt(mean(h[r]^2) + eps) * gain )
+//   xn[r] = h[r] / sqrt(mean(h[r]^2) + eps) * gain          (fp32; T is the type of the gain)
 
 template <typename T>
 __global__ __launch_bounds__(256) void addnorm_kernel(float* __restrict__ h, const float* __restrict__ part, int nsplit,
                                                       size_t sstride, int d, const T* __restrict__ gain, float eps,
-                                                      T* __restrict__ xn) {
+                                                      float* __restrict__ xn) {
     __shared__ float red[4];
     const int r = blockIdx.x;
     float* hr = h + (size_t)r * d;
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(256) void addnorm_kernel(float* __restrict__ h, con
     const float tot = (red[0] + red[1]) + (red[2] + red[3]);
     const float inv = 1.0f / sqrtf(tot / (float)d + eps);
     if (xn)
-        for (int i = threadIdx.x; i < d; i += 256) xn[(size_t)r * d + i] = El<T>::st(hr[i] * inv * El<T>::ld(gain[i]));
+        for (int i = threadIdx.x; i < d; i += 256) xn[(size_t)r * d + i] = hr[i] * inv * El<T>::ld(gain[i]);
 }
 
 // out[i] = sum_s part[s][i]                         (only for logits when the head GEMM is split)
@@ -188,37 +188,54 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 // Weights are in streaming-tile order (see pack_weight_kernel): tile (t, c) is 1 KiB holding
 // output features 16t..16t+15 and inputs 32c..32c+31; lane l owns 16 bytes = 8 consecutive inputs
 // 32c + 8(l/16).. of feature 16t + l%16 - exactly the A operand of v_mfma_f32_16x16x32_bf16, so
-// one wavefront load instruction reads one contiguous KiB.  The activations (m <= 16 rows) are
-// the B operand, staged once per workgroup in LDS.  D[i][j] = sum_k A[i][k] B[k][j]: lane l gets
-// D[4(l/16)+v][l%16], v = 0..3, i.e. 4 consecutive output features of activation row l%16.
+// one wavefront load instruction reads one contiguous KiB.  The activations (m <= 16 rows, fp32
+// in memory) are the B operand, staged once per workgroup in LDS as two bf16 terms x = hi + lo
+// (hi = bf16(x), lo = bf16(x - hi)): each weight tile feeds two MFMAs, which keeps ~16 mantissa
+// bits of the activations at no HBM cost (the matrix cores idle >95 % of the time here anyway).
+// D[i][j] = sum_k A[i][k] B[k][j]: lane l gets D[4(l/16)+v][l%16], v = 0..3, i.e. 4 consecutive
+// output features of activation row l%16.
 //
 // Work split: workgroup = (tile group tg, k-split ks); its 4 wavefronts take tiles
 // tg*tpb + wave, +4, ...; the k-split covers chunks [ks*cps, ks*cps + cps).  Partial sums go to
 // out[ks][r][n] (row stride N, split stride m*N) and are added by the consumer kernel.
 // Up to three matrices are concatenated along n at tile boundaries t0 <= t1 <= ntiles.
-//   grid (ceil(ntiles/tpb) * ksplit), block 256, dynamic LDS m * (cps*4 + 1) * 16 bytes.
+//   grid (ceil(ntiles/tpb) * ksplit), block 256, dynamic LDS 2 * m * (cps*4 + 1) * 16 bytes.
 
 constexpr int GEMM_U = 8;  // tiles in flight per wavefront (8 KiB)
 
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ x, int ldx, int m, int K,
+__device__ __forceinline__ uint32_t pack_bf16x2(bf16_t lo, bf16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
+
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict__ x, int ldx, int m, int K,
                                                         const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
                                                         const bf16_t* __restrict__ W2, int t0, int t1, int ntiles,
                                                         float* __restrict__ out, int N, int ksplit, int cps, int tpb) {
-    extern __shared__ uint4 xs[];
+    extern __shared__ uint4 xs[];   // [2 (hi, lo)][m][rs]
     const int kchunks = K >> 5;
     const int ks = blockIdx.x % ksplit, tg = blockIdx.x / ksplit;
     const int c0 = ks * cps;
     const int nc = min(cps, kchunks - c0);
     const int rs = cps * 4 + 1;  // LDS row stride in 16-byte units (+1 pads away bank conflicts)
+    uint4* xlo = xs + m * rs;
     for (int idx = threadIdx.x; idx < m * nc * 4; idx += 256) {
         const int r = idx / (nc * 4), c = idx - r * (nc * 4);
-        xs[r * rs + c] = *reinterpret_cast<const uint4*>(x + (size_t)r * ldx + (size_t)c0 * 32 + (size_t)c * 8);
+        const float* src = x + (size_t)r * ldx + (size_t)c0 * 32 + (size_t)c * 8;
+        const float4 a = *reinterpret_cast<const float4*>(src), b = *reinterpret_cast<const float4*>(src + 4);
+        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        bf16_t hi[8], lo[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            hi[e] = f2bf(v[e]);
+            lo[e] = f2bf(v[e] - bf2f(hi[e]));
+        }
+        xs[r * rs + c] = make_uint4(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]), pack_bf16x2(hi[4], hi[5]), pack_bf16x2(hi[6], hi[7]));
+        xlo[r * rs + c] = make_uint4(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(lo[4], lo[5]), pack_bf16x2(lo[6], lo[7]));
     }
     __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row = lane & 15, g = lane >> 4;
     const bool rowok = row < m;
     const uint4* xa = xs + (rowok ? row : 0) * rs + g;
+    const uint4* xb = xlo + (rowok ? row : 0) * rs + g;
     const uint4 zero = make_uint4(0, 0, 0, 0);
     for (int tt = wave; tt < tpb; tt += 4) {
         const int t = tg * tpb + tt;
@@ -229,7 +246,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
         else if (t < t1) { W = W1; tl = t - t0; }
         else { W = W2; tl = t - t1; }
         const u32x4* wp = reinterpret_cast<const u32x4*>(W) + ((size_t)tl * kchunks + c0) * 64 + lane;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acl = {0.f, 0.f, 0.f, 0.f};
         int c = 0;
         for (; c + GEMM_U <= nc; c += GEMM_U) {
             u32x4 w[GEMM_U];
@@ -237,20 +254,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
             for (int u = 0; u < GEMM_U; ++u) w[u] = __builtin_nontemporal_load(wp + (size_t)(c + u) * 64);
 #pragma unroll
             for (int u = 0; u < GEMM_U; ++u) {
-                uint4 a = xa[(c + u) * 4];
-                if (!rowok) a = zero;
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, a), acc, 0, 0, 0);
+                uint4 ah = xa[(c + u) * 4], al = xb[(c + u) * 4];
+                if (!rowok) { ah = zero; al = zero; }
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, ah), acc, 0, 0, 0);
+                acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, al), acl, 0, 0, 0);
             }
         }
         for (; c < nc; ++c) {
             const u32x4 w = __builtin_nontemporal_load(wp + (size_t)c * 64);
-            uint4 a = xa[c * 4];
-            if (!rowok) a = zero;
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, a), acc, 0, 0, 0);
+            uint4 ah = xa[c * 4], al = xb[c * 4];
+            if (!rowok) { ah = zero; al = zero; }
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, ah), acc, 0, 0, 0);
+            acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, al), acl, 0, 0, 0);
         }
         if (rowok) {
             float* o = out + (size_t)ks * m * N + (size_t)row * N + (size_t)t * 16 + g * 4;
-            *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            *reinterpret_cast<float4*>(o) = make_float4(acc[0] + acl[0], acc[1] + acl[1], acc[2] + acl[2], acc[3] + acl[3]);
         }
     }
 }
@@ -273,11 +292,11 @@ __global__ void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restr
 // ------------------------------------------------------------------------------------------
 // RoPE (rotate-half pairing, angle = pos * theta^(-2i/hd)) on q and k, K/V cache append.
 //   part: split-K partials of the fused q|k|v projection, [s][r][N], N = (H + 2 KH) * hd.
-//   q out [m][H*hd]; cache planes [kv_head][max_ctx][hd].     grid (H + 2KH, m), block 64
+//   q out fp32 [m][H*hd]; cache planes (type T) [kv_head][max_ctx][hd].     grid (H + 2KH, m), block 64
 
 template <typename T>
 __global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int N, int pos0, int H, int KH,
-                               int hd, float theta, T* __restrict__ q, T* __restrict__ kc, T* __restrict__ vc, int max_ctx) {
+                               int hd, float theta, float* __restrict__ q, T* __restrict__ kc, T* __restrict__ vc, int max_ctx) {
     const int head = blockIdx.x, r = blockIdx.y, i = threadIdx.x, half = hd >> 1;
     if (i >= half) return;
     const size_t col = (size_t)r * N + (size_t)head * hd + i;
@@ -295,9 +314,14 @@ __global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_
         const float rb = (float)((double)a * sn + (double)b * cs);
         a = ra; b = rb;
     }
+    if (head < H) {
+        float* qd = q + (size_t)r * H * hd + (size_t)head * hd;
+        qd[i] = a;
+        qd[i + half] = b;
+        return;
+    }
     T* dst;
-    if (head < H) dst = q + (size_t)r * H * hd + (size_t)head * hd;
-    else if (head < H + KH) dst = kc + ((size_t)(head - H) * max_ctx + pos) * hd;
+    if (head < H + KH) dst = kc + ((size_t)(head - H) * max_ctx + pos) * hd;
     else dst = vc + ((size_t)(head - H - KH) * max_ctx + pos) * hd;
     dst[i] = El<T>::st(a);
     dst[i + half] = El<T>::st(b);
@@ -308,12 +332,12 @@ __global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_
 // (row r sees positions 0..pos0+r), split along the KV length in chunks of 128 positions.
 // K and V chunks are staged in LDS with coalesced 16-byte loads; scores, softmax and PV in fp32.
 //   partial kernel: grid (nchunks, H), block 256 -> part[h][c][16][HD+2] = (o[HD], max, sum)
-//   combine kernel: grid (H, m), block HD        -> out[r][h*HD + :] = T( sum_c o_c e^{m_c-M} / sum_c l_c e^{m_c-M} )
+//   combine kernel: grid (H, m), block HD        -> out[r][h*HD + :] = sum_c o_c e^{m_c-M} / sum_c l_c e^{m_c-M}
 
 constexpr int ATT_CH = 128;
 
 template <typename T, int HD>
-__global__ __launch_bounds__(256) void attn_partial_kernel(const T* __restrict__ q, const T* __restrict__ kc,
+__global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restrict__ q, const T* __restrict__ kc,
                                                            const T* __restrict__ vc, int m, int pos0, int H, int KH,
                                                            int max_ctx, float scale, float* __restrict__ part, int nchunks) {
     constexpr int EPV = 16 / (int)sizeof(T);     // elements per 16-byte piece
@@ -335,7 +359,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const T* __restrict__
 
     for (int idx = tid; idx < m * HD; idx += 256) {
         const int r = idx / HD, i = idx - r * HD;
-        qs[idx] = El<T>::ld(q[(size_t)r * H * HD + (size_t)h * HD + i]);
+        qs[idx] = q[(size_t)r * H * HD + (size_t)h * HD + i];
     }
     const T* kbase = kc + ((size_t)kh * max_ctx + p0) * HD;
     for (int idx = tid; idx < np * VPR; idx += 256) {
@@ -429,7 +453,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const T* __restrict__
 }
 
 template <typename T, int HD>
-__global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks, int H, T* __restrict__ out) {
+__global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks, int H, float* __restrict__ out) {
     const int h = blockIdx.x, r = blockIdx.y, col = threadIdx.x;
     const float* base = part + ((size_t)h * nchunks * 16 + r) * (HD + 2);
     const size_t cs = (size_t)16 * (HD + 2);
@@ -443,16 +467,15 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks,
         Lsum += base[c * cs + HD + 1] * w;
         o += base[c * cs + col] * w;
     }
-    out[(size_t)r * H * HD + (size_t)h * HD + col] = El<T>::st(o / Lsum);
+    out[(size_t)r * H * HD + (size_t)h * HD + col] = o / Lsum;
 }
 
 // ------------------------------------------------------------------------------------------
 // FFN activation on split-K partials:  SwiGLU  out = silu(gate) * up  (part columns: gate | up),
 //                                      GELU    out = 0.5 u (1 + erf(u / sqrt 2)).
 
-template <typename T>
 __global__ void ffn_act_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int m, int f, int act,
-                               T* __restrict__ out) {
+                               float* __restrict__ out) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)m * f) return;
     const int r = (int)(idx / f), i = (int)(idx - (size_t)r * f);
@@ -462,11 +485,11 @@ __global__ void ffn_act_kernel(const float* __restrict__ part, int nsplit, size_
             g += part[(size_t)s * sstride + (size_t)r * 2 * f + i];
             u += part[(size_t)s * sstride + (size_t)r * 2 * f + f + i];
         }
-        out[idx] = El<T>::st(g / (1.0f + expf(-g)) * u);
+        out[idx] = g / (1.0f + expf(-g)) * u;
     } else {
         float u = 0.f;
         for (int s = 0; s < nsplit; ++s) u += part[(size_t)s * sstride + (size_t)r * f + i];
-        out[idx] = El<T>::st(0.5f * u * (1.0f + erff(u * 0.70710678118654752f)));
+        out[idx] = 0.5f * u * (1.0f + erff(u * 0.70710678118654752f));
     }
 }
 

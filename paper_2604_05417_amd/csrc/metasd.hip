@@ -57,7 +57,7 @@ struct Split {
 };
 
 Split choose_split(int m, int ntiles, int kchunks) {
-    const int cps_max = std::max(1, ((LDS_BUDGET / 16 / m) - 1) / 4);
+    const int cps_max = std::max(1, ((LDS_BUDGET / 32 / m) - 1) / 4);   // two bf16 terms per activation
     int want = (2048 + ntiles / 2) / ntiles;                      // aim for about 2048 wavefront work units
     want = std::max(1, std::min(want, 8));
     want = std::min(want, std::max(1, kchunks / 8));              // at least 8 chunks per slice
@@ -68,7 +68,7 @@ Split choose_split(int m, int ntiles, int kchunks) {
     s.ksplit = ks;
     s.cps = cps;
     s.tpb = 4;
-    s.lds = (size_t)m * (cps * 4 + 1) * 16;
+    s.lds = (size_t)2 * m * (cps * 4 + 1) * 16;
     return s;
 }
 
@@ -172,6 +172,18 @@ struct metasd_ctx {
     Bandit bandit;
     HostResult* hres = nullptr;
     std::string err;
+    // optional per-launch timing of the three bandwidth-bound kernels (metasd_profile)
+    struct ProfRec { hipEvent_t a, b; int kind; double bytes; };
+    bool prof_on = false;
+    std::vector<ProfRec> prof;       // event pool
+    size_t prof_used = 0;
+    bool prof_begin(int kind, double bytes) {
+        if (!prof_on || prof_used >= prof.size()) return false;
+        prof[prof_used].kind = kind;
+        prof[prof_used].bytes = bytes;
+        return hipEventRecord(prof[prof_used].a, stream) == hipSuccess;
+    }
+    void prof_end() { (void)hipEventRecord(prof[prof_used].b, stream); ++prof_used; }
 
     int32_t* d_hist() const { return reinterpret_cast<int32_t*>(ws + lay.hist); }
     float* d_h() const { return reinterpret_cast<float*>(ws + lay.h); }
@@ -240,9 +252,12 @@ int gemm<bf16_t>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void
     const Split s = choose_split(m, ntiles, kchunks);
     float* out = (direct_out && s.ksplit == 1) ? direct_out : c->d_part();
     const int groups = (ntiles + s.tpb - 1) / s.tpb;
-    hipLaunchKernelGGL(gemm_bf16_kernel, dim3(groups * s.ksplit), dim3(256), s.lds, c->stream, (const bf16_t*)x, ldx, m, K,
+    // algorithmic bytes: every weight once, the activations once, the result once
+    const bool timed = c->prof_begin(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
+    hipLaunchKernelGGL(gemm_bf16_kernel, dim3(groups * s.ksplit), dim3(256), s.lds, c->stream, (const float*)x, ldx, m, K,
                        (const bf16_t*)W0, (const bf16_t*)W1, (const bf16_t*)W2, n0 / 16, (n0 + n1) / 16, ntiles, out, N,
                        s.ksplit, s.cps, s.tpb);
+    if (timed) c->prof_end();
     LAUNCH_CHECK(c, "gemm_bf16");
     if (direct_out && s.ksplit > 1) {
         const size_t n = (size_t)m * N;
@@ -262,11 +277,15 @@ int attention_hd(metasd_ctx* c, const Model& M, int L, int pos0, int m) {
     const T* vc = kc + plane;
     const int nchunks = (pos0 + m + ATT_CH - 1) / ATT_CH;
     const float scale = 1.0f / sqrtf((float)HD);
-    hipLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(nchunks, d.n_heads), dim3(256), 0, c->stream, (const T*)c->d_q(), kc,
+    // algorithmic bytes: K and V of every cached position once per KV head, q in, partials out
+    const bool timed = c->prof_begin(METASD_PROF_ATTN, 2.0 * d.n_kv_heads * (double)(pos0 + m) * HD * sizeof(T) +
+                                                          (double)m * d.n_heads * HD * 4);
+    hipLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(nchunks, d.n_heads), dim3(256), 0, c->stream, (const float*)c->d_q(), kc,
                        vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale, c->d_apart(), nchunks);
+    if (timed) c->prof_end();
     LAUNCH_CHECK(c, "attn_partial");
     hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3(d.n_heads, m), dim3(HD), 0, c->stream, c->d_apart(), nchunks,
-                       d.n_heads, (T*)c->d_ao());
+                       d.n_heads, (float*)c->d_ao());
     LAUNCH_CHECK(c, "attn_combine");
     return 0;
 }
@@ -292,7 +311,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
     const int DQ = H * hd, DKV = KH * hd;
     hipStream_t st = c->stream;
     float* h = c->d_h();
-    T* xn = (T*)c->d_xn();
+    float* xn = (float*)c->d_xn();
     float* part = c->d_part();
     int ns = 0, rc;
     hipLaunchKernelGGL(embed_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, h);
@@ -307,7 +326,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
         hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, part, ns, (size_t)m * NQKV, NQKV, pos0, H, KH,
-                           hd, d.rope_theta, (T*)c->d_q(), kc, kc + plane, c->cfg.max_ctx);
+                           hd, d.rope_theta, (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx);
         LAUNCH_CHECK(c, "rope_kv");
         if ((rc = attention<T>(c, M, L, pos0, m))) return rc;
         if ((rc = gemm<T>(c, c->d_ao(), DQ, m, DQ, M.layer_w(L, 4), D, nullptr, 0, nullptr, 0, nullptr, &ns))) return rc;
@@ -321,8 +340,8 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         }
         const size_t nact = (size_t)m * F;
         const int NF = (d.act == METASD_SWIGLU ? 2 : 1) * F;
-        hipLaunchKernelGGL(ffn_act_kernel<T>, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)m * NF, m, F,
-                           d.act, (T*)c->d_act());
+        hipLaunchKernelGGL(ffn_act_kernel, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)m * NF, m, F,
+                           d.act, (float*)c->d_act());
         LAUNCH_CHECK(c, "ffn_act");
         if ((rc = gemm<T>(c, c->d_act(), F, m, F, M.layer_w(L, 8), D, nullptr, 0, nullptr, 0, nullptr, &ns))) return rc;
     }
@@ -491,6 +510,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
 int32_t metasd_destroy(metasd_ctx* c) {
     if (!c) return METASD_OK;
     if (c->hres) (void)hipHostFree(c->hres);
+    for (auto& r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     delete c;
     return METASD_OK;
 }
@@ -612,9 +632,11 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
     if (gamma != c->cur_gamma) return c->fail(METASD_E_INVALID, "accept: gamma %d differs from the drafted %d", gamma, c->cur_gamma);
     const int V = c->target.d.vocab, l = c->l;
     int32_t* res = c->d_res();
+    const bool timed = c->prof_begin(METASD_PROF_ACCEPT, (double)(2 * gamma + 1) * V * 4);
     if (launch_accept(c->stream, c->d_P(), c->d_Q(), c->d_hist() + l, 1, gamma, V, c->cfg.temperature, c->cfg.seed,
                       (uint32_t)c->round, 0u, c->d_cand(), c->d_bd(), res, res + 1, (uint32_t*)(res + 2), c->d_hist(), l))
         return c->fail(METASD_E_HIP, "launch accept kernels failed");
+    if (timed) c->prof_end();
     HostResult* hr = c->hres;
     HIP_TRY(c, hipMemcpyAsync(&hr->n_acc, res, 12, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipMemcpyAsync(hr->d, c->d_draft(), (size_t)gamma * 4, hipMemcpyDeviceToHost, c->stream));
@@ -671,6 +693,42 @@ int32_t metasd_philox_words(uint64_t seed, uint32_t c0_start, int32_t n, uint32_
     hipLaunchKernelGGL(philox_words_kernel, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)hip_stream, seed, c0_start, n, c1, c2,
                        c3, out);
     if (hipGetLastError() != hipSuccess) return fail_global(METASD_E_HIP, "philox_words: launch failed");
+    return METASD_OK;
+}
+
+// ---- per-kernel timing
+
+int32_t metasd_profile(metasd_ctx* c, int32_t max_records) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (max_records < 0 || max_records > (1 << 20)) return c->fail(METASD_E_INVALID, "profile: max_records out of range");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    while ((int)c->prof.size() < max_records) {
+        metasd_ctx::ProfRec r{};
+        HIP_TRY(c, hipEventCreate(&r.a));
+        hipError_t e = hipEventCreate(&r.b);
+        if (e != hipSuccess) { (void)hipEventDestroy(r.a); return c->fail(METASD_E_HIP, "hipEventCreate: %s", hipGetErrorString(e)); }
+        c->prof.push_back(r);
+    }
+    c->prof_used = 0;
+    c->prof_on = max_records > 0;
+    return METASD_OK;
+}
+
+int32_t metasd_profile_read(metasd_ctx* c, int32_t kind, double* ms_total, int64_t* launches, double* bytes_total) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (kind < 0 || kind > 2) return c->fail(METASD_E_INVALID, "profile_read: unknown kind %d", kind);
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    double ms = 0.0, by = 0.0;
+    int64_t n = 0;
+    for (size_t i = 0; i < c->prof_used; ++i) {
+        if (c->prof[i].kind != kind) continue;
+        float t = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&t, c->prof[i].a, c->prof[i].b));
+        ms += t; by += c->prof[i].bytes; ++n;
+    }
+    if (ms_total) *ms_total = ms;
+    if (launches) *launches = n;
+    if (bytes_total) *bytes_total = by;
     return METASD_OK;
 }
 

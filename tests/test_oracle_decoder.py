@@ -13,8 +13,8 @@ import workloads as W
 
 
 def torch_forward(desc, weights, tokens, bf16=False):
-    """Prefill from an empty cache, library ops only.  bf16: round GEMM operands like the oracle."""
-    rnd = (lambda x: x.to(torch.bfloat16).to(torch.float64)) if bf16 else (lambda x: x)
+    """Prefill from an empty cache, library ops only.  bf16: K and V are rounded when cached, like the oracle."""
+    rnd = (lambda x: x.to(torch.float32).to(torch.bfloat16).to(torch.float64)) if bf16 else (lambda x: x)
     f32 = lambda x: x.to(torch.float32).to(torch.float64)
     w = [None if t is None else t.to(torch.float64) for t in weights]
     d, H, KH = desc["d_model"], desc["n_heads"], desc["n_kv_heads"]
@@ -31,20 +31,20 @@ def torch_forward(desc, weights, tokens, bf16=False):
 
     for L in range(desc["n_layers"]):
         an, wq, wk, wv, wo, fn, wg, wu, wd = w[1 + 9 * L: 10 + 9 * L]
-        a = rnd(F.rms_norm(h, (d,), an, desc["rms_eps"]))
-        q = rnd(rope(f32(F.linear(a, wq)).view(m, H, hd)))
+        a = f32(F.rms_norm(h, (d,), an, desc["rms_eps"]))
+        q = rope(f32(F.linear(a, wq)).view(m, H, hd))
         k = rnd(rope(f32(F.linear(a, wk)).view(m, KH, hd)))
         v = rnd(f32(F.linear(a, wv)).view(m, KH, hd))
         o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None], v.transpose(0, 1)[None],
                                            is_causal=True, enable_gqa=True)[0].transpose(0, 1).reshape(m, d)
-        h = f32(h + f32(F.linear(rnd(o), wo)))
-        b = rnd(F.rms_norm(h, (d,), fn, desc["rms_eps"]))
+        h = f32(h + f32(F.linear(f32(o), wo)))
+        b = f32(F.rms_norm(h, (d,), fn, desc["rms_eps"]))
         if desc["act"] == W.SWIGLU:
-            act = rnd(F.silu(f32(F.linear(b, wg))) * f32(F.linear(b, wu)))
+            act = f32(F.silu(f32(F.linear(b, wg))) * f32(F.linear(b, wu)))
         else:
-            act = rnd(F.gelu(f32(F.linear(b, wu))))
+            act = f32(F.gelu(f32(F.linear(b, wu))))
         h = f32(h + f32(F.linear(act, wd)))
-    x = rnd(F.rms_norm(h, (d,), w[-2], desc["rms_eps"]))
+    x = f32(F.rms_norm(h, (d,), w[-2], desc["rms_eps"]))
     return f32(F.linear(x, w[-1])).numpy()
 
 
@@ -63,11 +63,11 @@ def test_forward_matches_library_model(name):
     M = oracle.Model(desc, W.to_numpy(w), 32)
     got = M.forward(toks, 0, "all")
     want = torch_forward(desc, w, toks, bf16=desc["dtype"] == W.BF16)
-    tol = 2e-2 if desc["dtype"] == W.BF16 else 2e-5       # bf16: a rounding flip moves an operand by 2^-8
+    tol = 2e-3 if desc["dtype"] == W.BF16 else 2e-5       # bf16: a K/V rounding flip moves one cache entry by 2^-8
     assert np.abs(got - want).max() < tol
     assert np.abs(want).max() > 0.1                        # the comparison is not vacuous
     if desc["dtype"] == W.BF16:
-        assert np.median(np.abs(got - want)) < 2e-4
+        assert np.median(np.abs(got - want)) < 2e-5
 
 
 def test_block_equals_single_rows_and_cache_reuse():
