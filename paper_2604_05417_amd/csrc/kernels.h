@@ -107,35 +107,48 @@ __global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restric
 }
 
 // ------------------------------------------------------------------------------------------
-// residual add of split-K partial sums + RMSNorm:      grid (m), block 256
+// residual add of split-K partial sums + RMSNorm:      grid (m), block 1024, d % 4 == 0
 //   h[r] += sum_s part[s][r]   (skipped when nsplit == 0)
 //   xn[r] = h[r] / sqrt(mean(h[r]^2) + eps) * gain          (fp32; T is the type of the gain)
 
 template <typename T>
-__global__ __launch_bounds__(256) void addnorm_kernel(float* __restrict__ h, const float* __restrict__ part, int nsplit,
-                                                      size_t sstride, int d, const T* __restrict__ gain, float eps,
-                                                      float* __restrict__ xn) {
-    __shared__ float red[4];
+__global__ __launch_bounds__(1024) void addnorm_kernel(float* __restrict__ h, const float* __restrict__ part, int nsplit,
+                                                       size_t sstride, int d, const T* __restrict__ gain, float eps,
+                                                       float* __restrict__ xn) {
+    __shared__ float red[16];
     const int r = blockIdx.x;
     float* hr = h + (size_t)r * d;
     float ss = 0.f;
-    for (int i = threadIdx.x; i < d; i += 256) {
-        float v = hr[i];
+    for (int i = threadIdx.x * 4; i < d; i += 4096) {
+        float4 v = *reinterpret_cast<const float4*>(hr + i);
         if (nsplit > 0) {
-            float y = 0.f;
-            for (int s = 0; s < nsplit; ++s) y += part[(size_t)s * sstride + (size_t)r * d + i];
-            v += y;
-            hr[i] = v;
+            float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int s = 0; s < nsplit; ++s) {      // fixed order: deterministic
+                const float4 p = *reinterpret_cast<const float4*>(part + (size_t)s * sstride + (size_t)r * d + i);
+                y.x += p.x; y.y += p.y; y.z += p.z; y.w += p.w;
+            }
+            v.x += y.x; v.y += y.y; v.z += y.z; v.w += y.w;
+            *reinterpret_cast<float4*>(hr + i) = v;
         }
-        ss += v * v;
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
     ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
-    const float tot = (red[0] + red[1]) + (red[2] + red[3]);
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += red[w];
     const float inv = 1.0f / sqrtf(tot / (float)d + eps);
     if (xn)
-        for (int i = threadIdx.x; i < d; i += 256) xn[(size_t)r * d + i] = hr[i] * inv * El<T>::ld(gain[i]);
+        for (int i = threadIdx.x * 4; i < d; i += 4096) {
+            const float4 v = *reinterpret_cast<const float4*>(hr + i);
+            float4 o;
+            o.x = v.x * inv * El<T>::ld(gain[i]);
+            o.y = v.y * inv * El<T>::ld(gain[i + 1]);
+            o.z = v.z * inv * El<T>::ld(gain[i + 2]);
+            o.w = v.w * inv * El<T>::ld(gain[i + 3]);
+            *reinterpret_cast<float4*>(xn + (size_t)r * d + i) = o;
+        }
 }
 
 // out[i] = sum_s part[s][i]                         (only for logits when the head GEMM is split)
@@ -452,6 +465,158 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
     }
 }
 
+// bf16-cache variant on MFMA.  One workgroup (4 wavefronts) per (chunk of 128 positions, query head):
+//   S^T[pos][row] = K[pos][:] . q[row][:]   A = K rows straight from global (16 B per lane, no LDS),
+//                                           B = q as two bf16 terms (hi + lo); wavefront w owns
+//                                           positions 32w .. 32w+31 of the chunk;
+//   softmax numerators p = exp(s - max) per row over the chunk (shuffles across the 4 lane groups,
+//   LDS across the 4 wavefronts), written to LDS as P[row][pos] in two bf16 terms;
+//   O^T[hd][row] = V^T[hd][pos] . P^T[pos][row]   A = V gathered from the LDS-staged V chunk,
+//                                           wavefront w owns head-dim tiles {w, w+4, ..}.
+// Output layout and the combine kernel are shared with the generic kernel above.
+
+template <int HD>
+__global__ __launch_bounds__(256) void attn_partial_mfma_kernel(const float* __restrict__ q, const bf16_t* __restrict__ kc,
+                                                                const bf16_t* __restrict__ vc, int m, int pos0, int H, int KH,
+                                                                int max_ctx, float scale, float* __restrict__ part, int nchunks) {
+    constexpr int RS = HD + 8;                 // padded LDS row stride of the V chunk (elements)
+    constexpr int VPR = HD / 8;                // 16-byte pieces per row
+    constexpr int PS = ATT_CH + 8;             // padded row stride of P (elements)
+    constexpr int KC = HD / 32;                // 32-wide head-dim chunks
+    constexpr int NT = HD / 16;                // 16-wide head-dim tiles
+    __shared__ __align__(16) bf16_t vs[ATT_CH * RS];
+    __shared__ __align__(16) bf16_t phi[16 * PS];
+    __shared__ __align__(16) bf16_t plo[16 * PS];
+    __shared__ float wmax[4][16], wsum[4][16];
+
+    const int c = blockIdx.x, h = blockIdx.y, kh = h / (H / KH);
+    const int L = pos0 + m;
+    const int p0 = c * ATT_CH;
+    const int np = min(ATT_CH, L - p0);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row = lane & 15, g = lane >> 4;
+    const bool rowok = row < m;
+
+    // ---- issue the V chunk loads first (consumed last), rows beyond the ragged end are zero
+    const bf16_t* vbase = vc + ((size_t)kh * max_ctx + p0) * HD;
+    constexpr int VIT = ATT_CH * VPR / 256;    // 16-byte pieces per thread
+    uint4 vreg[VIT];
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) {
+        const int idx = tid + it * 256;
+        const int p = idx / VPR, v = idx - p * VPR;
+        vreg[it] = (p < np) ? *reinterpret_cast<const uint4*>(vbase + (size_t)p * HD + v * 8) : make_uint4(0, 0, 0, 0);
+    }
+    // ---- q fragments (B operand): q[row][32 kc + 8 g .. +8] as hi / lo bf16
+    uint4 qh[KC], ql[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+        qh[k] = make_uint4(0, 0, 0, 0);
+        ql[k] = make_uint4(0, 0, 0, 0);
+        if (rowok) {
+            const float* src = q + (size_t)row * H * HD + (size_t)h * HD + k * 32 + g * 8;
+            const float4 a = *reinterpret_cast<const float4*>(src), b = *reinterpret_cast<const float4*>(src + 4);
+            const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+            bf16_t hi[8], lo[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                hi[e] = f2bf(v[e]);
+                lo[e] = f2bf(v[e] - bf2f(hi[e]));
+            }
+            qh[k] = make_uint4(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]), pack_bf16x2(hi[4], hi[5]), pack_bf16x2(hi[6], hi[7]));
+            ql[k] = make_uint4(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(lo[4], lo[5]), pack_bf16x2(lo[6], lo[7]));
+        }
+    }
+    // ---- scores of this wavefront's 32 positions: two 16-position tiles
+    const bf16_t* kbase = kc + (size_t)kh * max_ctx * HD;
+    f32x4 sacc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int pl = wave * 32 + t * 16 + row;                       // this lane's K row within the chunk
+        const int pg = min(p0 + pl, L - 1);                            // clamp: stays inside the valid cache
+        const u32x4* kp = reinterpret_cast<const u32x4*>(kbase + (size_t)pg * HD + g * 8);
+        u32x4 kf[KC];
+#pragma unroll
+        for (int k = 0; k < KC; ++k) kf[k] = kp[k * 4];                // +32 elements = 4 x 16 bytes
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acl = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[k]), __builtin_bit_cast(bf16x8, qh[k]), acc, 0, 0, 0);
+            acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[k]), __builtin_bit_cast(bf16x8, ql[k]), acl, 0, 0, 0);
+        }
+        sacc[t] = acc + acl;
+    }
+    // lane (g, row) holds positions wave*32 + t*16 + 4g + v of query row `row`
+    float sv[8];
+    float lmax = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int pl = wave * 32 + t * 16 + g * 4 + v;
+            const bool ok = rowok && pl < np && (p0 + pl) <= pos0 + row;
+            const float x = ok ? sacc[t][v] * scale : -INFINITY;
+            sv[t * 4 + v] = x;
+            lmax = fmaxf(lmax, x);
+        }
+    lmax = fmaxf(lmax, __shfl_xor(lmax, 16, 64));
+    lmax = fmaxf(lmax, __shfl_xor(lmax, 32, 64));
+    if (g == 0) wmax[wave][row] = lmax;
+    // ---- stage V into LDS while the maxima settle
+#pragma unroll
+    for (int it = 0; it < VIT; ++it) {
+        const int idx = tid + it * 256;
+        const int p = idx / VPR, v = idx - p * VPR;
+        *reinterpret_cast<uint4*>(vs + p * RS + v * 8) = vreg[it];
+    }
+    __syncthreads();
+    const float mx = fmaxf(fmaxf(wmax[0][row], wmax[1][row]), fmaxf(wmax[2][row], wmax[3][row]));
+    float lsum = 0.f;
+    bf16_t ph[8], pl8[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float e = (mx == -INFINITY) ? 0.f : expf(sv[i] - mx);   // expf(-inf) = 0 for masked positions
+        lsum += e;
+        ph[i] = f2bf(e);
+        pl8[i] = f2bf(e - bf2f(ph[i]));
+    }
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    if (g == 0) wsum[wave][row] = lsum;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int pl = wave * 32 + t * 16 + g * 4;
+        *reinterpret_cast<uint2*>(phi + row * PS + pl) = make_uint2(pack_bf16x2(ph[t * 4], ph[t * 4 + 1]), pack_bf16x2(ph[t * 4 + 2], ph[t * 4 + 3]));
+        *reinterpret_cast<uint2*>(plo + row * PS + pl) = make_uint2(pack_bf16x2(pl8[t * 4], pl8[t * 4 + 1]), pack_bf16x2(pl8[t * 4 + 2], pl8[t * 4 + 3]));
+    }
+    __syncthreads();
+    // ---- O^T tiles: wavefront w takes head-dim tiles w, w+4, ..
+    float* dst = part + ((size_t)h * nchunks + c) * 16 * (HD + 2);
+#pragma unroll
+    for (int nt = wave; nt < NT; nt += 4) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acl = {0.f, 0.f, 0.f, 0.f};
+        const int col = nt * 16 + row;                                  // A operand row index i = lane % 16 -> head-dim column
+#pragma unroll
+        for (int k = 0; k < ATT_CH / 32; ++k) {
+            const bf16_t* vp = vs + (k * 32 + g * 8) * RS + col;
+            const uint4 a = make_uint4(pack_bf16x2(vp[0], vp[RS]), pack_bf16x2(vp[2 * RS], vp[3 * RS]),
+                                       pack_bf16x2(vp[4 * RS], vp[5 * RS]), pack_bf16x2(vp[6 * RS], vp[7 * RS]));
+            const uint4 bh = *reinterpret_cast<const uint4*>(phi + row * PS + k * 32 + g * 8);
+            const uint4 bl = *reinterpret_cast<const uint4*>(plo + row * PS + k * 32 + g * 8);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, bh), acc, 0, 0, 0);
+            acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, bl), acl, 0, 0, 0);
+        }
+        if (rowok) {
+            float* o = dst + row * (HD + 2) + nt * 16 + g * 4;           // D[i = 4g + v][j = row]
+            o[0] = acc[0] + acl[0]; o[1] = acc[1] + acl[1]; o[2] = acc[2] + acl[2]; o[3] = acc[3] + acl[3];
+        }
+    }
+    if (tid < m) {
+        dst[tid * (HD + 2) + HD] = fmaxf(fmaxf(wmax[0][tid], wmax[1][tid]), fmaxf(wmax[2][tid], wmax[3][tid]));
+        dst[tid * (HD + 2) + HD + 1] = (wsum[0][tid] + wsum[1][tid]) + (wsum[2][tid] + wsum[3][tid]);
+    }
+}
+
 template <typename T, int HD>
 __global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks, int H, float* __restrict__ out) {
     const int h = blockIdx.x, r = blockIdx.y, col = threadIdx.x;
@@ -460,12 +625,14 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks,
     float M = -INFINITY;
     for (int c = 0; c < nchunks; ++c) M = fmaxf(M, base[c * cs + HD]);
     float Lsum = 0.f, o = 0.f;
+#pragma unroll 4
     for (int c = 0; c < nchunks; ++c) {
         const float mc = base[c * cs + HD];
-        if (mc == -INFINITY) continue;
-        const float w = expf(mc - M);
-        Lsum += base[c * cs + HD + 1] * w;
-        o += base[c * cs + col] * w;
+        const float lc = base[c * cs + HD + 1];
+        const float oc = base[c * cs + col];
+        const float w = (mc == -INFINITY) ? 0.f : expf(mc - M);
+        Lsum += lc * w;
+        o += oc * w;
     }
     out[(size_t)r * H * HD + (size_t)h * HD + col] = o / Lsum;
 }

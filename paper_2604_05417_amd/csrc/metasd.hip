@@ -280,8 +280,15 @@ int attention_hd(metasd_ctx* c, const Model& M, int L, int pos0, int m) {
     // algorithmic bytes: K and V of every cached position once per KV head, q in, partials out
     const bool timed = c->prof_begin(METASD_PROF_ATTN, 2.0 * d.n_kv_heads * (double)(pos0 + m) * HD * sizeof(T) +
                                                           (double)m * d.n_heads * HD * 4);
-    hipLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(nchunks, d.n_heads), dim3(256), 0, c->stream, (const float*)c->d_q(), kc,
-                       vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale, c->d_apart(), nchunks);
+    if constexpr (sizeof(T) == 2 && HD >= 64) {
+        hipLaunchKernelGGL((attn_partial_mfma_kernel<HD>), dim3(nchunks, d.n_heads), dim3(256), 0, c->stream,
+                           (const float*)c->d_q(), kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale, c->d_apart(),
+                           nchunks);
+    } else {
+        hipLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(nchunks, d.n_heads), dim3(256), 0, c->stream,
+                           (const float*)c->d_q(), kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale, c->d_apart(),
+                           nchunks);
+    }
     if (timed) c->prof_end();
     LAUNCH_CHECK(c, "attn_partial");
     hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3(d.n_heads, m), dim3(HD), 0, c->stream, c->d_apart(), nchunks,
@@ -318,7 +325,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
     LAUNCH_CHECK(c, "embed");
     for (int L = 0; L < d.n_layers; ++L) {
         // h += previous FFN output (split partials); xn = norm(h)
-        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(256), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.layer_w(L, 0),
+        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.layer_w(L, 0),
                            d.rms_eps, xn);
         LAUNCH_CHECK(c, "addnorm");
         if ((rc = gemm<T>(c, xn, D, m, D, M.layer_w(L, 1), DQ, M.layer_w(L, 2), DKV, M.layer_w(L, 3), DKV, nullptr, &ns))) return rc;
@@ -330,7 +337,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         LAUNCH_CHECK(c, "rope_kv");
         if ((rc = attention<T>(c, M, L, pos0, m))) return rc;
         if ((rc = gemm<T>(c, c->d_ao(), DQ, m, DQ, M.layer_w(L, 4), D, nullptr, 0, nullptr, 0, nullptr, &ns))) return rc;
-        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(256), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.layer_w(L, 5),
+        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.layer_w(L, 5),
                            d.rms_eps, xn);
         LAUNCH_CHECK(c, "addnorm");
         if (d.act == METASD_SWIGLU) {
@@ -346,7 +353,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         if ((rc = gemm<T>(c, c->d_act(), F, m, F, M.layer_w(L, 8), D, nullptr, 0, nullptr, 0, nullptr, &ns))) return rc;
     }
     if (logits) {
-        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(256), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.final_norm(),
+        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.final_norm(),
                            d.rms_eps, xn);
         LAUNCH_CHECK(c, "addnorm");
         int dummy;
