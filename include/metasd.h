@@ -27,7 +27,7 @@
  *   dtype METASD_F32: every tensor is float, matrices row-major [out][in].
  *   dtype METASD_BF16: every tensor is bf16; embed and the norm gains are plain row-major, every
  *     matrix (wq .. w_down, lm_head) must be in the library's streaming-tile order produced by
- *     metasd_pack_weight (same byte size as the row-major matrix).
+ *     metasd_pack_weight (same byte size as the row-major matrix; wq and wk with rope_head_dim = hd).
  *
  * KV cache of a model (device, caller-owned): element type = model dtype, layout
  *     [layer][2 (K, V)][kv_head][max_ctx][hd],  bytes = metasd_kv_bytes().
@@ -91,8 +91,12 @@ int32_t metasd_workspace_bytes(const metasd_config* cfg, const metasd_model_desc
  * n_out*n_in*2 bytes, must not alias src): 1 KiB tiles of 16 output rows x 32 inputs, tile
  * (t, c) at ((t * n_in/32) + c) KiB, lane l of a wavefront owning bytes [16 l, 16 l + 16) =
  * W[16 t + l%16][32 c + 8 (l/16) .. +8].  Requires n_out % 16 == 0 and n_in % 32 == 0.
+ * rope_head_dim: 0 for every matrix except the q and k projections, which pass the head
+ * dimension hd: inside each head the rows are then re-ordered so that the two members (i, i + hd/2)
+ * of a rotary pair sit next to each other (packed row 16 j + c of a head <- source row 8 j + c/2,
+ * plus hd/2 when c is odd); the library undoes this when it writes q and the K cache.
  * Asynchronous on `hip_stream`. */
-int32_t metasd_pack_weight(void* dst, const void* src, int32_t n_out, int32_t n_in, void* hip_stream);
+int32_t metasd_pack_weight(void* dst, const void* src, int32_t n_out, int32_t n_in, int32_t rope_head_dim, void* hip_stream);
 
 /* ---- context ------------------------------------------------------------------------------ */
 
@@ -182,7 +186,9 @@ int32_t metasd_philox_words(uint64_t seed, uint32_t c0_start, int32_t n, uint32_
 #define METASD_PROF_GEMM 0   /* bf16 weight-streaming GEMM launches */
 #define METASD_PROF_ATTN 1   /* KV-cache attention (partial) launches */
 #define METASD_PROF_ACCEPT 2 /* accept step launches of metasd_accept */
-/* max_records > 0: from now on bracket every launch of the three bandwidth-bound kernels with a
+#define METASD_PROF_FORWARD 3 /* one-launch block forwards of a bf16 target (all layers, optional LM head) */
+#define METASD_PROF_DRAFT_FORWARD 4 /* the same for bf16 drafters */
+/* max_records > 0: from now on bracket every launch of the bandwidth-bound kernels with a
  * pair of HIP events on the context's stream (at most max_records launches are recorded; the
  * pool is created here, not in the hot path) and reset the record count; 0: stop recording. */
 int32_t metasd_profile(metasd_ctx*, int32_t max_records);

@@ -54,7 +54,7 @@ def load_library():
     sig = {
         "metasd_kv_bytes": [C.POINTER(_Desc), i32, C.POINTER(sz)],
         "metasd_workspace_bytes": [C.POINTER(_Config), C.POINTER(_Desc), C.POINTER(_Desc), C.POINTER(sz)],
-        "metasd_pack_weight": [vp, vp, i32, i32, vp],
+        "metasd_pack_weight": [vp, vp, i32, i32, i32, vp],
         "metasd_create": [C.POINTER(vp), C.POINTER(_Config), C.POINTER(_Desc), C.POINTER(_Desc), C.POINTER(vp),
                           C.POINTER(C.POINTER(vp)), vp, C.POINTER(vp), vp, sz, vp],
         "metasd_destroy": [vp],
@@ -104,12 +104,14 @@ def _desc(d: dict) -> _Desc:
                  d.get("rms_eps", 1e-5), d.get("rope_theta", 10000.0))
 
 
-def pack_weight(w: torch.Tensor, stream=None) -> torch.Tensor:
-    """Row-major bf16 matrix [n_out, n_in] on the GPU -> streaming-tile order (same shape container)."""
+def pack_weight(w: torch.Tensor, rope_head_dim: int = 0, stream=None) -> torch.Tensor:
+    """Row-major bf16 matrix [n_out, n_in] on the GPU -> streaming-tile order (same shape container).
+    rope_head_dim: the head dimension for the q and k projections, 0 for every other matrix."""
     _require_gpu()
     assert w.is_cuda and w.dtype == torch.bfloat16 and w.dim() == 2 and w.is_contiguous()
     out = torch.empty_like(w)
-    _check(load_library().metasd_pack_weight(out.data_ptr(), w.data_ptr(), w.shape[0], w.shape[1], _stream_ptr(stream)))
+    _check(load_library().metasd_pack_weight(out.data_ptr(), w.data_ptr(), w.shape[0], w.shape[1], rope_head_dim,
+                                             _stream_ptr(stream)))
     return out
 
 
@@ -162,10 +164,12 @@ class MetaSD:
         nl = desc["n_layers"]
         is_matrix = (index == 2 + PER_LAYER * nl) or (1 <= index <= PER_LAYER * nl and (index - 1) % PER_LAYER in MATRIX_SLOTS)
         pack = desc["dtype"] == 1 and is_matrix
-        key = (w.data_ptr(), tuple(w.shape), pack)
+        is_qk = 1 <= index <= PER_LAYER * nl and (index - 1) % PER_LAYER in (1, 2)
+        rope_hd = desc["d_model"] // desc["n_heads"] if (pack and is_qk) else 0
+        key = (w.data_ptr(), tuple(w.shape), pack, rope_hd)
         if key not in self._packed:
             dev = w.to(self.device).contiguous()
-            self._packed[key] = (pack_weight(dev) if pack else dev, w)   # keep the source alive: the key stays unique
+            self._packed[key] = (pack_weight(dev, rope_hd) if pack else dev, w)   # keep the source alive: the key stays unique
         return self._packed[key][0]
 
     def _table(self, desc, weights):
@@ -256,7 +260,7 @@ class MetaSD:
 
     def profile_read(self, kind: str) -> dict:
         ms, n, by = C.c_double(0), C.c_int64(0), C.c_double(0)
-        _check(self.L.metasd_profile_read(self._h, {"gemm": 0, "attn": 1, "accept": 2}[kind], C.byref(ms), C.byref(n), C.byref(by)), self._h)
+        _check(self.L.metasd_profile_read(self._h, {"gemm": 0, "attn": 1, "accept": 2, "forward": 3, "draft_forward": 4}[kind], C.byref(ms), C.byref(n), C.byref(by)), self._h)
         return dict(ms=ms.value, launches=n.value, bytes=by.value)
 
     def state(self, model: int = -1):

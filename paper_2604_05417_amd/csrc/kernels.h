@@ -288,7 +288,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict_
 }
 
 // Row-major bf16 W[n_out][n_in] -> streaming-tile order.  One thread per 16-byte piece.
-__global__ void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int n_out, int n_in) {
+// rope_hd > 0 (q and k projections): inside every head of rope_hd output features the rows are
+// re-ordered so that tile j holds the rotary pairs (i, i + rope_hd/2), i = 8j .. 8j+7, side by side:
+// packed row 16j + c  <-  source row (c even ? 8j + c/2 : 8j + c/2 + rope_hd/2).  The GEMM epilogue
+// then finds both members of a pair in one lane and writes them back to their natural positions.
+__global__ void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int n_out, int n_in, int rope_hd) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // index of a 16-byte piece in dst
     const size_t total = (size_t)n_out * n_in / 8;
     if (i >= total) return;
@@ -297,7 +301,12 @@ __global__ void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restr
     const size_t tile = i >> 6;
     const int c = (int)(tile % kchunks);
     const size_t t = tile / kchunks;
-    const size_t rowi = t * 16 + (lane & 15);
+    size_t rowi = t * 16 + (lane & 15);
+    if (rope_hd > 0) {
+        const size_t head = rowi / rope_hd;
+        const int rr = (int)(rowi - head * rope_hd), j = rr >> 4, cc = rr & 15;
+        rowi = head * rope_hd + (size_t)(8 * j + (cc >> 1) + ((cc & 1) ? (rope_hd >> 1) : 0));
+    }
     const size_t col = (size_t)c * 32 + (size_t)(lane >> 4) * 8;
     dst[i] = src[(rowi * n_in + col) / 8];
 }
@@ -309,14 +318,18 @@ __global__ void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restr
 
 template <typename T>
 __global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int N, int pos0, int H, int KH,
-                               int hd, float theta, float* __restrict__ q, T* __restrict__ kc, T* __restrict__ vc, int max_ctx) {
+                               int hd, float theta, float* __restrict__ q, T* __restrict__ kc, T* __restrict__ vc, int max_ctx,
+                               int interleaved) {
     const int head = blockIdx.x, r = blockIdx.y, i = threadIdx.x, half = hd >> 1;
     if (i >= half) return;
-    const size_t col = (size_t)r * N + (size_t)head * hd + i;
+    // interleaved (rope-ordered packed weights): q / k columns hold the pair (i, i + half) at 16(i/8) + 2(i%8), +1
+    const bool il = interleaved && head < H + KH;
+    const size_t base = (size_t)r * N + (size_t)head * hd;
+    const size_t ca = base + (il ? 16 * (i >> 3) + 2 * (i & 7) : i), cb = il ? ca + 1 : ca + half;
     float a = 0.f, b = 0.f;
     for (int s = 0; s < nsplit; ++s) {
-        a += part[(size_t)s * sstride + col];
-        b += part[(size_t)s * sstride + col + half];
+        a += part[(size_t)s * sstride + ca];
+        b += part[(size_t)s * sstride + cb];
     }
     const int pos = pos0 + r;
     if (head < H + KH) {

@@ -8,12 +8,14 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
 #include <vector>
 
 #include "kernels.h"
+#include "persist.h"
 
 using namespace msd;
 
@@ -45,6 +47,7 @@ struct Model {
     void* kv = nullptr;
     int hd = 0;
     int kv_len = 0;  // positions valid in the KV cache
+    const void** d_table = nullptr;   // device copy of w (persistent kernel)
     const void* layer_w(int L, int i) const { return w[1 + PER_LAYER * L + i]; }
     const void* final_norm() const { return w[1 + PER_LAYER * d.n_layers]; }
     const void* lm_head() const { return w[2 + PER_LAYER * d.n_layers]; }
@@ -93,7 +96,7 @@ const char* check_model(const metasd_model_desc& d, const char* who, char* buf, 
 
 // Workspace layout shared by metasd_workspace_bytes and metasd_create.
 struct Layout {
-    size_t hist, h, xn, part, q, ao, act, apart, P, Q, cand, bd, res, draft, total;
+    size_t hist, h, xn, part, q, ao, act, apart, P, Q, cand, bd, res, draft, bar, tables, table_stride, total;
 };
 
 Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const metasd_model_desc* dr) {
@@ -125,7 +128,7 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     L.part = take(partmax);
     L.q = take((size_t)MAX_ROWS * dmax * 4);
     L.ao = take((size_t)MAX_ROWS * dmax * 4);
-    L.act = take((size_t)MAX_ROWS * fmax * 4);
+    L.act = take((size_t)MAX_ROWS * fmax * 4 * 2);          // also the fused gate | up result
     L.apart = take((size_t)hmax * nchunks * 16 * (hdmax + 2) * 4);
     L.P = take((size_t)(c.gamma_max + 1) * vmax * 4);
     L.Q = take((size_t)c.gamma_max * vmax * 4);
@@ -133,6 +136,11 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     L.bd = take((size_t)c.gamma_max * sizeof(double));
     L.res = take(64);
     L.draft = take(64);
+    L.bar = take(sizeof(GridBar));
+    int lmax = t.n_layers;
+    for (int k = 0; k < c.K; ++k) lmax = std::max(lmax, dr[k].n_layers);
+    L.table_stride = align_up((size_t)(1 + PER_LAYER * lmax + 2) * sizeof(void*));
+    L.tables = take(L.table_stride * (size_t)(c.K + 1));
     L.total = o;
     return L;
 }
@@ -151,6 +159,7 @@ struct HostResult {   // pinned host mirror of one accept
     int32_t pad;
     int32_t d[16];
     double bd[16];
+    GridBar bar;
 };
 
 enum Phase { PH_NONE = 0, PH_READY, PH_DRAFTED, PH_VERIFIED };
@@ -175,6 +184,8 @@ struct metasd_ctx {
     // optional per-launch timing of the three bandwidth-bound kernels (metasd_profile)
     struct ProfRec { hipEvent_t a, b; int kind; double bytes; };
     bool prof_on = false;
+    bool persistent = false;         // bf16 models run the one-launch forward (cooperative launch available)
+    int n_cu = 0;
     std::vector<ProfRec> prof;       // event pool
     size_t prof_used = 0;
     bool prof_begin(int kind, double bytes) {
@@ -199,6 +210,7 @@ struct metasd_ctx {
     double* d_bd() const { return reinterpret_cast<double*>(ws + lay.bd); }
     int32_t* d_res() const { return reinterpret_cast<int32_t*>(ws + lay.res); }
     int32_t* d_draft() const { return reinterpret_cast<int32_t*>(ws + lay.draft); }
+    GridBar* d_bar() const { return reinterpret_cast<GridBar*>(ws + lay.bar); }
 
     int fail(int code, const char* fmt, ...) {
         char buf[512];
@@ -333,7 +345,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
         hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, part, ns, (size_t)m * NQKV, NQKV, pos0, H, KH,
-                           hd, d.rope_theta, (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx);
+                           hd, d.rope_theta, (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, sizeof(T) == 2 ? 1 : 0);
         LAUNCH_CHECK(c, "rope_kv");
         if ((rc = attention<T>(c, M, L, pos0, m))) return rc;
         if ((rc = gemm<T>(c, c->d_ao(), DQ, m, DQ, M.layer_w(L, 4), D, nullptr, 0, nullptr, 0, nullptr, &ns))) return rc;
@@ -363,6 +375,54 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
     return 0;
 }
 
+// ---- bf16 models: the whole block forward in one cooperative launch (see persist.h)
+
+int upload_table(metasd_ctx* c, Model& M) {
+    HIP_TRY(c, hipMemcpyAsync((void*)M.d_table, M.w.data(), M.w.size() * sizeof(void*), hipMemcpyHostToDevice, c->stream));
+    return 0;
+}
+
+template <int HD>
+int launch_persistent(metasd_ctx* c, FwdP& P) {
+    void* args[] = {(void*)&P};
+    hipError_t e = hipLaunchCooperativeKernel((const void*)forward_persistent_kernel<HD>, dim3(c->n_cu), dim3(PK_NT), args,
+                                              (unsigned)PK_LDS_BYTES, c->stream);
+    if (e != hipSuccess) return c->fail(METASD_E_HIP, "cooperative launch of the persistent forward: %s", hipGetErrorString(e));
+    return 0;
+}
+
+int forward_persistent(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int first_row) {
+    const metasd_model_desc& d = M.d;
+    FwdP P{};
+    P.n_layers = d.n_layers; P.D = d.d_model; P.H = d.n_heads; P.KH = d.n_kv_heads; P.hd = M.hd; P.F = d.d_ffn; P.V = d.vocab;
+    P.act = d.act; P.eps = d.rms_eps; P.theta = d.rope_theta;
+    P.w = (const void* const*)M.d_table;
+    P.kv = (bf16_t*)M.kv; P.max_ctx = c->cfg.max_ctx;
+    P.tok = c->d_hist() + pos0; P.m = m; P.pos0 = pos0;
+    P.h = c->d_h(); P.q = (float*)c->d_q(); P.ao = (float*)c->d_ao(); P.gu = (float*)c->d_act(); P.apart = c->d_apart();
+    P.logits = logits; P.first_row = first_row;
+    P.bar = c->d_bar(); P.spin_limit = 4000000;
+    if ((pos0 + m + ATT_CH - 1) / ATT_CH * (size_t)d.n_heads * 16 * (M.hd + 2) * 4 > c->lay.P - c->lay.apart)
+        return c->fail(METASD_E_INVALID, "attention partial buffer too small");
+    // algorithmic bytes of the launch: every weight once, the KV cache of [0, pos0 + m) once, the embedding rows
+    double bytes = 0.0;
+    {
+        const double D = d.d_model, F = d.d_ffn, DQ = (double)d.n_heads * M.hd, DKV = (double)d.n_kv_heads * M.hd;
+        const double per_layer = (D * (DQ + 2 * DKV) + DQ * D + (d.act == METASD_SWIGLU ? 3.0 : 2.0) * D * F + 2 * D) * 2;
+        bytes = d.n_layers * (per_layer + 2.0 * DKV * (pos0 + m) * 2) + (logits ? (double)d.vocab * D * 2 + (double)(m - first_row) * d.vocab * 4 : 0.0) +
+                (double)m * D * 2;
+    }
+    const bool timed = c->prof_begin(&M == &c->target ? METASD_PROF_FORWARD : METASD_PROF_DRAFT_FORWARD, bytes);
+    int rc;
+    switch (M.hd) {
+        case 32: rc = launch_persistent<32>(c, P); break;
+        case 64: rc = launch_persistent<64>(c, P); break;
+        default: rc = launch_persistent<128>(c, P); break;
+    }
+    if (timed) c->prof_end();
+    return rc;
+}
+
 // Forward over tokens hist[pos0 .. pos0+n) in blocks of <= 16 rows (later blocks see the KV of
 // earlier ones).  logits (optional): want_all ? all n rows (n <= 16) : the last row only.
 int forward(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool want_all) {
@@ -373,8 +433,10 @@ int forward(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool want_a
         const bool last = done + m == n;
         float* lg = (last && logits) ? logits : nullptr;
         const int first_row = want_all ? 0 : m - 1;
-        int rc = M.d.dtype == METASD_BF16 ? forward_rows<bf16_t>(c, M, pos0 + done, m, lg, first_row)
-                                          : forward_rows<float>(c, M, pos0 + done, m, lg, first_row);
+        int rc;
+        if (M.d.dtype != METASD_BF16) rc = forward_rows<float>(c, M, pos0 + done, m, lg, first_row);
+        else if (c->persistent) rc = forward_persistent(c, M, pos0 + done, m, lg, first_row);
+        else rc = forward_rows<bf16_t>(c, M, pos0 + done, m, lg, first_row);
         if (rc) return rc;
         done += m;
     }
@@ -446,12 +508,14 @@ int32_t metasd_workspace_bytes(const metasd_config* cfg, const metasd_model_desc
     return METASD_OK;
 }
 
-int32_t metasd_pack_weight(void* dst, const void* src, int32_t n_out, int32_t n_in, void* hip_stream) {
+int32_t metasd_pack_weight(void* dst, const void* src, int32_t n_out, int32_t n_in, int32_t rope_head_dim, void* hip_stream) {
     if (!dst || !src || dst == src) return fail_global(METASD_E_INVALID, "metasd_pack_weight: NULL or aliased pointers");
     if (n_out < 16 || n_in < 32 || n_out % 16 || n_in % 32) return fail_global(METASD_E_INVALID, "metasd_pack_weight: n_out %% 16 and n_in %% 32 must be 0");
+    if (rope_head_dim != 0 && (rope_head_dim < 32 || rope_head_dim % 32 || n_out % rope_head_dim))
+        return fail_global(METASD_E_INVALID, "metasd_pack_weight: rope_head_dim must be 0 or a multiple of 32 dividing n_out");
     const size_t total = (size_t)n_out * n_in / 8;
     hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)hip_stream,
-                       (const uint4*)src, (uint4*)dst, n_out, n_in);
+                       (const uint4*)src, (uint4*)dst, n_out, n_in, rope_head_dim);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_global(METASD_E_HIP, "pack_weight: %s", hipGetErrorString(e));
     return METASD_OK;
@@ -510,6 +574,34 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         delete c;
         return rc;
     }
+    // persistent forward: needs cooperative launch, > 64 KiB of dynamic LDS and a device table per model
+    {
+        int dev = 0, coop = 0, ncu = 0;
+        bool ok = hipGetDevice(&dev) == hipSuccess &&
+                  hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) == hipSuccess && coop &&
+                  hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && ncu > 0;
+        ok = ok && hipFuncSetAttribute((const void*)forward_persistent_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize, PK_LDS_BYTES) == hipSuccess;
+        ok = ok && hipFuncSetAttribute((const void*)forward_persistent_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, PK_LDS_BYTES) == hipSuccess;
+        ok = ok && hipFuncSetAttribute((const void*)forward_persistent_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, PK_LDS_BYTES) == hipSuccess;
+        (void)hipGetLastError();
+        if (const char* ev = getenv("METASD_STEPWISE")) ok = ok && ev[0] != '1';
+        c->persistent = ok;
+        c->n_cu = ncu;
+        if (const char* ev = getenv("METASD_NB")) { int v = atoi(ev); if (v >= 1 && v <= ncu) c->n_cu = v; }   // fewer workgroups (debugging)
+    }
+    c->target.d_table = (const void**)(c->ws + lay.tables);
+    for (int k = 0; k < cfg->K; ++k) c->drafters[k].d_table = (const void**)(c->ws + lay.tables + lay.table_stride * (size_t)(k + 1));
+    e = hipMemsetAsync(c->d_bar(), 0, sizeof(GridBar), c->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync((void*)c->target.d_table, c->target.w.data(), c->target.w.size() * sizeof(void*), hipMemcpyHostToDevice, c->stream);
+    for (int k = 0; k < cfg->K && e == hipSuccess; ++k)
+        e = hipMemcpyAsync((void*)c->drafters[k].d_table, c->drafters[k].w.data(), c->drafters[k].w.size() * sizeof(void*), hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) {
+        rc = fail_global(METASD_E_HIP, "context set-up: %s", hipGetErrorString(e));
+        (void)hipHostFree(c->hres);
+        delete c;
+        return rc;
+    }
     *out = c;
     return METASD_OK;
 }
@@ -554,6 +646,9 @@ int32_t metasd_swap_weight(metasd_ctx* c, int32_t model, int32_t index, const vo
     Model& M = model < 0 ? c->target : c->drafters[model];
     if (index < 0 || index >= (int)M.w.size() || !dev_ptr || (uintptr_t)dev_ptr % 16) return c->fail(METASD_E_INVALID, "swap_weight: bad index or pointer");
     M.w[index] = dev_ptr;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));        // no launch in flight reads the old table
+    if (int rc = upload_table(c, M)) return rc;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
     return METASD_OK;
 }
 
@@ -648,7 +743,13 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
     HIP_TRY(c, hipMemcpyAsync(&hr->n_acc, res, 12, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipMemcpyAsync(hr->d, c->d_draft(), (size_t)gamma * 4, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipMemcpyAsync(hr->bd, c->d_bd(), (size_t)gamma * 8, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(&hr->bar, c->d_bar(), sizeof(GridBar), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (hr->bar.abort) {
+        (void)hipMemsetAsync(c->d_bar(), 0, sizeof(GridBar), c->stream);
+        c->phase = PH_NONE;
+        return c->fail(METASD_E_HIP, "persistent forward: a device-wide barrier timed out; call metasd_set_context to start over");
+    }
     const int n = hr->n_acc;
     if (n < 0 || n > gamma || hr->token < 0 || hr->token >= V) return c->fail(METASD_E_HIP, "accept: device returned n_acc %d token %d", n, hr->token);
     for (int j = 0; j < n; ++j) c->hist[l + j] = hr->d[j];
@@ -723,7 +824,7 @@ int32_t metasd_profile(metasd_ctx* c, int32_t max_records) {
 
 int32_t metasd_profile_read(metasd_ctx* c, int32_t kind, double* ms_total, int64_t* launches, double* bytes_total) {
     if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
-    if (kind < 0 || kind > 2) return c->fail(METASD_E_INVALID, "profile_read: unknown kind %d", kind);
+    if (kind < 0 || kind > 4) return c->fail(METASD_E_INVALID, "profile_read: unknown kind %d", kind);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     double ms = 0.0, by = 0.0;
     int64_t n = 0;

@@ -56,7 +56,7 @@ def test_sizes_and_validation(lib):
     assert lib.metasd_workspace_bytes(C.byref(cfg), C.byref(desc()), dr2, C.byref(n)) == -1
     h = C.c_void_p()
     assert lib.metasd_create(C.byref(h), C.byref(cfg), C.byref(desc()), dr, None, None, None, None, None, 0, None) == -1
-    assert lib.metasd_pack_weight(None, None, 16, 32, None) == -1
+    assert lib.metasd_pack_weight(None, None, 16, 32, 0, None) == -1
     assert lib.metasd_accept_logits(None, None, None, 1, 1, 8, 1.0, 0, 0, 0, None, None, None, None, None, None) == -1
     assert lib.metasd_sample_logits(None, 1, 8, 1.0, 0, 0, 0, 0, None, None) == -1
     assert lib.metasd_destroy(None) == 0
