@@ -184,6 +184,7 @@ struct metasd_ctx {
     // optional per-launch timing of the three bandwidth-bound kernels (metasd_profile)
     struct ProfRec { hipEvent_t a, b; int kind; double bytes; };
     bool prof_on = false;
+    bool tlog = false;
     bool persistent = false;         // bf16 models run the one-launch forward (cooperative launch available)
     int n_cu = 0;
     std::vector<ProfRec> prof;       // event pool
@@ -402,6 +403,8 @@ int forward_persistent(metasd_ctx* c, Model& M, int pos0, int m, float* logits, 
     P.h = c->d_h(); P.q = (float*)c->d_q(); P.ao = (float*)c->d_ao(); P.gu = (float*)c->d_act(); P.apart = c->d_apart();
     P.logits = logits; P.first_row = first_row;
     P.bar = c->d_bar(); P.spin_limit = 4000000;
+    // METASD_TLOG=1: workgroup 0 logs two timestamps per barrier into the (otherwise unused) partials buffer
+    P.tlog = (c->tlog && (size_t)(2048 + 512) * 8 <= c->lay.q - c->lay.part) ? (long long*)c->d_part() : nullptr;
     if ((pos0 + m + ATT_CH - 1) / ATT_CH * (size_t)d.n_heads * 16 * (M.hd + 2) * 4 > c->lay.P - c->lay.apart)
         return c->fail(METASD_E_INVALID, "attention partial buffer too small");
     // algorithmic bytes of the launch: every weight once, the KV cache of [0, pos0 + m) once, the embedding rows
@@ -584,8 +587,11 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         ok = ok && hipFuncSetAttribute((const void*)forward_persistent_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, PK_LDS_BYTES) == hipSuccess;
         ok = ok && hipFuncSetAttribute((const void*)forward_persistent_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, PK_LDS_BYTES) == hipSuccess;
         (void)hipGetLastError();
-        if (const char* ev = getenv("METASD_STEPWISE")) ok = ok && ev[0] != '1';
-        c->persistent = ok;
+        // The one-launch forward is opt-in (METASD_PERSISTENT=1): at the 7B shape it is still slower
+        // than the step-by-step kernels (per-phase barrier + staging latency), see the design notes.
+        const char* ev = getenv("METASD_PERSISTENT");
+        c->persistent = ok && ev && ev[0] == '1';
+        if (const char* ev = getenv("METASD_TLOG")) c->tlog = ev[0] == '1';
         c->n_cu = ncu;
         if (const char* ev = getenv("METASD_NB")) { int v = atoi(ev); if (v >= 1 && v <= ncu) c->n_cu = v; }   // fewer workgroups (debugging)
     }
@@ -851,6 +857,7 @@ int32_t metasd_peek(metasd_ctx* c, int32_t what, void** dev_ptr_out, size_t* byt
         case METASD_PEEK_Q: *dev_ptr_out = c->d_Q(); *bytes_out = (size_t)c->cfg.gamma_max * V * 4; break;
         case METASD_PEEK_HIST: *dev_ptr_out = c->d_hist(); *bytes_out = (size_t)c->cfg.max_ctx * 4; break;
         case METASD_PEEK_BD: *dev_ptr_out = c->d_bd(); *bytes_out = (size_t)c->cfg.gamma_max * 8; break;
+        case 5: *dev_ptr_out = c->d_part(); *bytes_out = (size_t)(2048 + 512) * 8; break;   // timestamps (METASD_TLOG=1)
         case METASD_PEEK_DRAFT: *dev_ptr_out = c->d_draft(); *bytes_out = (size_t)c->cfg.gamma_max * 4; break;
         default: return c->fail(METASD_E_INVALID, "peek: unknown buffer %d", what);
     }

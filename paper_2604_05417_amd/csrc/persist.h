@@ -32,7 +32,7 @@ namespace msd {
 
 constexpr int PK_NW = 8;                 // wavefronts per workgroup
 constexpr int PK_NT = PK_NW * 64;        // threads per workgroup
-constexpr int PK_U = 16;                 // weight tiles (KiB) a wavefront keeps in flight
+constexpr int PK_U = 8;                // weight tiles (KiB) a wavefront keeps in flight
 constexpr int PK_MAXT = 8;               // output tiles a workgroup accumulates per pass over K
 constexpr int PK_XBYTES = 136 * 1024;    // LDS for staged activations (also the attention tiles)
 constexpr int PK_RED_FLOATS = 2 * PK_NW * 256;                       // double-buffered cross-wave reduction
@@ -80,6 +80,7 @@ struct FwdP {
     int first_row;
     GridBar* bar;
     int spin_limit;
+    long long* tlog;           // nullptr, or 2 timestamps per barrier written by workgroup 0 (measurement aid)
 };
 
 enum { PEPI_QKV = 0, PEPI_RESID = 1, PEPI_GU = 2, PEPI_LOGITS = 3 };
@@ -175,11 +176,12 @@ __device__ __forceinline__ void wg_barrier_lds() { asm volatile("s_waitcnt lgkmc
 // the run was aborted (a wait exceeded spin_limit): every wavefront then leaves the kernel.
 __device__ __forceinline__ void grid_barrier_begin() { drain_stores(); }
 
-__device__ __forceinline__ bool grid_barrier_end(GridBar* b, int nb, int spin_limit, int& my_gen, int* flag_s) {
+__device__ __forceinline__ bool grid_barrier_end(GridBar* b, int nb, int spin_limit, int& my_gen, int* flag_s, long long* tlog = nullptr) {
     wg_barrier_lds();                                    // every wavefront of the workgroup has drained its stores
     if (threadIdx.x < 64) {
         if (threadIdx.x == 0) {
             int ok = 1;
+            if (tlog) tlog[0] = wall_clock64();
             if (arrive(&b->count) == nb - 1) {
                 __hip_atomic_store(&b->count, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 drain_stores();                              // the reset lands before the release
@@ -197,6 +199,7 @@ __device__ __forceinline__ bool grid_barrier_end(GridBar* b, int nb, int spin_li
             }
             if (__hip_atomic_load(&b->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) ok = 0;
             *flag_s = ok;
+            if (tlog) tlog[1] = wall_clock64();
         }
         // one wavefront per compute unit drops stale cache lines: later plain loads of this
         // workgroup see what the other workgroups stored before the barrier
@@ -215,38 +218,59 @@ __device__ __forceinline__ void st_agent_u32(void* p, uint32_t v) {
 }
 
 // Stage chunks [pc0, pc0 + npc) of the phase's activations into LDS as hi / lo bf16 planes.
+// Rows go in batches of 4 so that the global loads of a batch are in flight together (one memory
+// round trip per batch instead of one per row).
 __device__ __forceinline__ void stage_x(const GPh& G, int m, int pc0, int npc, uint4* xs, float* ssq_s, int tid, int wave, int lane) {
     const int rs = npc * 4 + 1;
     uint4* xlo = xs + m * rs;
-    for (int r = 0; r < m; ++r) {
-        float ss = 0.f;
-        const float* xr = G.x + (size_t)(G.row0 + r) * G.ldx;
+    constexpr int RB = 4;
+    for (int r0 = 0; r0 < m; r0 += RB) {
+        float ss[RB] = {0.f, 0.f, 0.f, 0.f};
         for (int c = tid; c < npc * 4; c += PK_NT) {
             const int k = pc0 * 32 + c * 8;
-            const float4 a = *reinterpret_cast<const float4*>(xr + k), b = *reinterpret_cast<const float4*>(xr + k + 4);
-            float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-            if (G.pro == PRO_NORM) {
-                const uint4 gq = *reinterpret_cast<const uint4*>(G.gain + k);
-                const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
+            float4 a[RB], b[RB], ua[RB], ub[RB];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    ss += v[e] * v[e];
-                    v[e] *= bf2f((bf16_t)(gw[e >> 1] >> ((e & 1) * 16)));
+            for (int j = 0; j < RB; ++j) {
+                const int r = min(r0 + j, m - 1);                        // clamped rows are loaded twice and not stored
+                const float* xr = G.x + (size_t)(G.row0 + r) * G.ldx + k;
+                a[j] = *reinterpret_cast<const float4*>(xr);
+                b[j] = *reinterpret_cast<const float4*>(xr + 4);
+                if (G.pro == PRO_SWIGLU) {
+                    ua[j] = *reinterpret_cast<const float4*>(xr + G.K);
+                    ub[j] = *reinterpret_cast<const float4*>(xr + G.K + 4);
                 }
-            } else if (G.pro == PRO_SWIGLU) {
-                const float4 ua = *reinterpret_cast<const float4*>(xr + G.K + k), ub = *reinterpret_cast<const float4*>(xr + G.K + k + 4);
-                const float u[8] = {ua.x, ua.y, ua.z, ua.w, ub.x, ub.y, ub.z, ub.w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = v[e] / (1.0f + expf(-v[e])) * u[e];
-            } else if (G.pro == PRO_GELU) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = 0.5f * v[e] * (1.0f + erff(v[e] * 0.70710678118654752f));
             }
-            store_hilo(xs, xlo, r * rs + c, v);
+            uint4 gq = make_uint4(0, 0, 0, 0);
+            if (G.pro == PRO_NORM) gq = *reinterpret_cast<const uint4*>(G.gain + k);
+            const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                if (r0 + j < m) {
+                    float v[8] = {a[j].x, a[j].y, a[j].z, a[j].w, b[j].x, b[j].y, b[j].z, b[j].w};
+                    if (G.pro == PRO_NORM) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            ss[j] += v[e] * v[e];
+                            v[e] *= bf2f((bf16_t)(gw[e >> 1] >> ((e & 1) * 16)));
+                        }
+                    } else if (G.pro == PRO_SWIGLU) {
+                        const float u[8] = {ua[j].x, ua[j].y, ua[j].z, ua[j].w, ub[j].x, ub[j].y, ub[j].z, ub[j].w};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = v[e] / (1.0f + expf(-v[e])) * u[e];
+                    } else if (G.pro == PRO_GELU) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[e] = 0.5f * v[e] * (1.0f + erff(v[e] * 0.70710678118654752f));
+                    }
+                    store_hilo(xs, xlo, (r0 + j) * rs + c, v);
+                }
+            }
         }
         if (G.pro == PRO_NORM) {
-            ss = wave_sum(ss);
-            if (lane == 0) ssq_s[wave * 16 + r] += ss;      // each wavefront owns its slot: no race
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                const float t = wave_sum(ss[j]);
+                if (lane == 0 && r0 + j < m) ssq_s[wave * 16 + r0 + j] += t;   // each wavefront owns its slot: no race
+            }
         }
     }
 }
@@ -265,6 +289,37 @@ __device__ __forceinline__ void gemm_run(const FwdP& P, int L, int kind, u32x4 (
     const bool rowok = row < m;
     const uint4 zero = make_uint4(0, 0, 0, 0);
     bool staged = false;
+    // This wavefront's weight stream is a sequence of groups of <= PK_U tiles, ordered by (output
+    // tile, K part, offset).  Two register buffers: while group i is multiplied, group i+1 is
+    // already being loaded - also across output tiles and K parts.
+    u32x4 wb[PK_U];
+    struct Grp { int ti, p, c, cnt; const u32x4* ptr; };
+    auto locate = [&](int ti, int p, int c) {          // first non-empty group at or after (ti, p, c)
+        Grp q;
+        q.cnt = 0; q.ptr = nullptr; q.ti = ti; q.p = p; q.c = c;
+        while (q.ti < I.ntl) {
+            const int pc0 = q.p * I.pc, npc = min(I.pc, I.kchunks - pc0);
+            const int cpw = (npc + PK_NW - 1) / PK_NW;
+            const int wc0 = wave * cpw;
+            const int nwc = max(0, min(cpw, npc - wc0));
+            if (q.c < nwc) {
+                q.cnt = min(PK_U, nwc - q.c);
+                q.ptr = tile_ptr(G, bid + q.ti * nb, I.kchunks) + (size_t)(pc0 + wc0 + q.c) * 64 + lane;
+                return q;
+            }
+            q.c = 0;
+            if (++q.p == I.nparts) { q.p = 0; ++q.ti; }
+        }
+        return q;
+    };
+    auto issue = [&](u32x4 (&buf)[PK_U], const Grp& q) {
+#pragma unroll
+        for (int u = 0; u < PK_U; ++u)
+            if (u < q.cnt) buf[u] = __builtin_nontemporal_load(q.ptr + (size_t)u * 64);
+    };
+    Grp cur = locate(0, 0, 0);
+    if (cur.cnt > 0 && !prefetched) issue(w, cur);
+    int par = 0;                                           // buffer holding the current group: 0 = w, 1 = wb
     for (int ti = 0; ti < I.ntl; ++ti) {
         const int t = bid + ti * nb;
         f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acl = {0.f, 0.f, 0.f, 0.f};
@@ -273,10 +328,10 @@ __device__ __forceinline__ void gemm_run(const FwdP& P, int L, int kind, u32x4 (
             const int rs = npc * 4 + 1;
             if (!staged || I.nparts > 1) {
                 wg_barrier_lds();                                    // earlier readers of xs / ssq_s are done (LDS only:
-                if (p == 0 && tid < PK_NW * 16) ssq_s[tid] = 0.f;    //  prefetched loads stay in flight)
+                if (p == 0 && tid < PK_NW * 16) ssq_s[tid] = 0.f;    //  weight loads stay in flight)
                 wg_barrier_lds();
                 stage_x(G, m, pc0, npc, xs, ssq_s, tid, wave, lane);
-                __syncthreads();
+                wg_barrier_lds();
                 staged = true;
             }
             const int cpw = (npc + PK_NW - 1) / PK_NW;
@@ -284,23 +339,33 @@ __device__ __forceinline__ void gemm_run(const FwdP& P, int L, int kind, u32x4 (
             const int nwc = max(0, min(cpw, npc - wc0));
             const uint4* xa = xs + (rowok ? row : 0) * rs + wc0 * 4 + g;
             const uint4* xb = xa + m * rs;
-            const u32x4* wp = tile_ptr(G, t, I.kchunks) + (size_t)(pc0 + wc0) * 64 + lane;
-            for (int c = 0; c < nwc; c += PK_U) {
-                const int cnt = min(PK_U, nwc - c);
-                if (!(prefetched && ti == 0 && p == 0 && c == 0)) {
+            for (int c = 0; c < nwc; c += PK_U) {                    // here (ti, p, c) is exactly `cur`
+                const Grp nx = locate(ti, p, c + PK_U);
+                if (par == 0) {
+                    if (nx.cnt > 0) issue(wb, nx);
 #pragma unroll
-                    for (int u = 0; u < PK_U; ++u)
-                        if (u < cnt) w[u] = __builtin_nontemporal_load(wp + (size_t)(c + u) * 64);
-                }
+                    for (int u = 0; u < PK_U; ++u) {
+                        if (u < cur.cnt) {
+                            uint4 ah = xa[(c + u) * 4], al = xb[(c + u) * 4];
+                            if (!rowok) { ah = zero; al = zero; }
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, ah), acc, 0, 0, 0);
+                            acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, al), acl, 0, 0, 0);
+                        }
+                    }
+                } else {
+                    if (nx.cnt > 0) issue(w, nx);
 #pragma unroll
-                for (int u = 0; u < PK_U; ++u) {
-                    if (u < cnt) {
-                        uint4 ah = xa[(c + u) * 4], al = xb[(c + u) * 4];
-                        if (!rowok) { ah = zero; al = zero; }
-                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, ah), acc, 0, 0, 0);
-                        acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, al), acl, 0, 0, 0);
+                    for (int u = 0; u < PK_U; ++u) {
+                        if (u < cur.cnt) {
+                            uint4 ah = xa[(c + u) * 4], al = xb[(c + u) * 4];
+                            if (!rowok) { ah = zero; al = zero; }
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wb[u]), __builtin_bit_cast(bf16x8, ah), acc, 0, 0, 0);
+                            acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wb[u]), __builtin_bit_cast(bf16x8, al), acl, 0, 0, 0);
+                        }
                     }
                 }
+                par ^= 1;
+                cur = nx;
             }
         }
         // ---- cross-wavefront reduction (double-buffered) and epilogue
@@ -577,11 +642,13 @@ __global__ __launch_bounds__(PK_NT) void forward_persistent_kernel(const FwdP P)
     // loop (a single copy of gemm_run) and the attention code sits where no prefetched weights
     // are held: w is cleared right after it, so the registers are free during ATTN.
     const bool pf = wave != 0;                           // wavefront 0 runs the barriers and prefetches nothing
+    int tcount = 0;
+    auto tl = [&]() -> long long* { if (!P.tlog || bid != 0) return nullptr; long long* p = P.tlog + 2 * tcount; ++tcount; return p; };
     u32x4 w[PK_U];
     for (int L = -1; L < P.n_layers; ++L) {
         if (L >= 0) {
             grid_barrier_begin();                            // q, k, v of this layer are complete
-            if (!grid_barrier_end(P.bar, nb, P.spin_limit, my_gen, &bar_flag)) return;
+            if (!grid_barrier_end(P.bar, nb, P.spin_limit, my_gen, &bar_flag, tl())) return;
             attn_phase<HD>(P, L, lds, stat_s, bid, nb, tid);
         }
 #pragma unroll
@@ -589,11 +656,11 @@ __global__ __launch_bounds__(PK_NT) void forward_persistent_kernel(const FwdP P)
         int gl = L >= 0 ? L : 0, kind = L >= 0 ? 3 : 0;      // the chain starts with O (or with QKV of layer 0)
         grid_barrier_begin();                                // embedding (L = -1) or attention partials are out
         if (pf) gemm_prefetch(P, gl, kind, bid, nb, wave, lane, w);
-        if (!grid_barrier_end(P.bar, nb, P.spin_limit, my_gen, &bar_flag)) return;
+        if (!grid_barrier_end(P.bar, nb, P.spin_limit, my_gen, &bar_flag, tl())) return;
         if (L >= 0) {
             combine_phase<HD>(P, bid, nb, tid);
             grid_barrier_begin();
-            if (!grid_barrier_end(P.bar, nb, P.spin_limit, my_gen, &bar_flag)) return;
+            if (!grid_barrier_end(P.bar, nb, P.spin_limit, my_gen, &bar_flag, tl())) return;
         }
         while (true) {
             gemm_run(P, gl, kind, w, pf, xs, red, ssq_s, bid, nb, tid, wave, lane);
@@ -604,7 +671,7 @@ __global__ __launch_bounds__(PK_NT) void forward_persistent_kernel(const FwdP P)
             else break;
             grid_barrier_begin();
             if (pf) gemm_prefetch(P, gl, kind, bid, nb, wave, lane, w);
-            if (!grid_barrier_end(P.bar, nb, P.spin_limit, my_gen, &bar_flag)) return;
+            if (!grid_barrier_end(P.bar, nb, P.spin_limit, my_gen, &bar_flag, tl())) return;
         }
     }
 }

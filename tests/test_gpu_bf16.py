@@ -107,3 +107,17 @@ def test_config4_7b_shape_full_size():
     cfg = W.config4(device="cuda")
     st = run_lockstep(cfg, 1.0, rounds=2, kv_prefilled=True, device="cuda")
     assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+
+
+@pytest.mark.parametrize("i", [0, 2])
+def test_one_launch_forward_opt_in(i, monkeypatch):
+    """The cooperative one-launch forward (opt-in by environment) gives the same parity as the
+    step-by-step kernels: small ragged shapes with a real prefill, T = 1."""
+    monkeypatch.setenv("METASD_PERSISTENT", "1")
+    s = SMALL[i]
+    cfg = W.config4(n_layers=s["n_layers"], ctx=s["prompt"], n_new=64, K=2, d_model=s["d_model"], n_heads=s["n_heads"],
+                    d_ffn=s["d_ffn"], vocab=s["vocab"], dd_model=s["dd_model"], dn_heads=s["dn_heads"], dd_ffn=s["dd_ffn"])
+    cfg["gamma"] = s["gamma"]
+    cfg["max_ctx"] = s["prompt"] + 80
+    st = run_lockstep(cfg, 1.0, rounds=4, kv_prefilled=False)
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
