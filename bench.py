@@ -32,7 +32,7 @@ def log(*a):
 
 def read_traffic():
     """HBM bytes per GEMM launch from the committed rocprofv3 counter summary, if present."""
-    path = os.path.join(ROOT, "profiles", "verify_forward_c4_traffic.json")
+    path = os.path.join(ROOT, "profiles", "gemm_bf16_kernel_c4_traffic.json")
     try:
         with open(path) as f:
             return json.load(f).get("hbm_bytes_per_launch")
@@ -65,7 +65,7 @@ def main():
     dev = "cuda"
     t0 = time.time()
     cfg = W.config4(device=dev, n_layers=args.layers, ctx=args.ctx)
-    total_rounds = 2 * K_steps + Wm                              # timed pass + instrumented pass
+    total_rounds = 3 * K_steps + Wm                              # timed pass + phase pass + per-launch pass
     cfg["max_ctx"] = args.ctx + (gamma + 1) * total_rounds + 16
     td, tw = cfg["target"]
     g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=gamma, max_ctx=cfg["max_ctx"], temperature=cfg["T"],
@@ -82,7 +82,13 @@ def main():
 
     fill_kv(args.ctx - 1)
     g.set_context(cfg["prompt"], kv_prefilled=True)
+    # one device-to-device copy of exactly 256 MiB: the known-size kernel that the HBM counters
+    # (FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc) of this same command are scaled by
+    cal = torch.empty(2, 64 << 20, dtype=torch.float32, device=dev)
+    cal[0].fill_(1.0)
+    cal[1].copy_(cal[0])
     torch.cuda.synchronize()
+    del cal
     log(f"[bench] setup {time.time() - t0:.1f}s; weights {sum(t.numel() * 2 for t in tw if t is not None) / 1e9:.2f} GB")
 
     state = dict(seg=0, new_tokens=0)
@@ -116,9 +122,7 @@ def main():
     value = toks / dt
     ms_per_step = dt / K_steps * 1e3
 
-    # ---- instrumented pass over the same kind of steps: HIP events around every launch of the
-    # bandwidth-bound kernels (library stream) and around the three phases
-    g.profile(4096 * 4)
+    # ---- phase pass: the same kind of steps with events between the three phases (no per-launch timing)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K_steps)]
     for i in range(K_steps):
         k = g.bandit_select()
@@ -129,6 +133,12 @@ def main():
         g.bandit_update(k, n, gamma, bd)
     torch.cuda.synchronize()
     phase = [float(np.median([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(K_steps)])) for j in range(3)]
+    # ---- per-launch pass: HIP events attached to every dispatch of the bandwidth-bound kernels
+    # (begin/end of the kernel itself, on the library's stream)
+    g.profile(4096 * 4)
+    for i in range(K_steps):
+        one_round()
+    torch.cuda.synchronize()
     pg, pa, pc = g.profile_read("gemm"), g.profile_read("attn"), g.profile_read("accept")
     pf, pd = g.profile_read("forward"), g.profile_read("draft_forward")
     g.profile(0)

@@ -185,12 +185,14 @@ int32_t metasd_philox_words(uint64_t seed, uint32_t c0_start, int32_t n, uint32_
 
 #define METASD_PROF_GEMM 0   /* bf16 weight-streaming GEMM launches */
 #define METASD_PROF_ATTN 1   /* KV-cache attention (partial) launches */
-#define METASD_PROF_ACCEPT 2 /* accept step launches of metasd_accept */
-#define METASD_PROF_FORWARD 3 /* one-launch block forwards of a bf16 target (all layers, optional LM head) */
+#define METASD_PROF_ACCEPT 2 /* the per-position accept kernel of metasd_accept */
+#define METASD_PROF_FORWARD 3 /* one-launch block forwards of a bf16 target (opt-in path; all layers, optional LM head) */
 #define METASD_PROF_DRAFT_FORWARD 4 /* the same for bf16 drafters */
-/* max_records > 0: from now on bracket every launch of the bandwidth-bound kernels with a
- * pair of HIP events on the context's stream (at most max_records launches are recorded; the
- * pool is created here, not in the hot path) and reset the record count; 0: stop recording. */
+/* max_records > 0: from now on every launch of the bandwidth-bound kernels carries a pair of HIP
+ * events attached to the dispatch itself (begin and end of that kernel on the context's stream;
+ * the cooperative one-launch forward is bracketed by two recorded events instead).  At most
+ * max_records launches are recorded; the event pool is created here, not in the hot path, and
+ * the record count is reset.  0: stop recording. */
 int32_t metasd_profile(metasd_ctx*, int32_t max_records);
 /* Synchronise and sum over the recorded launches of one kind: elapsed milliseconds, number of
  * launches, algorithmic bytes (weights / KV / logits each counted once per launch, plus the

@@ -229,56 +229,104 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict_
     const int nc = min(cps, kchunks - c0);
     const int rs = cps * 4 + 1;  // LDS row stride in 16-byte units (+1 pads away bank conflicts)
     uint4* xlo = xs + m * rs;
-    for (int idx = threadIdx.x; idx < m * nc * 4; idx += 256) {
-        const int r = idx / (nc * 4), c = idx - r * (nc * 4);
-        const float* src = x + (size_t)r * ldx + (size_t)c0 * 32 + (size_t)c * 8;
-        const float4 a = *reinterpret_cast<const float4*>(src), b = *reinterpret_cast<const float4*>(src + 4);
-        const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        bf16_t hi[8], lo[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            hi[e] = f2bf(v[e]);
-            lo[e] = f2bf(v[e] - bf2f(hi[e]));
-        }
-        xs[r * rs + c] = make_uint4(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]), pack_bf16x2(hi[4], hi[5]), pack_bf16x2(hi[6], hi[7]));
-        xlo[r * rs + c] = make_uint4(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(lo[4], lo[5]), pack_bf16x2(lo[6], lo[7]));
-    }
-    __syncthreads();
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int row = lane & 15, g = lane >> 4;
-    const bool rowok = row < m;
-    const uint4* xa = xs + (rowok ? row : 0) * rs + g;
-    const uint4* xb = xlo + (rowok ? row : 0) * rs + g;
-    const uint4 zero = make_uint4(0, 0, 0, 0);
-    for (int tt = wave; tt < tpb; tt += 4) {
-        const int t = tg * tpb + tt;
-        if (t >= ntiles) break;
+    const int ngroups = (nc + GEMM_U - 1) / GEMM_U;
+    // weight tiles of chunk group gi of tile t (tiles past the slice's end read as zero)
+    auto tile_base = [&](int t) -> const u32x4* {
         const bf16_t* W;
         int tl;
         if (t < t0) { W = W0; tl = t; }
         else if (t < t1) { W = W1; tl = t - t0; }
         else { W = W2; tl = t - t1; }
-        const u32x4* wp = reinterpret_cast<const u32x4*>(W) + ((size_t)tl * kchunks + c0) * 64 + lane;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acl = {0.f, 0.f, 0.f, 0.f};
-        int c = 0;
-        for (; c + GEMM_U <= nc; c += GEMM_U) {
-            u32x4 w[GEMM_U];
+        return reinterpret_cast<const u32x4*>(W) + ((size_t)tl * kchunks + c0) * 64 + lane;
+    };
+    // every load is unconditional (chunks past the slice's end re-read its last tile and are
+    // multiplied by zero activations): a branch around a load would make the compiler drain the
+    // whole load queue before the first multiply and undo the two-buffer pipeline below
+    auto issue = [&](u32x4 (&w)[GEMM_U], const u32x4* wp, int gi) {
 #pragma unroll
-            for (int u = 0; u < GEMM_U; ++u) w[u] = __builtin_nontemporal_load(wp + (size_t)(c + u) * 64);
+        for (int u = 0; u < GEMM_U; ++u) w[u] = __builtin_nontemporal_load(wp + (size_t)min(gi * GEMM_U + u, nc - 1) * 64);
+    };
+    u32x4 wa[GEMM_U], wb[GEMM_U];
+    // the first KiBs of this wavefront's first tile are requested before the activations are staged,
+    // so the weight stream starts with the kernel and the staging latency hides behind it
+    const int tfirst = tg * tpb + wave;
+    const bool any = wave < tpb && tfirst < ntiles;
+    const u32x4* wp = any ? tile_base(tfirst) : nullptr;
+    if (any) issue(wa, wp, 0);
+    {
+        const int total = m * nc * 4, per = nc * 4;
+        for (int base = 0; base < total; base += 256 * 4) {
+            float4 a[4], b[4];
+            int dst[4];
 #pragma unroll
-            for (int u = 0; u < GEMM_U; ++u) {
-                uint4 ah = xa[(c + u) * 4], al = xb[(c + u) * 4];
-                if (!rowok) { ah = zero; al = zero; }
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, ah), acc, 0, 0, 0);
-                acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, al), acl, 0, 0, 0);
+            for (int u = 0; u < 4; ++u) {
+                const int idx = base + u * 256 + (int)threadIdx.x;
+                dst[u] = -1;
+                if (idx < total) {
+                    const int r = idx / per, c = idx - r * per;
+                    const float* src = x + (size_t)r * ldx + (size_t)c0 * 32 + (size_t)c * 8;
+                    a[u] = *reinterpret_cast<const float4*>(src);
+                    b[u] = *reinterpret_cast<const float4*>(src + 4);
+                    dst[u] = r * rs + c;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (dst[u] < 0) continue;
+                const float v[8] = {a[u].x, a[u].y, a[u].z, a[u].w, b[u].x, b[u].y, b[u].z, b[u].w};
+                bf16_t hi[8], lo[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    hi[e] = f2bf(v[e]);
+                    lo[e] = f2bf(v[e] - bf2f(hi[e]));
+                }
+                xs[dst[u]] = make_uint4(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]), pack_bf16x2(hi[4], hi[5]), pack_bf16x2(hi[6], hi[7]));
+                xlo[dst[u]] = make_uint4(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(lo[4], lo[5]), pack_bf16x2(lo[6], lo[7]));
             }
         }
-        for (; c < nc; ++c) {
-            const u32x4 w = __builtin_nontemporal_load(wp + (size_t)c * 64);
-            uint4 ah = xa[c * 4], al = xb[c * 4];
-            if (!rowok) { ah = zero; al = zero; }
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, ah), acc, 0, 0, 0);
-            acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, al), acl, 0, 0, 0);
+    }
+    __syncthreads();
+    const int row = lane & 15, g = lane >> 4;
+    const bool rowok = row < m;
+    const uint4* xa = xs + (rowok ? row : 0) * rs + g;
+    const uint4* xb = xlo + (rowok ? row : 0) * rs + g;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    f32x4 acc, acl;
+    auto multiply = [&](const u32x4 (&w)[GEMM_U], int gi) {
+#pragma unroll
+        for (int u = 0; u < GEMM_U; ++u) {
+            const int c = gi * GEMM_U + u;
+            const bool live = rowok && c < nc;
+            uint4 ah = xa[min(c, nc - 1) * 4], al = xb[min(c, nc - 1) * 4];
+            if (!live) { ah = zero; al = zero; }
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, ah), acc, 0, 0, 0);
+            acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, al), acl, 0, 0, 0);
+        }
+    };
+    for (int tt = wave; tt < tpb; tt += 4) {
+        const int t = tg * tpb + tt;
+        if (t >= ntiles) break;
+        if (tt != wave) {
+            wp = tile_base(t);
+            issue(wa, wp, 0);
+        }
+        acc = f32x4{0.f, 0.f, 0.f, 0.f};
+        acl = f32x4{0.f, 0.f, 0.f, 0.f};
+        // two register buffers: the next group of tiles is in flight while this one is multiplied
+        int gi = 0;
+        for (; gi + 2 < ngroups; gi += 2) {
+            issue(wb, wp, gi + 1);
+            multiply(wa, gi);
+            issue(wa, wp, gi + 2);
+            multiply(wb, gi + 1);
+        }
+        if (gi + 2 == ngroups) {
+            issue(wb, wp, gi + 1);
+            multiply(wa, gi);
+            multiply(wb, gi + 1);
+        } else {
+            multiply(wa, gi);
         }
         if (rowok) {
             float* o = out + (size_t)ks * m * N + (size_t)row * N + (size_t)t * 16 + g * 4;

@@ -3,6 +3,7 @@
 #include "../../include/metasd.h"
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cmath>
@@ -189,6 +190,17 @@ struct metasd_ctx {
     int n_cu = 0;
     std::vector<ProfRec> prof;       // event pool
     size_t prof_used = 0;
+    // Next free record, or nullptr when profiling is off / the pool is used up.  The launcher hands
+    // the record's two events to the dispatch itself (hipExtLaunchKernelGGL), so they carry the
+    // kernel's own begin and end times rather than those of marker packets around it.
+    ProfRec* prof_take(int kind, double bytes) {
+        if (!prof_on || prof_used >= prof.size()) return nullptr;
+        ProfRec* r = &prof[prof_used++];
+        r->kind = kind;
+        r->bytes = bytes;
+        return r;
+    }
+    // for launches that cannot carry events (cooperative): marker events on the stream around them
     bool prof_begin(int kind, double bytes) {
         if (!prof_on || prof_used >= prof.size()) return false;
         prof[prof_used].kind = kind;
@@ -266,11 +278,10 @@ int gemm<bf16_t>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void
     float* out = (direct_out && s.ksplit == 1) ? direct_out : c->d_part();
     const int groups = (ntiles + s.tpb - 1) / s.tpb;
     // algorithmic bytes: every weight once, the activations once, the result once
-    const bool timed = c->prof_begin(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
-    hipLaunchKernelGGL(gemm_bf16_kernel, dim3(groups * s.ksplit), dim3(256), s.lds, c->stream, (const float*)x, ldx, m, K,
-                       (const bf16_t*)W0, (const bf16_t*)W1, (const bf16_t*)W2, n0 / 16, (n0 + n1) / 16, ntiles, out, N,
-                       s.ksplit, s.cps, s.tpb);
-    if (timed) c->prof_end();
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
+    hipExtLaunchKernelGGL(gemm_bf16_kernel, dim3(groups * s.ksplit), dim3(256), (uint32_t)s.lds, c->stream, pr ? pr->a : nullptr,
+                          pr ? pr->b : nullptr, 0u, (const float*)x, ldx, m, K, (const bf16_t*)W0, (const bf16_t*)W1,
+                          (const bf16_t*)W2, n0 / 16, (n0 + n1) / 16, ntiles, out, N, s.ksplit, s.cps, s.tpb);
     LAUNCH_CHECK(c, "gemm_bf16");
     if (direct_out && s.ksplit > 1) {
         const size_t n = (size_t)m * N;
@@ -291,18 +302,18 @@ int attention_hd(metasd_ctx* c, const Model& M, int L, int pos0, int m) {
     const int nchunks = (pos0 + m + ATT_CH - 1) / ATT_CH;
     const float scale = 1.0f / sqrtf((float)HD);
     // algorithmic bytes: K and V of every cached position once per KV head, q in, partials out
-    const bool timed = c->prof_begin(METASD_PROF_ATTN, 2.0 * d.n_kv_heads * (double)(pos0 + m) * HD * sizeof(T) +
-                                                          (double)m * d.n_heads * HD * 4);
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_ATTN, 2.0 * d.n_kv_heads * (double)(pos0 + m) * HD * sizeof(T) +
+                                                                 (double)m * d.n_heads * HD * 4);
+    hipEvent_t ea = pr ? pr->a : nullptr, eb = pr ? pr->b : nullptr;
     if constexpr (sizeof(T) == 2 && HD >= 64) {
-        hipLaunchKernelGGL((attn_partial_mfma_kernel<HD>), dim3(nchunks, d.n_heads), dim3(256), 0, c->stream,
-                           (const float*)c->d_q(), kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale, c->d_apart(),
-                           nchunks);
+        hipExtLaunchKernelGGL((attn_partial_mfma_kernel<HD>), dim3(nchunks, d.n_heads), dim3(256), 0u, c->stream, ea, eb, 0u,
+                              (const float*)c->d_q(), kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale,
+                              c->d_apart(), nchunks);
     } else {
-        hipLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(nchunks, d.n_heads), dim3(256), 0, c->stream,
-                           (const float*)c->d_q(), kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale, c->d_apart(),
-                           nchunks);
+        hipExtLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(nchunks, d.n_heads), dim3(256), 0u, c->stream, ea, eb, 0u,
+                              (const float*)c->d_q(), kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale,
+                              c->d_apart(), nchunks);
     }
-    if (timed) c->prof_end();
     LAUNCH_CHECK(c, "attn_partial");
     hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3(d.n_heads, m), dim3(HD), 0, c->stream, c->d_apart(), nchunks,
                        d.n_heads, (float*)c->d_ao());
@@ -456,9 +467,9 @@ int launch_sample(hipStream_t st, const float* logits, int rows, int V, float T,
 
 int launch_accept(hipStream_t st, const float* P, const float* Q, const int32_t* d, int rows, int gamma, int V, float T,
                   uint64_t seed, uint32_t round, uint32_t seq0, int2* cand, double* bd, int32_t* n_acc, int32_t* token,
-                  uint32_t* mask, int32_t* hist, int l) {
-    hipLaunchKernelGGL(accept_rows_kernel, dim3(gamma + 1, rows), dim3(AK_NT), 0, st, P, Q, d, gamma, V, T, seed, round, seq0,
-                       cand, bd);
+                  uint32_t* mask, int32_t* hist, int l, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr) {
+    hipExtLaunchKernelGGL(accept_rows_kernel, dim3(gamma + 1, rows), dim3(AK_NT), 0u, st, ev_begin, ev_end, 0u, P, Q, d, gamma, V,
+                          T, seed, round, seq0, cand, bd);
     if (hipGetLastError() != hipSuccess) return METASD_E_HIP;
     hipLaunchKernelGGL(accept_finalize_kernel, dim3((rows + 63) / 64), dim3(64), 0, st, cand, rows, gamma, n_acc, token, mask,
                        hist, l);
@@ -740,11 +751,11 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
     if (gamma != c->cur_gamma) return c->fail(METASD_E_INVALID, "accept: gamma %d differs from the drafted %d", gamma, c->cur_gamma);
     const int V = c->target.d.vocab, l = c->l;
     int32_t* res = c->d_res();
-    const bool timed = c->prof_begin(METASD_PROF_ACCEPT, (double)(2 * gamma + 1) * V * 4);
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_ACCEPT, (double)(2 * gamma + 1) * V * 4);
     if (launch_accept(c->stream, c->d_P(), c->d_Q(), c->d_hist() + l, 1, gamma, V, c->cfg.temperature, c->cfg.seed,
-                      (uint32_t)c->round, 0u, c->d_cand(), c->d_bd(), res, res + 1, (uint32_t*)(res + 2), c->d_hist(), l))
+                      (uint32_t)c->round, 0u, c->d_cand(), c->d_bd(), res, res + 1, (uint32_t*)(res + 2), c->d_hist(), l,
+                      pr ? pr->a : nullptr, pr ? pr->b : nullptr))
         return c->fail(METASD_E_HIP, "launch accept kernels failed");
-    if (timed) c->prof_end();
     HostResult* hr = c->hres;
     HIP_TRY(c, hipMemcpyAsync(&hr->n_acc, res, 12, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipMemcpyAsync(hr->d, c->d_draft(), (size_t)gamma * 4, hipMemcpyDeviceToHost, c->stream));
