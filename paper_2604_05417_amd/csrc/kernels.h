@@ -722,41 +722,47 @@ __global__ void ffn_act_kernel(const float* __restrict__ part, int nsplit, size_
 }
 
 // ------------------------------------------------------------------------------------------
-// Vocab-wide softmax + accept test + residual / bonus inverse-CDF draw, one workgroup of 1024
+// Vocab-wide softmax + accept test + residual / bonus inverse-CDF draw, one workgroup of 512
 // threads per (sequence row, block position).  The logits of the position (target row and, for
 // j < gamma, drafter row) are read from HBM exactly once into registers: wavefront w owns the
-// contiguous vocabulary segment [2048 w, 2048 w + 2048), lane l the float4 at 256 c + 4 l of
-// chunk c = 0..7.  exp() is evaluated in fp32, every sum and the CDF in fp64.
+// contiguous vocabulary segment [4096 w, 4096 w + 4096), lane l the float4 at 256 c + 4 l of
+// chunk c = 0..15 (128 data registers per lane; 512 threads leave the compiler 256 registers, with
+// 1024 threads and 128 registers the same code spills).
+//
+// Arithmetic: exp(x - max) per element in fp32 (hardware exp2 with a two-term argument, about
+// 1.5 ulp); p = e_p / Z_p and q = e_q / Z_q per element in fp32 with 1/Z carried as two floats (so
+// the element error is one random rounding, not a common factor); every sum - Z_p, Z_q, the
+// residual mass, sum min(p, q), the CDF - in fp64.  The accept ratio p(d)/q(d) is formed in fp64.
+// The search for the drawn token is hierarchical (wavefront totals, then chunk totals inside the
+// one wavefront that holds the target, then a lane scan, then the four elements of that lane).
 
-constexpr int AK_NT = 1024, AK_WAVES = 16, AK_CH = 8, AK_SEG = AK_CH * 256;  // V <= 32768
+constexpr int AK_NT = 512, AK_WAVES = 8, AK_CH = 16, AK_SEG = AK_CH * 256;  // V <= 32768
 
 struct AkShared {
-    float fmx[AK_WAVES];
-    double dsum[AK_WAVES];
+    float fmx[2][AK_WAVES];
+    double dz[2][AK_WAVES];
+    double dw[2][AK_WAVES];
     int ival[AK_WAVES];
     int token;
 };
 
-__device__ __forceinline__ float ak_block_max(float v, AkShared& sm, int wave, int lane) {
-    v = wave_max(v);
-    __syncthreads();
-    if (lane == 0) sm.fmx[wave] = v;
-    __syncthreads();
-    float r = sm.fmx[0];
-#pragma unroll
-    for (int w = 1; w < AK_WAVES; ++w) r = fmaxf(r, sm.fmx[w]);
-    return r;
+// exp(a) for a <= 0 (or -inf): 2^(a log2 e) with log2 e split in two floats so that the argument
+// carries about 48 bits; results below the normal range flush to zero.
+__device__ __forceinline__ float ak_exp(float a) {
+    const float L2E_HI = 1.44269502162933349609375f, L2E_LO = 1.92596299112661746e-8f;
+    const float th = a * L2E_HI;
+    const float tl = fmaf(a, L2E_LO, fmaf(a, L2E_HI, -th));
+    const float e = __builtin_amdgcn_exp2f(th);
+    const float r = fmaf(e * tl, 0.693147182464599609375f, e);
+    return a > -INFINITY ? r : 0.f;
 }
 
-__device__ __forceinline__ double ak_block_sum(double v, AkShared& sm, int wave, int lane) {
-    v = wave_sum(v);
-    __syncthreads();
-    if (lane == 0) sm.dsum[wave] = v;
-    __syncthreads();
-    double r = 0.0;
-#pragma unroll
-    for (int w = 0; w < AK_WAVES; ++w) r += sm.dsum[w];
-    return r;
+// exp((x - mx) / T): for T = 1 the fp32 difference is the correctly rounded argument; otherwise
+// the argument is scaled in fp64 before it is rounded.
+template <bool UNIT_T>
+__device__ __forceinline__ float ak_expx(float x, float mx, double invT) {
+    if constexpr (UNIT_T) return ak_exp(x - mx);
+    else return ak_exp((float)(((double)x - (double)mx) * invT));
 }
 
 __device__ __forceinline__ void ak_load(const float* __restrict__ row, int V, int wave, int lane, float (&x)[AK_CH][4]) {
@@ -772,111 +778,91 @@ __device__ __forceinline__ void ak_load(const float* __restrict__ row, int V, in
     }
 }
 
-// x <- exp((x - max) / T) in place (fp32 exp of an fp64-scaled argument); returns the block sum.
-__device__ __forceinline__ double ak_exp_sum(float (&x)[AK_CH][4], float mx, double invT, AkShared& sm, int wave, int lane) {
+__device__ __forceinline__ float ak_thread_max(const float (&x)[AK_CH][4]) {
+    float lm = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < AK_CH; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) lm = fmaxf(lm, x[c][e]);
+    return lm;
+}
+
+// x <- exp((x - mx)/T) in place; returns this thread's fp64 sum.
+template <bool UNIT_T>
+__device__ __forceinline__ double ak_exp_inplace(float (&x)[AK_CH][4], float mx, double invT) {
     double s = 0.0;
 #pragma unroll
     for (int c = 0; c < AK_CH; ++c)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float v = expf((float)(((double)x[c][e] - (double)mx) * invT));
+            const float v = ak_expx<UNIT_T>(x[c][e], mx, invT);
             x[c][e] = v;
             s += (double)v;
         }
-    return ak_block_sum(s, sm, wave, lane);
+    return s;
 }
 
-// Weight of element (c, e) for the draw: mode 0 = max(0, p - q), mode 1 = p (unnormalised exp).
-__device__ __forceinline__ double ak_weight(const float (&ep)[AK_CH][4], const float (&eq)[AK_CH][4], int c, int e,
-                                            double ipz, double iqz, int mode) {
-    if (mode == 1) return (double)ep[c][e];
-    const double dlt = (double)ep[c][e] * ipz - (double)eq[c][e] * iqz;
-    return dlt > 0.0 ? dlt : 0.0;
+__device__ __forceinline__ double ak_chunk_sum(const float (&w)[AK_CH][4], int c) {
+    return ((double)w[c][0] + (double)w[c][1]) + ((double)w[c][2] + (double)w[c][3]);
 }
 
-// Inverse CDF in ascending vocabulary order: smallest v with sum_{w<=v} weight_w > u * Z.
-// Returns the token in every thread.  *z_out = Z.
-__device__ int ak_inverse_cdf(const float (&ep)[AK_CH][4], const float (&eq)[AK_CH][4], double ipz, double iqz, int mode,
-                              float u, int V, AkShared& sm, int wave, int lane, double* z_out) {
-    double s[AK_CH];
-    double lt = 0.0;
-#pragma unroll
-    for (int c = 0; c < AK_CH; ++c) {
-        s[c] = 0.0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) s[c] += ak_weight(ep, eq, c, e, ipz, iqz, mode);
-        lt += s[c];
-    }
-    const double wt = wave_sum(lt);
-    __syncthreads();
-    if (lane == 0) sm.dsum[wave] = wt;
-    if (threadIdx.x == 0) sm.token = -1;
-    __syncthreads();
-    double Z = 0.0;
-#pragma unroll
-    for (int w = 0; w < AK_WAVES; ++w) Z += sm.dsum[w];
-    *z_out = Z;
-    if (!(Z > 0.0)) return -1;
+// Inverse CDF in ascending vocabulary order over the non-negative weights w (registers):
+// smallest v with sum_{i<=v} w_i > u * Z, where wtot[0..16) in LDS are the wavefront totals
+// (already visible to every thread) and Z their sum.  If rounding leaves no such v, the last
+// index with weight.  The winner is written to sm.token; the caller synchronises before reading.
+__device__ __forceinline__ void ak_search(const float (&w)[AK_CH][4], const double* wtot, double Z, float u, int V, AkShared& sm,
+                                          int wave, int lane) {
     const double target = (double)u * Z;
-    // wavefront holding the target; if rounding leaves none, the last one with weight
     int wstar = -1, wlast = 0;
     double base = 0.0, run = 0.0;
 #pragma unroll
-    for (int w = 0; w < AK_WAVES; ++w) {
-        const double ww = sm.dsum[w];
-        if (ww > 0.0) wlast = w;
+    for (int k = 0; k < AK_WAVES; ++k) {
+        const double ww = wtot[k];
+        if (ww > 0.0) wlast = k;
         if (wstar < 0) {
-            if (run + ww > target) { wstar = w; base = run; }
+            if (run + ww > target) { wstar = k; base = run; }
             else run += ww;
         }
     }
     bool take_last = false;
     if (wstar < 0) { wstar = wlast; take_last = true; }
-    if (wave == wstar) {   // wave-uniform branch
-        int cstar = -1, clast = -1;
-        double cb = base;
+    if (wave != wstar) return;   // wave-uniform
+    int cstar = -1, clast = -1;
+    double cb = base;
 #pragma unroll
-        for (int c = 0; c < AK_CH; ++c) {
-            const double ct = wave_sum(s[c]);
-            if (ct > 0.0) clast = c;
-            if (cstar < 0 && !take_last) {
-                if (cb + ct > target) cstar = c;
-                else cb += ct;
-            }
-        }
-        if (cstar < 0) { cstar = clast < 0 ? 0 : clast; take_last = true; }
-        double sc = 0.0;
-#pragma unroll
-        for (int c = 0; c < AK_CH; ++c)
-            if (c == cstar) sc = s[c];
-        const double incl = wave_scan_incl(sc, lane);
-        unsigned long long bal = __ballot(take_last ? (sc > 0.0) : (cb + incl > target));
-        if (bal == 0ull) { take_last = true; bal = __ballot(sc > 0.0); }
-        int lstar;
-        if (bal == 0ull) lstar = 0;
-        else lstar = take_last ? (63 - __clzll((long long)bal)) : (__ffsll((long long)bal) - 1);
-        if (lane == lstar) {
-            double acc = cb + incl - sc;
-            int tok = -1, lastpos = -1;
-            const int idx0 = wave * AK_SEG + cstar * 256 + lane * 4;
-#pragma unroll
-            for (int c = 0; c < AK_CH; ++c) {
-                if (c == cstar) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const double w = ak_weight(ep, eq, c, e, ipz, iqz, mode);
-                        acc += w;
-                        if (w > 0.0) lastpos = idx0 + e;
-                        if (tok < 0 && !take_last && acc > target) tok = idx0 + e;
-                    }
-                }
-            }
-            if (tok < 0) tok = lastpos >= 0 ? lastpos : min(idx0, V - 1);
-            sm.token = tok;
+    for (int c = 0; c < AK_CH; ++c) {
+        const double ct = wave_sum(ak_chunk_sum(w, c));
+        if (ct > 0.0) clast = c;
+        if (cstar < 0 && !take_last) {
+            if (cb + ct > target) cstar = c;
+            else cb += ct;
         }
     }
-    __syncthreads();
-    return sm.token;
+    if (cstar < 0) { cstar = clast < 0 ? 0 : clast; take_last = true; }
+    float w4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < AK_CH; ++c)
+        if (c == cstar) { w4[0] = w[c][0]; w4[1] = w[c][1]; w4[2] = w[c][2]; w4[3] = w[c][3]; }
+    const double sc = ((double)w4[0] + (double)w4[1]) + ((double)w4[2] + (double)w4[3]);
+    const double incl = wave_scan_incl(sc, lane);
+    unsigned long long bal = __ballot(take_last ? (sc > 0.0) : (cb + incl > target));
+    if (bal == 0ull) { take_last = true; bal = __ballot(sc > 0.0); }
+    int lstar;
+    if (bal == 0ull) lstar = 0;
+    else lstar = take_last ? (63 - __clzll((long long)bal)) : (__ffsll((long long)bal) - 1);
+    if (lane == lstar) {
+        double acc = cb + incl - sc;
+        int tok = -1, lastpos = -1;
+        const int idx0 = wave * AK_SEG + cstar * 256 + lane * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc += (double)w4[e];
+            if (w4[e] > 0.f) lastpos = idx0 + e;
+            if (tok < 0 && !take_last && acc > target) tok = idx0 + e;
+        }
+        if (tok < 0) tok = lastpos >= 0 ? lastpos : min(idx0, V - 1);
+        sm.token = tok;
+    }
 }
 
 // argmax with lowest index on ties; returns the index in every thread
@@ -897,14 +883,13 @@ __device__ int ak_argmax(const float (&x)[AK_CH][4], AkShared& sm, int wave, int
         const int oi = __shfl_xor(bi, o, 64);
         if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
     }
+    if (lane == 0) { sm.fmx[0][wave] = bv; sm.ival[wave] = bi; }
     __syncthreads();
-    if (lane == 0) { sm.fmx[wave] = bv; sm.ival[wave] = bi; }
-    __syncthreads();
-    float rv = sm.fmx[0];
+    float rv = sm.fmx[0][0];
     int ri = sm.ival[0];
 #pragma unroll
     for (int w = 1; w < AK_WAVES; ++w) {
-        const float ov = sm.fmx[w];
+        const float ov = sm.fmx[0][w];
         const int oi = sm.ival[w];
         if (ov > rv || (ov == rv && oi < ri)) { rv = ov; ri = oi; }
     }
@@ -915,11 +900,11 @@ __device__ int ak_argmax(const float (&x)[AK_CH][4], AkShared& sm, int wave, int
 //   j < gamma : test u_acc < min(1, p(d)/q(d)); candidate = draw from norm(max(0, p - q)) (from p if p == q)
 //   j == gamma: candidate = draw from p (bonus token); test result unused (1)
 //   T == 0    : test = [d == argmax P_j], candidate = argmax P_j
-__global__ __launch_bounds__(AK_NT) void accept_rows_kernel(const float* __restrict__ P, const float* __restrict__ Q,
-                                                            const int32_t* __restrict__ d, int gamma, int V, float T,
-                                                            uint64_t seed, uint32_t round, uint32_t seq0,
-                                                            int2* __restrict__ cand, double* __restrict__ bd) {
-    __shared__ AkShared sm;
+template <bool UNIT_T>
+__device__ __forceinline__ void accept_rows_body(const float* __restrict__ P, const float* __restrict__ Q,
+                                                 const int32_t* __restrict__ d, int gamma, int V, float T, uint64_t seed,
+                                                 uint32_t round, uint32_t seq0, int2* __restrict__ cand,
+                                                 double* __restrict__ bd, AkShared& sm) {
     const int j = blockIdx.x, b = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float* Prow = P + ((size_t)b * (gamma + 1) + j) * V;
@@ -938,54 +923,89 @@ __global__ __launch_bounds__(AK_NT) void accept_rows_kernel(const float* __restr
     }
     const double invT = 1.0 / (double)T;
     if (has_q) ak_load(Qrow, V, wave, lane, xq);
-    else {
-#pragma unroll
-        for (int c = 0; c < AK_CH; ++c) xq[c][0] = xq[c][1] = xq[c][2] = xq[c][3] = -INFINITY;
+    // the two logits of the draft token (tiny second read, issued with the stream)
+    float pdl = 0.f, qdl = 0.f;
+    if (has_q) { pdl = Prow[dtok]; qdl = Qrow[dtok]; }
+    if (threadIdx.x == 0) sm.token = -1;
+    // ---- maxima
+    {
+        const float a = wave_max(ak_thread_max(xp));
+        const float c = has_q ? wave_max(ak_thread_max(xq)) : -INFINITY;
+        if (lane == 0) { sm.fmx[0][wave] = a; sm.fmx[1][wave] = c; }
     }
-    float lm = -INFINITY;
+    __syncthreads();
+    float mp = sm.fmx[0][0], mq = sm.fmx[1][0];
 #pragma unroll
-    for (int c = 0; c < AK_CH; ++c)
+    for (int k = 1; k < AK_WAVES; ++k) { mp = fmaxf(mp, sm.fmx[0][k]); mq = fmaxf(mq, sm.fmx[1][k]); }
+    // ---- exp and the two normalisers
+    {
+        const double a = wave_sum(ak_exp_inplace<UNIT_T>(xp, mp, invT));
+        const double c = has_q ? wave_sum(ak_exp_inplace<UNIT_T>(xq, mq, invT)) : 0.0;
+        if (lane == 0) { sm.dz[0][wave] = a; sm.dz[1][wave] = c; }
+    }
+    __syncthreads();
+    double Zp = 0.0, Zq = 0.0;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) lm = fmaxf(lm, xp[c][e]);
-    const float mp = ak_block_max(lm, sm, wave, lane);
-    const double Zp = ak_exp_sum(xp, mp, invT, sm, wave, lane);
-    const double ipz = 1.0 / Zp;
+    for (int k = 0; k < AK_WAVES; ++k) { Zp += sm.dz[0][k]; Zq += sm.dz[1][k]; }
     const float u_res = philox_uniform(seed, seq0 + (uint32_t)b, round, 0u, 1u);
-    int accept = 1, token;
-    double Z;
-    if (has_q) {
-        lm = -INFINITY;
-#pragma unroll
-        for (int c = 0; c < AK_CH; ++c)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) lm = fmaxf(lm, xq[c][e]);
-        const float mq = ak_block_max(lm, sm, wave, lane);
-        const double Zq = ak_exp_sum(xq, mq, invT, sm, wave, lane);
-        const double iqz = 1.0 / Zq;
-        double mn = 0.0;
-#pragma unroll
-        for (int c = 0; c < AK_CH; ++c)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const double pv = (double)xp[c][e] * ipz, qv = (double)xq[c][e] * iqz;
-                mn += pv < qv ? pv : qv;
-            }
-        const double bdj = ak_block_sum(mn, sm, wave, lane);
-        const float epd = expf((float)(((double)Prow[dtok] - (double)mp) * invT));
-        const float eqd = expf((float)(((double)Qrow[dtok] - (double)mq) * invT));
-        const double qd = (double)eqd * iqz;
+    int accept = 1;
+    if (!has_q) {   // bonus position: draw from p
+        ak_search(xp, sm.dz[0], Zp, u_res, V, sm, wave, lane);
+        __syncthreads();
+        if (threadIdx.x == 0) cand[(size_t)b * (gamma + 1) + j] = make_int2(sm.token, 1);
+        return;
+    }
+    const double ipz = 1.0 / Zp, iqz = 1.0 / Zq;
+    const float ip_hi = (float)ipz, ip_lo = (float)(ipz - (double)ip_hi);
+    const float iq_hi = (float)iqz, iq_lo = (float)(iqz - (double)iq_hi);
+    // ---- accept test on the draft token
+    {
+        const double pd = (double)ak_expx<UNIT_T>(pdl, mp, invT) * ipz, qd = (double)ak_expx<UNIT_T>(qdl, mq, invT) * iqz;
         if (qd > 0.0) {
-            const double ratio = ((double)epd * ipz) / qd;
+            const double ratio = pd / qd;
             const float u_acc = philox_uniform(seed, seq0 + (uint32_t)b, round, (uint32_t)j, 0u);
             accept = (double)u_acc < (ratio < 1.0 ? ratio : 1.0);
         }
-        token = ak_inverse_cdf(xp, xq, ipz, iqz, 0, u_res, V, sm, wave, lane, &Z);
-        if (token < 0) token = ak_inverse_cdf(xp, xq, ipz, iqz, 1, u_res, V, sm, wave, lane, &Z);   // p == q
-        if (threadIdx.x == 0 && bd) bd[(size_t)b * gamma + j] = bdj;
-    } else {
-        token = ak_inverse_cdf(xp, xq, ipz, 0.0, 1, u_res, V, sm, wave, lane, &Z);
     }
-    if (threadIdx.x == 0) cand[(size_t)b * (gamma + 1) + j] = make_int2(token, accept);
+    // ---- residual weights max(0, p - q) (kept in xq) and sum min(p, q)
+    {
+        double tw = 0.0, tm = 0.0;
+#pragma unroll
+        for (int c = 0; c < AK_CH; ++c) {
+            float mn4 = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float pv = fmaf(xp[c][e], ip_lo, xp[c][e] * ip_hi), qv = fmaf(xq[c][e], iq_lo, xq[c][e] * iq_hi);
+                mn4 += fminf(pv, qv);
+                xq[c][e] = fmaxf(pv - qv, 0.f);
+            }
+            tw += ak_chunk_sum(xq, c);
+            tm += (double)mn4;
+        }
+        tw = wave_sum(tw);
+        tm = wave_sum(tm);
+        if (lane == 0) { sm.dw[0][wave] = tw; sm.dw[1][wave] = tm; }
+    }
+    __syncthreads();
+    double Zr = 0.0, bdj = 0.0;
+#pragma unroll
+    for (int k = 0; k < AK_WAVES; ++k) { Zr += sm.dw[0][k]; bdj += sm.dw[1][k]; }
+    if (Zr > 0.0) ak_search(xq, sm.dw[0], Zr, u_res, V, sm, wave, lane);
+    else ak_search(xp, sm.dz[0], Zp, u_res, V, sm, wave, lane);   // p == q: a rejection has probability 0; draw from p
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        cand[(size_t)b * (gamma + 1) + j] = make_int2(sm.token, accept);
+        if (bd) bd[(size_t)b * gamma + j] = bdj;
+    }
+}
+
+__global__ __launch_bounds__(AK_NT) void accept_rows_kernel(const float* __restrict__ P, const float* __restrict__ Q,
+                                                            const int32_t* __restrict__ d, int gamma, int V, float T,
+                                                            uint64_t seed, uint32_t round, uint32_t seq0,
+                                                            int2* __restrict__ cand, double* __restrict__ bd) {
+    __shared__ AkShared sm;
+    if (T == 1.0f) accept_rows_body<true>(P, Q, d, gamma, V, T, seed, round, seq0, cand, bd, sm);
+    else accept_rows_body<false>(P, Q, d, gamma, V, T, seed, round, seq0, cand, bd, sm);
 }
 
 // Per row: N_acc = first failed test, emitted token = candidate of that position, mask bits.
@@ -1010,8 +1030,28 @@ __global__ void accept_finalize_kernel(const int2* __restrict__ cand, int rows, 
 }
 
 // Token draw from one row of logits: argmax (T = 0) or inverse CDF of softmax(logits / T) with the
-// stream-2 uniform at (seq0 + row, round, pos).  grid (rows), block 1024.  tok[row * tok_stride]
+// stream-2 uniform at (seq0 + row, round, pos).  grid (rows), block 512.  tok[row * tok_stride]
 // (and tok_copy[row] when given).
+template <bool UNIT_T>
+__device__ __forceinline__ int sample_rows_body(float (&xp)[AK_CH][4], int V, float T, float u, AkShared& sm, int wave, int lane) {
+    if (threadIdx.x == 0) sm.token = -1;
+    const float a = wave_max(ak_thread_max(xp));
+    if (lane == 0) sm.fmx[0][wave] = a;
+    __syncthreads();
+    float mp = sm.fmx[0][0];
+#pragma unroll
+    for (int k = 1; k < AK_WAVES; ++k) mp = fmaxf(mp, sm.fmx[0][k]);
+    const double s = wave_sum(ak_exp_inplace<UNIT_T>(xp, mp, 1.0 / (double)T));
+    if (lane == 0) sm.dz[0][wave] = s;
+    __syncthreads();
+    double Zp = 0.0;
+#pragma unroll
+    for (int k = 0; k < AK_WAVES; ++k) Zp += sm.dz[0][k];
+    ak_search(xp, sm.dz[0], Zp, u, V, sm, wave, lane);
+    __syncthreads();
+    return sm.token;
+}
+
 __global__ __launch_bounds__(AK_NT) void sample_rows_kernel(const float* __restrict__ logits, int V, float T, uint64_t seed,
                                                             uint32_t round, uint32_t pos, uint32_t seq0,
                                                             int32_t* __restrict__ tok, int tok_stride,
@@ -1025,16 +1065,8 @@ __global__ __launch_bounds__(AK_NT) void sample_rows_kernel(const float* __restr
     if (T <= 0.f) {
         token = ak_argmax(xp, sm, wave, lane);
     } else {
-        float lm = -INFINITY;
-#pragma unroll
-        for (int c = 0; c < AK_CH; ++c)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) lm = fmaxf(lm, xp[c][e]);
-        const float mp = ak_block_max(lm, sm, wave, lane);
-        const double Zp = ak_exp_sum(xp, mp, 1.0 / (double)T, sm, wave, lane);
         const float u = philox_uniform(seed, seq0 + (uint32_t)b, round, pos, 2u);
-        double Z;
-        token = ak_inverse_cdf(xp, xp, 1.0 / Zp, 0.0, 1, u, V, sm, wave, lane, &Z);
+        token = T == 1.0f ? sample_rows_body<true>(xp, V, T, u, sm, wave, lane) : sample_rows_body<false>(xp, V, T, u, sm, wave, lane);
     }
     if (threadIdx.x == 0) {
         tok[(size_t)b * tok_stride] = token;
