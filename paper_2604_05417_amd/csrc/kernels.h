@@ -729,8 +729,7 @@ __global__ void ffn_act_kernel(const float* __restrict__ part, int nsplit, size_
 // chunk c = 0..15 (128 data registers per lane; 512 threads leave the compiler 256 registers, with
 // 1024 threads and 128 registers the same code spills).
 //
-// Arithmetic: exp(x - max) per element in fp32 (hardware exp2 with a two-term argument, about
-// 1.5 ulp); p = e_p / Z_p and q = e_q / Z_q per element in fp32 with 1/Z carried as two floats (so
+// Arithmetic: exp(x - max) per element in fp32 (hardware exp2); p = e_p / Z_p and q = e_q / Z_q per element in fp32 with 1/Z carried as two floats (so
 // the element error is one random rounding, not a common factor); every sum - Z_p, Z_q, the
 // residual mass, sum min(p, q), the CDF - in fp64.  The accept ratio p(d)/q(d) is formed in fp64.
 // The search for the drawn token is hierarchical (wavefront totals, then chunk totals inside the
@@ -746,15 +745,13 @@ struct AkShared {
     int token;
 };
 
-// exp(a) for a <= 0 (or -inf): 2^(a log2 e) with log2 e split in two floats so that the argument
-// carries about 48 bits; results below the normal range flush to zero.
+// exp(a) for a <= 0 (or -inf): hardware 2^(a log2 e).  The fp32 product rounds the argument, so the
+// relative error grows with |a| (about 4e-7 at a = -10); it is random per element, which leaves
+// sums over the vocabulary and the accept ratio far inside their near-tie windows.  Results below
+// the normal range flush to zero.
 __device__ __forceinline__ float ak_exp(float a) {
-    const float L2E_HI = 1.44269502162933349609375f, L2E_LO = 1.92596299112661746e-8f;
-    const float th = a * L2E_HI;
-    const float tl = fmaf(a, L2E_LO, fmaf(a, L2E_HI, -th));
-    const float e = __builtin_amdgcn_exp2f(th);
-    const float r = fmaf(e * tl, 0.693147182464599609375f, e);
-    return a > -INFINITY ? r : 0.f;
+    const float e = __builtin_amdgcn_exp2f(a * 1.44269502162933349609375f);
+    return a > -INFINITY ? e : 0.f;
 }
 
 // exp((x - mx) / T): for T = 1 the fp32 difference is the correctly rounded argument; otherwise
