@@ -116,20 +116,31 @@ __global__ __launch_bounds__(1024) void addnorm_kernel(float* __restrict__ h, co
                                                        size_t sstride, int d, const T* __restrict__ gain, float eps,
                                                        float* __restrict__ xn) {
     __shared__ float red[16];
+    constexpr int KEEP = 2;                 // float4 columns per thread kept in registers (d <= 8192); beyond that via memory
     const int r = blockIdx.x;
     float* hr = h + (size_t)r * d;
+    const float* pr = part + (size_t)r * d;
+    float4 keep[KEEP];
     float ss = 0.f;
-    for (int i = threadIdx.x * 4; i < d; i += 4096) {
+    int k = 0;
+    for (int i = threadIdx.x * 4; i < d; i += 4096, ++k) {
         float4 v = *reinterpret_cast<const float4*>(hr + i);
         if (nsplit > 0) {
             float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int s = 0; s < nsplit; ++s) {      // fixed order: deterministic
-                const float4 p = *reinterpret_cast<const float4*>(part + (size_t)s * sstride + (size_t)r * d + i);
-                y.x += p.x; y.y += p.y; y.z += p.z; y.w += p.w;
+            for (int s0 = 0; s0 < nsplit; s0 += 8) {      // eight partials in flight; added in the fixed order s = 0, 1, ..
+                float4 p[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    p[u] = (s0 + u < nsplit) ? *reinterpret_cast<const float4*>(pr + (size_t)(s0 + u) * sstride + i)
+                                             : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (s0 + u < nsplit) { y.x += p[u].x; y.y += p[u].y; y.z += p[u].z; y.w += p[u].w; }
             }
             v.x += y.x; v.y += y.y; v.z += y.z; v.w += y.w;
             *reinterpret_cast<float4*>(hr + i) = v;
         }
+        if (k < KEEP) keep[k] = v;
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
     ss = wave_sum(ss);
@@ -139,9 +150,10 @@ __global__ __launch_bounds__(1024) void addnorm_kernel(float* __restrict__ h, co
 #pragma unroll
     for (int w = 0; w < 16; ++w) tot += red[w];
     const float inv = 1.0f / sqrtf(tot / (float)d + eps);
-    if (xn)
-        for (int i = threadIdx.x * 4; i < d; i += 4096) {
-            const float4 v = *reinterpret_cast<const float4*>(hr + i);
+    if (xn) {
+        k = 0;
+        for (int i = threadIdx.x * 4; i < d; i += 4096, ++k) {
+            const float4 v = k < KEEP ? keep[k < KEEP ? k : 0] : *reinterpret_cast<const float4*>(hr + i);
             float4 o;
             o.x = v.x * inv * El<T>::ld(gain[i]);
             o.y = v.y * inv * El<T>::ld(gain[i + 1]);
@@ -149,6 +161,7 @@ __global__ __launch_bounds__(1024) void addnorm_kernel(float* __restrict__ h, co
             o.w = v.w * inv * El<T>::ld(gain[i + 3]);
             *reinterpret_cast<float4*>(xn + (size_t)r * d + i) = o;
         }
+    }
 }
 
 // out[i] = sum_s part[s][i]                         (only for logits when the head GEMM is split)
@@ -364,26 +377,44 @@ __global__ void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restr
 //   part: split-K partials of the fused q|k|v projection, [s][r][N], N = (H + 2 KH) * hd.
 //   q out fp32 [m][H*hd]; cache planes (type T) [kv_head][max_ctx][hd].     grid (H + 2KH, m), block 64
 
+// Rotation table of one forward block: tab[r][i] = (cos, sin)(pos0 + r) * theta^(-2i/hd), in fp64 (the
+// rotation is applied in fp64 and rounded once).  grid (m), block hd/2.  Built once per forward, used by every layer.
+__global__ void rope_table_kernel(int pos0, int hd, float theta, double2* __restrict__ tab) {
+    const int r = blockIdx.x, i = threadIdx.x, half = hd >> 1;
+    if (i >= half) return;
+    const double freq = pow((double)theta, -2.0 * (double)i / (double)hd);
+    double sn, cs;
+    sincos((double)(pos0 + r) * freq, &sn, &cs);
+    tab[r * half + i] = make_double2(cs, sn);
+}
+
 template <typename T>
 __global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int N, int pos0, int H, int KH,
-                               int hd, float theta, float* __restrict__ q, T* __restrict__ kc, T* __restrict__ vc, int max_ctx,
-                               int interleaved) {
+                               int hd, const double2* __restrict__ tab, float* __restrict__ q, T* __restrict__ kc,
+                               T* __restrict__ vc, int max_ctx, int interleaved) {
     const int head = blockIdx.x, r = blockIdx.y, i = threadIdx.x, half = hd >> 1;
     if (i >= half) return;
     // interleaved (rope-ordered packed weights): q / k columns hold the pair (i, i + half) at 16(i/8) + 2(i%8), +1
     const bool il = interleaved && head < H + KH;
     const size_t base = (size_t)r * N + (size_t)head * hd;
     const size_t ca = base + (il ? 16 * (i >> 3) + 2 * (i & 7) : i), cb = il ? ca + 1 : ca + half;
+    const double2 cssn = tab[r * half + i];
     float a = 0.f, b = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-        a += part[(size_t)s * sstride + ca];
-        b += part[(size_t)s * sstride + cb];
+    for (int s0 = 0; s0 < nsplit; s0 += 8) {          // eight partials in flight, added in order
+        float pa[8], pb[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool ok = s0 + u < nsplit;
+            pa[u] = ok ? part[(size_t)(s0 + u) * sstride + ca] : 0.f;
+            pb[u] = ok ? part[(size_t)(s0 + u) * sstride + cb] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (s0 + u < nsplit) { a += pa[u]; b += pb[u]; }
     }
     const int pos = pos0 + r;
     if (head < H + KH) {
-        const double freq = pow((double)theta, -2.0 * (double)i / (double)hd);
-        double sn, cs;
-        sincos((double)pos * freq, &sn, &cs);
+        const double cs = cssn.x, sn = cssn.y;
         const float ra = (float)((double)a * cs - (double)b * sn);
         const float rb = (float)((double)a * sn + (double)b * cs);
         a = ra; b = rb;
@@ -684,16 +715,29 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks,
     const float* base = part + ((size_t)h * nchunks * 16 + r) * (HD + 2);
     const size_t cs = (size_t)16 * (HD + 2);
     float M = -INFINITY;
-    for (int c = 0; c < nchunks; ++c) M = fmaxf(M, base[c * cs + HD]);
+    for (int c0 = 0; c0 < nchunks; c0 += 8) {           // eight chunk records in flight
+        float mc[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mc[u] = (c0 + u < nchunks) ? base[(c0 + u) * cs + HD] : -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) M = fmaxf(M, mc[u]);
+    }
     float Lsum = 0.f, o = 0.f;
-#pragma unroll 4
-    for (int c = 0; c < nchunks; ++c) {
-        const float mc = base[c * cs + HD];
-        const float lc = base[c * cs + HD + 1];
-        const float oc = base[c * cs + col];
-        const float w = (mc == -INFINITY) ? 0.f : expf(mc - M);
-        Lsum += lc * w;
-        o += oc * w;
+    for (int c0 = 0; c0 < nchunks; c0 += 8) {
+        float mc[8], lc[8], oc[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool ok = c0 + u < nchunks;
+            mc[u] = ok ? base[(c0 + u) * cs + HD] : -INFINITY;
+            lc[u] = ok ? base[(c0 + u) * cs + HD + 1] : 0.f;
+            oc[u] = ok ? base[(c0 + u) * cs + col] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float w = (mc[u] == -INFINITY) ? 0.f : expf(mc[u] - M);
+            Lsum += lc[u] * w;
+            o += oc[u] * w;
+        }
     }
     out[(size_t)r * H * HD + (size_t)h * HD + col] = o / Lsum;
 }
@@ -707,18 +751,22 @@ __global__ void ffn_act_kernel(const float* __restrict__ part, int nsplit, size_
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)m * f) return;
     const int r = (int)(idx / f), i = (int)(idx - (size_t)r * f);
-    if (act == 1) {
-        float g = 0.f, u = 0.f;
-        for (int s = 0; s < nsplit; ++s) {
-            g += part[(size_t)s * sstride + (size_t)r * 2 * f + i];
-            u += part[(size_t)s * sstride + (size_t)r * 2 * f + f + i];
+    const size_t cg = (size_t)r * (act == 1 ? 2 : 1) * f + i, cu = cg + f;
+    float g = 0.f, u = 0.f;
+    for (int s0 = 0; s0 < nsplit; s0 += 4) {            // four partials in flight, added in order
+        float pg[4], pu[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const bool ok = s0 + k < nsplit;
+            pg[k] = ok ? part[(size_t)(s0 + k) * sstride + cg] : 0.f;
+            pu[k] = (ok && act == 1) ? part[(size_t)(s0 + k) * sstride + cu] : 0.f;
         }
-        out[idx] = g / (1.0f + expf(-g)) * u;
-    } else {
-        float u = 0.f;
-        for (int s = 0; s < nsplit; ++s) u += part[(size_t)s * sstride + (size_t)r * f + i];
-        out[idx] = 0.5f * u * (1.0f + erff(u * 0.70710678118654752f));
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (s0 + k < nsplit) { g += pg[k]; u += pu[k]; }
     }
+    if (act == 1) out[idx] = g / (1.0f + expf(-g)) * u;
+    else out[idx] = 0.5f * g * (1.0f + erff(g * 0.70710678118654752f));
 }
 
 // ------------------------------------------------------------------------------------------

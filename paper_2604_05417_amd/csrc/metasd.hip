@@ -60,13 +60,18 @@ struct Split {
     size_t lds;
 };
 
+int env_int(const char* name, int dflt) { const char* e = getenv(name); return e ? atoi(e) : dflt; }
+int ks_cap() { static const int v = std::max(1, std::min(env_int("METASD_GEMM_KSMAX", 8), 32)); return v; }
+
 Split choose_split(int m, int ntiles, int kchunks) {
+    static const int target_units = env_int("METASD_GEMM_UNITS", 3072), align = std::max(1, env_int("METASD_GEMM_ALIGN", 8));
     const int cps_max = std::max(1, ((LDS_BUDGET / 32 / m) - 1) / 4);   // two bf16 terms per activation
-    int want = (2048 + ntiles / 2) / ntiles;                      // aim for about 2048 wavefront work units
-    want = std::max(1, std::min(want, 8));
+    int want = (target_units + ntiles / 2) / ntiles;              // aim for about 3072 wavefront work units
+    want = std::max(1, std::min(want, ks_cap()));
     want = std::min(want, std::max(1, kchunks / 8));              // at least 8 chunks per slice
     int ks = std::max(want, (kchunks + cps_max - 1) / cps_max);   // LDS capacity wins
     int cps = (kchunks + ks - 1) / ks;
+    if (align > 1 && (cps + align - 1) / align * align <= cps_max) cps = (cps + align - 1) / align * align;
     ks = (kchunks + cps - 1) / cps;
     Split s;
     s.ksplit = ks;
@@ -97,7 +102,7 @@ const char* check_model(const metasd_model_desc& d, const char* who, char* buf, 
 
 // Workspace layout shared by metasd_workspace_bytes and metasd_create.
 struct Layout {
-    size_t hist, h, xn, part, q, ao, act, apart, P, Q, cand, bd, res, draft, bar, tables, table_stride, total;
+    size_t hist, h, xn, part, q, ao, act, apart, rope, P, Q, cand, bd, res, draft, bar, tables, table_stride, total;
 };
 
 Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const metasd_model_desc* dr) {
@@ -113,7 +118,7 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
             int ksplit = 1;
             if (d.dtype == METASD_BF16) ksplit = choose_split(MAX_ROWS, ns[i] / 16, ks[i] / 32).ksplit;
             // a smaller m never needs more splits for LDS, but may use up to 8 for parallelism
-            ksplit = std::max(ksplit, 8);
+            ksplit = std::max(ksplit, ks_cap());
             partmax = std::max(partmax, (size_t)ksplit * MAX_ROWS * ns[i] * sizeof(float));
         }
     };
@@ -131,6 +136,7 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     L.ao = take((size_t)MAX_ROWS * dmax * 4);
     L.act = take((size_t)MAX_ROWS * fmax * 4 * 2);          // also the fused gate | up result
     L.apart = take((size_t)hmax * nchunks * 16 * (hdmax + 2) * 4);
+    L.rope = take((size_t)MAX_ROWS * (hdmax / 2) * sizeof(double2));
     L.P = take((size_t)(c.gamma_max + 1) * vmax * 4);
     L.Q = take((size_t)c.gamma_max * vmax * 4);
     L.cand = take((size_t)(c.gamma_max + 1) * sizeof(int2));
@@ -217,6 +223,7 @@ struct metasd_ctx {
     void* d_ao() const { return ws + lay.ao; }
     void* d_act() const { return ws + lay.act; }
     float* d_apart() const { return reinterpret_cast<float*>(ws + lay.apart); }
+    double2* d_rope() const { return reinterpret_cast<double2*>(ws + lay.rope); }
     float* d_P() const { return reinterpret_cast<float*>(ws + lay.P); }
     float* d_Q() const { return reinterpret_cast<float*>(ws + lay.Q); }
     int2* d_cand() const { return reinterpret_cast<int2*>(ws + lay.cand); }
@@ -347,6 +354,8 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
     int ns = 0, rc;
     hipLaunchKernelGGL(embed_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, h);
     LAUNCH_CHECK(c, "embed");
+    hipLaunchKernelGGL(rope_table_kernel, dim3(m), dim3(hd / 2), 0, st, pos0, hd, d.rope_theta, c->d_rope());
+    LAUNCH_CHECK(c, "rope_table");
     for (int L = 0; L < d.n_layers; ++L) {
         // h += previous FFN output (split partials); xn = norm(h)
         hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.layer_w(L, 0),
@@ -357,7 +366,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
         hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, part, ns, (size_t)m * NQKV, NQKV, pos0, H, KH,
-                           hd, d.rope_theta, (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, sizeof(T) == 2 ? 1 : 0);
+                           hd, (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, sizeof(T) == 2 ? 1 : 0);
         LAUNCH_CHECK(c, "rope_kv");
         if ((rc = attention<T>(c, M, L, pos0, m))) return rc;
         if ((rc = gemm<T>(c, c->d_ao(), DQ, m, DQ, M.layer_w(L, 4), D, nullptr, 0, nullptr, 0, nullptr, &ns))) return rc;
