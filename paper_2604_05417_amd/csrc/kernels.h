@@ -261,41 +261,55 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict_
         for (int u = 0; u < GEMM_U; ++u) w[u] = __builtin_nontemporal_load(wp + (size_t)min(gi * GEMM_U + u, nc - 1) * 64);
     };
     u32x4 wa[GEMM_U], wb[GEMM_U];
-    // the first KiBs of this wavefront's first tile are requested before the activations are staged,
-    // so the weight stream starts with the kernel and the staging latency hides behind it
     const int tfirst = tg * tpb + wave;
-    const bool any = wave < tpb && tfirst < ntiles;
-    const u32x4* wp = any ? tile_base(tfirst) : nullptr;
-    if (any) issue(wa, wp, 0);
+    const u32x4* wp = tile_base(min(tfirst, ntiles - 1));   // a wavefront without a tile still loads (unconditional requests keep the counters exact)
+    // Order of the requests (a wavefront's loads return in order): first the activations of this
+    // workgroup's slice (L2 hits, needed first), then the first KiBs of the weight stream, which
+    // stay in flight while the activations are converted and written to LDS.
     {
+        constexpr int XB = 6;                         // 8-element pieces per thread and batch
         const int total = m * nc * 4, per = nc * 4;
-        for (int base = 0; base < total; base += 256 * 4) {
-            float4 a[4], b[4];
-            int dst[4];
+        auto convert_store = [&](const float4& a, const float4& b, int idx) {
+            const int r = idx / per, c = idx - r * per;
+            const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+            bf16_t hi[8], lo[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int idx = base + u * 256 + (int)threadIdx.x;
-                dst[u] = -1;
-                if (idx < total) {
-                    const int r = idx / per, c = idx - r * per;
-                    const float* src = x + (size_t)r * ldx + (size_t)c0 * 32 + (size_t)c * 8;
-                    a[u] = *reinterpret_cast<const float4*>(src);
-                    b[u] = *reinterpret_cast<const float4*>(src + 4);
-                    dst[u] = r * rs + c;
-                }
+            for (int e = 0; e < 8; ++e) {
+                hi[e] = f2bf(v[e]);
+                lo[e] = f2bf(v[e] - bf2f(hi[e]));
+            }
+            xs[r * rs + c] = make_uint4(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]), pack_bf16x2(hi[4], hi[5]), pack_bf16x2(hi[6], hi[7]));
+            xlo[r * rs + c] = make_uint4(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(lo[4], lo[5]), pack_bf16x2(lo[6], lo[7]));
+        };
+        auto piece = [&](int idx) -> const float* {   // clamped: every load is unconditional and in range
+            const int ic = min(idx, total - 1);
+            const int r = ic / per, c = ic - r * per;
+            return x + (size_t)r * ldx + (size_t)c0 * 32 + (size_t)c * 8;
+        };
+        float4 a[XB], b[XB];
+#pragma unroll
+        for (int u = 0; u < XB; ++u) {
+            const float* src = piece((int)threadIdx.x + u * 256);
+            a[u] = *reinterpret_cast<const float4*>(src);
+            b[u] = *reinterpret_cast<const float4*>(src + 4);
+        }
+        issue(wa, wp, 0);
+#pragma unroll
+        for (int u = 0; u < XB; ++u) {
+            const int idx = (int)threadIdx.x + u * 256;
+            if (idx < total) convert_store(a[u], b[u], idx);
+        }
+        for (int base = XB * 256; base < total; base += XB * 256) {   // taller / wider blocks: further batches
+#pragma unroll
+            for (int u = 0; u < XB; ++u) {
+                const float* src = piece(base + (int)threadIdx.x + u * 256);
+                a[u] = *reinterpret_cast<const float4*>(src);
+                b[u] = *reinterpret_cast<const float4*>(src + 4);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (dst[u] < 0) continue;
-                const float v[8] = {a[u].x, a[u].y, a[u].z, a[u].w, b[u].x, b[u].y, b[u].z, b[u].w};
-                bf16_t hi[8], lo[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    hi[e] = f2bf(v[e]);
-                    lo[e] = f2bf(v[e] - bf2f(hi[e]));
-                }
-                xs[dst[u]] = make_uint4(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]), pack_bf16x2(hi[4], hi[5]), pack_bf16x2(hi[6], hi[7]));
-                xlo[dst[u]] = make_uint4(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(lo[4], lo[5]), pack_bf16x2(lo[6], lo[7]));
+            for (int u = 0; u < XB; ++u) {
+                const int idx = base + (int)threadIdx.x + u * 256;
+                if (idx < total) convert_store(a[u], b[u], idx);
             }
         }
     }
