@@ -791,9 +791,10 @@ __global__ void ffn_act_kernel(const float* __restrict__ part, int nsplit, size_
 // chunk c = 0..15 (128 data registers per lane; 512 threads leave the compiler 256 registers, with
 // 1024 threads and 128 registers the same code spills).
 //
-// Arithmetic: exp(x - max) per element in fp32 (hardware exp2); p = e_p / Z_p and q = e_q / Z_q per element in fp32 with 1/Z carried as two floats (so
-// the element error is one random rounding, not a common factor); every sum - Z_p, Z_q, the
-// residual mass, sum min(p, q), the CDF - in fp64.  The accept ratio p(d)/q(d) is formed in fp64.
+// Arithmetic: exp(x - max) per element in fp32 (hardware exp2); p = e_p / Z_p and q = e_q / Z_q per
+// element in fp32 with 1/Z carried as two floats (so the element error is one random rounding, not a
+// common factor); sums - Z_p, Z_q, the residual mass, sum min(p, q), the CDF - in fp32 inside a
+// thread (64 values) and in fp64 across threads.  The accept ratio p(d)/q(d) is formed in fp64.
 // The search for the drawn token is hierarchical (wavefront totals, then chunk totals inside the
 // one wavefront that holds the target, then a lane scan, then the four elements of that lane).
 
@@ -812,8 +813,7 @@ struct AkShared {
 // sums over the vocabulary and the accept ratio far inside their near-tie windows.  Results below
 // the normal range flush to zero.
 __device__ __forceinline__ float ak_exp(float a) {
-    const float e = __builtin_amdgcn_exp2f(a * 1.44269502162933349609375f);
-    return a > -INFINITY ? e : 0.f;
+    return __builtin_amdgcn_exp2f(a * 1.44269502162933349609375f);   // a = -inf gives 0
 }
 
 // exp((x - mx) / T): for T = 1 the fp32 difference is the correctly rounded argument; otherwise
@@ -846,23 +846,28 @@ __device__ __forceinline__ float ak_thread_max(const float (&x)[AK_CH][4]) {
     return lm;
 }
 
-// x <- exp((x - mx)/T) in place; returns this thread's fp64 sum.
+// x <- exp((x - mx)/T) in place; returns this thread's sum.  Inside a thread the 64 values are
+// added in fp32 (rounding errors are random and average out over the 512 threads: about 1e-8 of
+// the total); across threads every sum is fp64.
 template <bool UNIT_T>
 __device__ __forceinline__ double ak_exp_inplace(float (&x)[AK_CH][4], float mx, double invT) {
-    double s = 0.0;
+    float s = 0.f;
 #pragma unroll
-    for (int c = 0; c < AK_CH; ++c)
+    for (int c = 0; c < AK_CH; ++c) {
+        float s4 = 0.f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const float v = ak_expx<UNIT_T>(x[c][e], mx, invT);
             x[c][e] = v;
-            s += (double)v;
+            s4 += v;
         }
-    return s;
+        s += s4;
+    }
+    return (double)s;
 }
 
-__device__ __forceinline__ double ak_chunk_sum(const float (&w)[AK_CH][4], int c) {
-    return ((double)w[c][0] + (double)w[c][1]) + ((double)w[c][2] + (double)w[c][3]);
+__device__ __forceinline__ float ak_chunk_sum(const float (&w)[AK_CH][4], int c) {
+    return (w[c][0] + w[c][1]) + (w[c][2] + w[c][3]);
 }
 
 // Inverse CDF in ascending vocabulary order over the non-negative weights w (registers):
@@ -890,7 +895,7 @@ __device__ __forceinline__ void ak_search(const float (&w)[AK_CH][4], const doub
     double cb = base;
 #pragma unroll
     for (int c = 0; c < AK_CH; ++c) {
-        const double ct = wave_sum(ak_chunk_sum(w, c));
+        const double ct = wave_sum((double)ak_chunk_sum(w, c));
         if (ct > 0.0) clast = c;
         if (cstar < 0 && !take_last) {
             if (cb + ct > target) cstar = c;
@@ -902,7 +907,7 @@ __device__ __forceinline__ void ak_search(const float (&w)[AK_CH][4], const doub
 #pragma unroll
     for (int c = 0; c < AK_CH; ++c)
         if (c == cstar) { w4[0] = w[c][0]; w4[1] = w[c][1]; w4[2] = w[c][2]; w4[3] = w[c][3]; }
-    const double sc = ((double)w4[0] + (double)w4[1]) + ((double)w4[2] + (double)w4[3]);
+    const double sc = (double)((w4[0] + w4[1]) + (w4[2] + w4[3]));
     const double incl = wave_scan_incl(sc, lane);
     unsigned long long bal = __ballot(take_last ? (sc > 0.0) : (cb + incl > target));
     if (bal == 0ull) { take_last = true; bal = __ballot(sc > 0.0); }
@@ -1028,7 +1033,7 @@ __device__ __forceinline__ void accept_rows_body(const float* __restrict__ P, co
     }
     // ---- residual weights max(0, p - q) (kept in xq) and sum min(p, q)
     {
-        double tw = 0.0, tm = 0.0;
+        float fw = 0.f, fm = 0.f;
 #pragma unroll
         for (int c = 0; c < AK_CH; ++c) {
             float mn4 = 0.f;
@@ -1038,9 +1043,10 @@ __device__ __forceinline__ void accept_rows_body(const float* __restrict__ P, co
                 mn4 += fminf(pv, qv);
                 xq[c][e] = fmaxf(pv - qv, 0.f);
             }
-            tw += ak_chunk_sum(xq, c);
-            tm += (double)mn4;
+            fw += ak_chunk_sum(xq, c);
+            fm += mn4;
         }
+        double tw = (double)fw, tm = (double)fm;
         tw = wave_sum(tw);
         tm = wave_sum(tm);
         if (lane == 0) { sm.dw[0][wave] = tw; sm.dw[1][wave] = tm; }
