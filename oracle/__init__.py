@@ -17,6 +17,9 @@ What pins each function (all in ``tests/test_oracle_*.py``, CPU only):
                     block-vs-single-row consistency, RoPE closed forms on head_dim 2 and 4.
 * ``generate``    - greedy speculative decoding equals target-only greedy decoding token for
                     token (Alg. 3 is lossless); accounting identity B = tau + sum N_acc.
+* ``policies``    - discounted / sliding-window UCB, sequential halving, EXP3, uniform random (the
+                    paper's appendix "Extensions"): hand-worked runs in ``tests/golden/policies_hand.txt``,
+                    reductions to Alg. 2, EXP3 closed forms (``tests/test_oracle_policies.py``).
 * ``philox``      - parity unpinned against the published generator's known-answer vectors;
                     structural and statistical tests only.
 """
@@ -313,3 +316,4 @@ def reward_bd(bd: np.ndarray) -> float:
 
 
 from .loop import SdState, sd_round, generate, ar_decode  # noqa: E402,F401
+from . import policies  # noqa: E402,F401
