@@ -55,6 +55,16 @@ extern "C" {
 #define METASD_BF16 1
 #define METASD_REWARD_BE 0 /* block efficiency  N_acc / N_max */
 #define METASD_REWARD_BD 1 /* block divergence, Def. 2 */
+
+/* Drafter-selection policy.  UCB is Alg. 2 (MetaSD-UCB); the others are the paper's appendix
+ * "Extensions" (switching costs, non-stationary rewards) and its EXP3 / random baselines. */
+#define METASD_POLICY_UCB 0    /* Alg. 2 */
+#define METASD_POLICY_DUCB 1   /* discounted UCB: policy_param = discount in (0, 1] */
+#define METASD_POLICY_SWUCB 2  /* sliding-window UCB: policy_window = window length in rounds (>= 1) */
+#define METASD_POLICY_EXP3 3   /* EXP3: policy_param = mixing gamma in (0, 1]; draws from Philox stream 3 */
+#define METASD_POLICY_SH 4     /* sequential halving over policy_window rounds, then the survivor for good
+                                  (pure exploration-then-commit with the exploration budget in rounds) */
+#define METASD_POLICY_RANDOM 5 /* uniform random arm; Philox stream 3 */
 #define METASD_MAX_GAMMA 15 /* a verification block is gamma+1 <= 16 rows */
 #define METASD_MAX_K 64
 
@@ -76,6 +86,9 @@ typedef struct {
     int32_t reward;     /* METASD_REWARD_BE | METASD_REWARD_BD (used by metasd_bandit_update) */
     double ucb_beta;    /* exploration strength beta of Alg. 2 */
     uint64_t seed;      /* Philox key of all uniforms */
+    int32_t policy;        /* METASD_POLICY_*; 0 (UCB) for a zero-initialised tail */
+    int32_t policy_window; /* SWUCB: window; SH: exploration budget in rounds; else ignored */
+    double policy_param;   /* DUCB: discount; EXP3: gamma; else ignored */
 } metasd_config;
 
 /* ---- sizes -------------------------------------------------------------------------------- */
@@ -125,14 +138,20 @@ int32_t metasd_swap_weight(metasd_ctx*, int32_t model, int32_t index, const void
 
 /* ---- bandit (host, fp64; Alg. 2) ------------------------------------------------------------ */
 
-/* Arm for the next round: arms 0..K-1 once each in index order, afterwards
- * argmax_i mu_i + beta * sqrt(2 ln t / n_i), t = completed rounds, lowest index on ties. */
+/* Arm for the next round.  UCB (Alg. 2): arms 0..K-1 once each in index order, afterwards
+ * argmax_i mu_i + beta * sqrt(2 ln t / n_i), t = completed rounds, lowest index on ties.
+ * DUCB / SWUCB: the same index on discounted / windowed estimates (an arm without a pull in the
+ * window is tried first).  EXP3: draw from (1 - g) w_i / sum w + g / K.  SH: the surviving arms in
+ * turn, each floor(T / (|S| ceil(log2 K))) (at least 1) times per phase, the better half kept.
+ * Call once per round: EXP3 keeps the probabilities of the latest call for the update. */
 int32_t metasd_bandit_select(metasd_ctx*, int32_t seq, int32_t* k_out);
 /* Feed back the round's reward to arm k: BE reward n_acc / gamma, or, when the context was
  * created with METASD_REWARD_BD, bd_reward (the value metasd_accept reported).  mu_k becomes
- * (mu_k n_k + r)/(n_k + 1), n_k and t advance.  Errors: INVALID. */
+ * (mu_k n_k + r)/(n_k + 1), n_k and t advance (UCB; the other policies update as their
+ * algorithms state).  Errors: INVALID. */
 int32_t metasd_bandit_update(metasd_ctx*, int32_t seq, int32_t k, int32_t n_acc, int32_t gamma, double bd_reward);
-/* Copy out mu[K], n[K], t (any pointer may be NULL). */
+/* Copy out mu[K], n[K], t (any pointer may be NULL): the estimates and counts the policy's index
+ * uses (UCB, DUCB, SWUCB) or the plain per-arm mean reward and pull count (EXP3, SH, RANDOM). */
 int32_t metasd_bandit_state(const metasd_ctx*, int32_t seq, double* mu, int32_t* n, int32_t* t);
 
 /* ---- one speculative-sampling round (Alg. 3) -------------------------------------------------- */

@@ -31,7 +31,8 @@ class _Desc(C.Structure):
 
 class _Config(C.Structure):
     _fields_ = [("K", C.c_int32), ("gamma_max", C.c_int32), ("batch", C.c_int32), ("max_ctx", C.c_int32),
-                ("temperature", C.c_float), ("reward", C.c_int32), ("ucb_beta", C.c_double), ("seed", C.c_uint64)]
+                ("temperature", C.c_float), ("reward", C.c_int32), ("ucb_beta", C.c_double), ("seed", C.c_uint64),
+                ("policy", C.c_int32), ("policy_window", C.c_int32), ("policy_param", C.c_double)]
 
 
 def lib_path() -> str:
@@ -115,11 +116,15 @@ def pack_weight(w: torch.Tensor, rope_head_dim: int = 0, stream=None) -> torch.T
     return out
 
 
+POLICIES = {"ucb": 0, "ducb": 1, "swucb": 2, "exp3": 3, "sh": 4, "random": 5}
+
+
 class MetaSD:
     """One MetaSD context: a target, K drafters, their KV caches and the workspace (all torch-owned)."""
 
     def __init__(self, target, drafters, gamma_max: int, max_ctx: int, temperature: float, seed: int,
-                 ucb_beta: float = 1.0, reward: str = "BE", device: str = "cuda:0"):
+                 ucb_beta: float = 1.0, reward: str = "BE", device: str = "cuda:0", policy: str = "ucb",
+                 policy_param: float = 0.0, policy_window: int = 0):
         _require_gpu()
         self.L = load_library()
         self.device = torch.device(device)
@@ -131,7 +136,8 @@ class MetaSD:
         tdesc, tw = target
         self.tdesc = dict(tdesc)
         self.ddescs = [dict(d) for d, _ in drafters]
-        self.cfg = _Config(self.K, gamma_max, 1, max_ctx, temperature, 1 if reward == "BD" else 0, ucb_beta, seed)
+        self.cfg = _Config(self.K, gamma_max, 1, max_ctx, temperature, 1 if reward == "BD" else 0, ucb_beta, seed,
+                           POLICIES[policy], policy_window, policy_param)
         self._tdesc_c = _desc(tdesc)
         self._ddesc_c = (_Desc * self.K)(*[_desc(d) for d in self.ddescs])
         self._tw = self._table(tdesc, tw)

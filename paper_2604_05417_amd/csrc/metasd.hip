@@ -152,12 +152,147 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     return L;
 }
 
+// uniform in [0,1) at Philox counter (seq, round, pos, stream): the host twin of philox_uniform
+float host_philox_uniform(uint64_t seed, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {
+    uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c0 = n0; c1 = (uint32_t)p1; c2 = n2; c3 = (uint32_t)p0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return (float)(c0 >> 8) * (1.0f / 16777216.0f);
+}
+
+// Drafter-selection state of one sequence.  UCB is Alg. 2; the others are the algorithms of the
+// paper's appendix on switching costs and non-stationary rewards, and its EXP3 / random baselines.
 struct Bandit {
-    int K = 0, t = 0;
-    double beta = 1.0;
-    std::vector<double> mu;
-    std::vector<int> n;
-    void reset() { t = 0; std::fill(mu.begin(), mu.end(), 0.0); std::fill(n.begin(), n.end(), 0); }
+    int K = 0, t = 0, policy = METASD_POLICY_UCB, window = 0;
+    double beta = 1.0, param = 1.0;
+    uint64_t seed = 0;
+    std::vector<double> mu;     // reported estimate per arm
+    std::vector<int> n;         // reported count per arm
+    std::vector<double> aux;    // D-UCB: discounted reward sums; EXP3: weights; SH: reward sums of the phase
+    std::vector<int> last;      // D-UCB: round of the arm's latest pull
+    std::vector<double> prob;   // EXP3: probabilities of the latest select
+    std::vector<std::pair<int, double>> recent;   // SW-UCB: (arm, reward) of the rounds in the window, oldest first
+    std::vector<int> alive;     // SH: surviving arms, ascending
+    int sh_phases = 0, sh_pos = 0;
+
+    void init(const metasd_config& c) {
+        K = c.K; beta = c.ucb_beta; policy = c.policy; param = c.policy_param; window = c.policy_window; seed = c.seed;
+        reset();
+    }
+    void reset() {
+        t = 0;
+        mu.assign(K, 0.0); n.assign(K, 0);
+        aux.assign(K, policy == METASD_POLICY_EXP3 ? 1.0 : 0.0);
+        last.assign(K, 0);
+        prob.assign(K, 1.0 / std::max(K, 1));
+        recent.clear();
+        alive.resize(K);
+        for (int i = 0; i < K; ++i) alive[i] = i;
+        sh_phases = 0;
+        for (int v = 1; v < K; v <<= 1) ++sh_phases;   // ceil(log2 K)
+        sh_pos = 0;
+    }
+    int ucb_argmax() const {
+        int best = 0;
+        double bs = -INFINITY;
+        for (int i = 0; i < K; ++i) {
+            const double s = mu[i] + beta * std::sqrt(2.0 * std::log((double)t) / (double)n[i]);
+            if (s > bs) { bs = s; best = i; }
+        }
+        return best;
+    }
+    static int draw(const std::vector<double>& p, double u) {   // first arm whose cumulative probability exceeds u
+        double c = 0.0;
+        for (size_t i = 0; i < p.size(); ++i) {
+            c += p[i];
+            if (c > u) return (int)i;
+        }
+        return (int)p.size() - 1;
+    }
+    int sh_pulls() const { return std::max(1, window / ((int)alive.size() * std::max(sh_phases, 1))); }
+
+    int select() {
+        switch (policy) {
+            case METASD_POLICY_UCB:
+            case METASD_POLICY_DUCB:
+                return t < K ? t : ucb_argmax();
+            case METASD_POLICY_SWUCB:
+                if (t < K) return t;
+                for (int i = 0; i < K; ++i)
+                    if (n[i] == 0) return i;            // no pull left in the window: no estimate, try it
+                return ucb_argmax();
+            case METASD_POLICY_EXP3: {
+                double tot = 0.0;
+                for (double w : aux) tot += w;
+                for (int i = 0; i < K; ++i) prob[i] = (1.0 - param) * (aux[i] / tot) + param / (double)K;
+                return draw(prob, (double)host_philox_uniform(seed, 0u, (uint32_t)t, 0u, 3u));
+            }
+            case METASD_POLICY_SH:
+                return alive.size() == 1 ? alive[0] : alive[sh_pos / sh_pulls()];
+            default: {                                   // METASD_POLICY_RANDOM
+                std::vector<double> p(K, 1.0 / (double)K);
+                return draw(p, (double)host_philox_uniform(seed, 0u, (uint32_t)t, 0u, 3u));
+            }
+        }
+    }
+
+    void plain_mean(int k, double r) { mu[k] = (mu[k] * (double)n[k] + r) / (double)(n[k] + 1); n[k] += 1; }
+
+    void update(int k, double r) {
+        switch (policy) {
+            case METASD_POLICY_DUCB:
+                // discounted sum carried from the arm's latest pull: S <- S gamma^(t - t_last) + r
+                aux[k] = (n[k] > 0 ? aux[k] * std::pow(param, (double)(t - last[k])) : 0.0) + r;
+                last[k] = t;
+                n[k] += 1;
+                mu[k] = aux[k] / (double)n[k];
+                break;
+            case METASD_POLICY_SWUCB: {
+                recent.emplace_back(k, r);
+                if ((int)recent.size() > window) recent.erase(recent.begin());
+                std::vector<double> s(K, 0.0);
+                std::fill(n.begin(), n.end(), 0);
+                for (const auto& e : recent) { s[e.first] += e.second; n[e.first] += 1; }
+                for (int i = 0; i < K; ++i) mu[i] = n[i] ? s[i] / (double)n[i] : 0.0;
+                break;
+            }
+            case METASD_POLICY_EXP3: {
+                aux[k] *= std::exp(param * (r / prob[k]) / (double)K);
+                const double big = *std::max_element(aux.begin(), aux.end());
+                if (big > 1e100) {                       // exact power-of-two rescale, probabilities unchanged
+                    int e;
+                    std::frexp(big, &e);
+                    for (double& w : aux) w = std::ldexp(w, -e);
+                }
+                plain_mean(k, r);
+                break;
+            }
+            case METASD_POLICY_SH:
+                plain_mean(k, r);
+                if (alive.size() > 1) {
+                    aux[k] += r;
+                    if (++sh_pos == (int)alive.size() * sh_pulls()) {   // phase over: keep the better half
+                        std::vector<int> order = alive;
+                        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return aux[a] > aux[b]; });
+                        order.resize((alive.size() + 1) / 2);
+                        std::sort(order.begin(), order.end());
+                        alive = order;
+                        std::fill(aux.begin(), aux.end(), 0.0);
+                        sh_pos = 0;
+                    }
+                }
+                break;
+            default:                                     // UCB (Alg. 2 mean update), RANDOM
+                plain_mean(k, r);
+                break;
+        }
+        t += 1;
+    }
 };
 
 struct HostResult {   // pinned host mirror of one accept
@@ -512,6 +647,16 @@ static int check_config(const metasd_config* cfg, const metasd_model_desc* targe
     if (!(cfg->temperature >= 0.f)) return fail_global(METASD_E_INVALID, "temperature must be >= 0");
     if (cfg->reward != METASD_REWARD_BE && cfg->reward != METASD_REWARD_BD) return fail_global(METASD_E_INVALID, "reward");
     if (!(cfg->ucb_beta >= 0.0)) return fail_global(METASD_E_INVALID, "ucb_beta must be >= 0");
+    switch (cfg->policy) {
+        case METASD_POLICY_UCB: case METASD_POLICY_RANDOM: break;
+        case METASD_POLICY_DUCB: case METASD_POLICY_EXP3:
+            if (!(cfg->policy_param > 0.0 && cfg->policy_param <= 1.0)) return fail_global(METASD_E_INVALID, "policy_param must be in (0, 1] for this policy");
+            break;
+        case METASD_POLICY_SWUCB: case METASD_POLICY_SH:
+            if (cfg->policy_window < 1) return fail_global(METASD_E_INVALID, "policy_window must be >= 1 for this policy");
+            break;
+        default: return fail_global(METASD_E_INVALID, "unknown policy %d", cfg->policy);
+    }
     char buf[256];
     if (const char* e = check_model(*target, "target", buf, sizeof buf)) return fail_global(METASD_E_INVALID, "%s", e);
     for (int k = 0; k < cfg->K; ++k) {
@@ -587,10 +732,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
     }
     if (rc) { delete c; return rc; }
     c->hist.assign(cfg->max_ctx, 0);
-    c->bandit.K = cfg->K;
-    c->bandit.beta = cfg->ucb_beta;
-    c->bandit.mu.assign(cfg->K, 0.0);
-    c->bandit.n.assign(cfg->K, 0);
+    c->bandit.init(*cfg);
     hipError_t e = hipHostMalloc((void**)&c->hres, sizeof(HostResult), hipHostMallocDefault);
     if (e != hipSuccess) {
         rc = fail_global(METASD_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e));
@@ -683,15 +825,7 @@ int32_t metasd_swap_weight(metasd_ctx* c, int32_t model, int32_t index, const vo
 int32_t metasd_bandit_select(metasd_ctx* c, int32_t seq, int32_t* k_out) {
     if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
     if (seq != 0 || !k_out) return c->fail(METASD_E_INVALID, "bandit_select: bad argument");
-    const Bandit& b = c->bandit;
-    if (b.t < b.K) { *k_out = b.t; return METASD_OK; }
-    int best = 0;
-    double bs = -INFINITY;
-    for (int i = 0; i < b.K; ++i) {
-        const double s = b.mu[i] + b.beta * std::sqrt(2.0 * std::log((double)b.t) / (double)b.n[i]);
-        if (s > bs) { bs = s; best = i; }
-    }
-    *k_out = best;
+    *k_out = c->bandit.select();
     return METASD_OK;
 }
 
@@ -703,10 +837,7 @@ int32_t metasd_bandit_update(metasd_ctx* c, int32_t seq, int32_t k, int32_t n_ac
         if (!(bd_reward >= 0.0 && bd_reward <= 1.0 + 1e-9)) return c->fail(METASD_E_INVALID, "bandit_update: BD reward %g not in [0,1]", bd_reward);
         r = bd_reward;
     }
-    Bandit& b = c->bandit;
-    b.mu[k] = (b.mu[k] * (double)b.n[k] + r) / (double)(b.n[k] + 1);
-    b.n[k] += 1;
-    b.t += 1;
+    c->bandit.update(k, r);
     return METASD_OK;
 }
 
