@@ -231,11 +231,36 @@ constexpr int GEMM_U = 8;  // tiles in flight per wavefront (8 KiB)
 
 __device__ __forceinline__ uint32_t pack_bf16x2(bf16_t lo, bf16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
 
+// Optional prologues for short, narrow blocks (drafter steps: m <= 4 rows, d_model <= 1024), where the
+// split-K partials of the previous GEMM are few enough that every workgroup can afford to consume them
+// itself; each one removes a kernel from the dependent chain of a layer:
+//   PRO_NORM     x = RMSNorm(h_in + sum of the previous GEMM's partials) * gain.  Every workgroup forms
+//                the full rows (it needs their sum of squares), keeps them in LDS, and stages its
+//                slice; workgroup 0 also writes the rows to h_out (a second buffer: the others still
+//                read h_in).  Replaces addnorm_kernel.
+//   PRO_ACT      x = SiLU(gate) * up or GELU(up) from the partials of the gate | up GEMM.  Replaces ffn_act_kernel.
+//   PRO_COMBINE  x = attention output merged from the per-chunk partials.  Replaces attn_combine_kernel.
+enum { PRO_PLAIN = 0, PRO_NORM = 1, PRO_ACT = 2, PRO_COMBINE = 3 };
+
+struct GemmPro {
+    const float* src;      // NORM: h_in [m][K];  ACT: partials [s][m][(1|2) K];  COMBINE: attention partials
+    const float* part;     // NORM: partials [s][m][K] of the previous GEMM (ns may be 0)
+    float* h_out;          // NORM: updated residual stream [m][K]
+    const bf16_t* gain;    // NORM
+    size_t sstride;        // NORM / ACT: split stride of the partials (floats)
+    int ns;                // NORM / ACT: number of partials
+    float eps;             // NORM
+    int act;               // ACT: 1 SwiGLU, 0 GELU
+    int nchunks, hd;       // COMBINE: attention chunks, head dim
+};
+
+template <int PRO>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict__ x, int ldx, int m, int K,
                                                         const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
                                                         const bf16_t* __restrict__ W2, int t0, int t1, int ntiles,
-                                                        float* __restrict__ out, int N, int ksplit, int cps, int tpb) {
-    extern __shared__ uint4 xs[];   // [2 (hi, lo)][m][rs]
+                                                        float* __restrict__ out, int N, int ksplit, int cps, int tpb,
+                                                        GemmPro pro) {
+    extern __shared__ uint4 xs[];   // [2 (hi, lo)][m][rs]  (+ [m][K] floats for PRO_NORM)
     const int kchunks = K >> 5;
     const int ks = blockIdx.x % ksplit, tg = blockIdx.x / ksplit;
     const int c0 = ks * cps;
@@ -263,24 +288,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict_
     u32x4 wa[GEMM_U], wb[GEMM_U];
     const int tfirst = tg * tpb + wave;
     const u32x4* wp = tile_base(min(tfirst, ntiles - 1));   // a wavefront without a tile still loads (unconditional requests keep the counters exact)
-    // Order of the requests (a wavefront's loads return in order): first the activations of this
-    // workgroup's slice (L2 hits, needed first), then the first KiBs of the weight stream, which
-    // stay in flight while the activations are converted and written to LDS.
-    {
-        constexpr int XB = 6;                         // 8-element pieces per thread and batch
-        const int total = m * nc * 4, per = nc * 4;
-        auto convert_store = [&](const float4& a, const float4& b, int idx) {
-            const int r = idx / per, c = idx - r * per;
-            const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-            bf16_t hi[8], lo[8];
+    const int total = m * nc * 4, per = nc * 4;
+    auto convert_store = [&](const float (&v)[8], int idx) {
+        const int r = idx / per, c = idx - r * per;
+        bf16_t hi[8], lo[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                hi[e] = f2bf(v[e]);
-                lo[e] = f2bf(v[e] - bf2f(hi[e]));
-            }
-            xs[r * rs + c] = make_uint4(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]), pack_bf16x2(hi[4], hi[5]), pack_bf16x2(hi[6], hi[7]));
-            xlo[r * rs + c] = make_uint4(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(lo[4], lo[5]), pack_bf16x2(lo[6], lo[7]));
-        };
+        for (int e = 0; e < 8; ++e) {
+            hi[e] = f2bf(v[e]);
+            lo[e] = f2bf(v[e] - bf2f(hi[e]));
+        }
+        xs[r * rs + c] = make_uint4(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]), pack_bf16x2(hi[4], hi[5]), pack_bf16x2(hi[6], hi[7]));
+        xlo[r * rs + c] = make_uint4(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(lo[4], lo[5]), pack_bf16x2(lo[6], lo[7]));
+    };
+    if constexpr (PRO == PRO_PLAIN) {
+        // Order of the requests (a wavefront's loads return in order): first the activations of this
+        // workgroup's slice (L2 hits, needed first), then the first KiBs of the weight stream, which
+        // stay in flight while the activations are converted and written to LDS.
+        constexpr int XB = 6;                         // 8-element pieces per thread and batch
         auto piece = [&](int idx) -> const float* {   // clamped: every load is unconditional and in range
             const int ic = min(idx, total - 1);
             const int r = ic / per, c = ic - r * per;
@@ -297,7 +321,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict_
 #pragma unroll
         for (int u = 0; u < XB; ++u) {
             const int idx = (int)threadIdx.x + u * 256;
-            if (idx < total) convert_store(a[u], b[u], idx);
+            const float v[8] = {a[u].x, a[u].y, a[u].z, a[u].w, b[u].x, b[u].y, b[u].z, b[u].w};
+            if (idx < total) convert_store(v, idx);
         }
         for (int base = XB * 256; base < total; base += XB * 256) {   // taller / wider blocks: further batches
 #pragma unroll
@@ -309,8 +334,141 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict_
 #pragma unroll
             for (int u = 0; u < XB; ++u) {
                 const int idx = base + (int)threadIdx.x + u * 256;
-                if (idx < total) convert_store(a[u], b[u], idx);
+                const float v[8] = {a[u].x, a[u].y, a[u].z, a[u].w, b[u].x, b[u].y, b[u].z, b[u].w};
+                if (idx < total) convert_store(v, idx);
             }
+        }
+    } else if constexpr (PRO == PRO_NORM) {
+        float* vrow = reinterpret_cast<float*>(xs + 2 * m * rs);     // [m][K] updated residual rows
+        float* red = vrow + (size_t)m * K;                           // [m][4] per-wavefront sums of squares
+        for (int r = 0; r < m; ++r) {
+            float ss = 0.f;
+            for (int i = (int)threadIdx.x * 4; i < K; i += 1024) {
+                float4 v = *reinterpret_cast<const float4*>(pro.src + (size_t)r * K + i);
+                if (pro.ns > 0) {
+                    float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
+                    for (int s0 = 0; s0 < pro.ns; s0 += 8) {      // eight partials in flight, added in the order s = 0, 1, ..
+                        float4 pp[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            pp[u] = (s0 + u < pro.ns) ? *reinterpret_cast<const float4*>(pro.part + (size_t)(s0 + u) * pro.sstride + (size_t)r * K + i)
+                                                      : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            if (s0 + u < pro.ns) { y.x += pp[u].x; y.y += pp[u].y; y.z += pp[u].z; y.w += pp[u].w; }
+                    }
+                    v.x += y.x; v.y += y.y; v.z += y.z; v.w += y.w;
+                }
+                *reinterpret_cast<float4*>(vrow + (size_t)r * K + i) = v;
+                ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+            }
+            ss = wave_sum(ss);
+            if (lane == 0) red[r * 4 + wave] = ss;
+        }
+        issue(wa, wp, 0);
+        __syncthreads();
+        if (blockIdx.x == 0)
+            for (int i = (int)threadIdx.x * 4; i < m * K; i += 1024)
+                *reinterpret_cast<float4*>(pro.h_out + i) = *reinterpret_cast<const float4*>(vrow + i);
+        for (int idx = (int)threadIdx.x; idx < total; idx += 256) {
+            const int r = idx / per, c = idx - r * per, k0 = c0 * 32 + c * 8;
+            const float tot = (red[r * 4] + red[r * 4 + 1]) + (red[r * 4 + 2] + red[r * 4 + 3]);
+            const float inv = 1.0f / sqrtf(tot / (float)K + pro.eps);
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = vrow[(size_t)r * K + k0 + e] * inv * bf2f(pro.gain[k0 + e]);
+            convert_store(v, idx);
+        }
+    } else if constexpr (PRO == PRO_ACT) {
+        issue(wa, wp, 0);
+        const int ldp = (pro.act == 1 ? 2 : 1) * K;
+        for (int idx = (int)threadIdx.x; idx < total; idx += 256) {
+            const int r = idx / per, c = idx - r * per, k0 = c0 * 32 + c * 8;
+            const float* pg = pro.src + (size_t)r * ldp + k0;
+            float gsum[8], usum[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) gsum[e] = usum[e] = 0.f;
+            for (int s0 = 0; s0 < pro.ns; s0 += 2) {              // two partials in flight, added in order
+                float4 ga[2], gb[2], ua[2], ub[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const bool ok = s0 + u < pro.ns;
+                    const float* q = pg + (size_t)(ok ? s0 + u : 0) * pro.sstride;
+                    ga[u] = *reinterpret_cast<const float4*>(q);
+                    gb[u] = *reinterpret_cast<const float4*>(q + 4);
+                    if (pro.act == 1) { ua[u] = *reinterpret_cast<const float4*>(q + K); ub[u] = *reinterpret_cast<const float4*>(q + K + 4); }
+                    else { ua[u] = make_float4(0.f, 0.f, 0.f, 0.f); ub[u] = ua[u]; }
+                }
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+                    if (s0 + u < pro.ns) {
+                        gsum[0] += ga[u].x; gsum[1] += ga[u].y; gsum[2] += ga[u].z; gsum[3] += ga[u].w;
+                        gsum[4] += gb[u].x; gsum[5] += gb[u].y; gsum[6] += gb[u].z; gsum[7] += gb[u].w;
+                        usum[0] += ua[u].x; usum[1] += ua[u].y; usum[2] += ua[u].z; usum[3] += ua[u].w;
+                        usum[4] += ub[u].x; usum[5] += ub[u].y; usum[6] += ub[u].z; usum[7] += ub[u].w;
+                    }
+            }
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                v[e] = pro.act == 1 ? gsum[e] / (1.0f + expf(-gsum[e])) * usum[e] : 0.5f * gsum[e] * (1.0f + erff(gsum[e] * 0.70710678118654752f));
+            convert_store(v, idx);
+        }
+    } else {   // PRO_COMBINE: eight threads per 8-element piece, each merging every eighth chunk
+        issue(wa, wp, 0);
+        const size_t cs = (size_t)16 * (pro.hd + 2);
+        const int sub = (int)threadIdx.x & 7;
+        for (int ib = 0; ib < total; ib += 32) {
+            const int idx = ib + ((int)threadIdx.x >> 3), ic = min(idx, total - 1);
+            const int r = ic / per, c = ic - r * per, k0 = c0 * 32 + c * 8;
+            const int head = k0 / pro.hd, col = k0 - head * pro.hd;
+            const float* base = pro.src + ((size_t)head * pro.nchunks * 16 + r) * (pro.hd + 2);
+            float mc[4], lc[4];
+            float2 oc[4][4];
+            float M = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {                          // chunks sub, sub + 8, .. (up to 32 chunks per pass)
+                const int ch = sub + 8 * u;
+                const bool ok = ch < pro.nchunks;
+                const float* rec = base + (size_t)(ok ? ch : 0) * cs;
+                mc[u] = ok ? rec[pro.hd] : -INFINITY;
+                lc[u] = ok ? rec[pro.hd + 1] : 0.f;
+                const float2* op = reinterpret_cast<const float2*>(rec + col);
+                oc[u][0] = op[0]; oc[u][1] = op[1]; oc[u][2] = op[2]; oc[u][3] = op[3];
+                M = fmaxf(M, mc[u]);
+            }
+            for (int ch0 = 32; ch0 < pro.nchunks; ch0 += 8)        // longer contexts: the maximum needs every chunk
+                if (ch0 + sub < pro.nchunks) M = fmaxf(M, base[(size_t)(ch0 + sub) * cs + pro.hd]);
+            M = fmaxf(M, __shfl_xor(M, 1, 64));
+            M = fmaxf(M, __shfl_xor(M, 2, 64));
+            M = fmaxf(M, __shfl_xor(M, 4, 64));
+            float Lsum = 0.f, o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = 0.f;
+            auto merge = [&](float mcv, float lcv, const float2 (&ov)[4]) {
+                const float w = (mcv == -INFINITY) ? 0.f : expf(mcv - M);
+                Lsum += lcv * w;
+                o[0] += ov[0].x * w; o[1] += ov[0].y * w; o[2] += ov[1].x * w; o[3] += ov[1].y * w;
+                o[4] += ov[2].x * w; o[5] += ov[2].y * w; o[6] += ov[3].x * w; o[7] += ov[3].y * w;
+            };
+#pragma unroll
+            for (int u = 0; u < 4; ++u) merge(mc[u], lc[u], oc[u]);
+            for (int ch = 32 + sub; ch < pro.nchunks; ch += 8) {
+                const float* rec = base + (size_t)ch * cs;
+                const float2* op = reinterpret_cast<const float2*>(rec + col);
+                const float2 ov[4] = {op[0], op[1], op[2], op[3]};
+                merge(rec[pro.hd], rec[pro.hd + 1], ov);
+            }
+#pragma unroll
+            for (int sh = 1; sh < 8; sh <<= 1) {
+                Lsum += __shfl_xor(Lsum, sh, 64);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] += __shfl_xor(o[e], sh, 64);
+            }
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = o[e] / Lsum;
+            if (sub == 0 && idx < total) convert_store(v, idx);
         }
     }
     __syncthreads();

@@ -66,7 +66,7 @@ int ks_cap() { static const int v = std::max(1, std::min(env_int("METASD_GEMM_KS
 Split choose_split(int m, int ntiles, int kchunks) {
     static const int target_units = env_int("METASD_GEMM_UNITS", 3072), align = std::max(1, env_int("METASD_GEMM_ALIGN", 8));
     const int cps_max = std::max(1, ((LDS_BUDGET / 32 / m) - 1) / 4);   // two bf16 terms per activation
-    int want = (target_units + ntiles / 2) / ntiles;              // aim for about 3072 wavefront work units
+    int want = target_units / ntiles;                             // aim for about 3072 wavefront work units, never fewer tiles' worth
     want = std::max(1, std::min(want, ks_cap()));
     want = std::min(want, std::max(1, kchunks / 8));              // at least 8 chunks per slice
     int ks = std::max(want, (kchunks + cps_max - 1) / cps_max);   // LDS capacity wins
@@ -102,7 +102,7 @@ const char* check_model(const metasd_model_desc& d, const char* who, char* buf, 
 
 // Workspace layout shared by metasd_workspace_bytes and metasd_create.
 struct Layout {
-    size_t hist, h, xn, part, q, ao, act, apart, rope, P, Q, cand, bd, res, draft, bar, tables, table_stride, total;
+    size_t hist, h, h2, xn, part, part2, q, ao, act, apart, rope, P, Q, cand, bd, res, draft, bar, tables, table_stride, total;
 };
 
 Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const metasd_model_desc* dr) {
@@ -130,8 +130,10 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes); return at; };
     L.hist = take((size_t)c.max_ctx * 4);
     L.h = take((size_t)MAX_ROWS * dmax * 4);
+    L.h2 = take((size_t)MAX_ROWS * dmax * 4);
     L.xn = take((size_t)MAX_ROWS * dmax * 4);
     L.part = take(partmax);
+    L.part2 = take(partmax);
     L.q = take((size_t)MAX_ROWS * dmax * 4);
     L.ao = take((size_t)MAX_ROWS * dmax * 4);
     L.act = take((size_t)MAX_ROWS * fmax * 4 * 2);          // also the fused gate | up result
@@ -328,6 +330,7 @@ struct metasd_ctx {
     bool prof_on = false;
     bool tlog = false;
     bool persistent = false;         // bf16 models run the one-launch forward (cooperative launch available)
+    bool fuse_small = true;          // short blocks of narrow bf16 models use the GEMMs with fused prologues (METASD_FUSE_SMALL=0: off)
     int n_cu = 0;
     std::vector<ProfRec> prof;       // event pool
     size_t prof_used = 0;
@@ -354,6 +357,8 @@ struct metasd_ctx {
     float* d_h() const { return reinterpret_cast<float*>(ws + lay.h); }
     void* d_xn() const { return ws + lay.xn; }
     float* d_part() const { return reinterpret_cast<float*>(ws + lay.part); }
+    float* d_part_pp(int i) const { return reinterpret_cast<float*>(ws + (i ? lay.part2 : lay.part)); }
+    float* d_h_pp(int i) const { return reinterpret_cast<float*>(ws + (i ? lay.h2 : lay.h)); }
     void* d_q() const { return ws + lay.q; }
     void* d_ao() const { return ws + lay.ao; }
     void* d_act() const { return ws + lay.act; }
@@ -421,14 +426,41 @@ int gemm<bf16_t>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void
     const int groups = (ntiles + s.tpb - 1) / s.tpb;
     // algorithmic bytes: every weight once, the activations once, the result once
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
-    hipExtLaunchKernelGGL(gemm_bf16_kernel, dim3(groups * s.ksplit), dim3(256), (uint32_t)s.lds, c->stream, pr ? pr->a : nullptr,
-                          pr ? pr->b : nullptr, 0u, (const float*)x, ldx, m, K, (const bf16_t*)W0, (const bf16_t*)W1,
-                          (const bf16_t*)W2, n0 / 16, (n0 + n1) / 16, ntiles, out, N, s.ksplit, s.cps, s.tpb);
+    hipExtLaunchKernelGGL(gemm_bf16_kernel<PRO_PLAIN>, dim3(groups * s.ksplit), dim3(256), (uint32_t)s.lds, c->stream,
+                          pr ? pr->a : nullptr, pr ? pr->b : nullptr, 0u, (const float*)x, ldx, m, K, (const bf16_t*)W0,
+                          (const bf16_t*)W1, (const bf16_t*)W2, n0 / 16, (n0 + n1) / 16, ntiles, out, N, s.ksplit, s.cps, s.tpb,
+                          GemmPro{});
     LAUNCH_CHECK(c, "gemm_bf16");
     if (direct_out && s.ksplit > 1) {
         const size_t n = (size_t)m * N;
         hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->d_part(),
                            s.ksplit, n, n, direct_out);
+        LAUNCH_CHECK(c, "sum_partials");
+    }
+    *nsplit_out = direct_out ? 0 : s.ksplit;
+    return 0;
+}
+
+// bf16 GEMM whose prologue forms the activations itself (PRO_NORM / PRO_ACT / PRO_COMBINE, see kernels.h).
+// Partials go to part_out (split stride m*N), or, when direct_out is given and no split is needed, there.
+template <int PRO>
+int gemm_pro(metasd_ctx* c, const GemmPro& pro, int m, int K, const void* W0, int n0, const void* W1, int n1, const void* W2,
+             int n2, float* part_out, float* direct_out, int* nsplit_out) {
+    const int N = n0 + n1 + n2;
+    const int ntiles = N / 16, kchunks = K / 32;
+    const Split s = choose_split(m, ntiles, kchunks);
+    float* out = (direct_out && s.ksplit == 1) ? direct_out : part_out;
+    const int groups = (ntiles + s.tpb - 1) / s.tpb;
+    const size_t lds = s.lds + (PRO == PRO_NORM ? (size_t)m * K * 4 + (size_t)m * 16 : 0);
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
+    hipExtLaunchKernelGGL(gemm_bf16_kernel<PRO>, dim3(groups * s.ksplit), dim3(256), (uint32_t)lds, c->stream, pr ? pr->a : nullptr,
+                          pr ? pr->b : nullptr, 0u, (const float*)nullptr, K, m, K, (const bf16_t*)W0, (const bf16_t*)W1,
+                          (const bf16_t*)W2, n0 / 16, (n0 + n1) / 16, ntiles, out, N, s.ksplit, s.cps, s.tpb, pro);
+    LAUNCH_CHECK(c, "gemm_bf16 (fused prologue)");
+    if (direct_out && s.ksplit > 1) {
+        const size_t n = (size_t)m * N;
+        hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, part_out, s.ksplit, n, n,
+                           direct_out);
         LAUNCH_CHECK(c, "sum_partials");
     }
     *nsplit_out = direct_out ? 0 : s.ksplit;
@@ -531,6 +563,92 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
     return 0;
 }
 
+// Short blocks of narrow bf16 models (drafter steps): the same forward with the add+norm, the FFN
+// activation and the attention combine folded into the prologue of the GEMM that consumes them -
+// 6 launches per layer instead of 10.  The residual stream and the partials ping-pong between two
+// buffers, because a GEMM's workgroups read the old ones while others already write the new ones.
+bool fused_small_ok(const Model& M, int m) {
+    const metasd_model_desc& d = M.d;
+    return d.dtype == METASD_BF16 && m <= 4 && d.d_model <= 1024 && d.d_ffn <= 4096 && M.hd >= 64;
+}
+
+int forward_rows_fused(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int first_row) {
+    typedef bf16_t T;
+    const metasd_model_desc& d = M.d;
+    const int D = d.d_model, H = d.n_heads, KH = d.n_kv_heads, hd = M.hd, F = d.d_ffn, V = d.vocab;
+    const int DQ = H * hd, DKV = KH * hd, NQKV = DQ + 2 * DKV;
+    hipStream_t st = c->stream;
+    int hp = 0, pp = 0, ns = 0, rc;     // current residual buffer, current partials buffer, partials in it
+    hipLaunchKernelGGL(embed_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, c->d_h_pp(0));
+    LAUNCH_CHECK(c, "embed");
+    hipLaunchKernelGGL(rope_table_kernel, dim3(m), dim3(hd / 2), 0, st, pos0, hd, d.rope_theta, c->d_rope());
+    LAUNCH_CHECK(c, "rope_table");
+    auto norm_pro = [&](const void* gain, int row0) {
+        GemmPro p{};
+        p.src = c->d_h_pp(hp) + (size_t)row0 * D;
+        p.part = c->d_part_pp(pp) + (size_t)row0 * D;
+        p.h_out = c->d_h_pp(hp ^ 1) + (size_t)row0 * D;
+        p.gain = (const bf16_t*)gain;
+        p.sstride = (size_t)m * D;
+        p.ns = ns;
+        p.eps = d.rms_eps;
+        return p;
+    };
+    const int nchunks = (pos0 + m + ATT_CH - 1) / ATT_CH;
+    for (int L = 0; L < d.n_layers; ++L) {
+        // QKV projection of norm(h + previous FFN output)
+        if ((rc = gemm_pro<PRO_NORM>(c, norm_pro(M.layer_w(L, 0), 0), m, D, M.layer_w(L, 1), DQ, M.layer_w(L, 2), DKV, M.layer_w(L, 3), DKV,
+                                     c->d_part_pp(pp ^ 1), nullptr, &ns))) return rc;
+        hp ^= 1; pp ^= 1;
+        const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
+        T* kc = (T*)M.kv + (size_t)L * 2 * plane;
+        hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, c->d_part_pp(pp), ns, (size_t)m * NQKV, NQKV, pos0, H,
+                           KH, hd, (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, 1);
+        LAUNCH_CHECK(c, "rope_kv");
+        {
+            const float scale = 1.0f / sqrtf((float)hd);
+            metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_ATTN, 2.0 * KH * (double)(pos0 + m) * hd * 2 + (double)m * H * hd * 4);
+            hipEvent_t ea = pr ? pr->a : nullptr, eb = pr ? pr->b : nullptr;
+            if (hd == 64)
+                hipExtLaunchKernelGGL((attn_partial_mfma_kernel<64>), dim3(nchunks, H), dim3(256), 0u, st, ea, eb, 0u, (const float*)c->d_q(),
+                                      (const T*)kc, (const T*)(kc + plane), m, pos0, H, KH, c->cfg.max_ctx, scale, c->d_apart(), nchunks);
+            else
+                hipExtLaunchKernelGGL((attn_partial_mfma_kernel<128>), dim3(nchunks, H), dim3(256), 0u, st, ea, eb, 0u, (const float*)c->d_q(),
+                                      (const T*)kc, (const T*)(kc + plane), m, pos0, H, KH, c->cfg.max_ctx, scale, c->d_apart(), nchunks);
+            LAUNCH_CHECK(c, "attn_partial");
+        }
+        // output projection of the merged attention output
+        {
+            GemmPro p{};
+            p.src = c->d_apart(); p.nchunks = nchunks; p.hd = hd;
+            if ((rc = gemm_pro<PRO_COMBINE>(c, p, m, DQ, M.layer_w(L, 4), D, nullptr, 0, nullptr, 0, c->d_part_pp(pp ^ 1), nullptr, &ns))) return rc;
+            pp ^= 1;
+        }
+        // gate | up projection of norm(h + attention output)
+        if (d.act == METASD_SWIGLU)
+            rc = gemm_pro<PRO_NORM>(c, norm_pro(M.layer_w(L, 5), 0), m, D, M.layer_w(L, 6), F, M.layer_w(L, 7), F, nullptr, 0,
+                                    c->d_part_pp(pp ^ 1), nullptr, &ns);
+        else
+            rc = gemm_pro<PRO_NORM>(c, norm_pro(M.layer_w(L, 5), 0), m, D, M.layer_w(L, 7), F, nullptr, 0, nullptr, 0, c->d_part_pp(pp ^ 1),
+                                    nullptr, &ns);
+        if (rc) return rc;
+        hp ^= 1; pp ^= 1;
+        // down projection of the activation
+        {
+            GemmPro p{};
+            p.src = c->d_part_pp(pp); p.ns = ns; p.sstride = (size_t)m * (d.act == METASD_SWIGLU ? 2 : 1) * F; p.act = d.act == METASD_SWIGLU ? 1 : 0;
+            if ((rc = gemm_pro<PRO_ACT>(c, p, m, F, M.layer_w(L, 8), D, nullptr, 0, nullptr, 0, c->d_part_pp(pp ^ 1), nullptr, &ns))) return rc;
+            pp ^= 1;
+        }
+    }
+    if (logits) {
+        int dummy;
+        if ((rc = gemm_pro<PRO_NORM>(c, norm_pro(M.final_norm(), first_row), m - first_row, D, M.lm_head(), V, nullptr, 0, nullptr, 0,
+                                     c->d_part_pp(pp ^ 1), logits, &dummy))) return rc;
+    }
+    return 0;
+}
+
 // ---- bf16 models: the whole block forward in one cooperative launch (see persist.h)
 
 int upload_table(metasd_ctx* c, Model& M) {
@@ -594,6 +712,7 @@ int forward(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool want_a
         int rc;
         if (M.d.dtype != METASD_BF16) rc = forward_rows<float>(c, M, pos0 + done, m, lg, first_row);
         else if (c->persistent) rc = forward_persistent(c, M, pos0 + done, m, lg, first_row);
+        else if (c->fuse_small && fused_small_ok(M, m)) rc = forward_rows_fused(c, M, pos0 + done, m, lg, first_row);
         else rc = forward_rows<bf16_t>(c, M, pos0 + done, m, lg, first_row);
         if (rc) return rc;
         done += m;
@@ -754,6 +873,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         const char* ev = getenv("METASD_PERSISTENT");
         c->persistent = ok && ev && ev[0] == '1';
         if (const char* ev = getenv("METASD_TLOG")) c->tlog = ev[0] == '1';
+        if (const char* ev = getenv("METASD_FUSE_SMALL")) c->fuse_small = ev[0] != '0';
         c->n_cu = ncu;
         if (const char* ev = getenv("METASD_NB")) { int v = atoi(ev); if (v >= 1 && v <= ncu) c->n_cu = v; }   // fewer workgroups (debugging)
     }

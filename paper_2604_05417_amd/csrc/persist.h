@@ -49,7 +49,7 @@ __device__ __forceinline__ void st_agent(float* p, float v) { __hip_atomic_store
 __device__ __forceinline__ void drain_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ int arrive(int* cnt) { return __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
-enum { PRO_PLAIN = 0, PRO_NORM = 1, PRO_SWIGLU = 2, PRO_GELU = 3 };
+enum { PKPRO_PLAIN = 0, PKPRO_NORM = 1, PKPRO_SWIGLU = 2, PKPRO_GELU = 3 };
 
 // 8 activations -> two bf16 terms (hi = bf16(x), lo = bf16(x - hi)), one 16-byte LDS unit each
 __device__ __forceinline__ void store_hilo(uint4* xs, uint4* xlo, int at, const float (&v)[8]) {
@@ -128,7 +128,7 @@ __device__ __forceinline__ void make_gemm(const FwdP& P, int L, int kind, GPh& G
     G.x = op ? P.ao : (dn ? P.gu : P.h);
     G.ldx = op ? DQ : (dn ? (swiglu ? 2 * F : F) : D);
     G.K = op ? DQ : (dn ? F : D);
-    G.pro = op ? PRO_PLAIN : (dn ? (swiglu ? PRO_SWIGLU : PRO_GELU) : PRO_NORM);
+    G.pro = op ? PKPRO_PLAIN : (dn ? (swiglu ? PKPRO_SWIGLU : PKPRO_GELU) : PKPRO_NORM);
     const int gi = qkv ? base : (gu ? base + 5 : 1 + 9 * nl);      // norm gain (unused for O and down)
     G.gain = (const bf16_t*)P.w[gi];
     const int w0 = qkv ? base + 1 : op ? base + 4 : gu ? (swiglu ? base + 6 : base + 7) : dn ? base + 8 : 2 + 9 * nl;
@@ -235,29 +235,29 @@ __device__ __forceinline__ void stage_x(const GPh& G, int m, int pc0, int npc, u
                 const float* xr = G.x + (size_t)(G.row0 + r) * G.ldx + k;
                 a[j] = *reinterpret_cast<const float4*>(xr);
                 b[j] = *reinterpret_cast<const float4*>(xr + 4);
-                if (G.pro == PRO_SWIGLU) {
+                if (G.pro == PKPRO_SWIGLU) {
                     ua[j] = *reinterpret_cast<const float4*>(xr + G.K);
                     ub[j] = *reinterpret_cast<const float4*>(xr + G.K + 4);
                 }
             }
             uint4 gq = make_uint4(0, 0, 0, 0);
-            if (G.pro == PRO_NORM) gq = *reinterpret_cast<const uint4*>(G.gain + k);
+            if (G.pro == PKPRO_NORM) gq = *reinterpret_cast<const uint4*>(G.gain + k);
             const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
 #pragma unroll
             for (int j = 0; j < RB; ++j) {
                 if (r0 + j < m) {
                     float v[8] = {a[j].x, a[j].y, a[j].z, a[j].w, b[j].x, b[j].y, b[j].z, b[j].w};
-                    if (G.pro == PRO_NORM) {
+                    if (G.pro == PKPRO_NORM) {
 #pragma unroll
                         for (int e = 0; e < 8; ++e) {
                             ss[j] += v[e] * v[e];
                             v[e] *= bf2f((bf16_t)(gw[e >> 1] >> ((e & 1) * 16)));
                         }
-                    } else if (G.pro == PRO_SWIGLU) {
+                    } else if (G.pro == PKPRO_SWIGLU) {
                         const float u[8] = {ua[j].x, ua[j].y, ua[j].z, ua[j].w, ub[j].x, ub[j].y, ub[j].z, ub[j].w};
 #pragma unroll
                         for (int e = 0; e < 8; ++e) v[e] = v[e] / (1.0f + expf(-v[e])) * u[e];
-                    } else if (G.pro == PRO_GELU) {
+                    } else if (G.pro == PKPRO_GELU) {
 #pragma unroll
                         for (int e = 0; e < 8; ++e) v[e] = 0.5f * v[e] * (1.0f + erff(v[e] * 0.70710678118654752f));
                     }
@@ -265,7 +265,7 @@ __device__ __forceinline__ void stage_x(const GPh& G, int m, int pc0, int npc, u
                 }
             }
         }
-        if (G.pro == PRO_NORM) {
+        if (G.pro == PKPRO_NORM) {
 #pragma unroll
             for (int j = 0; j < RB; ++j) {
                 const float t = wave_sum(ss[j]);
@@ -380,7 +380,7 @@ __device__ __forceinline__ void gemm_run(const FwdP& P, int L, int kind, u32x4 (
                 const float4 pv = *reinterpret_cast<const float4*>(rb + ww * 256 + row * 16 + g * 4);
                 v.x += pv.x; v.y += pv.y; v.z += pv.z; v.w += pv.w;
             }
-            if (G.pro == PRO_NORM) {
+            if (G.pro == PKPRO_NORM) {
                 float ssq = 0.f;
 #pragma unroll
                 for (int ww = 0; ww < PK_NW; ++ww) ssq += ssq_s[ww * 16 + row];
