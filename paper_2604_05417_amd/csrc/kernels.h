@@ -547,7 +547,8 @@ __global__ void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restr
 // ------------------------------------------------------------------------------------------
 // RoPE (rotate-half pairing, angle = pos * theta^(-2i/hd)) on q and k, K/V cache append.
 //   part: split-K partials of the fused q|k|v projection, [s][r][N], N = (H + 2 KH) * hd.
-//   q out fp32 [m][H*hd]; cache planes (type T) [kv_head][max_ctx][hd].     grid (H + 2KH, m), block 64
+//   q out fp32 [m][H*hd] (q_split: as two bf16 arrays, see below); cache planes (type T) [kv_head][max_ctx][hd].
+//   grid (H + 2KH, m), block 64
 
 // Rotation table of one forward block: tab[r][i] = (cos, sin)(pos0 + r) * theta^(-2i/hd), in fp64 (the
 // rotation is applied in fp64 and rounded once).  grid (m), block hd/2.  Built once per forward, used by every layer.
@@ -563,7 +564,7 @@ __global__ void rope_table_kernel(int pos0, int hd, float theta, double2* __rest
 template <typename T>
 __global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int N, int pos0, int H, int KH,
                                int hd, const double2* __restrict__ tab, float* __restrict__ q, T* __restrict__ kc,
-                               T* __restrict__ vc, int max_ctx, int interleaved) {
+                               T* __restrict__ vc, int max_ctx, int interleaved, int q_split) {
     const int head = blockIdx.x, r = blockIdx.y, i = threadIdx.x, half = hd >> 1;
     if (i >= half) return;
     // interleaved (rope-ordered packed weights): q / k columns hold the pair (i, i + half) at 16(i/8) + 2(i%8), +1
@@ -592,6 +593,14 @@ __global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_
         a = ra; b = rb;
     }
     if (head < H) {
+        if (q_split) {   // q as two bf16 terms (hi = bf16(q), lo = bf16(q - hi)): [m][H hd] hi, then [m][H hd] lo
+            bf16_t* qh = reinterpret_cast<bf16_t*>(q) + (size_t)r * H * hd + (size_t)head * hd;
+            bf16_t* ql = qh + (size_t)gridDim.y * H * hd;
+            const bf16_t ah = f2bf(a), bh = f2bf(b);
+            qh[i] = ah; qh[i + half] = bh;
+            ql[i] = f2bf(a - bf2f(ah)); ql[i + half] = f2bf(b - bf2f(bh));
+            return;
+        }
         float* qd = q + (size_t)r * H * hd + (size_t)head * hd;
         qd[i] = a;
         qd[i + half] = b;
@@ -771,24 +780,16 @@ __global__ __launch_bounds__(256) void attn_partial_mfma_kernel(const float* __r
         const int p = idx / VPR, v = idx - p * VPR;
         vreg[it] = (p < np) ? *reinterpret_cast<const uint4*>(vbase + (size_t)p * HD + v * 8) : make_uint4(0, 0, 0, 0);
     }
-    // ---- q fragments (B operand): q[row][32 kc + 8 g .. +8] as hi / lo bf16
+    // ---- q fragments (B operand): q[row][32 kc + 8 g .. +8], already split into two bf16 terms by rope_kv_kernel
     uint4 qh[KC], ql[KC];
 #pragma unroll
     for (int k = 0; k < KC; ++k) {
         qh[k] = make_uint4(0, 0, 0, 0);
         ql[k] = make_uint4(0, 0, 0, 0);
         if (rowok) {
-            const float* src = q + (size_t)row * H * HD + (size_t)h * HD + k * 32 + g * 8;
-            const float4 a = *reinterpret_cast<const float4*>(src), b = *reinterpret_cast<const float4*>(src + 4);
-            const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-            bf16_t hi[8], lo[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                hi[e] = f2bf(v[e]);
-                lo[e] = f2bf(v[e] - bf2f(hi[e]));
-            }
-            qh[k] = make_uint4(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]), pack_bf16x2(hi[4], hi[5]), pack_bf16x2(hi[6], hi[7]));
-            ql[k] = make_uint4(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(lo[4], lo[5]), pack_bf16x2(lo[6], lo[7]));
+            const bf16_t* src = reinterpret_cast<const bf16_t*>(q) + (size_t)row * H * HD + (size_t)h * HD + k * 32 + g * 8;
+            qh[k] = *reinterpret_cast<const uint4*>(src);
+            ql[k] = *reinterpret_cast<const uint4*>(src + (size_t)m * H * HD);
         }
     }
     // ---- scores of this wavefront's 32 positions: two 16-position tiles

@@ -533,7 +533,8 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
         hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, part, ns, (size_t)m * NQKV, NQKV, pos0, H, KH,
-                           hd, (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, sizeof(T) == 2 ? 1 : 0);
+                           hd, (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, sizeof(T) == 2 ? 1 : 0,
+                           (sizeof(T) == 2 && hd >= 64) ? 1 : 0);
         LAUNCH_CHECK(c, "rope_kv");
         if ((rc = attention<T>(c, M, L, pos0, m))) return rc;
         if ((rc = gemm<T>(c, c->d_ao(), DQ, m, DQ, M.layer_w(L, 4), D, nullptr, 0, nullptr, 0, nullptr, &ns))) return rc;
@@ -603,7 +604,7 @@ int forward_rows_fused(metasd_ctx* c, Model& M, int pos0, int m, float* logits, 
         const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
         hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, c->d_part_pp(pp), ns, (size_t)m * NQKV, NQKV, pos0, H,
-                           KH, hd, (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, 1);
+                           KH, hd, (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, 1, 1);
         LAUNCH_CHECK(c, "rope_kv");
         {
             const float scale = 1.0f / sqrtf((float)hd);
