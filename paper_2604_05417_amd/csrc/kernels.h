@@ -106,15 +106,34 @@ __global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restric
     for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)r * d + i] = El<T>::ld(E[t * d + i]);
 }
 
+// Activations handed to the bf16 GEMM are stored as two bf16 terms, x = hi + lo with hi = bf16(x),
+// lo = bf16(x - hi): array hi[n] at `base`, array lo[n] right behind it (n = elements of the whole
+// block).  The producer pays the conversion once; every GEMM workgroup then copies 16-byte pieces.
+__device__ __forceinline__ void store_split4(float* base, size_t n, size_t at, const float4& v) {
+    bf16_t* hi = reinterpret_cast<bf16_t*>(base) + at;
+    bf16_t* lo = hi + n;
+    const bf16_t h0 = f2bf(v.x), h1 = f2bf(v.y), h2 = f2bf(v.z), h3 = f2bf(v.w);
+    *reinterpret_cast<uint2*>(hi) = make_uint2((uint32_t)h0 | ((uint32_t)h1 << 16), (uint32_t)h2 | ((uint32_t)h3 << 16));
+    const bf16_t l0 = f2bf(v.x - bf2f(h0)), l1 = f2bf(v.y - bf2f(h1)), l2 = f2bf(v.z - bf2f(h2)), l3 = f2bf(v.w - bf2f(h3));
+    *reinterpret_cast<uint2*>(lo) = make_uint2((uint32_t)l0 | ((uint32_t)l1 << 16), (uint32_t)l2 | ((uint32_t)l3 << 16));
+}
+__device__ __forceinline__ void store_split1(float* base, size_t n, size_t at, float v) {
+    bf16_t* hi = reinterpret_cast<bf16_t*>(base) + at;
+    const bf16_t h = f2bf(v);
+    hi[0] = h;
+    hi[n] = f2bf(v - bf2f(h));
+}
+
 // ------------------------------------------------------------------------------------------
 // residual add of split-K partial sums + RMSNorm:      grid (m), block 1024, d % 4 == 0
 //   h[r] += sum_s part[s][r]   (skipped when nsplit == 0)
 //   xn[r] = h[r] / sqrt(mean(h[r]^2) + eps) * gain          (fp32; T is the type of the gain)
+// split != 0: xn is written as two bf16 arrays (see store_split4), the form the bf16 GEMM stages.
 
 template <typename T>
 __global__ __launch_bounds__(1024) void addnorm_kernel(float* __restrict__ h, const float* __restrict__ part, int nsplit,
                                                        size_t sstride, int d, const T* __restrict__ gain, float eps,
-                                                       float* __restrict__ xn) {
+                                                       float* __restrict__ xn, int split) {
     __shared__ float red[16];
     constexpr int KEEP = 2;                 // float4 columns per thread kept in registers (d <= 8192); beyond that via memory
     const int r = blockIdx.x;
@@ -159,7 +178,8 @@ __global__ __launch_bounds__(1024) void addnorm_kernel(float* __restrict__ h, co
             o.y = v.y * inv * El<T>::ld(gain[i + 1]);
             o.z = v.z * inv * El<T>::ld(gain[i + 2]);
             o.w = v.w * inv * El<T>::ld(gain[i + 3]);
-            *reinterpret_cast<float4*>(xn + (size_t)r * d + i) = o;
+            if (split) store_split4(xn, (size_t)gridDim.x * d, (size_t)r * d + i, o);
+            else *reinterpret_cast<float4*>(xn + (size_t)r * d + i) = o;
         }
     }
 }
@@ -215,9 +235,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 // output features 16t..16t+15 and inputs 32c..32c+31; lane l owns 16 bytes = 8 consecutive inputs
 // 32c + 8(l/16).. of feature 16t + l%16 - exactly the A operand of v_mfma_f32_16x16x32_bf16, so
 // one wavefront load instruction reads one contiguous KiB.  The activations (m <= 16 rows, fp32
-// in memory) are the B operand, staged once per workgroup in LDS as two bf16 terms x = hi + lo
-// (hi = bf16(x), lo = bf16(x - hi)): each weight tile feeds two MFMAs, which keeps ~16 mantissa
-// bits of the activations at no HBM cost (the matrix cores idle >95 % of the time here anyway).
+// values) are the B operand, staged once per workgroup in LDS as two bf16 terms x = hi + lo
+// (hi = bf16(x), lo = bf16(x - hi), written in that form by the producing kernel): each weight tile
+// feeds two MFMAs, which keeps ~16 mantissa bits of the activations at no HBM cost (the matrix
+// cores idle >95 % of the time here anyway).
 // D[i][j] = sum_k A[i][k] B[k][j]: lane l gets D[4(l/16)+v][l%16], v = 0..3, i.e. 4 consecutive
 // output features of activation row l%16.
 //
@@ -244,6 +265,7 @@ enum { PRO_PLAIN = 0, PRO_NORM = 1, PRO_ACT = 2, PRO_COMBINE = 3 };
 
 struct GemmPro {
     const float* src;      // NORM: h_in [m][K];  ACT: partials [s][m][(1|2) K];  COMBINE: attention partials
+                           // (PLAIN: unused; sstride = offset in elements from the hi array x to the lo array)
     const float* part;     // NORM: partials [s][m][K] of the previous GEMM (ns may be 0)
     float* h_out;          // NORM: updated residual stream [m][K]
     const bf16_t* gain;    // NORM
@@ -304,38 +326,38 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict_
         // Order of the requests (a wavefront's loads return in order): first the activations of this
         // workgroup's slice (L2 hits, needed first), then the first KiBs of the weight stream, which
         // stay in flight while the activations are converted and written to LDS.
+        // x is given as two bf16 arrays (hi at x, lo at x + pro.sstride elements), row stride ldx.
         constexpr int XB = 6;                         // 8-element pieces per thread and batch
-        auto piece = [&](int idx) -> const float* {   // clamped: every load is unconditional and in range
+        const bf16_t* xh = reinterpret_cast<const bf16_t*>(x);
+        auto piece = [&](int idx) -> const bf16_t* {  // clamped: every load is unconditional and in range
             const int ic = min(idx, total - 1);
             const int r = ic / per, c = ic - r * per;
-            return x + (size_t)r * ldx + (size_t)c0 * 32 + (size_t)c * 8;
+            return xh + (size_t)r * ldx + (size_t)c0 * 32 + (size_t)c * 8;
         };
-        float4 a[XB], b[XB];
+        u32x4 a[XB], b[XB];   // (ext vectors: arrays of the HIP struct type end up in scratch memory)
 #pragma unroll
         for (int u = 0; u < XB; ++u) {
-            const float* src = piece((int)threadIdx.x + u * 256);
-            a[u] = *reinterpret_cast<const float4*>(src);
-            b[u] = *reinterpret_cast<const float4*>(src + 4);
+            const bf16_t* src = piece((int)threadIdx.x + u * 256);
+            a[u] = *reinterpret_cast<const u32x4*>(src);
+            b[u] = *reinterpret_cast<const u32x4*>(src + pro.sstride);
         }
         issue(wa, wp, 0);
 #pragma unroll
         for (int u = 0; u < XB; ++u) {
             const int idx = (int)threadIdx.x + u * 256;
-            const float v[8] = {a[u].x, a[u].y, a[u].z, a[u].w, b[u].x, b[u].y, b[u].z, b[u].w};
-            if (idx < total) convert_store(v, idx);
+            if (idx < total) { const int r = idx / per, c = idx - r * per; xs[r * rs + c] = __builtin_bit_cast(uint4, a[u]); xlo[r * rs + c] = __builtin_bit_cast(uint4, b[u]); }
         }
         for (int base = XB * 256; base < total; base += XB * 256) {   // taller / wider blocks: further batches
 #pragma unroll
             for (int u = 0; u < XB; ++u) {
-                const float* src = piece(base + (int)threadIdx.x + u * 256);
-                a[u] = *reinterpret_cast<const float4*>(src);
-                b[u] = *reinterpret_cast<const float4*>(src + 4);
+                const bf16_t* src = piece(base + (int)threadIdx.x + u * 256);
+                a[u] = *reinterpret_cast<const u32x4*>(src);
+                b[u] = *reinterpret_cast<const u32x4*>(src + pro.sstride);
             }
 #pragma unroll
             for (int u = 0; u < XB; ++u) {
                 const int idx = base + (int)threadIdx.x + u * 256;
-                const float v[8] = {a[u].x, a[u].y, a[u].z, a[u].w, b[u].x, b[u].y, b[u].z, b[u].w};
-                if (idx < total) convert_store(v, idx);
+                if (idx < total) { const int r = idx / per, c = idx - r * per; xs[r * rs + c] = __builtin_bit_cast(uint4, a[u]); xlo[r * rs + c] = __builtin_bit_cast(uint4, b[u]); }
             }
         }
     } else if constexpr (PRO == PRO_NORM) {
@@ -883,7 +905,7 @@ __global__ __launch_bounds__(256) void attn_partial_mfma_kernel(const float* __r
 }
 
 template <typename T, int HD>
-__global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks, int H, float* __restrict__ out) {
+__global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks, int H, float* __restrict__ out, int split) {
     const int h = blockIdx.x, r = blockIdx.y, col = threadIdx.x;
     const float* base = part + ((size_t)h * nchunks * 16 + r) * (HD + 2);
     const size_t cs = (size_t)16 * (HD + 2);
@@ -912,7 +934,8 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks,
             o += oc[u] * w;
         }
     }
-    out[(size_t)r * H * HD + (size_t)h * HD + col] = o / Lsum;
+    if (split) store_split1(out, (size_t)gridDim.y * H * HD, (size_t)r * H * HD + (size_t)h * HD + col, o / Lsum);
+    else out[(size_t)r * H * HD + (size_t)h * HD + col] = o / Lsum;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -920,7 +943,7 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks,
 //                                      GELU    out = 0.5 u (1 + erf(u / sqrt 2)).
 
 __global__ void ffn_act_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int m, int f, int act,
-                               float* __restrict__ out) {
+                               float* __restrict__ out, int split) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)m * f) return;
     const int r = (int)(idx / f), i = (int)(idx - (size_t)r * f);
@@ -938,8 +961,9 @@ __global__ void ffn_act_kernel(const float* __restrict__ part, int nsplit, size_
         for (int k = 0; k < 4; ++k)
             if (s0 + k < nsplit) { g += pg[k]; u += pu[k]; }
     }
-    if (act == 1) out[idx] = g / (1.0f + expf(-g)) * u;
-    else out[idx] = 0.5f * g * (1.0f + erff(g * 0.70710678118654752f));
+    const float y = act == 1 ? g / (1.0f + expf(-g)) * u : 0.5f * g * (1.0f + erff(g * 0.70710678118654752f));
+    if (split) store_split1(out, (size_t)m * f, idx, y);
+    else out[idx] = y;
 }
 
 // ------------------------------------------------------------------------------------------

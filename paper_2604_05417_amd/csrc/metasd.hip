@@ -402,11 +402,11 @@ namespace {
 // when direct_out != nullptr the summed result is written there instead and 0 is returned.
 template <typename T>
 int gemm(metasd_ctx* c, const void* x, int ldx, int m, int K, const void* W0, int n0, const void* W1, int n1,
-         const void* W2, int n2, float* direct_out, int* nsplit_out);
+         const void* W2, int n2, float* direct_out, int* nsplit_out, size_t x_lo_off = 0);
 
 template <>
 int gemm<float>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void* W0, int n0, const void* W1, int n1,
-                const void* W2, int n2, float* direct_out, int* nsplit_out) {
+                const void* W2, int n2, float* direct_out, int* nsplit_out, size_t) {
     const int N = n0 + n1 + n2;
     float* out = direct_out ? direct_out : c->d_part();
     hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 3) / 4), dim3(256), 0, c->stream, (const float*)x, ldx, m, K,
@@ -417,8 +417,9 @@ int gemm<float>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void*
 }
 
 template <>
+// x: the activations as two bf16 arrays, hi at x and lo x_lo_off elements behind it (see store_split4).
 int gemm<bf16_t>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void* W0, int n0, const void* W1, int n1,
-                 const void* W2, int n2, float* direct_out, int* nsplit_out) {
+                 const void* W2, int n2, float* direct_out, int* nsplit_out, size_t x_lo_off) {
     const int N = n0 + n1 + n2;
     const int ntiles = N / 16, kchunks = K / 32;
     const Split s = choose_split(m, ntiles, kchunks);
@@ -426,10 +427,12 @@ int gemm<bf16_t>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void
     const int groups = (ntiles + s.tpb - 1) / s.tpb;
     // algorithmic bytes: every weight once, the activations once, the result once
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
+    GemmPro plain{};
+    plain.sstride = x_lo_off;
     hipExtLaunchKernelGGL(gemm_bf16_kernel<PRO_PLAIN>, dim3(groups * s.ksplit), dim3(256), (uint32_t)s.lds, c->stream,
                           pr ? pr->a : nullptr, pr ? pr->b : nullptr, 0u, (const float*)x, ldx, m, K, (const bf16_t*)W0,
                           (const bf16_t*)W1, (const bf16_t*)W2, n0 / 16, (n0 + n1) / 16, ntiles, out, N, s.ksplit, s.cps, s.tpb,
-                          GemmPro{});
+                          plain);
     LAUNCH_CHECK(c, "gemm_bf16");
     if (direct_out && s.ksplit > 1) {
         const size_t n = (size_t)m * N;
@@ -490,7 +493,7 @@ int attention_hd(metasd_ctx* c, const Model& M, int L, int pos0, int m) {
     }
     LAUNCH_CHECK(c, "attn_partial");
     hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3(d.n_heads, m), dim3(HD), 0, c->stream, c->d_apart(), nchunks,
-                       d.n_heads, (float*)c->d_ao());
+                       d.n_heads, (float*)c->d_ao(), sizeof(T) == 2 ? 1 : 0);
     LAUNCH_CHECK(c, "attn_combine");
     return 0;
 }
@@ -519,6 +522,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
     float* xn = (float*)c->d_xn();
     float* part = c->d_part();
     int ns = 0, rc;
+    constexpr int split = sizeof(T) == 2 ? 1 : 0;   // bf16 models: activations for the GEMM are stored as two bf16 arrays
     hipLaunchKernelGGL(embed_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, h);
     LAUNCH_CHECK(c, "embed");
     hipLaunchKernelGGL(rope_table_kernel, dim3(m), dim3(hd / 2), 0, st, pos0, hd, d.rope_theta, c->d_rope());
@@ -526,9 +530,9 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
     for (int L = 0; L < d.n_layers; ++L) {
         // h += previous FFN output (split partials); xn = norm(h)
         hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.layer_w(L, 0),
-                           d.rms_eps, xn);
+                           d.rms_eps, xn, split);
         LAUNCH_CHECK(c, "addnorm");
-        if ((rc = gemm<T>(c, xn, D, m, D, M.layer_w(L, 1), DQ, M.layer_w(L, 2), DKV, M.layer_w(L, 3), DKV, nullptr, &ns))) return rc;
+        if ((rc = gemm<T>(c, xn, D, m, D, M.layer_w(L, 1), DQ, M.layer_w(L, 2), DKV, M.layer_w(L, 3), DKV, nullptr, &ns, (size_t)m * D))) return rc;
         const int NQKV = DQ + 2 * DKV;
         const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
@@ -537,28 +541,29 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
                            (sizeof(T) == 2 && hd >= 64) ? 1 : 0);
         LAUNCH_CHECK(c, "rope_kv");
         if ((rc = attention<T>(c, M, L, pos0, m))) return rc;
-        if ((rc = gemm<T>(c, c->d_ao(), DQ, m, DQ, M.layer_w(L, 4), D, nullptr, 0, nullptr, 0, nullptr, &ns))) return rc;
+        if ((rc = gemm<T>(c, c->d_ao(), DQ, m, DQ, M.layer_w(L, 4), D, nullptr, 0, nullptr, 0, nullptr, &ns, (size_t)m * DQ))) return rc;
         hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.layer_w(L, 5),
-                           d.rms_eps, xn);
+                           d.rms_eps, xn, split);
         LAUNCH_CHECK(c, "addnorm");
         if (d.act == METASD_SWIGLU) {
-            if ((rc = gemm<T>(c, xn, D, m, D, M.layer_w(L, 6), F, M.layer_w(L, 7), F, nullptr, 0, nullptr, &ns))) return rc;
+            if ((rc = gemm<T>(c, xn, D, m, D, M.layer_w(L, 6), F, M.layer_w(L, 7), F, nullptr, 0, nullptr, &ns, (size_t)m * D))) return rc;
         } else {
-            if ((rc = gemm<T>(c, xn, D, m, D, M.layer_w(L, 7), F, nullptr, 0, nullptr, 0, nullptr, &ns))) return rc;
+            if ((rc = gemm<T>(c, xn, D, m, D, M.layer_w(L, 7), F, nullptr, 0, nullptr, 0, nullptr, &ns, (size_t)m * D))) return rc;
         }
         const size_t nact = (size_t)m * F;
         const int NF = (d.act == METASD_SWIGLU ? 2 : 1) * F;
         hipLaunchKernelGGL(ffn_act_kernel, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)m * NF, m, F,
-                           d.act, (float*)c->d_act());
+                           d.act, (float*)c->d_act(), split);
         LAUNCH_CHECK(c, "ffn_act");
-        if ((rc = gemm<T>(c, c->d_act(), F, m, F, M.layer_w(L, 8), D, nullptr, 0, nullptr, 0, nullptr, &ns))) return rc;
+        if ((rc = gemm<T>(c, c->d_act(), F, m, F, M.layer_w(L, 8), D, nullptr, 0, nullptr, 0, nullptr, &ns, (size_t)m * F))) return rc;
     }
     if (logits) {
         hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.final_norm(),
-                           d.rms_eps, xn);
+                           d.rms_eps, xn, split);
         LAUNCH_CHECK(c, "addnorm");
         int dummy;
-        if ((rc = gemm<T>(c, xn + (size_t)first_row * D, D, m - first_row, D, M.lm_head(), V, nullptr, 0, nullptr, 0, logits, &dummy)))
+        const void* xrow = split ? (const void*)((const bf16_t*)xn + (size_t)first_row * D) : (const void*)(xn + (size_t)first_row * D);
+        if ((rc = gemm<T>(c, xrow, D, m - first_row, D, M.lm_head(), V, nullptr, 0, nullptr, 0, logits, &dummy, (size_t)m * D)))
             return rc;
     }
     return 0;
