@@ -183,8 +183,13 @@ int32_t metasd_accept(metasd_ctx*, int32_t gamma, int32_t* n_acc_out, int32_t* t
 /* Accept step on rows of logits: P [rows][gamma+1][V], Q [rows][gamma][V] fp32, d [rows][gamma]
  * int32, all device.  Row b uses the uniforms of sequence id seq0 + b at `round`.  Outputs
  * (device, any of mask/bd may be NULL): n_acc [rows], token [rows], mask [rows] (bit j), bd
- * [rows][gamma] doubles (sum_v min(p_j, q_j)).  scratch: device, rows*(gamma+1)*16 bytes.
+ * [rows][gamma] doubles (sum_v min(p_j, q_j)).  scratch: device, METASD_ACCEPT_SCRATCH_BYTES(rows, gamma)
+ * bytes, zero-filled before its first use; later calls may reuse it as it is (each launch tags what
+ * it writes there with a process-wide launch number), but two launches that overlap in time must not
+ * share it.  A token of -2 reports that the four workgroups of a position did not meet within the
+ * kernel's bounded wait (nothing hangs; the result of that row is invalid).
  * Requires V % 4 == 0 and V <= 32768.  Asynchronous on hip_stream. */
+#define METASD_ACCEPT_SCRATCH_BYTES(rows, gamma) ((size_t)(rows) * ((size_t)(gamma) + 1) * 336)
 int32_t metasd_accept_logits(const float* P, const float* Q, const int32_t* d, int32_t rows, int32_t gamma,
                              int32_t V, float temperature, uint64_t seed, uint32_t round, uint32_t seq0,
                              int32_t* n_acc, int32_t* token, uint32_t* mask, double* bd, void* scratch,

@@ -300,7 +300,7 @@ def accept_logits(P: torch.Tensor, Q: torch.Tensor, d: torch.Tensor, T: float, s
         dev = P.device
         out = dict(n_acc=torch.empty(rows, dtype=torch.int32, device=dev), token=torch.empty(rows, dtype=torch.int32, device=dev),
                    mask=torch.empty(rows, dtype=torch.int32, device=dev), bd=torch.empty((rows, gamma), dtype=torch.float64, device=dev),
-                   scratch=torch.empty(rows * (gamma + 1) * 16, dtype=torch.uint8, device=dev))
+                   scratch=torch.zeros(rows * (gamma + 1) * 336, dtype=torch.uint8, device=dev))   # zero-filled once, reusable
     _check(load_library().metasd_accept_logits(P.data_ptr(), Q.data_ptr(), d.data_ptr(), rows, gamma, V, T, seed, rnd, seq0,
                                                out["n_acc"].data_ptr(), out["token"].data_ptr(), out["mask"].data_ptr(),
                                                out["bd"].data_ptr(), out["scratch"].data_ptr(), _stream_ptr(stream)))

@@ -1256,6 +1256,390 @@ __global__ __launch_bounds__(AK_NT) void accept_rows_kernel(const float* __restr
     else accept_rows_body<false>(P, Q, d, gamma, V, T, seed, round, seq0, cand, bd, sm);
 }
 
+// ------------------------------------------------------------------------------------------
+// The same accept step with every (row, position) split over four workgroups of 256 threads, one
+// per quarter of the vocabulary (8192 entries: wavefront w of quarter q owns [8192 q + 2048 w, +2048),
+// 64 data registers per lane).  Four such workgroups fit on a CU, so the loads of one overlap the
+// arithmetic of another, and 64 rows x 6 positions give 1536 equal pieces for 1024 resident slots
+// instead of 384 items for 256.  The quarters of an item meet twice through 64-bit words in global
+// memory, each word = (launch epoch << 32 | payload), written and polled with relaxed agent-scope
+// atomics: a reader knows a word is this launch's as soon as the epoch matches, so there are no
+// flags, no fences and nothing to clear between launches (the buffer starts zeroed and epochs only
+// grow).  Sums travel as two floats (hi + lo, 48 bits) so that all four workgroups use identical values.
+//   meeting A: each quarter's maxima m_k and sums z_k = sum exp(x - m_k) of P_j and Q_j.  With
+//              M = max m_k the normaliser is Z = sum_k z_k exp(m_k - M), and an element's probability
+//              is exp(x - m_k) * (exp(m_k - M) / Z): the per-quarter factor is folded into 1/Z, so no
+//              element is touched twice.
+//   meeting B: each quarter's residual mass and sum min(p, q) -> Z_res, the BD term, and the quarter
+//              that holds u Z_res; only that quarter searches (wavefront, chunk, lane, element).
+// The candidate of the position is published as one more tagged word, and the workgroup (quarter 0,
+// bonus position) of every row waits for the row's gamma + 1 candidates and writes N_acc, the
+// emitted token and the mask - no second kernel.
+// Liveness: workgroups are dispatched in id order on every XCD, and a workgroup only waits for
+// workgroups with ids below its own or in its own group of four, so the oldest unfinished item
+// always has everything it waits for resident or done.  The polls are bounded all the same: after
+// spin_limit polls the item is marked failed (token -2) and every wave exits.
+
+constexpr int AS_NT = 256, AS_WAVES = 4, AS_CH = 8, AS_WSEG = AS_CH * 256, AS_Q = 4, AS_QSEG = AS_WAVES * AS_WSEG;
+constexpr int AS_WORDS = 10;                                   // exchange words per quarter
+constexpr int AS_XCHG_BYTES = AS_Q * AS_WORDS * 8;             // per (row, position)
+constexpr uint32_t AS_CAND_ACCEPT = 1u << 30, AS_CAND_FAIL = 1u << 29;
+
+struct AsShared {
+    float fmx[2][AS_WAVES];
+    double dz[2][AS_WAVES];
+    double dw[2][AS_WAVES];
+    int ival[AS_WAVES];
+    float xw[AS_Q][AS_WORDS];
+    int token, fail;
+};
+
+__device__ __forceinline__ void as_put(unsigned long long* slot, uint32_t epoch, uint32_t payload) {
+    __hip_atomic_store(slot, ((unsigned long long)epoch << 32) | (unsigned long long)payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool as_get(const unsigned long long* slot, uint32_t epoch, int spin_limit, uint32_t* payload) {
+    for (int it = 0; it < spin_limit; ++it) {
+        const unsigned long long w = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(w >> 32) == epoch) { *payload = (uint32_t)w; return true; }
+        __builtin_amdgcn_s_sleep(2);
+    }
+    return false;
+}
+
+// Publish NW floats of this quarter (words first .. first + NW) and collect the same words of all four.
+// `mine` must hold the same values in every thread.  Returns false after a timeout (sm.fail is set).
+template <int NW>
+__device__ __forceinline__ bool as_exchange(unsigned long long* slots, int q, uint32_t epoch, const float (&mine)[NW], int first,
+                                            AsShared& sm, int spin_limit) {
+    const int t = (int)threadIdx.x;
+    if (t < NW) as_put(slots + q * AS_WORDS + first + t, epoch, __float_as_uint(mine[t]));
+    if (t < AS_Q * NW) {
+        const int qq = t / NW, ww = t - qq * NW;
+        uint32_t bits = 0;
+        if (as_get(slots + qq * AS_WORDS + first + ww, epoch, spin_limit, &bits)) sm.xw[qq][first + ww] = __uint_as_float(bits);
+        else sm.fail = 1;
+    }
+    __syncthreads();
+    return sm.fail == 0;
+}
+
+__device__ __forceinline__ void as_load(const float* __restrict__ row, int V, int seg0, int lane, float (&x)[AS_CH][4]) {
+#pragma unroll
+    for (int c = 0; c < AS_CH; ++c) {
+        const int idx = seg0 + c * 256 + lane * 4;
+        if (idx < V) {
+            const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(row + idx));
+            x[c][0] = v[0]; x[c][1] = v[1]; x[c][2] = v[2]; x[c][3] = v[3];
+        } else {
+            x[c][0] = x[c][1] = x[c][2] = x[c][3] = -INFINITY;
+        }
+    }
+}
+
+__device__ __forceinline__ float as_thread_max(const float (&x)[AS_CH][4]) {
+    float lm = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < AS_CH; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) lm = fmaxf(lm, x[c][e]);
+    return lm;
+}
+
+// x <- exp((x - mx)/T) in place (mx finite); returns this thread's sum (fp32 inside the thread).
+template <bool UNIT_T>
+__device__ __forceinline__ double as_exp_inplace(float (&x)[AS_CH][4], float mx, double invT) {
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < AS_CH; ++c) {
+        float s4 = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float v = ak_expx<UNIT_T>(x[c][e], mx, invT);
+            x[c][e] = v;
+            s4 += v;
+        }
+        s += s4;
+    }
+    return (double)s;
+}
+
+// Quarter, wavefront, chunk, lane, element holding the target u * Z of the inverse CDF over scale * w.
+// tq[0..4): the quarters' totals in the common scale (identical in all four workgroups); wtot: this quarter's
+// wavefront totals of w (LDS); scale: this quarter's factor.  Only the quarter that holds the target continues;
+// it leaves the token in sm.token.  Returns (workgroup-uniform) whether this workgroup is that quarter.
+// Rounding gaps fall back to the last index with weight, level by level.
+__device__ __forceinline__ bool as_search(const float (&w)[AS_CH][4], const double* wtot, double scale, const double (&tq)[AS_Q],
+                                          double Z, float u, int V, int q, AsShared& sm, int wave, int lane) {
+    const double target = (double)u * Z;
+    int qstar = -1, qlast = 0;
+    double base = 0.0, run = 0.0;
+#pragma unroll
+    for (int k = 0; k < AS_Q; ++k) {
+        if (tq[k] > 0.0) qlast = k;
+        if (qstar < 0) {
+            if (run + tq[k] > target) { qstar = k; base = run; }
+            else run += tq[k];
+        }
+    }
+    bool take_last = false;
+    if (qstar < 0) { qstar = qlast; take_last = true; }
+    if (q != qstar) return false;
+    int wstar = -1, wlast = 0;
+    double wbase = base;
+#pragma unroll
+    for (int k = 0; k < AS_WAVES; ++k) {
+        const double ww = wtot[k] * scale;
+        if (ww > 0.0) wlast = k;
+        if (wstar < 0 && !take_last) {
+            if (wbase + ww > target) wstar = k;
+            else wbase += ww;
+        }
+    }
+    if (wstar < 0) { wstar = wlast; take_last = true; }
+    if (wave == wstar) {   // wave-uniform
+        int cstar = -1, clast = -1;
+        double cb = wbase;
+#pragma unroll
+        for (int c = 0; c < AS_CH; ++c) {
+            const double ct = wave_sum((double)((w[c][0] + w[c][1]) + (w[c][2] + w[c][3]))) * scale;
+            if (ct > 0.0) clast = c;
+            if (cstar < 0 && !take_last) {
+                if (cb + ct > target) cstar = c;
+                else cb += ct;
+            }
+        }
+        if (cstar < 0) { cstar = clast < 0 ? 0 : clast; take_last = true; }
+        float w4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < AS_CH; ++c)
+            if (c == cstar) { w4[0] = w[c][0]; w4[1] = w[c][1]; w4[2] = w[c][2]; w4[3] = w[c][3]; }
+        const double sc = (double)((w4[0] + w4[1]) + (w4[2] + w4[3])) * scale;
+        const double incl = wave_scan_incl(sc, lane);
+        unsigned long long bal = __ballot(take_last ? (sc > 0.0) : (cb + incl > target));
+        if (bal == 0ull) { take_last = true; bal = __ballot(sc > 0.0); }
+        int lstar;
+        if (bal == 0ull) lstar = 0;
+        else lstar = take_last ? (63 - __clzll((long long)bal)) : (__ffsll((long long)bal) - 1);
+        if (lane == lstar) {
+            double acc = cb + incl - sc;
+            int tok = -1, lastpos = -1;
+            const int idx0 = q * AS_QSEG + wave * AS_WSEG + cstar * 256 + lane * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc += (double)w4[e] * scale;
+                if (w4[e] > 0.f) lastpos = idx0 + e;
+                if (tok < 0 && !take_last && acc > target) tok = idx0 + e;
+            }
+            if (tok < 0) tok = lastpos >= 0 ? lastpos : min(idx0, V - 1);
+            sm.token = tok;
+        }
+    }
+    __syncthreads();
+    return true;
+}
+
+template <bool UNIT_T>
+__device__ __forceinline__ void accept_split_item(const float* __restrict__ P, const float* __restrict__ Q,
+                                                  const int32_t* __restrict__ d, int gamma, int V, float T, uint64_t seed,
+                                                  uint32_t round, uint32_t seq0, unsigned long long* __restrict__ cand,
+                                                  double* __restrict__ bd, unsigned long long* __restrict__ xchg, uint32_t epoch,
+                                                  int spin_limit, AsShared& sm) {
+    const int q = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t item = (size_t)b * (gamma + 1) + j;
+    unsigned long long* slots = xchg + item * (AS_Q * AS_WORDS);
+    const float* Prow = P + item * V;
+    const bool has_q = j < gamma;
+    const float* Qrow = has_q ? Q + ((size_t)b * gamma + j) * V : nullptr;
+    const int dtok = has_q ? min(max(d[(size_t)b * gamma + j], 0), V - 1) : -1;   // clamped: stays in bounds for any input
+    const int seg0 = q * AS_QSEG + wave * AS_WSEG;
+    float xp[AS_CH][4], xq[AS_CH][4];
+    as_load(Prow, V, seg0, lane, xp);
+    auto fail_out = [&]() { if (threadIdx.x == 0) as_put(cand + item, epoch, AS_CAND_FAIL); };
+    if (T <= 0.f) {   // greedy: argmax with the lowest index on ties
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int c = 0; c < AS_CH; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int idx = seg0 + c * 256 + lane * 4 + e;
+                if (xp[c][e] > bv) { bv = xp[c][e]; bi = idx; }
+            }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(bv, o, 64);
+            const int oi = __shfl_xor(bi, o, 64);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        if (lane == 0) { sm.fmx[0][wave] = bv; sm.ival[wave] = bi; }
+        __syncthreads();
+        float rv = sm.fmx[0][0];
+        int ri = sm.ival[0];
+#pragma unroll
+        for (int k = 1; k < AS_WAVES; ++k)
+            if (sm.fmx[0][k] > rv || (sm.fmx[0][k] == rv && sm.ival[k] < ri)) { rv = sm.fmx[0][k]; ri = sm.ival[k]; }
+        const float mine[2] = {rv, __int_as_float(ri)};
+        if (!as_exchange<2>(slots, q, epoch, mine, 0, sm, spin_limit)) { fail_out(); return; }
+        if (q == 0 && threadIdx.x == 0) {
+            float gv = sm.xw[0][0];
+            int gi = __float_as_int(sm.xw[0][1]);
+            for (int k = 1; k < AS_Q; ++k) {
+                const float ov = sm.xw[k][0];
+                const int oi = __float_as_int(sm.xw[k][1]);
+                if (ov > gv || (ov == gv && oi < gi)) { gv = ov; gi = oi; }
+            }
+            const bool acc = has_q ? (dtok == gi) : true;
+            as_put(cand + item, epoch, (acc ? AS_CAND_ACCEPT : 0u) | (uint32_t)gi);
+            if (has_q && bd) bd[(size_t)b * gamma + j] = acc ? 1.0 : 0.0;
+        }
+        return;
+    }
+    const double invT = 1.0 / (double)T;
+    if (has_q) as_load(Qrow, V, seg0, lane, xq);
+    float pdl = 0.f, qdl = 0.f;
+    if (has_q) { pdl = Prow[dtok]; qdl = Qrow[dtok]; }
+    // ---- local maxima
+    {
+        const float a = wave_max(as_thread_max(xp));
+        const float c = has_q ? wave_max(as_thread_max(xq)) : -INFINITY;
+        if (lane == 0) { sm.fmx[0][wave] = a; sm.fmx[1][wave] = c; }
+    }
+    __syncthreads();
+    float lmp = sm.fmx[0][0], lmq = sm.fmx[1][0];
+#pragma unroll
+    for (int k = 1; k < AS_WAVES; ++k) { lmp = fmaxf(lmp, sm.fmx[0][k]); lmq = fmaxf(lmq, sm.fmx[1][k]); }
+    // a quarter beyond the vocabulary (or fully masked) has no maximum: it exponentiates against 0 and contributes nothing
+    const float emp = lmp > -INFINITY ? lmp : 0.f, emq = lmq > -INFINITY ? lmq : 0.f;
+    // ---- local exp and sums
+    {
+        const double a = wave_sum(as_exp_inplace<UNIT_T>(xp, emp, invT));
+        const double c = has_q ? wave_sum(as_exp_inplace<UNIT_T>(xq, emq, invT)) : 0.0;
+        if (lane == 0) { sm.dz[0][wave] = a; sm.dz[1][wave] = c; }
+    }
+    __syncthreads();
+    // ---- meeting A
+    double zpq[AS_Q], Zp = 0.0, Zq = 0.0, sp_mine, sq_mine;
+    float mp, mq;
+    {
+        double lp = 0.0, lq = 0.0;
+#pragma unroll
+        for (int k = 0; k < AS_WAVES; ++k) { lp += sm.dz[0][k]; lq += sm.dz[1][k]; }
+        const float ph = (float)lp, qh = (float)lq;
+        const float mine[6] = {lmp, lmq, ph, (float)(lp - (double)ph), qh, (float)(lq - (double)qh)};
+        if (!as_exchange<6>(slots, q, epoch, mine, 0, sm, spin_limit)) { fail_out(); return; }
+        mp = fmaxf(fmaxf(sm.xw[0][0], sm.xw[1][0]), fmaxf(sm.xw[2][0], sm.xw[3][0]));
+        mq = fmaxf(fmaxf(sm.xw[0][1], sm.xw[1][1]), fmaxf(sm.xw[2][1], sm.xw[3][1]));
+        sp_mine = 0.0; sq_mine = 0.0;
+#pragma unroll
+        for (int k = 0; k < AS_Q; ++k) {
+            // factor of quarter k: exp((m_k - M)/T); 0 for a quarter without a maximum
+            const double sp = sm.xw[k][0] > -INFINITY ? (double)ak_expx<UNIT_T>(sm.xw[k][0], mp, invT) : 0.0;
+            const double sq = sm.xw[k][1] > -INFINITY ? (double)ak_expx<UNIT_T>(sm.xw[k][1], mq, invT) : 0.0;
+            zpq[k] = ((double)sm.xw[k][2] + (double)sm.xw[k][3]) * sp;
+            Zp += zpq[k];
+            Zq += ((double)sm.xw[k][4] + (double)sm.xw[k][5]) * sq;
+            if (k == q) { sp_mine = sp; sq_mine = sq; }
+        }
+    }
+    const float u_res = philox_uniform(seed, seq0 + (uint32_t)b, round, 0u, 1u);
+    if (!has_q) {   // bonus position: draw from p
+        if (as_search(xp, sm.dz[0], sp_mine, zpq, Zp, u_res, V, q, sm, wave, lane) && threadIdx.x == 0)
+            as_put(cand + item, epoch, AS_CAND_ACCEPT | (uint32_t)sm.token);
+        return;
+    }
+    const double ipz = sp_mine / Zp, iqz = sq_mine / Zq;      // this quarter's exp(m_k - M) / Z
+    const float ip_hi = (float)ipz, ip_lo = (float)(ipz - (double)ip_hi);
+    const float iq_hi = (float)iqz, iq_lo = (float)(iqz - (double)iq_hi);
+    bool accept = true;
+    {
+        const double pd = (double)ak_expx<UNIT_T>(pdl, mp, invT) / Zp, qd = (double)ak_expx<UNIT_T>(qdl, mq, invT) / Zq;
+        if (qd > 0.0) {
+            const double ratio = pd / qd;
+            const float u_acc = philox_uniform(seed, seq0 + (uint32_t)b, round, (uint32_t)j, 0u);
+            accept = (double)u_acc < (ratio < 1.0 ? ratio : 1.0);
+        }
+    }
+    // ---- residual weights max(0, p - q) (kept in xq) and sum min(p, q)
+    {
+        float fw = 0.f, fm = 0.f;
+#pragma unroll
+        for (int c = 0; c < AS_CH; ++c) {
+            float mn4 = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float pv = fmaf(xp[c][e], ip_lo, xp[c][e] * ip_hi), qv = fmaf(xq[c][e], iq_lo, xq[c][e] * iq_hi);
+                mn4 += fminf(pv, qv);
+                xq[c][e] = fmaxf(pv - qv, 0.f);
+            }
+            fw += (xq[c][0] + xq[c][1]) + (xq[c][2] + xq[c][3]);
+            fm += mn4;
+        }
+        const double tw = wave_sum((double)fw), tm = wave_sum((double)fm);
+        if (lane == 0) { sm.dw[0][wave] = tw; sm.dw[1][wave] = tm; }
+    }
+    __syncthreads();
+    // ---- meeting B
+    double zrq[AS_Q], Zr = 0.0, bdj = 0.0;
+    {
+        double lr = 0.0, lm = 0.0;
+#pragma unroll
+        for (int k = 0; k < AS_WAVES; ++k) { lr += sm.dw[0][k]; lm += sm.dw[1][k]; }
+        const float rh = (float)lr, mh = (float)lm;
+        const float mine[4] = {rh, (float)(lr - (double)rh), mh, (float)(lm - (double)mh)};
+        if (!as_exchange<4>(slots, q, epoch, mine, 6, sm, spin_limit)) { fail_out(); return; }
+#pragma unroll
+        for (int k = 0; k < AS_Q; ++k) {
+            zrq[k] = (double)sm.xw[k][6] + (double)sm.xw[k][7];
+            Zr += zrq[k];
+            bdj += (double)sm.xw[k][8] + (double)sm.xw[k][9];
+        }
+    }
+    bool mine_wins;
+    if (Zr > 0.0) mine_wins = as_search(xq, sm.dw[0], 1.0, zrq, Zr, u_res, V, q, sm, wave, lane);
+    else mine_wins = as_search(xp, sm.dz[0], sp_mine, zpq, Zp, u_res, V, q, sm, wave, lane);   // p == q: draw from p
+    if (mine_wins && threadIdx.x == 0) {
+        if (bd) bd[(size_t)b * gamma + j] = bdj;
+        as_put(cand + item, epoch, (accept ? AS_CAND_ACCEPT : 0u) | (uint32_t)sm.token);
+    }
+}
+
+// grid (4 quarters, gamma + 1 positions, rows), block 256.  cand: one tagged word per (row, position);
+// xchg: AS_XCHG_BYTES per (row, position); both zero-filled before their first use.
+__global__ __launch_bounds__(AS_NT) void accept_split_kernel(const float* __restrict__ P, const float* __restrict__ Q,
+                                                             const int32_t* __restrict__ d, int gamma, int V, float T,
+                                                             uint64_t seed, uint32_t round, uint32_t seq0,
+                                                             unsigned long long* __restrict__ cand, double* __restrict__ bd,
+                                                             unsigned long long* __restrict__ xchg, uint32_t epoch, int spin_limit,
+                                                             int32_t* __restrict__ n_acc, int32_t* __restrict__ token,
+                                                             uint32_t* __restrict__ mask, int32_t* __restrict__ hist, int l) {
+    __shared__ AsShared sm;
+    if (threadIdx.x == 0) { sm.token = -1; sm.fail = 0; }
+    if (T == 1.0f) accept_split_item<true>(P, Q, d, gamma, V, T, seed, round, seq0, cand, bd, xchg, epoch, spin_limit, sm);
+    else accept_split_item<false>(P, Q, d, gamma, V, T, seed, round, seq0, cand, bd, xchg, epoch, spin_limit, sm);
+    // ---- per row: first failed test, emitted token, mask (one thread of the bonus position's first quarter)
+    if (blockIdx.x == 0 && (int)blockIdx.y == gamma && threadIdx.x == 0) {
+        const int b = blockIdx.z;
+        int n = gamma, tok = -2;
+        uint32_t mk = 0, cn = 0;
+        bool ok = true;
+        for (int j = gamma; j >= 0 && ok; --j) {
+            uint32_t w = 0;
+            ok = as_get(cand + (size_t)b * (gamma + 1) + j, epoch, spin_limit, &w) && !(w & AS_CAND_FAIL);
+            if (!ok) break;
+            if (j == gamma) { cn = w; continue; }
+            if (w & AS_CAND_ACCEPT) mk |= 1u << j;
+            else { n = j; cn = w; }
+        }
+        if (ok) tok = (int)(cn & 0x1fffffffu);
+        else { n = 0; mk = 0; }
+        n_acc[b] = n;
+        token[b] = tok;
+        if (mask) mask[b] = mk;
+        if (hist && tok >= 0) hist[l + n] = tok;
+    }
+}
+
 // Per row: N_acc = first failed test, emitted token = candidate of that position, mask bits.
 // hist (optional): hist[b*hist_stride + l + n] = token  (commit of the emitted token).
 __global__ void accept_finalize_kernel(const int2* __restrict__ cand, int rows, int gamma, int32_t* __restrict__ n_acc,
@@ -1274,7 +1658,7 @@ __global__ void accept_finalize_kernel(const int2* __restrict__ cand, int rows, 
     n_acc[b] = n;
     token[b] = tok;
     if (mask) mask[b] = mk;
-    if (hist) hist[l + n] = tok;
+    if (hist && tok >= 0) hist[l + n] = tok;
 }
 
 // Token draw from one row of logits: argmax (T = 0) or inverse CDF of softmax(logits / T) with the

@@ -6,6 +6,7 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -102,7 +103,7 @@ const char* check_model(const metasd_model_desc& d, const char* who, char* buf, 
 
 // Workspace layout shared by metasd_workspace_bytes and metasd_create.
 struct Layout {
-    size_t hist, h, h2, xn, part, part2, q, ao, act, apart, rope, P, Q, cand, bd, res, draft, bar, tables, table_stride, total;
+    size_t hist, h, h2, xn, part, part2, q, ao, act, apart, rope, P, Q, cand, bd, res, draft, bar, xchg, tables, table_stride, total;
 };
 
 Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const metasd_model_desc* dr) {
@@ -146,6 +147,7 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     L.res = take(64);
     L.draft = take(64);
     L.bar = take(sizeof(GridBar));
+    L.xchg = take((size_t)(c.gamma_max + 1) * AS_XCHG_BYTES);
     int lmax = t.n_layers;
     for (int k = 0; k < c.K; ++k) lmax = std::max(lmax, dr[k].n_layers);
     L.table_stride = align_up((size_t)(1 + PER_LAYER * lmax + 2) * sizeof(void*));
@@ -357,6 +359,7 @@ struct metasd_ctx {
     float* d_h() const { return reinterpret_cast<float*>(ws + lay.h); }
     void* d_xn() const { return ws + lay.xn; }
     float* d_part() const { return reinterpret_cast<float*>(ws + lay.part); }
+    unsigned long long* d_xchg() const { return reinterpret_cast<unsigned long long*>(ws + lay.xchg); }
     float* d_part_pp(int i) const { return reinterpret_cast<float*>(ws + (i ? lay.part2 : lay.part)); }
     float* d_h_pp(int i) const { return reinterpret_cast<float*>(ws + (i ? lay.h2 : lay.h)); }
     void* d_q() const { return ws + lay.q; }
@@ -734,9 +737,29 @@ int launch_sample(hipStream_t st, const float* logits, int rows, int V, float T,
     return hipGetLastError() == hipSuccess ? 0 : METASD_E_HIP;
 }
 
+// Launch epoch of the split accept kernel's exchange words: unique per launch in this process, never 0.
+uint32_t next_epoch() {
+    static std::atomic<uint32_t> e{0};
+    uint32_t v = ++e;
+    if (v == 0) v = ++e;
+    return v;
+}
+bool accept_split_enabled() {
+    static const bool on = env_int("METASD_ACCEPT_SPLIT", 1) != 0;
+    return on;
+}
+
+// xchg != nullptr: four workgroups per (row, position) (accept_split_kernel); else one (accept_rows_kernel).
 int launch_accept(hipStream_t st, const float* P, const float* Q, const int32_t* d, int rows, int gamma, int V, float T,
                   uint64_t seed, uint32_t round, uint32_t seq0, int2* cand, double* bd, int32_t* n_acc, int32_t* token,
-                  uint32_t* mask, int32_t* hist, int l, hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr) {
+                  uint32_t* mask, int32_t* hist, int l, unsigned long long* xchg, hipEvent_t ev_begin = nullptr,
+                  hipEvent_t ev_end = nullptr) {
+    if (xchg && accept_split_enabled()) {   // one launch: the kernel also writes N_acc, the token and the mask
+        hipExtLaunchKernelGGL(accept_split_kernel, dim3(AS_Q, gamma + 1, rows), dim3(AS_NT), 0u, st, ev_begin, ev_end, 0u, P, Q, d, gamma,
+                              V, T, seed, round, seq0, (unsigned long long*)cand, bd, xchg, next_epoch(), 1 << 18, n_acc, token, mask,
+                              hist, l);
+        return hipGetLastError() == hipSuccess ? 0 : METASD_E_HIP;
+    }
     hipExtLaunchKernelGGL(accept_rows_kernel, dim3(gamma + 1, rows), dim3(AK_NT), 0u, st, ev_begin, ev_end, 0u, P, Q, d, gamma, V,
                           T, seed, round, seq0, cand, bd);
     if (hipGetLastError() != hipSuccess) return METASD_E_HIP;
@@ -886,6 +909,8 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
     c->target.d_table = (const void**)(c->ws + lay.tables);
     for (int k = 0; k < cfg->K; ++k) c->drafters[k].d_table = (const void**)(c->ws + lay.tables + lay.table_stride * (size_t)(k + 1));
     e = hipMemsetAsync(c->d_bar(), 0, sizeof(GridBar), c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->d_xchg(), 0, (size_t)(cfg->gamma_max + 1) * AS_XCHG_BYTES, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->d_cand(), 0, (size_t)(cfg->gamma_max + 1) * sizeof(int2), c->stream);
     if (e == hipSuccess) e = hipMemcpyAsync((void*)c->target.d_table, c->target.w.data(), c->target.w.size() * sizeof(void*), hipMemcpyHostToDevice, c->stream);
     for (int k = 0; k < cfg->K && e == hipSuccess; ++k)
         e = hipMemcpyAsync((void*)c->drafters[k].d_table, c->drafters[k].w.data(), c->drafters[k].w.size() * sizeof(void*), hipMemcpyHostToDevice, c->stream);
@@ -1020,7 +1045,7 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_ACCEPT, (double)(2 * gamma + 1) * V * 4);
     if (launch_accept(c->stream, c->d_P(), c->d_Q(), c->d_hist() + l, 1, gamma, V, c->cfg.temperature, c->cfg.seed,
                       (uint32_t)c->round, 0u, c->d_cand(), c->d_bd(), res, res + 1, (uint32_t*)(res + 2), c->d_hist(), l,
-                      pr ? pr->a : nullptr, pr ? pr->b : nullptr))
+                      c->d_xchg(), pr ? pr->a : nullptr, pr ? pr->b : nullptr))
         return c->fail(METASD_E_HIP, "launch accept kernels failed");
     HostResult* hr = c->hres;
     HIP_TRY(c, hipMemcpyAsync(&hr->n_acc, res, 12, hipMemcpyDeviceToHost, c->stream));
@@ -1034,6 +1059,7 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
         return c->fail(METASD_E_HIP, "persistent forward: a device-wide barrier timed out; call metasd_set_context to start over");
     }
     const int n = hr->n_acc;
+    if (hr->token == -2) { c->phase = PH_NONE; return c->fail(METASD_E_HIP, "accept: the workgroups of a position did not meet (exchange timed out); call metasd_set_context to start over"); }
     if (n < 0 || n > gamma || hr->token < 0 || hr->token >= V) return c->fail(METASD_E_HIP, "accept: device returned n_acc %d token %d", n, hr->token);
     for (int j = 0; j < n; ++j) c->hist[l + j] = hr->d[j];
     c->hist[l + n] = hr->token;
@@ -1063,8 +1089,10 @@ int32_t metasd_accept_logits(const float* P, const float* Q, const int32_t* d, i
     if (!P || !Q || !d || !n_acc || !token || !scratch) return fail_global(METASD_E_INVALID, "accept_logits: NULL pointer");
     if (rows < 1 || rows > 65535 || gamma < 1 || gamma > 31 || !valid_vocab(V) || !(temperature >= 0.f))
         return fail_global(METASD_E_INVALID, "accept_logits: rows 1..65535, gamma 1..31, V %% 4 == 0, V <= 32768, T >= 0");
+    // scratch: [rows (gamma+1)] candidates of 16 bytes, then the exchange words of the split kernel
+    unsigned long long* xchg = (unsigned long long*)((char*)scratch + (size_t)rows * (gamma + 1) * 16);
     if (launch_accept((hipStream_t)hip_stream, P, Q, d, rows, gamma, V, temperature, seed, round, seq0, (int2*)scratch, bd, n_acc,
-                      token, mask, nullptr, 0))
+                      token, mask, nullptr, 0, xchg))
         return fail_global(METASD_E_HIP, "accept_logits: launch failed");
     return METASD_OK;
 }
