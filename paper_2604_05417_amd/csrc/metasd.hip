@@ -756,7 +756,8 @@ int launch_accept(hipStream_t st, const float* P, const float* Q, const int32_t*
                   hipEvent_t ev_end = nullptr) {
     if (xchg && accept_split_enabled()) {   // one launch: the kernel also writes N_acc, the token and the mask
         hipExtLaunchKernelGGL(accept_split_kernel, dim3(AS_Q, gamma + 1, rows), dim3(AS_NT), 0u, st, ev_begin, ev_end, 0u, P, Q, d, gamma,
-                              V, T, seed, round, seq0, (unsigned long long*)cand, bd, xchg, next_epoch(), 1 << 18, n_acc, token, mask,
+                              V, T, seed, round, seq0, (unsigned long long*)cand, bd, xchg, next_epoch(),
+                              std::max(0, env_int("METASD_ACCEPT_SPIN_LIMIT", 1 << 18)), n_acc, token, mask,
                               hist, l);
         return hipGetLastError() == hipSuccess ? 0 : METASD_E_HIP;
     }

@@ -130,3 +130,23 @@ def test_bad_arguments():
     out = M.accept_logits(P, P[:, :1].contiguous(), torch.full((1, 1), 999, dtype=torch.int32, device="cuda"), 1.0, 1)
     torch.cuda.synchronize()
     assert 0 <= int(out["token"][0]) < 16
+
+
+def test_accept_bounded_wait_reports_failure_and_recovers(monkeypatch):
+    """The four workgroups of a position meet through memory with bounded polls.  With the bound forced to
+    zero from the host every poll gives up at once: all waves exit, every row reports token -2, nothing
+    hangs; the next call with the normal bound and the same scratch buffer is correct again."""
+    c = W.config2(1.0, rows=8, device="cuda")
+    P, Q = c["P"], c["Q"]
+    d = torch.stack([M.sample_logits(Q[:, j].contiguous(), 1.0, 1, 0, j, 0) for j in range(c["gamma"])], 1).contiguous()
+    good = M.accept_logits(P, Q, d, 1.0, 1, 0, 0)
+    torch.cuda.synchronize()
+    ref_tok, ref_n = good["token"].clone(), good["n_acc"].clone()
+    monkeypatch.setenv("METASD_ACCEPT_SPIN_LIMIT", "0")
+    bad = M.accept_logits(P, Q, d, 1.0, 1, 0, 0, out=good)
+    torch.cuda.synchronize()
+    assert (bad["token"] == -2).all()
+    monkeypatch.delenv("METASD_ACCEPT_SPIN_LIMIT")
+    again = M.accept_logits(P, Q, d, 1.0, 1, 0, 0, out=good)
+    torch.cuda.synchronize()
+    assert torch.equal(again["token"], ref_tok) and torch.equal(again["n_acc"], ref_n)
