@@ -576,9 +576,10 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
 // activation and the attention combine folded into the prologue of the GEMM that consumes them -
 // 6 launches per layer instead of 10.  The residual stream and the partials ping-pong between two
 // buffers, because a GEMM's workgroups read the old ones while others already write the new ones.
+int fused_max_rows() { static const int v = std::max(1, std::min(env_int("METASD_FUSE_ROWS", 4), 8)); return v; }
 bool fused_small_ok(const Model& M, int m) {
     const metasd_model_desc& d = M.d;
-    return d.dtype == METASD_BF16 && m <= 4 && d.d_model <= 1024 && d.d_ffn <= 4096 && M.hd >= 64;
+    return d.dtype == METASD_BF16 && m <= fused_max_rows() && d.d_model <= 1024 && d.d_ffn <= 4096 && M.hd >= 64;
 }
 
 int forward_rows_fused(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int first_row) {
