@@ -121,3 +121,15 @@ def test_one_launch_forward_opt_in(i, monkeypatch):
     cfg["max_ctx"] = s["prompt"] + 80
     st = run_lockstep(cfg, 1.0, rounds=4, kv_prefilled=False)
     assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+
+
+def test_long_context_small_models():
+    """More than 32 attention chunks (context 4300): the fused attention-combine prologue of the drafters'
+    output projection walks the chunk records beyond its first batch; synthetic KV prefix, T = 1."""
+    s = SMALL[0]
+    cfg = W.config4(n_layers=s["n_layers"], ctx=4300, n_new=64, K=2, d_model=s["d_model"], n_heads=s["n_heads"],
+                    d_ffn=s["d_ffn"], vocab=s["vocab"], dd_model=s["dd_model"], dn_heads=s["dn_heads"], dd_ffn=s["dd_ffn"], device="cuda")
+    cfg["gamma"] = 3                       # verify blocks of 4 rows: the target takes the fused-prologue path too
+    cfg["max_ctx"] = 4300 + 64
+    st = run_lockstep(cfg, 1.0, rounds=4, kv_prefilled=True, device="cuda")
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
