@@ -48,7 +48,7 @@ def main():
     ap.add_argument("--ctx", type=int, default=2048)
     ap.add_argument("--layers", type=int, default=32, help="target layers (32 = the 7B shape; fewer is NOT the benchmark)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rounds", type=int, default=3)
+    ap.add_argument("--cpu-rounds", type=int, default=8)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (one process, no collectives); use --gpus 1")

@@ -65,6 +65,24 @@ __device__ __forceinline__ double wave_scan_incl(double v, int lane) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Tagged words: how workgroups of one launch hand small results to each other through global memory.
+// A word is (launch epoch << 32 | 32-bit payload), written and polled with relaxed agent-scope atomics
+// (they go through to memory, past the per-XCD L2).  The reader knows a word belongs to this launch as
+// soon as the epoch matches: no flag, no fence, and nothing to clear between launches - the buffer is
+// zeroed once and epochs only grow.  Polls are bounded; the caller decides what a timeout means.
+__device__ __forceinline__ void tw_put(unsigned long long* slot, uint32_t epoch, uint32_t payload) {
+    __hip_atomic_store(slot, ((unsigned long long)epoch << 32) | (unsigned long long)payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool tw_get(const unsigned long long* slot, uint32_t epoch, int spin_limit, uint32_t* payload) {
+    for (int it = 0; it < spin_limit; ++it) {
+        const unsigned long long w = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(w >> 32) == epoch) { *payload = (uint32_t)w; return true; }
+        __builtin_amdgcn_s_sleep(2);
+    }
+    return false;
+}
+
+// ------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC'11)
 // counter (c0..c3), key = 64-bit seed; ten rounds, Weyl-sequence key schedule.
 
@@ -185,11 +203,14 @@ __global__ __launch_bounds__(1024) void addnorm_kernel(float* __restrict__ h, co
 }
 
 // out[i] = sum_s part[s][i]                         (only for logits when the head GEMM is split)
-__global__ void sum_partials_kernel(const float* __restrict__ part, int nsplit, size_t sstride, size_t n, float* __restrict__ out) {
+// inv (optional): 1/rms per row, N columns per row (the GEMM ran on an input that was not yet normalised)
+__global__ void sum_partials_kernel(const float* __restrict__ part, int nsplit, size_t sstride, size_t n, float* __restrict__ out,
+                                    const float* __restrict__ inv, int N) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     float y = 0.f;
     for (int s = 0; s < nsplit; ++s) y += part[(size_t)s * sstride + i];
+    if (inv) y *= inv[i / (size_t)N];
     out[i] = y;
 }
 
@@ -265,7 +286,8 @@ enum { PRO_PLAIN = 0, PRO_NORM = 1, PRO_ACT = 2, PRO_COMBINE = 3 };
 
 struct GemmPro {
     const float* src;      // NORM: h_in [m][K];  ACT: partials [s][m][(1|2) K];  COMBINE: attention partials
-                           // (PLAIN: unused; sstride = offset in elements from the hi array x to the lo array)
+                           // (PLAIN: sstride = offset in elements from the hi array x to the lo array; optional:
+                           //  src = sums of squares [ns tile groups][16], h_out = 1/rms per row [m], eps)
     const float* part;     // NORM: partials [s][m][K] of the previous GEMM (ns may be 0)
     float* h_out;          // NORM: updated residual stream [m][K]
     const bf16_t* gain;    // NORM
@@ -276,12 +298,34 @@ struct GemmPro {
     int nchunks, hd;       // COMBINE: attention chunks, head dim
 };
 
-template <int PRO>
+// Epilogue variant for the two projections that feed the residual stream (attention output, FFN down):
+// EPI_RESIDUAL.  The split-K siblings of a tile group (consecutive workgroup ids ks = 0 .. ksplit-1) do not
+// leave their partial sums to a later kernel: siblings 0 .. ksplit-2 publish them as tagged words, and the
+// last sibling adds them in the order s = 0, 1, .. (its own last), then
+//     h += sum;   xg = h * gain -> the two-bf16 form the next GEMM stages (not yet normalised);
+//     ssq[tile group][row] = sum of h^2 over the group's 64 columns.
+// RMSNorm's 1/rms commutes with the next GEMM, so that GEMM runs on h * gain and the kernels that
+// consume its output scale by 1/sqrt(sum_groups ssq / D + eps): the add+norm kernel disappears from
+// the chain.  The last sibling only waits for workgroups with lower ids; a timeout sets *abort.
+enum { EPI_PARTIALS = 0, EPI_RESIDUAL = 1 };
+
+struct GemmEpi {
+    unsigned long long* xw;   // tagged words [ksplit - 1][m][N]
+    float* h;                 // residual stream [m][N], updated in place
+    const bf16_t* gain;       // gain of the norm that follows [N]
+    float* xsplit;            // h * gain as two bf16 arrays (hi [m][N], then lo [m][N])
+    float* ssq;               // [ceil(ntiles / tpb)][16]
+    int* abort;
+    uint32_t epoch;
+    int spin_limit;
+};
+
+template <int PRO, int EPI = EPI_PARTIALS>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict__ x, int ldx, int m, int K,
                                                         const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
                                                         const bf16_t* __restrict__ W2, int t0, int t1, int ntiles,
                                                         float* __restrict__ out, int N, int ksplit, int cps, int tpb,
-                                                        GemmPro pro) {
+                                                        GemmPro pro, GemmEpi epi) {
     extern __shared__ uint4 xs[];   // [2 (hi, lo)][m][rs]  (+ [m][K] floats for PRO_NORM)
     const int kchunks = K >> 5;
     const int ks = blockIdx.x % ksplit, tg = blockIdx.x / ksplit;
@@ -323,6 +367,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict_
         xlo[r * rs + c] = make_uint4(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]), pack_bf16x2(lo[4], lo[5]), pack_bf16x2(lo[6], lo[7]));
     };
     if constexpr (PRO == PRO_PLAIN) {
+        // When the input is h * gain of a residual epilogue (not yet normalised), workgroup 0 also turns the
+        // per-tile-group sums of squares into 1/rms per row for the kernels that consume this GEMM's output.
+        if (pro.src && blockIdx.x == 0 && wave == 0) {
+            for (int r = 0; r < m; ++r) {
+                float t = 0.f;
+                for (int i = lane; i < pro.ns; i += 64) t += pro.src[i * 16 + r];
+                t = wave_sum(t);
+                if (lane == 0) pro.h_out[r] = 1.0f / sqrtf(t / (float)K + pro.eps);
+            }
+        }
         // Order of the requests (a wavefront's loads return in order): first the activations of this
         // workgroup's slice (L2 hits, needed first), then the first KiBs of the weight stream, which
         // stay in flight while the activations are converted and written to LDS.
@@ -511,33 +565,105 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict_
             acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, al), acl, 0, 0, 0);
         }
     };
+    __shared__ float epi_red[4][16];
     for (int tt = wave; tt < tpb; tt += 4) {
         const int t = tg * tpb + tt;
-        if (t >= ntiles) break;
-        if (tt != wave) {
+        const bool live_tile = t < ntiles;
+        if (!live_tile && EPI == EPI_PARTIALS) break;
+        if (tt != wave && live_tile) {
             wp = tile_base(t);
             issue(wa, wp, 0);
         }
         acc = f32x4{0.f, 0.f, 0.f, 0.f};
         acl = f32x4{0.f, 0.f, 0.f, 0.f};
-        // two register buffers: the next group of tiles is in flight while this one is multiplied
-        int gi = 0;
-        for (; gi + 2 < ngroups; gi += 2) {
-            issue(wb, wp, gi + 1);
-            multiply(wa, gi);
-            issue(wa, wp, gi + 2);
-            multiply(wb, gi + 1);
+        if (live_tile) {
+            // two register buffers: the next group of tiles is in flight while this one is multiplied
+            int gi = 0;
+            for (; gi + 2 < ngroups; gi += 2) {
+                issue(wb, wp, gi + 1);
+                multiply(wa, gi);
+                issue(wa, wp, gi + 2);
+                multiply(wb, gi + 1);
+            }
+            if (gi + 2 == ngroups) {
+                issue(wb, wp, gi + 1);
+                multiply(wa, gi);
+                multiply(wb, gi + 1);
+            } else {
+                multiply(wa, gi);
+            }
         }
-        if (gi + 2 == ngroups) {
-            issue(wb, wp, gi + 1);
-            multiply(wa, gi);
-            multiply(wb, gi + 1);
+        const float4 mine = make_float4(acc[0] + acl[0], acc[1] + acl[1], acc[2] + acl[2], acc[3] + acl[3]);
+        if constexpr (EPI == EPI_PARTIALS) {
+            if (rowok) {
+                float* o = out + (size_t)ks * m * N + (size_t)row * N + (size_t)t * 16 + g * 4;
+                *reinterpret_cast<float4*>(o) = mine;
+            }
         } else {
-            multiply(wa, gi);
+            const size_t col = (size_t)t * 16 + g * 4;
+            const bool own = rowok && live_tile;
+            if (ks < ksplit - 1) {                     // publish this sibling's partial tile
+                if (own) {
+                    unsigned long long* dst = epi.xw + ((size_t)ks * m + row) * N + col;
+                    tw_put(dst + 0, epi.epoch, __float_as_uint(mine.x));
+                    tw_put(dst + 1, epi.epoch, __float_as_uint(mine.y));
+                    tw_put(dst + 2, epi.epoch, __float_as_uint(mine.z));
+                    tw_put(dst + 3, epi.epoch, __float_as_uint(mine.w));
+                }
+            } else {                                   // last sibling: reduce, residual, gain, sum of squares
+                float ss = 0.f;
+                if (own) {
+                    float4 hv = *reinterpret_cast<const float4*>(epi.h + (size_t)row * N + col);
+                    float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
+                    bool ok = true;
+                    for (int sb0 = 0; sb0 < ksplit - 1 && ok; sb0 += 8) {      // up to eight siblings (32 words) in flight
+                        const int nb = min(8, ksplit - 1 - sb0);
+                        unsigned long long w[8][4];
+                        ok = false;
+                        for (int it = 0; it < epi.spin_limit && !ok; ++it) {
+                            ok = true;
+#pragma unroll
+                            for (int u = 0; u < 8; ++u) {
+                                const unsigned long long* src = epi.xw + ((size_t)(sb0 + min(u, nb - 1)) * m + row) * N + col;
+#pragma unroll
+                                for (int v = 0; v < 4; ++v) w[u][v] = __hip_atomic_load(src + v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            }
+#pragma unroll
+                            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                                for (int v = 0; v < 4; ++v) ok = ok && (uint32_t)(w[u][v] >> 32) == epi.epoch;
+                            if (!ok) __builtin_amdgcn_s_sleep(2);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            if (u < nb) {
+                                y.x += __uint_as_float((uint32_t)w[u][0]); y.y += __uint_as_float((uint32_t)w[u][1]);
+                                y.z += __uint_as_float((uint32_t)w[u][2]); y.w += __uint_as_float((uint32_t)w[u][3]);
+                            }
+                    }
+                    if (!ok) __hip_atomic_store(epi.abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    y.x += mine.x; y.y += mine.y; y.z += mine.z; y.w += mine.w;
+                    hv.x += y.x; hv.y += y.y; hv.z += y.z; hv.w += y.w;
+                    *reinterpret_cast<float4*>(epi.h + (size_t)row * N + col) = hv;
+                    const uint2 gn = *reinterpret_cast<const uint2*>(epi.gain + col);
+                    const float4 xg = make_float4(hv.x * bf2f((bf16_t)(gn.x & 0xffffu)), hv.y * bf2f((bf16_t)(gn.x >> 16)),
+                                                  hv.z * bf2f((bf16_t)(gn.y & 0xffffu)), hv.w * bf2f((bf16_t)(gn.y >> 16)));
+                    store_split4(epi.xsplit, (size_t)m * N, (size_t)row * N + col, xg);
+                    ss = hv.x * hv.x + hv.y * hv.y + hv.z * hv.z + hv.w * hv.w;
+                }
+                ss += __shfl_xor(ss, 16, 64);
+                ss += __shfl_xor(ss, 32, 64);
+                if (g == 0) epi_red[wave][row] = ss;   // 16 columns of this wavefront's tile
+            }
         }
-        if (rowok) {
-            float* o = out + (size_t)ks * m * N + (size_t)row * N + (size_t)t * 16 + g * 4;
-            *reinterpret_cast<float4*>(o) = make_float4(acc[0] + acl[0], acc[1] + acl[1], acc[2] + acl[2], acc[3] + acl[3]);
+    }
+    if constexpr (EPI == EPI_RESIDUAL) {
+        if (ks == ksplit - 1) {                        // workgroup-uniform
+            __syncthreads();
+            if (threadIdx.x < 16) {
+                const int r = (int)threadIdx.x;
+                epi.ssq[(size_t)tg * 16 + r] = (epi_red[0][r] + epi_red[1][r]) + (epi_red[2][r] + epi_red[3][r]);
+            }
         }
     }
 }
@@ -586,7 +712,7 @@ __global__ void rope_table_kernel(int pos0, int hd, float theta, double2* __rest
 template <typename T>
 __global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int N, int pos0, int H, int KH,
                                int hd, const double2* __restrict__ tab, float* __restrict__ q, T* __restrict__ kc,
-                               T* __restrict__ vc, int max_ctx, int interleaved, int q_split) {
+                               T* __restrict__ vc, int max_ctx, int interleaved, int q_split, const float* __restrict__ inv) {
     const int head = blockIdx.x, r = blockIdx.y, i = threadIdx.x, half = hd >> 1;
     if (i >= half) return;
     // interleaved (rope-ordered packed weights): q / k columns hold the pair (i, i + half) at 16(i/8) + 2(i%8), +1
@@ -607,6 +733,7 @@ __global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_
         for (int u = 0; u < 8; ++u)
             if (s0 + u < nsplit) { a += pa[u]; b += pb[u]; }
     }
+    if (inv) { const float sc = inv[r]; a *= sc; b *= sc; }   // 1/rms of the input row (the projection ran on h * gain)
     const int pos = pos0 + r;
     if (head < H + KH) {
         const double cs = cssn.x, sn = cssn.y;
@@ -943,7 +1070,7 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks,
 //                                      GELU    out = 0.5 u (1 + erf(u / sqrt 2)).
 
 __global__ void ffn_act_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int m, int f, int act,
-                               float* __restrict__ out, int split) {
+                               float* __restrict__ out, int split, const float* __restrict__ inv) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)m * f) return;
     const int r = (int)(idx / f), i = (int)(idx - (size_t)r * f);
@@ -961,6 +1088,7 @@ __global__ void ffn_act_kernel(const float* __restrict__ part, int nsplit, size_
         for (int k = 0; k < 4; ++k)
             if (s0 + k < nsplit) { g += pg[k]; u += pu[k]; }
     }
+    if (inv) { const float sc = inv[r]; g *= sc; u *= sc; }
     const float y = act == 1 ? g / (1.0f + expf(-g)) * u : 0.5f * g * (1.0f + erff(g * 0.70710678118654752f));
     if (split) store_split1(out, (size_t)m * f, idx, y);
     else out[idx] = y;
@@ -1294,16 +1422,9 @@ struct AsShared {
     int token, fail;
 };
 
-__device__ __forceinline__ void as_put(unsigned long long* slot, uint32_t epoch, uint32_t payload) {
-    __hip_atomic_store(slot, ((unsigned long long)epoch << 32) | (unsigned long long)payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+__device__ __forceinline__ void as_put(unsigned long long* slot, uint32_t epoch, uint32_t payload) { tw_put(slot, epoch, payload); }
 __device__ __forceinline__ bool as_get(const unsigned long long* slot, uint32_t epoch, int spin_limit, uint32_t* payload) {
-    for (int it = 0; it < spin_limit; ++it) {
-        const unsigned long long w = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((uint32_t)(w >> 32) == epoch) { *payload = (uint32_t)w; return true; }
-        __builtin_amdgcn_s_sleep(2);
-    }
-    return false;
+    return tw_get(slot, epoch, spin_limit, payload);
 }
 
 // Publish NW floats of this quarter (words first .. first + NW) and collect the same words of all four.

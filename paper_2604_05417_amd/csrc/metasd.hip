@@ -62,6 +62,13 @@ struct Split {
 };
 
 int env_int(const char* name, int dflt) { const char* e = getenv(name); return e ? atoi(e) : dflt; }
+// Launch epoch of tagged exchange words (see tw_put in kernels.h): unique per launch in this process, never 0.
+uint32_t next_epoch() {
+    static std::atomic<uint32_t> e{0};
+    uint32_t v = ++e;
+    if (v == 0) v = ++e;
+    return v;
+}
 int ks_cap() { static const int v = std::max(1, std::min(env_int("METASD_GEMM_KSMAX", 8), 32)); return v; }
 
 Split choose_split(int m, int ntiles, int kchunks) {
@@ -103,7 +110,7 @@ const char* check_model(const metasd_model_desc& d, const char* who, char* buf, 
 
 // Workspace layout shared by metasd_workspace_bytes and metasd_create.
 struct Layout {
-    size_t hist, h, h2, xn, part, part2, q, ao, act, apart, rope, P, Q, cand, bd, res, draft, bar, xchg, tables, table_stride, total;
+    size_t hist, h, h2, xn, part, part2, gx, ssq, inv, q, ao, act, apart, rope, P, Q, cand, bd, res, draft, bar, xchg, tables, table_stride, total;
 };
 
 Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const metasd_model_desc* dr) {
@@ -135,6 +142,9 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     L.xn = take((size_t)MAX_ROWS * dmax * 4);
     L.part = take(partmax);
     L.part2 = take(partmax);
+    L.gx = take((size_t)ks_cap() * MAX_ROWS * dmax * 8);          // tagged partial sums of the residual GEMMs
+    L.ssq = take((size_t)(dmax / 64 + 1) * 16 * 4);
+    L.inv = take(64);
     L.q = take((size_t)MAX_ROWS * dmax * 4);
     L.ao = take((size_t)MAX_ROWS * dmax * 4);
     L.act = take((size_t)MAX_ROWS * fmax * 4 * 2);          // also the fused gate | up result
@@ -332,6 +342,8 @@ struct metasd_ctx {
     bool prof_on = false;
     bool tlog = false;
     bool persistent = false;         // bf16 models run the one-launch forward (cooperative launch available)
+    bool gemm_reduce = true;         // bf16 models: residual GEMMs reduce their split-K partials themselves (METASD_GEMM_REDUCE=0: off)
+    float cur_eps = 1e-5f;           // rms_eps of the model whose forward is being launched
     bool fuse_small = true;          // short blocks of narrow bf16 models use the GEMMs with fused prologues (METASD_FUSE_SMALL=0: off)
     int n_cu = 0;
     std::vector<ProfRec> prof;       // event pool
@@ -359,6 +371,9 @@ struct metasd_ctx {
     float* d_h() const { return reinterpret_cast<float*>(ws + lay.h); }
     void* d_xn() const { return ws + lay.xn; }
     float* d_part() const { return reinterpret_cast<float*>(ws + lay.part); }
+    unsigned long long* d_gx() const { return reinterpret_cast<unsigned long long*>(ws + lay.gx); }
+    float* d_ssq() const { return reinterpret_cast<float*>(ws + lay.ssq); }
+    float* d_inv() const { return reinterpret_cast<float*>(ws + lay.inv); }
     unsigned long long* d_xchg() const { return reinterpret_cast<unsigned long long*>(ws + lay.xchg); }
     float* d_part_pp(int i) const { return reinterpret_cast<float*>(ws + (i ? lay.part2 : lay.part)); }
     float* d_h_pp(int i) const { return reinterpret_cast<float*>(ws + (i ? lay.h2 : lay.h)); }
@@ -405,11 +420,12 @@ namespace {
 // when direct_out != nullptr the summed result is written there instead and 0 is returned.
 template <typename T>
 int gemm(metasd_ctx* c, const void* x, int ldx, int m, int K, const void* W0, int n0, const void* W1, int n1,
-         const void* W2, int n2, float* direct_out, int* nsplit_out, size_t x_lo_off = 0);
+         const void* W2, int n2, float* direct_out, int* nsplit_out, size_t x_lo_off = 0, const float* ssq = nullptr,
+         int ntg = 0, float* inv_out = nullptr, int inv_row0 = 0);
 
 template <>
 int gemm<float>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void* W0, int n0, const void* W1, int n1,
-                const void* W2, int n2, float* direct_out, int* nsplit_out, size_t) {
+                const void* W2, int n2, float* direct_out, int* nsplit_out, size_t, const float*, int, float*, int) {
     const int N = n0 + n1 + n2;
     float* out = direct_out ? direct_out : c->d_part();
     hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 3) / 4), dim3(256), 0, c->stream, (const float*)x, ldx, m, K,
@@ -421,29 +437,59 @@ int gemm<float>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void*
 
 template <>
 // x: the activations as two bf16 arrays, hi at x and lo x_lo_off elements behind it (see store_split4).
+// ssq != nullptr: x is h * gain of a residual epilogue, not yet normalised; workgroup 0 writes 1/rms per row
+// to inv_out (rows inv_row0 ..) for the consumers of this GEMM's output, and a direct result is scaled by it.
 int gemm<bf16_t>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void* W0, int n0, const void* W1, int n1,
-                 const void* W2, int n2, float* direct_out, int* nsplit_out, size_t x_lo_off) {
+                 const void* W2, int n2, float* direct_out, int* nsplit_out, size_t x_lo_off, const float* ssq, int ntg,
+                 float* inv_out, int inv_row0) {
     const int N = n0 + n1 + n2;
     const int ntiles = N / 16, kchunks = K / 32;
     const Split s = choose_split(m, ntiles, kchunks);
-    float* out = (direct_out && s.ksplit == 1) ? direct_out : c->d_part();
+    const bool direct = direct_out && s.ksplit == 1 && !ssq;     // a scaled result always goes through sum_partials
+    float* out = direct ? direct_out : c->d_part();
     const int groups = (ntiles + s.tpb - 1) / s.tpb;
     // algorithmic bytes: every weight once, the activations once, the result once
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
     GemmPro plain{};
     plain.sstride = x_lo_off;
+    if (ssq) { plain.src = ssq + inv_row0; plain.ns = ntg; plain.h_out = inv_out + inv_row0; plain.eps = c->cur_eps; }
     hipExtLaunchKernelGGL(gemm_bf16_kernel<PRO_PLAIN>, dim3(groups * s.ksplit), dim3(256), (uint32_t)s.lds, c->stream,
                           pr ? pr->a : nullptr, pr ? pr->b : nullptr, 0u, (const float*)x, ldx, m, K, (const bf16_t*)W0,
                           (const bf16_t*)W1, (const bf16_t*)W2, n0 / 16, (n0 + n1) / 16, ntiles, out, N, s.ksplit, s.cps, s.tpb,
-                          plain);
+                          plain, GemmEpi{});
     LAUNCH_CHECK(c, "gemm_bf16");
-    if (direct_out && s.ksplit > 1) {
+    if (direct_out && !direct) {
         const size_t n = (size_t)m * N;
         hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, c->d_part(),
-                           s.ksplit, n, n, direct_out);
+                           s.ksplit, n, n, direct_out, ssq ? (const float*)(inv_out + inv_row0) : nullptr, N);
         LAUNCH_CHECK(c, "sum_partials");
     }
     *nsplit_out = direct_out ? 0 : s.ksplit;
+    return 0;
+}
+
+// bf16 GEMM into the residual stream (attention output / FFN down projection): the split-K siblings reduce
+// among themselves and the last one updates h, writes h * gain in the two-bf16 form for the next GEMM and the
+// per-tile-group sums of squares (EPI_RESIDUAL in kernels.h).  N = d_model.
+int gemm_residual(metasd_ctx* c, const void* x, int ldx, int m, int K, const void* W, int N, size_t x_lo_off, float* h,
+                  const void* gain_next, float* xsplit, float* ssq, int* ntg_out) {
+    const int ntiles = N / 16, kchunks = K / 32;
+    const Split s = choose_split(m, ntiles, kchunks);
+    const int groups = (ntiles + s.tpb - 1) / s.tpb;
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
+    GemmPro plain{};
+    plain.sstride = x_lo_off;
+    GemmEpi epi{};
+    epi.xw = c->d_gx(); epi.h = h; epi.gain = (const bf16_t*)gain_next; epi.xsplit = xsplit; epi.ssq = ssq;
+    epi.abort = &reinterpret_cast<GridBar*>(c->d_bar())->abort;
+    epi.epoch = next_epoch();
+    epi.spin_limit = std::max(0, env_int("METASD_GEMM_SPIN_LIMIT", 1 << 18));
+    hipExtLaunchKernelGGL((gemm_bf16_kernel<PRO_PLAIN, EPI_RESIDUAL>), dim3(groups * s.ksplit), dim3(256), (uint32_t)s.lds, c->stream,
+                          pr ? pr->a : nullptr, pr ? pr->b : nullptr, 0u, (const float*)x, ldx, m, K, (const bf16_t*)W,
+                          (const bf16_t*)W, (const bf16_t*)W, ntiles, ntiles, ntiles, (float*)nullptr, N, s.ksplit, s.cps, s.tpb,
+                          plain, epi);
+    LAUNCH_CHECK(c, "gemm_bf16 (residual epilogue)");
+    *ntg_out = groups;
     return 0;
 }
 
@@ -461,12 +507,12 @@ int gemm_pro(metasd_ctx* c, const GemmPro& pro, int m, int K, const void* W0, in
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
     hipExtLaunchKernelGGL(gemm_bf16_kernel<PRO>, dim3(groups * s.ksplit), dim3(256), (uint32_t)lds, c->stream, pr ? pr->a : nullptr,
                           pr ? pr->b : nullptr, 0u, (const float*)nullptr, K, m, K, (const bf16_t*)W0, (const bf16_t*)W1,
-                          (const bf16_t*)W2, n0 / 16, (n0 + n1) / 16, ntiles, out, N, s.ksplit, s.cps, s.tpb, pro);
+                          (const bf16_t*)W2, n0 / 16, (n0 + n1) / 16, ntiles, out, N, s.ksplit, s.cps, s.tpb, pro, GemmEpi{});
     LAUNCH_CHECK(c, "gemm_bf16 (fused prologue)");
     if (direct_out && s.ksplit > 1) {
         const size_t n = (size_t)m * N;
         hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->stream, part_out, s.ksplit, n, n,
-                           direct_out);
+                           direct_out, (const float*)nullptr, N);
         LAUNCH_CHECK(c, "sum_partials");
     }
     *nsplit_out = direct_out ? 0 : s.ksplit;
@@ -541,7 +587,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
         hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, part, ns, (size_t)m * NQKV, NQKV, pos0, H, KH,
                            hd, (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, sizeof(T) == 2 ? 1 : 0,
-                           (sizeof(T) == 2 && hd >= 64) ? 1 : 0);
+                           (sizeof(T) == 2 && hd >= 64) ? 1 : 0, (const float*)nullptr);
         LAUNCH_CHECK(c, "rope_kv");
         if ((rc = attention<T>(c, M, L, pos0, m))) return rc;
         if ((rc = gemm<T>(c, c->d_ao(), DQ, m, DQ, M.layer_w(L, 4), D, nullptr, 0, nullptr, 0, nullptr, &ns, (size_t)m * DQ))) return rc;
@@ -556,7 +602,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         const size_t nact = (size_t)m * F;
         const int NF = (d.act == METASD_SWIGLU ? 2 : 1) * F;
         hipLaunchKernelGGL(ffn_act_kernel, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)m * NF, m, F,
-                           d.act, (float*)c->d_act(), split);
+                           d.act, (float*)c->d_act(), split, (const float*)nullptr);
         LAUNCH_CHECK(c, "ffn_act");
         if ((rc = gemm<T>(c, c->d_act(), F, m, F, M.layer_w(L, 8), D, nullptr, 0, nullptr, 0, nullptr, &ns, (size_t)m * F))) return rc;
     }
@@ -568,6 +614,65 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         const void* xrow = split ? (const void*)((const bf16_t*)xn + (size_t)first_row * D) : (const void*)(xn + (size_t)first_row * D);
         if ((rc = gemm<T>(c, xrow, D, m - first_row, D, M.lm_head(), V, nullptr, 0, nullptr, 0, logits, &dummy, (size_t)m * D)))
             return rc;
+    }
+    return 0;
+}
+
+// bf16 models, general case: the two projections into the residual stream reduce their split-K partials
+// inside the GEMM and hand the next GEMM h * gain directly (EPI_RESIDUAL); the kernels that consume a
+// projection of such an input scale by 1/rms.  8 launches per layer instead of 10 (no add+norm kernels).
+int forward_rows_residual(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int first_row) {
+    typedef bf16_t T;
+    const metasd_model_desc& d = M.d;
+    const int D = d.d_model, H = d.n_heads, KH = d.n_kv_heads, hd = M.hd, F = d.d_ffn, V = d.vocab;
+    const int DQ = H * hd, DKV = KH * hd, NQKV = DQ + 2 * DKV;
+    hipStream_t st = c->stream;
+    float* h = c->d_h();
+    float* xn = (float*)c->d_xn();
+    float* part = c->d_part();
+    float* ssq = c->d_ssq();
+    float* inv = c->d_inv();
+    int ns = 0, rc, ntg = 0;
+    c->cur_eps = d.rms_eps;
+    hipLaunchKernelGGL(embed_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, h);
+    LAUNCH_CHECK(c, "embed");
+    hipLaunchKernelGGL(rope_table_kernel, dim3(m), dim3(hd / 2), 0, st, pos0, hd, d.rope_theta, c->d_rope());
+    LAUNCH_CHECK(c, "rope_table");
+    // first norm: a plain RMSNorm of the embedding rows (normalised x, no scaling downstream)
+    hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, 0, (size_t)m * D, D, (const T*)M.layer_w(0, 0), d.rms_eps,
+                       xn, 1);
+    LAUNCH_CHECK(c, "addnorm");
+    bool scaled = false;            // does xn hold h * gain (true) or the normalised rows (false)?
+    for (int L = 0; L < d.n_layers; ++L) {
+        if ((rc = gemm<T>(c, xn, D, m, D, M.layer_w(L, 1), DQ, M.layer_w(L, 2), DKV, M.layer_w(L, 3), DKV, nullptr, &ns, (size_t)m * D,
+                          scaled ? ssq : nullptr, ntg, inv, 0))) return rc;
+        const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
+        T* kc = (T*)M.kv + (size_t)L * 2 * plane;
+        hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, part, ns, (size_t)m * NQKV, NQKV, pos0, H, KH, hd,
+                           (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, 1, hd >= 64 ? 1 : 0,
+                           scaled ? (const float*)inv : nullptr);
+        LAUNCH_CHECK(c, "rope_kv");
+        if ((rc = attention<T>(c, M, L, pos0, m))) return rc;
+        if ((rc = gemm_residual(c, c->d_ao(), DQ, m, DQ, M.layer_w(L, 4), D, (size_t)m * DQ, h, M.layer_w(L, 5), xn, ssq, &ntg))) return rc;
+        if (d.act == METASD_SWIGLU) {
+            if ((rc = gemm<T>(c, xn, D, m, D, M.layer_w(L, 6), F, M.layer_w(L, 7), F, nullptr, 0, nullptr, &ns, (size_t)m * D, ssq, ntg, inv, 0))) return rc;
+        } else {
+            if ((rc = gemm<T>(c, xn, D, m, D, M.layer_w(L, 7), F, nullptr, 0, nullptr, 0, nullptr, &ns, (size_t)m * D, ssq, ntg, inv, 0))) return rc;
+        }
+        const size_t nact = (size_t)m * F;
+        const int NF = (d.act == METASD_SWIGLU ? 2 : 1) * F;
+        hipLaunchKernelGGL(ffn_act_kernel, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)m * NF, m, F, d.act,
+                           (float*)c->d_act(), 1, (const float*)inv);
+        LAUNCH_CHECK(c, "ffn_act");
+        const void* gain_next = L + 1 < d.n_layers ? M.layer_w(L + 1, 0) : M.final_norm();
+        if ((rc = gemm_residual(c, c->d_act(), F, m, F, M.layer_w(L, 8), D, (size_t)m * F, h, gain_next, xn, ssq, &ntg))) return rc;
+        scaled = true;
+    }
+    if (logits) {
+        int dummy;
+        const void* xrow = (const void*)((const bf16_t*)xn + (size_t)first_row * D);
+        if ((rc = gemm<T>(c, xrow, D, m - first_row, D, M.lm_head(), V, nullptr, 0, nullptr, 0, logits, &dummy, (size_t)m * D, ssq, ntg, inv,
+                          first_row))) return rc;
     }
     return 0;
 }
@@ -613,7 +718,7 @@ int forward_rows_fused(metasd_ctx* c, Model& M, int pos0, int m, float* logits, 
         const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
         hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, c->d_part_pp(pp), ns, (size_t)m * NQKV, NQKV, pos0, H,
-                           KH, hd, (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, 1, 1);
+                           KH, hd, (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, 1, 1, (const float*)nullptr);
         LAUNCH_CHECK(c, "rope_kv");
         {
             const float scale = 1.0f / sqrtf((float)hd);
@@ -723,6 +828,7 @@ int forward(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool want_a
         if (M.d.dtype != METASD_BF16) rc = forward_rows<float>(c, M, pos0 + done, m, lg, first_row);
         else if (c->persistent) rc = forward_persistent(c, M, pos0 + done, m, lg, first_row);
         else if (c->fuse_small && fused_small_ok(M, m)) rc = forward_rows_fused(c, M, pos0 + done, m, lg, first_row);
+        else if (c->gemm_reduce) rc = forward_rows_residual(c, M, pos0 + done, m, lg, first_row);
         else rc = forward_rows<bf16_t>(c, M, pos0 + done, m, lg, first_row);
         if (rc) return rc;
         done += m;
@@ -738,13 +844,6 @@ int launch_sample(hipStream_t st, const float* logits, int rows, int V, float T,
     return hipGetLastError() == hipSuccess ? 0 : METASD_E_HIP;
 }
 
-// Launch epoch of the split accept kernel's exchange words: unique per launch in this process, never 0.
-uint32_t next_epoch() {
-    static std::atomic<uint32_t> e{0};
-    uint32_t v = ++e;
-    if (v == 0) v = ++e;
-    return v;
-}
 bool accept_split_enabled() {
     static const bool on = env_int("METASD_ACCEPT_SPLIT", 1) != 0;
     return on;
@@ -905,12 +1004,14 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         c->persistent = ok && ev && ev[0] == '1';
         if (const char* ev = getenv("METASD_TLOG")) c->tlog = ev[0] == '1';
         if (const char* ev = getenv("METASD_FUSE_SMALL")) c->fuse_small = ev[0] != '0';
+        if (const char* ev = getenv("METASD_GEMM_REDUCE")) c->gemm_reduce = ev[0] != '0';
         c->n_cu = ncu;
         if (const char* ev = getenv("METASD_NB")) { int v = atoi(ev); if (v >= 1 && v <= ncu) c->n_cu = v; }   // fewer workgroups (debugging)
     }
     c->target.d_table = (const void**)(c->ws + lay.tables);
     for (int k = 0; k < cfg->K; ++k) c->drafters[k].d_table = (const void**)(c->ws + lay.tables + lay.table_stride * (size_t)(k + 1));
     e = hipMemsetAsync(c->d_bar(), 0, sizeof(GridBar), c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->d_gx(), 0, c->lay.ssq - c->lay.gx, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->d_xchg(), 0, (size_t)(cfg->gamma_max + 1) * AS_XCHG_BYTES, c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->d_cand(), 0, (size_t)(cfg->gamma_max + 1) * sizeof(int2), c->stream);
     if (e == hipSuccess) e = hipMemcpyAsync((void*)c->target.d_table, c->target.w.data(), c->target.w.size() * sizeof(void*), hipMemcpyHostToDevice, c->stream);
@@ -1058,7 +1159,7 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
     if (hr->bar.abort) {
         (void)hipMemsetAsync(c->d_bar(), 0, sizeof(GridBar), c->stream);
         c->phase = PH_NONE;
-        return c->fail(METASD_E_HIP, "persistent forward: a device-wide barrier timed out; call metasd_set_context to start over");
+        return c->fail(METASD_E_HIP, "a bounded device-side wait between workgroups timed out (split-K reduction or device-wide barrier); call metasd_set_context to start over");
     }
     const int n = hr->n_acc;
     if (hr->token == -2) { c->phase = PH_NONE; return c->fail(METASD_E_HIP, "accept: the workgroups of a position did not meet (exchange timed out); call metasd_set_context to start over"); }
