@@ -133,3 +133,29 @@ def test_long_context_small_models():
     cfg["max_ctx"] = 4300 + 64
     st = run_lockstep(cfg, 1.0, rounds=4, kv_prefilled=True, device="cuda")
     assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+
+
+def test_split_k_reduction_bounded_wait_reports_failure(monkeypatch):
+    """The sibling workgroups of a residual GEMM meet through memory with bounded polls.  With the bound
+    forced to zero from the host the last sibling gives up at once: every wave exits, accept reports the
+    failure (-4), and after set_context the same context works again."""
+    s = SMALL[0]
+    cfg = W.config4(n_layers=s["n_layers"], ctx=s["prompt"], n_new=64, K=2, d_model=s["d_model"], n_heads=s["n_heads"],
+                    d_ffn=s["d_ffn"], vocab=s["vocab"], dd_model=s["dd_model"], dn_heads=s["dn_heads"], dd_ffn=s["dd_ffn"])
+    td, tw = cfg["target"]
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=5, max_ctx=s["prompt"] + 80, temperature=1.0, seed=3)
+    g.set_context(cfg["prompt"])
+    k, n, tok, mask, bd = g.round(5)
+    assert 0 <= n <= 5
+    monkeypatch.setenv("METASD_GEMM_SPIN_LIMIT", "0")
+    k = g.bandit_select()
+    g.draft(k, 5)
+    g.verify(5)                                   # 6 rows: the general bf16 path with the reducing GEMMs
+    with pytest.raises(M.MetaSDError) as e:
+        g.accept(5)
+    assert e.value.code == -4
+    monkeypatch.delenv("METASD_GEMM_SPIN_LIMIT")
+    g.set_context(cfg["prompt"])
+    k, n2, tok2, mask2, bd2 = g.round(5)
+    assert (n2, tok2) == (n, tok)                 # same seed, same prompt, same round index: the same outcome as the first time
+    g.close()
