@@ -844,10 +844,7 @@ int launch_sample(hipStream_t st, const float* logits, int rows, int V, float T,
     return hipGetLastError() == hipSuccess ? 0 : METASD_E_HIP;
 }
 
-bool accept_split_enabled() {
-    static const bool on = env_int("METASD_ACCEPT_SPLIT", 1) != 0;
-    return on;
-}
+bool accept_split_enabled() { return env_int("METASD_ACCEPT_SPLIT", 1) != 0; }   // read per launch: tests toggle it
 
 // xchg != nullptr: four workgroups per (row, position) (accept_split_kernel); else one (accept_rows_kernel).
 int launch_accept(hipStream_t st, const float* P, const float* Q, const int32_t* d, int rows, int gamma, int V, float T,

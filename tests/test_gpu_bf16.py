@@ -159,3 +159,17 @@ def test_split_k_reduction_bounded_wait_reports_failure(monkeypatch):
     k, n2, tok2, mask2, bd2 = g.round(5)
     assert (n2, tok2) == (n, tok)                 # same seed, same prompt, same round index: the same outcome as the first time
     g.close()
+
+
+@pytest.mark.parametrize("env", ["METASD_GEMM_REDUCE", "METASD_FUSE_SMALL", "METASD_ACCEPT_SPLIT"])
+def test_step_by_step_variants_stay_in_parity(env, monkeypatch):
+    """Each fused variant can be switched off from the environment (the plain kernels then run); the plain
+    variants keep the same parity."""
+    monkeypatch.setenv(env, "0")
+    s = SMALL[0]
+    cfg = W.config4(n_layers=s["n_layers"], ctx=s["prompt"], n_new=64, K=2, d_model=s["d_model"], n_heads=s["n_heads"],
+                    d_ffn=s["d_ffn"], vocab=s["vocab"], dd_model=s["dd_model"], dn_heads=s["dn_heads"], dd_ffn=s["dd_ffn"])
+    cfg["gamma"] = s["gamma"]
+    cfg["max_ctx"] = s["prompt"] + 80
+    st = run_lockstep(cfg, 1.0, rounds=4, kv_prefilled=False)
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
