@@ -668,6 +668,116 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict_
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Residual-stream GEMM without split-K partials, for a projection whose whole input block fits in LDS
+// (the attention output projection: K = d_model).  One workgroup of 8 wavefronts per 16-feature tile;
+// wavefront w streams the w-th eighth of the tile's K range against its own slice of the activations
+// (staged privately: no workgroup barrier before the multiplies), the eight partial tiles are added
+// through LDS, and wavefront 0 applies the residual epilogue of EPI_RESIDUAL directly: h += out,
+// h * gain in the two-bf16 form, sums of squares per tile.  No sibling workgroups, nothing to wait for.
+//   grid (ntiles), block 512, dynamic LDS 2 * 8 * m * (cpw*4 + 1) * 16 + 8 * 64 * 16 bytes, cpw = ceil(K/32/8).
+// ssq is [ntiles][16] here (one entry per tile).
+
+__global__ __launch_bounds__(512) void gemm_fullk_residual_kernel(const bf16_t* __restrict__ xh, size_t x_lo_off, int ldx, int m, int K,
+                                                                  const bf16_t* __restrict__ W, int ntiles, int N,
+                                                                  float* __restrict__ h, const bf16_t* __restrict__ gain,
+                                                                  float* __restrict__ xsplit, float* __restrict__ ssq) {
+    extern __shared__ uint4 lds[];
+    const int kchunks = K >> 5;
+    const int cpw = (kchunks + 7) >> 3;            // chunks per wavefront
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blockIdx.x;
+    const int c0 = wave * cpw, nc = max(0, min(cpw, kchunks - c0));
+    const int rs = cpw * 4 + 1;
+    uint4* xs = lds + (size_t)wave * 2 * m * rs;   // this wavefront's [2 (hi, lo)][m][rs]
+    uint4* xlo = xs + m * rs;
+    f32x4* red = reinterpret_cast<f32x4*>(lds + (size_t)8 * 2 * m * rs);   // [8][64]
+    const u32x4* wp = reinterpret_cast<const u32x4*>(W) + ((size_t)t * kchunks + c0) * 64 + lane;
+    const int ngroups = (nc + GEMM_U - 1) / GEMM_U;
+    auto issue = [&](u32x4 (&w)[GEMM_U], int gi) {
+#pragma unroll
+        for (int u = 0; u < GEMM_U; ++u) w[u] = __builtin_nontemporal_load(wp + (size_t)min(gi * GEMM_U + u, max(nc, 1) - 1) * 64);
+    };
+    u32x4 wa[GEMM_U], wb[GEMM_U];
+    // activations of this wavefront's slice first (they come back first), then the weight stream
+    {
+        const int total = m * nc * 4, per = nc * 4;
+        constexpr int XB = 6;
+        for (int base = 0; base < total; base += XB * 64) {
+            u32x4 a[XB], b[XB];
+#pragma unroll
+            for (int u = 0; u < XB; ++u) {
+                const int ic = min(base + lane + u * 64, total - 1);
+                const int r = ic / per, c = ic - r * per;
+                const bf16_t* src = xh + (size_t)r * ldx + (size_t)c0 * 32 + (size_t)c * 8;
+                a[u] = *reinterpret_cast<const u32x4*>(src);
+                b[u] = *reinterpret_cast<const u32x4*>(src + x_lo_off);
+            }
+            if (base == 0 && nc > 0) issue(wa, 0);
+#pragma unroll
+            for (int u = 0; u < XB; ++u) {
+                const int idx = base + lane + u * 64;
+                if (idx < total) { const int r = idx / per, c = idx - r * per; xs[r * rs + c] = __builtin_bit_cast(uint4, a[u]); xlo[r * rs + c] = __builtin_bit_cast(uint4, b[u]); }
+            }
+        }
+    }
+    const int row = lane & 15, g = lane >> 4;
+    const bool rowok = row < m;
+    const uint4* xa = xs + (rowok ? row : 0) * rs + g;
+    const uint4* xb = xlo + (rowok ? row : 0) * rs + g;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acl = {0.f, 0.f, 0.f, 0.f};
+    auto multiply = [&](const u32x4 (&w)[GEMM_U], int gi) {
+#pragma unroll
+        for (int u = 0; u < GEMM_U; ++u) {
+            const int c = gi * GEMM_U + u;
+            const bool live = rowok && c < nc;
+            uint4 ah = xa[min(c, nc - 1) * 4], al = xb[min(c, nc - 1) * 4];
+            if (!live) { ah = zero; al = zero; }
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, ah), acc, 0, 0, 0);
+            acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[u]), __builtin_bit_cast(bf16x8, al), acl, 0, 0, 0);
+        }
+    };
+    if (nc > 0) {
+        // the LDS writes above are this wavefront's own; its reads below follow them in program order
+        int gi = 0;
+        for (; gi + 2 < ngroups; gi += 2) {
+            issue(wb, gi + 1);
+            multiply(wa, gi);
+            issue(wa, gi + 2);
+            multiply(wb, gi + 1);
+        }
+        if (gi + 2 == ngroups) {
+            issue(wb, gi + 1);
+            multiply(wa, gi);
+            multiply(wb, gi + 1);
+        } else {
+            multiply(wa, gi);
+        }
+    }
+    red[wave * 64 + lane] = acc + acl;
+    __syncthreads();
+    if (wave != 0) return;
+    f32x4 y = red[lane];
+#pragma unroll
+    for (int w = 1; w < 8; ++w) y += red[w * 64 + lane];      // fixed order: deterministic
+    float ss = 0.f;
+    if (rowok) {
+        const size_t col = (size_t)t * 16 + g * 4;
+        float4 hv = *reinterpret_cast<const float4*>(h + (size_t)row * N + col);
+        hv.x += y[0]; hv.y += y[1]; hv.z += y[2]; hv.w += y[3];
+        *reinterpret_cast<float4*>(h + (size_t)row * N + col) = hv;
+        const uint2 gn = *reinterpret_cast<const uint2*>(gain + col);
+        const float4 xg = make_float4(hv.x * bf2f((bf16_t)(gn.x & 0xffffu)), hv.y * bf2f((bf16_t)(gn.x >> 16)),
+                                      hv.z * bf2f((bf16_t)(gn.y & 0xffffu)), hv.w * bf2f((bf16_t)(gn.y >> 16)));
+        store_split4(xsplit, (size_t)m * N, (size_t)row * N + col, xg);
+        ss = hv.x * hv.x + hv.y * hv.y + hv.z * hv.z + hv.w * hv.w;
+    }
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if (g == 0) ssq[(size_t)t * 16 + row] = ss;
+}
+
 // Row-major bf16 W[n_out][n_in] -> streaming-tile order.  One thread per 16-byte piece.
 // rope_hd > 0 (q and k projections): inside every head of rope_hd output features the rows are
 // re-ordered so that tile j holds the rotary pairs (i, i + rope_hd/2), i = 8j .. 8j+7, side by side:

@@ -39,6 +39,7 @@ constexpr int PER_LAYER = 9;
 constexpr int MAX_ROWS = 16;
 constexpr size_t ALIGN = 256;
 constexpr int LDS_BUDGET = 60 * 1024;
+constexpr size_t FULLK_LDS_MAX = 150 * 1024;   // gemm_fullk_residual_kernel: the whole activation block in LDS
 
 size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 size_t elem_size(const metasd_model_desc& d) { return d.dtype == METASD_BF16 ? 2 : 4; }
@@ -143,7 +144,7 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     L.part = take(partmax);
     L.part2 = take(partmax);
     L.gx = take((size_t)ks_cap() * MAX_ROWS * dmax * 8);          // tagged partial sums of the residual GEMMs
-    L.ssq = take((size_t)(dmax / 64 + 1) * 16 * 4);
+    L.ssq = take((size_t)(dmax / 16 + 1) * 16 * 4);              // per tile group (or per tile) and row
     L.inv = take(64);
     L.q = take((size_t)MAX_ROWS * dmax * 4);
     L.ao = take((size_t)MAX_ROWS * dmax * 4);
@@ -342,6 +343,7 @@ struct metasd_ctx {
     bool prof_on = false;
     bool tlog = false;
     bool persistent = false;         // bf16 models run the one-launch forward (cooperative launch available)
+    bool fullk = true;               // residual GEMMs whose input fits in LDS run without split-K (METASD_GEMM_FULLK=0: off)
     bool gemm_reduce = true;         // bf16 models: residual GEMMs reduce their split-K partials themselves (METASD_GEMM_REDUCE=0: off)
     float cur_eps = 1e-5f;           // rms_eps of the model whose forward is being launched
     bool fuse_small = true;          // short blocks of narrow bf16 models use the GEMMs with fused prologues (METASD_FUSE_SMALL=0: off)
@@ -468,12 +470,31 @@ int gemm<bf16_t>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void
     return 0;
 }
 
+// The same projection without split-K (gemm_fullk_residual_kernel): used when the input block fits in LDS
+// and there are enough tiles to occupy the CUs.
+bool fullk_ok(const metasd_ctx* c, int m, int K, int ntiles, size_t* lds_out) {
+    const int cpw = (K / 32 + 7) / 8;
+    const size_t lds = (size_t)2 * 8 * m * (cpw * 4 + 1) * 16 + (size_t)8 * 64 * 16;
+    *lds_out = lds;
+    return c->fullk && lds <= FULLK_LDS_MAX && ntiles * 4 >= c->n_cu * 3;
+}
+
 // bf16 GEMM into the residual stream (attention output / FFN down projection): the split-K siblings reduce
 // among themselves and the last one updates h, writes h * gain in the two-bf16 form for the next GEMM and the
 // per-tile-group sums of squares (EPI_RESIDUAL in kernels.h).  N = d_model.
 int gemm_residual(metasd_ctx* c, const void* x, int ldx, int m, int K, const void* W, int N, size_t x_lo_off, float* h,
                   const void* gain_next, float* xsplit, float* ssq, int* ntg_out) {
     const int ntiles = N / 16, kchunks = K / 32;
+    size_t lds_full = 0;
+    if (fullk_ok(c, m, K, ntiles, &lds_full)) {
+        metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
+        hipExtLaunchKernelGGL(gemm_fullk_residual_kernel, dim3(ntiles), dim3(512), (uint32_t)lds_full, c->stream, pr ? pr->a : nullptr,
+                              pr ? pr->b : nullptr, 0u, (const bf16_t*)x, x_lo_off, ldx, m, K, (const bf16_t*)W, ntiles, N, h,
+                              (const bf16_t*)gain_next, xsplit, ssq);
+        LAUNCH_CHECK(c, "gemm_bf16 (full-K residual)");
+        *ntg_out = ntiles;
+        return 0;
+    }
     const Split s = choose_split(m, ntiles, kchunks);
     const int groups = (ntiles + s.tpb - 1) / s.tpb;
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
@@ -1002,6 +1023,8 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         if (const char* ev = getenv("METASD_TLOG")) c->tlog = ev[0] == '1';
         if (const char* ev = getenv("METASD_FUSE_SMALL")) c->fuse_small = ev[0] != '0';
         if (const char* ev = getenv("METASD_GEMM_REDUCE")) c->gemm_reduce = ev[0] != '0';
+        if (const char* ev = getenv("METASD_GEMM_FULLK")) c->fullk = ev[0] != '0';
+        if (hipFuncSetAttribute((const void*)gemm_fullk_residual_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)FULLK_LDS_MAX) != hipSuccess) { c->fullk = false; (void)hipGetLastError(); }
         c->n_cu = ncu;
         if (const char* ev = getenv("METASD_NB")) { int v = atoi(ev); if (v >= 1 && v <= ncu) c->n_cu = v; }   // fewer workgroups (debugging)
     }
