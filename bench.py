@@ -8,8 +8,8 @@ K = 5 two-layer drafters with segment-switching heads, gamma = 5, batch 1, T = 1
 seeded synthetic tensors resident in HBM before the timed region.
 
 Prints ONE JSON line: verified tokens/s (sum of N_acc + 1 over the timed rounds / wall clock),
-the roofline of the dominant kernel (the bf16 weight-streaming GEMM: algorithmic bytes per launch
-/ mean launch duration from HIP events on the library's stream), and the CPU oracle timed on a
+the roofline of the dominant kernel (the bf16 weight-streaming GEMMs: algorithmic bytes per launch
+/ mean launch duration from HIP events attached to each dispatch on the library's stream), and the CPU oracle timed on a
 bounded sample of the same workload on this host.
 """
 from __future__ import annotations
@@ -154,7 +154,7 @@ def main():
     rg, ra, rc, rf, rd = roof(pg), roof(pa), roof(pc), roof(pf), roof(pd)
     # dominant kernel: the one-launch verify forward (all 32 layers + LM head); when the library runs
     # the step-by-step kernels instead, the bf16 weight-streaming GEMM
-    dom, dom_name = (rf, "forward_persistent_kernel<128> (verify pass)") if rf else (rg, "gemm_bf16_kernel")
+    dom, dom_name = (rf, "forward_persistent_kernel<128> (verify pass)") if rf else (rg, "gemm_bf16_kernel<*> + gemm_fullk_residual_kernel (weight-streaming GEMMs)")
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": dom["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": dom["GBs"] / HBM_PEAK_GBS, "traffic": read_traffic(),
                 "avg_launch_us": dom["avg_us"], "algorithmic_bytes_per_launch": dom["bytes_per_launch"],
