@@ -17,8 +17,13 @@
  *     pinned host buffer for results.
  *   - All device work is enqueued on the HIP stream given to metasd_create (NULL = default
  *     stream); draft and verify are asynchronous, accept synchronises the stream.
- *   - This version runs one sequence per context (config.batch must be 1) for draft / verify;
- *     metasd_accept_logits and metasd_sample_logits take any number of rows.
+ *   - A context holds config.batch independent sequences (1..METASD_MAX_BATCH), each with its own
+ *     token history, KV caches and bandit; they advance in lock-step, one round per
+ *     draft / verify / accept call: every sequence drafts with its own arm (sequences that share
+ *     an arm share that drafter's forward pass), one verification block holds all
+ *     batch x (gamma + 1) rows, one accept launch tests them all.  Sequence b uses Philox sequence
+ *     id b.  batch == 1 runs the single-sequence kernels; metasd_accept_logits and
+ *     metasd_sample_logits take any number of rows.
  *
  * Model weights.  A model is described by metasd_model_desc and a table of device pointers in
  * this order: embed [V][d]; per layer: attn_norm [d], wq [H*hd][d], wk [KH*hd][d],
@@ -29,8 +34,8 @@
  *     matrix (wq .. w_down, lm_head) must be in the library's streaming-tile order produced by
  *     metasd_pack_weight (same byte size as the row-major matrix; wq and wk with rope_head_dim = hd).
  *
- * KV cache of a model (device, caller-owned): element type = model dtype, layout
- *     [layer][2 (K, V)][kv_head][max_ctx][hd],  bytes = metasd_kv_bytes().
+ * KV cache of a model (device, caller-owned): element type = model dtype, one cache per sequence,
+ *     [sequence][layer][2 (K, V)][kv_head][max_ctx][hd],  bytes = batch * metasd_kv_bytes().
  */
 #ifndef METASD_H
 #define METASD_H
@@ -67,6 +72,7 @@ extern "C" {
 #define METASD_POLICY_RANDOM 5 /* uniform random arm; Philox stream 3 */
 #define METASD_MAX_GAMMA 15 /* a verification block is gamma+1 <= 16 rows */
 #define METASD_MAX_K 64
+#define METASD_MAX_BATCH 32 /* sequences per context; a verification block has batch * (gamma+1) <= 512 rows */
 
 typedef struct metasd_ctx metasd_ctx; /* opaque; freed by metasd_destroy */
 
@@ -80,7 +86,7 @@ typedef struct {
 typedef struct {
     int32_t K;          /* number of drafters, 1..METASD_MAX_K */
     int32_t gamma_max;  /* largest draft length N_max that will be used, 1..METASD_MAX_GAMMA */
-    int32_t batch;      /* must be 1 */
+    int32_t batch;      /* independent sequences in this context, 1..METASD_MAX_BATCH */
     int32_t max_ctx;    /* capacity of the token history and of every KV cache, in positions */
     float temperature;  /* 0 => greedy; otherwise p = softmax(logits / T) for target and drafter */
     int32_t reward;     /* METASD_REWARD_BE | METASD_REWARD_BD (used by metasd_bandit_update) */
@@ -93,7 +99,8 @@ typedef struct {
 
 /* ---- sizes -------------------------------------------------------------------------------- */
 
-/* Bytes of one model's KV cache for max_ctx positions. */
+/* Bytes of one model's KV cache for ONE sequence of max_ctx positions (a context needs batch times this,
+ * sequence b's cache starting b * bytes into the buffer). */
 int32_t metasd_kv_bytes(const metasd_model_desc* m, int32_t max_ctx, size_t* bytes_out);
 
 /* Bytes of device workspace metasd_create needs for this configuration. */
@@ -115,7 +122,7 @@ int32_t metasd_pack_weight(void* dst, const void* src, int32_t n_out, int32_t n_
 
 /* Create a context.  Descriptors and pointer tables are copied; the device memory they point
  * to stays owned by the caller and must outlive the context.  target_kv / drafter_kv[k] are
- * KV caches of metasd_kv_bytes() each; workspace is >= metasd_workspace_bytes() and 256-byte
+ * KV caches of batch * metasd_kv_bytes() each; workspace is >= metasd_workspace_bytes() and 256-byte
  * aligned.  Errors: INVALID (NULL, unsupported shape: see metasd_last_error), WORKSPACE, HIP. */
 int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_model_desc* target,
                       const metasd_model_desc* drafters /*[K]*/, const void* const* target_weights,
@@ -123,8 +130,10 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
                       void* const* drafter_kv /*[K]*/, void* workspace, size_t workspace_bytes, void* hip_stream);
 int32_t metasd_destroy(metasd_ctx*);
 
-/* Start a new query (Alg. 1 input "initial prompt x^{1:l}"): upload n >= 1 prompt tokens (host),
- * reset the round counter and the bandit (the bandit is re-initialised for every query).
+/* Start a new query for sequence seq (Alg. 1 input "initial prompt x^{1:l}"): upload n >= 1 prompt
+ * tokens (host) and reset that sequence's bandit (the bandit is re-initialised for every query).
+ * The round counter - shared by the sequences of a batch, it is the round word of every Philox
+ * counter - restarts when sequence 0 is set; a round can be drafted once every sequence has a context.
  * kv_prefilled == 0: the target prefills positions [0, n-1) now (asynchronously); drafters start
  *   empty and catch up the first time they are selected.
  * kv_prefilled != 0: the caller has already written the KV entries of positions [0, n-1) of
@@ -156,7 +165,7 @@ int32_t metasd_bandit_state(const metasd_ctx*, int32_t seq, double* mu, int32_t*
 
 /* ---- one speculative-sampling round (Alg. 3) -------------------------------------------------- */
 
-/* Draft gamma tokens with drafter k[0]: the drafter first consumes the committed tokens it has
+/* Draft gamma tokens for every sequence b with drafter k[b]: the drafter first consumes the committed tokens it has
  * not processed yet (ending with the last committed token), then runs gamma-1 single-token steps.
  * Token j is argmax (T = 0) or the inverse-CDF draw of softmax(logits/T) with the Philox uniform
  * at (seq, round, j, stream 2).  Draft tokens and drafter logits stay on the device.
@@ -165,7 +174,7 @@ int32_t metasd_draft(metasd_ctx*, const int32_t* k /*[batch] host*/, int32_t gam
 
 /* Target forward over the gamma+1 rows [last committed token, d_1 .. d_gamma] at positions
  * l-1 .. l-1+gamma against the KV cache (causal inside the block); appends their K/V and leaves
- * fp32 logits [gamma+1][V] on the device.  Errors: INVALID, ORDER (draft not done), HIP. */
+ * fp32 logits [batch][gamma+1][V] on the device.  Errors: INVALID, ORDER (draft not done), HIP. */
 int32_t metasd_verify(metasd_ctx*, int32_t gamma);
 
 /* Accept test u_j < min(1, p_j(d_j)/q_j(d_j)) for j < gamma with the uniform at (seq, round, j,
@@ -225,9 +234,11 @@ int32_t metasd_profile_read(metasd_ctx*, int32_t kind, double* ms_total, int64_t
 
 /* ---- introspection ---------------------------------------------------------------------------- */
 
+/* batch == 1: the row strides are those of gamma_max.  batch > 1: the buffers are packed for the gamma of
+ * the last round - P [batch][gamma+1][V], Q [batch][gamma][V], BD and DRAFT [batch][gamma]. */
 #define METASD_PEEK_P 0     /* float [gamma_max+1][V]  target logits of the last verify */
 #define METASD_PEEK_Q 1     /* float [gamma_max][V]    drafter logits of the last draft */
-#define METASD_PEEK_HIST 2  /* int32 [max_ctx]         token history (committed + speculative) */
+#define METASD_PEEK_HIST 2  /* int32 [batch][max_ctx]  token history (committed + speculative) */
 #define METASD_PEEK_BD 3    /* double [gamma_max]      sum_v min(p_j, q_j) of the last accept */
 #define METASD_PEEK_DRAFT 4 /* int32 [gamma_max]       draft tokens d_1..d_gamma of the last draft */
 /* Device pointer and byte size of an internal buffer (valid until metasd_destroy). */
@@ -236,6 +247,9 @@ int32_t metasd_peek(metasd_ctx*, int32_t what, void** dev_ptr_out, size_t* bytes
 /* Committed length l, number of positions in the KV cache of model (-1 target, k drafter),
  * completed rounds.  Any pointer may be NULL. */
 int32_t metasd_state(const metasd_ctx*, int32_t model, int32_t* l_out, int32_t* kv_len_out, int32_t* round_out);
+/* The same for sequence seq of a batch (metasd_state reports sequence 0). */
+int32_t metasd_state_seq(const metasd_ctx*, int32_t seq, int32_t model, int32_t* l_out, int32_t* kv_len_out,
+                         int32_t* round_out);
 
 /* Message of the last error on this context (ctx == NULL: of the last context-free call on
  * this thread).  Never NULL. */

@@ -14,7 +14,7 @@ MATRIX_SLOTS = (1, 2, 3, 4, 6, 7, 8)          # wq wk wv wo w_gate w_up w_down w
 EXPORTS = ["metasd_kv_bytes", "metasd_workspace_bytes", "metasd_pack_weight", "metasd_create", "metasd_destroy",
            "metasd_set_context", "metasd_swap_weight", "metasd_bandit_select", "metasd_bandit_update",
            "metasd_bandit_state", "metasd_draft", "metasd_verify", "metasd_accept", "metasd_accept_logits",
-           "metasd_sample_logits", "metasd_philox_words", "metasd_profile", "metasd_profile_read", "metasd_peek", "metasd_state", "metasd_last_error"]
+           "metasd_sample_logits", "metasd_philox_words", "metasd_profile", "metasd_profile_read", "metasd_peek", "metasd_state", "metasd_state_seq", "metasd_last_error"]
 
 
 class MetaSDError(RuntimeError):
@@ -66,7 +66,7 @@ def load_library():
         "metasd_bandit_state": [vp, i32, vp, vp, C.POINTER(i32)],
         "metasd_draft": [vp, C.POINTER(i32), i32],
         "metasd_verify": [vp, i32],
-        "metasd_accept": [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(u32), C.POINTER(f64)],
+        "metasd_accept": [vp, i32, vp, vp, vp, vp],
         "metasd_accept_logits": [vp, vp, vp, i32, i32, i32, f32, u64, u32, u32, vp, vp, vp, vp, vp, vp],
         "metasd_sample_logits": [vp, i32, i32, f32, u64, u32, u32, u32, vp, vp],
         "metasd_philox_words": [u64, u32, i32, u32, u32, u32, vp, vp],
@@ -74,6 +74,7 @@ def load_library():
         "metasd_profile_read": [vp, i32, C.POINTER(f64), C.POINTER(C.c_int64), C.POINTER(f64)],
         "metasd_peek": [vp, i32, C.POINTER(vp), C.POINTER(sz)],
         "metasd_state": [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)],
+        "metasd_state_seq": [vp, i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)],
     }
     for name, args in sig.items():
         fn = getattr(L, name)
@@ -124,19 +125,20 @@ class MetaSD:
 
     def __init__(self, target, drafters, gamma_max: int, max_ctx: int, temperature: float, seed: int,
                  ucb_beta: float = 1.0, reward: str = "BE", device: str = "cuda:0", policy: str = "ucb",
-                 policy_param: float = 0.0, policy_window: int = 0):
+                 policy_param: float = 0.0, policy_window: int = 0, batch: int = 1):
         _require_gpu()
         self.L = load_library()
         self.device = torch.device(device)
         self.K = len(drafters)
         self.gamma_max = gamma_max
         self.max_ctx = max_ctx
+        self.batch = batch
         self._packed = {}       # data_ptr of a row-major matrix -> packed tensor (early-exit drafters share the target's)
         self._keep = []
         tdesc, tw = target
         self.tdesc = dict(tdesc)
         self.ddescs = [dict(d) for d, _ in drafters]
-        self.cfg = _Config(self.K, gamma_max, 1, max_ctx, temperature, 1 if reward == "BD" else 0, ucb_beta, seed,
+        self.cfg = _Config(self.K, gamma_max, batch, max_ctx, temperature, 1 if reward == "BD" else 0, ucb_beta, seed,
                            POLICIES[policy], policy_window, policy_param)
         self._tdesc_c = _desc(tdesc)
         self._ddesc_c = (_Desc * self.K)(*[_desc(d) for d in self.ddescs])
@@ -192,9 +194,9 @@ class MetaSD:
         _check(self.L.metasd_kv_bytes(C.byref(desc_c), self.max_ctx, C.byref(nbytes)))
         dt = torch.bfloat16 if desc["dtype"] == 1 else torch.float32
         hd = desc["d_model"] // desc["n_heads"]
-        t = torch.zeros((desc["n_layers"], 2, desc["n_kv_heads"], self.max_ctx, hd), dtype=dt, device=self.device)
-        assert t.numel() * t.element_size() == nbytes.value
-        return t
+        t = torch.zeros((self.batch, desc["n_layers"], 2, desc["n_kv_heads"], self.max_ctx, hd), dtype=dt, device=self.device)
+        assert t.numel() * t.element_size() == nbytes.value * self.batch
+        return t[0] if self.batch == 1 else t
 
     # ---- C ABI, same names
     def close(self):
@@ -209,50 +211,72 @@ class MetaSD:
         except Exception:
             pass
 
-    def set_context(self, tokens, kv_prefilled: bool = False):
+    def set_context(self, tokens, kv_prefilled: bool = False, seq: int = 0):
         tok = np.ascontiguousarray(tokens, np.int32)
-        _check(self.L.metasd_set_context(self._h, 0, tok.ctypes.data_as(C.c_void_p), tok.shape[0], int(kv_prefilled)), self._h)
+        _check(self.L.metasd_set_context(self._h, seq, tok.ctypes.data_as(C.c_void_p), tok.shape[0], int(kv_prefilled)), self._h)
 
     def swap_weight(self, model: int, index: int, tensor: torch.Tensor):
         """tensor must already be in device layout (bf16 matrices: packed with pack_weight)."""
         self._keep.append(tensor)
         _check(self.L.metasd_swap_weight(self._h, model, index, tensor.data_ptr()), self._h)
 
-    def bandit_select(self) -> int:
+    def bandit_select(self, seq: int = 0) -> int:
         k = C.c_int32(-1)
-        _check(self.L.metasd_bandit_select(self._h, 0, C.byref(k)), self._h)
+        _check(self.L.metasd_bandit_select(self._h, seq, C.byref(k)), self._h)
         return int(k.value)
 
-    def bandit_update(self, k: int, n_acc: int, gamma: int, bd_reward: float = float("nan")):
-        _check(self.L.metasd_bandit_update(self._h, 0, k, n_acc, gamma, bd_reward), self._h)
+    def bandit_update(self, k: int, n_acc: int, gamma: int, bd_reward: float = float("nan"), seq: int = 0):
+        _check(self.L.metasd_bandit_update(self._h, seq, k, n_acc, gamma, bd_reward), self._h)
 
-    def bandit_state(self):
+    def bandit_state(self, seq: int = 0):
         mu = np.zeros(self.K, np.float64)
         n = np.zeros(self.K, np.int32)
         t = C.c_int32(0)
-        _check(self.L.metasd_bandit_state(self._h, 0, mu.ctypes.data_as(C.c_void_p), n.ctypes.data_as(C.c_void_p), C.byref(t)))
+        _check(self.L.metasd_bandit_state(self._h, seq, mu.ctypes.data_as(C.c_void_p), n.ctypes.data_as(C.c_void_p), C.byref(t)))
         return mu, n, int(t.value)
 
-    def draft(self, k: int, gamma: int):
-        kk = (C.c_int32 * 1)(k)
+    def draft(self, k, gamma: int):
+        """k: the arm (batch 1) or one arm per sequence."""
+        ks = [k] * self.batch if np.isscalar(k) else list(k)
+        assert len(ks) == self.batch
+        kk = (C.c_int32 * self.batch)(*[int(v) for v in ks])
         _check(self.L.metasd_draft(self._h, kk, gamma), self._h)
 
     def verify(self, gamma: int):
         _check(self.L.metasd_verify(self._h, gamma), self._h)
 
     def accept(self, gamma: int):
-        n, tok, mask, bd = C.c_int32(0), C.c_int32(0), C.c_uint32(0), C.c_double(0.0)
-        _check(self.L.metasd_accept(self._h, gamma, C.byref(n), C.byref(tok), C.byref(mask), C.byref(bd)), self._h)
-        return int(n.value), int(tok.value), int(mask.value), float(bd.value)
+        """batch 1: (n_acc, token, mask, bd); otherwise four arrays of `batch` entries."""
+        B = self.batch
+        n, tok, mask, bd = np.zeros(B, np.int32), np.zeros(B, np.int32), np.zeros(B, np.uint32), np.zeros(B, np.float64)
+        _check(self.L.metasd_accept(self._h, gamma, n.ctypes.data_as(C.c_void_p), tok.ctypes.data_as(C.c_void_p),
+                                    mask.ctypes.data_as(C.c_void_p), bd.ctypes.data_as(C.c_void_p)), self._h)
+        if B == 1:
+            return int(n[0]), int(tok[0]), int(mask[0]), float(bd[0])
+        return n, tok, mask, bd
 
-    def peek(self, what: str) -> torch.Tensor:
-        """View of an internal device buffer: 'P' [gamma_max+1, V], 'Q' [gamma_max, V], 'hist' [max_ctx], 'bd' [gamma_max], 'draft' [gamma_max]."""
+    def peek(self, what: str, gamma: int | None = None) -> torch.Tensor:
+        """View of an internal device buffer: 'P' [gamma_max+1, V], 'Q' [gamma_max, V], 'hist' [max_ctx], 'bd' [gamma_max],
+        'draft' [gamma_max].  batch > 1: pass the gamma of the last round; the views are P [batch, gamma+1, V],
+        Q [batch, gamma, V], hist [batch, max_ctx], bd / draft [batch, gamma]."""
         code = {"P": 0, "Q": 1, "hist": 2, "bd": 3, "draft": 4}[what]
         p, n = C.c_void_p(), C.c_size_t(0)
         _check(self.L.metasd_peek(self._h, code, C.byref(p), C.byref(n)), self._h)
         off = p.value - self.workspace.data_ptr()
         raw = self.workspace[off: off + n.value]
         V = self.tdesc["vocab"]
+        if self.batch > 1:
+            B, g = self.batch, gamma
+            if what == "hist":
+                return raw.view(torch.int32).view(B, self.max_ctx)
+            assert g is not None
+            if what == "P":
+                return raw.view(torch.float32)[: B * (g + 1) * V].view(B, g + 1, V)
+            if what == "Q":
+                return raw.view(torch.float32)[: B * g * V].view(B, g, V)
+            if what == "draft":
+                return raw.view(torch.int32)[: B * g].view(B, g)
+            return raw.view(torch.float64)[: B * g].view(B, g)
         if what == "P":
             return raw.view(torch.float32).view(self.gamma_max + 1, V)
         if what == "Q":
@@ -269,9 +293,9 @@ class MetaSD:
         _check(self.L.metasd_profile_read(self._h, {"gemm": 0, "attn": 1, "accept": 2, "forward": 3, "draft_forward": 4}[kind], C.byref(ms), C.byref(n), C.byref(by)), self._h)
         return dict(ms=ms.value, launches=n.value, bytes=by.value)
 
-    def state(self, model: int = -1):
+    def state(self, model: int = -1, seq: int = 0):
         l, kv, r = C.c_int32(0), C.c_int32(0), C.c_int32(0)
-        _check(self.L.metasd_state(self._h, model, C.byref(l), C.byref(kv), C.byref(r)))
+        _check(self.L.metasd_state_seq(self._h, seq, model, C.byref(l), C.byref(kv), C.byref(r)))
         return int(l.value), int(kv.value), int(r.value)
 
     # ---- convenience: one full round (select -> draft -> verify -> accept -> update)

@@ -6,7 +6,8 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc", "metasd.hip")
-DEPS = [SRC, os.path.join(HERE, "csrc", "kernels.h"), os.path.join(HERE, "..", "include", "metasd.h")]
+DEPS = [SRC, os.path.join(HERE, "csrc", "kernels.h"), os.path.join(HERE, "csrc", "persist.h"), os.path.join(HERE, "csrc", "batch.h"),
+        os.path.join(HERE, "..", "include", "metasd.h")]
 LIB = os.path.join(HERE, "libmetasd.so")
 
 HIPCC_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-shared", "-fPIC",

@@ -1,0 +1,258 @@
+// Kernels for blocks of rows that belong to several sequences (batch > 1), and the bf16 GEMM for
+// more than 16 rows.  Included after kernels.h; the single-sequence kernels there stay as they are.
+//
+// A block is a list of segments: segment s holds rows [s*ms, s*ms + m[s]) - the tokens of sequence
+// seq[s] at positions pos0[s] .. pos0[s] + m[s] - 1.  All segments are ms rows apart (ms = the longest
+// segment of the block, <= 16); rows j >= m[s] of a segment are padding: they are computed like the
+// segment's last row, write no K/V and are never read back.  A verification block has m[s] = gamma + 1
+// for every sequence (no padding), a draft step m[s] = 1; only catch-up blocks are ragged.
+#pragma once
+
+namespace msd {
+
+constexpr int MAX_SEGS = 32;
+
+struct Segs {
+    int n, ms;
+    int seq[MAX_SEGS], m[MAX_SEGS], pos0[MAX_SEGS];
+};
+
+struct SeqTab { int v[MAX_SEGS]; };
+
+// Workgroup barrier that orders LDS accesses only (global loads stay in flight).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// h[r] = E[token of row r]; tokens come from the per-sequence histories hist[seq][max_ctx].   grid (R), block 256
+template <typename T>
+__global__ void embed_seg_kernel(const int32_t* __restrict__ hist, int max_ctx, const T* __restrict__ E, int d,
+                                 float* __restrict__ h, Segs sg) {
+    const int r = blockIdx.x, s = r / sg.ms, j = min(r - s * sg.ms, sg.m[s] - 1);
+    const size_t t = (size_t)hist[(size_t)sg.seq[s] * max_ctx + sg.pos0[s] + j];
+    for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)r * d + i] = El<T>::ld(E[t * d + i]);
+}
+
+// Rotation table per block row (see rope_table_kernel).   grid (R), block hd/2
+__global__ void rope_table_seg_kernel(Segs sg, int hd, float theta, double2* __restrict__ tab) {
+    const int r = blockIdx.x, i = threadIdx.x, half = hd >> 1;
+    if (i >= half) return;
+    const int s = r / sg.ms, j = min(r - s * sg.ms, sg.m[s] - 1);
+    const double freq = pow((double)theta, -2.0 * (double)i / (double)hd);
+    double sn, cs;
+    sincos((double)(sg.pos0[s] + j) * freq, &sn, &cs);
+    tab[r * half + i] = make_double2(cs, sn);
+}
+
+// RoPE + K/V append per block row; kc / vc are the planes of sequence 0, sequence b's are kv_seq_stride
+// elements further.   grid (H + 2KH, R), block 64
+template <typename T>
+__global__ void rope_kv_seg_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int N, Segs sg, int H, int KH,
+                                   int hd, const double2* __restrict__ tab, float* __restrict__ q, T* __restrict__ kc,
+                                   T* __restrict__ vc, size_t kv_seq_stride, int max_ctx, int interleaved, int q_split) {
+    const int r = blockIdx.y, s = r / sg.ms, j = r - s * sg.ms;
+    const bool valid = j < sg.m[s];
+    const size_t so = (size_t)sg.seq[s] * kv_seq_stride;
+    rope_kv_body<T>(part, nsplit, sstride, N, sg.pos0[s] + min(j, sg.m[s] - 1), H, KH, hd, tab, q, kc + so, vc + so, max_ctx,
+                    interleaved, q_split, nullptr, valid);
+}
+
+// Attention partials per (chunk, head, segment); records of segment s start s * H * nch_max chunk records
+// into part.   grid (nch_max, H, segments), block 256
+template <typename T, int HD>
+__global__ __launch_bounds__(256) void attn_partial_seg_kernel(const float* __restrict__ q, const T* __restrict__ kc,
+                                                               const T* __restrict__ vc, size_t kv_seq_stride, Segs sg, int H,
+                                                               int KH, int max_ctx, float scale, float* __restrict__ part,
+                                                               int nch_max) {
+    const int s = blockIdx.z, m = sg.m[s], pos0 = sg.pos0[s], c = blockIdx.x;
+    if (c * ATT_CH >= pos0 + m) return;                 // workgroup-uniform
+    const size_t so = (size_t)sg.seq[s] * kv_seq_stride;
+    attn_partial_body<T, HD>(q + (size_t)s * sg.ms * H * HD, kc + so, vc + so, m, pos0, H, KH, max_ctx, scale,
+                             part + (size_t)s * H * nch_max * 16 * (HD + 2), nch_max, c, (int)blockIdx.y);
+}
+
+template <int HD>
+__global__ __launch_bounds__(256) void attn_partial_mfma_seg_kernel(const float* __restrict__ q, const bf16_t* __restrict__ kc,
+                                                                    const bf16_t* __restrict__ vc, size_t kv_seq_stride, Segs sg,
+                                                                    int H, int KH, int max_ctx, float scale,
+                                                                    float* __restrict__ part, int nch_max, size_t q_lo_off) {
+    const int s = blockIdx.z, m = sg.m[s], pos0 = sg.pos0[s], c = blockIdx.x;
+    if (c * ATT_CH >= pos0 + m) return;                 // workgroup-uniform
+    const size_t so = (size_t)sg.seq[s] * kv_seq_stride;
+    const bf16_t* qs = reinterpret_cast<const bf16_t*>(q) + (size_t)s * sg.ms * H * HD;
+    attn_partial_mfma_body<HD>(reinterpret_cast<const float*>(qs), kc + so, vc + so, m, pos0, H, KH, max_ctx, scale,
+                               part + (size_t)s * H * nch_max * 16 * (HD + 2), nch_max, c, (int)blockIdx.y, q_lo_off);
+}
+
+// grid (H, R), block HD
+template <int HD>
+__global__ void attn_combine_seg_kernel(const float* __restrict__ part, int nch_max, int H, float* __restrict__ out, int split,
+                                        Segs sg) {
+    const int r = blockIdx.y, s = r / sg.ms, j = min(r - s * sg.ms, sg.m[s] - 1);
+    const int nch = (sg.pos0[s] + sg.m[s] + ATT_CH - 1) / ATT_CH;
+    attn_combine_body<HD>(part + (size_t)s * H * nch_max * 16 * (HD + 2), nch, nch_max, H, out, split, (int)blockIdx.x, j, r,
+                          (size_t)gridDim.y * H * HD);
+}
+
+// out[dst row][n] = sum of split-K partials of block row r, for the rows that carry logits:
+//   dst row = seq * out_seq_rows + out_row0 + (last_only ? 0 : j);  last_only: only the last valid row of a segment.
+// grid (ceil(N / 256), R), block 256
+__global__ void sum_partials_seg_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int N, float* __restrict__ out,
+                                        Segs sg, int out_seq_rows, int out_row0, int last_only) {
+    const int r = blockIdx.y, s = r / sg.ms, j = r - s * sg.ms;
+    const int n = blockIdx.x * 256 + threadIdx.x;
+    if (j >= sg.m[s] || (last_only && j != sg.m[s] - 1) || n >= N) return;
+    float y = 0.f;
+    for (int k = 0; k < nsplit; ++k) y += part[(size_t)k * sstride + (size_t)r * N + n];
+    out[((size_t)sg.seq[s] * out_seq_rows + out_row0 + (last_only ? 0 : j)) * N + n] = y;
+}
+
+// Draft token of every sequence b from its row of logits (logits + b * row_stride):
+//   hist[b * max_ctx + at.v[b]] = token, draft[b * draft_stride] = token.   grid (batch), block 512
+__global__ __launch_bounds__(AK_NT) void sample_seq_kernel(const float* __restrict__ logits, size_t row_stride, int V, float T,
+                                                           uint64_t seed, uint32_t round, uint32_t pos,
+                                                           int32_t* __restrict__ hist, int max_ctx, SeqTab at,
+                                                           int32_t* __restrict__ draft, int draft_stride) {
+    __shared__ AkShared sm;
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float xp[AK_CH][4];
+    ak_load(logits + (size_t)b * row_stride, V, wave, lane, xp);
+    int token;
+    if (T <= 0.f) {
+        token = ak_argmax(xp, sm, wave, lane);
+    } else {
+        const float u = philox_uniform(seed, (uint32_t)b, round, pos, 2u);
+        token = T == 1.0f ? sample_rows_body<true>(xp, V, T, u, sm, wave, lane) : sample_rows_body<false>(xp, V, T, u, sm, wave, lane);
+    }
+    if (threadIdx.x == 0) {
+        hist[(size_t)b * max_ctx + at.v[b]] = token;
+        draft[(size_t)b * draft_stride] = token;
+    }
+}
+
+// Commit of the emitted tokens: hist[b][l_b + n_acc[b]] = token[b].   grid (1), block 64
+__global__ void commit_tokens_kernel(const int32_t* __restrict__ n_acc, const int32_t* __restrict__ token, int32_t* __restrict__ hist,
+                                     int max_ctx, SeqTab l, int batch) {
+    const int b = threadIdx.x;
+    if (b >= batch) return;
+    const int tok = token[b];
+    if (tok >= 0) hist[(size_t)b * max_ctx + l.v[b] + n_acc[b]] = tok;
+}
+
+// ------------------------------------------------------------------------------------------
+// bf16 GEMM on MFMA for blocks of more than 16 rows (verification of a batch: R = batch x (gamma + 1)).
+//   out[ks][r][n] = sum over the K-slice of x[r][k] W[n][k],  W in streaming-tile order,
+//   x as two bf16 arrays (hi at xh, lo x_lo_off elements behind), row stride ldx.
+// One workgroup of 8 wavefronts owns 8 feature tiles (128 features) x one K-slice x all R rows:
+// wavefronts 0-3 the first four tiles, 4-7 the other four; within a quad wavefront w takes the
+// 16-row blocks w, w+4, ..  (RBW of them).  Per 32-wide K chunk the R x 32 activations (both terms)
+// are staged in LDS, double-buffered; a wavefront reads each activation fragment once and feeds it
+// to the four tiles it holds in registers (8 MFMAs per LDS read pair), so LDS reads stay far below
+// the MFMA rate.  Weights: PD chunks (4 KiB each per wavefront) in flight in registers; the two
+// wavefronts that share tiles request the same lines (L1 / L2 hits).  Activation pieces are
+// requested PD chunks ahead as well, so that a wavefront's in-order load returns never drain the
+// weight queue.   grid (ceil(ntiles/8) * ksplit), block 512,
+// dynamic LDS 2 * 8 * (64 RBW + 1) * 16 bytes;  R <= 64 RBW.
+template <int RBW, int PD>
+__global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __restrict__ xh, size_t x_lo_off, int ldx, int R, int K,
+                                                             const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
+                                                             const bf16_t* __restrict__ W2, int t0, int t1, int ntiles,
+                                                             float* __restrict__ out, size_t out_sstride, int N, int ksplit,
+                                                             int cps) {
+    extern __shared__ uint4 lds[];                 // [2 buffers][8 pieces (4 hi, 4 lo)][LR rows]
+    constexpr int R16 = 64 * RBW, LR = R16 + 1;
+    const int kchunks = K >> 5;
+    const int ks = blockIdx.x % ksplit, tg = blockIdx.x / ksplit;
+    const int c0 = ks * cps, nc = min(cps, kchunks - c0);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, quad = wave >> 2, wr = wave & 3;
+    const int row16 = lane & 15, g = lane >> 4;
+    const u32x4* wp[4];
+    int tl[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        tl[i] = tg * 8 + quad * 4 + i;
+        const int t = min(tl[i], ntiles - 1);
+        const bf16_t* W;
+        int tt;
+        if (t < t0) { W = W0; tt = t; }
+        else if (t < t1) { W = W1; tt = t - t0; }
+        else { W = W2; tt = t - t1; }
+        wp[i] = reinterpret_cast<const u32x4*>(W) + ((size_t)tt * kchunks + c0) * 64 + lane;
+    }
+    // every load is unconditional and clamped into range: chunks past the slice's end re-read its last
+    // chunk and are multiplied by zero
+    auto wload = [&](u32x4 (&dst)[4], int c) {
+        const int cc = min(c, nc - 1);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dst[i] = __builtin_nontemporal_load(wp[i] + (size_t)cc * 64);
+    };
+    auto aload = [&](u32x4 (&dst)[RBW], int c) {
+        const int cc = min(c, nc - 1);
+#pragma unroll
+        for (int u = 0; u < RBW; ++u) {
+            const int idx = tid + 512 * u, row = min(idx >> 3, R - 1), which = idx & 7;
+            const bf16_t* src = xh + (size_t)row * ldx + (size_t)(c0 + cc) * 32 + (which & 3) * 8 + ((which >> 2) ? x_lo_off : (size_t)0);
+            dst[u] = *reinterpret_cast<const u32x4*>(src);
+        }
+    };
+    auto astore = [&](const u32x4 (&src)[RBW], int buf) {
+        uint4* base = lds + (size_t)buf * 8 * LR;
+#pragma unroll
+        for (int u = 0; u < RBW; ++u) {
+            const int idx = tid + 512 * u;
+            base[(idx & 7) * LR + (idx >> 3)] = __builtin_bit_cast(uint4, src[u]);
+        }
+    };
+    f32x4 acc[RBW][4];
+#pragma unroll
+    for (int a = 0; a < RBW; ++a)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[a][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    auto compute = [&](const u32x4 (&w)[4], int buf, bool live) {
+        const uint4* base = lds + (size_t)buf * 8 * LR;
+#pragma unroll
+        for (int a = 0; a < RBW; ++a) {
+            const int rowi = (wr + 4 * a) * 16 + row16;
+            uint4 bh = base[g * LR + rowi], bl = base[(4 + g) * LR + rowi];
+            if (!live) { bh = zero; bl = zero; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[i]), __builtin_bit_cast(bf16x8, bh), acc[a][i], 0, 0, 0);
+                acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[i]), __builtin_bit_cast(bf16x8, bl), acc[a][i], 0, 0, 0);
+            }
+        }
+    };
+    u32x4 w[PD][4], ar[PD][RBW], a0[RBW];
+    aload(a0, 0);
+#pragma unroll
+    for (int u = 0; u < PD; ++u) aload(ar[u], 1 + u);
+#pragma unroll
+    for (int u = 0; u < PD; ++u) wload(w[u], u);
+    astore(a0, 0);
+    lds_barrier();
+    for (int cb = 0; cb < nc; cb += PD) {
+#pragma unroll
+        for (int u = 0; u < PD; ++u) {
+            const int c = cb + u;
+            astore(ar[u], (c + 1) & 1);            // chunk c+1, requested PD iterations ago
+            aload(ar[u], c + 1 + PD);
+            compute(w[u], c & 1, c < nc);
+            wload(w[u], c + PD);
+            lds_barrier();
+        }
+    }
+#pragma unroll
+    for (int a = 0; a < RBW; ++a) {
+        const int row = (wr + 4 * a) * 16 + row16;
+        if (row < R) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (tl[i] < ntiles) {
+                    float* o = out + (size_t)ks * out_sstride + (size_t)row * N + (size_t)tl[i] * 16 + g * 4;
+                    *reinterpret_cast<float4*>(o) = make_float4(acc[a][i][0], acc[a][i][1], acc[a][i][2], acc[a][i][3]);
+                }
+        }
+    }
+}
+
+}  // namespace msd

@@ -819,10 +819,12 @@ __global__ void rope_table_kernel(int pos0, int hd, float theta, double2* __rest
     tab[r * half + i] = make_double2(cs, sn);
 }
 
+// Body for block row r = blockIdx.y at position pos; write_kv = false for padding rows (q is still written).
 template <typename T>
-__global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int N, int pos0, int H, int KH,
-                               int hd, const double2* __restrict__ tab, float* __restrict__ q, T* __restrict__ kc,
-                               T* __restrict__ vc, int max_ctx, int interleaved, int q_split, const float* __restrict__ inv) {
+__device__ __forceinline__ void rope_kv_body(const float* __restrict__ part, int nsplit, size_t sstride, int N, int pos, int H,
+                                             int KH, int hd, const double2* __restrict__ tab, float* __restrict__ q,
+                                             T* __restrict__ kc, T* __restrict__ vc, int max_ctx, int interleaved, int q_split,
+                                             const float* __restrict__ inv, bool write_kv) {
     const int head = blockIdx.x, r = blockIdx.y, i = threadIdx.x, half = hd >> 1;
     if (i >= half) return;
     // interleaved (rope-ordered packed weights): q / k columns hold the pair (i, i + half) at 16(i/8) + 2(i%8), +1
@@ -844,7 +846,6 @@ __global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_
             if (s0 + u < nsplit) { a += pa[u]; b += pb[u]; }
     }
     if (inv) { const float sc = inv[r]; a *= sc; b *= sc; }   // 1/rms of the input row (the projection ran on h * gain)
-    const int pos = pos0 + r;
     if (head < H + KH) {
         const double cs = cssn.x, sn = cssn.y;
         const float ra = (float)((double)a * cs - (double)b * sn);
@@ -865,11 +866,20 @@ __global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_
         qd[i + half] = b;
         return;
     }
+    if (!write_kv) return;
     T* dst;
     if (head < H + KH) dst = kc + ((size_t)(head - H) * max_ctx + pos) * hd;
     else dst = vc + ((size_t)(head - H - KH) * max_ctx + pos) * hd;
     dst[i] = El<T>::st(a);
     dst[i + half] = El<T>::st(b);
+}
+
+template <typename T>
+__global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int N, int pos0, int H, int KH,
+                               int hd, const double2* __restrict__ tab, float* __restrict__ q, T* __restrict__ kc,
+                               T* __restrict__ vc, int max_ctx, int interleaved, int q_split, const float* __restrict__ inv) {
+    rope_kv_body<T>(part, nsplit, sstride, N, pos0 + (int)blockIdx.y, H, KH, hd, tab, q, kc, vc, max_ctx, interleaved, q_split, inv,
+                    true);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -882,9 +892,9 @@ __global__ void rope_kv_kernel(const float* __restrict__ part, int nsplit, size_
 constexpr int ATT_CH = 128;
 
 template <typename T, int HD>
-__global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restrict__ q, const T* __restrict__ kc,
-                                                           const T* __restrict__ vc, int m, int pos0, int H, int KH,
-                                                           int max_ctx, float scale, float* __restrict__ part, int nchunks) {
+__device__ __forceinline__ void attn_partial_body(const float* __restrict__ q, const T* __restrict__ kc,
+                                                  const T* __restrict__ vc, int m, int pos0, int H, int KH, int max_ctx,
+                                                  float scale, float* __restrict__ part, int nchunks, int c, int h) {
     constexpr int EPV = 16 / (int)sizeof(T);     // elements per 16-byte piece
     constexpr int RS = HD + EPV;                 // padded LDS row stride (elements)
     constexpr int VPR = HD / EPV;                // 16-byte pieces per row
@@ -896,7 +906,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
     __shared__ float mrow[16], lrow[16];
     T* kv = reinterpret_cast<T*>(kvraw);
 
-    const int c = blockIdx.x, h = blockIdx.y, kh = h / (H / KH);
+    const int kh = h / (H / KH);
     const int L = pos0 + m;
     const int p0 = c * ATT_CH;
     const int np = min(ATT_CH, L - p0);
@@ -997,6 +1007,13 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
     }
 }
 
+template <typename T, int HD>
+__global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restrict__ q, const T* __restrict__ kc,
+                                                           const T* __restrict__ vc, int m, int pos0, int H, int KH,
+                                                           int max_ctx, float scale, float* __restrict__ part, int nchunks) {
+    attn_partial_body<T, HD>(q, kc, vc, m, pos0, H, KH, max_ctx, scale, part, nchunks, (int)blockIdx.x, (int)blockIdx.y);
+}
+
 // bf16-cache variant on MFMA.  One workgroup (4 wavefronts) per (chunk of 128 positions, query head):
 //   S^T[pos][row] = K[pos][:] . q[row][:]   A = K rows straight from global (16 B per lane, no LDS),
 //                                           B = q as two bf16 terms (hi + lo); wavefront w owns
@@ -1007,10 +1024,12 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
 //                                           wavefront w owns head-dim tiles {w, w+4, ..}.
 // Output layout and the combine kernel are shared with the generic kernel above.
 
+// q_lo_off: distance (elements) from the hi array of q to its lo array (rows of the whole block x H x HD).
 template <int HD>
-__global__ __launch_bounds__(256) void attn_partial_mfma_kernel(const float* __restrict__ q, const bf16_t* __restrict__ kc,
-                                                                const bf16_t* __restrict__ vc, int m, int pos0, int H, int KH,
-                                                                int max_ctx, float scale, float* __restrict__ part, int nchunks) {
+__device__ __forceinline__ void attn_partial_mfma_body(const float* __restrict__ q, const bf16_t* __restrict__ kc,
+                                                       const bf16_t* __restrict__ vc, int m, int pos0, int H, int KH,
+                                                       int max_ctx, float scale, float* __restrict__ part, int nchunks, int c,
+                                                       int h, size_t q_lo_off) {
     constexpr int RS = HD + 8;                 // padded LDS row stride of the V chunk (elements)
     constexpr int VPR = HD / 8;                // 16-byte pieces per row
     constexpr int PS = ATT_CH + 8;             // padded row stride of P (elements)
@@ -1021,7 +1040,7 @@ __global__ __launch_bounds__(256) void attn_partial_mfma_kernel(const float* __r
     __shared__ __align__(16) bf16_t plo[16 * PS];
     __shared__ float wmax[4][16], wsum[4][16];
 
-    const int c = blockIdx.x, h = blockIdx.y, kh = h / (H / KH);
+    const int kh = h / (H / KH);
     const int L = pos0 + m;
     const int p0 = c * ATT_CH;
     const int np = min(ATT_CH, L - p0);
@@ -1048,7 +1067,7 @@ __global__ __launch_bounds__(256) void attn_partial_mfma_kernel(const float* __r
         if (rowok) {
             const bf16_t* src = reinterpret_cast<const bf16_t*>(q) + (size_t)row * H * HD + (size_t)h * HD + k * 32 + g * 8;
             qh[k] = *reinterpret_cast<const uint4*>(src);
-            ql[k] = *reinterpret_cast<const uint4*>(src + (size_t)m * H * HD);
+            ql[k] = *reinterpret_cast<const uint4*>(src + q_lo_off);
         }
     }
     // ---- scores of this wavefront's 32 positions: two 16-position tiles
@@ -1141,10 +1160,21 @@ __global__ __launch_bounds__(256) void attn_partial_mfma_kernel(const float* __r
     }
 }
 
-template <typename T, int HD>
-__global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks, int H, float* __restrict__ out, int split) {
-    const int h = blockIdx.x, r = blockIdx.y, col = threadIdx.x;
-    const float* base = part + ((size_t)h * nchunks * 16 + r) * (HD + 2);
+template <int HD>
+__global__ __launch_bounds__(256) void attn_partial_mfma_kernel(const float* __restrict__ q, const bf16_t* __restrict__ kc,
+                                                                const bf16_t* __restrict__ vc, int m, int pos0, int H, int KH,
+                                                                int max_ctx, float scale, float* __restrict__ part, int nchunks) {
+    attn_partial_mfma_body<HD>(q, kc, vc, m, pos0, H, KH, max_ctx, scale, part, nchunks, (int)blockIdx.x, (int)blockIdx.y,
+                               (size_t)m * H * HD);
+}
+
+// Merge of the chunk records of (head h, block row r): nchunks records are merged, records of one head are
+// nch_stride chunks apart; the result goes to row r_out of out (split: as two bf16 arrays lo_off elements apart).
+template <int HD>
+__device__ __forceinline__ void attn_combine_body(const float* __restrict__ part, int nchunks, int nch_stride, int H,
+                                                  float* __restrict__ out, int split, int h, int r, int r_out, size_t lo_off) {
+    const int col = threadIdx.x;
+    const float* base = part + ((size_t)h * nch_stride * 16 + r) * (HD + 2);
     const size_t cs = (size_t)16 * (HD + 2);
     float M = -INFINITY;
     for (int c0 = 0; c0 < nchunks; c0 += 8) {           // eight chunk records in flight
@@ -1171,8 +1201,14 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks,
             o += oc[u] * w;
         }
     }
-    if (split) store_split1(out, (size_t)gridDim.y * H * HD, (size_t)r * H * HD + (size_t)h * HD + col, o / Lsum);
-    else out[(size_t)r * H * HD + (size_t)h * HD + col] = o / Lsum;
+    if (split) store_split1(out, lo_off, (size_t)r_out * H * HD + (size_t)h * HD + col, o / Lsum);
+    else out[(size_t)r_out * H * HD + (size_t)h * HD + col] = o / Lsum;
+}
+
+template <typename T, int HD>
+__global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks, int H, float* __restrict__ out, int split) {
+    attn_combine_body<HD>(part, nchunks, nchunks, H, out, split, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.y,
+                          (size_t)gridDim.y * H * HD);
 }
 
 // ------------------------------------------------------------------------------------------

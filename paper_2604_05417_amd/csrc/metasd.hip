@@ -18,6 +18,7 @@
 
 #include "kernels.h"
 #include "persist.h"
+#include "batch.h"
 
 using namespace msd;
 
@@ -39,6 +40,7 @@ constexpr int PER_LAYER = 9;
 constexpr int MAX_ROWS = 16;
 constexpr size_t ALIGN = 256;
 constexpr int LDS_BUDGET = 60 * 1024;
+constexpr int ROWS_PD = 4;                    // gemm_bf16_rows_kernel: chunks in flight (2 for the 512-row variant)
 constexpr size_t FULLK_LDS_MAX = 150 * 1024;   // gemm_fullk_residual_kernel: the whole activation block in LDS
 
 size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
@@ -49,7 +51,7 @@ struct Model {
     std::vector<const void*> w;
     void* kv = nullptr;
     int hd = 0;
-    int kv_len = 0;  // positions valid in the KV cache
+    std::vector<int> kvl;   // positions valid in the KV cache, per sequence
     const void** d_table = nullptr;   // device copy of w (persistent kernel)
     const void* layer_w(int L, int i) const { return w[1 + PER_LAYER * L + i]; }
     const void* final_norm() const { return w[1 + PER_LAYER * d.n_layers]; }
@@ -87,6 +89,18 @@ Split choose_split(int m, int ntiles, int kchunks) {
     s.cps = cps;
     s.tpb = 4;
     s.lds = (size_t)2 * m * (cps * 4 + 1) * 16;
+    return s;
+}
+
+// Split of a gemm_bf16_rows_kernel launch: 8 tiles per workgroup, K split until about one workgroup per CU.
+Split choose_split_rows(int ntiles, int kchunks) {
+    const int groups = (ntiles + 7) / 8;
+    int ks = std::max(1, std::min({(256 + groups - 1) / groups, 8, std::max(1, kchunks / 8)}));
+    int cps = (kchunks + ks - 1) / ks;
+    cps = (cps + ROWS_PD - 1) / ROWS_PD * ROWS_PD;
+    ks = (kchunks + cps - 1) / cps;
+    Split s;
+    s.ksplit = ks; s.cps = cps; s.tpb = 8; s.lds = 0;
     return s;
 }
 
@@ -129,6 +143,10 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
             // a smaller m never needs more splits for LDS, but may use up to 8 for parallelism
             ksplit = std::max(ksplit, ks_cap());
             partmax = std::max(partmax, (size_t)ksplit * MAX_ROWS * ns[i] * sizeof(float));
+            if (c.batch > 1) {
+                const int kr = d.dtype == METASD_BF16 ? choose_split_rows(ns[i] / 16, ks[i] / 32).ksplit : 1;
+                partmax = std::max(partmax, (size_t)std::max(kr, ksplit) * MAX_ROWS * c.batch * ns[i] * sizeof(float));
+            }
         }
     };
     acc(t);
@@ -137,28 +155,29 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     Layout L{};
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes); return at; };
-    L.hist = take((size_t)c.max_ctx * 4);
-    L.h = take((size_t)MAX_ROWS * dmax * 4);
+    const size_t B = (size_t)c.batch, RM = (size_t)MAX_ROWS * B;   // sequences, rows of the largest block
+    L.hist = take(B * c.max_ctx * 4);
+    L.h = take(RM * dmax * 4);
     L.h2 = take((size_t)MAX_ROWS * dmax * 4);
-    L.xn = take((size_t)MAX_ROWS * dmax * 4);
+    L.xn = take(RM * dmax * 4);
     L.part = take(partmax);
     L.part2 = take(partmax);
     L.gx = take((size_t)ks_cap() * MAX_ROWS * dmax * 8);          // tagged partial sums of the residual GEMMs
     L.ssq = take((size_t)(dmax / 16 + 1) * 16 * 4);              // per tile group (or per tile) and row
     L.inv = take(64);
-    L.q = take((size_t)MAX_ROWS * dmax * 4);
-    L.ao = take((size_t)MAX_ROWS * dmax * 4);
-    L.act = take((size_t)MAX_ROWS * fmax * 4 * 2);          // also the fused gate | up result
-    L.apart = take((size_t)hmax * nchunks * 16 * (hdmax + 2) * 4);
-    L.rope = take((size_t)MAX_ROWS * (hdmax / 2) * sizeof(double2));
-    L.P = take((size_t)(c.gamma_max + 1) * vmax * 4);
-    L.Q = take((size_t)c.gamma_max * vmax * 4);
-    L.cand = take((size_t)(c.gamma_max + 1) * sizeof(int2));
-    L.bd = take((size_t)c.gamma_max * sizeof(double));
-    L.res = take(64);
-    L.draft = take(64);
+    L.q = take(RM * dmax * 4);
+    L.ao = take(RM * dmax * 4);
+    L.act = take(RM * fmax * 4 * 2);          // also the fused gate | up result
+    L.apart = take(B * hmax * nchunks * 16 * (hdmax + 2) * 4);
+    L.rope = take(RM * (hdmax / 2) * sizeof(double2));
+    L.P = take(B * (c.gamma_max + 1) * vmax * 4);
+    L.Q = take(B * c.gamma_max * vmax * 4);
+    L.cand = take(B * (c.gamma_max + 1) * sizeof(int2));
+    L.bd = take(B * c.gamma_max * sizeof(double));
+    L.res = take(std::max<size_t>(64, B * 12));
+    L.draft = take(std::max<size_t>(64, B * c.gamma_max * 4));
     L.bar = take(sizeof(GridBar));
-    L.xchg = take((size_t)(c.gamma_max + 1) * AS_XCHG_BYTES);
+    L.xchg = take(B * (c.gamma_max + 1) * AS_XCHG_BYTES);
     int lmax = t.n_layers;
     for (int k = 0; k < c.K; ++k) lmax = std::max(lmax, dr[k].n_layers);
     L.table_stride = align_up((size_t)(1 + PER_LAYER * lmax + 2) * sizeof(void*));
@@ -186,6 +205,7 @@ struct Bandit {
     int K = 0, t = 0, policy = METASD_POLICY_UCB, window = 0;
     double beta = 1.0, param = 1.0;
     uint64_t seed = 0;
+    uint32_t seq = 0;           // sequence id: first Philox counter word of this bandit's draws
     std::vector<double> mu;     // reported estimate per arm
     std::vector<int> n;         // reported count per arm
     std::vector<double> aux;    // D-UCB: discounted reward sums; EXP3: weights; SH: reward sums of the phase
@@ -245,13 +265,13 @@ struct Bandit {
                 double tot = 0.0;
                 for (double w : aux) tot += w;
                 for (int i = 0; i < K; ++i) prob[i] = (1.0 - param) * (aux[i] / tot) + param / (double)K;
-                return draw(prob, (double)host_philox_uniform(seed, 0u, (uint32_t)t, 0u, 3u));
+                return draw(prob, (double)host_philox_uniform(seed, seq, (uint32_t)t, 0u, 3u));
             }
             case METASD_POLICY_SH:
                 return alive.size() == 1 ? alive[0] : alive[sh_pos / sh_pulls()];
             default: {                                   // METASD_POLICY_RANDOM
                 std::vector<double> p(K, 1.0 / (double)K);
-                return draw(p, (double)host_philox_uniform(seed, 0u, (uint32_t)t, 0u, 3u));
+                return draw(p, (double)host_philox_uniform(seed, seq, (uint32_t)t, 0u, 3u));
             }
         }
     }
@@ -330,13 +350,23 @@ struct metasd_ctx {
     hipStream_t stream = nullptr;
     char* ws = nullptr;
     Layout lay{};
-    std::vector<int32_t> hist;   // host mirror of committed tokens
-    int l = 0;                   // committed tokens
-    int round = 0;
-    int cur_k = -1, cur_gamma = 0;
+    struct SeqState {
+        std::vector<int32_t> hist;   // host mirror of committed tokens
+        int l = 0;                   // committed tokens
+        int cur_k = -1;              // drafter of the running round
+        bool ready = false;          // a context has been set
+        Bandit bandit;
+    };
+    std::vector<SeqState> sq;        // one per sequence (cfg.batch)
+    int round = 0;                   // rounds completed since the contexts were set (all sequences advance together)
+    int cur_gamma = 0;
     Phase phase = PH_NONE;
-    Bandit bandit;
     HostResult* hres = nullptr;
+    char* hbatch = nullptr;      // pinned results of a batched accept: int32 n_acc[B], token[B], mask[B], d[B][gamma_max]; double bd[B][gamma_max]; GridBar
+    size_t hb_d() const { return (size_t)cfg.batch * 12; }
+    size_t hb_bd() const { return (hb_d() + (size_t)cfg.batch * cfg.gamma_max * 4 + 7) / 8 * 8; }
+    size_t hb_bar() const { return hb_bd() + (size_t)cfg.batch * cfg.gamma_max * 8; }
+    size_t hb_bytes() const { return hb_bar() + sizeof(GridBar); }
     std::string err;
     // optional per-launch timing of the three bandwidth-bound kernels (metasd_profile)
     struct ProfRec { hipEvent_t a, b; int kind; double bytes; };
@@ -854,8 +884,239 @@ int forward(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool want_a
         if (rc) return rc;
         done += m;
     }
-    M.kv_len = pos0 + n;
+    M.kvl[0] = pos0 + n;
     return 0;
+}
+
+
+// ================================================================================================
+// Blocks of rows from several sequences (cfg.batch > 1): the plain step-by-step forward on the
+// segment-aware kernels of batch.h.  Rows R = sg.n * sg.ms; row-wise kernels (add+norm, activation)
+// are the single-sequence ones launched over R rows.
+
+// GEMM over R rows into split-K partials part[s][R][N] (split stride R*N).
+template <typename T>
+int gemm_rows(metasd_ctx* c, const void* x, int ldx, int R, int K, const void* W0, int n0, const void* W1, int n1, const void* W2,
+              int n2, int* nsplit_out);
+
+template <>
+int gemm_rows<float>(metasd_ctx* c, const void* x, int ldx, int R, int K, const void* W0, int n0, const void* W1, int n1,
+                     const void* W2, int n2, int* nsplit_out) {
+    const int N = n0 + n1 + n2;
+    for (int r0 = 0; r0 < R; r0 += MAX_ROWS) {
+        hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 3) / 4), dim3(256), 0, c->stream, (const float*)x + (size_t)r0 * ldx, ldx,
+                           std::min(MAX_ROWS, R - r0), K, (const float*)W0, (const float*)W1, (const float*)W2, n0, n0 + n1, N,
+                           c->d_part() + (size_t)r0 * N);
+        LAUNCH_CHECK(c, "gemm_f32");
+    }
+    *nsplit_out = 1;
+    return 0;
+}
+
+// more than 64 KiB of dynamic LDS needs the function attribute (set once per variant; harmless below the limit)
+template <int RBW, int PD>
+int rows_lds_attr(metasd_ctx* c) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        const size_t lds = (size_t)2 * 8 * (64 * RBW + 1) * 16;
+        if (hipFuncSetAttribute((const void*)gemm_bf16_rows_kernel<RBW, PD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return c->fail(METASD_E_HIP, "gemm_bf16_rows_kernel: cannot reserve %zu bytes of LDS", lds);
+        attr_set = true;
+    }
+    return 0;
+}
+
+template <int RBW, int PD>
+int launch_gemm_rows(metasd_ctx* c, const bf16_t* xh, size_t x_lo_off, int ldx, int R, int K, const void* W0, const void* W1,
+                     const void* W2, int t0, int t1, int ntiles, float* out, int N, const Split& s, metasd_ctx::ProfRec* pr) {
+    const size_t lds = (size_t)2 * 8 * (64 * RBW + 1) * 16;
+    if (int rc = rows_lds_attr<RBW, PD>(c)) return rc;
+    const int groups = (ntiles + 7) / 8;
+    hipExtLaunchKernelGGL((gemm_bf16_rows_kernel<RBW, PD>), dim3(groups * s.ksplit), dim3(512), (uint32_t)lds, c->stream,
+                          pr ? pr->a : nullptr, pr ? pr->b : nullptr, 0u, xh, x_lo_off, ldx, R, K, (const bf16_t*)W0, (const bf16_t*)W1,
+                          (const bf16_t*)W2, t0, t1, ntiles, out, (size_t)R * N, N, s.ksplit, s.cps);
+    LAUNCH_CHECK(c, "gemm_bf16_rows");
+    return 0;
+}
+
+// rows [r0, r0 + nr) of a block of R rows (nr <= 256)
+int launch_gemm_rows_off(metasd_ctx* c, const bf16_t* xh, size_t x_lo_off, int ldx, int R, int r0, int nr, int K, const void* W0,
+                         const void* W1, const void* W2, int t0, int t1, int ntiles, int N, const Split& s, metasd_ctx::ProfRec* pr) {
+    const size_t lds = (size_t)2 * 8 * (64 * 4 + 1) * 16;
+    if (int rc = rows_lds_attr<4, ROWS_PD>(c)) return rc;
+    const int groups = (ntiles + 7) / 8;
+    hipExtLaunchKernelGGL((gemm_bf16_rows_kernel<4, ROWS_PD>), dim3(groups * s.ksplit), dim3(512), (uint32_t)lds, c->stream,
+                          pr ? pr->a : nullptr, pr ? pr->b : nullptr, 0u, xh + (size_t)r0 * ldx, x_lo_off, ldx, nr, K, (const bf16_t*)W0,
+                          (const bf16_t*)W1, (const bf16_t*)W2, t0, t1, ntiles, c->d_part() + (size_t)r0 * N, (size_t)R * N, N, s.ksplit, s.cps);
+    LAUNCH_CHECK(c, "gemm_bf16_rows");
+    return 0;
+}
+
+template <>
+int gemm_rows<bf16_t>(metasd_ctx* c, const void* x, int ldx, int R, int K, const void* W0, int n0, const void* W1, int n1,
+                      const void* W2, int n2, int* nsplit_out) {
+    const size_t x_lo_off = (size_t)R * ldx;      // producers write hi [R][ldx], then lo [R][ldx]
+    if (R <= MAX_ROWS) return gemm<bf16_t>(c, x, ldx, R, K, W0, n0, W1, n1, W2, n2, nullptr, nsplit_out, x_lo_off);
+    const int N = n0 + n1 + n2, ntiles = N / 16, kchunks = K / 32;
+    const Split s = choose_split_rows(ntiles, kchunks);
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)R * K * 4 + (double)R * N * 4 * s.ksplit);
+    const bf16_t* xh = (const bf16_t*)x;
+    const int t0 = n0 / 16, t1 = (n0 + n1) / 16;
+    int rc;
+    if (R <= 64) rc = launch_gemm_rows<1, ROWS_PD>(c, xh, x_lo_off, ldx, R, K, W0, W1, W2, t0, t1, ntiles, c->d_part(), N, s, pr);
+    else if (R <= 128) rc = launch_gemm_rows<2, ROWS_PD>(c, xh, x_lo_off, ldx, R, K, W0, W1, W2, t0, t1, ntiles, c->d_part(), N, s, pr);
+    else if (R <= 256) rc = launch_gemm_rows<4, ROWS_PD>(c, xh, x_lo_off, ldx, R, K, W0, W1, W2, t0, t1, ntiles, c->d_part(), N, s, pr);
+    else {   // more than 256 rows: two passes over the weights, 256 rows each (the 512-row variant would spill registers)
+        rc = 0;
+        for (int r0 = 0; r0 < R && !rc; r0 += 256)
+            rc = launch_gemm_rows_off(c, xh, x_lo_off, ldx, R, r0, std::min(256, R - r0), K, W0, W1, W2, t0, t1, ntiles, N, s, r0 ? nullptr : pr);
+    }
+    *nsplit_out = s.ksplit;
+    return rc;
+}
+
+template <typename T, int HD>
+int attention_seg_hd(metasd_ctx* c, const Model& M, int L, const Segs& sg) {
+    const metasd_model_desc& d = M.d;
+    const int R = sg.n * sg.ms;
+    const size_t plane = (size_t)d.n_kv_heads * c->cfg.max_ctx * HD;
+    const size_t seq_stride = (size_t)d.n_layers * 2 * plane;
+    const T* kc = (const T*)M.kv + (size_t)L * 2 * plane;
+    const T* vc = kc + plane;
+    int nch_max = 1;
+    double kvpos = 0.0;
+    for (int s = 0; s < sg.n; ++s) {
+        nch_max = std::max(nch_max, (sg.pos0[s] + sg.m[s] + ATT_CH - 1) / ATT_CH);
+        kvpos += (double)(sg.pos0[s] + sg.m[s]);
+    }
+    const float scale = 1.0f / sqrtf((float)HD);
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_ATTN, 2.0 * d.n_kv_heads * kvpos * HD * sizeof(T) + (double)R * d.n_heads * HD * 4);
+    hipEvent_t ea = pr ? pr->a : nullptr, eb = pr ? pr->b : nullptr;
+    if constexpr (sizeof(T) == 2 && HD >= 64) {
+        hipExtLaunchKernelGGL((attn_partial_mfma_seg_kernel<HD>), dim3(nch_max, d.n_heads, sg.n), dim3(256), 0u, c->stream, ea, eb, 0u,
+                              (const float*)c->d_q(), kc, vc, seq_stride, sg, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale,
+                              c->d_apart(), nch_max, (size_t)R * d.n_heads * HD);
+    } else {
+        hipExtLaunchKernelGGL((attn_partial_seg_kernel<T, HD>), dim3(nch_max, d.n_heads, sg.n), dim3(256), 0u, c->stream, ea, eb, 0u,
+                              (const float*)c->d_q(), kc, vc, seq_stride, sg, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale,
+                              c->d_apart(), nch_max);
+    }
+    LAUNCH_CHECK(c, "attn_partial (segments)");
+    hipLaunchKernelGGL((attn_combine_seg_kernel<HD>), dim3(d.n_heads, R), dim3(HD), 0, c->stream, c->d_apart(), nch_max, d.n_heads,
+                       (float*)c->d_ao(), sizeof(T) == 2 ? 1 : 0, sg);
+    LAUNCH_CHECK(c, "attn_combine (segments)");
+    return 0;
+}
+
+template <typename T>
+int attention_seg(metasd_ctx* c, const Model& M, int L, const Segs& sg) {
+    switch (M.hd) {
+        case 32: return attention_seg_hd<T, 32>(c, M, L, sg);
+        case 64: return attention_seg_hd<T, 64>(c, M, L, sg);
+        default:
+            if constexpr (sizeof(T) == 2) return attention_seg_hd<T, 128>(c, M, L, sg);
+            return c->fail(METASD_E_INVALID, "fp32 head_dim 128 unsupported");
+    }
+}
+
+// Forward of the block sg through model M; appends K/V of the valid rows.  logits == nullptr: none.
+// Otherwise the rows that carry logits are written to logits[(seq * out_seq_rows + out_row0 + j) * V]
+// (last_only: only the last valid row of each segment, at j = 0).
+template <typename T>
+int forward_segs_t(metasd_ctx* c, Model& M, const Segs& sg, float* logits, int out_seq_rows, int out_row0, int last_only) {
+    const metasd_model_desc& d = M.d;
+    const int D = d.d_model, H = d.n_heads, KH = d.n_kv_heads, hd = M.hd, F = d.d_ffn, V = d.vocab;
+    const int DQ = H * hd, DKV = KH * hd, NQKV = DQ + 2 * DKV;
+    const int R = sg.n * sg.ms;
+    hipStream_t st = c->stream;
+    float* h = c->d_h();
+    float* xn = (float*)c->d_xn();
+    float* part = c->d_part();
+    int ns = 0, rc;
+    constexpr int split = sizeof(T) == 2 ? 1 : 0;
+    const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
+    const size_t seq_stride = (size_t)d.n_layers * 2 * plane;
+    hipLaunchKernelGGL(embed_seg_kernel<T>, dim3(R), dim3(256), 0, st, (const int32_t*)c->d_hist(), c->cfg.max_ctx, (const T*)M.w[0], D, h, sg);
+    LAUNCH_CHECK(c, "embed (segments)");
+    hipLaunchKernelGGL(rope_table_seg_kernel, dim3(R), dim3(hd / 2), 0, st, sg, hd, d.rope_theta, c->d_rope());
+    LAUNCH_CHECK(c, "rope_table (segments)");
+    for (int L = 0; L < d.n_layers; ++L) {
+        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(R), dim3(1024), 0, st, h, part, ns, (size_t)R * D, D, (const T*)M.layer_w(L, 0),
+                           d.rms_eps, xn, split);
+        LAUNCH_CHECK(c, "addnorm");
+        if ((rc = gemm_rows<T>(c, xn, D, R, D, M.layer_w(L, 1), DQ, M.layer_w(L, 2), DKV, M.layer_w(L, 3), DKV, &ns))) return rc;
+        T* kc = (T*)M.kv + (size_t)L * 2 * plane;
+        hipLaunchKernelGGL(rope_kv_seg_kernel<T>, dim3(H + 2 * KH, R), dim3(64), 0, st, part, ns, (size_t)R * NQKV, NQKV, sg, H, KH, hd,
+                           (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, seq_stride, c->cfg.max_ctx, split,
+                           (split && hd >= 64) ? 1 : 0);
+        LAUNCH_CHECK(c, "rope_kv (segments)");
+        if ((rc = attention_seg<T>(c, M, L, sg))) return rc;
+        if ((rc = gemm_rows<T>(c, c->d_ao(), DQ, R, DQ, M.layer_w(L, 4), D, nullptr, 0, nullptr, 0, &ns))) return rc;
+        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(R), dim3(1024), 0, st, h, part, ns, (size_t)R * D, D, (const T*)M.layer_w(L, 5),
+                           d.rms_eps, xn, split);
+        LAUNCH_CHECK(c, "addnorm");
+        if (d.act == METASD_SWIGLU) {
+            if ((rc = gemm_rows<T>(c, xn, D, R, D, M.layer_w(L, 6), F, M.layer_w(L, 7), F, nullptr, 0, &ns))) return rc;
+        } else {
+            if ((rc = gemm_rows<T>(c, xn, D, R, D, M.layer_w(L, 7), F, nullptr, 0, nullptr, 0, &ns))) return rc;
+        }
+        const size_t nact = (size_t)R * F;
+        const int NF = (d.act == METASD_SWIGLU ? 2 : 1) * F;
+        hipLaunchKernelGGL(ffn_act_kernel, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)R * NF, R, F, d.act,
+                           (float*)c->d_act(), split, (const float*)nullptr);
+        LAUNCH_CHECK(c, "ffn_act");
+        if ((rc = gemm_rows<T>(c, c->d_act(), F, R, F, M.layer_w(L, 8), D, nullptr, 0, nullptr, 0, &ns))) return rc;
+    }
+    if (logits) {
+        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(R), dim3(1024), 0, st, h, part, ns, (size_t)R * D, D, (const T*)M.final_norm(),
+                           d.rms_eps, xn, split);
+        LAUNCH_CHECK(c, "addnorm");
+        if ((rc = gemm_rows<T>(c, xn, D, R, D, M.lm_head(), V, nullptr, 0, nullptr, 0, &ns))) return rc;
+        hipLaunchKernelGGL(sum_partials_seg_kernel, dim3((V + 255) / 256, R), dim3(256), 0, st, (const float*)part, ns, (size_t)R * V, V,
+                           logits, sg, out_seq_rows, out_row0, last_only);
+        LAUNCH_CHECK(c, "sum_partials (segments)");
+    }
+    for (int s = 0; s < sg.n; ++s) M.kvl[sg.seq[s]] = sg.pos0[s] + sg.m[s];
+    return 0;
+}
+
+int forward_segs(metasd_ctx* c, Model& M, const Segs& sg, float* logits, int out_seq_rows, int out_row0, int last_only) {
+    for (int s = 0; s < sg.n; ++s)
+        if (sg.pos0[s] + sg.m[s] > c->cfg.max_ctx)
+            return c->fail(METASD_E_OVERFLOW, "sequence %d: positions %d..%d exceed max_ctx %d", sg.seq[s], sg.pos0[s], sg.pos0[s] + sg.m[s], c->cfg.max_ctx);
+    if (M.d.dtype == METASD_BF16) return forward_segs_t<bf16_t>(c, M, sg, logits, out_seq_rows, out_row0, last_only);
+    return forward_segs_t<float>(c, M, sg, logits, out_seq_rows, out_row0, last_only);
+}
+
+// Model M processes, for every listed sequence, the tokens at positions [M.kvl[seq], upto[seq]) in blocks of
+// at most 16 rows per sequence.  logits (optional): the logits of each sequence's last token go to
+// logits[(seq * out_seq_rows + out_row0) * V].
+int catch_up(metasd_ctx* c, Model& M, const std::vector<int>& seqs, const std::vector<int>& upto, float* logits, int out_seq_rows,
+             int out_row0) {
+    for (;;) {
+        Segs sg{};
+        int pend_max = 0;
+        bool more = false;
+        for (size_t i = 0; i < seqs.size(); ++i) {
+            const int b = seqs[i], pend = upto[i] - M.kvl[b];
+            if (pend <= 0) continue;
+            const int s = sg.n++;
+            sg.seq[s] = b; sg.pos0[s] = M.kvl[b]; sg.m[s] = std::min(MAX_ROWS, pend);
+            pend_max = std::max(pend_max, sg.m[s]);
+            more = more || pend > MAX_ROWS;
+        }
+        if (sg.n == 0) return 0;
+        sg.ms = pend_max;
+        // logits are only needed from a sequence's last block; every block that ends a sequence computes them
+        bool ends = false;
+        for (int s = 0; s < sg.n; ++s) {
+            size_t i = 0;
+            while (seqs[i] != sg.seq[s]) ++i;
+            ends = ends || sg.pos0[s] + sg.m[s] == upto[i];
+        }
+        if (int rc = forward_segs(c, M, sg, (logits && ends) ? logits : nullptr, out_seq_rows, out_row0, 1)) return rc;
+        if (!more) return 0;
+    }
 }
 
 int launch_sample(hipStream_t st, const float* logits, int rows, int V, float T, uint64_t seed, uint32_t round, uint32_t pos,
@@ -889,6 +1150,102 @@ int launch_accept(hipStream_t st, const float* P, const float* Q, const int32_t*
 
 bool valid_vocab(int V) { return V >= 4 && V % 4 == 0 && V <= AK_WAVES * AK_SEG; }
 
+// ---- one round over a batch of independent sequences (cfg.batch > 1): every sequence drafts with its own
+// arm (sequences that share an arm share that drafter's forward), one verification block over all
+// batch x (gamma + 1) rows, one accept launch over all rows.
+
+int draft_batch(metasd_ctx* c, const int32_t* k, int gamma) {
+    const int B = c->cfg.batch, V = c->target.d.vocab;
+    for (int b = 0; b < B; ++b) {
+        if (k[b] < 0 || k[b] >= c->cfg.K) return c->fail(METASD_E_INVALID, "draft: drafter index of sequence %d out of range", b);
+        if (c->sq[b].l + gamma + 1 > c->cfg.max_ctx)
+            return c->fail(METASD_E_OVERFLOW, "draft: sequence %d: l + gamma + 1 = %d exceeds max_ctx %d", b, c->sq[b].l + gamma + 1, c->cfg.max_ctx);
+    }
+    SeqTab at{};
+    for (int j = 0; j < gamma; ++j) {
+        for (int a = 0; a < c->cfg.K; ++a) {
+            std::vector<int> seqs, upto;
+            for (int b = 0; b < B; ++b)
+                if (k[b] == a) { seqs.push_back(b); upto.push_back(c->sq[b].l + j); }
+            if (seqs.empty()) continue;
+            // j = 0: every committed token the drafter has not seen (ends with the last committed one);
+            // j > 0: the draft token d_j at position l + j - 1
+            if (int rc = catch_up(c, c->drafters[a], seqs, upto, c->d_Q(), gamma, j)) return rc;
+        }
+        for (int b = 0; b < B; ++b) at.v[b] = c->sq[b].l + j;
+        hipLaunchKernelGGL(sample_seq_kernel, dim3(B), dim3(AK_NT), 0, c->stream, (const float*)c->d_Q() + (size_t)j * V, (size_t)gamma * V, V,
+                           c->cfg.temperature, c->cfg.seed, (uint32_t)c->round, (uint32_t)j, c->d_hist(), c->cfg.max_ctx, at,
+                           c->d_draft() + j, gamma);
+        LAUNCH_CHECK(c, "sample (batch)");
+    }
+    for (int b = 0; b < B; ++b) c->sq[b].cur_k = k[b];
+    return 0;
+}
+
+int verify_batch(metasd_ctx* c, int gamma) {
+    Segs sg{};
+    sg.n = c->cfg.batch;
+    sg.ms = gamma + 1;
+    for (int b = 0; b < sg.n; ++b) { sg.seq[b] = b; sg.m[b] = gamma + 1; sg.pos0[b] = c->sq[b].l - 1; }
+    return forward_segs(c, c->target, sg, c->d_P(), gamma + 1, 0, 0);
+}
+
+int accept_batch(metasd_ctx* c, int gamma, int32_t* n_acc_out, int32_t* token_out, uint32_t* mask_out, double* bd_out) {
+    const int B = c->cfg.batch, V = c->target.d.vocab, gm = c->cfg.gamma_max;
+    int32_t* res = c->d_res();
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_ACCEPT, (double)B * (2 * gamma + 1) * V * 4);
+    if (launch_accept(c->stream, c->d_P(), c->d_Q(), c->d_draft(), B, gamma, V, c->cfg.temperature, c->cfg.seed, (uint32_t)c->round, 0u,
+                      c->d_cand(), c->d_bd(), res, res + B, (uint32_t*)(res + 2 * B), nullptr, 0, c->d_xchg(), pr ? pr->a : nullptr,
+                      pr ? pr->b : nullptr))
+        return c->fail(METASD_E_HIP, "launch accept kernels failed");
+    SeqTab lt{};
+    for (int b = 0; b < B; ++b) lt.v[b] = c->sq[b].l;
+    hipLaunchKernelGGL(commit_tokens_kernel, dim3(1), dim3(64), 0, c->stream, (const int32_t*)res, (const int32_t*)(res + B), c->d_hist(),
+                       c->cfg.max_ctx, lt, B);
+    LAUNCH_CHECK(c, "commit_tokens");
+    char* hb = c->hbatch;
+    HIP_TRY(c, hipMemcpyAsync(hb, res, (size_t)B * 12, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(hb + c->hb_d(), c->d_draft(), (size_t)B * gamma * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(hb + c->hb_bd(), c->d_bd(), (size_t)B * gamma * 8, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(hb + c->hb_bar(), c->d_bar(), sizeof(GridBar), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    (void)gm;
+    const int32_t* hn = (const int32_t*)hb;
+    const int32_t* ht = hn + B;
+    const uint32_t* hm = (const uint32_t*)(hn + 2 * B);
+    const int32_t* hd = (const int32_t*)(hb + c->hb_d());
+    const double* hbd = (const double*)(hb + c->hb_bd());
+    if (((const GridBar*)(hb + c->hb_bar()))->abort) {
+        (void)hipMemsetAsync(c->d_bar(), 0, sizeof(GridBar), c->stream);
+        c->phase = PH_NONE;
+        return c->fail(METASD_E_HIP, "a bounded device-side wait between workgroups timed out; call metasd_set_context to start over");
+    }
+    for (int b = 0; b < B; ++b) {
+        if (ht[b] == -2) { c->phase = PH_NONE; return c->fail(METASD_E_HIP, "accept: the workgroups of a position did not meet (exchange timed out); call metasd_set_context to start over"); }
+        if (hn[b] < 0 || hn[b] > gamma || ht[b] < 0 || ht[b] >= V) return c->fail(METASD_E_HIP, "accept: device returned n_acc %d token %d for sequence %d", hn[b], ht[b], b);
+    }
+    for (int b = 0; b < B; ++b) {
+        metasd_ctx::SeqState& S = c->sq[b];
+        const int l = S.l, n = hn[b];
+        for (int j = 0; j < n; ++j) S.hist[l + j] = hd[(size_t)b * gamma + j];
+        S.hist[l + n] = ht[b];
+        S.l = l + n + 1;
+        c->target.kvl[b] = l + n;
+        c->drafters[S.cur_k].kvl[b] = std::min(l + n, l + gamma - 1);
+        if (n_acc_out) n_acc_out[b] = n;
+        if (token_out) token_out[b] = ht[b];
+        if (mask_out) mask_out[b] = hm[b];
+        if (bd_out) {
+            double sum = 0.0;
+            for (int j = 0; j < gamma; ++j) sum += hbd[(size_t)b * gamma + j];
+            bd_out[b] = sum / (double)gamma;
+        }
+    }
+    c->round += 1;
+    c->phase = PH_READY;
+    return METASD_OK;
+}
+
 }  // namespace
 
 // ================================================================================================ C ABI
@@ -909,7 +1266,7 @@ static int check_config(const metasd_config* cfg, const metasd_model_desc* targe
     if (!cfg || !target || !drafters) return fail_global(METASD_E_INVALID, "NULL config or descriptor");
     if (cfg->K < 1 || cfg->K > METASD_MAX_K) return fail_global(METASD_E_INVALID, "K must be in 1..%d", METASD_MAX_K);
     if (cfg->gamma_max < 1 || cfg->gamma_max > METASD_MAX_GAMMA) return fail_global(METASD_E_INVALID, "gamma_max must be in 1..%d", METASD_MAX_GAMMA);
-    if (cfg->batch != 1) return fail_global(METASD_E_INVALID, "batch must be 1 in this version");
+    if (cfg->batch < 1 || cfg->batch > METASD_MAX_BATCH) return fail_global(METASD_E_INVALID, "batch must be in 1..%d", METASD_MAX_BATCH);
     if (cfg->max_ctx < cfg->gamma_max + 2) return fail_global(METASD_E_INVALID, "max_ctx too small");
     if (!(cfg->temperature >= 0.f)) return fail_global(METASD_E_INVALID, "temperature must be >= 0");
     if (cfg->reward != METASD_REWARD_BE && cfg->reward != METASD_REWARD_BD) return fail_global(METASD_E_INVALID, "reward");
@@ -971,6 +1328,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         M.d = d;
         M.hd = d.d_model / d.n_heads;
         M.kv = kv;
+        M.kvl.assign(cfg->batch, 0);
         const int nw = 1 + PER_LAYER * d.n_layers + 2;
         M.w.assign(w, w + nw);
         for (int i = 0; i < nw; ++i) {
@@ -998,11 +1356,17 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         }
     }
     if (rc) { delete c; return rc; }
-    c->hist.assign(cfg->max_ctx, 0);
-    c->bandit.init(*cfg);
+    c->sq.resize(cfg->batch);
+    for (int b = 0; b < cfg->batch; ++b) {
+        c->sq[b].hist.assign(cfg->max_ctx, 0);
+        c->sq[b].bandit.init(*cfg);
+        c->sq[b].bandit.seq = (uint32_t)b;
+    }
     hipError_t e = hipHostMalloc((void**)&c->hres, sizeof(HostResult), hipHostMallocDefault);
+    if (e == hipSuccess && cfg->batch > 1) e = hipHostMalloc((void**)&c->hbatch, c->hb_bytes(), hipHostMallocDefault);
     if (e != hipSuccess) {
         rc = fail_global(METASD_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e));
+        if (c->hres) (void)hipHostFree(c->hres);
         delete c;
         return rc;
     }
@@ -1032,8 +1396,8 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
     for (int k = 0; k < cfg->K; ++k) c->drafters[k].d_table = (const void**)(c->ws + lay.tables + lay.table_stride * (size_t)(k + 1));
     e = hipMemsetAsync(c->d_bar(), 0, sizeof(GridBar), c->stream);
     if (e == hipSuccess) e = hipMemsetAsync(c->d_gx(), 0, c->lay.ssq - c->lay.gx, c->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(c->d_xchg(), 0, (size_t)(cfg->gamma_max + 1) * AS_XCHG_BYTES, c->stream);
-    if (e == hipSuccess) e = hipMemsetAsync(c->d_cand(), 0, (size_t)(cfg->gamma_max + 1) * sizeof(int2), c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->d_xchg(), 0, (size_t)cfg->batch * (cfg->gamma_max + 1) * AS_XCHG_BYTES, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(c->d_cand(), 0, (size_t)cfg->batch * (cfg->gamma_max + 1) * sizeof(int2), c->stream);
     if (e == hipSuccess) e = hipMemcpyAsync((void*)c->target.d_table, c->target.w.data(), c->target.w.size() * sizeof(void*), hipMemcpyHostToDevice, c->stream);
     for (int k = 0; k < cfg->K && e == hipSuccess; ++k)
         e = hipMemcpyAsync((void*)c->drafters[k].d_table, c->drafters[k].w.data(), c->drafters[k].w.size() * sizeof(void*), hipMemcpyHostToDevice, c->stream);
@@ -1041,6 +1405,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
     if (e != hipSuccess) {
         rc = fail_global(METASD_E_HIP, "context set-up: %s", hipGetErrorString(e));
         (void)hipHostFree(c->hres);
+        if (c->hbatch) (void)hipHostFree(c->hbatch);
         delete c;
         return rc;
     }
@@ -1051,6 +1416,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
 int32_t metasd_destroy(metasd_ctx* c) {
     if (!c) return METASD_OK;
     if (c->hres) (void)hipHostFree(c->hres);
+    if (c->hbatch) (void)hipHostFree(c->hbatch);
     for (auto& r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     delete c;
     return METASD_OK;
@@ -1058,26 +1424,28 @@ int32_t metasd_destroy(metasd_ctx* c) {
 
 int32_t metasd_set_context(metasd_ctx* c, int32_t seq, const int32_t* tokens, int32_t n, int32_t kv_prefilled) {
     if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
-    if (seq != 0 || !tokens || n < 1) return c->fail(METASD_E_INVALID, "set_context: bad seq / tokens / n");
+    if (seq < 0 || seq >= c->cfg.batch || !tokens || n < 1) return c->fail(METASD_E_INVALID, "set_context: bad seq / tokens / n");
     if (n + c->cfg.gamma_max + 1 > c->cfg.max_ctx) return c->fail(METASD_E_OVERFLOW, "set_context: n + gamma_max + 1 = %d exceeds max_ctx %d", n + c->cfg.gamma_max + 1, c->cfg.max_ctx);
     for (int i = 0; i < n; ++i)
         if (tokens[i] < 0 || tokens[i] >= c->target.d.vocab) return c->fail(METASD_E_INVALID, "set_context: token %d out of range at %d", tokens[i], i);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    std::copy(tokens, tokens + n, c->hist.begin());
-    HIP_TRY(c, hipMemcpyAsync(c->d_hist(), c->hist.data(), (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
+    metasd_ctx::SeqState& S = c->sq[seq];
+    std::copy(tokens, tokens + n, S.hist.begin());
+    HIP_TRY(c, hipMemcpyAsync(c->d_hist() + (size_t)seq * c->cfg.max_ctx, S.hist.data(), (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    c->l = n;
-    c->round = 0;
-    c->bandit.reset();
-    c->phase = PH_READY;
-    if (kv_prefilled) {
-        c->target.kv_len = n - 1;
-        for (auto& d : c->drafters) d.kv_len = n - 1;
-    } else {
-        c->target.kv_len = 0;
-        for (auto& d : c->drafters) d.kv_len = 0;
-        if (n > 1)
-            if (int rc = forward(c, c->target, 0, n - 1, nullptr, false)) return rc;
+    S.l = n;
+    S.bandit.reset();
+    S.ready = true;
+    // the round counter (Philox round word, shared by the sequences of a batch) restarts when sequence 0 is set
+    if (seq == 0) c->round = 0;
+    bool all = true;
+    for (const auto& q : c->sq) all = all && q.ready;
+    c->phase = all ? PH_READY : PH_NONE;
+    c->target.kvl[seq] = kv_prefilled ? n - 1 : 0;
+    for (auto& d : c->drafters) d.kvl[seq] = kv_prefilled ? n - 1 : 0;
+    if (!kv_prefilled && n > 1) {
+        if (c->cfg.batch == 1) { if (int rc = forward(c, c->target, 0, n - 1, nullptr, false)) return rc; }
+        else if (int rc = catch_up(c, c->target, std::vector<int>{seq}, std::vector<int>{n - 1}, nullptr, 0, 0)) return rc;
     }
     return METASD_OK;
 }
@@ -1098,28 +1466,29 @@ int32_t metasd_swap_weight(metasd_ctx* c, int32_t model, int32_t index, const vo
 
 int32_t metasd_bandit_select(metasd_ctx* c, int32_t seq, int32_t* k_out) {
     if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
-    if (seq != 0 || !k_out) return c->fail(METASD_E_INVALID, "bandit_select: bad argument");
-    *k_out = c->bandit.select();
+    if (seq < 0 || seq >= c->cfg.batch || !k_out) return c->fail(METASD_E_INVALID, "bandit_select: bad argument");
+    *k_out = c->sq[seq].bandit.select();
     return METASD_OK;
 }
 
 int32_t metasd_bandit_update(metasd_ctx* c, int32_t seq, int32_t k, int32_t n_acc, int32_t gamma, double bd_reward) {
     if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
-    if (seq != 0 || k < 0 || k >= c->cfg.K || gamma < 1 || n_acc < 0 || n_acc > gamma) return c->fail(METASD_E_INVALID, "bandit_update: bad argument");
+    if (seq < 0 || seq >= c->cfg.batch || k < 0 || k >= c->cfg.K || gamma < 1 || n_acc < 0 || n_acc > gamma) return c->fail(METASD_E_INVALID, "bandit_update: bad argument");
     double r = (double)n_acc / (double)gamma;
     if (c->cfg.reward == METASD_REWARD_BD) {
         if (!(bd_reward >= 0.0 && bd_reward <= 1.0 + 1e-9)) return c->fail(METASD_E_INVALID, "bandit_update: BD reward %g not in [0,1]", bd_reward);
         r = bd_reward;
     }
-    c->bandit.update(k, r);
+    c->sq[seq].bandit.update(k, r);
     return METASD_OK;
 }
 
 int32_t metasd_bandit_state(const metasd_ctx* c, int32_t seq, double* mu, int32_t* n, int32_t* t) {
-    if (!c || seq != 0) return fail_global(METASD_E_INVALID, "bandit_state: bad argument");
-    if (mu) std::copy(c->bandit.mu.begin(), c->bandit.mu.end(), mu);
-    if (n) std::copy(c->bandit.n.begin(), c->bandit.n.end(), n);
-    if (t) *t = c->bandit.t;
+    if (!c || seq < 0 || seq >= c->cfg.batch) return fail_global(METASD_E_INVALID, "bandit_state: bad argument");
+    const Bandit& B = c->sq[seq].bandit;
+    if (mu) std::copy(B.mu.begin(), B.mu.end(), mu);
+    if (n) std::copy(B.n.begin(), B.n.end(), n);
+    if (t) *t = B.t;
     return METASD_OK;
 }
 
@@ -1129,22 +1498,28 @@ int32_t metasd_draft(metasd_ctx* c, const int32_t* k, int32_t gamma) {
     if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
     if (!k || k[0] < 0 || k[0] >= c->cfg.K) return c->fail(METASD_E_INVALID, "draft: drafter index out of range");
     if (gamma < 1 || gamma > c->cfg.gamma_max) return c->fail(METASD_E_INVALID, "draft: gamma %d not in 1..%d", gamma, c->cfg.gamma_max);
-    if (c->phase != PH_READY) return c->fail(METASD_E_ORDER, "draft: call set_context first / finish the previous round with accept");
-    if (c->l + gamma + 1 > c->cfg.max_ctx) return c->fail(METASD_E_OVERFLOW, "draft: l + gamma + 1 = %d exceeds max_ctx %d", c->l + gamma + 1, c->cfg.max_ctx);
+    if (c->phase != PH_READY) return c->fail(METASD_E_ORDER, "draft: call set_context first (for every sequence) / finish the previous round with accept");
+    if (c->cfg.batch > 1) {
+        if (int rc = draft_batch(c, k, gamma)) return rc;
+        c->cur_gamma = gamma;
+        c->phase = PH_DRAFTED;
+        return METASD_OK;
+    }
+    if (c->sq[0].l + gamma + 1 > c->cfg.max_ctx) return c->fail(METASD_E_OVERFLOW, "draft: l + gamma + 1 = %d exceeds max_ctx %d", c->sq[0].l + gamma + 1, c->cfg.max_ctx);
     Model& D = c->drafters[k[0]];
-    const int V = D.d.vocab, l = c->l;
+    const int V = D.d.vocab, l = c->sq[0].l;
     const float T = c->cfg.temperature;
     for (int j = 0; j < gamma; ++j) {
         float* Qj = c->d_Q() + (size_t)j * V;
         int rc;
-        if (j == 0) rc = forward(c, D, D.kv_len, l - D.kv_len, Qj, false);   // catch-up, ends with the last committed token
+        if (j == 0) rc = forward(c, D, D.kvl[0], l - D.kvl[0], Qj, false);   // catch-up, ends with the last committed token
         else rc = forward(c, D, l + j - 1, 1, Qj, false);
         if (rc) return rc;
         if (launch_sample(c->stream, Qj, 1, V, T, c->cfg.seed, (uint32_t)c->round, (uint32_t)j, 0u, c->d_hist() + l + j, 1,
                           c->d_draft() + j))
             return c->fail(METASD_E_HIP, "launch sample_rows failed");
     }
-    c->cur_k = k[0];
+    c->sq[0].cur_k = k[0];
     c->cur_gamma = gamma;
     c->phase = PH_DRAFTED;
     return METASD_OK;
@@ -1154,7 +1529,8 @@ int32_t metasd_verify(metasd_ctx* c, int32_t gamma) {
     if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
     if (c->phase != PH_DRAFTED) return c->fail(METASD_E_ORDER, "verify: draft has not been run for this round");
     if (gamma != c->cur_gamma) return c->fail(METASD_E_INVALID, "verify: gamma %d differs from the drafted %d", gamma, c->cur_gamma);
-    if (int rc = forward(c, c->target, c->l - 1, gamma + 1, c->d_P(), true)) return rc;
+    if (c->cfg.batch > 1) { if (int rc = verify_batch(c, gamma)) return rc; }
+    else if (int rc = forward(c, c->target, c->sq[0].l - 1, gamma + 1, c->d_P(), true)) return rc;
     c->phase = PH_VERIFIED;
     return METASD_OK;
 }
@@ -1163,7 +1539,8 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
     if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
     if (c->phase != PH_VERIFIED) return c->fail(METASD_E_ORDER, "accept: verify has not been run for this round");
     if (gamma != c->cur_gamma) return c->fail(METASD_E_INVALID, "accept: gamma %d differs from the drafted %d", gamma, c->cur_gamma);
-    const int V = c->target.d.vocab, l = c->l;
+    if (c->cfg.batch > 1) return accept_batch(c, gamma, n_acc_out, token_out, mask_out, bd_out);
+    const int V = c->target.d.vocab, l = c->sq[0].l;
     int32_t* res = c->d_res();
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_ACCEPT, (double)(2 * gamma + 1) * V * 4);
     if (launch_accept(c->stream, c->d_P(), c->d_Q(), c->d_hist() + l, 1, gamma, V, c->cfg.temperature, c->cfg.seed,
@@ -1184,13 +1561,13 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
     const int n = hr->n_acc;
     if (hr->token == -2) { c->phase = PH_NONE; return c->fail(METASD_E_HIP, "accept: the workgroups of a position did not meet (exchange timed out); call metasd_set_context to start over"); }
     if (n < 0 || n > gamma || hr->token < 0 || hr->token >= V) return c->fail(METASD_E_HIP, "accept: device returned n_acc %d token %d", n, hr->token);
-    for (int j = 0; j < n; ++j) c->hist[l + j] = hr->d[j];
-    c->hist[l + n] = hr->token;
+    for (int j = 0; j < n; ++j) c->sq[0].hist[l + j] = hr->d[j];
+    c->sq[0].hist[l + n] = hr->token;
     // commit: rows 0..n of the verification block stay in the target's cache; the drafter keeps
     // the committed prefix it has processed (it never saw d_gamma)
-    c->l = l + n + 1;
-    c->target.kv_len = l + n;
-    c->drafters[c->cur_k].kv_len = std::min(l + n, l + gamma - 1);
+    c->sq[0].l = l + n + 1;
+    c->target.kvl[0] = l + n;
+    c->drafters[c->sq[0].cur_k].kvl[0] = std::min(l + n, l + gamma - 1);
     c->round += 1;
     c->phase = PH_READY;
     if (n_acc_out) *n_acc_out = n;
@@ -1281,23 +1658,27 @@ int32_t metasd_peek(metasd_ctx* c, int32_t what, void** dev_ptr_out, size_t* byt
     if (!dev_ptr_out || !bytes_out) return c->fail(METASD_E_INVALID, "peek: NULL output");
     const size_t V = (size_t)c->target.d.vocab;
     switch (what) {
-        case METASD_PEEK_P: *dev_ptr_out = c->d_P(); *bytes_out = (size_t)(c->cfg.gamma_max + 1) * V * 4; break;
-        case METASD_PEEK_Q: *dev_ptr_out = c->d_Q(); *bytes_out = (size_t)c->cfg.gamma_max * V * 4; break;
-        case METASD_PEEK_HIST: *dev_ptr_out = c->d_hist(); *bytes_out = (size_t)c->cfg.max_ctx * 4; break;
-        case METASD_PEEK_BD: *dev_ptr_out = c->d_bd(); *bytes_out = (size_t)c->cfg.gamma_max * 8; break;
+        case METASD_PEEK_P: *dev_ptr_out = c->d_P(); *bytes_out = (size_t)c->cfg.batch * (c->cfg.gamma_max + 1) * V * 4; break;
+        case METASD_PEEK_Q: *dev_ptr_out = c->d_Q(); *bytes_out = (size_t)c->cfg.batch * c->cfg.gamma_max * V * 4; break;
+        case METASD_PEEK_HIST: *dev_ptr_out = c->d_hist(); *bytes_out = (size_t)c->cfg.batch * c->cfg.max_ctx * 4; break;
+        case METASD_PEEK_BD: *dev_ptr_out = c->d_bd(); *bytes_out = (size_t)c->cfg.batch * c->cfg.gamma_max * 8; break;
         case 5: *dev_ptr_out = c->d_part(); *bytes_out = (size_t)(2048 + 512) * 8; break;   // timestamps (METASD_TLOG=1)
-        case METASD_PEEK_DRAFT: *dev_ptr_out = c->d_draft(); *bytes_out = (size_t)c->cfg.gamma_max * 4; break;
+        case METASD_PEEK_DRAFT: *dev_ptr_out = c->d_draft(); *bytes_out = (size_t)c->cfg.batch * c->cfg.gamma_max * 4; break;
         default: return c->fail(METASD_E_INVALID, "peek: unknown buffer %d", what);
     }
     return METASD_OK;
 }
 
-int32_t metasd_state(const metasd_ctx* c, int32_t model, int32_t* l_out, int32_t* kv_len_out, int32_t* round_out) {
-    if (!c || model < -1 || model >= c->cfg.K) return fail_global(METASD_E_INVALID, "state: bad argument");
-    if (l_out) *l_out = c->l;
-    if (kv_len_out) *kv_len_out = model < 0 ? c->target.kv_len : c->drafters[model].kv_len;
+int32_t metasd_state_seq(const metasd_ctx* c, int32_t seq, int32_t model, int32_t* l_out, int32_t* kv_len_out, int32_t* round_out) {
+    if (!c || model < -1 || model >= c->cfg.K || seq < 0 || seq >= c->cfg.batch) return fail_global(METASD_E_INVALID, "state: bad argument");
+    if (l_out) *l_out = c->sq[seq].l;
+    if (kv_len_out) *kv_len_out = model < 0 ? c->target.kvl[seq] : c->drafters[model].kvl[seq];
     if (round_out) *round_out = c->round;
     return METASD_OK;
+}
+
+int32_t metasd_state(const metasd_ctx* c, int32_t model, int32_t* l_out, int32_t* kv_len_out, int32_t* round_out) {
+    return metasd_state_seq(c, 0, model, l_out, kv_len_out, round_out);
 }
 
 }  // extern "C"

@@ -28,8 +28,9 @@ def top2_gap(x: np.ndarray) -> float:
 
 
 class LockStep:
-    def __init__(self, gpu, target, drafters, prompt, gamma, T, seed, beta, logit_tol, kv_prefilled=False, reward="BE"):
+    def __init__(self, gpu, target, drafters, prompt, gamma, T, seed, beta, logit_tol, kv_prefilled=False, reward="BE", seq=0):
         self.gpu, self.target, self.drafters = gpu, target, drafters
+        self.seq = seq                                   # sequence of a batched context (its Philox sequence id)
         self.gamma, self.T, self.seed, self.tol, self.reward = gamma, T, seed, logit_tol, reward
         self.hist = np.zeros(target.max_ctx, np.int32)
         self.l = len(prompt)
@@ -42,15 +43,16 @@ class LockStep:
         if not kv_prefilled and self.l > 1:
             target.forward(prompt[: self.l - 1], 0, None)
 
-    def round(self, force_k=None):
-        g, T, seed, gamma, l, t = self.gpu, self.T, self.seed, self.gamma, self.l, self.t
-        st = self.stats
-        V = self.target.desc["vocab"]
-        exact = self.tol <= 1e-3
-        k_gpu = g.bandit_select()
+    def select(self, force_k=None):
+        """Arm of this round: the GPU's bandit and the oracle's must agree."""
+        k_gpu = self.gpu.bandit_select(seq=self.seq)
         k_or = self.bandit.select()
-        assert k_gpu == k_or, f"round {t}: arm {k_gpu} vs oracle {k_or}"
-        k = k_gpu if force_k is None else force_k
+        assert k_gpu == k_or, f"seq {self.seq} round {self.t}: arm {k_gpu} vs oracle {k_or}"
+        return k_gpu if force_k is None else force_k
+
+    def round(self, force_k=None):
+        g, gamma, l = self.gpu, self.gamma, self.l
+        k = self.select(force_k)
         g.draft(k, gamma)
         g.verify(gamma)
         n_gpu, tok_gpu, mask_gpu, bd_gpu = g.accept(gamma)
@@ -58,12 +60,20 @@ class LockStep:
         Qg = g.peek("Q")[:gamma].cpu().numpy()
         d = g.peek("draft")[:gamma].cpu().numpy().copy()
         hist_gpu = g.peek("hist")[l: l + gamma + 1].cpu().numpy()
+        return self.check(k, n_gpu, tok_gpu, mask_gpu, bd_gpu, Pg, Qg, d, hist_gpu)
+
+    def check(self, k, n_gpu, tok_gpu, mask_gpu, bd_gpu, Pg, Qg, d, hist_gpu):
+        """Compare one finished GPU round of this sequence with the oracle and commit it on both sides."""
+        g, T, seed, gamma, l, t, sq = self.gpu, self.T, self.seed, self.gamma, self.l, self.t, self.seq
+        st = self.stats
+        V = self.target.desc["vocab"]
+        exact = self.tol <= 1e-3
         assert (hist_gpu[:n_gpu] == d[:n_gpu]).all() and hist_gpu[n_gpu] == tok_gpu     # committed on the device too
         # ---- oracle, teacher-forced on the GPU's draft tokens
         D = self.drafters[k]
         Qo = np.empty((gamma, V), np.float32)
         Qo[0] = D.forward(self.hist[self.c[k]: l], self.c[k], "last")
-        u_d = [oracle.uniform(seed, 0, t, j, oracle.STREAM_DRAFT) for j in range(gamma)]
+        u_d = [oracle.uniform(seed, sq, t, j, oracle.STREAM_DRAFT) for j in range(gamma)]
         for j in range(gamma):       # stage B for the draft: the oracle's draw on the GPU's own logits
             tj, mg = oracle.sample(Qg[j], T, u_d[j], with_margin=True)
             if tj != d[j]:
@@ -85,8 +95,8 @@ class LockStep:
         dq, dp = float(np.abs(Qo - Qg).max()), float(np.abs(Po - Pg).max())
         st["max_dq"], st["max_dp"] = max(st["max_dq"], dq), max(st["max_dp"], dp)
         assert dq <= self.tol and dp <= self.tol, f"round {t}: logits differ by {dq} (drafter) / {dp} (target) > {self.tol}"
-        u_acc = np.array([oracle.uniform(seed, 0, t, j, oracle.STREAM_ACCEPT) for j in range(gamma)], np.float32)
-        u_res = oracle.uniform(seed, 0, t, 0, oracle.STREAM_RESIDUAL)
+        u_acc = np.array([oracle.uniform(seed, sq, t, j, oracle.STREAM_ACCEPT) for j in range(gamma)], np.float32)
+        u_res = oracle.uniform(seed, sq, t, 0, oracle.STREAM_RESIDUAL)
         # ---- stage B: oracle accept on the GPU's logits
         rb = oracle.accept(Pg, Qg, d, T, u_acc, u_res)
         mask_b = sum(int(m) << j for j, m in enumerate(rb["mask"]))
@@ -125,15 +135,40 @@ class LockStep:
         self.t += 1
         rew = oracle.reward_be(n, gamma) if self.reward == "BE" else bd_gpu
         self.bandit.update(k, rew)
-        g.bandit_update(k, n, gamma, bd_gpu)
-        mu, nn, tt = g.bandit_state()
+        g.bandit_update(k, n, gamma, bd_gpu, seq=sq)
+        mu, nn, tt = g.bandit_state(seq=sq)
         assert np.allclose(mu, self.bandit.mu, atol=1e-12) and (nn == self.bandit.n).all() and tt == self.bandit.t
-        lg, kvg, rg = g.state(-1)
+        lg, kvg, rg = g.state(-1, seq=sq)
         assert (lg, kvg, rg) == (self.l, self.l - 1, self.t)
-        assert g.state(k)[1] == self.c[k]
+        assert g.state(k, seq=sq)[1] == self.c[k]
         st["rounds"] += 1
         st["n_acc"].append(n)
         st["arms"].append(k)
         if T > 0:
             st["alpha"].append(float(np.mean(rb["bd"])))
         return n, tok_gpu
+
+
+class BatchLockStep:
+    """B sequences of one batched GPU context, each compared with its own oracle models (own KV caches)."""
+
+    def __init__(self, gpu, seqs):
+        self.gpu, self.seqs = gpu, seqs                  # seqs: LockStep objects with seq = 0 .. B-1, all sharing `gpu`
+
+    def round(self, force_k=None):
+        g = self.gpu
+        gamma = self.seqs[0].gamma
+        ks = [ls.select(None if force_k is None else force_k[b]) for b, ls in enumerate(self.seqs)]
+        ls0 = [ls.l for ls in self.seqs]
+        g.draft(ks, gamma)
+        g.verify(gamma)
+        n, tok, mask, bd = g.accept(gamma)
+        P = g.peek("P", gamma).cpu().numpy()
+        Q = g.peek("Q", gamma).cpu().numpy()
+        D = g.peek("draft", gamma).cpu().numpy().copy()
+        H = g.peek("hist").cpu().numpy()
+        out = []
+        for b, ls in enumerate(self.seqs):
+            l = ls0[b]
+            out.append(ls.check(ks[b], int(n[b]), int(tok[b]), int(mask[b]), float(bd[b]), P[b], Q[b], D[b], H[b, l: l + gamma + 1]))
+        return ks, out

@@ -49,8 +49,12 @@ def test_sizes_and_validation(lib):
     assert lib.metasd_workspace_bytes(C.byref(cfg), C.byref(desc()), dr, C.byref(n)) == 0 and n.value > 0
     bad = B._Config(3, 16, 1, 96, 1.0, 0, 1.0, 1)
     assert lib.metasd_workspace_bytes(C.byref(bad), C.byref(desc()), dr, C.byref(n)) == -1
-    bad = B._Config(3, 4, 2, 96, 1.0, 0, 1.0, 1)
-    assert lib.metasd_workspace_bytes(C.byref(bad), C.byref(desc()), dr, C.byref(n)) == -1
+    one = n.value
+    two = B._Config(3, 4, 2, 96, 1.0, 0, 1.0, 1)            # a batch of two sequences needs a larger workspace
+    assert lib.metasd_workspace_bytes(C.byref(two), C.byref(desc()), dr, C.byref(n)) == 0 and n.value > one
+    for batch in (0, 33):
+        bad = B._Config(3, 4, batch, 96, 1.0, 0, 1.0, 1)
+        assert lib.metasd_workspace_bytes(C.byref(bad), C.byref(desc()), dr, C.byref(n)) == -1
     assert b"batch" in lib.metasd_last_error(None)
     dr2 = (B._Desc * 3)(desc(n_layers=1), desc(n_layers=1, vocab=256), desc(n_layers=1))
     assert lib.metasd_workspace_bytes(C.byref(cfg), C.byref(desc()), dr2, C.byref(n)) == -1

@@ -1,0 +1,147 @@
+"""GPU parity of batched contexts (several independent sequences per context, each with its own
+bandit, drafter choice, KV caches and Philox sequence id) against the oracle: every sequence is
+compared round by round with its own oracle models (see lockstep.py).  Prompts have different
+lengths, so blocks are ragged; the arms differ between sequences, so drafters run on subsets."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_05417_amd as M
+import workloads as W
+from lockstep import BatchLockStep, LockStep
+from test_gpu_bf16 import SMALL, TOL, oracle_models
+
+pytestmark = pytest.mark.gpu
+
+
+def batch_pair(cfg, T, prompts, logit_tol, reward="BE", kv_prefilled=False, policy="ucb", **kw):
+    td, tw = cfg["target"]
+    B = len(prompts)
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=cfg["gamma"], max_ctx=cfg["max_ctx"], temperature=T, seed=cfg["seed"],
+                 ucb_beta=cfg["beta"], reward=reward, batch=B, policy=policy, **kw)
+    seqs = []
+    for b, p in enumerate(prompts):
+        ot, od = oracle_models(cfg)                     # own KV caches per sequence
+        seqs.append((ot, od))
+    return g, seqs
+
+
+def make_lockstep(g, cfg, seqs, prompts, T, tol, reward="BE", kv_prefilled=False):
+    out = []
+    for b, (p, (ot, od)) in enumerate(zip(prompts, seqs)):
+        g.set_context(p, kv_prefilled=kv_prefilled, seq=b)
+        out.append(LockStep(g, ot, od, p, cfg["gamma"], T, cfg["seed"], cfg["beta"], logit_tol=tol, kv_prefilled=kv_prefilled,
+                            reward=reward, seq=b))
+    return BatchLockStep(g, out)
+
+
+@pytest.mark.parametrize("T,reward", [(0.0, "BE"), (1.0, "BD")])
+def test_fp32_batch_of_three(T, reward):
+    """Tiny fp32 configuration, three sequences with prompts of 16, 9 and 23 tokens, real prefill."""
+    cfg = W.config1()
+    prompts = [cfg["prompt"], W.prompt_tokens(9, 512, 11), W.prompt_tokens(23, 512, 12)]
+    g, seqs = batch_pair(cfg, T, prompts, 1e-4, reward)
+    bl = make_lockstep(g, cfg, seqs, prompts, T, 1e-4, reward)
+    arms = []
+    for r in range(10):
+        force = None if r < 5 else [(r + b) % 3 for b in range(3)]       # later rounds: three different arms in one round
+        ks, _ = bl.round(force)
+        arms.append(ks)
+    for ls in bl.seqs:
+        st = ls.stats
+        assert st["mismatch_own"] == 0 and st["ties_own"] + st["ties_shared"] <= 1, st
+        assert st["max_dp"] <= 1e-4 and st["max_dq"] <= 1e-4
+    assert arms[0] == [0, 0, 0] and arms[1] == [1, 1, 1] and arms[2] == [2, 2, 2]       # Alg. 2's initial sweep, per sequence
+    if T == 0.0:                                                                         # lossless, sequence by sequence
+        for b, ls in enumerate(bl.seqs):
+            ref = oracle.ar_decode(oracle.Model(cfg["target"][0], W.to_numpy(cfg["target"][1]), cfg["max_ctx"]), prompts[b], 10, T=0.0)
+            assert np.array_equal(ls.hist[len(prompts[b]): len(prompts[b]) + 10], ref)
+    g.close()
+
+
+@pytest.mark.parametrize("B,i", [(2, 0), (5, 0), (12, 1), (7, 2)])
+def test_bf16_batches_span_the_gemm_variants(B, i):
+    """Small bf16 models: 2 x 6 = 12 rows (single-tile GEMM), 5 x 6 = 30 and 7 x 8 = 56 rows (64-row variant),
+    12 x 4 = 48; prompts of different lengths (ragged catch-up blocks, several attention chunks)."""
+    s = SMALL[i]
+    cfg = W.config4(n_layers=s["n_layers"], ctx=s["prompt"], n_new=64, K=2, d_model=s["d_model"], n_heads=s["n_heads"],
+                    d_ffn=s["d_ffn"], vocab=s["vocab"], dd_model=s["dd_model"], dn_heads=s["dn_heads"], dd_ffn=s["dd_ffn"])
+    cfg["gamma"] = s["gamma"]
+    cfg["max_ctx"] = s["prompt"] + 80
+    prompts = [W.prompt_tokens(max(2, s["prompt"] - 17 * b), s["vocab"], 30 + b) for b in range(B)]
+    g, seqs = batch_pair(cfg, 1.0, prompts, TOL)
+    bl = make_lockstep(g, cfg, seqs, prompts, 1.0, TOL)
+    for r in range(4):
+        force = None if r < 2 else [(b + r) % 2 for b in range(B)]      # after the sweep: mixed arms in one round
+        bl.round(force)
+    for ls in bl.seqs:
+        st = ls.stats
+        assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+    g.close()
+
+
+@pytest.mark.parametrize("rows", [(11, 6), (20, 7), (32, 8)])
+def test_bf16_wide_blocks(rows):
+    """More rows than one 64-row workgroup tile holds: 11 x 7 = 77 rows (128-row variant), 20 x 8 = 160 rows
+    (256-row variant) and the largest batch, 32 x 9 = 288 rows (two passes of the 256-row variant); real prefill."""
+    B, gamma = rows
+    s = SMALL[0]
+    cfg = W.config4(n_layers=2, ctx=140, n_new=64, K=2, d_model=s["d_model"], n_heads=s["n_heads"], d_ffn=s["d_ffn"], vocab=s["vocab"],
+                    dd_model=s["dd_model"], dn_heads=s["dn_heads"], dd_ffn=s["dd_ffn"])
+    cfg["gamma"] = gamma
+    cfg["max_ctx"] = 140 + 40
+    prompts = [W.prompt_tokens(140 - (b % 3), s["vocab"], 50 + b) for b in range(B)]
+    g, seqs = batch_pair(cfg, 1.0, prompts, TOL)
+    bl = make_lockstep(g, cfg, seqs, prompts, 1.0, TOL)
+    for r in range(2):
+        bl.round()
+    for ls in bl.seqs:
+        st = ls.stats
+        assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+    g.close()
+
+
+def test_batch_limits_and_errors():
+    cfg = W.config1()
+    td, tw = cfg["target"]
+    with pytest.raises(M.MetaSDError) as e:
+        M.MetaSD((td, tw), cfg["drafters"], gamma_max=4, max_ctx=64, temperature=1.0, seed=1, batch=33)
+    assert e.value.code == -1
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=4, max_ctx=64, temperature=1.0, seed=1, batch=2)
+    g.set_context(cfg["prompt"], seq=0)
+    with pytest.raises(M.MetaSDError) as e:
+        g.draft([0, 0], 4)                                 # sequence 1 has no context yet
+    assert e.value.code == -3
+    with pytest.raises(M.MetaSDError) as e:
+        g.set_context(cfg["prompt"], seq=2)
+    assert e.value.code == -1
+    g.set_context(cfg["prompt"][:5], seq=1)
+    with pytest.raises(M.MetaSDError) as e:
+        g.draft([0, 3], 4)                                 # K = 3
+    assert e.value.code == -1
+    g.draft([2, 1], 3)
+    g.verify(3)
+    n, tok, mask, bd = g.accept(3)
+    assert n.shape == (2,) and ((0 <= n) & (n <= 3)).all() and ((0 <= tok) & (tok < 512)).all()
+    assert g.state(-1, seq=0)[0] == 16 + n[0] + 1 and g.state(-1, seq=1)[0] == 5 + n[1] + 1
+    # identical sequences in one batch differ only by their Philox sequence id: same logits, independent draws
+    g.close()
+
+
+def test_identical_prompts_share_logits_not_draws():
+    """Two sequences with the same prompt and arm see the same drafter and target logits in round 0
+    (bit for bit: the rows go through the same kernels) but draw with different uniforms."""
+    cfg = W.config1()
+    td, tw = cfg["target"]
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=4, max_ctx=96, temperature=1.0, seed=5, batch=2)
+    for b in range(2):
+        g.set_context(cfg["prompt"], seq=b)
+    g.draft([1, 1], 4)
+    Q = g.peek("Q", 4).cpu().numpy()
+    d = g.peek("draft", 4).cpu().numpy()
+    assert np.array_equal(Q[0, 0], Q[1, 0])                # first step: same context on both
+    assert not np.array_equal(d[0], d[1])                  # sequence ids 0 and 1 give different uniforms
+    g.verify(4)
+    g.accept(4)
+    g.close()
