@@ -49,9 +49,14 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="target layers (32 = the 7B shape; fewer is NOT the benchmark)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rounds", type=int, default=8)
+    ap.add_argument("--workload", default="c4", choices=["c4", "c5"],
+                    help="c4 (default): the headline benchmark; c5: the batched configuration (32 sequences, gamma 7, KV context 4096), a side measurement")
+    ap.add_argument("--batch", type=int, default=32, help="sequences of the c5 workload")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (one process, no collectives); use --gpus 1")
+    if args.workload == "c5":
+        return bench_c5(args)
 
     import numpy as np
     import torch
@@ -195,6 +200,100 @@ def main():
                                "segment-switching heads, gamma=5, batch 1, T=1, UCB beta=1, BE reward",
                    "gamma": gamma, "batch": 1, "ctx": args.ctx, "K": g.K},
         "roofline": roofline, "cpu_baseline": cpu, "detail": extra,
+    }
+    g.close()
+    print(json.dumps(out), flush=True)
+
+
+def bench_c5(args):
+    """The batched configuration: 7B-shape target, `batch` independent sequences (own bandit, arm, KV caches) at KV
+    context 4096 (unless --ctx is given), gamma = 7, T = 0.7; a step is one round of all sequences.  One JSON line."""
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU available; the MetaSD library has no CPU path")
+    import paper_2604_05417_amd as M
+    import workloads as W
+    dev, gamma, B = "cuda", 7, args.batch
+    ctx = args.ctx if args.ctx != 2048 else 4096
+    K_steps, Wm = args.steps if args.steps != 64 else 6, min(args.warmup, 2)
+    t0 = time.time()
+    cfg = W.config4(device=dev, n_layers=args.layers, ctx=ctx)
+    total = 3 * K_steps + Wm
+    max_ctx = ctx + (gamma + 1) * total + 16
+    td, tw = cfg["target"]
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=gamma, max_ctx=max_ctx, temperature=0.7, seed=cfg["seed"], ucb_beta=cfg["beta"],
+                 batch=B)
+    models = [(td, g.kv_target)] + [(dd, g.kv_drafters[k]) for k, (dd, _) in enumerate(cfg["drafters"])]
+    for b in range(B):                                           # seeded synthetic KV prefix, different per sequence
+        for i, (desc, kv) in enumerate(models):
+            k, v = W.kv_fill(desc, ctx - 1, cfg["kv_seed"] + 16 * b + i, device=dev)
+            kv[b, :, 0, :, : ctx - 1] = k
+            kv[b, :, 1, :, : ctx - 1] = v
+        g.set_context(W.prompt_tokens(ctx, td["vocab"], 3 + b), kv_prefilled=True, seq=b)
+    torch.cuda.synchronize()
+    log(f"[bench c5] setup {time.time() - t0:.1f}s; batch {B}, ctx {ctx}, KV {g.kv_target.numel() * 2 / 1e9:.1f} GB")
+
+    def one_round():
+        ks = [g.bandit_select(seq=b) for b in range(B)]
+        g.draft(ks, gamma)
+        g.verify(gamma)
+        n, tok, mask, bd = g.accept(gamma)
+        for b in range(B):
+            g.bandit_update(ks[b], int(n[b]), gamma, float(bd[b]), seq=b)
+        return n
+
+    for _ in range(Wm):
+        one_round()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    toks, accs = 0, []
+    for _ in range(K_steps):
+        n = one_round()
+        toks += int(n.sum()) + B
+        accs.append(float(n.mean()))
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t1
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K_steps)]
+    for i in range(K_steps):
+        ks = [g.bandit_select(seq=b) for b in range(B)]
+        ev[i][0].record(); g.draft(ks, gamma)
+        ev[i][1].record(); g.verify(gamma)
+        ev[i][2].record(); n, tok, mask, bd = g.accept(gamma)
+        ev[i][3].record()
+        for b in range(B):
+            g.bandit_update(ks[b], int(n[b]), gamma, float(bd[b]), seq=b)
+    torch.cuda.synchronize()
+    phase = [float(np.median([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(K_steps)])) for j in range(3)]
+    g.profile(1 << 16)
+    for _ in range(K_steps):
+        one_round()
+    torch.cuda.synchronize()
+    pg, pa, pc = g.profile_read("gemm"), g.profile_read("attn"), g.profile_read("accept")
+    g.profile(0)
+
+    def roof(p):
+        if not p["launches"]:
+            return None
+        return dict(launches=p["launches"], avg_us=p["ms"] / p["launches"] * 1e3, bytes_per_launch=p["bytes"] / p["launches"],
+                    GBs=p["bytes"] / (p["ms"] * 1e-3) / 1e9, ms_per_step=p["ms"] / K_steps)
+
+    n_params = sum(t.numel() for i, t in enumerate(tw) if t is not None and i != 0)
+    kv_tok = 2 * td["n_layers"] * td["n_kv_heads"] * (td["d_model"] // td["n_heads"]) * 2
+    l_mid = ctx + (Wm + 1.5 * K_steps) * (np.mean(accs) + 1)
+    verify_bytes = n_params * 2 + B * (kv_tok * l_mid + kv_tok * (gamma + 1) + (gamma + 1) * td["vocab"] * 4)
+    R = B * (gamma + 1)
+    out = {
+        "metric": "verified tokens/sec @1 GPU (7B-shape, batched)", "value": toks / dt, "unit": "tokens/s", "n_gpus": 1,
+        "steps": K_steps, "warmup": Wm, "ms_per_step": dt / K_steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"C5: 7B-shape bf16 target ({td['n_layers']} layers), {B} independent sequences with their own UCB "
+                               f"bandit over K=5 two-layer drafters, KV context {ctx}, gamma=7, T=0.7; {R} verification rows",
+                   "gamma": gamma, "batch": B, "ctx": ctx, "K": g.K},
+        "detail": {"draft_ms": phase[0], "verify_ms": phase[1], "accept_ms": phase[2], "verify_algorithmic_GB": verify_bytes / 1e9,
+                   "verify_hbm_frac": verify_bytes / (phase[1] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                   "verify_gemm_TFLOPs": 2.0 * R * n_params / (phase[1] * 1e-3) / 1e12,
+                   "gemm_kernel": roof(pg), "attn_kernel": roof(pa), "accept_kernel": roof(pc), "mean_n_acc": float(np.mean(accs))},
     }
     g.close()
     print(json.dumps(out), flush=True)

@@ -145,3 +145,59 @@ def test_identical_prompts_share_logits_not_draws():
     g.verify(4)
     g.accept(4)
     g.close()
+
+
+def test_config5_full_size_sampled_sequences():
+    """The batched configuration at full size - 7B-shape target, 32 sequences, KV context 4096 (synthetic
+    prefix, different per sequence), gamma = 7, T = 0.7, 256 verification rows, in the launch
+    configuration `bench.py --workload c5` times - with two of the 32 sequences (one in each half of
+    the row range) followed by the oracle: drafter and target logits, accept outcome, commit."""
+    B, gamma, ctx, T = 32, 7, 4096, 0.7
+    cfg = W.config4(device="cuda", ctx=ctx)
+    cfg["gamma"], cfg["max_ctx"] = gamma, ctx + 2 * (gamma + 1) + 8
+    td, tw = cfg["target"]
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=gamma, max_ctx=cfg["max_ctx"], temperature=T, seed=cfg["seed"],
+                 ucb_beta=cfg["beta"], batch=B)
+    sampled = (5, 30)
+    tw_np = W.to_numpy(tw)                                  # shared by the oracle models of both sampled sequences
+    dw_np = [W.to_numpy(dw) for _, dw in cfg["drafters"]]
+    models = [(td, g.kv_target)] + [(dd, g.kv_drafters[k]) for k, (dd, _) in enumerate(cfg["drafters"])]
+    seqs = {}
+    for b in range(B):
+        prompt = W.prompt_tokens(ctx, td["vocab"], 3 + b)
+        om = None
+        if b in sampled:
+            om = [oracle.Model(td, tw_np, cfg["max_ctx"])] + [oracle.Model(dd, dw_np[k], cfg["max_ctx"]) for k, (dd, _) in enumerate(cfg["drafters"])]
+        for i, (desc, kv) in enumerate(models):
+            k, v = W.kv_fill(desc, ctx - 1, cfg["kv_seed"] + 16 * b + i, device="cuda")
+            kv[b, :, 0, :, : ctx - 1] = k
+            kv[b, :, 1, :, : ctx - 1] = v
+            if om is not None:
+                om[i].kv(0)[:, :, : ctx - 1] = k.float().cpu().numpy()
+                om[i].kv(1)[:, :, : ctx - 1] = v.float().cpu().numpy()
+        g.set_context(prompt, kv_prefilled=True, seq=b)
+        if om is not None:
+            seqs[b] = LockStep(g, om[0], om[1:], prompt, gamma, T, cfg["seed"], cfg["beta"], logit_tol=TOL, kv_prefilled=True, seq=b)
+    for r in range(2):
+        ks = [seqs[b].select() if b in seqs else g.bandit_select(seq=b) for b in range(B)]
+        if r == 1:                                          # second round: the sequences of a batch use different drafters
+            ks = [(k + b) % g.K for b, k in enumerate(ks)]
+        l0 = {b: ls.l for b, ls in seqs.items()}
+        g.draft(ks, gamma)
+        g.verify(gamma)
+        n, tok, mask, bd = g.accept(gamma)
+        P, Q = g.peek("P", gamma), g.peek("Q", gamma)
+        D, H = g.peek("draft", gamma).cpu().numpy().copy(), g.peek("hist").cpu().numpy()
+        for b in range(B):
+            if b in seqs:
+                l = l0[b]
+                seqs[b].check(ks[b], int(n[b]), int(tok[b]), int(mask[b]), float(bd[b]), P[b].cpu().numpy(), Q[b].cpu().numpy(), D[b],
+                              H[b, l: l + gamma + 1])
+            else:
+                assert 0 <= n[b] <= gamma and 0 <= tok[b] < td["vocab"]
+                g.bandit_update(ks[b], int(n[b]), gamma, float(bd[b]), seq=b)
+    for ls in seqs.values():
+        st = ls.stats
+        print("C5 sampled sequence", ls.seq, {k: st[k] for k in ("max_dp", "max_dq", "ties_shared", "ties_own", "mismatch_own")})
+        assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+    g.close()
