@@ -8,6 +8,8 @@
 // for every sequence (no padding), a draft step m[s] = 1; only catch-up blocks are ragged.
 #pragma once
 
+#include <type_traits>
+
 namespace msd {
 
 constexpr int MAX_SEGS = 32;
@@ -144,62 +146,69 @@ __global__ void commit_tokens_kernel(const int32_t* __restrict__ n_acc, const in
 //   x as two bf16 arrays (hi at xh, lo x_lo_off elements behind), row stride ldx.
 // One workgroup of 8 wavefronts owns 8 feature tiles (128 features) x one K-slice x all R rows:
 // wavefronts 0-3 the first four tiles, 4-7 the other four; within a quad wavefront w takes the
-// 16-row blocks w, w+4, ..  (RBW of them).  Per 32-wide K chunk the R x 32 activations (both terms)
-// are staged in LDS, double-buffered; a wavefront reads each activation fragment once and feeds it
-// to the four tiles it holds in registers (8 MFMAs per LDS read pair), so LDS reads stay far below
-// the MFMA rate.  Weights: PD chunks (4 KiB each per wavefront) in flight in registers; the two
-// wavefronts that share tiles request the same lines (L1 / L2 hits).  Activation pieces are
-// requested PD chunks ahead as well, so that a wavefront's in-order load returns never drain the
-// weight queue.   grid (ceil(ntiles/8) * ksplit), block 512,
-// dynamic LDS 2 * 8 * (64 RBW + 1) * 16 bytes;  R <= 64 RBW.
-template <int RBW, int PD>
+// 16-row blocks w, w+4, ..  (RBW of them).  The K-slice advances in stages of two 32-wide chunks:
+// per stage the R x 64 activations (both terms: 128 contiguous bytes per row and term, so the
+// requests are whole cache lines) are staged in LDS, double-buffered, one workgroup barrier per
+// stage; a wavefront reads each activation fragment once and feeds it to the four tiles it holds
+// in registers (8 MFMAs per LDS read pair), so LDS reads stay far below the MFMA rate.  Weights:
+// PD stages (8 KiB each per wavefront) in flight in registers; the wavefronts that share tiles
+// request the same lines (L1 / L2 hits).  Activation pieces are requested one stage ahead.
+// LO = false leaves out the low-order terms of the activations (plain bf16 activations).
+//   grid (ceil(ntiles/8) * ksplit), block 512, dynamic LDS 2 * (LO ? 16 : 8) * (64 RBW + 1) * 16 bytes;  R <= 64 RBW.
+template <int RBW, int PD, bool LO>
 __global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __restrict__ xh, size_t x_lo_off, int ldx, int R, int K,
                                                              const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
                                                              const bf16_t* __restrict__ W2, int t0, int t1, int ntiles,
                                                              float* __restrict__ out, size_t out_sstride, int N, int ksplit,
                                                              int cps) {
-    extern __shared__ uint4 lds[];                 // [2 buffers][8 pieces (4 hi, 4 lo)][LR rows]
+    extern __shared__ uint4 lds[];                 // [2 buffers][NP pieces][LR rows]
     constexpr int R16 = 64 * RBW, LR = R16 + 1;
+    constexpr int NP = LO ? 16 : 8;                // 16-byte pieces per row and stage: 8 hi (+ 8 lo)
+    constexpr int APT = R16 * NP / 512;            // pieces per thread and stage
     const int kchunks = K >> 5;
     const int ks = blockIdx.x % ksplit, tg = blockIdx.x / ksplit;
     const int c0 = ks * cps, nc = min(cps, kchunks - c0);
+    const int nst = (nc + 1) >> 1;                 // stages of two chunks
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, quad = wave >> 2, wr = wave & 3;
     const int row16 = lane & 15, g = lane >> 4;
-    const u32x4* wp[4];
-    int tl[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        tl[i] = tg * 8 + quad * 4 + i;
-        const int t = min(tl[i], ntiles - 1);
+    const int tl0 = tg * 8 + quad * 4;             // this wavefront's four tiles: tl0 .. tl0 + 3
+    auto tile_ptr = [&](int i) -> const u32x4* {
+        const int t = min(tl0 + i, ntiles - 1);
         const bf16_t* W;
         int tt;
         if (t < t0) { W = W0; tt = t; }
         else if (t < t1) { W = W1; tt = t - t0; }
         else { W = W2; tt = t - t1; }
-        wp[i] = reinterpret_cast<const u32x4*>(W) + ((size_t)tt * kchunks + c0) * 64 + lane;
-    }
+        return reinterpret_cast<const u32x4*>(W) + ((size_t)tt * kchunks + c0) * 64 + lane;
+    };
+    const u32x4 *wp0 = tile_ptr(0), *wp1 = tile_ptr(1), *wp2 = tile_ptr(2), *wp3 = tile_ptr(3);
     // every load is unconditional and clamped into range: chunks past the slice's end re-read its last
     // chunk and are multiplied by zero
-    auto wload = [&](u32x4 (&dst)[4], int c) {
-        const int cc = min(c, nc - 1);
+    auto wload = [&](u32x4 (&dst)[8], int st) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) dst[i] = __builtin_nontemporal_load(wp[i] + (size_t)cc * 64);
+        for (int cc = 0; cc < 2; ++cc) {
+            const size_t co = (size_t)min(2 * st + cc, nc - 1) * 64;   // plain loads: the four wavefronts that share these tiles meet in L1
+            dst[cc * 4 + 0] = wp0[co];
+            dst[cc * 4 + 1] = wp1[co];
+            dst[cc * 4 + 2] = wp2[co];
+            dst[cc * 4 + 3] = wp3[co];
+        }
     };
-    auto aload = [&](u32x4 (&dst)[RBW], int c) {
-        const int cc = min(c, nc - 1);
+    auto aload = [&](u32x4 (&dst)[APT], int st) {
 #pragma unroll
-        for (int u = 0; u < RBW; ++u) {
-            const int idx = tid + 512 * u, row = min(idx >> 3, R - 1), which = idx & 7;
-            const bf16_t* src = xh + (size_t)row * ldx + (size_t)(c0 + cc) * 32 + (which & 3) * 8 + ((which >> 2) ? x_lo_off : (size_t)0);
+        for (int u = 0; u < APT; ++u) {
+            const int idx = tid + 512 * u, row = min(idx / NP, R - 1), which = idx % NP;
+            const int c = min(2 * st + ((which & 7) >> 2), nc - 1);
+            const bf16_t* src = xh + (size_t)row * ldx + (size_t)(c0 + c) * 32 + (which & 3) * 8 + ((which >> 3) ? x_lo_off : (size_t)0);
             dst[u] = *reinterpret_cast<const u32x4*>(src);
         }
     };
-    auto astore = [&](const u32x4 (&src)[RBW], int buf) {
-        uint4* base = lds + (size_t)buf * 8 * LR;
+    auto astore = [&](const u32x4 (&src)[APT], int buf) {
+        uint4* base = lds + (size_t)buf * NP * LR;
 #pragma unroll
-        for (int u = 0; u < RBW; ++u) {
+        for (int u = 0; u < APT; ++u) {
             const int idx = tid + 512 * u;
-            base[(idx & 7) * LR + (idx >> 3)] = __builtin_bit_cast(uint4, src[u]);
+            base[(idx % NP) * LR + idx / NP] = __builtin_bit_cast(uint4, src[u]);
         }
     };
     f32x4 acc[RBW][4];
@@ -207,37 +216,63 @@ __global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __res
     for (int a = 0; a < RBW; ++a)
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc[a][i] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const uint4 zero = make_uint4(0, 0, 0, 0);
-    auto compute = [&](const u32x4 (&w)[4], int buf, bool live) {
-        const uint4* base = lds + (size_t)buf * 8 * LR;
+    // Chunks past the slice's end are multiplied by zero: the (re-read, clamped) weight tiles of such a chunk
+    // are masked in registers - they arrived long ago, so the mask costs no wait; masking the activation
+    // fragments instead would make every LDS read wait for its data at once.
+    // The activation fragments of step k+1 (a step = one 16-row block of one chunk) are read from LDS
+    // before the MFMAs of step k are issued, so the LDS latency hides behind 8 (4) MFMAs.
+    auto compute = [&](u32x4 (&w)[8], int buf, int st) {
+        const u32x4* base = reinterpret_cast<const u32x4*>(lds) + (size_t)buf * NP * LR;
+        const uint32_t mask0 = 2 * st < nc ? 0xffffffffu : 0u, mask1 = 2 * st + 1 < nc ? 0xffffffffu : 0u;
 #pragma unroll
-        for (int a = 0; a < RBW; ++a) {
+        for (int i = 0; i < 4; ++i) { w[i] &= mask0; w[4 + i] &= mask1; }
+        u32x4 fh[2], fl[2];
+        auto fetch = [&](int k) {               // step k: chunk cc = k / RBW, row block a = k % RBW
+            const int cc = k / RBW, a = k % RBW;
             const int rowi = (wr + 4 * a) * 16 + row16;
-            uint4 bh = base[g * LR + rowi], bl = base[(4 + g) * LR + rowi];
-            if (!live) { bh = zero; bl = zero; }
+            fh[k & 1] = base[(cc * 4 + g) * LR + rowi];
+            if constexpr (LO) fl[k & 1] = base[(8 + cc * 4 + g) * LR + rowi];
+        };
+        fetch(0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[i]), __builtin_bit_cast(bf16x8, bh), acc[a][i], 0, 0, 0);
-                acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[i]), __builtin_bit_cast(bf16x8, bl), acc[a][i], 0, 0, 0);
+        for (int k = 0; k < 2 * RBW; ++k) {
+            if (k + 1 < 2 * RBW) fetch(k + 1);
+            const int cc = k / RBW, a = k % RBW;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[cc * 4 + i]), __builtin_bit_cast(bf16x8, fh[k & 1]), acc[a][i], 0, 0, 0);
+            if constexpr (LO) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[cc * 4 + i]), __builtin_bit_cast(bf16x8, fl[k & 1]), acc[a][i], 0, 0, 0);
             }
         }
-    };
-    u32x4 w[PD][4], ar[PD][RBW], a0[RBW];
-    aload(a0, 0);
+        // shape of the schedule: the reads of the next step, then the MFMAs of this one
+        __builtin_amdgcn_sched_group_barrier(0x100, LO ? 2 : 1, 0);
 #pragma unroll
-    for (int u = 0; u < PD; ++u) aload(ar[u], 1 + u);
+        for (int k = 0; k < 2 * RBW; ++k) {
+            if (k + 1 < 2 * RBW) __builtin_amdgcn_sched_group_barrier(0x100, LO ? 2 : 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, LO ? 8 : 4, 0);
+        }
+    };
+    // Order of the requests (a wavefront's loads return in order): the activations of stage st+1 are
+    // requested before the multiplies of stage st-1 and written to LDS before those of stage st; the only
+    // loads requested after them and before that write are weights the next multiplies need anyway.
+    u32x4 w[PD][8], ar[APT];
+    aload(ar, 0);
 #pragma unroll
     for (int u = 0; u < PD; ++u) wload(w[u], u);
-    astore(a0, 0);
+    astore(ar, 0);
+    aload(ar, 1);
     lds_barrier();
-    for (int cb = 0; cb < nc; cb += PD) {
+    for (int sb = 0; sb < nst; sb += PD) {
 #pragma unroll
         for (int u = 0; u < PD; ++u) {
-            const int c = cb + u;
-            astore(ar[u], (c + 1) & 1);            // chunk c+1, requested PD iterations ago
-            aload(ar[u], c + 1 + PD);
-            compute(w[u], c & 1, c < nc);
-            wload(w[u], c + PD);
+            const int st = sb + u;
+            astore(ar, (st + 1) & 1);              // stage st+1 (its buffer was last read in stage st-1, before the last barrier)
+            aload(ar, st + 2);                     // returns while this stage is multiplied
+            compute(w[u], st & 1, st);
+            wload(w[u], st + PD);
             lds_barrier();
         }
     }
@@ -247,8 +282,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __res
         if (row < R) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                if (tl[i] < ntiles) {
-                    float* o = out + (size_t)ks * out_sstride + (size_t)row * N + (size_t)tl[i] * 16 + g * 4;
+                if (tl0 + i < ntiles) {
+                    float* o = out + (size_t)ks * out_sstride + (size_t)row * N + (size_t)(tl0 + i) * 16 + g * 4;
                     *reinterpret_cast<float4*>(o) = make_float4(acc[a][i][0], acc[a][i][1], acc[a][i][2], acc[a][i][3]);
                 }
         }

@@ -40,7 +40,7 @@ constexpr int PER_LAYER = 9;
 constexpr int MAX_ROWS = 16;
 constexpr size_t ALIGN = 256;
 constexpr int LDS_BUDGET = 60 * 1024;
-constexpr int ROWS_PD = 4;                    // gemm_bf16_rows_kernel: chunks in flight (2 for the 512-row variant)
+constexpr int ROWS_PD = 2;                    // gemm_bf16_rows_kernel: stages (of two chunks) in flight
 constexpr size_t FULLK_LDS_MAX = 150 * 1024;   // gemm_fullk_residual_kernel: the whole activation block in LDS
 
 size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
@@ -92,12 +92,21 @@ Split choose_split(int m, int ntiles, int kchunks) {
     return s;
 }
 
-// Split of a gemm_bf16_rows_kernel launch: 8 tiles per workgroup, K split until about one workgroup per CU.
-Split choose_split_rows(int ntiles, int kchunks) {
+// Split of a gemm_bf16_rows_kernel launch: 8 tiles per workgroup, one workgroup per CU at a time.  The K split
+// minimises (rounds of workgroups over the CUs) x (chunks per slice) plus the traffic of the partial sums.
+Split choose_split_rows(int ntiles, int kchunks, int R = 256) {
+    static const int forced = env_int("METASD_ROWS_KS", 0);
     const int groups = (ntiles + 7) / 8;
-    int ks = std::max(1, std::min({(256 + groups - 1) / groups, 8, std::max(1, kchunks / 8)}));
-    int cps = (kchunks + ks - 1) / ks;
-    cps = (cps + ROWS_PD - 1) / ROWS_PD * ROWS_PD;
+    int best = 1;
+    double best_cost = 1e30;
+    for (int ks = 1; ks <= 8 && kchunks / ks >= 8; ++ks) {
+        const int cps = ((kchunks + ks - 1) / ks + 3) / 4 * 4;
+        const int rounds = (groups * ks + 255) / 256;
+        const double cost = (double)rounds * cps * 0.5 + (ks > 1 ? (double)ks * R * ntiles * 16 * 8 / 4e6 : 0.0);   // us
+        if (cost < best_cost) { best_cost = cost; best = ks; }
+    }
+    int ks = forced > 0 ? std::min(forced, std::max(1, kchunks / 8)) : best;
+    int cps = ((kchunks + ks - 1) / ks + 3) / 4 * 4;
     ks = (kchunks + cps - 1) / cps;
     Split s;
     s.ksplit = ks; s.cps = cps; s.tpb = 8; s.lds = 0;
@@ -144,7 +153,7 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
             ksplit = std::max(ksplit, ks_cap());
             partmax = std::max(partmax, (size_t)ksplit * MAX_ROWS * ns[i] * sizeof(float));
             if (c.batch > 1) {
-                const int kr = d.dtype == METASD_BF16 ? choose_split_rows(ns[i] / 16, ks[i] / 32).ksplit : 1;
+                const int kr = d.dtype == METASD_BF16 ? std::min(8, std::max(1, ks[i] / 32 / 8)) : 1;   // any split choose_split_rows may take
                 partmax = std::max(partmax, (size_t)std::max(kr, ksplit) * MAX_ROWS * c.batch * ns[i] * sizeof(float));
             }
         }
@@ -914,38 +923,18 @@ int gemm_rows<float>(metasd_ctx* c, const void* x, int ldx, int R, int K, const 
 }
 
 // more than 64 KiB of dynamic LDS needs the function attribute (set once per variant; harmless below the limit)
-template <int RBW, int PD>
-int rows_lds_attr(metasd_ctx* c) {
+template <int RBW, bool LO, int PD = ROWS_PD>
+int launch_gemm_rows(metasd_ctx* c, const bf16_t* xh, size_t x_lo_off, int ldx, int R, int r0, int nr, int K, const void* W0,
+                     const void* W1, const void* W2, int t0, int t1, int ntiles, int N, const Split& s, metasd_ctx::ProfRec* pr) {
+    const size_t lds = (size_t)2 * (LO ? 16 : 8) * (64 * RBW + 1) * 16;
     static bool attr_set = false;
     if (!attr_set) {
-        const size_t lds = (size_t)2 * 8 * (64 * RBW + 1) * 16;
-        if (hipFuncSetAttribute((const void*)gemm_bf16_rows_kernel<RBW, PD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        if (hipFuncSetAttribute((const void*)gemm_bf16_rows_kernel<RBW, PD, LO>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return c->fail(METASD_E_HIP, "gemm_bf16_rows_kernel: cannot reserve %zu bytes of LDS", lds);
         attr_set = true;
     }
-    return 0;
-}
-
-template <int RBW, int PD>
-int launch_gemm_rows(metasd_ctx* c, const bf16_t* xh, size_t x_lo_off, int ldx, int R, int K, const void* W0, const void* W1,
-                     const void* W2, int t0, int t1, int ntiles, float* out, int N, const Split& s, metasd_ctx::ProfRec* pr) {
-    const size_t lds = (size_t)2 * 8 * (64 * RBW + 1) * 16;
-    if (int rc = rows_lds_attr<RBW, PD>(c)) return rc;
     const int groups = (ntiles + 7) / 8;
-    hipExtLaunchKernelGGL((gemm_bf16_rows_kernel<RBW, PD>), dim3(groups * s.ksplit), dim3(512), (uint32_t)lds, c->stream,
-                          pr ? pr->a : nullptr, pr ? pr->b : nullptr, 0u, xh, x_lo_off, ldx, R, K, (const bf16_t*)W0, (const bf16_t*)W1,
-                          (const bf16_t*)W2, t0, t1, ntiles, out, (size_t)R * N, N, s.ksplit, s.cps);
-    LAUNCH_CHECK(c, "gemm_bf16_rows");
-    return 0;
-}
-
-// rows [r0, r0 + nr) of a block of R rows (nr <= 256)
-int launch_gemm_rows_off(metasd_ctx* c, const bf16_t* xh, size_t x_lo_off, int ldx, int R, int r0, int nr, int K, const void* W0,
-                         const void* W1, const void* W2, int t0, int t1, int ntiles, int N, const Split& s, metasd_ctx::ProfRec* pr) {
-    const size_t lds = (size_t)2 * 8 * (64 * 4 + 1) * 16;
-    if (int rc = rows_lds_attr<4, ROWS_PD>(c)) return rc;
-    const int groups = (ntiles + 7) / 8;
-    hipExtLaunchKernelGGL((gemm_bf16_rows_kernel<4, ROWS_PD>), dim3(groups * s.ksplit), dim3(512), (uint32_t)lds, c->stream,
+    hipExtLaunchKernelGGL((gemm_bf16_rows_kernel<RBW, PD, LO>), dim3(groups * s.ksplit), dim3(512), (uint32_t)lds, c->stream,
                           pr ? pr->a : nullptr, pr ? pr->b : nullptr, 0u, xh + (size_t)r0 * ldx, x_lo_off, ldx, nr, K, (const bf16_t*)W0,
                           (const bf16_t*)W1, (const bf16_t*)W2, t0, t1, ntiles, c->d_part() + (size_t)r0 * N, (size_t)R * N, N, s.ksplit, s.cps);
     LAUNCH_CHECK(c, "gemm_bf16_rows");
@@ -958,18 +947,25 @@ int gemm_rows<bf16_t>(metasd_ctx* c, const void* x, int ldx, int R, int K, const
     const size_t x_lo_off = (size_t)R * ldx;      // producers write hi [R][ldx], then lo [R][ldx]
     if (R <= MAX_ROWS) return gemm<bf16_t>(c, x, ldx, R, K, W0, n0, W1, n1, W2, n2, nullptr, nsplit_out, x_lo_off);
     const int N = n0 + n1 + n2, ntiles = N / 16, kchunks = K / 32;
-    const Split s = choose_split_rows(ntiles, kchunks);
+    const Split s = choose_split_rows(ntiles, kchunks, R);
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)R * K * 4 + (double)R * N * 4 * s.ksplit);
     const bf16_t* xh = (const bf16_t*)x;
     const int t0 = n0 / 16, t1 = (n0 + n1) / 16;
-    int rc;
-    if (R <= 64) rc = launch_gemm_rows<1, ROWS_PD>(c, xh, x_lo_off, ldx, R, K, W0, W1, W2, t0, t1, ntiles, c->d_part(), N, s, pr);
-    else if (R <= 128) rc = launch_gemm_rows<2, ROWS_PD>(c, xh, x_lo_off, ldx, R, K, W0, W1, W2, t0, t1, ntiles, c->d_part(), N, s, pr);
-    else if (R <= 256) rc = launch_gemm_rows<4, ROWS_PD>(c, xh, x_lo_off, ldx, R, K, W0, W1, W2, t0, t1, ntiles, c->d_part(), N, s, pr);
-    else {   // more than 256 rows: two passes over the weights, 256 rows each (the 512-row variant would spill registers)
-        rc = 0;
-        for (int r0 = 0; r0 < R && !rc; r0 += 256)
-            rc = launch_gemm_rows_off(c, xh, x_lo_off, ldx, R, r0, std::min(256, R - r0), K, W0, W1, W2, t0, t1, ntiles, N, s, r0 ? nullptr : pr);
+    static const bool lo = env_int("METASD_ROWS_LO", 1) != 0;     // 0: plain bf16 activations (measurement aid)
+    int rc = 0;
+    // more than 256 rows: two passes over the weights, 256 rows each (a 512-row variant would spill registers)
+    for (int r0 = 0; r0 < R && !rc; r0 += 256) {
+        const int nr = std::min(256, R - r0);
+        metasd_ctx::ProfRec* p = r0 ? nullptr : pr;
+        static const int pd = env_int("METASD_ROWS_PD", ROWS_PD);
+#define ROWS_ARGS (c, xh, x_lo_off, ldx, R, r0, nr, K, W0, W1, W2, t0, t1, ntiles, N, s, p)
+#define ROWS_GO(RBW) (pd == 3 ? (lo ? launch_gemm_rows<RBW, true, 3> ROWS_ARGS : launch_gemm_rows<RBW, false, 3> ROWS_ARGS) \
+                              : (lo ? launch_gemm_rows<RBW, true> ROWS_ARGS : launch_gemm_rows<RBW, false> ROWS_ARGS))
+        if (nr <= 64) rc = ROWS_GO(1);
+        else if (nr <= 128) rc = ROWS_GO(2);
+        else rc = ROWS_GO(4);
+#undef ROWS_GO
+#undef ROWS_ARGS
     }
     *nsplit_out = s.ksplit;
     return rc;
