@@ -21,8 +21,9 @@ Readings (the paper is silent or inconsistent here):
     five would survive); the better half (largest reward sums) is kept - the printed inequality keeps
     the worse half; ties rank the lower index higher; inside a phase arms are pulled one after the
     other, each n_t = max(1, floor(T / (|S_t| ceil(log2 K)))) times in a row.
-  - Random draws (EXP3, Rand): one Philox uniform per round, counter (sequence 0, round t, 0,
-    stream 3); the arm is the first whose cumulative probability exceeds u.
+  - Random draws (EXP3, Rand): one Philox uniform per round, counter (sequence id, round t, 0,
+    stream 3); the arm is the first whose cumulative probability exceeds u.  The sequence id is 0
+    for a single sequence; in a batch every sequence has its own bandit drawing under its own id.
 
 Pins: ``tests/test_oracle_policies.py`` (hand-worked runs in ``tests/golden/policies_hand.txt``,
 reductions to Alg. 2 for discount 1 / an unbounded window, closed forms of the EXP3 update).
@@ -109,8 +110,8 @@ def _draw(probs, u: float) -> int:
 
 
 class Exp3:
-    def __init__(self, K: int, gamma: float, seed: int):
-        self.K, self.g, self.seed = K, gamma, seed
+    def __init__(self, K: int, gamma: float, seed: int, seq: int = 0):
+        self.K, self.g, self.seed, self.seq = K, gamma, seed, seq
         self.t = 0
         self.w = [1.0] * K
         self.p = [1.0 / K] * K
@@ -125,7 +126,7 @@ class Exp3:
 
     def select(self) -> int:
         self.p = self.probs()
-        return _draw(self.p, float(_uniform(self.seed, 0, self.t, 0, 3)))
+        return _draw(self.p, float(_uniform(self.seed, self.seq, self.t, 0, 3)))
 
     def update(self, arm: int, reward: float):
         rhat = reward / self.p[arm]
@@ -140,14 +141,14 @@ class Exp3:
 
 
 class UniformRandom:
-    def __init__(self, K: int, seed: int):
-        self.K, self.seed = K, seed
+    def __init__(self, K: int, seed: int, seq: int = 0):
+        self.K, self.seed, self.seq = K, seed, seq
         self.t = 0
         self.mu = [0.0] * K
         self.n = [0] * K
 
     def select(self) -> int:
-        return _draw([1.0 / self.K] * self.K, float(_uniform(self.seed, 0, self.t, 0, 3)))
+        return _draw([1.0 / self.K] * self.K, float(_uniform(self.seed, self.seq, self.t, 0, 3)))
 
     def update(self, arm: int, reward: float):
         self.mu[arm] = (self.mu[arm] * self.n[arm] + reward) / (self.n[arm] + 1)

@@ -57,6 +57,37 @@ def test_policy_matches_oracle_arm_for_arm(case):
     g.close()
 
 
+@pytest.mark.parametrize("name", ["exp3", "random", "ducb"])
+def test_batched_bandits_are_independent(name):
+    """Three sequences in one context: each has its own policy state, and the randomised policies draw
+    with the sequence's own Philox id (the oracle policy built with seq = b)."""
+    cfg = W.config1()
+    K = 3
+    kw = dict(policy_param=0.4) if name == "exp3" else dict(policy_param=0.8) if name == "ducb" else {}
+    g = M.MetaSD(cfg["target"], cfg["drafters"], gamma_max=cfg["gamma"], max_ctx=cfg["max_ctx"], temperature=1.0, seed=11, ucb_beta=0.7,
+                 reward="BD", policy=name, batch=3, **kw)
+    make = {"exp3": lambda b: P.Exp3(K, 0.4, 11, seq=b), "random": lambda b: P.UniformRandom(K, 11, seq=b),
+            "ducb": lambda b: P.DiscountedUcb(K, 0.7, 0.8)}[name]
+    refs = [make(b) for b in range(3)]
+    rng = np.random.default_rng(5)
+    means = rng.random((3, K))
+    arms = [[], [], []]
+    for t in range(200):
+        for b in range(3):
+            a = g.bandit_select(seq=b)
+            assert a == refs[b].select(), (name, b, t)
+            r = float(np.clip(means[b, a] + 0.2 * rng.standard_normal(), 0.0, 1.0))
+            g.bandit_update(a, 0, cfg["gamma"], r, seq=b)
+            refs[b].update(a, r)
+            arms[b].append(a)
+    for b in range(3):
+        mu, n, tt = g.bandit_state(seq=b)
+        assert tt == refs[b].t and list(n) == list(refs[b].n)
+        np.testing.assert_allclose(mu, np.asarray(refs[b].mu, np.float64), rtol=0, atol=1e-12)
+    assert arms[0] != arms[1] and arms[1] != arms[2]
+    g.close()
+
+
 def test_bad_policy_arguments_are_rejected():
     for kw in (dict(policy="ducb", policy_param=0.0), dict(policy="exp3", policy_param=1.5), dict(policy="swucb", policy_window=0),
                dict(policy="sh", policy_window=0)):
