@@ -957,10 +957,8 @@ int gemm_rows<bf16_t>(metasd_ctx* c, const void* x, int ldx, int R, int K, const
     for (int r0 = 0; r0 < R && !rc; r0 += 256) {
         const int nr = std::min(256, R - r0);
         metasd_ctx::ProfRec* p = r0 ? nullptr : pr;
-        static const int pd = env_int("METASD_ROWS_PD", ROWS_PD);
 #define ROWS_ARGS (c, xh, x_lo_off, ldx, R, r0, nr, K, W0, W1, W2, t0, t1, ntiles, N, s, p)
-#define ROWS_GO(RBW) (pd == 3 ? (lo ? launch_gemm_rows<RBW, true, 3> ROWS_ARGS : launch_gemm_rows<RBW, false, 3> ROWS_ARGS) \
-                              : (lo ? launch_gemm_rows<RBW, true> ROWS_ARGS : launch_gemm_rows<RBW, false> ROWS_ARGS))
+#define ROWS_GO(RBW) (lo ? launch_gemm_rows<RBW, true> ROWS_ARGS : launch_gemm_rows<RBW, false> ROWS_ARGS)
         if (nr <= 64) rc = ROWS_GO(1);
         else if (nr <= 128) rc = ROWS_GO(2);
         else rc = ROWS_GO(4);
