@@ -1212,10 +1212,11 @@ int accept_batch(metasd_ctx* c, int gamma, int32_t* n_acc_out, int32_t* token_ou
     if (((const GridBar*)(hb + c->hb_bar()))->abort) {
         (void)hipMemsetAsync(c->d_bar(), 0, sizeof(GridBar), c->stream);
         c->phase = PH_NONE;
-        return c->fail(METASD_E_HIP, "a bounded device-side wait between workgroups timed out; call metasd_set_context to start over");
+        for (auto& q : c->sq) q.ready = false;
+        return c->fail(METASD_E_HIP, "a bounded device-side wait between workgroups timed out; call metasd_set_context (for every sequence) to start over");
     }
     for (int b = 0; b < B; ++b) {
-        if (ht[b] == -2) { c->phase = PH_NONE; return c->fail(METASD_E_HIP, "accept: the workgroups of a position did not meet (exchange timed out); call metasd_set_context to start over"); }
+        if (ht[b] == -2) { c->phase = PH_NONE; for (auto& q : c->sq) q.ready = false; return c->fail(METASD_E_HIP, "accept: the workgroups of a position did not meet (exchange timed out); call metasd_set_context to start over"); }
         if (hn[b] < 0 || hn[b] > gamma || ht[b] < 0 || ht[b] >= V) return c->fail(METASD_E_HIP, "accept: device returned n_acc %d token %d for sequence %d", hn[b], ht[b], b);
     }
     for (int b = 0; b < B; ++b) {

@@ -60,6 +60,39 @@ def test_fp32_batch_of_three(T, reward):
     g.close()
 
 
+def test_fp32_batch_of_six_more_than_sixteen_rows():
+    """fp32 models with a verification block of 6 x 5 = 30 rows (the fp32 GEMM runs per 16-row block)."""
+    cfg = W.config1()
+    prompts = [W.prompt_tokens(5 + 3 * b, 512, 20 + b) for b in range(6)]
+    g, seqs = batch_pair(cfg, 1.0, prompts, 1e-4)
+    bl = make_lockstep(g, cfg, seqs, prompts, 1.0, 1e-4)
+    for r in range(5):
+        bl.round()
+    for ls in bl.seqs:
+        st = ls.stats
+        assert st["mismatch_own"] == 0 and st["ties_own"] + st["ties_shared"] <= 1, st
+        assert st["max_dp"] <= 1e-4 and st["max_dq"] <= 1e-4
+    g.close()
+
+
+def test_bf16_gqa_early_exit_batch():
+    """Grouped-query attention (8 query heads on 2 KV heads) and early-exit drafters that share the target's
+    tensors, 5 sequences x 6 rows, real prefill of prompts of different lengths."""
+    td = W.model_desc(4, 256, 8, 2, 512, 1024, W.SWIGLU, W.BF16)
+    tw = W.gen_weights(td, 0)
+    drafters = [W.early_exit_drafter(td, tw, e, 0.01, 100 + k) for k, e in enumerate((1, 2, 3))]
+    cfg = dict(target=(td, tw), drafters=drafters, gamma=5, beta=1.0, seed=1, max_ctx=150 + 64)
+    prompts = [W.prompt_tokens(150 - 29 * b, 1024, 40 + b) for b in range(5)]
+    g, seqs = batch_pair(cfg, 1.0, prompts, TOL)
+    bl = make_lockstep(g, cfg, seqs, prompts, 1.0, TOL)
+    for r in range(5):
+        bl.round(None if r < 3 else [(b + r) % 3 for b in range(5)])
+    for ls in bl.seqs:
+        st = ls.stats
+        assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+    g.close()
+
+
 @pytest.mark.parametrize("B,i", [(2, 0), (5, 0), (12, 1), (7, 2)])
 def test_bf16_batches_span_the_gemm_variants(B, i):
     """Small bf16 models: 2 x 6 = 12 rows (single-tile GEMM), 5 x 6 = 30 and 7 x 8 = 56 rows (64-row variant),
