@@ -33,7 +33,7 @@ __global__ void embed_seg_kernel(const int32_t* __restrict__ hist, int max_ctx, 
     for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)r * d + i] = El<T>::ld(E[t * d + i]);
 }
 
-// Rotation table per block row (see rope_table_kernel).   grid (R), block hd/2
+// Rotation table per block row: tab[r][i] = (cos, sin)(position of row r * theta^(-2i/hd)), in fp64.   grid (R), block hd/2
 __global__ void rope_table_seg_kernel(Segs sg, int hd, float theta, double2* __restrict__ tab) {
     const int r = blockIdx.x, i = threadIdx.x, half = hd >> 1;
     if (i >= half) return;

@@ -115,15 +115,6 @@ __global__ void philox_words_kernel(uint64_t seed, uint32_t c0_start, int n, uin
 }
 
 // ------------------------------------------------------------------------------------------
-// embedding gather: h[r][:] = E[tok[r]][:]          grid (m), block 256
-
-template <typename T>
-__global__ void embed_kernel(const int32_t* __restrict__ tok, const T* __restrict__ E, int d, float* __restrict__ h) {
-    const int r = blockIdx.x;
-    const size_t t = (size_t)tok[r];
-    for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)r * d + i] = El<T>::ld(E[t * d + i]);
-}
-
 // Activations handed to the bf16 GEMM are stored as two bf16 terms, x = hi + lo with hi = bf16(x),
 // lo = bf16(x - hi): array hi[n] at `base`, array lo[n] right behind it (n = elements of the whole
 // block).  The producer pays the conversion once; every GEMM workgroup then copies 16-byte pieces.
@@ -808,16 +799,8 @@ __global__ void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restr
 //   q out fp32 [m][H*hd] (q_split: as two bf16 arrays, see below); cache planes (type T) [kv_head][max_ctx][hd].
 //   grid (H + 2KH, m), block 64
 
-// Rotation table of one forward block: tab[r][i] = (cos, sin)(pos0 + r) * theta^(-2i/hd), in fp64 (the
-// rotation is applied in fp64 and rounded once).  grid (m), block hd/2.  Built once per forward, used by every layer.
-__global__ void rope_table_kernel(int pos0, int hd, float theta, double2* __restrict__ tab) {
-    const int r = blockIdx.x, i = threadIdx.x, half = hd >> 1;
-    if (i >= half) return;
-    const double freq = pow((double)theta, -2.0 * (double)i / (double)hd);
-    double sn, cs;
-    sincos((double)(pos0 + r) * freq, &sn, &cs);
-    tab[r * half + i] = make_double2(cs, sn);
-}
+// The rotation table of a forward block, tab[r][i] = (cos, sin)((pos0 + r) * theta^(-2i/hd)) in fp64 (the rotation is
+// applied in fp64 and rounded once), is built once per forward by embed_rope_kernel and used by every layer.
 
 // Body for block row r = blockIdx.y at position pos; write_kv = false for padding rows (q is still written).
 template <typename T>
@@ -872,6 +855,22 @@ __device__ __forceinline__ void rope_kv_body(const float* __restrict__ part, int
     else dst = vc + ((size_t)(head - H - KH) * max_ctx + pos) * hd;
     dst[i] = El<T>::st(a);
     dst[i + half] = El<T>::st(b);
+}
+
+// Token embedding and rotation table of a block in one launch: h[r][:] = E[tok[r]][:], and (first hd/2
+// threads of row r's workgroup) tab[r][i] = (cos, sin)((pos0 + r) * theta^(-2i/hd)).   grid (m), block 256
+template <typename T>
+__global__ void embed_rope_kernel(const int32_t* __restrict__ tok, const T* __restrict__ E, int d, float* __restrict__ h, int pos0,
+                                  int hd, float theta, double2* __restrict__ tab) {
+    const int r = blockIdx.x, i = threadIdx.x, half = hd >> 1;
+    const size_t t = (size_t)tok[r];
+    for (int k = i; k < d; k += blockDim.x) h[(size_t)r * d + k] = El<T>::ld(E[t * d + k]);
+    if (i < half) {
+        const double freq = pow((double)theta, -2.0 * (double)i / (double)hd);
+        double sn, cs;
+        sincos((double)(pos0 + r) * freq, &sn, &cs);
+        tab[r * half + i] = make_double2(cs, sn);
+    }
 }
 
 template <typename T>

@@ -632,10 +632,9 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
     float* part = c->d_part();
     int ns = 0, rc;
     constexpr int split = sizeof(T) == 2 ? 1 : 0;   // bf16 models: activations for the GEMM are stored as two bf16 arrays
-    hipLaunchKernelGGL(embed_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, h);
-    LAUNCH_CHECK(c, "embed");
-    hipLaunchKernelGGL(rope_table_kernel, dim3(m), dim3(hd / 2), 0, st, pos0, hd, d.rope_theta, c->d_rope());
-    LAUNCH_CHECK(c, "rope_table");
+    hipLaunchKernelGGL(embed_rope_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, h, pos0, hd, d.rope_theta,
+                       c->d_rope());
+    LAUNCH_CHECK(c, "embed + rope table");
     for (int L = 0; L < d.n_layers; ++L) {
         // h += previous FFN output (split partials); xn = norm(h)
         hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.layer_w(L, 0),
@@ -694,10 +693,9 @@ int forward_rows_residual(metasd_ctx* c, Model& M, int pos0, int m, float* logit
     float* inv = c->d_inv();
     int ns = 0, rc, ntg = 0;
     c->cur_eps = d.rms_eps;
-    hipLaunchKernelGGL(embed_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, h);
-    LAUNCH_CHECK(c, "embed");
-    hipLaunchKernelGGL(rope_table_kernel, dim3(m), dim3(hd / 2), 0, st, pos0, hd, d.rope_theta, c->d_rope());
-    LAUNCH_CHECK(c, "rope_table");
+    hipLaunchKernelGGL(embed_rope_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, h, pos0, hd, d.rope_theta,
+                       c->d_rope());
+    LAUNCH_CHECK(c, "embed + rope table");
     // first norm: a plain RMSNorm of the embedding rows (normalised x, no scaling downstream)
     hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, 0, (size_t)m * D, D, (const T*)M.layer_w(0, 0), d.rms_eps,
                        xn, 1);
@@ -754,10 +752,9 @@ int forward_rows_fused(metasd_ctx* c, Model& M, int pos0, int m, float* logits, 
     const int DQ = H * hd, DKV = KH * hd, NQKV = DQ + 2 * DKV;
     hipStream_t st = c->stream;
     int hp = 0, pp = 0, ns = 0, rc;     // current residual buffer, current partials buffer, partials in it
-    hipLaunchKernelGGL(embed_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, c->d_h_pp(0));
-    LAUNCH_CHECK(c, "embed");
-    hipLaunchKernelGGL(rope_table_kernel, dim3(m), dim3(hd / 2), 0, st, pos0, hd, d.rope_theta, c->d_rope());
-    LAUNCH_CHECK(c, "rope_table");
+    hipLaunchKernelGGL(embed_rope_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, c->d_h_pp(0), pos0, hd,
+                       d.rope_theta, c->d_rope());
+    LAUNCH_CHECK(c, "embed + rope table");
     auto norm_pro = [&](const void* gain, int row0) {
         GemmPro p{};
         p.src = c->d_h_pp(hp) + (size_t)row0 * D;
