@@ -339,14 +339,6 @@ struct Bandit {
     }
 };
 
-struct HostResult {   // pinned host mirror of one accept
-    int32_t n_acc, token;
-    uint32_t mask;
-    int32_t pad;
-    int32_t d[16];
-    double bd[16];
-    GridBar bar;
-};
 
 enum Phase { PH_NONE = 0, PH_READY, PH_DRAFTED, PH_VERIFIED };
 
@@ -370,12 +362,17 @@ struct metasd_ctx {
     int round = 0;                   // rounds completed since the contexts were set (all sequences advance together)
     int cur_gamma = 0;
     Phase phase = PH_NONE;
-    HostResult* hres = nullptr;
-    char* hbatch = nullptr;      // pinned results of a batched accept: int32 n_acc[B], token[B], mask[B], d[B][gamma_max]; double bd[B][gamma_max]; GridBar
-    size_t hb_d() const { return (size_t)cfg.batch * 12; }
-    size_t hb_bd() const { return (hb_d() + (size_t)cfg.batch * cfg.gamma_max * 4 + 7) / 8 * 8; }
-    size_t hb_bar() const { return hb_bd() + (size_t)cfg.batch * cfg.gamma_max * 8; }
-    size_t hb_bytes() const { return hb_bar() + sizeof(GridBar); }
+    // Pinned host mirror of the workspace span [lay.bd, lay.bar + sizeof(GridBar)): the BD terms, the result words
+    // (n_acc, token, mask per sequence), the draft tokens and the abort flag come back in one copy per accept.
+    char* hspan = nullptr;
+    size_t span_bytes() const { return lay.bar + sizeof(GridBar) - lay.bd; }
+    template <typename U> const U* mirror(size_t ws_offset) const { return reinterpret_cast<const U*>(hspan + (ws_offset - lay.bd)); }
+    int fetch_results() {          // copy the span and wait for it (the only synchronisation of a round)
+        hipError_t e = hipMemcpyAsync(hspan, ws + lay.bd, span_bytes(), hipMemcpyDeviceToHost, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) return fail(METASD_E_HIP, "reading back the accept results: %s", hipGetErrorString(e));
+        return 0;
+    }
     std::string err;
     // optional per-launch timing of the three bandwidth-bound kernels (metasd_profile)
     struct ProfRec { hipEvent_t a, b; int kind; double bytes; };
@@ -1194,19 +1191,14 @@ int accept_batch(metasd_ctx* c, int gamma, int32_t* n_acc_out, int32_t* token_ou
     hipLaunchKernelGGL(commit_tokens_kernel, dim3(1), dim3(64), 0, c->stream, (const int32_t*)res, (const int32_t*)(res + B), c->d_hist(),
                        c->cfg.max_ctx, lt, B);
     LAUNCH_CHECK(c, "commit_tokens");
-    char* hb = c->hbatch;
-    HIP_TRY(c, hipMemcpyAsync(hb, res, (size_t)B * 12, hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(c, hipMemcpyAsync(hb + c->hb_d(), c->d_draft(), (size_t)B * gamma * 4, hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(c, hipMemcpyAsync(hb + c->hb_bd(), c->d_bd(), (size_t)B * gamma * 8, hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(c, hipMemcpyAsync(hb + c->hb_bar(), c->d_bar(), sizeof(GridBar), hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (int rc = c->fetch_results()) return rc;
     (void)gm;
-    const int32_t* hn = (const int32_t*)hb;
+    const int32_t* hn = c->mirror<int32_t>(c->lay.res);
     const int32_t* ht = hn + B;
     const uint32_t* hm = (const uint32_t*)(hn + 2 * B);
-    const int32_t* hd = (const int32_t*)(hb + c->hb_d());
-    const double* hbd = (const double*)(hb + c->hb_bd());
-    if (((const GridBar*)(hb + c->hb_bar()))->abort) {
+    const int32_t* hd = c->mirror<int32_t>(c->lay.draft);
+    const double* hbd = c->mirror<double>(c->lay.bd);
+    if (c->mirror<GridBar>(c->lay.bar)->abort) {
         (void)hipMemsetAsync(c->d_bar(), 0, sizeof(GridBar), c->stream);
         c->phase = PH_NONE;
         for (auto& q : c->sq) q.ready = false;
@@ -1354,11 +1346,9 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         c->sq[b].bandit.init(*cfg);
         c->sq[b].bandit.seq = (uint32_t)b;
     }
-    hipError_t e = hipHostMalloc((void**)&c->hres, sizeof(HostResult), hipHostMallocDefault);
-    if (e == hipSuccess && cfg->batch > 1) e = hipHostMalloc((void**)&c->hbatch, c->hb_bytes(), hipHostMallocDefault);
+    hipError_t e = hipHostMalloc((void**)&c->hspan, c->span_bytes(), hipHostMallocDefault);
     if (e != hipSuccess) {
         rc = fail_global(METASD_E_HIP, "hipHostMalloc: %s", hipGetErrorString(e));
-        if (c->hres) (void)hipHostFree(c->hres);
         delete c;
         return rc;
     }
@@ -1396,8 +1386,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) {
         rc = fail_global(METASD_E_HIP, "context set-up: %s", hipGetErrorString(e));
-        (void)hipHostFree(c->hres);
-        if (c->hbatch) (void)hipHostFree(c->hbatch);
+        (void)hipHostFree(c->hspan);
         delete c;
         return rc;
     }
@@ -1407,8 +1396,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
 
 int32_t metasd_destroy(metasd_ctx* c) {
     if (!c) return METASD_OK;
-    if (c->hres) (void)hipHostFree(c->hres);
-    if (c->hbatch) (void)hipHostFree(c->hbatch);
+    if (c->hspan) (void)hipHostFree(c->hspan);
     for (auto& r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     delete c;
     return METASD_OK;
@@ -1539,22 +1527,20 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
                       (uint32_t)c->round, 0u, c->d_cand(), c->d_bd(), res, res + 1, (uint32_t*)(res + 2), c->d_hist(), l,
                       c->d_xchg(), pr ? pr->a : nullptr, pr ? pr->b : nullptr))
         return c->fail(METASD_E_HIP, "launch accept kernels failed");
-    HostResult* hr = c->hres;
-    HIP_TRY(c, hipMemcpyAsync(&hr->n_acc, res, 12, hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(c, hipMemcpyAsync(hr->d, c->d_draft(), (size_t)gamma * 4, hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(c, hipMemcpyAsync(hr->bd, c->d_bd(), (size_t)gamma * 8, hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(c, hipMemcpyAsync(&hr->bar, c->d_bar(), sizeof(GridBar), hipMemcpyDeviceToHost, c->stream));
-    HIP_TRY(c, hipStreamSynchronize(c->stream));
-    if (hr->bar.abort) {
+    if (int rc = c->fetch_results()) return rc;
+    const int32_t* hres = c->mirror<int32_t>(c->lay.res);     // n_acc, token, mask
+    const int32_t* hd = c->mirror<int32_t>(c->lay.draft);
+    const double* hbd = c->mirror<double>(c->lay.bd);
+    if (c->mirror<GridBar>(c->lay.bar)->abort) {
         (void)hipMemsetAsync(c->d_bar(), 0, sizeof(GridBar), c->stream);
         c->phase = PH_NONE;
         return c->fail(METASD_E_HIP, "a bounded device-side wait between workgroups timed out (split-K reduction or device-wide barrier); call metasd_set_context to start over");
     }
-    const int n = hr->n_acc;
-    if (hr->token == -2) { c->phase = PH_NONE; return c->fail(METASD_E_HIP, "accept: the workgroups of a position did not meet (exchange timed out); call metasd_set_context to start over"); }
-    if (n < 0 || n > gamma || hr->token < 0 || hr->token >= V) return c->fail(METASD_E_HIP, "accept: device returned n_acc %d token %d", n, hr->token);
-    for (int j = 0; j < n; ++j) c->sq[0].hist[l + j] = hr->d[j];
-    c->sq[0].hist[l + n] = hr->token;
+    const int n = hres[0], token = hres[1];
+    if (token == -2) { c->phase = PH_NONE; return c->fail(METASD_E_HIP, "accept: the workgroups of a position did not meet (exchange timed out); call metasd_set_context to start over"); }
+    if (n < 0 || n > gamma || token < 0 || token >= V) return c->fail(METASD_E_HIP, "accept: device returned n_acc %d token %d", n, token);
+    for (int j = 0; j < n; ++j) c->sq[0].hist[l + j] = hd[j];
+    c->sq[0].hist[l + n] = token;
     // commit: rows 0..n of the verification block stay in the target's cache; the drafter keeps
     // the committed prefix it has processed (it never saw d_gamma)
     c->sq[0].l = l + n + 1;
@@ -1563,11 +1549,11 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
     c->round += 1;
     c->phase = PH_READY;
     if (n_acc_out) *n_acc_out = n;
-    if (token_out) *token_out = hr->token;
-    if (mask_out) *mask_out = hr->mask;
+    if (token_out) *token_out = token;
+    if (mask_out) *mask_out = (uint32_t)hres[2];
     if (bd_out) {
         double s = 0.0;
-        for (int j = 0; j < gamma; ++j) s += hr->bd[j];
+        for (int j = 0; j < gamma; ++j) s += hbd[j];
         *bd_out = s / (double)gamma;
     }
     return METASD_OK;
