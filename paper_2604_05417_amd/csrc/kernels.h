@@ -287,6 +287,7 @@ struct GemmPro {
     float eps;             // NORM
     int act;               // ACT: 1 SwiGLU, 0 GELU
     int nchunks, hd;       // COMBINE: attention chunks, head dim
+    int row0;              // PLAIN with src: first row of the sums-of-squares table that belongs to this block
 };
 
 // Epilogue variant for the two projections that feed the residual stream (attention output, FFN down):
@@ -360,12 +361,31 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict_
     if constexpr (PRO == PRO_PLAIN) {
         // When the input is h * gain of a residual epilogue (not yet normalised), workgroup 0 also turns the
         // per-tile-group sums of squares into 1/rms per row for the kernels that consume this GEMM's output.
+        // (all rows of an entry come with four 16-byte loads, every load independent of the others: one memory
+        // round trip for the whole table instead of one per row - this wavefront is on the kernel's critical path)
         if (pro.src && blockIdx.x == 0 && wave == 0) {
-            for (int r = 0; r < m; ++r) {
-                float t = 0.f;
-                for (int i = lane; i < pro.ns; i += 64) t += pro.src[i * 16 + r];
-                t = wave_sum(t);
-                if (lane == 0) pro.h_out[r] = 1.0f / sqrtf(t / (float)K + pro.eps);
+            float4 t[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) t[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+            for (int i0 = 0; i0 < pro.ns; i0 += 64) {
+                const int i = i0 + lane;
+                const float sc = i < pro.ns ? 1.f : 0.f;
+                const float4* e = reinterpret_cast<const float4*>(pro.src + (size_t)min(i, pro.ns - 1) * 16);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = e[q];
+                    t[q].x += sc * v.x; t[q].y += sc * v.y; t[q].z += sc * v.z; t[q].w += sc * v.w;
+                }
+            }
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr) {                  // table row rr is this block's row rr - pro.row0
+                const float4 tq = t[rr >> 2];
+                float tr = (rr & 3) == 0 ? tq.x : (rr & 3) == 1 ? tq.y : (rr & 3) == 2 ? tq.z : tq.w;
+                if (rr >= pro.row0 && rr - pro.row0 < m) {     // wavefront-uniform
+                    tr = wave_sum(tr);
+                    if (lane == 0) pro.h_out[rr - pro.row0] = 1.0f / sqrtf(tr / (float)K + pro.eps);
+                }
             }
         }
         // Order of the requests (a wavefront's loads return in order): first the activations of this
@@ -744,6 +764,123 @@ __global__ __launch_bounds__(512) void gemm_fullk_residual_kernel(const bf16_t* 
             multiply(wb, gi + 1);
         } else {
             multiply(wa, gi);
+        }
+    }
+    red[wave * 64 + lane] = acc + acl;
+    __syncthreads();
+    if (wave != 0) return;
+    f32x4 y = red[lane];
+#pragma unroll
+    for (int w = 1; w < 8; ++w) y += red[w * 64 + lane];      // fixed order: deterministic
+    float ss = 0.f;
+    if (rowok) {
+        const size_t col = (size_t)t * 16 + g * 4;
+        float4 hv = *reinterpret_cast<const float4*>(h + (size_t)row * N + col);
+        hv.x += y[0]; hv.y += y[1]; hv.z += y[2]; hv.w += y[3];
+        *reinterpret_cast<float4*>(h + (size_t)row * N + col) = hv;
+        const uint2 gn = *reinterpret_cast<const uint2*>(gain + col);
+        const float4 xg = make_float4(hv.x * bf2f((bf16_t)(gn.x & 0xffffu)), hv.y * bf2f((bf16_t)(gn.x >> 16)),
+                                      hv.z * bf2f((bf16_t)(gn.y & 0xffffu)), hv.w * bf2f((bf16_t)(gn.y >> 16)));
+        store_split4(xsplit, (size_t)m * N, (size_t)row * N + col, xg);
+        ss = hv.x * hv.x + hv.y * hv.y + hv.z * hv.z + hv.w * hv.w;
+    }
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if (g == 0) ssq[(size_t)t * 16 + row] = ss;
+}
+
+// The same projection for an input block too large for LDS (the FFN down projection: K = d_ffn): each wavefront
+// still owns an eighth of the tile's K range, but stages its activations group by group (8 chunks = 256
+// inputs at a time, the granularity of its weight register buffers) into two small private LDS buffers:
+// while group g is multiplied, the activations of group g+1 are requested (L2 hits) and written to the other
+// buffer.  Wavefront-private, so no workgroup barrier inside the stream; LDS reduction over the eight
+// wavefronts and the residual epilogue as in gemm_fullk_residual_kernel.  No sibling workgroups.
+//   XB = ceil(m / 2): 16-byte pieces per lane, term and group.
+//   grid (ntiles), block 512, dynamic LDS 8 * 2 * 2 * m * 33 * 16 + 8 * 64 * 16 bytes.
+template <int XB>
+__global__ __launch_bounds__(512) void gemm_fullk_roll_residual_kernel(const bf16_t* __restrict__ xh, size_t x_lo_off, int ldx, int m, int K,
+                                                                       const bf16_t* __restrict__ W, int ntiles, int N,
+                                                                       float* __restrict__ h, const bf16_t* __restrict__ gain,
+                                                                       float* __restrict__ xsplit, float* __restrict__ ssq) {
+    extern __shared__ uint4 lds[];
+    constexpr int RS = GEMM_U * 4 + 1;             // LDS row stride (16-byte pieces), +1 against bank conflicts
+    const int kchunks = K >> 5;
+    const int cpw = (kchunks + 7) >> 3;            // chunks per wavefront
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blockIdx.x;
+    const int c0 = min(wave * cpw, kchunks - 1), nc = max(0, min(cpw, kchunks - wave * cpw));
+    uint4* xbuf = lds + (size_t)wave * 4 * m * RS;                         // [2 buffers][2 (hi, lo)][m][RS]
+    f32x4* red = reinterpret_cast<f32x4*>(lds + (size_t)8 * 4 * m * RS);   // [8][64]
+    const u32x4* wp = reinterpret_cast<const u32x4*>(W) + ((size_t)t * kchunks + c0) * 64 + lane;
+    const int ngroups = (nc + GEMM_U - 1) / GEMM_U;
+    const int last = max(nc, 1) - 1;
+    // every load is unconditional and clamped into valid memory; chunks past the slice's end meet masked weights
+    auto issue = [&](u32x4 (&w)[GEMM_U], int gi) {
+#pragma unroll
+        for (int u = 0; u < GEMM_U; ++u) w[u] = __builtin_nontemporal_load(wp + (size_t)min(gi * GEMM_U + u, last) * 64);
+    };
+    const int npieces = m * GEMM_U * 4;            // pieces per term and group
+    auto sload = [&](u32x4 (&a)[XB], u32x4 (&b)[XB], int gi) {
+#pragma unroll
+        for (int u = 0; u < XB; ++u) {
+            const int idx = min(lane + 64 * u, npieces - 1), r = idx / (GEMM_U * 4), c = idx - r * (GEMM_U * 4);
+            const int col = min((c0 + gi * GEMM_U) * 32 + c * 8, K - 8);
+            const bf16_t* src = xh + (size_t)r * ldx + col;
+            a[u] = *reinterpret_cast<const u32x4*>(src);
+            b[u] = *reinterpret_cast<const u32x4*>(src + x_lo_off);
+        }
+    };
+    auto sstore = [&](const u32x4 (&a)[XB], const u32x4 (&b)[XB], int buf) {
+        uint4* xs = xbuf + (size_t)buf * 2 * m * RS;
+#pragma unroll
+        for (int u = 0; u < XB; ++u) {
+            const int idx = lane + 64 * u;
+            if (idx < npieces) {
+                const int r = idx / (GEMM_U * 4), c = idx - r * (GEMM_U * 4);
+                xs[r * RS + c] = __builtin_bit_cast(uint4, a[u]);
+                xs[(m + r) * RS + c] = __builtin_bit_cast(uint4, b[u]);
+            }
+        }
+    };
+    const int row = lane & 15, g = lane >> 4;
+    const bool rowok = row < m;
+    const int rowc = rowok ? row : 0;              // rows beyond m read row 0: their output columns are never stored
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acl = {0.f, 0.f, 0.f, 0.f};
+    auto multiply = [&](const u32x4 (&w)[GEMM_U], int buf, int gi) {
+        const u32x4* xs = reinterpret_cast<const u32x4*>(xbuf + (size_t)buf * 2 * m * RS);
+#pragma unroll
+        for (int u = 0; u < GEMM_U; ++u) {
+            const uint32_t mask = gi * GEMM_U + u < nc ? 0xffffffffu : 0u;
+            const u32x4 wm = w[u] & mask;
+            const u32x4 ah = xs[rowc * RS + u * 4 + g], al = xs[(m + rowc) * RS + u * 4 + g];
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wm), __builtin_bit_cast(bf16x8, ah), acc, 0, 0, 0);
+            acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wm), __builtin_bit_cast(bf16x8, al), acl, 0, 0, 0);
+        }
+    };
+    u32x4 wa[GEMM_U], wb[GEMM_U], xa[XB], xb[XB];
+    if (nc > 0) {
+        sload(xa, xb, 0);                          // activations first: they come back first
+        issue(wa, 0);
+        sstore(xa, xb, 0);
+        int gi = 0;
+        for (; gi + 2 < ngroups; gi += 2) {
+            sload(xa, xb, gi + 1);
+            issue(wb, gi + 1);
+            multiply(wa, 0, gi);
+            sstore(xa, xb, 1);
+            sload(xa, xb, gi + 2);
+            issue(wa, gi + 2);
+            multiply(wb, 1, gi + 1);
+            sstore(xa, xb, 0);
+        }
+        if (gi + 2 == ngroups) {
+            sload(xa, xb, gi + 1);
+            issue(wb, gi + 1);
+            multiply(wa, 0, gi);
+            sstore(xa, xb, 1);
+            multiply(wb, 1, gi + 1);
+        } else {
+            multiply(wa, 0, gi);
         }
     }
     red[wave * 64 + lane] = acc + acl;

@@ -380,6 +380,7 @@ struct metasd_ctx {
     bool tlog = false;
     bool persistent = false;         // bf16 models run the one-launch forward (cooperative launch available)
     bool fullk = true;               // residual GEMMs whose input fits in LDS run without split-K (METASD_GEMM_FULLK=0: off)
+    bool fullk_roll = true;          // .. and larger inputs with rolling private staging (METASD_GEMM_ROLL=0: sibling reduction instead)
     bool gemm_reduce = true;         // bf16 models: residual GEMMs reduce their split-K partials themselves (METASD_GEMM_REDUCE=0: off)
     float cur_eps = 1e-5f;           // rms_eps of the model whose forward is being launched
     bool fuse_small = true;          // short blocks of narrow bf16 models use the GEMMs with fused prologues (METASD_FUSE_SMALL=0: off)
@@ -490,7 +491,7 @@ int gemm<bf16_t>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
     GemmPro plain{};
     plain.sstride = x_lo_off;
-    if (ssq) { plain.src = ssq + inv_row0; plain.ns = ntg; plain.h_out = inv_out + inv_row0; plain.eps = c->cur_eps; }
+    if (ssq) { plain.src = ssq; plain.row0 = inv_row0; plain.ns = ntg; plain.h_out = inv_out + inv_row0; plain.eps = c->cur_eps; }
     hipExtLaunchKernelGGL(gemm_bf16_kernel<PRO_PLAIN>, dim3(groups * s.ksplit), dim3(256), (uint32_t)s.lds, c->stream,
                           pr ? pr->a : nullptr, pr ? pr->b : nullptr, 0u, (const float*)x, ldx, m, K, (const bf16_t*)W0,
                           (const bf16_t*)W1, (const bf16_t*)W2, n0 / 16, (n0 + n1) / 16, ntiles, out, N, s.ksplit, s.cps, s.tpb,
@@ -528,6 +529,19 @@ int gemm_residual(metasd_ctx* c, const void* x, int ldx, int m, int K, const voi
                               pr ? pr->b : nullptr, 0u, (const bf16_t*)x, x_lo_off, ldx, m, K, (const bf16_t*)W, ntiles, N, h,
                               (const bf16_t*)gain_next, xsplit, ssq);
         LAUNCH_CHECK(c, "gemm_bf16 (full-K residual)");
+        *ntg_out = ntiles;
+        return 0;
+    }
+    const size_t lds_roll = (size_t)8 * 4 * m * (GEMM_U * 4 + 1) * 16 + (size_t)8 * 64 * 16;
+    if (c->fullk && c->fullk_roll && m <= 8 && ntiles * 4 >= c->n_cu * 3 && kchunks >= 8 * GEMM_U && lds_roll <= FULLK_LDS_MAX) {
+        metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
+        hipEvent_t ea = pr ? pr->a : nullptr, eb = pr ? pr->b : nullptr;
+#define ROLL_GO(XB) hipExtLaunchKernelGGL(gemm_fullk_roll_residual_kernel<XB>, dim3(ntiles), dim3(512), (uint32_t)lds_roll, c->stream, ea, eb, 0u, \
+                                          (const bf16_t*)x, x_lo_off, ldx, m, K, (const bf16_t*)W, ntiles, N, h, (const bf16_t*)gain_next, xsplit, ssq)
+        if (m <= 6) ROLL_GO(3);
+        else ROLL_GO(4);
+#undef ROLL_GO
+        LAUNCH_CHECK(c, "gemm_bf16 (full-K residual, rolling staging)");
         *ntg_out = ntiles;
         return 0;
     }
@@ -1370,6 +1384,15 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         if (const char* ev = getenv("METASD_FUSE_SMALL")) c->fuse_small = ev[0] != '0';
         if (const char* ev = getenv("METASD_GEMM_REDUCE")) c->gemm_reduce = ev[0] != '0';
         if (const char* ev = getenv("METASD_GEMM_FULLK")) c->fullk = ev[0] != '0';
+        if (const char* ev = getenv("METASD_GEMM_ROLL")) c->fullk_roll = ev[0] != '0';
+        {
+            const int roll_lds = (int)FULLK_LDS_MAX;
+            if (hipFuncSetAttribute((const void*)gemm_fullk_roll_residual_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, roll_lds) != hipSuccess ||
+                hipFuncSetAttribute((const void*)gemm_fullk_roll_residual_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, roll_lds) != hipSuccess) {
+                c->fullk_roll = false;
+                (void)hipGetLastError();
+            }
+        }
         if (hipFuncSetAttribute((const void*)gemm_fullk_residual_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)FULLK_LDS_MAX) != hipSuccess) { c->fullk = false; (void)hipGetLastError(); }
         c->n_cu = ncu;
         if (const char* ev = getenv("METASD_NB")) { int v = atoi(ev); if (v >= 1 && v <= ncu) c->n_cu = v; }   // fewer workgroups (debugging)
