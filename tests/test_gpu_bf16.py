@@ -173,3 +173,17 @@ def test_step_by_step_variants_stay_in_parity(env, monkeypatch):
     cfg["max_ctx"] = s["prompt"] + 80
     st = run_lockstep(cfg, 1.0, rounds=4, kv_prefilled=False)
     assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+
+
+@pytest.mark.parametrize("gamma,roll", [(3, "1"), (5, "1"), (7, "1"), (7, "0")])
+def test_wide_shallow_target_residual_projections(gamma, roll, monkeypatch):
+    """A target wide enough (d 3072 = 192 tiles, FFN 4096) for the residual projections without split-K -
+    output projection with its input block in LDS, down projection with rolling staging - at 4, 6 and 8
+    verification rows (both staging widths), and the same shape through the split-K sibling reduction."""
+    monkeypatch.setenv("METASD_GEMM_ROLL", roll)
+    cfg = W.config4(n_layers=2, ctx=70, n_new=64, K=2, d_model=3072, n_heads=24, d_ffn=4096, vocab=1024, dd_model=128, dn_heads=2,
+                    dd_ffn=160)
+    cfg["gamma"] = gamma
+    cfg["max_ctx"] = 70 + 64
+    st = run_lockstep(cfg, 1.0, rounds=3, kv_prefilled=False)
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
