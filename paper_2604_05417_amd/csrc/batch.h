@@ -144,18 +144,18 @@ __global__ void commit_tokens_kernel(const int32_t* __restrict__ n_acc, const in
 // bf16 GEMM on MFMA for blocks of more than 16 rows (verification of a batch: R = batch x (gamma + 1)).
 //   out[ks][r][n] = sum over the K-slice of x[r][k] W[n][k],  W in streaming-tile order,
 //   x as two bf16 arrays (hi at xh, lo x_lo_off elements behind), row stride ldx.
-// One workgroup of 8 wavefronts owns 8 feature tiles (128 features) x one K-slice x all R rows:
-// wavefronts 0-3 the first four tiles, 4-7 the other four; within a quad wavefront w takes the
+// One workgroup of 8 wavefronts owns 2 TPQ feature tiles (TPQ = 4: 128 features) x one K-slice x all R rows:
+// wavefronts 0-3 the first TPQ tiles, 4-7 the other TPQ; within a quad wavefront w takes the
 // 16-row blocks w, w+4, ..  (RBW of them).  The K-slice advances in stages of two 32-wide chunks:
 // per stage the R x 64 activations (both terms: 128 contiguous bytes per row and term, so the
 // requests are whole cache lines) are staged in LDS, double-buffered, one workgroup barrier per
-// stage; a wavefront reads each activation fragment once and feeds it to the four tiles it holds
-// in registers (8 MFMAs per LDS read pair), so LDS reads stay far below the MFMA rate.  Weights:
+// stage; a wavefront reads each activation fragment once and feeds it to the TPQ tiles it holds
+// in registers (2 TPQ MFMAs per LDS read pair), so LDS reads stay far below the MFMA rate.  Weights:
 // PD stages (8 KiB each per wavefront) in flight in registers; the wavefronts that share tiles
 // request the same lines (L1 / L2 hits).  Activation pieces are requested one stage ahead.
 // LO = false leaves out the low-order terms of the activations (plain bf16 activations).
-//   grid (ceil(ntiles/8) * ksplit), block 512, dynamic LDS 2 * (LO ? 16 : 8) * (64 RBW + 1) * 16 bytes;  R <= 64 RBW.
-template <int RBW, int PD, bool LO>
+//   grid (ceil(ntiles / (2 TPQ)) * ksplit), block 512, dynamic LDS 2 * (LO ? 16 : 8) * (64 RBW + 1) * 16 bytes;  R <= 64 RBW.
+template <int RBW, int PD, bool LO, int TPQ = 4>
 __global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __restrict__ xh, size_t x_lo_off, int ldx, int R, int K,
                                                              const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
                                                              const bf16_t* __restrict__ W2, int t0, int t1, int ntiles,
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __res
     const int nst = (nc + 1) >> 1;                 // stages of two chunks
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, quad = wave >> 2, wr = wave & 3;
     const int row16 = lane & 15, g = lane >> 4;
-    const int tl0 = tg * 8 + quad * 4;             // this wavefront's four tiles: tl0 .. tl0 + 3
+    const int tl0 = tg * 2 * TPQ + quad * TPQ;     // this wavefront's TPQ tiles: tl0 .. tl0 + TPQ - 1
     auto tile_ptr = [&](int i) -> const u32x4* {
         const int t = min(tl0 + i, ntiles - 1);
         const bf16_t* W;
@@ -181,17 +181,17 @@ __global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __res
         else { W = W2; tt = t - t1; }
         return reinterpret_cast<const u32x4*>(W) + ((size_t)tt * kchunks + c0) * 64 + lane;
     };
-    const u32x4 *wp0 = tile_ptr(0), *wp1 = tile_ptr(1), *wp2 = tile_ptr(2), *wp3 = tile_ptr(3);
+    const u32x4* wp[TPQ];
+#pragma unroll
+    for (int i = 0; i < TPQ; ++i) wp[i] = tile_ptr(i);
     // every load is unconditional and clamped into range: chunks past the slice's end re-read its last
     // chunk and are multiplied by zero
-    auto wload = [&](u32x4 (&dst)[8], int st) {
+    auto wload = [&](u32x4 (&dst)[2 * TPQ], int st) {
 #pragma unroll
         for (int cc = 0; cc < 2; ++cc) {
             const size_t co = (size_t)min(2 * st + cc, nc - 1) * 64;   // plain loads: the four wavefronts that share these tiles meet in L1
-            dst[cc * 4 + 0] = wp0[co];
-            dst[cc * 4 + 1] = wp1[co];
-            dst[cc * 4 + 2] = wp2[co];
-            dst[cc * 4 + 3] = wp3[co];
+#pragma unroll
+            for (int i = 0; i < TPQ; ++i) dst[cc * TPQ + i] = wp[i][co];
         }
     };
     auto aload = [&](u32x4 (&dst)[APT], int st) {
@@ -211,21 +211,21 @@ __global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __res
             base[(idx % NP) * LR + idx / NP] = __builtin_bit_cast(uint4, src[u]);
         }
     };
-    f32x4 acc[RBW][4];
+    f32x4 acc[RBW][TPQ];
 #pragma unroll
     for (int a = 0; a < RBW; ++a)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) acc[a][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < TPQ; ++i) acc[a][i] = f32x4{0.f, 0.f, 0.f, 0.f};
     // Chunks past the slice's end are multiplied by zero: the (re-read, clamped) weight tiles of such a chunk
     // are masked in registers - they arrived long ago, so the mask costs no wait; masking the activation
     // fragments instead would make every LDS read wait for its data at once.
     // The activation fragments of step k+1 (a step = one 16-row block of one chunk) are read from LDS
     // before the MFMAs of step k are issued, so the LDS latency hides behind 8 (4) MFMAs.
-    auto compute = [&](u32x4 (&w)[8], int buf, int st) {
+    auto compute = [&](u32x4 (&w)[2 * TPQ], int buf, int st) {
         const u32x4* base = reinterpret_cast<const u32x4*>(lds) + (size_t)buf * NP * LR;
         const uint32_t mask0 = 2 * st < nc ? 0xffffffffu : 0u, mask1 = 2 * st + 1 < nc ? 0xffffffffu : 0u;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { w[i] &= mask0; w[4 + i] &= mask1; }
+        for (int i = 0; i < TPQ; ++i) { w[i] &= mask0; w[TPQ + i] &= mask1; }
         u32x4 fh[2], fl[2];
         auto fetch = [&](int k) {               // step k: chunk cc = k / RBW, row block a = k % RBW
             const int cc = k / RBW, a = k % RBW;
@@ -239,12 +239,12 @@ __global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __res
             if (k + 1 < 2 * RBW) fetch(k + 1);
             const int cc = k / RBW, a = k % RBW;
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[cc * 4 + i]), __builtin_bit_cast(bf16x8, fh[k & 1]), acc[a][i], 0, 0, 0);
+            for (int i = 0; i < TPQ; ++i)
+                acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[cc * TPQ + i]), __builtin_bit_cast(bf16x8, fh[k & 1]), acc[a][i], 0, 0, 0);
             if constexpr (LO) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[cc * 4 + i]), __builtin_bit_cast(bf16x8, fl[k & 1]), acc[a][i], 0, 0, 0);
+                for (int i = 0; i < TPQ; ++i)
+                    acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[cc * TPQ + i]), __builtin_bit_cast(bf16x8, fl[k & 1]), acc[a][i], 0, 0, 0);
             }
         }
         // shape of the schedule: the reads of the next step, then the MFMAs of this one
@@ -252,18 +252,21 @@ __global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __res
 #pragma unroll
         for (int k = 0; k < 2 * RBW; ++k) {
             if (k + 1 < 2 * RBW) __builtin_amdgcn_sched_group_barrier(0x100, LO ? 2 : 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, LO ? 8 : 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, LO ? 2 * TPQ : TPQ, 0);
         }
     };
     // Order of the requests (a wavefront's loads return in order): the activations of stage st+1 are
     // requested before the multiplies of stage st-1 and written to LDS before those of stage st; the only
     // loads requested after them and before that write are weights the next multiplies need anyway.
-    u32x4 w[PD][8], ar[APT];
+    u32x4 w[PD][2 * TPQ];
+    u32x4 ar[APT];
     aload(ar, 0);
 #pragma unroll
-    for (int u = 0; u < PD; ++u) wload(w[u], u);
+    for (int u = 0; u + 1 < PD; ++u) wload(w[u], u);
     astore(ar, 0);
     aload(ar, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    wload(w[PD - 1], PD - 1);                      // as in the loop: the youngest requests on entry are weights
     lds_barrier();
     for (int sb = 0; sb < nst; sb += PD) {
 #pragma unroll
@@ -271,6 +274,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __res
             const int st = sb + u;
             astore(ar, (st + 1) & 1);              // stage st+1 (its buffer was last read in stage st-1, before the last barrier)
             aload(ar, st + 2);                     // returns while this stage is multiplied
+            // The activation requests stay ahead of this stage's weight requests: loads return in order, so an
+            // activation load scheduled behind them would make the next stage's LDS write wait for weights that
+            // are only needed two stages later (a full trip to HBM per stage).
+            __builtin_amdgcn_sched_barrier(0);
             compute(w[u], st & 1, st);
             wload(w[u], st + PD);
             lds_barrier();
@@ -281,7 +288,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __res
         const int row = (wr + 4 * a) * 16 + row16;
         if (row < R) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < TPQ; ++i)
                 if (tl0 + i < ntiles) {
                     float* o = out + (size_t)ks * out_sstride + (size_t)row * N + (size_t)(tl0 + i) * 16 + g * 4;
                     *reinterpret_cast<float4*>(o) = make_float4(acc[a][i][0], acc[a][i][1], acc[a][i][2], acc[a][i][3]);

@@ -92,24 +92,30 @@ Split choose_split(int m, int ntiles, int kchunks) {
     return s;
 }
 
-// Split of a gemm_bf16_rows_kernel launch: 8 tiles per workgroup, one workgroup per CU at a time.  The K split
-// minimises (rounds of workgroups over the CUs) x (chunks per slice) plus the traffic of the partial sums.
-Split choose_split_rows(int ntiles, int kchunks, int R = 256) {
+// Many-row GEMM (more than 16 rows): tiles per workgroup (8; for more than 128 rows also 6 or 4) and K split.
+// A workgroup holds a CU (its LDS), so the launch runs in ceil(workgroups / 256) rounds; measured on the 7B
+// shapes at 256 rows a round costs about 0.9 / 0.75 / 0.6 us per 32-wide K chunk with 8 / 6 / 4 tiles (a fixed
+// part for staging the activations plus the multiplies), and the split-K partials are written and read once.
+Split choose_split_rows(int ntiles, int kchunks, int R, int forced_tpb) {
     static const int forced = env_int("METASD_ROWS_KS", 0);
-    const int groups = (ntiles + 7) / 8;
-    int best = 1;
+    int best = 1, best_tpb = 8;
     double best_cost = 1e30;
-    for (int ks = 1; ks <= 8 && kchunks / ks >= 8; ++ks) {
-        const int cps = ((kchunks + ks - 1) / ks + 3) / 4 * 4;
-        const int rounds = (groups * ks + 255) / 256;
-        const double cost = (double)rounds * cps * 0.5 + (ks > 1 ? (double)ks * R * ntiles * 16 * 8 / 4e6 : 0.0);   // us
-        if (cost < best_cost) { best_cost = cost; best = ks; }
+    for (int tpb = 8; tpb >= 4; tpb -= 2) {
+        if (tpb != 8 && (R <= 128 || (forced_tpb && tpb != forced_tpb))) continue;
+        if (tpb == 8 && forced_tpb && forced_tpb != 8 && R > 128) continue;
+        const int groups = (ntiles + tpb - 1) / tpb;
+        for (int ks = 1; ks <= 8 && kchunks / ks >= 8; ++ks) {
+            const int cps = ((kchunks + ks - 1) / ks + 3) / 4 * 4;
+            const int rounds = (groups * ks + 255) / 256;
+            const double cost = (double)rounds * cps * (0.3 + 0.075 * tpb) + (ks > 1 ? (double)ks * R * ntiles * 16 * 8 / 8e6 : 0.0);   // us
+            if (cost < best_cost) { best_cost = cost; best = ks; best_tpb = tpb; }
+        }
     }
     int ks = forced > 0 ? std::min(forced, std::max(1, kchunks / 8)) : best;
     int cps = ((kchunks + ks - 1) / ks + 3) / 4 * 4;
     ks = (kchunks + cps - 1) / cps;
     Split s;
-    s.ksplit = ks; s.cps = cps; s.tpb = 8; s.lds = 0;
+    s.ksplit = ks; s.cps = cps; s.tpb = best_tpb; s.lds = 0;
     return s;
 }
 
@@ -380,6 +386,7 @@ struct metasd_ctx {
     bool tlog = false;
     bool persistent = false;         // bf16 models run the one-launch forward (cooperative launch available)
     bool fullk = true;               // residual GEMMs whose input fits in LDS run without split-K (METASD_GEMM_FULLK=0: off)
+    int rows_tpb = 0;                // many-row GEMM: tiles per workgroup, 0 = by the cost model (METASD_ROWS_TPB=4|6|8 forces one)
     bool fullk_roll = true;          // .. and larger inputs with rolling private staging (METASD_GEMM_ROLL=0: sibling reduction instead)
     bool gemm_reduce = true;         // bf16 models: residual GEMMs reduce their split-K partials themselves (METASD_GEMM_REDUCE=0: off)
     float cur_eps = 1e-5f;           // rms_eps of the model whose forward is being launched
@@ -931,18 +938,18 @@ int gemm_rows<float>(metasd_ctx* c, const void* x, int ldx, int R, int K, const 
 }
 
 // more than 64 KiB of dynamic LDS needs the function attribute (set once per variant; harmless below the limit)
-template <int RBW, bool LO, int PD = ROWS_PD>
+template <int RBW, bool LO, int TPQ = 4, int PD = ROWS_PD>
 int launch_gemm_rows(metasd_ctx* c, const bf16_t* xh, size_t x_lo_off, int ldx, int R, int r0, int nr, int K, const void* W0,
                      const void* W1, const void* W2, int t0, int t1, int ntiles, int N, const Split& s, metasd_ctx::ProfRec* pr) {
     const size_t lds = (size_t)2 * (LO ? 16 : 8) * (64 * RBW + 1) * 16;
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)gemm_bf16_rows_kernel<RBW, PD, LO>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        if (hipFuncSetAttribute((const void*)gemm_bf16_rows_kernel<RBW, PD, LO, TPQ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return c->fail(METASD_E_HIP, "gemm_bf16_rows_kernel: cannot reserve %zu bytes of LDS", lds);
         attr_set = true;
     }
-    const int groups = (ntiles + 7) / 8;
-    hipExtLaunchKernelGGL((gemm_bf16_rows_kernel<RBW, PD, LO>), dim3(groups * s.ksplit), dim3(512), (uint32_t)lds, c->stream,
+    const int groups = (ntiles + 2 * TPQ - 1) / (2 * TPQ);
+    hipExtLaunchKernelGGL((gemm_bf16_rows_kernel<RBW, PD, LO, TPQ>), dim3(groups * s.ksplit), dim3(512), (uint32_t)lds, c->stream,
                           pr ? pr->a : nullptr, pr ? pr->b : nullptr, 0u, xh + (size_t)r0 * ldx, x_lo_off, ldx, nr, K, (const bf16_t*)W0,
                           (const bf16_t*)W1, (const bf16_t*)W2, t0, t1, ntiles, c->d_part() + (size_t)r0 * N, (size_t)R * N, N, s.ksplit, s.cps);
     LAUNCH_CHECK(c, "gemm_bf16_rows");
@@ -955,7 +962,7 @@ int gemm_rows<bf16_t>(metasd_ctx* c, const void* x, int ldx, int R, int K, const
     const size_t x_lo_off = (size_t)R * ldx;      // producers write hi [R][ldx], then lo [R][ldx]
     if (R <= MAX_ROWS) return gemm<bf16_t>(c, x, ldx, R, K, W0, n0, W1, n1, W2, n2, nullptr, nsplit_out, x_lo_off);
     const int N = n0 + n1 + n2, ntiles = N / 16, kchunks = K / 32;
-    const Split s = choose_split_rows(ntiles, kchunks, R);
+    const Split s = choose_split_rows(ntiles, kchunks, R, c->rows_tpb);
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)R * K * 4 + (double)R * N * 4 * s.ksplit);
     const bf16_t* xh = (const bf16_t*)x;
     const int t0 = n0 / 16, t1 = (n0 + n1) / 16;
@@ -969,6 +976,8 @@ int gemm_rows<bf16_t>(metasd_ctx* c, const void* x, int ldx, int R, int K, const
 #define ROWS_GO(RBW) (lo ? launch_gemm_rows<RBW, true> ROWS_ARGS : launch_gemm_rows<RBW, false> ROWS_ARGS)
         if (nr <= 64) rc = ROWS_GO(1);
         else if (nr <= 128) rc = ROWS_GO(2);
+        else if (lo && s.tpb == 4) rc = launch_gemm_rows<4, true, 2> ROWS_ARGS;
+        else if (lo && s.tpb == 6) rc = launch_gemm_rows<4, true, 3> ROWS_ARGS;
         else rc = ROWS_GO(4);
 #undef ROWS_GO
 #undef ROWS_ARGS
@@ -1385,6 +1394,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         if (const char* ev = getenv("METASD_GEMM_REDUCE")) c->gemm_reduce = ev[0] != '0';
         if (const char* ev = getenv("METASD_GEMM_FULLK")) c->fullk = ev[0] != '0';
         if (const char* ev = getenv("METASD_GEMM_ROLL")) c->fullk_roll = ev[0] != '0';
+        if (const char* ev = getenv("METASD_ROWS_TPB")) { const int v = atoi(ev); c->rows_tpb = (v == 4 || v == 6 || v == 8) ? v : 0; }
         {
             const int roll_lds = (int)FULLK_LDS_MAX;
             if (hipFuncSetAttribute((const void*)gemm_fullk_roll_residual_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, roll_lds) != hipSuccess ||

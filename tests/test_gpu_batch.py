@@ -135,6 +135,27 @@ def test_bf16_wide_blocks(rows):
     g.close()
 
 
+@pytest.mark.parametrize("tpb", [4, 6])
+def test_bf16_wide_blocks_other_tile_counts(tpb, monkeypatch):
+    """The 256-row GEMM variant with 4 and 6 feature tiles per workgroup (the cost model picks them for the 7B shapes;
+    here forced at context creation): 20 x 8 = 160 rows, tile counts that are no multiple of 4 or 6 (ragged last group)."""
+    monkeypatch.setenv("METASD_ROWS_TPB", str(tpb))
+    s = SMALL[0]
+    cfg = W.config4(n_layers=2, ctx=140, n_new=64, K=2, d_model=s["d_model"], n_heads=s["n_heads"], d_ffn=s["d_ffn"], vocab=s["vocab"],
+                    dd_model=s["dd_model"], dn_heads=s["dn_heads"], dd_ffn=s["dd_ffn"])
+    cfg["gamma"] = 7
+    cfg["max_ctx"] = 140 + 40
+    prompts = [W.prompt_tokens(140 - (b % 3), s["vocab"], 50 + b) for b in range(20)]
+    g, seqs = batch_pair(cfg, 1.0, prompts, TOL)
+    bl = make_lockstep(g, cfg, seqs, prompts, 1.0, TOL)
+    for r in range(2):
+        bl.round()
+    for ls in bl.seqs:
+        st = ls.stats
+        assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+    g.close()
+
+
 def test_batch_limits_and_errors():
     cfg = W.config1()
     td, tw = cfg["target"]
