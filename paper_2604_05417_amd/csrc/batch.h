@@ -71,25 +71,27 @@ __global__ __launch_bounds__(256) void attn_partial_seg_kernel(const float* __re
                              part + (size_t)s * H * nch_max * 16 * (HD + 2), nch_max, c, (int)blockIdx.y);
 }
 
-template <int HD>
-__global__ __launch_bounds__(256) void attn_partial_mfma_seg_kernel(const float* __restrict__ q, const bf16_t* __restrict__ kc,
+template <int HD, bool MULTI>
+__global__ __launch_bounds__(256, 3) void attn_partial_mfma_seg_kernel(const float* __restrict__ q, const bf16_t* __restrict__ kc,
                                                                     const bf16_t* __restrict__ vc, size_t kv_seq_stride, Segs sg,
                                                                     int H, int KH, int max_ctx, float scale,
-                                                                    float* __restrict__ part, int nch_max, size_t q_lo_off) {
-    const int s = blockIdx.z, m = sg.m[s], pos0 = sg.pos0[s], c = blockIdx.x;
+                                                                    float* __restrict__ part, int nch_max, size_t q_lo_off, int cpw) {
+    // workgroup blockIdx.x takes chunks blockIdx.x * cpw .. + cpw - 1 of its (sequence, head) and writes record blockIdx.x
+    const int s = blockIdx.z, m = sg.m[s], pos0 = sg.pos0[s], c = blockIdx.x * cpw;
     if (c * ATT_CH >= pos0 + m) return;                 // workgroup-uniform
     const size_t so = (size_t)sg.seq[s] * kv_seq_stride;
     const bf16_t* qs = reinterpret_cast<const bf16_t*>(q) + (size_t)s * sg.ms * H * HD;
-    attn_partial_mfma_body<HD>(reinterpret_cast<const float*>(qs), kc + so, vc + so, m, pos0, H, KH, max_ctx, scale,
-                               part + (size_t)s * H * nch_max * 16 * (HD + 2), nch_max, c, (int)blockIdx.y, q_lo_off);
+    float* ps = part + (size_t)s * H * nch_max * 16 * (HD + 2);
+    attn_partial_mfma_body<HD, MULTI>(reinterpret_cast<const float*>(qs), kc + so, vc + so, m, pos0, H, KH, max_ctx, scale, ps, nch_max, c,
+                                      (int)blockIdx.y, q_lo_off, cpw, (int)blockIdx.x);
 }
 
 // grid (H, R), block HD
 template <int HD>
 __global__ void attn_combine_seg_kernel(const float* __restrict__ part, int nch_max, int H, float* __restrict__ out, int split,
-                                        Segs sg) {
+                                        Segs sg, int cpw) {
     const int r = blockIdx.y, s = r / sg.ms, j = min(r - s * sg.ms, sg.m[s] - 1);
-    const int nch = (sg.pos0[s] + sg.m[s] + ATT_CH - 1) / ATT_CH;
+    const int nch = ((sg.pos0[s] + sg.m[s] + ATT_CH - 1) / ATT_CH + cpw - 1) / cpw;    // records: one per cpw chunks
     attn_combine_body<HD>(part + (size_t)s * H * nch_max * 16 * (HD + 2), nch, nch_max, H, out, split, (int)blockIdx.x, j, r,
                           (size_t)gridDim.y * H * HD);
 }

@@ -1161,11 +1161,14 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
 // Output layout and the combine kernel are shared with the generic kernel above.
 
 // q_lo_off: distance (elements) from the hi array of q to its lo array (rows of the whole block x H x HD).
-template <int HD>
+// MULTI: the workgroup walks cpw consecutive chunks starting at chunk c and keeps a running (max, sum, O) per row
+// (each new chunk rescales what is there by exp(old max - new max)); it writes one record, number rec of head h,
+// so the records written and merged later shrink by the factor cpw.  Without MULTI: one chunk, record c.
+template <int HD, bool MULTI = false>
 __device__ __forceinline__ void attn_partial_mfma_body(const float* __restrict__ q, const bf16_t* __restrict__ kc,
                                                        const bf16_t* __restrict__ vc, int m, int pos0, int H, int KH,
                                                        int max_ctx, float scale, float* __restrict__ part, int nchunks, int c,
-                                                       int h, size_t q_lo_off) {
+                                                       int h, size_t q_lo_off, int cpw = 1, int rec = 0) {
     constexpr int RS = HD + 8;                 // padded LDS row stride of the V chunk (elements)
     constexpr int VPR = HD / 8;                // 16-byte pieces per row
     constexpr int PS = ATT_CH + 8;             // padded row stride of P (elements)
@@ -1178,22 +1181,12 @@ __device__ __forceinline__ void attn_partial_mfma_body(const float* __restrict__
 
     const int kh = h / (H / KH);
     const int L = pos0 + m;
-    const int p0 = c * ATT_CH;
-    const int np = min(ATT_CH, L - p0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row = lane & 15, g = lane >> 4;
     const bool rowok = row < m;
+    constexpr int VIT = ATT_CH * VPR / 256;    // 16-byte pieces of a V chunk per thread
+    constexpr int NTW = (NT + 3) / 4;          // head-dim tiles per wavefront
 
-    // ---- issue the V chunk loads first (consumed last), rows beyond the ragged end are zero
-    const bf16_t* vbase = vc + ((size_t)kh * max_ctx + p0) * HD;
-    constexpr int VIT = ATT_CH * VPR / 256;    // 16-byte pieces per thread
-    uint4 vreg[VIT];
-#pragma unroll
-    for (int it = 0; it < VIT; ++it) {
-        const int idx = tid + it * 256;
-        const int p = idx / VPR, v = idx - p * VPR;
-        vreg[it] = (p < np) ? *reinterpret_cast<const uint4*>(vbase + (size_t)p * HD + v * 8) : make_uint4(0, 0, 0, 0);
-    }
     // ---- q fragments (B operand): q[row][32 kc + 8 g .. +8], already split into two bf16 terms by rope_kv_kernel
     uint4 qh[KC], ql[KC];
 #pragma unroll
@@ -1206,93 +1199,142 @@ __device__ __forceinline__ void attn_partial_mfma_body(const float* __restrict__
             ql[k] = *reinterpret_cast<const uint4*>(src + q_lo_off);
         }
     }
-    // ---- scores of this wavefront's 32 positions: two 16-position tiles
     const bf16_t* kbase = kc + (size_t)kh * max_ctx * HD;
-    f32x4 sacc[2];
+    // running state of this lane's query row (MULTI): maximum, sum, and this wavefront's O^T tiles
+    float run_max = -INFINITY, run_sum = 0.f;
+    f32x4 orun[NTW];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        const int pl = wave * 32 + t * 16 + row;                       // this lane's K row within the chunk
-        const int pg = min(p0 + pl, L - 1);                            // clamp: stays inside the valid cache
-        const u32x4* kp = reinterpret_cast<const u32x4*>(kbase + (size_t)pg * HD + g * 8);
-        u32x4 kf[KC];
+    for (int i = 0; i < NTW; ++i) orun[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int nloop = MULTI ? cpw : 1;
+    for (int ci = 0; ci < nloop; ++ci) {
+        const int p0 = (c + ci) * ATT_CH;
+        if (MULTI && p0 >= L) break;               // workgroup-uniform
+        const int np = min(ATT_CH, L - p0);
+        // ---- issue the V chunk loads first (consumed last), rows beyond the ragged end are zero
+        const bf16_t* vbase = vc + ((size_t)kh * max_ctx + p0) * HD;
+        uint4 vreg[VIT];
 #pragma unroll
-        for (int k = 0; k < KC; ++k) kf[k] = kp[k * 4];                // +32 elements = 4 x 16 bytes
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acl = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int k = 0; k < KC; ++k) {
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[k]), __builtin_bit_cast(bf16x8, qh[k]), acc, 0, 0, 0);
-            acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[k]), __builtin_bit_cast(bf16x8, ql[k]), acl, 0, 0, 0);
+        for (int it = 0; it < VIT; ++it) {
+            const int idx = tid + it * 256;
+            const int p = idx / VPR, v = idx - p * VPR;
+            vreg[it] = (p < np) ? *reinterpret_cast<const uint4*>(vbase + (size_t)p * HD + v * 8) : make_uint4(0, 0, 0, 0);
         }
-        sacc[t] = acc + acl;
-    }
-    // lane (g, row) holds positions wave*32 + t*16 + 4g + v of query row `row`
-    float sv[8];
-    float lmax = -INFINITY;
+        // ---- scores of this wavefront's 32 positions: two 16-position tiles
+        f32x4 sacc[2];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < 2; ++t) {
+            const int pl = wave * 32 + t * 16 + row;                       // this lane's K row within the chunk
+            const int pg = min(p0 + pl, L - 1);                            // clamp: stays inside the valid cache
+            const u32x4* kp = reinterpret_cast<const u32x4*>(kbase + (size_t)pg * HD + g * 8);
+            u32x4 kf[KC];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int pl = wave * 32 + t * 16 + g * 4 + v;
-            const bool ok = rowok && pl < np && (p0 + pl) <= pos0 + row;
-            const float x = ok ? sacc[t][v] * scale : -INFINITY;
-            sv[t * 4 + v] = x;
-            lmax = fmaxf(lmax, x);
+            for (int k = 0; k < KC; ++k) kf[k] = kp[k * 4];                // +32 elements = 4 x 16 bytes
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acl = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int k = 0; k < KC; ++k) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[k]), __builtin_bit_cast(bf16x8, qh[k]), acc, 0, 0, 0);
+                acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[k]), __builtin_bit_cast(bf16x8, ql[k]), acl, 0, 0, 0);
+            }
+            sacc[t] = acc + acl;
         }
-    lmax = fmaxf(lmax, __shfl_xor(lmax, 16, 64));
-    lmax = fmaxf(lmax, __shfl_xor(lmax, 32, 64));
-    if (g == 0) wmax[wave][row] = lmax;
-    // ---- stage V into LDS while the maxima settle
+        // lane (g, row) holds positions wave*32 + t*16 + 4g + v of query row `row`
+        float sv[8];
+        float lmax = -INFINITY;
 #pragma unroll
-    for (int it = 0; it < VIT; ++it) {
-        const int idx = tid + it * 256;
-        const int p = idx / VPR, v = idx - p * VPR;
-        *reinterpret_cast<uint4*>(vs + p * RS + v * 8) = vreg[it];
-    }
-    __syncthreads();
-    const float mx = fmaxf(fmaxf(wmax[0][row], wmax[1][row]), fmaxf(wmax[2][row], wmax[3][row]));
-    float lsum = 0.f;
-    bf16_t ph[8], pl8[8];
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const float e = (mx == -INFINITY) ? 0.f : expf(sv[i] - mx);   // expf(-inf) = 0 for masked positions
-        lsum += e;
-        ph[i] = f2bf(e);
-        pl8[i] = f2bf(e - bf2f(ph[i]));
-    }
-    lsum += __shfl_xor(lsum, 16, 64);
-    lsum += __shfl_xor(lsum, 32, 64);
-    if (g == 0) wsum[wave][row] = lsum;
+            for (int v = 0; v < 4; ++v) {
+                const int pl = wave * 32 + t * 16 + g * 4 + v;
+                const bool ok = rowok && pl < np && (p0 + pl) <= pos0 + row;
+                const float x = ok ? sacc[t][v] * scale : -INFINITY;
+                sv[t * 4 + v] = x;
+                lmax = fmaxf(lmax, x);
+            }
+        lmax = fmaxf(lmax, __shfl_xor(lmax, 16, 64));
+        lmax = fmaxf(lmax, __shfl_xor(lmax, 32, 64));
+        if (g == 0) wmax[wave][row] = lmax;
+        // ---- stage V into LDS while the maxima settle
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        const int pl = wave * 32 + t * 16 + g * 4;
-        *reinterpret_cast<uint2*>(phi + row * PS + pl) = make_uint2(pack_bf16x2(ph[t * 4], ph[t * 4 + 1]), pack_bf16x2(ph[t * 4 + 2], ph[t * 4 + 3]));
-        *reinterpret_cast<uint2*>(plo + row * PS + pl) = make_uint2(pack_bf16x2(pl8[t * 4], pl8[t * 4 + 1]), pack_bf16x2(pl8[t * 4 + 2], pl8[t * 4 + 3]));
-    }
-    __syncthreads();
-    // ---- O^T tiles: wavefront w takes head-dim tiles w, w+4, ..
-    float* dst = part + ((size_t)h * nchunks + c) * 16 * (HD + 2);
-#pragma unroll
-    for (int nt = wave; nt < NT; nt += 4) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acl = {0.f, 0.f, 0.f, 0.f};
-        const int col = nt * 16 + row;                                  // A operand row index i = lane % 16 -> head-dim column
-#pragma unroll
-        for (int k = 0; k < ATT_CH / 32; ++k) {
-            const bf16_t* vp = vs + (k * 32 + g * 8) * RS + col;
-            const uint4 a = make_uint4(pack_bf16x2(vp[0], vp[RS]), pack_bf16x2(vp[2 * RS], vp[3 * RS]),
-                                       pack_bf16x2(vp[4 * RS], vp[5 * RS]), pack_bf16x2(vp[6 * RS], vp[7 * RS]));
-            const uint4 bh = *reinterpret_cast<const uint4*>(phi + row * PS + k * 32 + g * 8);
-            const uint4 bl = *reinterpret_cast<const uint4*>(plo + row * PS + k * 32 + g * 8);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, bh), acc, 0, 0, 0);
-            acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, bl), acl, 0, 0, 0);
+        for (int it = 0; it < VIT; ++it) {
+            const int idx = tid + it * 256;
+            const int p = idx / VPR, v = idx - p * VPR;
+            *reinterpret_cast<uint4*>(vs + p * RS + v * 8) = vreg[it];
         }
-        if (rowok) {
-            float* o = dst + row * (HD + 2) + nt * 16 + g * 4;           // D[i = 4g + v][j = row]
-            o[0] = acc[0] + acl[0]; o[1] = acc[1] + acl[1]; o[2] = acc[2] + acl[2]; o[3] = acc[3] + acl[3];
+        __syncthreads();
+        const float cmx = fmaxf(fmaxf(wmax[0][row], wmax[1][row]), fmaxf(wmax[2][row], wmax[3][row]));
+        const float mx = MULTI ? fmaxf(run_max, cmx) : cmx;
+        float lsum = 0.f;
+        bf16_t ph[8], pl8[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float e = (mx == -INFINITY) ? 0.f : expf(sv[i] - mx);   // expf(-inf) = 0 for masked positions
+            lsum += e;
+            ph[i] = f2bf(e);
+            pl8[i] = f2bf(e - bf2f(ph[i]));
         }
-    }
-    if (tid < m) {
-        dst[tid * (HD + 2) + HD] = fmaxf(fmaxf(wmax[0][tid], wmax[1][tid]), fmaxf(wmax[2][tid], wmax[3][tid]));
-        dst[tid * (HD + 2) + HD + 1] = (wsum[0][tid] + wsum[1][tid]) + (wsum[2][tid] + wsum[3][tid]);
+        lsum += __shfl_xor(lsum, 16, 64);
+        lsum += __shfl_xor(lsum, 32, 64);
+        if (g == 0) wsum[wave][row] = lsum;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int pl = wave * 32 + t * 16 + g * 4;
+            *reinterpret_cast<uint2*>(phi + row * PS + pl) = make_uint2(pack_bf16x2(ph[t * 4], ph[t * 4 + 1]), pack_bf16x2(ph[t * 4 + 2], ph[t * 4 + 3]));
+            *reinterpret_cast<uint2*>(plo + row * PS + pl) = make_uint2(pack_bf16x2(pl8[t * 4], pl8[t * 4 + 1]), pack_bf16x2(pl8[t * 4 + 2], pl8[t * 4 + 3]));
+        }
+        __syncthreads();
+        // what the earlier chunks left is rescaled to the new maximum
+        const float alpha = (MULTI && run_max != -INFINITY) ? expf(run_max - mx) : 0.f;
+        // ---- O^T tiles: wavefront w takes head-dim tiles w, w+4, ..
+        float* dst = part + ((size_t)h * nchunks + (MULTI ? rec : c)) * 16 * (HD + 2);
+#pragma unroll
+        for (int ti = 0; ti < NTW; ++ti) {
+            const int nt = wave + 4 * ti;
+            if (nt < NT) {                                                  // wavefront-uniform
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acl = {0.f, 0.f, 0.f, 0.f};
+                const int col = nt * 16 + row;                              // A operand row index i = lane % 16 -> head-dim column
+#pragma unroll
+                for (int k = 0; k < ATT_CH / 32; ++k) {
+                    const bf16_t* vp = vs + (k * 32 + g * 8) * RS + col;
+                    const uint4 a = make_uint4(pack_bf16x2(vp[0], vp[RS]), pack_bf16x2(vp[2 * RS], vp[3 * RS]),
+                                               pack_bf16x2(vp[4 * RS], vp[5 * RS]), pack_bf16x2(vp[6 * RS], vp[7 * RS]));
+                    const uint4 bh = *reinterpret_cast<const uint4*>(phi + row * PS + k * 32 + g * 8);
+                    const uint4 bl = *reinterpret_cast<const uint4*>(plo + row * PS + k * 32 + g * 8);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, bh), acc, 0, 0, 0);
+                    acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, bl), acl, 0, 0, 0);
+                }
+                if constexpr (MULTI) {
+                    orun[ti] = orun[ti] * alpha + (acc + acl);
+                } else if (rowok) {
+                    float* o = dst + row * (HD + 2) + nt * 16 + g * 4;       // D[i = 4g + v][j = row]
+                    o[0] = acc[0] + acl[0]; o[1] = acc[1] + acl[1]; o[2] = acc[2] + acl[2]; o[3] = acc[3] + acl[3];
+                }
+            }
+        }
+        if constexpr (MULTI) {
+            run_sum = run_sum * alpha + ((wsum[0][row] + wsum[1][row]) + (wsum[2][row] + wsum[3][row]));
+            run_max = mx;
+            const bool last = ci + 1 == nloop || p0 + ATT_CH >= L;
+            if (!last) {
+                __syncthreads();                   // the next chunk overwrites vs, phi, plo, wmax and wsum
+            } else {
+#pragma unroll
+                for (int ti = 0; ti < NTW; ++ti) {
+                    const int nt = wave + 4 * ti;
+                    if (nt < NT && rowok) {
+                        float* o = dst + row * (HD + 2) + nt * 16 + g * 4;
+                        o[0] = orun[ti][0]; o[1] = orun[ti][1]; o[2] = orun[ti][2]; o[3] = orun[ti][3];
+                    }
+                }
+                if (tid < m) {                     // wavefront 0, g = 0: this lane's row is tid
+                    dst[tid * (HD + 2) + HD] = run_max;
+                    dst[tid * (HD + 2) + HD + 1] = run_sum;
+                }
+            }
+        } else if (tid < m) {
+            dst[tid * (HD + 2) + HD] = fmaxf(fmaxf(wmax[0][tid], wmax[1][tid]), fmaxf(wmax[2][tid], wmax[3][tid]));
+            dst[tid * (HD + 2) + HD + 1] = (wsum[0][tid] + wsum[1][tid]) + (wsum[2][tid] + wsum[3][tid]);
+        }
     }
 }
 

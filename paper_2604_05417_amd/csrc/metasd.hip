@@ -386,6 +386,7 @@ struct metasd_ctx {
     bool tlog = false;
     bool persistent = false;         // bf16 models run the one-launch forward (cooperative launch available)
     bool fullk = true;               // residual GEMMs whose input fits in LDS run without split-K (METASD_GEMM_FULLK=0: off)
+    int att_cpw = 0;                 // batched attention: chunks per workgroup, 0 = by the rule in attention_seg_hd (METASD_ATT_CPW=1..64 forces one)
     int rows_tpb = 0;                // many-row GEMM: tiles per workgroup, 0 = by the cost model (METASD_ROWS_TPB=4|6|8 forces one)
     bool fullk_roll = true;          // .. and larger inputs with rolling private staging (METASD_GEMM_ROLL=0: sibling reduction instead)
     bool gemm_reduce = true;         // bf16 models: residual GEMMs reduce their split-K partials themselves (METASD_GEMM_REDUCE=0: off)
@@ -1003,10 +1004,23 @@ int attention_seg_hd(metasd_ctx* c, const Model& M, int L, const Segs& sg) {
     const float scale = 1.0f / sqrtf((float)HD);
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_ATTN, 2.0 * d.n_kv_heads * kvpos * HD * sizeof(T) + (double)R * d.n_heads * HD * 4);
     hipEvent_t ea = pr ? pr->a : nullptr, eb = pr ? pr->b : nullptr;
+    int cpw = 1;                       // chunks per workgroup (bf16 MFMA kernel): fewer, larger records while the grid still fills the chip
     if constexpr (sizeof(T) == 2 && HD >= 64) {
-        hipExtLaunchKernelGGL((attn_partial_mfma_seg_kernel<HD>), dim3(nch_max, d.n_heads, sg.n), dim3(256), 0u, c->stream, ea, eb, 0u,
-                              (const float*)c->d_q(), kc, vc, seq_stride, sg, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale,
-                              c->d_apart(), nch_max, (size_t)R * d.n_heads * HD);
+        // Measured at 32 sequences x 4096 positions (7B shape, head_dim 128): 391 + 53 us (partial + merge) with one chunk per
+        // workgroup, 380 + 10 us with eight; with head_dim 64 the chunks are too small for the loop to pay (37 -> 51 us).
+        if (HD >= 128)
+            for (int t = 8; t >= 2 && cpw == 1; t /= 2)
+                if ((size_t)d.n_heads * sg.n * ((nch_max + t - 1) / t) >= (size_t)c->n_cu * 4) cpw = t;
+        if (c->att_cpw > 0) cpw = c->att_cpw;
+        const dim3 grid((nch_max + cpw - 1) / cpw, d.n_heads, sg.n);
+        if (cpw > 1)
+            hipExtLaunchKernelGGL((attn_partial_mfma_seg_kernel<HD, true>), grid, dim3(256), 0u, c->stream, ea, eb, 0u, (const float*)c->d_q(), kc,
+                                  vc, seq_stride, sg, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale, c->d_apart(), nch_max,
+                                  (size_t)R * d.n_heads * HD, cpw);
+        else
+            hipExtLaunchKernelGGL((attn_partial_mfma_seg_kernel<HD, false>), grid, dim3(256), 0u, c->stream, ea, eb, 0u, (const float*)c->d_q(), kc,
+                                  vc, seq_stride, sg, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale, c->d_apart(), nch_max,
+                                  (size_t)R * d.n_heads * HD, cpw);
     } else {
         hipExtLaunchKernelGGL((attn_partial_seg_kernel<T, HD>), dim3(nch_max, d.n_heads, sg.n), dim3(256), 0u, c->stream, ea, eb, 0u,
                               (const float*)c->d_q(), kc, vc, seq_stride, sg, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale,
@@ -1014,7 +1028,7 @@ int attention_seg_hd(metasd_ctx* c, const Model& M, int L, const Segs& sg) {
     }
     LAUNCH_CHECK(c, "attn_partial (segments)");
     hipLaunchKernelGGL((attn_combine_seg_kernel<HD>), dim3(d.n_heads, R), dim3(HD), 0, c->stream, c->d_apart(), nch_max, d.n_heads,
-                       (float*)c->d_ao(), sizeof(T) == 2 ? 1 : 0, sg);
+                       (float*)c->d_ao(), sizeof(T) == 2 ? 1 : 0, sg, cpw);
     LAUNCH_CHECK(c, "attn_combine (segments)");
     return 0;
 }
@@ -1394,6 +1408,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         if (const char* ev = getenv("METASD_GEMM_REDUCE")) c->gemm_reduce = ev[0] != '0';
         if (const char* ev = getenv("METASD_GEMM_FULLK")) c->fullk = ev[0] != '0';
         if (const char* ev = getenv("METASD_GEMM_ROLL")) c->fullk_roll = ev[0] != '0';
+        if (const char* ev = getenv("METASD_ATT_CPW")) { const int v = atoi(ev); c->att_cpw = (v >= 1 && v <= 64) ? v : 0; }
         if (const char* ev = getenv("METASD_ROWS_TPB")) { const int v = atoi(ev); c->rows_tpb = (v == 4 || v == 6 || v == 8) ? v : 0; }
         {
             const int roll_lds = (int)FULLK_LDS_MAX;

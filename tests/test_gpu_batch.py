@@ -156,6 +156,28 @@ def test_bf16_wide_blocks_other_tile_counts(tpb, monkeypatch):
     g.close()
 
 
+@pytest.mark.parametrize("i,cpw", [(2, 2), (1, 3), (0, 4)])
+def test_bf16_attention_several_chunks_per_workgroup(i, cpw, monkeypatch):
+    """The batched attention kernel walking several 128-position chunks per workgroup with a running softmax state
+    (used for large batches of long contexts; here forced at context creation): head_dim 128 / 32 / 64, prompts of
+    270, 150 and 45 tokens and shorter ones, so sequences end in different chunk groups and the last group is ragged."""
+    monkeypatch.setenv("METASD_ATT_CPW", str(cpw))
+    s = SMALL[i]
+    cfg = W.config4(n_layers=s["n_layers"], ctx=s["prompt"], n_new=64, K=2, d_model=s["d_model"], n_heads=s["n_heads"],
+                    d_ffn=s["d_ffn"], vocab=s["vocab"], dd_model=s["dd_model"], dn_heads=s["dn_heads"], dd_ffn=s["dd_ffn"])
+    cfg["gamma"] = s["gamma"]
+    cfg["max_ctx"] = s["prompt"] + 80
+    prompts = [W.prompt_tokens(max(2, s["prompt"] - 61 * b), s["vocab"], 70 + b) for b in range(4)]
+    g, seqs = batch_pair(cfg, 1.0, prompts, TOL)
+    bl = make_lockstep(g, cfg, seqs, prompts, 1.0, TOL)
+    for r in range(3):
+        bl.round()
+    for ls in bl.seqs:
+        st = ls.stats
+        assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+    g.close()
+
+
 def test_batch_limits_and_errors():
     cfg = W.config1()
     td, tw = cfg["target"]
