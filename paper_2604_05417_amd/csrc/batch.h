@@ -21,6 +21,18 @@ struct Segs {
 
 struct SeqTab { int v[MAX_SEGS]; };
 
+// Blocks whose segments run through different models of one shape (the drafter step of a batched round: every
+// sequence advances by one token in the drafter its bandit chose).  Segments are ordered by model, so the rows of a
+// model are contiguous: group g holds rows [r0[g], r0[g] + m[g]).  Kernels that touch weights or caches take one
+// pointer per segment (SegPtrs) or per group (RowGroups).
+constexpr int MAX_GROUPS = 8;
+struct SegPtrs { const void* p[MAX_SEGS]; };
+struct RowGroups {
+    int n;
+    int r0[MAX_GROUPS], m[MAX_GROUPS];
+    const bf16_t* W[MAX_GROUPS][3];
+};
+
 // Workgroup barrier that orders LDS accesses only (global loads stay in flight).
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
@@ -31,6 +43,23 @@ __global__ void embed_seg_kernel(const int32_t* __restrict__ hist, int max_ctx, 
     const int r = blockIdx.x, s = r / sg.ms, j = min(r - s * sg.ms, sg.m[s] - 1);
     const size_t t = (size_t)hist[(size_t)sg.seq[s] * max_ctx + sg.pos0[s] + j];
     for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)r * d + i] = El<T>::ld(E[t * d + i]);
+}
+
+// The same with one embedding table per segment.
+template <typename T>
+__global__ void embed_segp_kernel(const int32_t* __restrict__ hist, int max_ctx, SegPtrs E, int d, float* __restrict__ h, Segs sg) {
+    const int r = blockIdx.x, s = r / sg.ms, j = min(r - s * sg.ms, sg.m[s] - 1);
+    const size_t t = (size_t)hist[(size_t)sg.seq[s] * max_ctx + sg.pos0[s] + j];
+    const T* Es = static_cast<const T*>(E.p[s]);
+    for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)r * d + i] = El<T>::ld(Es[t * d + i]);
+}
+
+// add + RMSNorm with one gain vector per segment (row r belongs to segment r / ms).   grid (R), block 1024
+template <typename T>
+__global__ __launch_bounds__(1024) void addnorm_segp_kernel(float* __restrict__ h, const float* __restrict__ part, int nsplit,
+                                                            size_t sstride, int d, SegPtrs gain, int ms, float eps,
+                                                            float* __restrict__ xn, int split) {
+    addnorm_body<T>(h, part, nsplit, sstride, d, static_cast<const T*>(gain.p[blockIdx.x / ms]), eps, xn, split);
 }
 
 // Rotation table per block row: tab[r][i] = (cos, sin)(position of row r * theta^(-2i/hd)), in fp64.   grid (R), block hd/2
@@ -55,6 +84,19 @@ __global__ void rope_kv_seg_kernel(const float* __restrict__ part, int nsplit, s
     const size_t so = (size_t)sg.seq[s] * kv_seq_stride;
     rope_kv_body<T>(part, nsplit, sstride, N, sg.pos0[s] + min(j, sg.m[s] - 1), H, KH, hd, tab, q, kc + so, vc + so, max_ctx,
                     interleaved, q_split, nullptr, valid);
+}
+
+// The same with the cache planes of each segment given directly (kc.p[s], vc.p[s]: the planes of the segment's
+// sequence in its model, at the layer in hand).
+template <typename T>
+__global__ void rope_kv_segp_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int N, Segs sg, int H, int KH,
+                                    int hd, const double2* __restrict__ tab, float* __restrict__ q, SegPtrs kc, SegPtrs vc,
+                                    int max_ctx, int interleaved, int q_split) {
+    const int r = blockIdx.y, s = r / sg.ms, j = r - s * sg.ms;
+    const bool valid = j < sg.m[s];
+    rope_kv_body<T>(part, nsplit, sstride, N, sg.pos0[s] + min(j, sg.m[s] - 1), H, KH, hd, tab, q,
+                    static_cast<T*>(const_cast<void*>(kc.p[s])), static_cast<T*>(const_cast<void*>(vc.p[s])), max_ctx, interleaved,
+                    q_split, nullptr, valid);
 }
 
 // Attention partials per (chunk, head, segment); records of segment s start s * H * nch_max chunk records
@@ -84,6 +126,19 @@ __global__ __launch_bounds__(256, 3) void attn_partial_mfma_seg_kernel(const flo
     float* ps = part + (size_t)s * H * nch_max * 16 * (HD + 2);
     attn_partial_mfma_body<HD, MULTI>(reinterpret_cast<const float*>(qs), kc + so, vc + so, m, pos0, H, KH, max_ctx, scale, ps, nch_max, c,
                                       (int)blockIdx.y, q_lo_off, cpw, (int)blockIdx.x);
+}
+
+// One chunk per workgroup, cache planes per segment (see rope_kv_segp_kernel).   grid (nch_max, H, segments), block 256
+template <int HD>
+__global__ __launch_bounds__(256, 3) void attn_partial_mfma_segp_kernel(const float* __restrict__ q, SegPtrs kc, SegPtrs vc, Segs sg,
+                                                                         int H, int KH, int max_ctx, float scale,
+                                                                         float* __restrict__ part, int nch_max, size_t q_lo_off) {
+    const int s = blockIdx.z, m = sg.m[s], pos0 = sg.pos0[s], c = blockIdx.x;
+    if (c * ATT_CH >= pos0 + m) return;                 // workgroup-uniform
+    const bf16_t* qs = reinterpret_cast<const bf16_t*>(q) + (size_t)s * sg.ms * H * HD;
+    attn_partial_mfma_body<HD, false>(reinterpret_cast<const float*>(qs), static_cast<const bf16_t*>(kc.p[s]),
+                                      static_cast<const bf16_t*>(vc.p[s]), m, pos0, H, KH, max_ctx, scale,
+                                      part + (size_t)s * H * nch_max * 16 * (HD + 2), nch_max, c, (int)blockIdx.y, q_lo_off);
 }
 
 // grid (H, R), block HD
@@ -158,11 +213,10 @@ __global__ void commit_tokens_kernel(const int32_t* __restrict__ n_acc, const in
 // LO = false leaves out the low-order terms of the activations (plain bf16 activations).
 //   grid (ceil(ntiles / (2 TPQ)) * ksplit), block 512, dynamic LDS 2 * (LO ? 16 : 8) * (64 RBW + 1) * 16 bytes;  R <= 64 RBW.
 template <int RBW, int PD, bool LO, int TPQ = 4>
-__global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __restrict__ xh, size_t x_lo_off, int ldx, int R, int K,
-                                                             const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
-                                                             const bf16_t* __restrict__ W2, int t0, int t1, int ntiles,
-                                                             float* __restrict__ out, size_t out_sstride, int N, int ksplit,
-                                                             int cps) {
+__device__ __forceinline__ void gemm_bf16_rows_body(const bf16_t* __restrict__ xh, size_t x_lo_off, int ldx, int R, int K,
+                                                    const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
+                                                    const bf16_t* __restrict__ W2, int t0, int t1, int ntiles,
+                                                    float* __restrict__ out, size_t out_sstride, int N, int ksplit, int cps) {
     extern __shared__ uint4 lds[];                 // [2 buffers][NP pieces][LR rows]
     constexpr int R16 = 64 * RBW, LR = R16 + 1;
     constexpr int NP = LO ? 16 : 8;                // 16-byte pieces per row and stage: 8 hi (+ 8 lo)
@@ -297,6 +351,27 @@ __global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __res
                 }
         }
     }
+}
+
+template <int RBW, int PD, bool LO, int TPQ = 4>
+__global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __restrict__ xh, size_t x_lo_off, int ldx, int R, int K,
+                                                             const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
+                                                             const bf16_t* __restrict__ W2, int t0, int t1, int ntiles,
+                                                             float* __restrict__ out, size_t out_sstride, int N, int ksplit,
+                                                             int cps) {
+    gemm_bf16_rows_body<RBW, PD, LO, TPQ>(xh, x_lo_off, ldx, R, K, W0, W1, W2, t0, t1, ntiles, out, out_sstride, N, ksplit, cps);
+}
+
+// One launch for several row groups with weights of their own (same shapes): blockIdx.y is the group; its rows
+// [r0, r0 + m) of x are multiplied with its matrices into the same rows of out.  m <= 64 RBW per group.
+//   grid (ceil(ntiles / 8) * ksplit, groups), block 512, dynamic LDS as gemm_bf16_rows_kernel<RBW, ..>
+template <int RBW, int PD>
+__global__ __launch_bounds__(512) void gemm_bf16_rows_grouped_kernel(const bf16_t* __restrict__ xh, size_t x_lo_off, int ldx, int K,
+                                                                     int t0, int t1, int ntiles, float* __restrict__ out,
+                                                                     size_t out_sstride, int N, int ksplit, int cps, RowGroups gg) {
+    const int g = blockIdx.y;
+    gemm_bf16_rows_body<RBW, PD, true, 4>(xh + (size_t)gg.r0[g] * ldx, x_lo_off, ldx, gg.m[g], K, gg.W[g][0], gg.W[g][1], gg.W[g][2], t0,
+                                        t1, ntiles, out + (size_t)gg.r0[g] * N, out_sstride, N, ksplit, cps);
 }
 
 }  // namespace msd

@@ -140,9 +140,8 @@ __device__ __forceinline__ void store_split1(float* base, size_t n, size_t at, f
 // split != 0: xn is written as two bf16 arrays (see store_split4), the form the bf16 GEMM stages.
 
 template <typename T>
-__global__ __launch_bounds__(1024) void addnorm_kernel(float* __restrict__ h, const float* __restrict__ part, int nsplit,
-                                                       size_t sstride, int d, const T* __restrict__ gain, float eps,
-                                                       float* __restrict__ xn, int split) {
+__device__ __forceinline__ void addnorm_body(float* __restrict__ h, const float* __restrict__ part, int nsplit, size_t sstride, int d,
+                                             const T* __restrict__ gain, float eps, float* __restrict__ xn, int split) {
     __shared__ float red[16];
     constexpr int KEEP = 2;                 // float4 columns per thread kept in registers (d <= 8192); beyond that via memory
     const int r = blockIdx.x;
@@ -191,6 +190,13 @@ __global__ __launch_bounds__(1024) void addnorm_kernel(float* __restrict__ h, co
             else *reinterpret_cast<float4*>(xn + (size_t)r * d + i) = o;
         }
     }
+}
+
+template <typename T>
+__global__ __launch_bounds__(1024) void addnorm_kernel(float* __restrict__ h, const float* __restrict__ part, int nsplit,
+                                                       size_t sstride, int d, const T* __restrict__ gain, float eps,
+                                                       float* __restrict__ xn, int split) {
+    addnorm_body<T>(h, part, nsplit, sstride, d, gain, eps, xn, split);
 }
 
 // out[i] = sum_s part[s][i]                         (only for logits when the head GEMM is split)

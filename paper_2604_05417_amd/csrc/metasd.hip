@@ -386,6 +386,7 @@ struct metasd_ctx {
     bool tlog = false;
     bool persistent = false;         // bf16 models run the one-launch forward (cooperative launch available)
     bool fullk = true;               // residual GEMMs whose input fits in LDS run without split-K (METASD_GEMM_FULLK=0: off)
+    bool grouped_on = true;          // batched drafting: one forward per step for all arms (METASD_DRAFT_GROUPED=0: one per arm)
     int att_cpw = 0;                 // batched attention: chunks per workgroup, 0 = by the rule in attention_seg_hd (METASD_ATT_CPW=1..64 forces one)
     int rows_tpb = 0;                // many-row GEMM: tiles per workgroup, 0 = by the cost model (METASD_ROWS_TPB=4|6|8 forces one)
     bool fullk_roll = true;          // .. and larger inputs with rolling private staging (METASD_GEMM_ROLL=0: sibling reduction instead)
@@ -1113,6 +1114,154 @@ int forward_segs(metasd_ctx* c, Model& M, const Segs& sg, float* logits, int out
     return forward_segs_t<float>(c, M, sg, logits, out_seq_rows, out_row0, last_only);
 }
 
+// ---- one drafter step of a batched round as a single forward: every sequence advances by one token in the drafter
+// its bandit chose.  All drafters must have the same shape (bf16, head_dim >= 64); segments are ordered by arm, each
+// kernel that touches weights or caches takes them per segment / per group (25 launches per step instead of 25 per
+// arm in use - the draft phase of a batch is bound by the host's launch rate otherwise).
+
+bool same_shape(const metasd_model_desc& a, const metasd_model_desc& b) {
+    return a.n_layers == b.n_layers && a.d_model == b.d_model && a.n_heads == b.n_heads && a.n_kv_heads == b.n_kv_heads &&
+           a.d_ffn == b.d_ffn && a.vocab == b.vocab && a.act == b.act && a.dtype == b.dtype && a.rms_eps == b.rms_eps &&
+           a.rope_theta == b.rope_theta;
+}
+
+bool grouped_step_supported(const metasd_ctx* c) {
+    if (!c->grouped_on || c->cfg.K > MAX_GROUPS) return false;
+    const metasd_model_desc& d0 = c->drafters[0].d;
+    if (d0.dtype != METASD_BF16 || c->drafters[0].hd < 64) return false;
+    for (int a = 1; a < c->cfg.K; ++a)
+        if (!same_shape(d0, c->drafters[a].d)) return false;
+    return true;
+}
+
+template <int RBW>
+int launch_gemm_rows_grouped(metasd_ctx* c, const void* x, int ldx, int R, int K, const RowGroups& gg, int n0, int n1, int N, const Split& s,
+                             metasd_ctx::ProfRec* pr) {
+    const size_t lds = (size_t)2 * 16 * (64 * RBW + 1) * 16;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)gemm_bf16_rows_grouped_kernel<RBW, ROWS_PD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return c->fail(METASD_E_HIP, "gemm_bf16_rows_grouped_kernel: cannot reserve %zu bytes of LDS", lds);
+        attr_set = true;
+    }
+    const int ntiles = N / 16, groups = (ntiles + 7) / 8;
+    hipExtLaunchKernelGGL((gemm_bf16_rows_grouped_kernel<RBW, ROWS_PD>), dim3(groups * s.ksplit, gg.n), dim3(512), (uint32_t)lds, c->stream,
+                          pr ? pr->a : nullptr, pr ? pr->b : nullptr, 0u, (const bf16_t*)x, (size_t)R * ldx, ldx, K, n0 / 16, (n0 + n1) / 16,
+                          ntiles, c->d_part(), (size_t)R * N, N, s.ksplit, s.cps, gg);
+    LAUNCH_CHECK(c, "gemm_bf16_rows (grouped)");
+    return 0;
+}
+
+// x: R rows in the two-bf16 form (hi, then lo R * ldx elements further); gg: the row groups and their matrices.
+int gemm_rows_grouped(metasd_ctx* c, const void* x, int ldx, int R, int K, const RowGroups& gg, int n0, int n1, int n2, int* nsplit_out) {
+    const int N = n0 + n1 + n2, ntiles = N / 16, kchunks = K / 32;
+    int mmax = 1;
+    for (int g = 0; g < gg.n; ++g) mmax = std::max(mmax, gg.m[g]);
+    const Split s = choose_split_rows(ntiles, kchunks, 64, 8);
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)gg.n * N * K * 2 + (double)R * K * 4 + (double)R * N * 4 * s.ksplit);
+    *nsplit_out = s.ksplit;
+    if (mmax <= 64) return launch_gemm_rows_grouped<1>(c, x, ldx, R, K, gg, n0, n1, N, s, pr);
+    if (mmax <= 128) return launch_gemm_rows_grouped<2>(c, x, ldx, R, K, gg, n0, n1, N, s, pr);
+    return launch_gemm_rows_grouped<4>(c, x, ldx, R, K, gg, n0, n1, N, s, pr);
+}
+
+// sg: the segments ordered by arm (ms <= 16 rows each, at most 256 rows per arm); arm[s]: the drafter of segment s.
+// The logits of each segment's last valid row go to logits[(seq * out_seq_rows + out_row0) * V].
+template <int HD>
+int forward_step_grouped(metasd_ctx* c, const Segs& sg, const int* arm, float* logits, int out_seq_rows, int out_row0) {
+    typedef bf16_t T;
+    const metasd_model_desc& d = c->drafters[arm[0]].d;
+    const int D = d.d_model, H = d.n_heads, KH = d.n_kv_heads, hd = HD, F = d.d_ffn, V = d.vocab;
+    const int DQ = H * hd, DKV = KH * hd, NQKV = DQ + 2 * DKV;
+    const int R = sg.n * sg.ms;
+    hipStream_t st = c->stream;
+    float* h = c->d_h();
+    float* xn = (float*)c->d_xn();
+    float* part = c->d_part();
+    int ns = 0, rc;
+    const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
+    const size_t seq_stride = (size_t)d.n_layers * 2 * plane;
+    // groups of consecutive segments with one arm
+    RowGroups gg{};
+    for (int s0 = 0; s0 < sg.n;) {
+        int s1 = s0;
+        while (s1 < sg.n && arm[s1] == arm[s0]) ++s1;
+        gg.r0[gg.n] = s0 * sg.ms; gg.m[gg.n] = (s1 - s0) * sg.ms; ++gg.n;
+        s0 = s1;
+    }
+    auto seg_ptrs = [&](auto&& of_model) {
+        SegPtrs p{};
+        for (int s = 0; s < sg.n; ++s) p.p[s] = of_model(c->drafters[arm[s]], s);
+        return p;
+    };
+    auto weights = [&](int L, int i0, int i1, int i2) {
+        RowGroups g = gg;
+        for (int q = 0; q < g.n; ++q) {
+            const Model& M = c->drafters[arm[g.r0[q] / sg.ms]];
+            g.W[q][0] = (const bf16_t*)(L < 0 ? M.lm_head() : M.layer_w(L, i0));
+            g.W[q][1] = i1 >= 0 ? (const bf16_t*)M.layer_w(L, i1) : nullptr;
+            g.W[q][2] = i2 >= 0 ? (const bf16_t*)M.layer_w(L, i2) : nullptr;
+        }
+        return g;
+    };
+    hipLaunchKernelGGL(embed_segp_kernel<T>, dim3(R), dim3(256), 0, st, (const int32_t*)c->d_hist(), c->cfg.max_ctx,
+                       seg_ptrs([](const Model& M, int) { return (const void*)M.w[0]; }), D, h, sg);
+    LAUNCH_CHECK(c, "embed (grouped)");
+    hipLaunchKernelGGL(rope_table_seg_kernel, dim3(R), dim3(hd / 2), 0, st, sg, hd, d.rope_theta, c->d_rope());
+    LAUNCH_CHECK(c, "rope_table (segments)");
+    int nch_max = 1;
+    double kvpos = 0.0;
+    for (int s = 0; s < sg.n; ++s) {
+        nch_max = std::max(nch_max, (sg.pos0[s] + sg.m[s] + ATT_CH - 1) / ATT_CH);
+        kvpos += (double)(sg.pos0[s] + sg.m[s]);
+    }
+    const float scale = 1.0f / sqrtf((float)HD);
+    for (int L = 0; L < d.n_layers; ++L) {
+        hipLaunchKernelGGL(addnorm_segp_kernel<T>, dim3(R), dim3(1024), 0, st, h, part, ns, (size_t)R * D, D,
+                           seg_ptrs([&](const Model& M, int) { return (const void*)M.layer_w(L, 0); }), sg.ms, d.rms_eps, xn, 1);
+        LAUNCH_CHECK(c, "addnorm (grouped)");
+        if ((rc = gemm_rows_grouped(c, xn, D, R, D, weights(L, 1, 2, 3), DQ, DKV, DKV, &ns))) return rc;
+        const SegPtrs kcs = seg_ptrs([&](const Model& M, int s) { return (const void*)((const T*)M.kv + (size_t)L * 2 * plane + (size_t)sg.seq[s] * seq_stride); });
+        const SegPtrs vcs = seg_ptrs([&](const Model& M, int s) { return (const void*)((const T*)M.kv + (size_t)L * 2 * plane + plane + (size_t)sg.seq[s] * seq_stride); });
+        hipLaunchKernelGGL(rope_kv_segp_kernel<T>, dim3(H + 2 * KH, R), dim3(64), 0, st, part, ns, (size_t)R * NQKV, NQKV, sg, H, KH, hd,
+                           (const double2*)c->d_rope(), (float*)c->d_q(), kcs, vcs, c->cfg.max_ctx, 1, 1);
+        LAUNCH_CHECK(c, "rope_kv (grouped)");
+        {
+            metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_ATTN, 2.0 * KH * kvpos * HD * sizeof(T) + (double)R * H * HD * 4);
+            hipExtLaunchKernelGGL((attn_partial_mfma_segp_kernel<HD>), dim3(nch_max, H, sg.n), dim3(256), 0u, st, pr ? pr->a : nullptr,
+                                  pr ? pr->b : nullptr, 0u, (const float*)c->d_q(), kcs, vcs, sg, H, KH, c->cfg.max_ctx, scale, c->d_apart(),
+                                  nch_max, (size_t)R * H * HD);
+            LAUNCH_CHECK(c, "attn_partial (grouped)");
+            hipLaunchKernelGGL((attn_combine_seg_kernel<HD>), dim3(H, R), dim3(HD), 0, st, c->d_apart(), nch_max, H, (float*)c->d_ao(), 1, sg, 1);
+            LAUNCH_CHECK(c, "attn_combine (segments)");
+        }
+        if ((rc = gemm_rows_grouped(c, c->d_ao(), DQ, R, DQ, weights(L, 4, -1, -1), D, 0, 0, &ns))) return rc;
+        hipLaunchKernelGGL(addnorm_segp_kernel<T>, dim3(R), dim3(1024), 0, st, h, part, ns, (size_t)R * D, D,
+                           seg_ptrs([&](const Model& M, int) { return (const void*)M.layer_w(L, 5); }), sg.ms, d.rms_eps, xn, 1);
+        LAUNCH_CHECK(c, "addnorm (grouped)");
+        if (d.act == METASD_SWIGLU) {
+            if ((rc = gemm_rows_grouped(c, xn, D, R, D, weights(L, 6, 7, -1), F, F, 0, &ns))) return rc;
+        } else {
+            if ((rc = gemm_rows_grouped(c, xn, D, R, D, weights(L, 7, -1, -1), F, 0, 0, &ns))) return rc;
+        }
+        const size_t nact = (size_t)R * F;
+        const int NF = (d.act == METASD_SWIGLU ? 2 : 1) * F;
+        hipLaunchKernelGGL(ffn_act_kernel, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)R * NF, R, F, d.act,
+                           (float*)c->d_act(), 1, (const float*)nullptr);
+        LAUNCH_CHECK(c, "ffn_act");
+        if ((rc = gemm_rows_grouped(c, c->d_act(), F, R, F, weights(L, 8, -1, -1), D, 0, 0, &ns))) return rc;
+    }
+    hipLaunchKernelGGL(addnorm_segp_kernel<T>, dim3(R), dim3(1024), 0, st, h, part, ns, (size_t)R * D, D,
+                       seg_ptrs([](const Model& M, int) { return (const void*)M.final_norm(); }), sg.ms, d.rms_eps, xn, 1);
+    LAUNCH_CHECK(c, "addnorm (grouped)");
+    if ((rc = gemm_rows_grouped(c, xn, D, R, D, weights(-1, 0, -1, -1), V, 0, 0, &ns))) return rc;
+    hipLaunchKernelGGL(sum_partials_seg_kernel, dim3((V + 255) / 256, R), dim3(256), 0, st, (const float*)part, ns, (size_t)R * V, V,
+                       logits, sg, out_seq_rows, out_row0, 1);
+    LAUNCH_CHECK(c, "sum_partials (segments)");
+    for (int s = 0; s < sg.n; ++s) c->drafters[arm[s]].kvl[sg.seq[s]] = sg.pos0[s] + sg.m[s];
+    return 0;
+}
+
 // Model M processes, for every listed sequence, the tokens at positions [M.kvl[seq], upto[seq]) in blocks of
 // at most 16 rows per sequence.  logits (optional): the logits of each sequence's last token go to
 // logits[(seq * out_seq_rows + out_row0) * V].
@@ -1187,7 +1336,41 @@ int draft_batch(metasd_ctx* c, const int32_t* k, int gamma) {
             return c->fail(METASD_E_OVERFLOW, "draft: sequence %d: l + gamma + 1 = %d exceeds max_ctx %d", b, c->sq[b].l + gamma + 1, c->cfg.max_ctx);
     }
     SeqTab at{};
+    const bool can_group = grouped_step_supported(c);
     for (int j = 0; j < gamma; ++j) {
+        // one forward for all arms when more than one arm is in use and every sequence has 1..16 tokens to process in its
+        // drafter (always so after the first step; in the first step unless a drafter was idle for many rounds)
+        bool grouped = can_group;
+        int arms_used = 0, pend_max = 0, rows_max = 0;
+        for (int a = 0; a < c->cfg.K && grouped; ++a) {
+            int nseq = 0;
+            for (int b = 0; b < B; ++b)
+                if (k[b] == a) {
+                    ++nseq;
+                    const int pend = c->sq[b].l + j - c->drafters[a].kvl[b];
+                    if (pend < 1 || pend > MAX_ROWS) grouped = false;
+                    pend_max = std::max(pend_max, pend);
+                }
+            arms_used += nseq > 0;
+            rows_max = std::max(rows_max, nseq);
+        }
+        if (grouped && arms_used > 1 && rows_max * pend_max <= 256) {
+            Segs sg{};
+            int arm[MAX_SEGS];
+            sg.ms = pend_max;
+            for (int a = 0; a < c->cfg.K; ++a)
+                for (int b = 0; b < B; ++b)
+                    if (k[b] == a) {
+                        const int s = sg.n++;
+                        sg.seq[s] = b; sg.pos0[s] = c->drafters[a].kvl[b]; sg.m[s] = c->sq[b].l + j - c->drafters[a].kvl[b];
+                        arm[s] = a;
+                    }
+            for (int s = 0; s < sg.n; ++s)
+                if (sg.pos0[s] + sg.m[s] > c->cfg.max_ctx) return c->fail(METASD_E_OVERFLOW, "draft: sequence %d exceeds max_ctx", sg.seq[s]);
+            const int rc = c->drafters[0].hd == 64 ? forward_step_grouped<64>(c, sg, arm, c->d_Q(), gamma, j)
+                                                    : forward_step_grouped<128>(c, sg, arm, c->d_Q(), gamma, j);
+            if (rc) return rc;
+        } else
         for (int a = 0; a < c->cfg.K; ++a) {
             std::vector<int> seqs, upto;
             for (int b = 0; b < B; ++b)
@@ -1408,6 +1591,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         if (const char* ev = getenv("METASD_GEMM_REDUCE")) c->gemm_reduce = ev[0] != '0';
         if (const char* ev = getenv("METASD_GEMM_FULLK")) c->fullk = ev[0] != '0';
         if (const char* ev = getenv("METASD_GEMM_ROLL")) c->fullk_roll = ev[0] != '0';
+        if (const char* ev = getenv("METASD_DRAFT_GROUPED")) c->grouped_on = ev[0] != '0';
         if (const char* ev = getenv("METASD_ATT_CPW")) { const int v = atoi(ev); c->att_cpw = (v >= 1 && v <= 64) ? v : 0; }
         if (const char* ev = getenv("METASD_ROWS_TPB")) { const int v = atoi(ev); c->rows_tpb = (v == 4 || v == 6 || v == 8) ? v : 0; }
         {

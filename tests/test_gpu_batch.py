@@ -178,6 +178,32 @@ def test_bf16_attention_several_chunks_per_workgroup(i, cpw, monkeypatch):
     g.close()
 
 
+@pytest.mark.parametrize("grouped", ["0", "1"])
+def test_bf16_mixed_arms_grouped_and_per_arm_drafting(grouped, monkeypatch):
+    """Sequences on different drafters in the same round: with drafters of one shape (bf16, head_dim >= 64) a draft step
+    is one forward for all arms (weights and caches picked per segment), otherwise - or with the switch off - one
+    forward per arm.  Both against the oracle, arms forced so that 2 and 3 arms share a round and drafters that sat
+    out a round have several tokens to catch up on."""
+    monkeypatch.setenv("METASD_DRAFT_GROUPED", grouped)
+    s = SMALL[0]
+    cfg = W.config4(n_layers=s["n_layers"], ctx=s["prompt"], n_new=64, K=3, d_model=s["d_model"], n_heads=s["n_heads"],
+                    d_ffn=s["d_ffn"], vocab=s["vocab"], dd_model=s["dd_model"], dn_heads=s["dn_heads"], dd_ffn=s["dd_ffn"])
+    cfg["gamma"] = 4
+    cfg["max_ctx"] = s["prompt"] + 80
+    B = 7
+    prompts = [W.prompt_tokens(max(2, s["prompt"] - 5 * b), s["vocab"], 90 + b) for b in range(B)]
+    g, seqs = batch_pair(cfg, 1.0, prompts, TOL)
+    bl = make_lockstep(g, cfg, seqs, prompts, 1.0, TOL)
+    plans = [[b % 3 for b in range(B)], [(b // 2) % 3 for b in range(B)], [b % 2 for b in range(B)], [2 - b % 3 for b in range(B)],
+             [(b + 1) % 3 for b in range(B)]]
+    for plan in plans:
+        bl.round(plan)
+    for ls in bl.seqs:
+        st = ls.stats
+        assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+    g.close()
+
+
 def test_batch_limits_and_errors():
     cfg = W.config1()
     td, tw = cfg["target"]
