@@ -27,7 +27,8 @@
  * leaves nothing tight to compare.
  *
  * Parity pins: see the header of oracle/__init__.py for which test pins which function.
- *   om_philox: pinned by the generator's published known-answer vectors and by structural and statistical tests.
+ *   om_philox: parity unpinned with respect to the published generator's known-answer vectors
+ *   (none are available offline); pinned only by structural and statistical tests.
  */
 #include <math.h>
 #include <stdint.h>
