@@ -137,7 +137,9 @@ def main():
         ev[i][3].record()
         g.bandit_update(k, n, gamma, bd)
     torch.cuda.synchronize()
-    phase = [float(np.median([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(K_steps)])) for j in range(3)]
+    phase_all = np.array([[ev[i][j].elapsed_time(ev[i][j + 1]) for j in range(3)] for i in range(K_steps)])
+    phase = [float(np.median(phase_all[:, j])) for j in range(3)]
+    phase_p10_p90 = [[float(np.percentile(phase_all[:, j], q)) for q in (10, 90)] for j in range(3)]
     # ---- per-launch pass: HIP events attached to every dispatch of the bandwidth-bound kernels
     # (begin/end of the kernel itself, on the library's stream)
     g.profile(4096 * 4)
@@ -171,13 +173,23 @@ def main():
     verify_bytes = n_params * 2 + kv_tok * l_mid + kv_tok * (gamma + 1) + (gamma + 1) * td["vocab"] * 4
     extra = {
         "verify_ms": phase[1], "draft_ms": phase[0], "accept_ms": phase[2],
+        "phase_ms_p10_p90": {"draft": phase_p10_p90[0], "verify": phase_p10_p90[1], "accept": phase_p10_p90[2]},
         "verify_hbm_frac": verify_bytes / (phase[1] * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "verify_algorithmic_GB": verify_bytes / 1e9,
+        "verify_positions_per_s": (gamma + 1) / (phase[1] * 1e-3),
         "gemm_kernel": rg, "attn_kernel": ra, "accept_kernel": rc, "draft_forward_kernel": rd,
         "mean_n_acc": float(np.mean(accs)), "alpha_mean_bd": float(np.mean(bds)),
         "arm_counts": [int(x) for x in np.bincount(arms, minlength=g.K)],
     }
 
+    try:
+        # the read rate a plain streaming kernel reaches on this machine, and the dominant kernel / the verify pass against it
+        ceil_gbs = read_ceiling(M, torch, dev)
+        extra["read_ceiling_GBs"] = ceil_gbs
+        extra["roofline_frac_of_read_ceiling"] = dom["GBs"] / ceil_gbs
+        extra["verify_frac_of_read_ceiling"] = verify_bytes / (phase[1] * 1e-3) / 1e9 / ceil_gbs
+    except Exception as e:
+        log(f"[bench] read ceiling measurement failed: {e!r}")
     try:
         extra["accept_c2"] = accept_c2_microbench(M, W, torch, dev)
         # the same kernel on four times as many rows: the fixed tail of the dependent chain amortises
@@ -297,6 +309,23 @@ def bench_c5(args):
     }
     g.close()
     print(json.dumps(out), flush=True)
+
+
+def read_ceiling(M, torch, dev, nbytes=1 << 30, iters=12):
+    """Read rate of a plain streaming-read kernel on this machine (GB/s): two 1 GiB buffers read alternately, so that no
+    cache holds the data; the figure the fractions of the 8 TB/s nominal peak can be set against."""
+    bufs = [torch.full((nbytes // 4,), float(i + 1), dtype=torch.float32, device=dev) for i in range(2)]
+    sink = torch.zeros(M.STREAM_READ_SINK_WORDS, dtype=torch.int32, device=dev)
+    for b in bufs:
+        M.stream_read(b, sink)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+    ev[0].record()
+    for i in range(iters):
+        M.stream_read(bufs[i & 1], sink)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(iters))
+    return nbytes / (ms[len(ms) // 2] * 1e-3) / 1e9
 
 
 def accept_c2_microbench(M, W, torch, dev, iters=200, rows=64, nsets=4):

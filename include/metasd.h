@@ -214,6 +214,13 @@ int32_t metasd_sample_logits(const float* logits, int32_t rows, int32_t V, float
 int32_t metasd_philox_words(uint64_t seed, uint32_t c0_start, int32_t n, uint32_t c1, uint32_t c2, uint32_t c3,
                             uint32_t* out, void* hip_stream);
 
+/* Measurement aid: one plain streaming read of src[0, bytes) (device, 16-byte aligned; bytes is rounded down to a
+ * multiple of 1024, at least 1024) on the given stream, so that a benchmark can state the read rate this machine reaches next to the
+ * nominal HBM peak.  sink: METASD_STREAM_READ_SINK_WORDS uint32 words of device memory that receive a digest of
+ * what was read (the caller's; contents are of no use).  Asynchronous; the caller times it with events. */
+#define METASD_STREAM_READ_SINK_WORDS 8192
+int32_t metasd_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream);
+
 /* ---- per-kernel timing (measurement aid) ------------------------------------------------------ */
 
 #define METASD_PROF_GEMM 0   /* bf16 weight-streaming GEMM launches */

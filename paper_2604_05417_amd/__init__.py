@@ -5,7 +5,7 @@ arguments and uses PyTorch to own device memory and the stream.  There is no CPU
 library is missing or no GPU is present the calls raise.
 """
 from .binding import (MetaSD, MetaSDError, accept_logits, lib_path, load_library, pack_weight, philox_words,
-                      sample_logits, EXPORTS)
+                      sample_logits, stream_read, STREAM_READ_SINK_WORDS, EXPORTS)
 
-__all__ = ["MetaSD", "MetaSDError", "accept_logits", "sample_logits", "philox_words", "pack_weight", "load_library",
+__all__ = ["MetaSD", "MetaSDError", "accept_logits", "sample_logits", "philox_words", "stream_read", "STREAM_READ_SINK_WORDS", "pack_weight", "load_library",
            "lib_path", "EXPORTS"]

@@ -14,7 +14,7 @@ MATRIX_SLOTS = (1, 2, 3, 4, 6, 7, 8)          # wq wk wv wo w_gate w_up w_down w
 EXPORTS = ["metasd_kv_bytes", "metasd_workspace_bytes", "metasd_pack_weight", "metasd_create", "metasd_destroy",
            "metasd_set_context", "metasd_swap_weight", "metasd_bandit_select", "metasd_bandit_update",
            "metasd_bandit_state", "metasd_draft", "metasd_verify", "metasd_accept", "metasd_accept_logits",
-           "metasd_sample_logits", "metasd_philox_words", "metasd_profile", "metasd_profile_read", "metasd_peek", "metasd_state", "metasd_state_seq", "metasd_last_error"]
+           "metasd_sample_logits", "metasd_philox_words", "metasd_stream_read", "metasd_profile", "metasd_profile_read", "metasd_peek", "metasd_state", "metasd_state_seq", "metasd_last_error"]
 
 
 class MetaSDError(RuntimeError):
@@ -70,6 +70,7 @@ def load_library():
         "metasd_accept_logits": [vp, vp, vp, i32, i32, i32, f32, u64, u32, u32, vp, vp, vp, vp, vp, vp],
         "metasd_sample_logits": [vp, i32, i32, f32, u64, u32, u32, u32, vp, vp],
         "metasd_philox_words": [u64, u32, i32, u32, u32, u32, vp, vp],
+        "metasd_stream_read": [vp, C.c_size_t, vp, vp],
         "metasd_profile": [vp, i32],
         "metasd_profile_read": [vp, i32, C.POINTER(f64), C.POINTER(C.c_int64), C.POINTER(f64)],
         "metasd_peek": [vp, i32, C.POINTER(vp), C.POINTER(sz)],
@@ -338,6 +339,18 @@ def sample_logits(logits: torch.Tensor, T: float, seed: int, rnd: int = 0, pos: 
     tok = torch.empty(rows, dtype=torch.int32, device=logits.device)
     _check(load_library().metasd_sample_logits(logits.data_ptr(), rows, V, T, seed, rnd, pos, seq0, tok.data_ptr(), _stream_ptr(stream)))
     return tok
+
+
+STREAM_READ_SINK_WORDS = 8192
+
+
+def stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    """One plain streaming read of `src` (CUDA, contiguous) on the current stream; `sink`: int32 tensor of at least
+    STREAM_READ_SINK_WORDS elements.  Asynchronous: time it with events."""
+    _require_gpu()
+    assert src.is_cuda and src.is_contiguous() and sink.is_cuda and sink.is_contiguous()
+    assert sink.numel() * sink.element_size() >= 4 * STREAM_READ_SINK_WORDS
+    _check(load_library().metasd_stream_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _stream_ptr()))
 
 
 def philox_words(seed: int, c0_start: int, n: int, c1: int, c2: int, c3: int, device="cuda:0") -> torch.Tensor:

@@ -281,6 +281,43 @@ __device__ __forceinline__ uint32_t pack_bf16x2(bf16_t lo, bf16_t hi) { return (
 //   PRO_COMBINE  x = attention output merged from the per-chunk partials.  Replaces attn_combine_kernel.
 enum { PRO_PLAIN = 0, PRO_NORM = 1, PRO_ACT = 2, PRO_COMBINE = 3 };
 
+// Plain streaming read (measurement aid: the read rate of the machine the benchmark runs on, next to the 8 TB/s
+// nominal peak).  The access pattern of the weight-streaming GEMMs without their arithmetic: every wavefront owns a
+// contiguous run of 1-KiB chunks (16 bytes per lane and load) and keeps 16 loads in flight; the workgroup leaves
+// one word per wavefront in sink so that the reads cannot be dropped.   grid (any), block 256
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ src, size_t nchunks, uint32_t* __restrict__ sink) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t nwaves = (size_t)gridDim.x * 4, gw = (size_t)blockIdx.x * 4 + wave;
+    const size_t per = (nchunks + nwaves - 1) / nwaves;
+    const size_t c0 = min(gw * per, nchunks), c1 = min(c0 + per, nchunks);
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    if (c1 > c0) {
+        const u32x4* wp = src + c0 * 64 + lane;
+        const size_t nc = c1 - c0;                 // every load is clamped into the run: the tail re-reads its last chunk
+        u32x4 a[8], b[8];
+        auto valid = [&](size_t c) -> uint32_t { return c < nc ? 0xffffffffu : 0u; };   // clamped re-reads do not count
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a[u] = __builtin_nontemporal_load(wp + min((size_t)u, nc - 1) * 64);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) b[u] = __builtin_nontemporal_load(wp + min((size_t)(8 + u), nc - 1) * 64);
+        for (size_t c = 16; c < nc + 16; c += 16) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc ^= a[u] & valid(c - 16 + u);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a[u] = __builtin_nontemporal_load(wp + min(c + u, nc - 1) * 64);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc ^= b[u] & valid(c - 8 + u);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) b[u] = __builtin_nontemporal_load(wp + min(c + 8 + u, nc - 1) * 64);
+        }
+        // the loads of the last turn lie past the run (c >= nc): nothing more to add
+    }
+    uint32_t w = (acc[0] ^ acc[1]) ^ (acc[2] ^ acc[3]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) w ^= __shfl_xor(w, o, 64);
+    if (lane == 0) sink[blockIdx.x * 4 + wave] = w;
+}
+
 struct GemmPro {
     const float* src;      // NORM: h_in [m][K];  ACT: partials [s][m][(1|2) K];  COMBINE: attention partials
                            // (PLAIN: sstride = offset in elements from the hi array x to the lo array; optional:

@@ -1825,6 +1825,17 @@ int32_t metasd_philox_words(uint64_t seed, uint32_t c0_start, int32_t n, uint32_
     return METASD_OK;
 }
 
+int32_t metasd_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream) {
+    if (!src || !sink || bytes < 1024 || ((uintptr_t)src & 15)) return fail_global(METASD_E_INVALID, "stream_read: bad argument");
+    int dev = 0, ncu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu < 1)
+        return fail_global(METASD_E_HIP, "stream_read: cannot query the device");
+    const int grid = std::min(ncu * 4, METASD_STREAM_READ_SINK_WORDS / 4);
+    hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream, (const u32x4*)src, bytes / 1024, sink);
+    if (hipGetLastError() != hipSuccess) return fail_global(METASD_E_HIP, "stream_read: launch failed");
+    return METASD_OK;
+}
+
 // ---- per-kernel timing
 
 int32_t metasd_profile(metasd_ctx* c, int32_t max_records) {

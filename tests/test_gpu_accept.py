@@ -108,6 +108,20 @@ def test_sampler_distribution_and_argmax():
     assert (M.sample_logits(L[:64], 0.0, seed=4).cpu().numpy() == 1).all()
 
 
+def test_stream_read_digest():
+    """The streaming-read measurement aid reads every 1-KiB chunk exactly once: the xor of its per-wavefront digests equals
+    the xor of all 32-bit words of the buffer (ragged: 1000 chunks + a tail below one chunk that is left out)."""
+    torch.manual_seed(5)
+    n_words = 1000 * 256 + 77
+    src = torch.randint(-2**31, 2**31 - 1, (n_words,), dtype=torch.int32, device="cuda")
+    sink = torch.zeros(M.STREAM_READ_SINK_WORDS, dtype=torch.int32, device="cuda")
+    M.stream_read(src, sink)
+    torch.cuda.synchronize()
+    want = np.bitwise_xor.reduce(src[:1000 * 256].cpu().numpy().view(np.uint32))
+    got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
+    assert int(got) == int(want)
+
+
 def test_philox_words_match_oracle():
     n = 1_000_000
     w = M.philox_words(12345678901234567, 4_294_000_000, n, 7, 3, 2).cpu().numpy().view(np.uint32)
