@@ -161,7 +161,7 @@ def main():
     rg, ra, rc, rf, rd = roof(pg), roof(pa), roof(pc), roof(pf), roof(pd)
     # dominant kernel: the one-launch verify forward (all 32 layers + LM head); when the library runs
     # the step-by-step kernels instead, the bf16 weight-streaming GEMM
-    dom, dom_name = (rf, "forward_persistent_kernel<128> (verify pass)") if rf else (rg, "gemm_bf16_kernel<*> + gemm_fullk_residual_kernel (weight-streaming GEMMs)")
+    dom, dom_name = (rf, "forward_persistent_kernel<128> (verify pass)") if rf else (rg, "gemm_bf16_kernel<*> + gemm_fullk_residual_kernel + gemm_fullk_roll_residual_kernel (weight-streaming GEMMs)")
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": dom["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": dom["GBs"] / HBM_PEAK_GBS, "traffic": read_traffic(),
                 "avg_launch_us": dom["avg_us"], "algorithmic_bytes_per_launch": dom["bytes_per_launch"],
