@@ -49,14 +49,17 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="target layers (32 = the 7B shape; fewer is NOT the benchmark)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rounds", type=int, default=8)
-    ap.add_argument("--workload", default="c4", choices=["c4", "c5"],
-                    help="c4 (default): the headline benchmark; c5: the batched configuration (32 sequences, gamma 7, KV context 4096), a side measurement")
+    ap.add_argument("--workload", default="c4", choices=["c4", "c5", "c2"],
+                    help="c4 (default): the headline benchmark; c5: the batched configuration (32 sequences, gamma 7, KV context 4096); "
+                         "c2: the accept kernel alone (64 rows x gamma 5 x vocab 32000); c5 and c2 are side measurements")
     ap.add_argument("--batch", type=int, default=32, help="sequences of the c5 workload")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (one process, no collectives); use --gpus 1")
     if args.workload == "c5":
         return bench_c5(args)
+    if args.workload == "c2":
+        return bench_c2(args)
 
     import numpy as np
     import torch
@@ -308,6 +311,25 @@ def bench_c5(args):
                    "gemm_kernel": roof(pg), "attn_kernel": roof(pa), "accept_kernel": roof(pc), "mean_n_acc": float(np.mean(accs))},
     }
     g.close()
+    print(json.dumps(out), flush=True)
+
+
+def bench_c2(args):
+    """The accept step alone on the C2 shape; a step = one call over 64 rows.  One JSON line; value = rows per second."""
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU available; the MetaSD library has no CPU path")
+    import paper_2604_05417_amd as M
+    import workloads as W
+    iters = max(args.steps, 1)
+    r = accept_c2_microbench(M, W, torch, "cuda", iters=iters, rows=64, nsets=4)
+    ceil_gbs = read_ceiling(M, torch, "cuda")
+    out = {"metric": "accept rows/sec @1 GPU (64 rows x gamma 5 x vocab 32000)", "value": 64 / (r["us_per_call"] * 1e-6), "unit": "rows/s",
+           "n_gpus": 1, "steps": iters, "warmup": 4, "ms_per_step": r["us_per_call"] * 1e-3, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic", "config": {"workload": r["workload"]},
+           "roofline": {"bound": "hbm", "kernel": "accept_split_kernel", "achieved": r["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": r["hbm_frac"], "traffic": None},
+           "cpu_baseline": None, "detail": {"accept_c2": r, "read_ceiling_GBs": ceil_gbs, "frac_of_read_ceiling": r["GBs"] / ceil_gbs}}
     print(json.dumps(out), flush=True)
 
 
