@@ -49,9 +49,10 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="target layers (32 = the 7B shape; fewer is NOT the benchmark)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rounds", type=int, default=8)
-    ap.add_argument("--workload", default="c4", choices=["c4", "c5", "c2"],
+    ap.add_argument("--workload", default="c4", choices=["c4", "c5", "c3", "c2"],
                     help="c4 (default): the headline benchmark; c5: the batched configuration (32 sequences, gamma 7, KV context 4096); "
-                         "c2: the accept kernel alone (64 rows x gamma 5 x vocab 32000); c5 and c2 are side measurements")
+                         "c3: the 1B-shape GQA target with four early-exit drafters, real 512-token prefill; "
+                         "c2: the accept kernel alone (64 rows x gamma 5 x vocab 32000); c5, c3 and c2 are side measurements")
     ap.add_argument("--batch", type=int, default=32, help="sequences of the c5 workload")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -60,6 +61,8 @@ def main():
         return bench_c5(args)
     if args.workload == "c2":
         return bench_c2(args)
+    if args.workload == "c3":
+        return bench_c3(args)
 
     import numpy as np
     import torch
@@ -310,6 +313,84 @@ def bench_c5(args):
                    "verify_gemm_TFLOPs": 2.0 * R * n_params / (phase[1] * 1e-3) / 1e12,
                    "gemm_kernel": roof(pg), "attn_kernel": roof(pa), "accept_kernel": roof(pc), "mean_n_acc": float(np.mean(accs))},
     }
+    g.close()
+    print(json.dumps(out), flush=True)
+
+
+def bench_c3(args):
+    """Configuration C3: 1B-shape bf16 target (16 layers, d 2048, 32 query / 8 KV heads, FFN 8192), K = 4 early-exit
+    drafters (target layers [0, l) + their own noisy head, own KV), gamma 5, T = 1; the 512-token prompt is prefilled by
+    the library (first draft / verify calls).  A step is one MetaSD round.  One JSON line."""
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU available; the MetaSD library has no CPU path")
+    import paper_2604_05417_amd as M
+    import workloads as W
+    dev = "cuda"
+    K_steps, Wm = args.steps, max(args.warmup, 5)                 # the warm-up covers the prefill and the bandit's sweep
+    cfg = W.config3(device=dev)
+    gamma = cfg["gamma"]
+    total = 3 * K_steps + Wm
+    cfg["max_ctx"] = len(cfg["prompt"]) + (gamma + 1) * total + 16
+    td, tw = cfg["target"]
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=gamma, max_ctx=cfg["max_ctx"], temperature=cfg["T"], seed=cfg["seed"],
+                 ucb_beta=cfg["beta"])
+    g.set_context(cfg["prompt"], kv_prefilled=False)
+
+    def one_round():
+        k = g.bandit_select()
+        g.draft(k, gamma)
+        g.verify(gamma)
+        n, tok, mask, bd = g.accept(gamma)
+        g.bandit_update(k, n, gamma, bd)
+        return k, n
+
+    for _ in range(Wm):
+        one_round()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    toks, accs, arms = 0, [], []
+    for _ in range(K_steps):
+        k, n = one_round()
+        toks += n + 1
+        accs.append(n); arms.append(k)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t1
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K_steps)]
+    for i in range(K_steps):
+        k = g.bandit_select()
+        ev[i][0].record(); g.draft(k, gamma)
+        ev[i][1].record(); g.verify(gamma)
+        ev[i][2].record(); n, tok, mask, bd = g.accept(gamma)
+        ev[i][3].record()
+        g.bandit_update(k, n, gamma, bd)
+    torch.cuda.synchronize()
+    phase = [float(np.median([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(K_steps)])) for j in range(3)]
+    g.profile(1 << 16)
+    for _ in range(K_steps):
+        one_round()
+    torch.cuda.synchronize()
+    pg, pa = g.profile_read("gemm"), g.profile_read("attn")
+    g.profile(0)
+    n_params = sum(t.numel() for i, t in enumerate(tw) if t is not None and i != 0)
+    kv_tok = 2 * td["n_layers"] * td["n_kv_heads"] * (td["d_model"] // td["n_heads"]) * 2
+    l_mid = len(cfg["prompt"]) + (Wm + 1.5 * K_steps) * (np.mean(accs) + 1)
+    verify_bytes = n_params * 2 + kv_tok * l_mid + kv_tok * (gamma + 1) + (gamma + 1) * td["vocab"] * 4
+    gbs = pg["bytes"] / (pg["ms"] * 1e-3) / 1e9 if pg["launches"] else 0.0
+    out = {"metric": "verified tokens/sec @1 GPU (1B-shape, gamma=5)", "value": toks / dt, "unit": "tokens/s", "n_gpus": 1, "steps": K_steps,
+           "warmup": Wm, "ms_per_step": dt / K_steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "C3: 1B-shape bf16 target (16 layers, d 2048, 32/8 heads, FFN 8192, vocab 32000), K=4 early-exit drafters "
+                                  "at layers 2/4/6/8, 512-token prompt prefilled on the GPU, gamma=5, T=1", "gamma": gamma, "batch": 1, "K": g.K},
+           "roofline": {"bound": "hbm", "kernel": "weight-streaming GEMMs (target and drafters)", "achieved": gbs, "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None},
+           "cpu_baseline": None,
+           "detail": {"draft_ms": phase[0], "verify_ms": phase[1], "accept_ms": phase[2],
+                      "verify_algorithmic_GB": verify_bytes / 1e9, "verify_hbm_frac": verify_bytes / (phase[1] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "gemm_launches": pg["launches"], "gemm_avg_us": pg["ms"] / max(pg["launches"], 1) * 1e3,
+                      "attn_avg_us": pa["ms"] / max(pa["launches"], 1) * 1e3, "mean_n_acc": float(np.mean(accs)),
+                      "arm_counts": [int(x) for x in np.bincount(arms, minlength=g.K)]}}
     g.close()
     print(json.dumps(out), flush=True)
 
