@@ -755,14 +755,18 @@ int forward_rows_residual(metasd_ctx* c, Model& M, int pos0, int m, float* logit
     return 0;
 }
 
-// Short blocks of narrow bf16 models (drafter steps): the same forward with the add+norm, the FFN
+// Short blocks of narrow bf16 models (drafter steps; d_model <= 2048, METASD_FUSE_DMAX): the same forward with the add+norm, the FFN
 // activation and the attention combine folded into the prologue of the GEMM that consumes them -
 // 6 launches per layer instead of 10.  The residual stream and the partials ping-pong between two
 // buffers, because a GEMM's workgroups read the old ones while others already write the new ones.
 int fused_max_rows() { static const int v = std::max(1, std::min(env_int("METASD_FUSE_ROWS", 4), 8)); return v; }
 bool fused_small_ok(const Model& M, int m) {
     const metasd_model_desc& d = M.d;
-    return d.dtype == METASD_BF16 && m <= fused_max_rows() && d.d_model <= 1024 && d.d_ffn <= 4096 && M.hd >= 64;
+    static const int dmax = env_int("METASD_FUSE_DMAX", 2048);
+    // the add+norm prologue keeps the block's residual rows in LDS (m * d_model floats) beside the staged activations:
+    // within the 64 KiB a kernel gets without asking for more
+    return d.dtype == METASD_BF16 && m <= fused_max_rows() && d.d_model <= dmax && d.d_ffn <= 4 * dmax && M.hd >= 64 &&
+           (size_t)m * d.d_model * 4 <= 40 * 1024;
 }
 
 int forward_rows_fused(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int first_row) {
