@@ -405,12 +405,32 @@ def bench_c2(args):
     iters = max(args.steps, 1)
     r = accept_c2_microbench(M, W, torch, "cuda", iters=iters, rows=64, nsets=4)
     ceil_gbs = read_ceiling(M, torch, "cuda")
+    cpu = None
+    if not args.no_cpu_baseline:
+        try:                                         # the oracle's accept step on one of the input sets, same host
+            import numpy as np
+            import oracle
+            c = W.config2(1.0, rows=64, device="cuda", variant=0)
+            Ph, Qh = c["P"].cpu().numpy(), c["Q"].cpu().numpy()
+            rows, gamma, V = Qh.shape
+            d = np.stack([oracle.sample_batch(Qh[:, j], 1.0, oracle.uniform_batch(c["seed"], 0, rows, 0, j, 2)) for j in range(gamma)], 1).astype(np.int32)
+            ua = np.stack([oracle.uniform_batch(c["seed"], 0, rows, 0, j, 0) for j in range(gamma)], 1)
+            ur = oracle.uniform_batch(c["seed"], 0, rows, 0, 0, 1)
+            oracle.accept_batch(Ph, Qh, d, 1.0, ua, ur)
+            reps, t1 = 5, time.perf_counter()
+            for _ in range(reps):
+                oracle.accept_batch(Ph, Qh, d, 1.0, ua, ur)
+            dt = (time.perf_counter() - t1) / reps
+            cpu = {"value": rows / dt, "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
+                   "sample": f"the oracle's accept step on one C2 input set (64 rows), mean of {reps} calls: {dt * 1e3:.1f} ms per call"}
+        except Exception as e:
+            log(f"[bench c2] cpu_baseline failed: {e!r}")
     out = {"metric": "accept rows/sec @1 GPU (64 rows x gamma 5 x vocab 32000)", "value": 64 / (r["us_per_call"] * 1e-6), "unit": "rows/s",
            "n_gpus": 1, "steps": iters, "warmup": 4, "ms_per_step": r["us_per_call"] * 1e-3, "higher_is_better": True, "scaling": "weak",
            "vs_baseline": None, "dtype": "f32", "data": "synthetic", "config": {"workload": r["workload"]},
            "roofline": {"bound": "hbm", "kernel": "accept_split_kernel", "achieved": r["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": r["hbm_frac"], "traffic": None},
-           "cpu_baseline": None, "detail": {"accept_c2": r, "read_ceiling_GBs": ceil_gbs, "frac_of_read_ceiling": r["GBs"] / ceil_gbs}}
+           "cpu_baseline": cpu, "detail": {"accept_c2": r, "read_ceiling_GBs": ceil_gbs, "frac_of_read_ceiling": r["GBs"] / ceil_gbs}}
     print(json.dumps(out), flush=True)
 
 
