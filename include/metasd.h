@@ -20,7 +20,8 @@
  *   - A context holds config.batch independent sequences (1..METASD_MAX_BATCH), each with its own
  *     token history, KV caches and bandit; they advance in lock-step, one round per
  *     draft / verify / accept call: every sequence drafts with its own arm (sequences that share
- *     an arm share that drafter's forward pass), one verification block holds all
+ *     an arm share that drafter's forward pass; drafters of one shape - bf16, head_dim >= 64 - share one
+ *     forward pass per step across arms, with the same results), one verification block holds all
  *     batch x (gamma + 1) rows, one accept launch tests them all.  Sequence b uses Philox sequence
  *     id b.  batch == 1 runs the single-sequence kernels; metasd_accept_logits and
  *     metasd_sample_logits take any number of rows.
