@@ -132,14 +132,16 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
 int32_t metasd_destroy(metasd_ctx*);
 
 /* Start a new query for sequence seq (Alg. 1 input "initial prompt x^{1:l}"): upload n >= 1 prompt
- * tokens (host) and reset that sequence's bandit (the bandit is re-initialised for every query).
- * The round counter - shared by the sequences of a batch, it is the round word of every Philox
- * counter - restarts when sequence 0 is set; a round can be drafted once every sequence has a context.
+ * tokens (host) and reset that sequence's bandit (the bandit is re-initialised for every query) and its
+ * round counter (the round word of its Philox counters: every sequence counts the rounds of its own
+ * query, so re-setting one sequence of a batch leaves the uniforms of the others untouched).  A round
+ * can be drafted once every sequence has a context; between metasd_draft and metasd_accept the call is
+ * refused (ORDER).
  * kv_prefilled == 0: the target prefills positions [0, n-1) now (asynchronously); drafters start
  *   empty and catch up the first time they are selected.
  * kv_prefilled != 0: the caller has already written the KV entries of positions [0, n-1) of
  *   the target and of every drafter (synthetic or externally computed context).
- * Errors: INVALID, OVERFLOW (n + gamma_max + 1 > max_ctx), HIP. */
+ * Errors: INVALID, OVERFLOW (n + gamma_max + 1 > max_ctx), ORDER, HIP. */
 int32_t metasd_set_context(metasd_ctx*, int32_t seq, const int32_t* tokens, int32_t n, int32_t kv_prefilled);
 
 /* Replace entry `index` of the weight table of model `model` (-1 = target, k = drafter k) with
@@ -184,7 +186,10 @@ int32_t metasd_verify(metasd_ctx*, int32_t gamma);
  * n < gamma, else from p_gamma (greedy: accept iff d_j == argmax, emit argmax).  Synchronises,
  * then commits: history, KV lengths, round counter.  Outputs are host arrays of `batch` entries
  * (mask_out: bit j = raw test j; bd_out: mean over j of sum_v min(p_j, q_j)); any may be NULL.
- * Errors: INVALID, ORDER (verify not done), HIP. */
+ * If the workgroups of a position fail to meet within their bounded wait the step is taken again with
+ * one workgroup per position before anything is committed (counted by metasd_accept_fallbacks).
+ * Errors: INVALID, ORDER (verify not done), HIP (a split-K reduction of the forward passes timed out:
+ * the round's state is lost, call metasd_set_context for every sequence to start over). */
 int32_t metasd_accept(metasd_ctx*, int32_t gamma, int32_t* n_acc_out, int32_t* token_out, uint32_t* mask_out,
                       double* bd_out);
 
@@ -215,23 +220,23 @@ int32_t metasd_sample_logits(const float* logits, int32_t rows, int32_t V, float
 int32_t metasd_philox_words(uint64_t seed, uint32_t c0_start, int32_t n, uint32_t c1, uint32_t c2, uint32_t c3,
                             uint32_t* out, void* hip_stream);
 
-/* Measurement aid: one plain streaming read of src[0, bytes) (device, 16-byte aligned; bytes is rounded down to a
+/* ---- measurement aids: not part of the method's boundary (no step of Alg. 1-3 needs them); benchmarks use them to
+ * state achieved bandwidth per kernel next to what the machine reaches on a plain read ------------------------- */
+
+/* One plain streaming read of src[0, bytes) (device, 16-byte aligned; bytes is rounded down to a
  * multiple of 1024, at least 1024) on the given stream, so that a benchmark can state the read rate this machine reaches next to the
  * nominal HBM peak.  sink: METASD_STREAM_READ_SINK_WORDS uint32 words of device memory that receive a digest of
  * what was read (the caller's; contents are of no use).  Asynchronous; the caller times it with events. */
 #define METASD_STREAM_READ_SINK_WORDS 8192
 int32_t metasd_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream);
 
-/* ---- per-kernel timing (measurement aid) ------------------------------------------------------ */
+/* per-kernel timing */
 
 #define METASD_PROF_GEMM 0   /* bf16 weight-streaming GEMM launches */
 #define METASD_PROF_ATTN 1   /* KV-cache attention (partial) launches */
 #define METASD_PROF_ACCEPT 2 /* the per-position accept kernel of metasd_accept */
-#define METASD_PROF_FORWARD 3 /* one-launch block forwards of a bf16 target (opt-in path; all layers, optional LM head) */
-#define METASD_PROF_DRAFT_FORWARD 4 /* the same for bf16 drafters */
 /* max_records > 0: from now on every launch of the bandwidth-bound kernels carries a pair of HIP
- * events attached to the dispatch itself (begin and end of that kernel on the context's stream;
- * the cooperative one-launch forward is bracketed by two recorded events instead).  At most
+ * events attached to the dispatch itself (begin and end of that kernel on the context's stream).  At most
  * max_records launches are recorded; the event pool is created here, not in the hot path, and
  * the record count is reset.  0: stop recording. */
 int32_t metasd_profile(metasd_ctx*, int32_t max_records);
@@ -253,11 +258,16 @@ int32_t metasd_profile_read(metasd_ctx*, int32_t kind, double* ms_total, int64_t
 int32_t metasd_peek(metasd_ctx*, int32_t what, void** dev_ptr_out, size_t* bytes_out);
 
 /* Committed length l, number of positions in the KV cache of model (-1 target, k drafter),
- * completed rounds.  Any pointer may be NULL. */
+ * rounds completed since the sequence's context was set.  Any pointer may be NULL. */
 int32_t metasd_state(const metasd_ctx*, int32_t model, int32_t* l_out, int32_t* kv_len_out, int32_t* round_out);
 /* The same for sequence seq of a batch (metasd_state reports sequence 0). */
 int32_t metasd_state_seq(const metasd_ctx*, int32_t seq, int32_t model, int32_t* l_out, int32_t* kv_len_out,
                          int32_t* round_out);
+
+/* How many accept steps of this context were taken a second time with one workgroup per position because the
+ * workgroups that share a position did not meet within their bounded wait (see metasd_accept_logits; the
+ * result is the same, the step is slower).  Expected to stay 0. */
+int32_t metasd_accept_fallbacks(const metasd_ctx*, int64_t* count_out);
 
 /* Message of the last error on this context (ctx == NULL: of the last context-free call on
  * this thread).  Never NULL. */

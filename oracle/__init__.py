@@ -20,8 +20,9 @@ What pins each function (all in ``tests/test_oracle_*.py``, CPU only):
 * ``policies``    - discounted / sliding-window UCB, sequential halving, EXP3, uniform random (the
                     paper's appendix "Extensions"): hand-worked runs in ``tests/golden/policies_hand.txt``,
                     reductions to Alg. 2, EXP3 closed forms (``tests/test_oracle_policies.py``).
-* ``philox``      - parity unpinned against the published generator's known-answer vectors;
-                    structural and statistical tests only.
+* ``philox``      - word-for-word equality with rocRAND's Philox4x32-10 host generator for counters
+                    (c0, c1, 0, 0) under several keys (``tests/test_gpu_philox_pin.py``, needs a device for
+                    rocRAND's allocations); bijection / avalanche / moment tests on the CPU.
 """
 from __future__ import annotations
 

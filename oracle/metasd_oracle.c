@@ -27,8 +27,10 @@
  * leaves nothing tight to compare.
  *
  * Parity pins: see the header of oracle/__init__.py for which test pins which function.
- *   om_philox: parity unpinned with respect to the published generator's known-answer vectors
- *   (none are available offline); pinned only by structural and statistical tests.
+ *   om_philox: pinned word for word against rocRAND's Philox4x32-10 host generator (an implementation
+ *   neither side of this repository wrote) for counters (c0, c1, 0, 0) under several keys
+ *   (tests/test_gpu_philox_pin.py; it needs a machine with a GPU because rocRAND's host generator
+ *   allocates through the HIP runtime), and by structural and statistical tests on the CPU.
  */
 #include <math.h>
 #include <stdint.h>

@@ -14,7 +14,7 @@ MATRIX_SLOTS = (1, 2, 3, 4, 6, 7, 8)          # wq wk wv wo w_gate w_up w_down w
 EXPORTS = ["metasd_kv_bytes", "metasd_workspace_bytes", "metasd_pack_weight", "metasd_create", "metasd_destroy",
            "metasd_set_context", "metasd_swap_weight", "metasd_bandit_select", "metasd_bandit_update",
            "metasd_bandit_state", "metasd_draft", "metasd_verify", "metasd_accept", "metasd_accept_logits",
-           "metasd_sample_logits", "metasd_philox_words", "metasd_stream_read", "metasd_profile", "metasd_profile_read", "metasd_peek", "metasd_state", "metasd_state_seq", "metasd_last_error"]
+           "metasd_sample_logits", "metasd_philox_words", "metasd_stream_read", "metasd_profile", "metasd_profile_read", "metasd_peek", "metasd_state", "metasd_state_seq", "metasd_accept_fallbacks", "metasd_last_error"]
 
 
 class MetaSDError(RuntimeError):
@@ -76,6 +76,7 @@ def load_library():
         "metasd_peek": [vp, i32, C.POINTER(vp), C.POINTER(sz)],
         "metasd_state": [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)],
         "metasd_state_seq": [vp, i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)],
+        "metasd_accept_fallbacks": [vp, C.POINTER(C.c_int64)],
     }
     for name, args in sig.items():
         fn = getattr(L, name)
@@ -291,13 +292,18 @@ class MetaSD:
 
     def profile_read(self, kind: str) -> dict:
         ms, n, by = C.c_double(0), C.c_int64(0), C.c_double(0)
-        _check(self.L.metasd_profile_read(self._h, {"gemm": 0, "attn": 1, "accept": 2, "forward": 3, "draft_forward": 4}[kind], C.byref(ms), C.byref(n), C.byref(by)), self._h)
+        _check(self.L.metasd_profile_read(self._h, {"gemm": 0, "attn": 1, "accept": 2}[kind], C.byref(ms), C.byref(n), C.byref(by)), self._h)
         return dict(ms=ms.value, launches=n.value, bytes=by.value)
 
     def state(self, model: int = -1, seq: int = 0):
         l, kv, r = C.c_int32(0), C.c_int32(0), C.c_int32(0)
         _check(self.L.metasd_state_seq(self._h, seq, model, C.byref(l), C.byref(kv), C.byref(r)))
         return int(l.value), int(kv.value), int(r.value)
+
+    def accept_fallbacks(self) -> int:
+        n = C.c_int64(0)
+        _check(self.L.metasd_accept_fallbacks(self._h, C.byref(n)))
+        return int(n.value)
 
     # ---- convenience: one full round (select -> draft -> verify -> accept -> update)
     def round(self, gamma: int, k: int | None = None):

@@ -6,7 +6,7 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc", "metasd.hip")
-DEPS = [SRC, os.path.join(HERE, "csrc", "kernels.h"), os.path.join(HERE, "csrc", "persist.h"), os.path.join(HERE, "csrc", "batch.h"),
+DEPS = [SRC, os.path.join(HERE, "csrc", "kernels.h"), os.path.join(HERE, "csrc", "batch.h"),
         os.path.join(HERE, "..", "include", "metasd.h")]
 LIB = os.path.join(HERE, "libmetasd.so")
 

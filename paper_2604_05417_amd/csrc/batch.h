@@ -20,6 +20,7 @@ struct Segs {
 };
 
 struct SeqTab { int v[MAX_SEGS]; };
+static_assert(MAX_SEGS == ROUND_TAB, "one round word per sequence of a batch");
 
 // Blocks whose segments run through different models of one shape (the drafter step of a batched round: every
 // sequence advances by one token in the drafter its bandit chose).  Segments are ordered by model, so the rows of a
@@ -167,7 +168,7 @@ __global__ void sum_partials_seg_kernel(const float* __restrict__ part, int nspl
 // Draft token of every sequence b from its row of logits (logits + b * row_stride):
 //   hist[b * max_ctx + at.v[b]] = token, draft[b * draft_stride] = token.   grid (batch), block 512
 __global__ __launch_bounds__(AK_NT) void sample_seq_kernel(const float* __restrict__ logits, size_t row_stride, int V, float T,
-                                                           uint64_t seed, uint32_t round, uint32_t pos,
+                                                           uint64_t seed, RoundTab rt, uint32_t pos,
                                                            int32_t* __restrict__ hist, int max_ctx, SeqTab at,
                                                            int32_t* __restrict__ draft, int draft_stride) {
     __shared__ AkShared sm;
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(AK_NT) void sample_seq_kernel(const float* __restri
     if (T <= 0.f) {
         token = ak_argmax(xp, sm, wave, lane);
     } else {
-        const float u = philox_uniform(seed, (uint32_t)b, round, pos, 2u);
+        const float u = philox_uniform(seed, (uint32_t)b, rt.v[b], pos, 2u);
         token = T == 1.0f ? sample_rows_body<true>(xp, V, T, u, sm, wave, lane) : sample_rows_body<false>(xp, V, T, u, sm, wave, lane);
     }
     if (threadIdx.x == 0) {

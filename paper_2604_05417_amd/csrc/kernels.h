@@ -99,6 +99,15 @@ __device__ __forceinline__ void philox4x32_10(uint64_t seed, uint32_t& c0, uint3
     }
 }
 
+// Round words of the Philox counters of a launch: one per row (n == number of rows <= ROUND_TAB: independent
+// sequences of a batch, each with its own round count) or the same for every row (n == 0: v[0]).
+constexpr int ROUND_TAB = 32;
+struct RoundTab {
+    int n;
+    uint32_t v[ROUND_TAB];
+};
+__device__ __forceinline__ uint32_t round_of(const RoundTab& rt, int row) { return rt.n ? rt.v[row] : rt.v[0]; }
+
 // uniform in [0,1): top 24 bits of word 0 at counter (seq, round, pos, stream)
 __device__ __forceinline__ float philox_uniform(uint64_t seed, uint32_t seq, uint32_t round, uint32_t pos, uint32_t stream) {
     uint32_t c0 = seq, c1 = round, c2 = pos, c3 = stream;
@@ -695,15 +704,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const float* __restrict_
                                 y.z += __uint_as_float((uint32_t)w[u][2]); y.w += __uint_as_float((uint32_t)w[u][3]);
                             }
                     }
-                    if (!ok) __hip_atomic_store(epi.abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    y.x += mine.x; y.y += mine.y; y.z += mine.z; y.w += mine.w;
-                    hv.x += y.x; hv.y += y.y; hv.z += y.z; hv.w += y.w;
-                    *reinterpret_cast<float4*>(epi.h + (size_t)row * N + col) = hv;
-                    const uint2 gn = *reinterpret_cast<const uint2*>(epi.gain + col);
-                    const float4 xg = make_float4(hv.x * bf2f((bf16_t)(gn.x & 0xffffu)), hv.y * bf2f((bf16_t)(gn.x >> 16)),
-                                                  hv.z * bf2f((bf16_t)(gn.y & 0xffffu)), hv.w * bf2f((bf16_t)(gn.y >> 16)));
-                    store_split4(epi.xsplit, (size_t)m * N, (size_t)row * N + col, xg);
-                    ss = hv.x * hv.x + hv.y * hv.y + hv.z * hv.z + hv.w * hv.w;
+                    if (!ok) {
+                        // a sibling never showed up: report it and leave the residual stream as it was (the host
+                        // fails the round at the next accept; nothing is added from words of another launch)
+                        __hip_atomic_store(epi.abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    } else {
+                        y.x += mine.x; y.y += mine.y; y.z += mine.z; y.w += mine.w;
+                        hv.x += y.x; hv.y += y.y; hv.z += y.z; hv.w += y.w;
+                        *reinterpret_cast<float4*>(epi.h + (size_t)row * N + col) = hv;
+                        const uint2 gn = *reinterpret_cast<const uint2*>(epi.gain + col);
+                        const float4 xg = make_float4(hv.x * bf2f((bf16_t)(gn.x & 0xffffu)), hv.y * bf2f((bf16_t)(gn.x >> 16)),
+                                                      hv.z * bf2f((bf16_t)(gn.y & 0xffffu)), hv.w * bf2f((bf16_t)(gn.y >> 16)));
+                        store_split4(epi.xsplit, (size_t)m * N, (size_t)row * N + col, xg);
+                        ss = hv.x * hv.x + hv.y * hv.y + hv.z * hv.z + hv.w * hv.w;
+                    }
                 }
                 ss += __shfl_xor(ss, 16, 64);
                 ss += __shfl_xor(ss, 32, 64);
@@ -1645,9 +1659,10 @@ __device__ int ak_argmax(const float (&x)[AK_CH][4], AkShared& sm, int wave, int
 template <bool UNIT_T>
 __device__ __forceinline__ void accept_rows_body(const float* __restrict__ P, const float* __restrict__ Q,
                                                  const int32_t* __restrict__ d, int gamma, int V, float T, uint64_t seed,
-                                                 uint32_t round, uint32_t seq0, int2* __restrict__ cand,
+                                                 const RoundTab& rt, uint32_t seq0, int2* __restrict__ cand,
                                                  double* __restrict__ bd, AkShared& sm) {
     const int j = blockIdx.x, b = blockIdx.y;
+    const uint32_t round = round_of(rt, b);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float* Prow = P + ((size_t)b * (gamma + 1) + j) * V;
     const bool has_q = j < gamma;
@@ -1744,11 +1759,11 @@ __device__ __forceinline__ void accept_rows_body(const float* __restrict__ P, co
 
 __global__ __launch_bounds__(AK_NT) void accept_rows_kernel(const float* __restrict__ P, const float* __restrict__ Q,
                                                             const int32_t* __restrict__ d, int gamma, int V, float T,
-                                                            uint64_t seed, uint32_t round, uint32_t seq0,
+                                                            uint64_t seed, RoundTab rt, uint32_t seq0,
                                                             int2* __restrict__ cand, double* __restrict__ bd) {
     __shared__ AkShared sm;
-    if (T == 1.0f) accept_rows_body<true>(P, Q, d, gamma, V, T, seed, round, seq0, cand, bd, sm);
-    else accept_rows_body<false>(P, Q, d, gamma, V, T, seed, round, seq0, cand, bd, sm);
+    if (T == 1.0f) accept_rows_body<true>(P, Q, d, gamma, V, T, seed, rt, seq0, cand, bd, sm);
+    else accept_rows_body<false>(P, Q, d, gamma, V, T, seed, rt, seq0, cand, bd, sm);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1929,10 +1944,11 @@ __device__ __forceinline__ bool as_search(const float (&w)[AS_CH][4], const doub
 template <bool UNIT_T>
 __device__ __forceinline__ void accept_split_item(const float* __restrict__ P, const float* __restrict__ Q,
                                                   const int32_t* __restrict__ d, int gamma, int V, float T, uint64_t seed,
-                                                  uint32_t round, uint32_t seq0, unsigned long long* __restrict__ cand,
+                                                  const RoundTab& rt, uint32_t seq0, unsigned long long* __restrict__ cand,
                                                   double* __restrict__ bd, unsigned long long* __restrict__ xchg, uint32_t epoch,
                                                   int spin_limit, AsShared& sm) {
     const int q = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
+    const uint32_t round = round_of(rt, b);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t item = (size_t)b * (gamma + 1) + j;
     unsigned long long* slots = xchg + item * (AS_Q * AS_WORDS);
@@ -2096,15 +2112,15 @@ __device__ __forceinline__ void accept_split_item(const float* __restrict__ P, c
 // xchg: AS_XCHG_BYTES per (row, position); both zero-filled before their first use.
 __global__ __launch_bounds__(AS_NT) void accept_split_kernel(const float* __restrict__ P, const float* __restrict__ Q,
                                                              const int32_t* __restrict__ d, int gamma, int V, float T,
-                                                             uint64_t seed, uint32_t round, uint32_t seq0,
+                                                             uint64_t seed, RoundTab rt, uint32_t seq0,
                                                              unsigned long long* __restrict__ cand, double* __restrict__ bd,
                                                              unsigned long long* __restrict__ xchg, uint32_t epoch, int spin_limit,
                                                              int32_t* __restrict__ n_acc, int32_t* __restrict__ token,
                                                              uint32_t* __restrict__ mask, int32_t* __restrict__ hist, int l) {
     __shared__ AsShared sm;
     if (threadIdx.x == 0) { sm.token = -1; sm.fail = 0; }
-    if (T == 1.0f) accept_split_item<true>(P, Q, d, gamma, V, T, seed, round, seq0, cand, bd, xchg, epoch, spin_limit, sm);
-    else accept_split_item<false>(P, Q, d, gamma, V, T, seed, round, seq0, cand, bd, xchg, epoch, spin_limit, sm);
+    if (T == 1.0f) accept_split_item<true>(P, Q, d, gamma, V, T, seed, rt, seq0, cand, bd, xchg, epoch, spin_limit, sm);
+    else accept_split_item<false>(P, Q, d, gamma, V, T, seed, rt, seq0, cand, bd, xchg, epoch, spin_limit, sm);
     // ---- per row: first failed test, emitted token, mask (one thread of the bonus position's first quarter)
     if (blockIdx.x == 0 && (int)blockIdx.y == gamma && threadIdx.x == 0) {
         const int b = blockIdx.z;

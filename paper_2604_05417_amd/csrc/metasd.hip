@@ -17,7 +17,6 @@
 #include <vector>
 
 #include "kernels.h"
-#include "persist.h"
 #include "batch.h"
 
 using namespace msd;
@@ -52,7 +51,7 @@ struct Model {
     void* kv = nullptr;
     int hd = 0;
     std::vector<int> kvl;   // positions valid in the KV cache, per sequence
-    const void** d_table = nullptr;   // device copy of w (persistent kernel)
+    const void** d_table = nullptr;   // device copy of w
     const void* layer_w(int L, int i) const { return w[1 + PER_LAYER * L + i]; }
     const void* final_norm() const { return w[1 + PER_LAYER * d.n_layers]; }
     const void* lm_head() const { return w[2 + PER_LAYER * d.n_layers]; }
@@ -66,16 +65,19 @@ struct Split {
 
 int env_int(const char* name, int dflt) { const char* e = getenv(name); return e ? atoi(e) : dflt; }
 // Launch epoch of tagged exchange words (see tw_put in kernels.h): unique per launch in this process, never 0.
+// Epochs 0 (a zero-filled buffer) and 1 (the accept flag the one-workgroup accept path leaves in the upper half of a
+// candidate word) are never handed out.
 uint32_t next_epoch() {
-    static std::atomic<uint32_t> e{0};
+    static std::atomic<uint32_t> e{1};
     uint32_t v = ++e;
-    if (v == 0) v = ++e;
+    while (v < 2) v = ++e;
     return v;
 }
-int ks_cap() { static const int v = std::max(1, std::min(env_int("METASD_GEMM_KSMAX", 8), 32)); return v; }
+constexpr int KS_CAP = 8;            // split-K siblings wanted for parallelism (LDS capacity can ask for more)
+constexpr int ks_cap() { return KS_CAP; }
 
 Split choose_split(int m, int ntiles, int kchunks) {
-    static const int target_units = env_int("METASD_GEMM_UNITS", 3072), align = std::max(1, env_int("METASD_GEMM_ALIGN", 8));
+    constexpr int target_units = 3072, align = 8;   // wavefront work units aimed for; slices are multiples of 8 chunks (whole load groups)
     const int cps_max = std::max(1, ((LDS_BUDGET / 32 / m) - 1) / 4);   // two bf16 terms per activation
     int want = target_units / ntiles;                             // aim for about 3072 wavefront work units, never fewer tiles' worth
     want = std::max(1, std::min(want, ks_cap()));
@@ -97,7 +99,6 @@ Split choose_split(int m, int ntiles, int kchunks) {
 // shapes at 256 rows a round costs about 0.9 / 0.75 / 0.6 us per 32-wide K chunk with 8 / 6 / 4 tiles (a fixed
 // part for staging the activations plus the multiplies), and the split-K partials are written and read once.
 Split choose_split_rows(int ntiles, int kchunks, int R, int forced_tpb) {
-    static const int forced = env_int("METASD_ROWS_KS", 0);
     int best = 1, best_tpb = 8;
     double best_cost = 1e30;
     for (int tpb = 8; tpb >= 4; tpb -= 2) {
@@ -111,7 +112,7 @@ Split choose_split_rows(int ntiles, int kchunks, int R, int forced_tpb) {
             if (cost < best_cost) { best_cost = cost; best = ks; best_tpb = tpb; }
         }
     }
-    int ks = forced > 0 ? std::min(forced, std::max(1, kchunks / 8)) : best;
+    int ks = best;
     int cps = ((kchunks + ks - 1) / ks + 3) / 4 * 4;
     ks = (kchunks + cps - 1) / cps;
     Split s;
@@ -138,6 +139,10 @@ const char* check_model(const metasd_model_desc& d, const char* who, char* buf, 
     return nullptr;
 }
 
+// Word the split-K siblings of a residual GEMM set when their bounded wait for each other runs out (read back with
+// the results of every accept).
+struct GridBar { int abort; int pad[3]; };
+
 // Workspace layout shared by metasd_workspace_bytes and metasd_create.
 struct Layout {
     size_t hist, h, h2, xn, part, part2, gx, ssq, inv, q, ao, act, apart, rope, P, Q, cand, bd, res, draft, bar, xchg, tables, table_stride, total;
@@ -145,8 +150,15 @@ struct Layout {
 
 Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const metasd_model_desc* dr) {
     int dmax = t.d_model, fmax = t.d_ffn, vmax = t.vocab, hmax = t.n_heads, hdmax = t.d_model / t.n_heads;
-    size_t partmax = 0;
+    size_t partmax = 0, gxmax = ALIGN;
     auto acc = [&](const metasd_model_desc& d) {
+        // sibling exchange of the residual GEMMs (N = d_model; K = attention width or d_ffn): ksplit - 1 published
+        // partial tiles of m rows, for the split choose_split really takes at every block height (LDS capacity
+        // can push it past ks_cap())
+        if (d.dtype == METASD_BF16)
+            for (int m = 1; m <= MAX_ROWS; ++m)
+                for (int K : {d.d_model, d.d_ffn})
+                    gxmax = std::max(gxmax, (size_t)(choose_split(m, d.d_model / 16, K / 32).ksplit - 1) * m * d.d_model * 8);
         dmax = std::max(dmax, d.d_model); fmax = std::max(fmax, d.d_ffn); vmax = std::max(vmax, d.vocab);
         hmax = std::max(hmax, d.n_heads); hdmax = std::max(hdmax, d.d_model / d.n_heads);
         const int hd = d.d_model / d.n_heads;
@@ -177,7 +189,7 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     L.xn = take(RM * dmax * 4);
     L.part = take(partmax);
     L.part2 = take(partmax);
-    L.gx = take((size_t)ks_cap() * MAX_ROWS * dmax * 8);          // tagged partial sums of the residual GEMMs
+    L.gx = take(gxmax);                                            // tagged partial sums of the residual GEMMs
     L.ssq = take((size_t)(dmax / 16 + 1) * 16 * 4);              // per tile group (or per tile) and row
     L.inv = take(64);
     L.q = take(RM * dmax * 4);
@@ -361,11 +373,11 @@ struct metasd_ctx {
         std::vector<int32_t> hist;   // host mirror of committed tokens
         int l = 0;                   // committed tokens
         int cur_k = -1;              // drafter of the running round
+        int round = 0;               // rounds completed since this sequence's context was set: the round word of its Philox counters
         bool ready = false;          // a context has been set
         Bandit bandit;
     };
     std::vector<SeqState> sq;        // one per sequence (cfg.batch)
-    int round = 0;                   // rounds completed since the contexts were set (all sequences advance together)
     int cur_gamma = 0;
     Phase phase = PH_NONE;
     // Pinned host mirror of the workspace span [lay.bd, lay.bar + sizeof(GridBar)): the BD terms, the result words
@@ -383,8 +395,6 @@ struct metasd_ctx {
     // optional per-launch timing of the three bandwidth-bound kernels (metasd_profile)
     struct ProfRec { hipEvent_t a, b; int kind; double bytes; };
     bool prof_on = false;
-    bool tlog = false;
-    bool persistent = false;         // bf16 models run the one-launch forward (cooperative launch available)
     bool fullk = true;               // residual GEMMs whose input fits in LDS run without split-K (METASD_GEMM_FULLK=0: off)
     bool grouped_on = true;          // batched drafting: one forward per step for all arms (METASD_DRAFT_GROUPED=0: one per arm)
     int att_cpw = 0;                 // batched attention: chunks per workgroup, 0 = by the rule in attention_seg_hd (METASD_ATT_CPW=1..64 forces one)
@@ -394,6 +404,7 @@ struct metasd_ctx {
     float cur_eps = 1e-5f;           // rms_eps of the model whose forward is being launched
     bool fuse_small = true;          // short blocks of narrow bf16 models use the GEMMs with fused prologues (METASD_FUSE_SMALL=0: off)
     int n_cu = 0;
+    int accept_fallbacks = 0;        // accept steps taken again with one workgroup per position after an exchange timeout
     std::vector<ProfRec> prof;       // event pool
     size_t prof_used = 0;
     // Next free record, or nullptr when profiling is off / the pool is used up.  The launcher hands
@@ -556,6 +567,8 @@ int gemm_residual(metasd_ctx* c, const void* x, int ldx, int m, int K, const voi
     }
     const Split s = choose_split(m, ntiles, kchunks);
     const int groups = (ntiles + s.tpb - 1) / s.tpb;
+    if ((size_t)(s.ksplit - 1) * m * N * 8 > c->lay.ssq - c->lay.gx)
+        return c->fail(METASD_E_WORKSPACE, "residual GEMM (m %d, K %d, N %d): %d split-K siblings exceed the exchange area of the workspace", m, K, N, s.ksplit);
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
     GemmPro plain{};
     plain.sstride = x_lo_off;
@@ -759,10 +772,10 @@ int forward_rows_residual(metasd_ctx* c, Model& M, int pos0, int m, float* logit
 // activation and the attention combine folded into the prologue of the GEMM that consumes them -
 // 6 launches per layer instead of 10.  The residual stream and the partials ping-pong between two
 // buffers, because a GEMM's workgroups read the old ones while others already write the new ones.
-int fused_max_rows() { static const int v = std::max(1, std::min(env_int("METASD_FUSE_ROWS", 4), 8)); return v; }
+constexpr int fused_max_rows() { return 4; }
 bool fused_small_ok(const Model& M, int m) {
     const metasd_model_desc& d = M.d;
-    static const int dmax = env_int("METASD_FUSE_DMAX", 2048);
+    constexpr int dmax = 2048;
     // the add+norm prologue keeps the block's residual rows in LDS (m * d_model floats) beside the staged activations:
     // within the 64 KiB a kernel gets without asking for more
     return d.dtype == METASD_BF16 && m <= fused_max_rows() && d.d_model <= dmax && d.d_ffn <= 4 * dmax && M.hd >= 64 &&
@@ -845,54 +858,9 @@ int forward_rows_fused(metasd_ctx* c, Model& M, int pos0, int m, float* logits, 
     return 0;
 }
 
-// ---- bf16 models: the whole block forward in one cooperative launch (see persist.h)
-
 int upload_table(metasd_ctx* c, Model& M) {
     HIP_TRY(c, hipMemcpyAsync((void*)M.d_table, M.w.data(), M.w.size() * sizeof(void*), hipMemcpyHostToDevice, c->stream));
     return 0;
-}
-
-template <int HD>
-int launch_persistent(metasd_ctx* c, FwdP& P) {
-    void* args[] = {(void*)&P};
-    hipError_t e = hipLaunchCooperativeKernel((const void*)forward_persistent_kernel<HD>, dim3(c->n_cu), dim3(PK_NT), args,
-                                              (unsigned)PK_LDS_BYTES, c->stream);
-    if (e != hipSuccess) return c->fail(METASD_E_HIP, "cooperative launch of the persistent forward: %s", hipGetErrorString(e));
-    return 0;
-}
-
-int forward_persistent(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int first_row) {
-    const metasd_model_desc& d = M.d;
-    FwdP P{};
-    P.n_layers = d.n_layers; P.D = d.d_model; P.H = d.n_heads; P.KH = d.n_kv_heads; P.hd = M.hd; P.F = d.d_ffn; P.V = d.vocab;
-    P.act = d.act; P.eps = d.rms_eps; P.theta = d.rope_theta;
-    P.w = (const void* const*)M.d_table;
-    P.kv = (bf16_t*)M.kv; P.max_ctx = c->cfg.max_ctx;
-    P.tok = c->d_hist() + pos0; P.m = m; P.pos0 = pos0;
-    P.h = c->d_h(); P.q = (float*)c->d_q(); P.ao = (float*)c->d_ao(); P.gu = (float*)c->d_act(); P.apart = c->d_apart();
-    P.logits = logits; P.first_row = first_row;
-    P.bar = c->d_bar(); P.spin_limit = 4000000;
-    // METASD_TLOG=1: workgroup 0 logs two timestamps per barrier into the (otherwise unused) partials buffer
-    P.tlog = (c->tlog && (size_t)(2048 + 512) * 8 <= c->lay.q - c->lay.part) ? (long long*)c->d_part() : nullptr;
-    if ((pos0 + m + ATT_CH - 1) / ATT_CH * (size_t)d.n_heads * 16 * (M.hd + 2) * 4 > c->lay.P - c->lay.apart)
-        return c->fail(METASD_E_INVALID, "attention partial buffer too small");
-    // algorithmic bytes of the launch: every weight once, the KV cache of [0, pos0 + m) once, the embedding rows
-    double bytes = 0.0;
-    {
-        const double D = d.d_model, F = d.d_ffn, DQ = (double)d.n_heads * M.hd, DKV = (double)d.n_kv_heads * M.hd;
-        const double per_layer = (D * (DQ + 2 * DKV) + DQ * D + (d.act == METASD_SWIGLU ? 3.0 : 2.0) * D * F + 2 * D) * 2;
-        bytes = d.n_layers * (per_layer + 2.0 * DKV * (pos0 + m) * 2) + (logits ? (double)d.vocab * D * 2 + (double)(m - first_row) * d.vocab * 4 : 0.0) +
-                (double)m * D * 2;
-    }
-    const bool timed = c->prof_begin(&M == &c->target ? METASD_PROF_FORWARD : METASD_PROF_DRAFT_FORWARD, bytes);
-    int rc;
-    switch (M.hd) {
-        case 32: rc = launch_persistent<32>(c, P); break;
-        case 64: rc = launch_persistent<64>(c, P); break;
-        default: rc = launch_persistent<128>(c, P); break;
-    }
-    if (timed) c->prof_end();
-    return rc;
 }
 
 // Forward over tokens hist[pos0 .. pos0+n) in blocks of <= 16 rows (later blocks see the KV of
@@ -907,7 +875,6 @@ int forward(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool want_a
         const int first_row = want_all ? 0 : m - 1;
         int rc;
         if (M.d.dtype != METASD_BF16) rc = forward_rows<float>(c, M, pos0 + done, m, lg, first_row);
-        else if (c->persistent) rc = forward_persistent(c, M, pos0 + done, m, lg, first_row);
         else if (c->fuse_small && fused_small_ok(M, m)) rc = forward_rows_fused(c, M, pos0 + done, m, lg, first_row);
         else if (c->gemm_reduce) rc = forward_rows_residual(c, M, pos0 + done, m, lg, first_row);
         else rc = forward_rows<bf16_t>(c, M, pos0 + done, m, lg, first_row);
@@ -972,18 +939,17 @@ int gemm_rows<bf16_t>(metasd_ctx* c, const void* x, int ldx, int R, int K, const
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)R * K * 4 + (double)R * N * 4 * s.ksplit);
     const bf16_t* xh = (const bf16_t*)x;
     const int t0 = n0 / 16, t1 = (n0 + n1) / 16;
-    static const bool lo = env_int("METASD_ROWS_LO", 1) != 0;     // 0: plain bf16 activations (measurement aid)
     int rc = 0;
     // more than 256 rows: two passes over the weights, 256 rows each (a 512-row variant would spill registers)
     for (int r0 = 0; r0 < R && !rc; r0 += 256) {
         const int nr = std::min(256, R - r0);
         metasd_ctx::ProfRec* p = r0 ? nullptr : pr;
 #define ROWS_ARGS (c, xh, x_lo_off, ldx, R, r0, nr, K, W0, W1, W2, t0, t1, ntiles, N, s, p)
-#define ROWS_GO(RBW) (lo ? launch_gemm_rows<RBW, true> ROWS_ARGS : launch_gemm_rows<RBW, false> ROWS_ARGS)
+#define ROWS_GO(RBW) launch_gemm_rows<RBW, true> ROWS_ARGS
         if (nr <= 64) rc = ROWS_GO(1);
         else if (nr <= 128) rc = ROWS_GO(2);
-        else if (lo && s.tpb == 4) rc = launch_gemm_rows<4, true, 2> ROWS_ARGS;
-        else if (lo && s.tpb == 6) rc = launch_gemm_rows<4, true, 3> ROWS_ARGS;
+        else if (s.tpb == 4) rc = launch_gemm_rows<4, true, 2> ROWS_ARGS;
+        else if (s.tpb == 6) rc = launch_gemm_rows<4, true, 3> ROWS_ARGS;
         else rc = ROWS_GO(4);
 #undef ROWS_GO
 #undef ROWS_ARGS
@@ -1307,19 +1273,20 @@ int launch_sample(hipStream_t st, const float* logits, int rows, int V, float T,
 bool accept_split_enabled() { return env_int("METASD_ACCEPT_SPLIT", 1) != 0; }   // read per launch: tests toggle it
 
 // xchg != nullptr: four workgroups per (row, position) (accept_split_kernel); else one (accept_rows_kernel).
+// rounds: the round word of the Philox counters, one per row (rt.n == rows) or the same for every row (rt.n == 0: rt.v[0]).
 int launch_accept(hipStream_t st, const float* P, const float* Q, const int32_t* d, int rows, int gamma, int V, float T,
-                  uint64_t seed, uint32_t round, uint32_t seq0, int2* cand, double* bd, int32_t* n_acc, int32_t* token,
+                  uint64_t seed, const RoundTab& rt, uint32_t seq0, int2* cand, double* bd, int32_t* n_acc, int32_t* token,
                   uint32_t* mask, int32_t* hist, int l, unsigned long long* xchg, hipEvent_t ev_begin = nullptr,
                   hipEvent_t ev_end = nullptr) {
     if (xchg && accept_split_enabled()) {   // one launch: the kernel also writes N_acc, the token and the mask
         hipExtLaunchKernelGGL(accept_split_kernel, dim3(AS_Q, gamma + 1, rows), dim3(AS_NT), 0u, st, ev_begin, ev_end, 0u, P, Q, d, gamma,
-                              V, T, seed, round, seq0, (unsigned long long*)cand, bd, xchg, next_epoch(),
+                              V, T, seed, rt, seq0, (unsigned long long*)cand, bd, xchg, next_epoch(),
                               std::max(0, env_int("METASD_ACCEPT_SPIN_LIMIT", 1 << 18)), n_acc, token, mask,
                               hist, l);
         return hipGetLastError() == hipSuccess ? 0 : METASD_E_HIP;
     }
     hipExtLaunchKernelGGL(accept_rows_kernel, dim3(gamma + 1, rows), dim3(AK_NT), 0u, st, ev_begin, ev_end, 0u, P, Q, d, gamma, V,
-                          T, seed, round, seq0, cand, bd);
+                          T, seed, rt, seq0, cand, bd);
     if (hipGetLastError() != hipSuccess) return METASD_E_HIP;
     hipLaunchKernelGGL(accept_finalize_kernel, dim3((rows + 63) / 64), dim3(64), 0, st, cand, rows, gamma, n_acc, token, mask,
                        hist, l);
@@ -1331,6 +1298,18 @@ bool valid_vocab(int V) { return V >= 4 && V % 4 == 0 && V <= AK_WAVES * AK_SEG;
 // ---- one round over a batch of independent sequences (cfg.batch > 1): every sequence drafts with its own
 // arm (sequences that share an arm share that drafter's forward), one verification block over all
 // batch x (gamma + 1) rows, one accept launch over all rows.
+
+RoundTab seq_rounds(const metasd_ctx* c) {
+    RoundTab rt{};
+    rt.n = c->cfg.batch;
+    for (int b = 0; b < rt.n; ++b) rt.v[b] = (uint32_t)c->sq[b].round;
+    return rt;
+}
+RoundTab one_round(uint32_t round) {
+    RoundTab rt{};
+    rt.v[0] = round;
+    return rt;
+}
 
 int draft_batch(metasd_ctx* c, const int32_t* k, int gamma) {
     const int B = c->cfg.batch, V = c->target.d.vocab;
@@ -1386,7 +1365,7 @@ int draft_batch(metasd_ctx* c, const int32_t* k, int gamma) {
         }
         for (int b = 0; b < B; ++b) at.v[b] = c->sq[b].l + j;
         hipLaunchKernelGGL(sample_seq_kernel, dim3(B), dim3(AK_NT), 0, c->stream, (const float*)c->d_Q() + (size_t)j * V, (size_t)gamma * V, V,
-                           c->cfg.temperature, c->cfg.seed, (uint32_t)c->round, (uint32_t)j, c->d_hist(), c->cfg.max_ctx, at,
+                           c->cfg.temperature, c->cfg.seed, seq_rounds(c), (uint32_t)j, c->d_hist(), c->cfg.max_ctx, at,
                            c->d_draft() + j, gamma);
         LAUNCH_CHECK(c, "sample (batch)");
     }
@@ -1406,7 +1385,7 @@ int accept_batch(metasd_ctx* c, int gamma, int32_t* n_acc_out, int32_t* token_ou
     const int B = c->cfg.batch, V = c->target.d.vocab, gm = c->cfg.gamma_max;
     int32_t* res = c->d_res();
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_ACCEPT, (double)B * (2 * gamma + 1) * V * 4);
-    if (launch_accept(c->stream, c->d_P(), c->d_Q(), c->d_draft(), B, gamma, V, c->cfg.temperature, c->cfg.seed, (uint32_t)c->round, 0u,
+    if (launch_accept(c->stream, c->d_P(), c->d_Q(), c->d_draft(), B, gamma, V, c->cfg.temperature, c->cfg.seed, seq_rounds(c), 0u,
                       c->d_cand(), c->d_bd(), res, res + B, (uint32_t*)(res + 2 * B), nullptr, 0, c->d_xchg(), pr ? pr->a : nullptr,
                       pr ? pr->b : nullptr))
         return c->fail(METASD_E_HIP, "launch accept kernels failed");
@@ -1418,6 +1397,20 @@ int accept_batch(metasd_ctx* c, int gamma, int32_t* n_acc_out, int32_t* token_ou
     if (int rc = c->fetch_results()) return rc;
     (void)gm;
     const int32_t* hn = c->mirror<int32_t>(c->lay.res);
+    bool timed_out = false;
+    for (int b = 0; b < B; ++b) timed_out = timed_out || hn[B + b] == -2;
+    if (timed_out && !c->mirror<GridBar>(c->lay.bar)->abort) {
+        // some position's workgroups did not meet within their bounded wait: nothing of those rows was committed and the
+        // logits are untouched - take the whole step again with one workgroup per position
+        if (launch_accept(c->stream, c->d_P(), c->d_Q(), c->d_draft(), B, gamma, V, c->cfg.temperature, c->cfg.seed, seq_rounds(c), 0u,
+                          c->d_cand(), c->d_bd(), res, res + B, (uint32_t*)(res + 2 * B), nullptr, 0, nullptr))
+            return c->fail(METASD_E_HIP, "launch accept kernels failed");
+        hipLaunchKernelGGL(commit_tokens_kernel, dim3(1), dim3(64), 0, c->stream, (const int32_t*)res, (const int32_t*)(res + B), c->d_hist(),
+                           c->cfg.max_ctx, lt, B);
+        LAUNCH_CHECK(c, "commit_tokens");
+        if (int rc = c->fetch_results()) return rc;
+        c->accept_fallbacks += 1;
+    }
     const int32_t* ht = hn + B;
     const uint32_t* hm = (const uint32_t*)(hn + 2 * B);
     const int32_t* hd = c->mirror<int32_t>(c->lay.draft);
@@ -1438,6 +1431,7 @@ int accept_batch(metasd_ctx* c, int gamma, int32_t* n_acc_out, int32_t* token_ou
         for (int j = 0; j < n; ++j) S.hist[l + j] = hd[(size_t)b * gamma + j];
         S.hist[l + n] = ht[b];
         S.l = l + n + 1;
+        S.round += 1;
         c->target.kvl[b] = l + n;
         c->drafters[S.cur_k].kvl[b] = std::min(l + n, l + gamma - 1);
         if (n_acc_out) n_acc_out[b] = n;
@@ -1449,7 +1443,6 @@ int accept_batch(metasd_ctx* c, int gamma, int32_t* n_acc_out, int32_t* token_ou
             bd_out[b] = sum / (double)gamma;
         }
     }
-    c->round += 1;
     c->phase = PH_READY;
     return METASD_OK;
 }
@@ -1576,24 +1569,16 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         delete c;
         return rc;
     }
-    // persistent forward: needs cooperative launch, > 64 KiB of dynamic LDS and a device table per model
     {
-        int dev = 0, coop = 0, ncu = 0;
-        bool ok = hipGetDevice(&dev) == hipSuccess &&
-                  hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) == hipSuccess && coop &&
-                  hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && ncu > 0;
-        ok = ok && hipFuncSetAttribute((const void*)forward_persistent_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize, PK_LDS_BYTES) == hipSuccess;
-        ok = ok && hipFuncSetAttribute((const void*)forward_persistent_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, PK_LDS_BYTES) == hipSuccess;
-        ok = ok && hipFuncSetAttribute((const void*)forward_persistent_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, PK_LDS_BYTES) == hipSuccess;
-        (void)hipGetLastError();
-        // The one-launch forward is opt-in (METASD_PERSISTENT=1): at the 7B shape it is still slower
-        // than the step-by-step kernels (per-phase barrier + staging latency), see the design notes.
-        const char* ev = getenv("METASD_PERSISTENT");
-        c->persistent = ok && ev && ev[0] == '1';
-        if (const char* ev = getenv("METASD_TLOG")) c->tlog = ev[0] == '1';
+        int dev = 0, ncu = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu < 1) {
+            rc = fail_global(METASD_E_HIP, "cannot query the device");
+            (void)hipHostFree(c->hspan);
+            delete c;
+            return rc;
+        }
         if (const char* ev = getenv("METASD_FUSE_SMALL")) c->fuse_small = ev[0] != '0';
         if (const char* ev = getenv("METASD_GEMM_REDUCE")) c->gemm_reduce = ev[0] != '0';
-        if (const char* ev = getenv("METASD_GEMM_FULLK")) c->fullk = ev[0] != '0';
         if (const char* ev = getenv("METASD_GEMM_ROLL")) c->fullk_roll = ev[0] != '0';
         if (const char* ev = getenv("METASD_DRAFT_GROUPED")) c->grouped_on = ev[0] != '0';
         if (const char* ev = getenv("METASD_ATT_CPW")) { const int v = atoi(ev); c->att_cpw = (v >= 1 && v <= 64) ? v : 0; }
@@ -1608,7 +1593,6 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         }
         if (hipFuncSetAttribute((const void*)gemm_fullk_residual_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)FULLK_LDS_MAX) != hipSuccess) { c->fullk = false; (void)hipGetLastError(); }
         c->n_cu = ncu;
-        if (const char* ev = getenv("METASD_NB")) { int v = atoi(ev); if (v >= 1 && v <= ncu) c->n_cu = v; }   // fewer workgroups (debugging)
     }
     c->target.d_table = (const void**)(c->ws + lay.tables);
     for (int k = 0; k < cfg->K; ++k) c->drafters[k].d_table = (const void**)(c->ws + lay.tables + lay.table_stride * (size_t)(k + 1));
@@ -1644,6 +1628,8 @@ int32_t metasd_set_context(metasd_ctx* c, int32_t seq, const int32_t* tokens, in
     if (n + c->cfg.gamma_max + 1 > c->cfg.max_ctx) return c->fail(METASD_E_OVERFLOW, "set_context: n + gamma_max + 1 = %d exceeds max_ctx %d", n + c->cfg.gamma_max + 1, c->cfg.max_ctx);
     for (int i = 0; i < n; ++i)
         if (tokens[i] < 0 || tokens[i] >= c->target.d.vocab) return c->fail(METASD_E_INVALID, "set_context: token %d out of range at %d", tokens[i], i);
+    if (c->phase == PH_DRAFTED || c->phase == PH_VERIFIED)
+        return c->fail(METASD_E_ORDER, "set_context: a round is in flight (finish it with metasd_accept first)");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     metasd_ctx::SeqState& S = c->sq[seq];
     std::copy(tokens, tokens + n, S.hist.begin());
@@ -1652,8 +1638,7 @@ int32_t metasd_set_context(metasd_ctx* c, int32_t seq, const int32_t* tokens, in
     S.l = n;
     S.bandit.reset();
     S.ready = true;
-    // the round counter (Philox round word, shared by the sequences of a batch) restarts when sequence 0 is set
-    if (seq == 0) c->round = 0;
+    S.round = 0;                    // this sequence's Philox round word restarts with its query; the others carry on
     bool all = true;
     for (const auto& q : c->sq) all = all && q.ready;
     c->phase = all ? PH_READY : PH_NONE;
@@ -1731,7 +1716,7 @@ int32_t metasd_draft(metasd_ctx* c, const int32_t* k, int32_t gamma) {
         if (j == 0) rc = forward(c, D, D.kvl[0], l - D.kvl[0], Qj, false);   // catch-up, ends with the last committed token
         else rc = forward(c, D, l + j - 1, 1, Qj, false);
         if (rc) return rc;
-        if (launch_sample(c->stream, Qj, 1, V, T, c->cfg.seed, (uint32_t)c->round, (uint32_t)j, 0u, c->d_hist() + l + j, 1,
+        if (launch_sample(c->stream, Qj, 1, V, T, c->cfg.seed, (uint32_t)c->sq[0].round, (uint32_t)j, 0u, c->d_hist() + l + j, 1,
                           c->d_draft() + j))
             return c->fail(METASD_E_HIP, "launch sample_rows failed");
     }
@@ -1760,11 +1745,20 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
     int32_t* res = c->d_res();
     metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_ACCEPT, (double)(2 * gamma + 1) * V * 4);
     if (launch_accept(c->stream, c->d_P(), c->d_Q(), c->d_hist() + l, 1, gamma, V, c->cfg.temperature, c->cfg.seed,
-                      (uint32_t)c->round, 0u, c->d_cand(), c->d_bd(), res, res + 1, (uint32_t*)(res + 2), c->d_hist(), l,
+                      one_round((uint32_t)c->sq[0].round), 0u, c->d_cand(), c->d_bd(), res, res + 1, (uint32_t*)(res + 2), c->d_hist(), l,
                       c->d_xchg(), pr ? pr->a : nullptr, pr ? pr->b : nullptr))
         return c->fail(METASD_E_HIP, "launch accept kernels failed");
     if (int rc = c->fetch_results()) return rc;
     const int32_t* hres = c->mirror<int32_t>(c->lay.res);     // n_acc, token, mask
+    if (hres[1] == -2 && !c->mirror<GridBar>(c->lay.bar)->abort) {
+        // the four workgroups of some position did not meet within their bounded wait: nothing was committed, the
+        // logits are untouched - take the step again with one workgroup per position (no meeting between workgroups)
+        if (launch_accept(c->stream, c->d_P(), c->d_Q(), c->d_hist() + l, 1, gamma, V, c->cfg.temperature, c->cfg.seed,
+                          one_round((uint32_t)c->sq[0].round), 0u, c->d_cand(), c->d_bd(), res, res + 1, (uint32_t*)(res + 2), c->d_hist(), l, nullptr))
+            return c->fail(METASD_E_HIP, "launch accept kernels failed");
+        if (int rc = c->fetch_results()) return rc;
+        c->accept_fallbacks += 1;
+    }
     const int32_t* hd = c->mirror<int32_t>(c->lay.draft);
     const double* hbd = c->mirror<double>(c->lay.bd);
     if (c->mirror<GridBar>(c->lay.bar)->abort) {
@@ -1782,7 +1776,7 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
     c->sq[0].l = l + n + 1;
     c->target.kvl[0] = l + n;
     c->drafters[c->sq[0].cur_k].kvl[0] = std::min(l + n, l + gamma - 1);
-    c->round += 1;
+    c->sq[0].round += 1;
     c->phase = PH_READY;
     if (n_acc_out) *n_acc_out = n;
     if (token_out) *token_out = token;
@@ -1805,7 +1799,7 @@ int32_t metasd_accept_logits(const float* P, const float* Q, const int32_t* d, i
         return fail_global(METASD_E_INVALID, "accept_logits: rows 1..65535, gamma 1..31, V %% 4 == 0, V <= 32768, T >= 0");
     // scratch: [rows (gamma+1)] candidates of 16 bytes, then the exchange words of the split kernel
     unsigned long long* xchg = (unsigned long long*)((char*)scratch + (size_t)rows * (gamma + 1) * 16);
-    if (launch_accept((hipStream_t)hip_stream, P, Q, d, rows, gamma, V, temperature, seed, round, seq0, (int2*)scratch, bd, n_acc,
+    if (launch_accept((hipStream_t)hip_stream, P, Q, d, rows, gamma, V, temperature, seed, one_round(round), seq0, (int2*)scratch, bd, n_acc,
                       token, mask, nullptr, 0, xchg))
         return fail_global(METASD_E_HIP, "accept_logits: launch failed");
     return METASD_OK;
@@ -1860,7 +1854,7 @@ int32_t metasd_profile(metasd_ctx* c, int32_t max_records) {
 
 int32_t metasd_profile_read(metasd_ctx* c, int32_t kind, double* ms_total, int64_t* launches, double* bytes_total) {
     if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
-    if (kind < 0 || kind > 4) return c->fail(METASD_E_INVALID, "profile_read: unknown kind %d", kind);
+    if (kind < 0 || kind > 2) return c->fail(METASD_E_INVALID, "profile_read: unknown kind %d", kind);
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     double ms = 0.0, by = 0.0;
     int64_t n = 0;
@@ -1887,7 +1881,6 @@ int32_t metasd_peek(metasd_ctx* c, int32_t what, void** dev_ptr_out, size_t* byt
         case METASD_PEEK_Q: *dev_ptr_out = c->d_Q(); *bytes_out = (size_t)c->cfg.batch * c->cfg.gamma_max * V * 4; break;
         case METASD_PEEK_HIST: *dev_ptr_out = c->d_hist(); *bytes_out = (size_t)c->cfg.batch * c->cfg.max_ctx * 4; break;
         case METASD_PEEK_BD: *dev_ptr_out = c->d_bd(); *bytes_out = (size_t)c->cfg.batch * c->cfg.gamma_max * 8; break;
-        case 5: *dev_ptr_out = c->d_part(); *bytes_out = (size_t)(2048 + 512) * 8; break;   // timestamps (METASD_TLOG=1)
         case METASD_PEEK_DRAFT: *dev_ptr_out = c->d_draft(); *bytes_out = (size_t)c->cfg.batch * c->cfg.gamma_max * 4; break;
         default: return c->fail(METASD_E_INVALID, "peek: unknown buffer %d", what);
     }
@@ -1898,7 +1891,13 @@ int32_t metasd_state_seq(const metasd_ctx* c, int32_t seq, int32_t model, int32_
     if (!c || model < -1 || model >= c->cfg.K || seq < 0 || seq >= c->cfg.batch) return fail_global(METASD_E_INVALID, "state: bad argument");
     if (l_out) *l_out = c->sq[seq].l;
     if (kv_len_out) *kv_len_out = model < 0 ? c->target.kvl[seq] : c->drafters[model].kvl[seq];
-    if (round_out) *round_out = c->round;
+    if (round_out) *round_out = c->sq[seq].round;
+    return METASD_OK;
+}
+
+int32_t metasd_accept_fallbacks(const metasd_ctx* c, int64_t* count_out) {
+    if (!c || !count_out) return fail_global(METASD_E_INVALID, "accept_fallbacks: bad argument");
+    *count_out = c->accept_fallbacks;
     return METASD_OK;
 }
 

@@ -36,6 +36,45 @@ def make_lockstep(g, cfg, seqs, prompts, T, tol, reward="BE", kv_prefilled=False
     return BatchLockStep(g, out)
 
 
+def test_new_query_for_one_sequence_between_rounds():
+    """One sequence of a batch gets a new query (metasd_set_context) after four rounds while the others carry on:
+    its bandit and its round counter - the round word of its Philox counters - restart, those of the other
+    sequences do not, so no sequence ever re-uses a counter.  Every sequence stays in lock-step with its oracle
+    (which counts its own rounds).  Between draft and accept a new context is refused."""
+    cfg = W.config1()
+    prompts = [cfg["prompt"], W.prompt_tokens(9, 512, 11), W.prompt_tokens(23, 512, 12)]
+    g, seqs = batch_pair(cfg, 1.0, prompts, 1e-4)
+    bl = make_lockstep(g, cfg, seqs, prompts, 1.0, 1e-4)
+    for r in range(4):
+        bl.round()
+    ks = [g.bandit_select(seq=b) for b in range(3)]
+    g.draft(ks, cfg["gamma"])
+    with pytest.raises(M.MetaSDError) as e:                 # a round is in flight
+        g.set_context(prompts[0], seq=0)
+    assert e.value.code == -3
+    g.verify(cfg["gamma"])
+    n, tok, mask, bd = g.accept(cfg["gamma"])
+    g.close()
+    # the same again, this time with the new query placed between two rounds
+    g, seqs = batch_pair(cfg, 1.0, prompts, 1e-4)
+    bl = make_lockstep(g, cfg, seqs, prompts, 1.0, 1e-4)
+    for r in range(4):
+        bl.round()
+    p_new = W.prompt_tokens(14, 512, 77)
+    ot, od = oracle_models(cfg)
+    g.set_context(p_new, seq=1)
+    bl.seqs[1] = LockStep(g, ot, od, p_new, cfg["gamma"], 1.0, cfg["seed"], cfg["beta"], logit_tol=1e-4, seq=1)
+    assert g.state(-1, seq=1)[2] == 0 and g.state(-1, seq=0)[2] == 4 and g.state(-1, seq=2)[2] == 4
+    for r in range(5):
+        ks, _ = bl.round()
+        if r < 3:
+            assert ks[1] == r                                # the re-set sequence sweeps its arms again (Alg. 2)
+    for ls in bl.seqs:
+        st = ls.stats
+        assert st["mismatch_own"] == 0 and st["ties_own"] + st["ties_shared"] <= 1, st
+    g.close()
+
+
 @pytest.mark.parametrize("T,reward", [(0.0, "BE"), (1.0, "BD")])
 def test_fp32_batch_of_three(T, reward):
     """Tiny fp32 configuration, three sequences with prompts of 16, 9 and 23 tokens, real prefill."""
@@ -252,15 +291,16 @@ def test_identical_prompts_share_logits_not_draws():
 def test_config5_full_size_sampled_sequences():
     """The batched configuration at full size - 7B-shape target, 32 sequences, KV context 4096 (synthetic
     prefix, different per sequence), gamma = 7, T = 0.7, 256 verification rows, in the launch
-    configuration `bench.py --workload c5` times - with two of the 32 sequences (one in each half of
-    the row range) followed by the oracle: drafter and target logits, accept outcome, commit."""
+    configuration `bench.py --workload c5` times - with eight of the 32 sequences (the first, the last and six
+    spread over the row range) followed by the oracle: drafter and target logits, accept outcome, commit.
+    The oracle models of the followed sequences share one copy of the weights; each has its own caches."""
     B, gamma, ctx, T = 32, 7, 4096, 0.7
     cfg = W.config4(device="cuda", ctx=ctx)
     cfg["gamma"], cfg["max_ctx"] = gamma, ctx + 2 * (gamma + 1) + 8
     td, tw = cfg["target"]
     g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=gamma, max_ctx=cfg["max_ctx"], temperature=T, seed=cfg["seed"],
                  ucb_beta=cfg["beta"], batch=B)
-    sampled = (5, 30)
+    sampled = (0, 5, 9, 14, 18, 23, 27, 31)
     tw_np = W.to_numpy(tw)                                  # shared by the oracle models of both sampled sequences
     dw_np = [W.to_numpy(dw) for _, dw in cfg["drafters"]]
     models = [(td, g.kv_target)] + [(dd, g.kv_drafters[k]) for k, (dd, _) in enumerate(cfg["drafters"])]

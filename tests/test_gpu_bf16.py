@@ -92,23 +92,104 @@ def test_gqa_early_exit_drafters_real_prefill():
     assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
 
 
-def test_config3_1b_shape_full_size():
+@pytest.mark.parametrize("T", [1.0, 0.0])
+def test_config3_1b_shape_full_size(T):
     """1B-shape target at full size (16 layers, d 2048, 32/8 heads, FFN 8192, vocab 32000), K = 4
-    early-exit drafters; 512-position synthetic KV prefix instead of a CPU prefill; 3 rounds, T = 1."""
+    early-exit drafters; 512-position synthetic KV prefix instead of a CPU prefill; 3 rounds, T = 1 and greedy."""
     cfg = W.config3(device="cuda")
     cfg["kv_seed"] = 7
-    st = run_lockstep(cfg, 1.0, rounds=3, kv_prefilled=True, device="cuda")
+    st = run_lockstep(cfg, T, rounds=3, kv_prefilled=True, device="cuda")
     assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
 
 
-def test_config4_7b_shape_full_size():
-    """7B-shape target at full size (32 layers, d 4096, FFN 11008, vocab 32000, KV context 2048),
-    K = 5 two-layer drafters; the launch configuration bench.py times; 2 rounds, T = 1."""
+def test_config3_1b_shape_real_prefill():
+    """The 1B-shape configuration as it is stated: the 512-token prompt is prefilled by the library
+    (metasd_set_context with kv_prefilled = 0: 31 blocks of 16 rows and a ragged last one through the target;
+    every drafter catches up over the whole prompt the first time it is selected) and by the oracle, then
+    4 rounds at T = 1 - one per drafter - compared logit by logit."""
+    cfg = W.config3(device="cuda")
+    st = run_lockstep(cfg, 1.0, rounds=4, kv_prefilled=False, device="cuda")
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+
+
+def test_config4_7b_shape_full_size_across_segment_switch():
+    """7B-shape target at full size (32 layers, d 4096, FFN 11008, vocab 32000, KV context 2048), K = 5
+    two-layer drafters, T = 1, in the launch configuration bench.py times, run the way bench.py runs it: the
+    drafters' heads are exchanged (metasd_swap_weight, all five) when the number of generated tokens crosses a
+    multiple of 32.  Runs until 36 tokens are out, i.e. across the first switch; every round is compared."""
     cfg = W.config4(device="cuda")
-    st = run_lockstep(cfg, 1.0, rounds=2, kv_prefilled=True, device="cuda")
+    td, tw = cfg["target"]
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=cfg["gamma"], max_ctx=cfg["max_ctx"], temperature=1.0, seed=cfg["seed"],
+                 ucb_beta=cfg["beta"])
+    ot, od = oracle_models(cfg)
+    fill_kv(cfg, g, ot, od, len(cfg["prompt"]) - 1, "cuda")
+    g.set_context(cfg["prompt"], kv_prefilled=True)
+    ls = LockStep(g, ot, od, cfg["prompt"], cfg["gamma"], 1.0, cfg["seed"], cfg["beta"], logit_tol=TOL, kv_prefilled=True)
+    head_index = 2 + 9 * cfg["drafters"][0][0]["n_layers"]
+    seg, new_tokens, switches = 0, 0, 0
+    while new_tokens < 36:
+        s = (new_tokens // cfg["seg_len"]) % 4
+        if s != seg:
+            for k, (dd, dw) in enumerate(cfg["drafters"]):
+                hk = cfg["heads"][k][s]
+                g.swap_weight(k, head_index, M.pack_weight(hk.cuda().contiguous()))
+                old = od[k]
+                od[k] = oracle.Model(dd, W.to_numpy(dw[:-1]) + W.to_numpy([hk]), cfg["max_ctx"])
+                od[k].kv(0)[:] = old.kv(0)                 # the head does not enter the KV cache
+                od[k].kv(1)[:] = old.kv(1)
+            seg, switches = s, switches + 1
+        n, tok = ls.round()
+        new_tokens += n + 1
+    st = ls.stats
+    g.close()
+    assert switches >= 1 and st["rounds"] >= 7, (switches, st["rounds"])
     assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
 
 
+def test_config4_7b_shape_full_size_greedy():
+    """The same configuration in greedy mode (T = 0: accept iff the draft token is the target's argmax), 3 rounds."""
+    cfg = W.config4(device="cuda")
+    st = run_lockstep(cfg, 0.0, rounds=3, kv_prefilled=True, device="cuda")
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+
+
+def test_tall_prefill_blocks_with_many_split_k_siblings():
+    """A narrow model with a very wide FFN (d 256, FFN 11008): the down projection of a 16-row prefill block
+    needs 12 split-K siblings for its activations to fit in LDS - more than the 8 the launch plan asks for on
+    its own - so the siblings' exchange area has to be sized from the split really taken.  Real prefill of a
+    40-token prompt (two full 16-row blocks and a ragged one), then rounds at gamma = 15 (16-row verification)."""
+    cfg = W.config4(n_layers=1, ctx=40, n_new=64, K=2, d_model=256, n_heads=4, d_ffn=11008, vocab=1024, dd_model=128, dn_heads=2,
+                    dd_ffn=160)
+    cfg["gamma"] = 15
+    cfg["max_ctx"] = 40 + 80
+    st = run_lockstep(cfg, 1.0, rounds=3, kv_prefilled=False)
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+
+
+def test_accept_exchange_timeout_falls_back_to_one_workgroup_per_position(monkeypatch):
+    """With the accept kernel's bounded wait forced to zero from the host its four workgroups per position never
+    meet; the context then takes the step again with one workgroup per position: same outcome as an undisturbed
+    run (same seed, prompt, round), the fallback is counted, nothing is lost."""
+    s = SMALL[0]
+    cfg = W.config4(n_layers=s["n_layers"], ctx=s["prompt"], n_new=64, K=2, d_model=s["d_model"], n_heads=s["n_heads"],
+                    d_ffn=s["d_ffn"], vocab=s["vocab"], dd_model=s["dd_model"], dn_heads=s["dn_heads"], dd_ffn=s["dd_ffn"])
+    td, tw = cfg["target"]
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=5, max_ctx=s["prompt"] + 80, temperature=1.0, seed=3)
+    g.set_context(cfg["prompt"])
+    want = [g.round(5) for _ in range(3)]
+    assert g.accept_fallbacks() == 0
+    g.set_context(cfg["prompt"])
+    monkeypatch.setenv("METASD_ACCEPT_SPIN_LIMIT", "0")
+    got = [g.round(5) for _ in range(3)]
+    monkeypatch.delenv("METASD_ACCEPT_SPIN_LIMIT")
+    assert g.accept_fallbacks() == 3
+    for a, b in zip(want, got):
+        assert a[:4] == b[:4] and abs(a[4] - b[4]) < 1e-6, (a, b)
+    g.close()
+
+
+@pytest.mark.skip(reason="the cooperative one-launch forward was taken out of the library: it was 2.2x slower than the "
+                         "step-by-step kernels for a 7B-shape verification pass and 2.5x slower for a drafter step")
 @pytest.mark.parametrize("i", [0, 2])
 def test_one_launch_forward_opt_in(i, monkeypatch):
     """The cooperative one-launch forward (opt-in by environment) gives the same parity as the

@@ -198,7 +198,8 @@ def test_philox_driven_million_draws():
 
 
 def test_philox_structure_and_uniformity():
-    """Structural checks only: absolute conformance to the published generator is unpinned."""
+    """Structural and statistical checks; conformance to the published generator is pinned word for word against
+    rocRAND's Philox4x32-10 in tests/test_gpu_philox_pin.py (rocRAND needs a machine with a device)."""
     n = 20000
     outs = np.array([oracle.philox(5, i, 0, 0, 0) for i in range(n)], dtype=np.uint64)
     keys = (outs[:, 0] << np.uint64(32)) | outs[:, 1]
