@@ -210,6 +210,20 @@ int32_t metasd_accept_logits(const float* P, const float* Q, const int32_t* d, i
                              int32_t* n_acc, int32_t* token, uint32_t* mask, double* bd, void* scratch,
                              void* hip_stream);
 
+/* The same step for callers that cannot allocate device memory or pass a workspace of their own (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): no scratch argument - the candidates
+ * and exchange words live in an array built into the library, METASD_ACCEPT_NOALLOC_MAX_ITEMS * 336 bytes
+ * (1.3 MiB) that every GPU the library runs on holds until the process ends.  Calls with
+ * rows * (gamma + 1) > METASD_ACCEPT_NOALLOC_MAX_ITEMS are refused (INVALID; use metasd_accept_logits).  The
+ * call allocates nothing and synchronises nothing: it enqueues one small kernel that clears the part of the array it
+ * uses (the array keeps the last call's contents) and the accept kernel, on hip_stream of the current device.
+ * All calls on one GPU share the array: two calls whose kernels overlap in time race.  Inputs, outputs, results and
+ * errors otherwise as metasd_accept_logits. */
+#define METASD_ACCEPT_NOALLOC_MAX_ITEMS 4096
+int32_t metasd_accept_logits_noalloc(const float* P, const float* Q, const int32_t* d, int32_t rows, int32_t gamma,
+                                     int32_t V, float temperature, uint64_t seed, uint32_t round, uint32_t seq0,
+                                     int32_t* n_acc, int32_t* token, uint32_t* mask, double* bd, void* hip_stream);
+
 /* Token draw per row of logits [rows][V] (device): argmax for T = 0, else inverse CDF of
  * softmax(logits/T) with the uniform at (seq0 + row, round, pos, stream 2).  tok [rows] device. */
 int32_t metasd_sample_logits(const float* logits, int32_t rows, int32_t V, float temperature, uint64_t seed,

@@ -14,7 +14,7 @@ MATRIX_SLOTS = (1, 2, 3, 4, 6, 7, 8)          # wq wk wv wo w_gate w_up w_down w
 EXPORTS = ["metasd_kv_bytes", "metasd_workspace_bytes", "metasd_pack_weight", "metasd_create", "metasd_destroy",
            "metasd_set_context", "metasd_swap_weight", "metasd_bandit_select", "metasd_bandit_update",
            "metasd_bandit_state", "metasd_draft", "metasd_verify", "metasd_accept", "metasd_accept_logits",
-           "metasd_sample_logits", "metasd_philox_words", "metasd_stream_read", "metasd_profile", "metasd_profile_read", "metasd_peek", "metasd_state", "metasd_state_seq", "metasd_accept_fallbacks", "metasd_last_error"]
+           "metasd_accept_logits_noalloc", "metasd_sample_logits", "metasd_philox_words", "metasd_stream_read", "metasd_profile", "metasd_profile_read", "metasd_peek", "metasd_state", "metasd_state_seq", "metasd_accept_fallbacks", "metasd_last_error"]
 
 
 class MetaSDError(RuntimeError):
@@ -68,6 +68,7 @@ def load_library():
         "metasd_verify": [vp, i32],
         "metasd_accept": [vp, i32, vp, vp, vp, vp],
         "metasd_accept_logits": [vp, vp, vp, i32, i32, i32, f32, u64, u32, u32, vp, vp, vp, vp, vp, vp],
+        "metasd_accept_logits_noalloc": [vp, vp, vp, i32, i32, i32, f32, u64, u32, u32, vp, vp, vp, vp, vp],
         "metasd_sample_logits": [vp, i32, i32, f32, u64, u32, u32, u32, vp, vp],
         "metasd_philox_words": [u64, u32, i32, u32, u32, u32, vp, vp],
         "metasd_stream_read": [vp, C.c_size_t, vp, vp],
@@ -335,6 +336,24 @@ def accept_logits(P: torch.Tensor, Q: torch.Tensor, d: torch.Tensor, T: float, s
     _check(load_library().metasd_accept_logits(P.data_ptr(), Q.data_ptr(), d.data_ptr(), rows, gamma, V, T, seed, rnd, seq0,
                                                out["n_acc"].data_ptr(), out["token"].data_ptr(), out["mask"].data_ptr(),
                                                out["bd"].data_ptr(), out["scratch"].data_ptr(), _stream_ptr(stream)))
+    return out
+
+
+ACCEPT_NOALLOC_MAX_ITEMS = 4096
+
+
+def accept_logits_noalloc(P: torch.Tensor, Q: torch.Tensor, d: torch.Tensor, T: float, seed: int, rnd: int, seq0: int, out: dict,
+                          stream=None) -> dict:
+    """metasd_accept_logits_noalloc: the caller passes inputs and the output tensors (out: n_acc, token, mask int32 [rows],
+    bd float64 [rows, gamma]); the binding allocates nothing either."""
+    _require_gpu()
+    rows, gamma, V = Q.shape
+    assert P.shape == (rows, gamma + 1, V) and d.shape == (rows, gamma)
+    assert P.is_cuda and Q.is_cuda and d.is_cuda and P.is_contiguous() and Q.is_contiguous() and d.is_contiguous()
+    assert P.dtype == torch.float32 and Q.dtype == torch.float32 and d.dtype == torch.int32
+    _check(load_library().metasd_accept_logits_noalloc(P.data_ptr(), Q.data_ptr(), d.data_ptr(), rows, gamma, V, T, seed, rnd, seq0,
+                                                       out["n_acc"].data_ptr(), out["token"].data_ptr(), out["mask"].data_ptr(),
+                                                       out["bd"].data_ptr(), _stream_ptr(stream)))
     return out
 
 

@@ -82,6 +82,12 @@ __device__ __forceinline__ bool tw_get(const unsigned long long* slot, uint32_t 
     return false;
 }
 
+// dst[0 .. n) = 0 (16-byte pieces).   grid ceil(n / 256), block 256
+__global__ void zero_fill_kernel(uint4* __restrict__ dst, unsigned n) {
+    const unsigned i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
 // ------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC'11)
 // counter (c0..c3), key = 64-bit seed; ten rounds, Weyl-sequence key schedule.

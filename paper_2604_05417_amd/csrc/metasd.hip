@@ -12,6 +12,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -20,6 +21,11 @@
 #include "batch.h"
 
 using namespace msd;
+
+// Scratch of metasd_accept_logits_noalloc: candidates and exchange words of up to METASD_ACCEPT_NOALLOC_MAX_ITEMS
+// (row, position) items.  Every GPU the library runs on holds its own copy at its own address; host code reaches it
+// only through the per-device pointer that noalloc_scratch() asks the runtime for.
+static __device__ __align__(256) unsigned char scratch[(size_t)METASD_ACCEPT_NOALLOC_MAX_ITEMS * 336];
 
 namespace {
 
@@ -1802,6 +1808,52 @@ int32_t metasd_accept_logits(const float* P, const float* Q, const int32_t* d, i
     if (launch_accept((hipStream_t)hip_stream, P, Q, d, rows, gamma, V, temperature, seed, one_round(round), seq0, (int2*)scratch, bd, n_acc,
                       token, mask, nullptr, 0, xchg))
         return fail_global(METASD_E_HIP, "accept_logits: launch failed");
+    return METASD_OK;
+}
+
+// Device address of `scratch` on the current device (asked for once per device, with that device current).
+static int noalloc_scratch(unsigned char** out) {
+    constexpr int MAX_DEV = 64;
+    static std::mutex mu;
+    static unsigned char* ptr[MAX_DEV] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_global(METASD_E_HIP, "accept_logits_noalloc: hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= MAX_DEV) return fail_global(METASD_E_INVALID, "accept_logits_noalloc: device index %d not supported", dev);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail_global(METASD_E_HIP, "accept_logits_noalloc: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        ptr[dev] = static_cast<unsigned char*>(p);
+    }
+    *out = ptr[dev];
+    return METASD_OK;
+}
+
+int32_t metasd_accept_logits_noalloc(const float* P, const float* Q, const int32_t* d, int32_t rows, int32_t gamma, int32_t V,
+                                     float temperature, uint64_t seed, uint32_t round, uint32_t seq0, int32_t* n_acc,
+                                     int32_t* token, uint32_t* mask, double* bd, void* hip_stream) {
+    if (!P || !Q || !d || !n_acc || !token) return fail_global(METASD_E_INVALID, "accept_logits_noalloc: NULL pointer");
+    if (rows < 1 || rows > 65535 || gamma < 1 || gamma > 31 || !valid_vocab(V) || !(temperature >= 0.f))
+        return fail_global(METASD_E_INVALID, "accept_logits_noalloc: rows 1..65535, gamma 1..31, V %% 4 == 0, V <= 32768, T >= 0");
+    const size_t items = (size_t)rows * (gamma + 1);
+    if (items > METASD_ACCEPT_NOALLOC_MAX_ITEMS)
+        return fail_global(METASD_E_INVALID, "accept_logits_noalloc: rows * (gamma + 1) = %zu exceeds the built-in scratch of %d items; use metasd_accept_logits with a scratch buffer of your own",
+                           items, METASD_ACCEPT_NOALLOC_MAX_ITEMS);
+    unsigned char* sp = nullptr;
+    if (int rc = noalloc_scratch(&sp)) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // The array keeps what the last call left.  The part this call uses is cleared by a kernel (not a memset: the call
+    // may be recorded into a graph, and a replay repeats this call's launch tag, so the words of the replay before
+    // must be gone).
+    const unsigned n16 = (unsigned)(items * 336 / 16);
+    hipLaunchKernelGGL(zero_fill_kernel, dim3((n16 + 255) / 256), dim3(256), 0, st, reinterpret_cast<uint4*>(sp), n16);
+    if (hipGetLastError() != hipSuccess) return fail_global(METASD_E_HIP, "accept_logits_noalloc: launch failed");
+    unsigned long long* xchg = reinterpret_cast<unsigned long long*>(sp + items * 16);
+    if (launch_accept(st, P, Q, d, rows, gamma, V, temperature, seed, one_round(round), seq0, reinterpret_cast<int2*>(sp), bd, n_acc, token, mask,
+                      nullptr, 0, xchg))
+        return fail_global(METASD_E_HIP, "accept_logits_noalloc: launch failed");
     return METASD_OK;
 }
 
