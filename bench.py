@@ -54,6 +54,8 @@ def main():
                          "c3: the 1B-shape GQA target with four early-exit drafters, real 512-token prefill; "
                          "c2: the accept kernel alone (64 rows x gamma 5 x vocab 32000); c5, c3 and c2 are side measurements")
     ap.add_argument("--batch", type=int, default=32, help="sequences of the c5 workload")
+    ap.add_argument("--own-kv", action="store_true", help="c3: give every early-exit drafter a KV cache of its own (recomputed when it is "
+                                                           "switched in) instead of letting it read the target's")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU (one process, no collectives); use --gpus 1")
@@ -153,6 +155,7 @@ def main():
         one_round()
     torch.cuda.synchronize()
     pg, pa, pc = g.profile_read("gemm"), g.profile_read("attn"), g.profile_read("accept")
+    shapes_target, shapes_all = g.profile_shapes(True), g.profile_shapes(False)
     g.profile(0)
 
     def roof(p):
@@ -182,6 +185,9 @@ def main():
         "verify_algorithmic_GB": verify_bytes / 1e9,
         "verify_positions_per_s": (gamma + 1) / (phase[1] * 1e-3),
         "gemm_kernel": rg, "attn_kernel": ra, "accept_kernel": rc,
+        # the weight-streaming GEMM launches by shape (N x K at m rows): the target's, then the drafters' (all minus the target's)
+        "gemm_shapes_target": shapes_target,
+        "gemm_shapes_drafters": [s for s in shapes_all if not any((s["N"], s["K"], s["m"]) == (t["N"], t["K"], t["m"]) for t in shapes_target)],
         "mean_n_acc": float(np.mean(accs)), "alpha_mean_bd": float(np.mean(bds)),
         "arm_counts": [int(x) for x in np.bincount(arms, minlength=g.K)],
     }
@@ -333,7 +339,7 @@ def bench_c3(args):
     cfg["max_ctx"] = len(cfg["prompt"]) + (gamma + 1) * total + 16
     td, tw = cfg["target"]
     g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=gamma, max_ctx=cfg["max_ctx"], temperature=cfg["T"], seed=cfg["seed"],
-                 ucb_beta=cfg["beta"])
+                 ucb_beta=cfg["beta"], share_target_kv=not args.own_kv)
     g.set_context(cfg["prompt"], kv_prefilled=False)
 
     def one_round():
@@ -380,7 +386,8 @@ def bench_c3(args):
            "warmup": Wm, "ms_per_step": dt / K_steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16", "data": "synthetic",
            "config": {"workload": "C3: 1B-shape bf16 target (16 layers, d 2048, 32/8 heads, FFN 8192, vocab 32000), K=4 early-exit drafters "
-                                  "at layers 2/4/6/8, 512-token prompt prefilled on the GPU, gamma=5, T=1", "gamma": gamma, "batch": 1, "K": g.K},
+                                  "at layers 2/4/6/8" + (" with KV caches of their own" if args.own_kv else " reading the target's KV cache") +
+                                  ", 512-token prompt prefilled on the GPU, gamma=5, T=1", "gamma": gamma, "batch": 1, "K": g.K},
            "roofline": {"bound": "hbm", "kernel": "weight-streaming GEMMs (target and drafters)", "achieved": gbs, "peak": HBM_PEAK_GBS,
                         "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None},
            "cpu_baseline": None,

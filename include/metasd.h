@@ -37,6 +37,15 @@
  *
  * KV cache of a model (device, caller-owned): element type = model dtype, one cache per sequence,
  *     [sequence][layer][2 (K, V)][kv_head][max_ctx][hd],  bytes = batch * metasd_kv_bytes().
+ *
+ * Drafter-switch KV strategies (the paper's appendix on switching costs and on efficient KV-cache strategies).
+ *   default: every drafter has a cache of its own; when it is selected it first consumes the committed tokens it
+ *     has not processed (the recomputation on a switch that the paper describes as its default).
+ *   shared:  drafter_kv[k] == target_kv declares drafter k an early-exit drafter - its layers are the target's first
+ *     n_layers layers (the same weight pointers; checked) followed by norm and head tensors of its own.  The K/V of
+ *     those layers at committed positions are the numbers the target's cache already holds, so the drafter reads them
+ *     there, never consumes a backlog, and writes the K/V of the positions it drafts into the shared cache, where the
+ *     verification pass then writes the same values again.  Nothing is recomputed on a switch.
  */
 #ifndef METASD_H
 #define METASD_H
@@ -258,6 +267,12 @@ int32_t metasd_profile(metasd_ctx*, int32_t max_records);
  * launches, algorithmic bytes (weights / KV / logits each counted once per launch, plus the
  * small activation traffic).  Any output may be NULL. */
 int32_t metasd_profile_read(metasd_ctx*, int32_t kind, double* ms_total, int64_t* launches, double* bytes_total);
+
+/* The recorded weight-streaming GEMM launches grouped by shape (N output features, K inputs, m rows): summed
+ * milliseconds, launches and algorithmic bytes per shape, in order of first appearance; target_only != 0 leaves out
+ * the drafters' launches.  At most max_rows shapes (arrays of that length); *rows_out = shapes written. */
+int32_t metasd_profile_shapes(metasd_ctx*, int32_t target_only, int32_t max_rows, int32_t* n_out, int32_t* k_out, int32_t* m_out,
+                              double* ms_out, int64_t* launches_out, double* bytes_out, int32_t* rows_out);
 
 /* ---- introspection ---------------------------------------------------------------------------- */
 

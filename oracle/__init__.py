@@ -68,6 +68,8 @@ def lib():
         L = C.CDLL(_LIB)
         L.om_model_create.restype = C.c_void_p
         L.om_model_create.argtypes = [C.POINTER(_Desc), C.POINTER(C.c_void_p), C.c_int32]
+        L.om_model_create_shared.restype = C.c_void_p
+        L.om_model_create_shared.argtypes = [C.POINTER(_Desc), C.POINTER(C.c_void_p), C.c_void_p]
         L.om_model_free.argtypes = [C.c_void_p]
         L.om_model_kv.restype = C.POINTER(C.c_float)
         L.om_model_kv.argtypes = [C.c_void_p, C.c_int]
@@ -116,11 +118,17 @@ def num_threads() -> int:
 class Model:
     """Decoder with a KV cache.  ``weights`` is the flat tensor table in the order
     embed, per layer (attn_norm, wq, wk, wv, wo, ffn_norm, w_gate | None, w_up, w_down),
-    final_norm, lm_head; fp32 arrays for dtype 0, uint16 bf16 bit patterns for dtype 1."""
+    final_norm, lm_head; fp32 arrays for dtype 0, uint16 bf16 bit patterns for dtype 1.
 
-    def __init__(self, desc: dict, weights: list, max_ctx: int):
+    share_kv_with: another Model (the target) whose first ``desc["n_layers"]`` layers are this model's layers - an
+    early-exit drafter.  The new model then keeps no cache of its own: it reads and writes the owner's (the
+    no-recomputation strategy for drafter switches, cf. the paper's appendix on switching costs); ``shares_kv`` is set."""
+
+    def __init__(self, desc: dict, weights: list, max_ctx: int, share_kv_with: "Model | None" = None):
         self.desc = dict(desc)
         self.max_ctx = int(max_ctx)
+        self.shares_kv = share_kv_with is not None
+        self._owner = share_kv_with                  # keeps the owner (and its arrays) alive
         want = np.uint16 if desc["dtype"] == 1 else np.float32
         self._keep = []
         ptrs = (C.c_void_p * len(weights))()
@@ -134,9 +142,13 @@ class Model:
             ptrs[i] = w.ctypes.data
         d = _Desc(desc["n_layers"], desc["d_model"], desc["n_heads"], desc["n_kv_heads"], desc["d_ffn"],
                   desc["vocab"], desc["act"], desc["dtype"], desc.get("rms_eps", 1e-5), desc.get("rope_theta", 1e4))
-        self._h = lib().om_model_create(C.byref(d), ptrs, self.max_ctx)
+        if share_kv_with is None:
+            self._h = lib().om_model_create(C.byref(d), ptrs, self.max_ctx)
+        else:
+            assert self.max_ctx == share_kv_with.max_ctx
+            self._h = lib().om_model_create_shared(C.byref(d), ptrs, share_kv_with._h)
         if not self._h:
-            raise MemoryError("om_model_create failed")
+            raise MemoryError("om_model_create failed (or the shapes of a shared-cache drafter do not match its owner's)")
         self.hd = desc["d_model"] // desc["n_heads"]
 
     def close(self):

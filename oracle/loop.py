@@ -7,7 +7,10 @@ Bookkeeping.  ``hist[0:l]`` are the committed tokens.  The target's KV cache hol
 ``[0, l-1)``: the last committed token has no KV yet, it is row 0 of the next verification
 block.  Drafter k's KV cache holds positions ``[0, c[k])`` with ``c[k] <= l-1``; when drafter k
 is selected it first consumes every committed token it has not seen (App. "Switching costs":
-the missing KV entries are recomputed when a drafter is switched in).
+the missing KV entries are recomputed when a drafter is switched in).  An early-exit drafter that
+shares the target's cache (``Model(..., share_kv_with=target)``) has nothing to consume: the
+target's cache already holds the K/V of its layers at every committed position but the last, so
+for it ``c[k] = l-1`` at the start of every round.
 """
 from __future__ import annotations
 
@@ -35,6 +38,8 @@ def sd_round(target, drafter, k: int, st: SdState, gamma: int, T: float, seed: i
     d = np.empty(gamma, np.int32)
     draft_margin = np.empty(gamma, np.float64)
     # --- draft: catch-up block (ends with the last committed token), then gamma-1 single steps
+    if getattr(drafter, "shares_kv", False):
+        st.c[k] = l - 1
     Q[0] = drafter.forward(st.hist[st.c[k]: l], st.c[k], "last")
     for j in range(gamma):
         if j > 0:

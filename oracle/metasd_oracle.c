@@ -66,6 +66,7 @@ typedef struct {
     int32_t hd;
     float *kc; /* [layer][kv_head][max_ctx][hd] */
     float *vc;
+    int borrowed; /* kc / vc belong to another model (early-exit drafter reading the target's cache) */
 } om_model;
 
 /* ---------------------------------------------------------------- helpers */
@@ -165,9 +166,32 @@ om_model *om_model_create(const om_desc *d, const void *const *weights, int32_t 
     return m;
 }
 
+/* An early-exit drafter that keeps no cache of its own (the paper's appendix on switching costs / efficient KV-cache
+ * strategies: avoid recomputing K/V when a drafter is switched in).  Its layers are the owner's first d->n_layers
+ * layers, so K/V of those layers at any position are the owner's by definition; the cache is layer-major, so the
+ * owner's arrays serve as they are.  The caller passes the same weight arrays for those layers. */
+om_model *om_model_create_shared(const om_desc *d, const void *const *weights, om_model *owner) {
+    if (!owner || d->n_layers > owner->d.n_layers || d->d_model != owner->d.d_model || d->n_heads != owner->d.n_heads ||
+        d->n_kv_heads != owner->d.n_kv_heads || d->dtype != owner->d.dtype)
+        return NULL;
+    om_model *m = (om_model *)calloc(1, sizeof(om_model));
+    if (!m) return NULL;
+    m->d = *d;
+    int nw = 1 + OM_PER_LAYER * d->n_layers + 2;
+    m->w = (const void **)malloc(sizeof(void *) * (size_t)nw);
+    memcpy(m->w, weights, sizeof(void *) * (size_t)nw);
+    m->max_ctx = owner->max_ctx;
+    m->hd = owner->hd;
+    m->kc = owner->kc;
+    m->vc = owner->vc;
+    m->borrowed = 1;
+    return m;
+}
+
 void om_model_free(om_model *m) {
     if (!m) return;
-    free(m->kc); free(m->vc); free((void *)m->w); free(m);
+    if (!m->borrowed) { free(m->kc); free(m->vc); }
+    free((void *)m->w); free(m);
 }
 
 /* which: 0 = K cache, 1 = V cache; layout [layer][kv_head][max_ctx][hd] */

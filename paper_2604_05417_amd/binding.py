@@ -14,7 +14,7 @@ MATRIX_SLOTS = (1, 2, 3, 4, 6, 7, 8)          # wq wk wv wo w_gate w_up w_down w
 EXPORTS = ["metasd_kv_bytes", "metasd_workspace_bytes", "metasd_pack_weight", "metasd_create", "metasd_destroy",
            "metasd_set_context", "metasd_swap_weight", "metasd_bandit_select", "metasd_bandit_update",
            "metasd_bandit_state", "metasd_draft", "metasd_verify", "metasd_accept", "metasd_accept_logits",
-           "metasd_accept_logits_noalloc", "metasd_sample_logits", "metasd_philox_words", "metasd_stream_read", "metasd_profile", "metasd_profile_read", "metasd_peek", "metasd_state", "metasd_state_seq", "metasd_accept_fallbacks", "metasd_last_error"]
+           "metasd_accept_logits_noalloc", "metasd_sample_logits", "metasd_philox_words", "metasd_stream_read", "metasd_profile", "metasd_profile_read", "metasd_profile_shapes", "metasd_peek", "metasd_state", "metasd_state_seq", "metasd_accept_fallbacks", "metasd_last_error"]
 
 
 class MetaSDError(RuntimeError):
@@ -74,6 +74,7 @@ def load_library():
         "metasd_stream_read": [vp, C.c_size_t, vp, vp],
         "metasd_profile": [vp, i32],
         "metasd_profile_read": [vp, i32, C.POINTER(f64), C.POINTER(C.c_int64), C.POINTER(f64)],
+        "metasd_profile_shapes": [vp, i32, i32, vp, vp, vp, vp, vp, vp, C.POINTER(i32)],
         "metasd_peek": [vp, i32, C.POINTER(vp), C.POINTER(sz)],
         "metasd_state": [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)],
         "metasd_state_seq": [vp, i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)],
@@ -128,7 +129,7 @@ class MetaSD:
 
     def __init__(self, target, drafters, gamma_max: int, max_ctx: int, temperature: float, seed: int,
                  ucb_beta: float = 1.0, reward: str = "BE", device: str = "cuda:0", policy: str = "ucb",
-                 policy_param: float = 0.0, policy_window: int = 0, batch: int = 1):
+                 policy_param: float = 0.0, policy_window: int = 0, batch: int = 1, share_target_kv: bool = False):
         _require_gpu()
         self.L = load_library()
         self.device = torch.device(device)
@@ -148,7 +149,11 @@ class MetaSD:
         self._tw = self._table(tdesc, tw)
         self._dw = [self._table(d, w) for d, w in drafters]
         self.kv_target = self._alloc_kv(self._tdesc_c, tdesc)
-        self.kv_drafters = [self._alloc_kv(self._ddesc_c[k], self.ddescs[k]) for k in range(self.K)]
+        # share_target_kv: a drafter whose layer tensors ARE the target's first layers (early exit) gets the target's cache
+        # itself (metasd.h, "shared" strategy); every other drafter gets a cache of its own
+        self.kv_shared = [share_target_kv and d["n_layers"] <= tdesc["n_layers"] and
+                          all(a is b for a, b in zip(w[: 1 + PER_LAYER * d["n_layers"]], tw)) for d, w in drafters]
+        self.kv_drafters = [self.kv_target if self.kv_shared[k] else self._alloc_kv(self._ddesc_c[k], self.ddescs[k]) for k in range(self.K)]
         nbytes = C.c_size_t(0)
         _check(self.L.metasd_workspace_bytes(C.byref(self.cfg), C.byref(self._tdesc_c), self._ddesc_c, C.byref(nbytes)))
         self.workspace = torch.zeros(nbytes.value, dtype=torch.uint8, device=self.device)
@@ -295,6 +300,19 @@ class MetaSD:
         ms, n, by = C.c_double(0), C.c_int64(0), C.c_double(0)
         _check(self.L.metasd_profile_read(self._h, {"gemm": 0, "attn": 1, "accept": 2}[kind], C.byref(ms), C.byref(n), C.byref(by)), self._h)
         return dict(ms=ms.value, launches=n.value, bytes=by.value)
+
+    def profile_shapes(self, target_only: bool = True, max_rows: int = 64) -> list:
+        """Recorded GEMM launches by shape: dicts N, K, m, launches, avg_us, bytes_per_launch, GBs."""
+        n, k, m = (np.zeros(max_rows, np.int32) for _ in range(3))
+        ms, by, cnt = np.zeros(max_rows, np.float64), np.zeros(max_rows, np.float64), np.zeros(max_rows, np.int64)
+        rows = C.c_int32(0)
+        vp = lambda a: a.ctypes.data_as(C.c_void_p)
+        _check(self.L.metasd_profile_shapes(self._h, int(target_only), max_rows, vp(n), vp(k), vp(m), vp(ms), vp(cnt), vp(by), C.byref(rows)), self._h)
+        out = []
+        for i in range(rows.value):
+            out.append(dict(N=int(n[i]), K=int(k[i]), m=int(m[i]), launches=int(cnt[i]), avg_us=ms[i] / cnt[i] * 1e3,
+                            bytes_per_launch=by[i] / cnt[i], GBs=by[i] / (ms[i] * 1e-3) / 1e9 if ms[i] > 0 else 0.0))
+        return out
 
     def state(self, model: int = -1, seq: int = 0):
         l, kv, r = C.c_int32(0), C.c_int32(0), C.c_int32(0)

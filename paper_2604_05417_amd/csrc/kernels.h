@@ -773,7 +773,13 @@ __global__ __launch_bounds__(512) void gemm_fullk_residual_kernel(const bf16_t* 
         for (int u = 0; u < GEMM_U; ++u) w[u] = __builtin_nontemporal_load(wp + (size_t)min(gi * GEMM_U + u, max(nc, 1) - 1) * 64);
     };
     u32x4 wa[GEMM_U], wb[GEMM_U];
-    // activations of this wavefront's slice first (they come back first), then the weight stream
+    // The epilogue's inputs (this tile's block of the residual stream and of the gain) are requested first of all, by every
+    // wavefront alike (only wavefront 0 uses them): their trip to memory overlaps the stream instead of following it.
+    const int erow = (lane & 15) < m ? (lane & 15) : 0;
+    const size_t ecol = (size_t)t * 16 + (lane >> 4) * 4;
+    const float4 h_pre = *reinterpret_cast<const float4*>(h + (size_t)erow * N + ecol);
+    const uint2 gn_pre = *reinterpret_cast<const uint2*>(gain + ecol);
+    // activations of this wavefront's slice next (they come back first), then the weight stream
     {
         const int total = m * nc * 4, per = nc * 4;
         constexpr int XB = 6;
@@ -838,10 +844,10 @@ __global__ __launch_bounds__(512) void gemm_fullk_residual_kernel(const bf16_t* 
     float ss = 0.f;
     if (rowok) {
         const size_t col = (size_t)t * 16 + g * 4;
-        float4 hv = *reinterpret_cast<const float4*>(h + (size_t)row * N + col);
+        float4 hv = h_pre;
         hv.x += y[0]; hv.y += y[1]; hv.z += y[2]; hv.w += y[3];
         *reinterpret_cast<float4*>(h + (size_t)row * N + col) = hv;
-        const uint2 gn = *reinterpret_cast<const uint2*>(gain + col);
+        const uint2 gn = gn_pre;
         const float4 xg = make_float4(hv.x * bf2f((bf16_t)(gn.x & 0xffffu)), hv.y * bf2f((bf16_t)(gn.x >> 16)),
                                       hv.z * bf2f((bf16_t)(gn.y & 0xffffu)), hv.w * bf2f((bf16_t)(gn.y >> 16)));
         store_split4(xsplit, (size_t)m * N, (size_t)row * N + col, xg);
@@ -921,6 +927,10 @@ __global__ __launch_bounds__(512) void gemm_fullk_roll_residual_kernel(const bf1
         }
     };
     u32x4 wa[GEMM_U], wb[GEMM_U], xa[XB], xb[XB];
+    // the epilogue's inputs are requested first of all (see gemm_fullk_residual_kernel)
+    const size_t ecol = (size_t)t * 16 + g * 4;
+    const float4 h_pre = *reinterpret_cast<const float4*>(h + (size_t)rowc * N + ecol);
+    const uint2 gn_pre = *reinterpret_cast<const uint2*>(gain + ecol);
     if (nc > 0) {
         sload(xa, xb, 0);                          // activations first: they come back first
         issue(wa, 0);
@@ -955,10 +965,10 @@ __global__ __launch_bounds__(512) void gemm_fullk_roll_residual_kernel(const bf1
     float ss = 0.f;
     if (rowok) {
         const size_t col = (size_t)t * 16 + g * 4;
-        float4 hv = *reinterpret_cast<const float4*>(h + (size_t)row * N + col);
+        float4 hv = h_pre;
         hv.x += y[0]; hv.y += y[1]; hv.z += y[2]; hv.w += y[3];
         *reinterpret_cast<float4*>(h + (size_t)row * N + col) = hv;
-        const uint2 gn = *reinterpret_cast<const uint2*>(gain + col);
+        const uint2 gn = gn_pre;
         const float4 xg = make_float4(hv.x * bf2f((bf16_t)(gn.x & 0xffffu)), hv.y * bf2f((bf16_t)(gn.x >> 16)),
                                       hv.z * bf2f((bf16_t)(gn.y & 0xffffu)), hv.w * bf2f((bf16_t)(gn.y >> 16)));
         store_split4(xsplit, (size_t)m * N, (size_t)row * N + col, xg);

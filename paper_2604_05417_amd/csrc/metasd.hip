@@ -55,6 +55,8 @@ struct Model {
     metasd_model_desc d{};
     std::vector<const void*> w;
     void* kv = nullptr;
+    bool shared_kv = false;  // an early-exit drafter whose layers are the target's first n_layers and whose cache IS the target's
+    int kv_layers = 0;       // layers of the cache buffer behind kv (the target's count for a shared cache): sequence stride
     int hd = 0;
     std::vector<int> kvl;   // positions valid in the KV cache, per sequence
     const void** d_table = nullptr;   // device copy of w
@@ -399,7 +401,7 @@ struct metasd_ctx {
     }
     std::string err;
     // optional per-launch timing of the three bandwidth-bound kernels (metasd_profile)
-    struct ProfRec { hipEvent_t a, b; int kind; double bytes; };
+    struct ProfRec { hipEvent_t a, b; int kind; double bytes; int n, k, m, model; };   // GEMM launches: N, K, rows, model (-1 target, else drafter)
     bool prof_on = false;
     bool fullk = true;               // residual GEMMs whose input fits in LDS run without split-K (METASD_GEMM_FULLK=0: off)
     bool grouped_on = true;          // batched drafting: one forward per step for all arms (METASD_DRAFT_GROUPED=0: one per arm)
@@ -416,11 +418,13 @@ struct metasd_ctx {
     // Next free record, or nullptr when profiling is off / the pool is used up.  The launcher hands
     // the record's two events to the dispatch itself (hipExtLaunchKernelGGL), so they carry the
     // kernel's own begin and end times rather than those of marker packets around it.
-    ProfRec* prof_take(int kind, double bytes) {
+    int cur_model = -1;              // model whose forward is being launched (-1 target, k drafter k): label of the timing records
+    ProfRec* prof_take(int kind, double bytes, int n = 0, int k = 0, int m = 0) {
         if (!prof_on || prof_used >= prof.size()) return nullptr;
         ProfRec* r = &prof[prof_used++];
         r->kind = kind;
         r->bytes = bytes;
+        r->n = n; r->k = k; r->m = m; r->model = cur_model;
         return r;
     }
     // for launches that cannot carry events (cooperative): marker events on the stream around them
@@ -514,7 +518,7 @@ int gemm<bf16_t>(metasd_ctx* c, const void* x, int ldx, int m, int K, const void
     float* out = direct ? direct_out : c->d_part();
     const int groups = (ntiles + s.tpb - 1) / s.tpb;
     // algorithmic bytes: every weight once, the activations once, the result once
-    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4, N, K, m);
     GemmPro plain{};
     plain.sstride = x_lo_off;
     if (ssq) { plain.src = ssq; plain.row0 = inv_row0; plain.ns = ntg; plain.h_out = inv_out + inv_row0; plain.eps = c->cur_eps; }
@@ -550,7 +554,7 @@ int gemm_residual(metasd_ctx* c, const void* x, int ldx, int m, int K, const voi
     const int ntiles = N / 16, kchunks = K / 32;
     size_t lds_full = 0;
     if (fullk_ok(c, m, K, ntiles, &lds_full)) {
-        metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
+        metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4, N, K, m);
         hipExtLaunchKernelGGL(gemm_fullk_residual_kernel, dim3(ntiles), dim3(512), (uint32_t)lds_full, c->stream, pr ? pr->a : nullptr,
                               pr ? pr->b : nullptr, 0u, (const bf16_t*)x, x_lo_off, ldx, m, K, (const bf16_t*)W, ntiles, N, h,
                               (const bf16_t*)gain_next, xsplit, ssq);
@@ -560,7 +564,7 @@ int gemm_residual(metasd_ctx* c, const void* x, int ldx, int m, int K, const voi
     }
     const size_t lds_roll = (size_t)8 * 4 * m * (GEMM_U * 4 + 1) * 16 + (size_t)8 * 64 * 16;
     if (c->fullk && c->fullk_roll && m <= 8 && ntiles * 4 >= c->n_cu * 3 && kchunks >= 8 * GEMM_U && lds_roll <= FULLK_LDS_MAX) {
-        metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
+        metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4, N, K, m);
         hipEvent_t ea = pr ? pr->a : nullptr, eb = pr ? pr->b : nullptr;
 #define ROLL_GO(XB) hipExtLaunchKernelGGL(gemm_fullk_roll_residual_kernel<XB>, dim3(ntiles), dim3(512), (uint32_t)lds_roll, c->stream, ea, eb, 0u, \
                                           (const bf16_t*)x, x_lo_off, ldx, m, K, (const bf16_t*)W, ntiles, N, h, (const bf16_t*)gain_next, xsplit, ssq)
@@ -575,7 +579,7 @@ int gemm_residual(metasd_ctx* c, const void* x, int ldx, int m, int K, const voi
     const int groups = (ntiles + s.tpb - 1) / s.tpb;
     if ((size_t)(s.ksplit - 1) * m * N * 8 > c->lay.ssq - c->lay.gx)
         return c->fail(METASD_E_WORKSPACE, "residual GEMM (m %d, K %d, N %d): %d split-K siblings exceed the exchange area of the workspace", m, K, N, s.ksplit);
-    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4, N, K, m);
     GemmPro plain{};
     plain.sstride = x_lo_off;
     GemmEpi epi{};
@@ -603,7 +607,7 @@ int gemm_pro(metasd_ctx* c, const GemmPro& pro, int m, int K, const void* W0, in
     float* out = (direct_out && s.ksplit == 1) ? direct_out : part_out;
     const int groups = (ntiles + s.tpb - 1) / s.tpb;
     const size_t lds = s.lds + (PRO == PRO_NORM ? (size_t)m * K * 4 + (size_t)m * 16 : 0);
-    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4);
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4, N, K, m);
     hipExtLaunchKernelGGL(gemm_bf16_kernel<PRO>, dim3(groups * s.ksplit), dim3(256), (uint32_t)lds, c->stream, pr ? pr->a : nullptr,
                           pr ? pr->b : nullptr, 0u, (const float*)nullptr, K, m, K, (const bf16_t*)W0, (const bf16_t*)W1,
                           (const bf16_t*)W2, n0 / 16, (n0 + n1) / 16, ntiles, out, N, s.ksplit, s.cps, s.tpb, pro, GemmEpi{});
@@ -871,7 +875,10 @@ int upload_table(metasd_ctx* c, Model& M) {
 
 // Forward over tokens hist[pos0 .. pos0+n) in blocks of <= 16 rows (later blocks see the KV of
 // earlier ones).  logits (optional): want_all ? all n rows (n <= 16) : the last row only.
+int model_index(const metasd_ctx* c, const Model& M) { return &M == &c->target ? -1 : (int)(&M - c->drafters.data()); }
+
 int forward(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool want_all) {
+    c->cur_model = model_index(c, M);
     if (pos0 + n > c->cfg.max_ctx) return c->fail(METASD_E_OVERFLOW, "positions %d..%d exceed max_ctx %d", pos0, pos0 + n, c->cfg.max_ctx);
     int done = 0;
     while (done < n) {
@@ -942,7 +949,7 @@ int gemm_rows<bf16_t>(metasd_ctx* c, const void* x, int ldx, int R, int K, const
     if (R <= MAX_ROWS) return gemm<bf16_t>(c, x, ldx, R, K, W0, n0, W1, n1, W2, n2, nullptr, nsplit_out, x_lo_off);
     const int N = n0 + n1 + n2, ntiles = N / 16, kchunks = K / 32;
     const Split s = choose_split_rows(ntiles, kchunks, R, c->rows_tpb);
-    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)R * K * 4 + (double)R * N * 4 * s.ksplit);
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)R * K * 4 + (double)R * N * 4 * s.ksplit, N, K, R);
     const bf16_t* xh = (const bf16_t*)x;
     const int t0 = n0 / 16, t1 = (n0 + n1) / 16;
     int rc = 0;
@@ -969,7 +976,7 @@ int attention_seg_hd(metasd_ctx* c, const Model& M, int L, const Segs& sg) {
     const metasd_model_desc& d = M.d;
     const int R = sg.n * sg.ms;
     const size_t plane = (size_t)d.n_kv_heads * c->cfg.max_ctx * HD;
-    const size_t seq_stride = (size_t)d.n_layers * 2 * plane;
+    const size_t seq_stride = (size_t)M.kv_layers * 2 * plane;
     const T* kc = (const T*)M.kv + (size_t)L * 2 * plane;
     const T* vc = kc + plane;
     int nch_max = 1;
@@ -1037,7 +1044,7 @@ int forward_segs_t(metasd_ctx* c, Model& M, const Segs& sg, float* logits, int o
     int ns = 0, rc;
     constexpr int split = sizeof(T) == 2 ? 1 : 0;
     const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
-    const size_t seq_stride = (size_t)d.n_layers * 2 * plane;
+    const size_t seq_stride = (size_t)M.kv_layers * 2 * plane;
     hipLaunchKernelGGL(embed_seg_kernel<T>, dim3(R), dim3(256), 0, st, (const int32_t*)c->d_hist(), c->cfg.max_ctx, (const T*)M.w[0], D, h, sg);
     LAUNCH_CHECK(c, "embed (segments)");
     hipLaunchKernelGGL(rope_table_seg_kernel, dim3(R), dim3(hd / 2), 0, st, sg, hd, d.rope_theta, c->d_rope());
@@ -1083,6 +1090,7 @@ int forward_segs_t(metasd_ctx* c, Model& M, const Segs& sg, float* logits, int o
 }
 
 int forward_segs(metasd_ctx* c, Model& M, const Segs& sg, float* logits, int out_seq_rows, int out_row0, int last_only) {
+    c->cur_model = model_index(c, M);
     for (int s = 0; s < sg.n; ++s)
         if (sg.pos0[s] + sg.m[s] > c->cfg.max_ctx)
             return c->fail(METASD_E_OVERFLOW, "sequence %d: positions %d..%d exceed max_ctx %d", sg.seq[s], sg.pos0[s], sg.pos0[s] + sg.m[s], c->cfg.max_ctx);
@@ -1134,7 +1142,7 @@ int gemm_rows_grouped(metasd_ctx* c, const void* x, int ldx, int R, int K, const
     int mmax = 1;
     for (int g = 0; g < gg.n; ++g) mmax = std::max(mmax, gg.m[g]);
     const Split s = choose_split_rows(ntiles, kchunks, 64, 8);
-    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)gg.n * N * K * 2 + (double)R * K * 4 + (double)R * N * 4 * s.ksplit);
+    metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)gg.n * N * K * 2 + (double)R * K * 4 + (double)R * N * 4 * s.ksplit, N, K, R);
     *nsplit_out = s.ksplit;
     if (mmax <= 64) return launch_gemm_rows_grouped<1>(c, x, ldx, R, K, gg, n0, n1, N, s, pr);
     if (mmax <= 128) return launch_gemm_rows_grouped<2>(c, x, ldx, R, K, gg, n0, n1, N, s, pr);
@@ -1146,6 +1154,7 @@ int gemm_rows_grouped(metasd_ctx* c, const void* x, int ldx, int R, int K, const
 template <int HD>
 int forward_step_grouped(metasd_ctx* c, const Segs& sg, const int* arm, float* logits, int out_seq_rows, int out_row0) {
     typedef bf16_t T;
+    c->cur_model = arm[0];
     const metasd_model_desc& d = c->drafters[arm[0]].d;
     const int D = d.d_model, H = d.n_heads, KH = d.n_kv_heads, hd = HD, F = d.d_ffn, V = d.vocab;
     const int DQ = H * hd, DKV = KH * hd, NQKV = DQ + 2 * DKV;
@@ -1156,7 +1165,6 @@ int forward_step_grouped(metasd_ctx* c, const Segs& sg, const int* arm, float* l
     float* part = c->d_part();
     int ns = 0, rc;
     const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
-    const size_t seq_stride = (size_t)d.n_layers * 2 * plane;
     // groups of consecutive segments with one arm
     RowGroups gg{};
     for (int s0 = 0; s0 < sg.n;) {
@@ -1197,8 +1205,8 @@ int forward_step_grouped(metasd_ctx* c, const Segs& sg, const int* arm, float* l
                            seg_ptrs([&](const Model& M, int) { return (const void*)M.layer_w(L, 0); }), sg.ms, d.rms_eps, xn, 1);
         LAUNCH_CHECK(c, "addnorm (grouped)");
         if ((rc = gemm_rows_grouped(c, xn, D, R, D, weights(L, 1, 2, 3), DQ, DKV, DKV, &ns))) return rc;
-        const SegPtrs kcs = seg_ptrs([&](const Model& M, int s) { return (const void*)((const T*)M.kv + (size_t)L * 2 * plane + (size_t)sg.seq[s] * seq_stride); });
-        const SegPtrs vcs = seg_ptrs([&](const Model& M, int s) { return (const void*)((const T*)M.kv + (size_t)L * 2 * plane + plane + (size_t)sg.seq[s] * seq_stride); });
+        const SegPtrs kcs = seg_ptrs([&](const Model& M, int s) { return (const void*)((const T*)M.kv + (size_t)L * 2 * plane + (size_t)sg.seq[s] * M.kv_layers * 2 * plane); });
+        const SegPtrs vcs = seg_ptrs([&](const Model& M, int s) { return (const void*)((const T*)M.kv + (size_t)L * 2 * plane + plane + (size_t)sg.seq[s] * M.kv_layers * 2 * plane); });
         hipLaunchKernelGGL(rope_kv_segp_kernel<T>, dim3(H + 2 * KH, R), dim3(64), 0, st, part, ns, (size_t)R * NQKV, NQKV, sg, H, KH, hd,
                            (const double2*)c->d_rope(), (float*)c->d_q(), kcs, vcs, c->cfg.max_ctx, 1, 1);
         LAUNCH_CHECK(c, "rope_kv (grouped)");
@@ -1305,6 +1313,12 @@ bool valid_vocab(int V) { return V >= 4 && V % 4 == 0 && V <= AK_WAVES * AK_SEG;
 // arm (sequences that share an arm share that drafter's forward), one verification block over all
 // batch x (gamma + 1) rows, one accept launch over all rows.
 
+// A drafter that shares the target's cache has, by definition, processed exactly what the target has.
+void sync_shared_kv(metasd_ctx* c) {
+    for (auto& D : c->drafters)
+        if (D.shared_kv) D.kvl = c->target.kvl;
+}
+
 RoundTab seq_rounds(const metasd_ctx* c) {
     RoundTab rt{};
     rt.n = c->cfg.batch;
@@ -1324,6 +1338,7 @@ int draft_batch(metasd_ctx* c, const int32_t* k, int gamma) {
         if (c->sq[b].l + gamma + 1 > c->cfg.max_ctx)
             return c->fail(METASD_E_OVERFLOW, "draft: sequence %d: l + gamma + 1 = %d exceeds max_ctx %d", b, c->sq[b].l + gamma + 1, c->cfg.max_ctx);
     }
+    sync_shared_kv(c);
     SeqTab at{};
     const bool can_group = grouped_step_supported(c);
     for (int j = 0; j < gamma; ++j) {
@@ -1449,6 +1464,7 @@ int accept_batch(metasd_ctx* c, int gamma, int32_t* n_acc_out, int32_t* token_ou
             bd_out[b] = sum / (double)gamma;
         }
     }
+    sync_shared_kv(c);
     c->phase = PH_READY;
     return METASD_OK;
 }
@@ -1535,6 +1551,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         M.d = d;
         M.hd = d.d_model / d.n_heads;
         M.kv = kv;
+        M.kv_layers = d.n_layers;
         M.kvl.assign(cfg->batch, 0);
         const int nw = 1 + PER_LAYER * d.n_layers + 2;
         M.w.assign(w, w + nw);
@@ -1560,6 +1577,17 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
             char who[32];
             snprintf(who, sizeof who, "drafter %d", k);
             rc = fill(c->drafters[k], drafters[k], drafter_weights[k], drafter_kv[k], who);
+            if (!rc && drafter_kv[k] == target_kv) {
+                // shared cache: the drafter must be the target's first layers, tensor for tensor, or its K/V would not be the target's
+                Model& D = c->drafters[k];
+                const metasd_model_desc &a = D.d, &b = *target;
+                bool same = a.n_layers <= b.n_layers && a.d_model == b.d_model && a.n_heads == b.n_heads && a.n_kv_heads == b.n_kv_heads &&
+                            a.d_ffn == b.d_ffn && a.act == b.act && a.dtype == b.dtype && a.rms_eps == b.rms_eps && a.rope_theta == b.rope_theta;
+                for (int i = 0; same && i < 1 + PER_LAYER * a.n_layers; ++i) same = D.w[i] == c->target.w[i];
+                if (!same) rc = fail_global(METASD_E_INVALID, "%s: shares the target's KV cache but its layers are not the target's first %d layers (same shapes and weight pointers required)", who, a.n_layers);
+                D.shared_kv = true;
+                D.kv_layers = b.n_layers;
+            }
         }
     }
     if (rc) { delete c; return rc; }
@@ -1649,7 +1677,7 @@ int32_t metasd_set_context(metasd_ctx* c, int32_t seq, const int32_t* tokens, in
     for (const auto& q : c->sq) all = all && q.ready;
     c->phase = all ? PH_READY : PH_NONE;
     c->target.kvl[seq] = kv_prefilled ? n - 1 : 0;
-    for (auto& d : c->drafters) d.kvl[seq] = kv_prefilled ? n - 1 : 0;
+    for (auto& d : c->drafters) d.kvl[seq] = (kv_prefilled || d.shared_kv) ? n - 1 : 0;
     if (!kv_prefilled && n > 1) {
         if (c->cfg.batch == 1) { if (int rc = forward(c, c->target, 0, n - 1, nullptr, false)) return rc; }
         else if (int rc = catch_up(c, c->target, std::vector<int>{seq}, std::vector<int>{n - 1}, nullptr, 0, 0)) return rc;
@@ -1713,6 +1741,7 @@ int32_t metasd_draft(metasd_ctx* c, const int32_t* k, int32_t gamma) {
         return METASD_OK;
     }
     if (c->sq[0].l + gamma + 1 > c->cfg.max_ctx) return c->fail(METASD_E_OVERFLOW, "draft: l + gamma + 1 = %d exceeds max_ctx %d", c->sq[0].l + gamma + 1, c->cfg.max_ctx);
+    sync_shared_kv(c);
     Model& D = c->drafters[k[0]];
     const int V = D.d.vocab, l = c->sq[0].l;
     const float T = c->cfg.temperature;
@@ -1783,6 +1812,7 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
     c->target.kvl[0] = l + n;
     c->drafters[c->sq[0].cur_k].kvl[0] = std::min(l + n, l + gamma - 1);
     c->sq[0].round += 1;
+    sync_shared_kv(c);
     c->phase = PH_READY;
     if (n_acc_out) *n_acc_out = n;
     if (token_out) *token_out = token;
@@ -1919,6 +1949,31 @@ int32_t metasd_profile_read(metasd_ctx* c, int32_t kind, double* ms_total, int64
     if (ms_total) *ms_total = ms;
     if (launches) *launches = n;
     if (bytes_total) *bytes_total = by;
+    return METASD_OK;
+}
+
+int32_t metasd_profile_shapes(metasd_ctx* c, int32_t target_only, int32_t max_rows, int32_t* n_out, int32_t* k_out, int32_t* m_out,
+                              double* ms_out, int64_t* launches_out, double* bytes_out, int32_t* rows_out) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (max_rows < 1 || !n_out || !k_out || !m_out || !ms_out || !launches_out || !bytes_out || !rows_out)
+        return c->fail(METASD_E_INVALID, "profile_shapes: bad argument");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    int rows = 0;
+    for (size_t i = 0; i < c->prof_used; ++i) {
+        const metasd_ctx::ProfRec& r = c->prof[i];
+        if (r.kind != METASD_PROF_GEMM || (target_only && r.model != -1)) continue;
+        int at = 0;
+        while (at < rows && !(n_out[at] == r.n && k_out[at] == r.k && m_out[at] == r.m)) ++at;
+        if (at == rows) {
+            if (rows == max_rows) continue;               // table full: further shapes are left out
+            n_out[at] = r.n; k_out[at] = r.k; m_out[at] = r.m; ms_out[at] = 0.0; launches_out[at] = 0; bytes_out[at] = 0.0;
+            ++rows;
+        }
+        float t = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&t, r.a, r.b));
+        ms_out[at] += t; launches_out[at] += 1; bytes_out[at] += r.bytes;
+    }
+    *rows_out = rows;
     return METASD_OK;
 }
 

@@ -71,6 +71,8 @@ class LockStep:
         assert (hist_gpu[:n_gpu] == d[:n_gpu]).all() and hist_gpu[n_gpu] == tok_gpu     # committed on the device too
         # ---- oracle, teacher-forced on the GPU's draft tokens
         D = self.drafters[k]
+        if getattr(D, "shares_kv", False):               # reads the target's cache: never a backlog
+            self.c[k] = l - 1
         Qo = np.empty((gamma, V), np.float32)
         Qo[0] = D.forward(self.hist[self.c[k]: l], self.c[k], "last")
         u_d = [oracle.uniform(seed, sq, t, j, oracle.STREAM_DRAFT) for j in range(gamma)]
@@ -132,6 +134,9 @@ class LockStep:
         self.hist[l + n] = tok_gpu
         self.l = l + n + 1
         self.c[k] = min(l + n, l + gamma - 1)
+        for i, Di in enumerate(self.drafters):
+            if getattr(Di, "shares_kv", False):
+                self.c[i] = self.l - 1
         self.t += 1
         rew = oracle.reward_be(n, gamma) if self.reward == "BE" else bd_gpu
         self.bandit.update(k, rew)

@@ -15,14 +15,14 @@ from test_gpu_bf16 import SMALL, TOL, oracle_models
 pytestmark = pytest.mark.gpu
 
 
-def batch_pair(cfg, T, prompts, logit_tol, reward="BE", kv_prefilled=False, policy="ucb", **kw):
+def batch_pair(cfg, T, prompts, logit_tol, reward="BE", kv_prefilled=False, policy="ucb", share_kv=False, **kw):
     td, tw = cfg["target"]
     B = len(prompts)
     g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=cfg["gamma"], max_ctx=cfg["max_ctx"], temperature=T, seed=cfg["seed"],
-                 ucb_beta=cfg["beta"], reward=reward, batch=B, policy=policy, **kw)
+                 ucb_beta=cfg["beta"], reward=reward, batch=B, policy=policy, share_target_kv=share_kv, **kw)
     seqs = []
     for b, p in enumerate(prompts):
-        ot, od = oracle_models(cfg)                     # own KV caches per sequence
+        ot, od = oracle_models(cfg, share_kv)           # own KV caches per sequence
         seqs.append((ot, od))
     return g, seqs
 
@@ -114,15 +114,17 @@ def test_fp32_batch_of_six_more_than_sixteen_rows():
     g.close()
 
 
-def test_bf16_gqa_early_exit_batch():
+@pytest.mark.parametrize("share_kv", [False, True])
+def test_bf16_gqa_early_exit_batch(share_kv):
     """Grouped-query attention (8 query heads on 2 KV heads) and early-exit drafters that share the target's
-    tensors, 5 sequences x 6 rows, real prefill of prompts of different lengths."""
+    tensors, 5 sequences x 6 rows, real prefill of prompts of different lengths; with caches of their own, and
+    reading the target's (each sequence's drafter reads that sequence's target cache)."""
     td = W.model_desc(4, 256, 8, 2, 512, 1024, W.SWIGLU, W.BF16)
     tw = W.gen_weights(td, 0)
     drafters = [W.early_exit_drafter(td, tw, e, 0.01, 100 + k) for k, e in enumerate((1, 2, 3))]
     cfg = dict(target=(td, tw), drafters=drafters, gamma=5, beta=1.0, seed=1, max_ctx=150 + 64)
     prompts = [W.prompt_tokens(150 - 29 * b, 1024, 40 + b) for b in range(5)]
-    g, seqs = batch_pair(cfg, 1.0, prompts, TOL)
+    g, seqs = batch_pair(cfg, 1.0, prompts, TOL, share_kv=share_kv)
     bl = make_lockstep(g, cfg, seqs, prompts, 1.0, TOL)
     for r in range(5):
         bl.round(None if r < 3 else [(b + r) % 3 for b in range(5)])

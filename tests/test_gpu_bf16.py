@@ -14,7 +14,8 @@ pytestmark = pytest.mark.gpu
 TOL = 3e-2
 
 
-def oracle_models(cfg):
+def oracle_models(cfg, share_kv=False):
+    """share_kv: early-exit drafters (their layer tensors are the target's) read the target's cache on the oracle side too."""
     td, tw = cfg["target"]
     tw_np = W.to_numpy(tw)
     cache = {id(t): a for t, a in zip(tw, tw_np) if t is not None}
@@ -22,13 +23,15 @@ def oracle_models(cfg):
     od = []
     for dd, dw in cfg["drafters"]:
         arrs = [None if t is None else (cache[id(t)] if id(t) in cache else W.to_numpy([t])[0]) for t in dw]
-        od.append(oracle.Model(dd, arrs, cfg["max_ctx"]))
+        early_exit = all(a is b for a, b in zip(dw[: 1 + 9 * dd["n_layers"]], tw))
+        od.append(oracle.Model(dd, arrs, cfg["max_ctx"], share_kv_with=ot if (share_kv and early_exit) else None))
     return ot, od
 
 
 def fill_kv(cfg, g, ot, od, ctx, device):
-    """Same seeded synthetic KV prefix on both sides (positions [0, ctx))."""
-    models = [(cfg["target"][0], g.kv_target, ot)] + [(dd, g.kv_drafters[k], od[k]) for k, (dd, _) in enumerate(cfg["drafters"])]
+    """Same seeded synthetic KV prefix on both sides (positions [0, ctx)); drafters that share the target's cache have none."""
+    models = [(cfg["target"][0], g.kv_target, ot)] + [(dd, g.kv_drafters[k], od[k]) for k, (dd, _) in enumerate(cfg["drafters"])
+                                                       if not g.kv_shared[k]]
     for i, (desc, kv_gpu, om) in enumerate(models):
         k, v = W.kv_fill(desc, ctx, cfg["kv_seed"] + i, device=device)
         kv_gpu[:, 0, :, :ctx] = k.to(kv_gpu.device)
@@ -37,11 +40,11 @@ def fill_kv(cfg, g, ot, od, ctx, device):
         om.kv(1)[:, :, :ctx] = v.float().cpu().numpy()
 
 
-def run_lockstep(cfg, T, rounds, kv_prefilled, device="cpu", swap_heads=False):
+def run_lockstep(cfg, T, rounds, kv_prefilled, device="cpu", swap_heads=False, share_kv=False, force_arms=None):
     td, tw = cfg["target"]
     g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=cfg["gamma"], max_ctx=cfg["max_ctx"], temperature=T, seed=cfg["seed"],
-                 ucb_beta=cfg["beta"])
-    ot, od = oracle_models(cfg)
+                 ucb_beta=cfg["beta"], share_target_kv=share_kv)
+    ot, od = oracle_models(cfg, share_kv)
     if kv_prefilled:
         fill_kv(cfg, g, ot, od, len(cfg["prompt"]) - 1, device)
     g.set_context(cfg["prompt"], kv_prefilled=kv_prefilled)
@@ -55,7 +58,7 @@ def run_lockstep(cfg, T, rounds, kv_prefilled, device="cpu", swap_heads=False):
                 od[k] = oracle.Model(dd, W.to_numpy(dw[:-1]) + W.to_numpy([hk]), cfg["max_ctx"])
                 od[k].kv(0)[:] = old.kv(0)                 # the head does not enter the KV cache
                 od[k].kv(1)[:] = old.kv(1)
-        ls.round()
+        ls.round(None if force_arms is None else force_arms[r])
     g.close()
     return ls.stats
 
@@ -99,6 +102,47 @@ def test_config3_1b_shape_full_size(T):
     cfg = W.config3(device="cuda")
     cfg["kv_seed"] = 7
     st = run_lockstep(cfg, T, rounds=3, kv_prefilled=True, device="cuda")
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+
+
+@pytest.mark.parametrize("T", [0.0, 1.0])
+def test_gqa_early_exit_drafters_share_the_target_cache(T):
+    """The same structure with the drafters reading the target's cache (no cache of their own, nothing recomputed when
+    the bandit switches drafters): real prefill by the target only, then rounds in which the arm changes every round,
+    including a return to a drafter that sat out; 3-row, 6-row and 1-row catch-ups never happen (every drafter step is
+    one row).  Compared with oracle drafters that share the oracle target's cache."""
+    td = W.model_desc(4, 256, 8, 2, 512, 1024, W.SWIGLU, W.BF16)
+    tw = W.gen_weights(td, 0)
+    drafters = [W.early_exit_drafter(td, tw, e, 0.01, 100 + k) for k, e in enumerate((1, 2, 3))]
+    cfg = dict(target=(td, tw), drafters=drafters, gamma=5, prompt=W.prompt_tokens(131, 1024, 3), beta=1.0, seed=1,
+               max_ctx=131 + 80)
+    st = run_lockstep(cfg, T, rounds=8, kv_prefilled=False, share_kv=True, force_arms=[None, None, None, 0, 2, 2, 1, 0])
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+
+
+def test_shared_cache_needs_the_targets_own_layers():
+    """drafter_kv[k] == target_kv is only accepted for a drafter whose layer tensors are the target's first layers."""
+    cfg = W.config4(n_layers=2, ctx=20, n_new=16, K=1, d_model=256, n_heads=4, d_ffn=512, vocab=1024, dd_model=256, dn_heads=4, dd_ffn=512)
+    td, tw = cfg["target"]
+    import ctypes as C
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=3, max_ctx=64, temperature=1.0, seed=1)      # same shapes, own weights, own cache: fine
+    L = g.L
+    tptr = (C.c_void_p * len(g._tw))(*g._tw)
+    dptr = (C.c_void_p * len(g._dw[0]))(*g._dw[0])
+    dtab = (C.POINTER(C.c_void_p) * 1)(C.cast(dptr, C.POINTER(C.c_void_p)))
+    dkv = (C.c_void_p * 1)(g.kv_target.data_ptr())                                                   # ... but on the target's cache: refused
+    h = C.c_void_p()
+    rc = L.metasd_create(C.byref(h), C.byref(g.cfg), C.byref(g._tdesc_c), g._ddesc_c, tptr, dtab, g.kv_target.data_ptr(), dkv,
+                         g.workspace.data_ptr(), g.workspace.numel(), 0)
+    assert rc == -1 and b"first" in L.metasd_last_error(None)
+    g.close()
+
+
+def test_config3_1b_shape_shared_cache():
+    """1B-shape configuration at full size with the four early-exit drafters on the target's cache; real 512-token prefill
+    (by the target alone: the drafters have nothing to prefill), 4 rounds at T = 1, one per drafter."""
+    cfg = W.config3(device="cuda")
+    st = run_lockstep(cfg, 1.0, rounds=4, kv_prefilled=False, device="cuda", share_kv=True)
     assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
 
 

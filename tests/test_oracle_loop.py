@@ -70,3 +70,47 @@ def test_drafter_catch_up_after_switch(c1):
     fresh = oracle.Model(c1["drafters"][1][0], c1["dw_np"][1], c1["max_ctx"])
     want = fresh.forward(st.hist[: r["l_before"]], 0, "last")
     assert np.abs(want - r["Q"][0]).max() < 1e-5
+
+
+def shared_models(cfg):
+    """Target and early-exit drafters that keep no cache of their own (they read and write the target's)."""
+    td, _ = cfg["target"]
+    T = oracle.Model(td, cfg["tw_np"], cfg["max_ctx"])
+    D = [oracle.Model(dd, w, cfg["max_ctx"], share_kv_with=T) for (dd, _), w in zip(cfg["drafters"], cfg["dw_np"])]
+    return T, D
+
+
+@pytest.mark.parametrize("T", [0.0, 1.0])
+def test_shared_cache_drafters_equal_own_cache_drafters(c1, T):
+    """An early-exit drafter runs the target's first layers, so the K/V it needs at committed positions are the
+    numbers the target's cache already holds (same weights, same inputs, and the oracle's arithmetic does not
+    depend on how rows are grouped into blocks).  Reading them there instead of recomputing them when the drafter
+    is switched in must therefore change nothing: the same drafter logits bit for bit, the same tokens, the same
+    arms - over a whole generation in which the bandit switches drafters."""
+    Ta, Da = models(c1)
+    a = oracle.generate(Ta, Da, c1["prompt"], c1["n_new"], c1["gamma"], T, c1["seed"], c1["beta"], keep_logits=True)
+    Tb, Db = shared_models(c1)
+    b = oracle.generate(Tb, Db, c1["prompt"], c1["n_new"], c1["gamma"], T, c1["seed"], c1["beta"], keep_logits=True)
+    assert np.array_equal(a["tokens"], b["tokens"])
+    assert [r["k"] for r in a["rounds"]] == [r["k"] for r in b["rounds"]]
+    assert len({r["k"] for r in a["rounds"]}) == 3                       # every drafter was switched in at least once
+    for ra, rb in zip(a["rounds"], b["rounds"]):
+        assert np.abs(ra["Q"] - rb["Q"]).max() <= 1e-5 and np.abs(ra["P"] - rb["P"]).max() <= 1e-5
+        assert np.array_equal(ra["Q"], rb["Q"]) and np.array_equal(ra["P"], rb["P"])
+        assert np.array_equal(ra["d"], rb["d"]) and ra["n_acc"] == rb["n_acc"] and ra["token"] == rb["token"]
+    # and a drafter whose layers are NOT the owner's first layers cannot be created on its cache
+    td = dict(c1["target"][0])
+    td["n_layers"] = 3
+    with pytest.raises(MemoryError):
+        oracle.Model(td, c1["tw_np"][:1] + c1["tw_np"][1:10] * 3 + c1["tw_np"][-2:], c1["max_ctx"], share_kv_with=Tb)
+
+
+def test_shared_cache_greedy_is_lossless(c1):
+    """Losslessness (paragraph after Alg. 3) holds for the shared-cache strategy as well: greedy speculative decoding
+    with drafters that read the target's cache reproduces target-only greedy decoding token for token."""
+    T0, _ = models(c1)
+    ref = oracle.ar_decode(T0, c1["prompt"], c1["n_new"], T=0.0)
+    for arm in (0, 2):
+        T, D = shared_models(c1)
+        out = oracle.generate(T, D, c1["prompt"], c1["n_new"], c1["gamma"], 0.0, c1["seed"], c1["beta"], policy=lambda t, a=arm: a)
+        assert np.array_equal(out["tokens"], ref)
