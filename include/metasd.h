@@ -202,6 +202,40 @@ int32_t metasd_verify(metasd_ctx*, int32_t gamma);
 int32_t metasd_accept(metasd_ctx*, int32_t gamma, int32_t* n_acc_out, int32_t* token_out, uint32_t* mask_out,
                       double* bd_out);
 
+/* ---- multi-candidate rounds: a tree of draft tokens verified in one pass with tree attention -----------------------
+ * (the white-box setting of the paper's Sec. 4, "Number of drafts": multi-draft methods verify a token tree; greedy
+ * decoding only - for T = 0 the acceptance rule follows from losslessness (the paragraph after Alg. 3): the output must
+ * be the target's own greedy continuation, so the accepted nodes are the longest path from the root on which every
+ * token is the target's most likely next token; the paper states no rule for sampled trees).
+ *
+ * The tree's SHAPE is the caller's: node 0 is the root (the last committed token); node i > 0 is the rank[i]-th most
+ * likely next token (by the drafter's logits; 0 = most likely, ties to the lower token) after node parent[i] < i.
+ * Nodes come in breadth-first order (depth never decreases), 2 <= n <= min(16, gamma_max + 1), and the nodes above
+ * the deepest level number at most gamma_max.  A chain (parent[i] = i - 1, rank 0) is ordinary greedy speculation. */
+#define METASD_MAX_TREE 16
+typedef struct {
+    int32_t n;
+    int32_t parent[METASD_MAX_TREE]; /* parent[0] ignored */
+    int32_t rank[METASD_MAX_TREE];   /* 0 .. 7; rank[0] ignored */
+} metasd_tree;
+
+/* Drafter k fills the tree level by level: one forward pass per level over that level's nodes (each node attends to
+ * the committed tokens and to its own ancestors, and is rotated for position l - 1 + depth), then the children of
+ * every node of the level get their tokens.  The first pass consumes the drafter's backlog of committed tokens as in
+ * metasd_draft.  Contexts with batch == 1 and temperature == 0 only.
+ * Errors: INVALID (shape, k, not greedy, batch > 1), OVERFLOW, ORDER, HIP. */
+int32_t metasd_draft_tree(metasd_ctx*, int32_t k, const metasd_tree* tree);
+/* One target pass over all n nodes with the same tree attention; node i's K/V go to cache slot l - 1 + i for now;
+ * fp32 logits [n][V] on the device (METASD_PEEK_P).  Errors: ORDER, HIP. */
+int32_t metasd_verify_tree(metasd_ctx*);
+/* Greedy acceptance: from the root, step to the child that carries the target's most likely token, as long as there is
+ * one; N_acc = steps taken, emitted token = the target's most likely token at the last node reached.  The K/V of the
+ * accepted nodes are moved from their tree slots to their positions (target and drafter caches), history, KV lengths
+ * and round counter are committed.  path_out (host, may be NULL): the accepted nodes, N_acc entries.  The BE reward of
+ * the round is N_acc / (depth of the tree): pass that depth as `gamma` to metasd_bandit_update.
+ * Synchronises.  Errors: ORDER, HIP. */
+int32_t metasd_accept_tree(metasd_ctx*, int32_t* n_acc_out, int32_t* token_out, int32_t* path_out);
+
 /* ---- stand-alone kernels on caller-supplied logits (device) ------------------------------------ */
 
 /* Accept step on rows of logits: P [rows][gamma+1][V], Q [rows][gamma][V] fp32, d [rows][gamma]
@@ -282,7 +316,7 @@ int32_t metasd_profile_shapes(metasd_ctx*, int32_t target_only, int32_t max_rows
 #define METASD_PEEK_Q 1     /* float [gamma_max][V]    drafter logits of the last draft */
 #define METASD_PEEK_HIST 2  /* int32 [batch][max_ctx]  token history (committed + speculative) */
 #define METASD_PEEK_BD 3    /* double [gamma_max]      sum_v min(p_j, q_j) of the last accept */
-#define METASD_PEEK_DRAFT 4 /* int32 [gamma_max]       draft tokens d_1..d_gamma of the last draft */
+#define METASD_PEEK_DRAFT 4 /* int32 [gamma_max + 1]   draft tokens d_1..d_gamma of the last draft; tree rounds: the token of every node (entry 0, the root, unused) */
 /* Device pointer and byte size of an internal buffer (valid until metasd_destroy). */
 int32_t metasd_peek(metasd_ctx*, int32_t what, void** dev_ptr_out, size_t* bytes_out);
 

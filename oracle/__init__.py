@@ -17,6 +17,11 @@ What pins each function (all in ``tests/test_oracle_*.py``, CPU only):
                     block-vs-single-row consistency, RoPE closed forms on head_dim 2 and 4.
 * ``generate``    - greedy speculative decoding equals target-only greedy decoding token for
                     token (Alg. 3 is lossless); accounting identity B = tau + sum N_acc.
+* ``Model.forward_rows`` / ``tree_round`` - tree attention and greedy tree acceptance: a chain-shaped tree equals
+                    ``Model.forward`` / ``sd_round`` bit for bit; a branching tree attends exactly like a chain along each
+                    root-to-node path; greedy tree decoding equals target-only greedy decoding token for token for good
+                    and bad drafters; the caches after compaction equal those of a model fed the committed tokens
+                    (``tests/test_oracle_tree.py``).
 * ``policies``    - discounted / sliding-window UCB, sequential halving, EXP3, uniform random (the
                     paper's appendix "Extensions"): hand-worked runs in ``tests/golden/policies_hand.txt``,
                     reductions to Alg. 2, EXP3 closed forms (``tests/test_oracle_policies.py``).
@@ -75,6 +80,8 @@ def lib():
         L.om_model_kv.argtypes = [C.c_void_p, C.c_int]
         L.om_forward.restype = C.c_int
         L.om_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int]
+        L.om_forward_rows.restype = C.c_int
+        L.om_forward_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.om_philox.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p]
         L.om_uniform.restype = C.c_float
         L.om_uniform.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]
@@ -181,6 +188,22 @@ class Model:
             rc = lib().om_forward(self._h, _ptr(tok), m, pos0, None, 0)
         if rc != 0:
             raise ValueError("om_forward: bad arguments (tokens / positions out of range)")
+        return out
+
+
+    def forward_rows(self, tokens, slots, positions, allow, want_logits: bool = True):
+        """Rows that need not form a chain (tree attention): row r writes its K/V to cache slot slots[r], is rotated for
+        positions[r] and attends to the slots p with allow[r, p] != 0.  Returns logits [m, V] (or None)."""
+        tok = np.ascontiguousarray(tokens, np.int32)
+        sl = np.ascontiguousarray(slots, np.int32)
+        ps = np.ascontiguousarray(positions, np.int32)
+        al = np.ascontiguousarray(allow, np.uint8)
+        m = tok.shape[0]
+        assert sl.shape == (m,) and ps.shape == (m,) and al.shape == (m, self.max_ctx)
+        out = np.empty((m, self.desc["vocab"]), np.float32) if want_logits else None
+        rc = lib().om_forward_rows(self._h, _ptr(tok), m, _ptr(sl), _ptr(ps), _ptr(al), _ptr(out) if want_logits else None)
+        if rc != 0:
+            raise ValueError("om_forward_rows: bad arguments")
         return out
 
 
@@ -329,4 +352,5 @@ def reward_bd(bd: np.ndarray) -> float:
 
 
 from .loop import SdState, sd_round, generate, ar_decode  # noqa: E402,F401
+from .tree import Tree, tree_round, generate_tree  # noqa: E402,F401
 from . import policies  # noqa: E402,F401

@@ -57,7 +57,7 @@ def sd_round(target, drafter, k: int, st: SdState, gamma: int, T: float, seed: i
     # --- commit: d_1..d_n stay, the emitted token follows them
     st.hist[l + n] = r["token"]
     st.l = l + n + 1
-    st.c[k] = min(l + n, l + gamma - 1)
+    st.c[k] = st.l - 1 if getattr(drafter, "shares_kv", False) else min(l + n, l + gamma - 1)
     out = dict(k=k, round=st.t, l_before=l, d=d.copy(), P=P, Q=Q, u_acc=u_acc, u_res=u_res,
                draft_margin=draft_margin, **r)
     st.t += 1

@@ -10,6 +10,8 @@
  *   om_forward      - the "M_p(x | x_1..x_l, ...)" / "M_q(...)" of Alg. 3 (speculative sampling):
  *                     a Llama-style decoder (Sec. 4 "Experimental setup": Llama architecture, SiLU)
  *                     run over a block of m positions against a KV cache.
+ *   om_forward_rows - the same decoder over rows that form a token tree rather than a chain (tree attention,
+ *                     Sec. 4 "Number of drafts"): per-row cache slot, position and set of visible slots.
  *   om_sample       - "x ~ M_q(...)" (Alg. 3, drafting loop) by inverse CDF, or argmax for T=0.
  *   om_accept       - Alg. 3, the accept / residual-resample / bonus-token part, plus the
  *                     per-position 1 - d_TV(p, q) terms of the block-divergence reward (Def. 2).
@@ -301,6 +303,110 @@ int om_forward(om_model *M, const int32_t *tokens, int m, int pos0, float *logit
             rmsnorm(d, h, m, D, fn, a);
             matmul(d, a, m, D, head, V, logits);
         }
+    }
+    free(h); free(a); free(q); free(k); free(v); free(o); free(y); free(g); free(u);
+    return 0;
+}
+
+/*
+ * Forward over m rows that need not form a chain: tree attention (Sec. 4, "Number of drafts": multi-draft methods
+ * verify a token tree with a tree-attention mechanism).  Row r carries token tokens[r]; its K/V are written to cache
+ * slot slot[r]; its q and k are rotated for position pos[r]; it attends to exactly the cache slots p with
+ * allow[r * max_ctx + p] != 0 (the caller lists them: the committed positions, the row's ancestors in the tree, the
+ * row itself).  All rows' K/V are written before any row attends, so a row may attend to slots written by other rows
+ * of the same call.  Everything else is om_forward's arithmetic, step for step; logits [m][V] (or NULL).
+ * With slot[r] = pos[r] = pos0 + r and allow = (p <= pos0 + r) this IS om_forward.
+ */
+int om_forward_rows(om_model *M, const int32_t *tokens, int m, const int32_t *slot, const int32_t *pos,
+                    const uint8_t *allow, float *logits) {
+    const om_desc *d = &M->d;
+    const int D = d->d_model, H = d->n_heads, KH = d->n_kv_heads, hd = M->hd, F = d->d_ffn, V = d->vocab;
+    const int DQ = H * hd, DKV = KH * hd;
+    if (m <= 0) return -1;
+    for (int r = 0; r < m; ++r)
+        if (tokens[r] < 0 || tokens[r] >= V || slot[r] < 0 || slot[r] >= M->max_ctx || pos[r] < 0) return -1;
+
+    float *h = (float *)malloc(sizeof(float) * (size_t)m * D);
+    float *a = (float *)malloc(sizeof(float) * (size_t)m * D);
+    float *q = (float *)malloc(sizeof(float) * (size_t)m * DQ);
+    float *k = (float *)malloc(sizeof(float) * (size_t)m * DKV);
+    float *v = (float *)malloc(sizeof(float) * (size_t)m * DKV);
+    float *o = (float *)malloc(sizeof(float) * (size_t)m * DQ);
+    float *y = (float *)malloc(sizeof(float) * (size_t)m * D);
+    float *g = (float *)malloc(sizeof(float) * (size_t)m * F);
+    float *u = (float *)malloc(sizeof(float) * (size_t)m * F);
+
+    const void *embed = M->w[0];
+    for (int r = 0; r < m; ++r)
+        for (int i = 0; i < D; ++i) h[(size_t)r * D + i] = (float)wget(d, embed, (size_t)tokens[r] * D + i);
+
+    for (int L = 0; L < d->n_layers; ++L) {
+        const void *const *w = M->w + 1 + OM_PER_LAYER * L;
+        rmsnorm(d, h, m, D, w[0], a);
+        matmul(d, a, m, D, w[1], DQ, q);
+        matmul(d, a, m, D, w[2], DKV, k);
+        matmul(d, a, m, D, w[3], DKV, v);
+        for (int r = 0; r < m; ++r) {
+            for (int hh = 0; hh < H; ++hh) om_rope(q + (size_t)r * DQ + (size_t)hh * hd, hd, pos[r], d->rope_theta);
+            for (int kh = 0; kh < KH; ++kh) {
+                float *kv = k + (size_t)r * DKV + (size_t)kh * hd;
+                om_rope(kv, hd, pos[r], d->rope_theta);
+                size_t base = (((size_t)L * KH + kh) * M->max_ctx + (size_t)slot[r]) * hd;
+                for (int i = 0; i < hd; ++i) {
+                    M->kc[base + i] = rnd(d, kv[i]);
+                    M->vc[base + i] = rnd(d, v[(size_t)r * DKV + (size_t)kh * hd + i]);
+                }
+            }
+        }
+        const double scale = 1.0 / sqrt((double)hd);
+#pragma omp parallel for schedule(static)
+        for (int hh = 0; hh < H; ++hh) {
+            int kh = hh / (H / KH);
+            const float *Kc = M->kc + ((size_t)L * KH + kh) * (size_t)M->max_ctx * hd;
+            const float *Vc = M->vc + ((size_t)L * KH + kh) * (size_t)M->max_ctx * hd;
+            double *s = (double *)malloc(sizeof(double) * (size_t)M->max_ctx);
+            double *acc = (double *)malloc(sizeof(double) * (size_t)hd);
+            for (int r = 0; r < m; ++r) {
+                const float *qv = q + (size_t)r * DQ + (size_t)hh * hd;
+                const uint8_t *al = allow + (size_t)r * M->max_ctx;
+                double mx = -INFINITY;
+                for (int p = 0; p < M->max_ctx; ++p) {
+                    if (!al[p]) continue;
+                    double dot = 0.0;
+                    for (int i = 0; i < hd; ++i) dot += (double)qv[i] * (double)Kc[(size_t)p * hd + i];
+                    s[p] = dot * scale;
+                    if (s[p] > mx) mx = s[p];
+                }
+                double Z = 0.0;
+                for (int p = 0; p < M->max_ctx; ++p)
+                    if (al[p]) { s[p] = exp(s[p] - mx); Z += s[p]; }
+                for (int i = 0; i < hd; ++i) acc[i] = 0.0;
+                for (int p = 0; p < M->max_ctx; ++p) {
+                    if (!al[p]) continue;
+                    double pw = s[p] / Z;
+                    for (int i = 0; i < hd; ++i) acc[i] += pw * (double)Vc[(size_t)p * hd + i];
+                }
+                for (int i = 0; i < hd; ++i) o[(size_t)r * DQ + (size_t)hh * hd + i] = (float)acc[i];
+            }
+            free(s); free(acc);
+        }
+        matmul(d, o, m, DQ, w[4], D, y);
+        for (size_t i = 0; i < (size_t)m * D; ++i) h[i] = (float)((double)h[i] + (double)y[i]);
+
+        rmsnorm(d, h, m, D, w[5], a);
+        matmul(d, a, m, D, w[7], F, u);
+        if (d->act == 1) {
+            matmul(d, a, m, D, w[6], F, g);
+            for (size_t i = 0; i < (size_t)m * F; ++i) u[i] = (float)(silu((double)g[i]) * (double)u[i]);
+        } else {
+            for (size_t i = 0; i < (size_t)m * F; ++i) u[i] = (float)gelu_erf((double)u[i]);
+        }
+        matmul(d, u, m, F, w[8], D, y);
+        for (size_t i = 0; i < (size_t)m * D; ++i) h[i] = (float)((double)h[i] + (double)y[i]);
+    }
+    if (logits) {
+        rmsnorm(d, h, m, D, M->w[1 + OM_PER_LAYER * d->n_layers], a);
+        matmul(d, a, m, D, M->w[2 + OM_PER_LAYER * d->n_layers], V, logits);
     }
     free(h); free(a); free(q); free(k); free(v); free(o); free(y); free(g); free(u);
     return 0;

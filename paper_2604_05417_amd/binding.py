@@ -13,7 +13,7 @@ MATRIX_SLOTS = (1, 2, 3, 4, 6, 7, 8)          # wq wk wv wo w_gate w_up w_down w
 
 EXPORTS = ["metasd_kv_bytes", "metasd_workspace_bytes", "metasd_pack_weight", "metasd_create", "metasd_destroy",
            "metasd_set_context", "metasd_swap_weight", "metasd_bandit_select", "metasd_bandit_update",
-           "metasd_bandit_state", "metasd_draft", "metasd_verify", "metasd_accept", "metasd_accept_logits",
+           "metasd_bandit_state", "metasd_draft", "metasd_verify", "metasd_accept", "metasd_draft_tree", "metasd_verify_tree", "metasd_accept_tree", "metasd_accept_logits",
            "metasd_accept_logits_noalloc", "metasd_sample_logits", "metasd_philox_words", "metasd_stream_read", "metasd_profile", "metasd_profile_read", "metasd_profile_shapes", "metasd_peek", "metasd_state", "metasd_state_seq", "metasd_accept_fallbacks", "metasd_last_error"]
 
 
@@ -33,6 +33,10 @@ class _Config(C.Structure):
     _fields_ = [("K", C.c_int32), ("gamma_max", C.c_int32), ("batch", C.c_int32), ("max_ctx", C.c_int32),
                 ("temperature", C.c_float), ("reward", C.c_int32), ("ucb_beta", C.c_double), ("seed", C.c_uint64),
                 ("policy", C.c_int32), ("policy_window", C.c_int32), ("policy_param", C.c_double)]
+
+
+class _Tree(C.Structure):
+    _fields_ = [("n", C.c_int32), ("parent", C.c_int32 * 16), ("rank", C.c_int32 * 16)]
 
 
 def lib_path() -> str:
@@ -67,6 +71,9 @@ def load_library():
         "metasd_draft": [vp, C.POINTER(i32), i32],
         "metasd_verify": [vp, i32],
         "metasd_accept": [vp, i32, vp, vp, vp, vp],
+        "metasd_draft_tree": [vp, i32, C.POINTER(_Tree)],
+        "metasd_verify_tree": [vp],
+        "metasd_accept_tree": [vp, C.POINTER(i32), C.POINTER(i32), vp],
         "metasd_accept_logits": [vp, vp, vp, i32, i32, i32, f32, u64, u32, u32, vp, vp, vp, vp, vp, vp],
         "metasd_accept_logits_noalloc": [vp, vp, vp, i32, i32, i32, f32, u64, u32, u32, vp, vp, vp, vp, vp],
         "metasd_sample_logits": [vp, i32, i32, f32, u64, u32, u32, u32, vp, vp],
@@ -262,6 +269,23 @@ class MetaSD:
         if B == 1:
             return int(n[0]), int(tok[0]), int(mask[0]), float(bd[0])
         return n, tok, mask, bd
+
+    # ---- tree rounds (greedy contexts): parent[i], rank[i] per node, node 0 the root
+    def draft_tree(self, k: int, parent, rank):
+        n = len(parent)
+        assert len(rank) == n and n <= 16
+        t = _Tree(n, (C.c_int32 * 16)(*[int(v) for v in parent]), (C.c_int32 * 16)(*[int(v) for v in rank]))
+        _check(self.L.metasd_draft_tree(self._h, k, C.byref(t)), self._h)
+
+    def verify_tree(self):
+        _check(self.L.metasd_verify_tree(self._h), self._h)
+
+    def accept_tree(self):
+        """(n_acc, token, path): path = the accepted nodes."""
+        n, tok = C.c_int32(0), C.c_int32(0)
+        path = np.zeros(16, np.int32)
+        _check(self.L.metasd_accept_tree(self._h, C.byref(n), C.byref(tok), path.ctypes.data_as(C.c_void_p)), self._h)
+        return int(n.value), int(tok.value), [int(v) for v in path[: n.value]]
 
     def peek(self, what: str, gamma: int | None = None) -> torch.Tensor:
         """View of an internal device buffer: 'P' [gamma_max+1, V], 'Q' [gamma_max, V], 'hist' [max_ctx], 'bd' [gamma_max],

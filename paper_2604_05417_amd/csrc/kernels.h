@@ -1004,6 +1004,23 @@ __global__ void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restr
 }
 
 // ------------------------------------------------------------------------------------------
+// Token trees (multi-candidate verification with tree attention, the white-box setting of the paper's Sec. 4).
+// A tree block holds nodes of a draft tree in breadth-first order: node 0 is the root (the last committed token, cache slot
+// and position `base`), node i > 0 hangs under a node with a lower index.  Node i lives in cache slot base + i, is rotated
+// for position base + depth(i), and attends to every committed position (< base) and to its ancestors and itself.
+// Block row r is node i0 + r.  on == 0: an ordinary causal block (row r at slot = position pos0 + r).
+constexpr int TREE_MAX = 16;
+struct TreeBlk {
+    int on, base, i0;
+    uint16_t anc[TREE_MAX];    // bit j: node j is this node or one of its ancestors
+    uint8_t depth[TREE_MAX];
+};
+__device__ __forceinline__ bool tree_allowed(const TreeBlk& tb, int p, int row) {
+    const int j = p - tb.base;
+    return j < 0 || (j < TREE_MAX && ((tb.anc[tb.i0 + row] >> j) & 1));
+}
+
+// ------------------------------------------------------------------------------------------
 // RoPE (rotate-half pairing, angle = pos * theta^(-2i/hd)) on q and k, K/V cache append.
 //   part: split-K partials of the fused q|k|v projection, [s][r][N], N = (H + 2 KH) * hd.
 //   q out fp32 [m][H*hd] (q_split: as two bf16 arrays, see below); cache planes (type T) [kv_head][max_ctx][hd].
@@ -1071,14 +1088,15 @@ __device__ __forceinline__ void rope_kv_body(const float* __restrict__ part, int
 // threads of row r's workgroup) tab[r][i] = (cos, sin)((pos0 + r) * theta^(-2i/hd)).   grid (m), block 256
 template <typename T>
 __global__ void embed_rope_kernel(const int32_t* __restrict__ tok, const T* __restrict__ E, int d, float* __restrict__ h, int pos0,
-                                  int hd, float theta, double2* __restrict__ tab) {
+                                  int hd, float theta, double2* __restrict__ tab, TreeBlk tb) {
     const int r = blockIdx.x, i = threadIdx.x, half = hd >> 1;
     const size_t t = (size_t)tok[r];
     for (int k = i; k < d; k += blockDim.x) h[(size_t)r * d + k] = El<T>::ld(E[t * d + k]);
     if (i < half) {
         const double freq = pow((double)theta, -2.0 * (double)i / (double)hd);
+        const int pos = tb.on ? tb.base + (int)tb.depth[tb.i0 + r] : pos0 + r;     // a tree node is rotated for its depth, not its slot
         double sn, cs;
-        sincos((double)(pos0 + r) * freq, &sn, &cs);
+        sincos((double)pos * freq, &sn, &cs);
         tab[r * half + i] = make_double2(cs, sn);
     }
 }
@@ -1103,7 +1121,8 @@ constexpr int ATT_CH = 128;
 template <typename T, int HD>
 __device__ __forceinline__ void attn_partial_body(const float* __restrict__ q, const T* __restrict__ kc,
                                                   const T* __restrict__ vc, int m, int pos0, int H, int KH, int max_ctx,
-                                                  float scale, float* __restrict__ part, int nchunks, int c, int h) {
+                                                  float scale, float* __restrict__ part, int nchunks, int c, int h,
+                                                  const TreeBlk* tb = nullptr) {
     constexpr int EPV = 16 / (int)sizeof(T);     // elements per 16-byte piece
     constexpr int RS = HD + EPV;                 // padded LDS row stride (elements)
     constexpr int VPR = HD / EPV;                // 16-byte pieces per row
@@ -1157,7 +1176,10 @@ __device__ __forceinline__ void attn_partial_body(const float* __restrict__ q, c
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int r = rbeg + j;
-                if (r < m) ss[r * ATT_CH + p] = (p < np && p0 + p <= pos0 + r) ? acc[j] * scale : -INFINITY;
+                if (r < m) {
+                    const bool see = tb ? tree_allowed(*tb, p0 + p, r) : (p0 + p <= pos0 + r);
+                    ss[r * ATT_CH + p] = (p < np && see) ? acc[j] * scale : -INFINITY;
+                }
             }
         }
     }
@@ -1222,6 +1244,13 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float* __restri
                                                            int max_ctx, float scale, float* __restrict__ part, int nchunks) {
     attn_partial_body<T, HD>(q, kc, vc, m, pos0, H, KH, max_ctx, scale, part, nchunks, (int)blockIdx.x, (int)blockIdx.y);
 }
+// the same for a tree block (row r = node tb.i0 + r in slot pos0 + r)
+template <typename T, int HD>
+__global__ __launch_bounds__(256) void attn_partial_tree_kernel(const float* __restrict__ q, const T* __restrict__ kc,
+                                                                const T* __restrict__ vc, int m, int pos0, int H, int KH,
+                                                                int max_ctx, float scale, float* __restrict__ part, int nchunks, TreeBlk tb) {
+    attn_partial_body<T, HD>(q, kc, vc, m, pos0, H, KH, max_ctx, scale, part, nchunks, (int)blockIdx.x, (int)blockIdx.y, &tb);
+}
 
 // bf16-cache variant on MFMA.  One workgroup (4 wavefronts) per (chunk of 128 positions, query head):
 //   S^T[pos][row] = K[pos][:] . q[row][:]   A = K rows straight from global (16 B per lane, no LDS),
@@ -1241,7 +1270,7 @@ template <int HD, bool MULTI = false>
 __device__ __forceinline__ void attn_partial_mfma_body(const float* __restrict__ q, const bf16_t* __restrict__ kc,
                                                        const bf16_t* __restrict__ vc, int m, int pos0, int H, int KH,
                                                        int max_ctx, float scale, float* __restrict__ part, int nchunks, int c,
-                                                       int h, size_t q_lo_off, int cpw = 1, int rec = 0) {
+                                                       int h, size_t q_lo_off, int cpw = 1, int rec = 0, const TreeBlk* tb = nullptr) {
     constexpr int RS = HD + 8;                 // padded LDS row stride of the V chunk (elements)
     constexpr int VPR = HD / 8;                // 16-byte pieces per row
     constexpr int PS = ATT_CH + 8;             // padded row stride of P (elements)
@@ -1319,7 +1348,8 @@ __device__ __forceinline__ void attn_partial_mfma_body(const float* __restrict__
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int pl = wave * 32 + t * 16 + g * 4 + v;
-                const bool ok = rowok && pl < np && (p0 + pl) <= pos0 + row;
+                const bool see = tb ? tree_allowed(*tb, p0 + pl, rowok ? row : 0) : (p0 + pl) <= pos0 + row;
+                const bool ok = rowok && pl < np && see;
                 const float x = ok ? sacc[t][v] * scale : -INFINITY;
                 sv[t * 4 + v] = x;
                 lmax = fmaxf(lmax, x);
@@ -1417,6 +1447,14 @@ __global__ __launch_bounds__(256) void attn_partial_mfma_kernel(const float* __r
                                                                 int max_ctx, float scale, float* __restrict__ part, int nchunks) {
     attn_partial_mfma_body<HD>(q, kc, vc, m, pos0, H, KH, max_ctx, scale, part, nchunks, (int)blockIdx.x, (int)blockIdx.y,
                                (size_t)m * H * HD);
+}
+template <int HD>
+__global__ __launch_bounds__(256) void attn_partial_mfma_tree_kernel(const float* __restrict__ q, const bf16_t* __restrict__ kc,
+                                                                     const bf16_t* __restrict__ vc, int m, int pos0, int H, int KH,
+                                                                     int max_ctx, float scale, float* __restrict__ part, int nchunks,
+                                                                     TreeBlk tb) {
+    attn_partial_mfma_body<HD>(q, kc, vc, m, pos0, H, KH, max_ctx, scale, part, nchunks, (int)blockIdx.x, (int)blockIdx.y,
+                               (size_t)m * H * HD, 1, 0, &tb);
 }
 
 // Merge of the chunk records of (head h, block row r): nchunks records are merged, records of one head are
@@ -2223,6 +2261,95 @@ __global__ __launch_bounds__(AK_NT) void sample_rows_kernel(const float* __restr
     if (threadIdx.x == 0) {
         tok[(size_t)b * tok_stride] = token;
         if (tok_copy) tok_copy[b] = token;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Greedy draft trees: the children of a node are its drafter's most likely next tokens.
+
+struct TreeShape {
+    int n;                          // nodes including the root
+    int8_t parent[TREE_MAX];        // parent[0] = -1; parent[i] < i
+    int8_t rank[TREE_MAX];          // node i is the rank[i]-th most likely next token after its parent (0 = most likely)
+};
+constexpr int TREE_RANKS = 8;
+
+// Row r holds the drafter's logits at node node0 + r.  The TREE_RANKS largest logits of the row are found in order (ties: the
+// lower token first) and every child of the node gets its token: hist[base + i] = tok[i] = winner[rank[i]].
+//   grid (rows), block 512
+__global__ __launch_bounds__(AK_NT) void tree_children_kernel(const float* __restrict__ logits, int V, TreeShape ts, int node0,
+                                                              int32_t* __restrict__ hist_base, int32_t* __restrict__ tok) {
+    __shared__ AkShared sm;
+    __shared__ int win[TREE_RANKS];
+    const int node = node0 + (int)blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float x[AK_CH][4];
+    ak_load(logits + (size_t)blockIdx.x * V, V, wave, lane, x);
+    int need = 0;                                   // ranks 0 .. need-1 are used by some child
+    for (int i = node + 1; i < ts.n; ++i)
+        if (ts.parent[i] == node) need = max(need, (int)ts.rank[i] + 1);
+    for (int k = 0; k < need; ++k) {
+        __syncthreads();                            // the previous turn's readers of sm are done
+        const int w = ak_argmax(x, sm, wave, lane);
+        if (threadIdx.x == 0) win[k] = w;
+#pragma unroll
+        for (int c = 0; c < AK_CH; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (wave * AK_SEG + c * 256 + lane * 4 + e == w) x[c][e] = -INFINITY;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0)
+        for (int i = node + 1; i < ts.n; ++i)
+            if (ts.parent[i] == node) {
+                const int t = win[ts.rank[i]];
+                hist_base[i] = t;
+                tok[i] = t;
+            }
+}
+
+// Greedy acceptance over a verified tree: amax[i] = the target's most likely token after node i.  Walk from the root:
+// while the current node has a child whose token is the target's choice, step to it.  n_acc = nodes stepped to,
+// token = the target's choice at the last node reached.  res: [0] n_acc, [1] token, [2 ..] the nodes of the path.
+// Commits the tokens: hist_base[1 + j] = tok[path[j]], hist_base[1 + n_acc] = token.     grid (1), block 64
+__global__ void accept_tree_kernel(const int32_t* __restrict__ amax, const int32_t* __restrict__ tok, TreeShape ts,
+                                   int32_t* __restrict__ res, int32_t* __restrict__ hist_base) {
+    if (threadIdx.x != 0) return;
+    int cur = 0, n = 0;
+    int path[TREE_MAX];
+    for (;;) {
+        const int want = amax[cur];
+        int next = -1;
+        for (int i = cur + 1; i < ts.n && next < 0; ++i)
+            if (ts.parent[i] == cur && tok[i] == want) next = i;
+        if (next < 0) break;
+        path[n++] = next;
+        cur = next;
+    }
+    const int token = amax[cur];
+    res[0] = n;
+    res[1] = token;
+    for (int j = 0; j < n; ++j) res[2 + j] = path[j];
+    for (int j = 0; j < n; ++j) hist_base[1 + j] = tok[path[j]];     // path[j] >= j + 1: reads from tok, a separate array
+    hist_base[1 + n] = token;
+}
+
+// After acceptance the K/V of the accepted nodes move from their tree slots to the positions they were rotated for:
+// slot base + path[j] -> base + 1 + j for j < n (path[j] >= j + 1 and ascending, so a thread that owns one element
+// offset and walks j upwards never overwrites a source it still needs).   grid (ceil(planes * hd / 256)), block 256
+// res: the result words of accept_tree_kernel (n_acc, token, path); limit: at most this many leading path nodes are moved
+// (a drafter has only processed the nodes above the deepest level).
+template <typename T>
+__global__ void kv_compact_kernel(T* __restrict__ kv, int planes, int max_ctx, int hd, int base, const int32_t* __restrict__ res, int limit,
+                                  int nodes) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;      // (plane, element of a row)
+    if (i >= (size_t)planes * hd) return;
+    const size_t plane = i / hd, e = i - plane * hd;
+    T* row0 = kv + (plane * max_ctx + base) * hd + e;
+    const int n = min(min(res[0], limit), nodes - 1);
+    for (int j = 0; j < n; ++j) {
+        const int src = min(max(res[2 + j], 1), nodes - 1), dst = 1 + j;        // clamped: stays inside the tree's slots whatever res holds
+        if (src != dst) row0[(size_t)dst * hd] = row0[(size_t)src * hd];
     }
 }
 

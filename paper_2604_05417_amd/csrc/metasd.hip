@@ -209,8 +209,8 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     L.Q = take(B * c.gamma_max * vmax * 4);
     L.cand = take(B * (c.gamma_max + 1) * sizeof(int2));
     L.bd = take(B * c.gamma_max * sizeof(double));
-    L.res = take(std::max<size_t>(64, B * 12));
-    L.draft = take(std::max<size_t>(64, B * c.gamma_max * 4));
+    L.res = take(std::max<size_t>(128, B * 12));                   // batch 1: also the path of a tree round (2 + 15 words)
+    L.draft = take(std::max<size_t>(64, B * (c.gamma_max + 1) * 4)); // chain: gamma tokens per sequence; tree: one per node
     L.bar = take(sizeof(GridBar));
     L.xchg = take(B * (c.gamma_max + 1) * AS_XCHG_BYTES);
     int lmax = t.n_layers;
@@ -366,7 +366,7 @@ struct Bandit {
 };
 
 
-enum Phase { PH_NONE = 0, PH_READY, PH_DRAFTED, PH_VERIFIED };
+enum Phase { PH_NONE = 0, PH_READY, PH_DRAFTED, PH_VERIFIED, PH_TREE_DRAFTED, PH_TREE_VERIFIED };
 
 }  // namespace
 
@@ -412,6 +412,12 @@ struct metasd_ctx {
     float cur_eps = 1e-5f;           // rms_eps of the model whose forward is being launched
     bool fuse_small = true;          // short blocks of narrow bf16 models use the GEMMs with fused prologues (METASD_FUSE_SMALL=0: off)
     int n_cu = 0;
+    const TreeBlk* tree = nullptr;   // set while a block of draft-tree nodes is being launched (positions and mask of its rows)
+    TreeShape tshape{};              // the tree of the running round (metasd_draft_tree)
+    int tdepth[TREE_MAX] = {};       // depth of every node, tlevel[d] = first node of depth d (tlevel[max depth + 1] = n)
+    int tlevel[TREE_MAX + 2] = {};
+    int tmaxdepth = 0;
+    uint16_t tanc[TREE_MAX] = {};
     int accept_fallbacks = 0;        // accept steps taken again with one workgroup per position after an exchange timeout
     std::vector<ProfRec> prof;       // event pool
     size_t prof_used = 0;
@@ -622,8 +628,9 @@ int gemm_pro(metasd_ctx* c, const GemmPro& pro, int m, int K, const void* W0, in
     return 0;
 }
 
+// combine == false: only the per-chunk records (the consumer merges them itself)
 template <typename T, int HD>
-int attention_hd(metasd_ctx* c, const Model& M, int L, int pos0, int m) {
+int attention_hd(metasd_ctx* c, const Model& M, int L, int pos0, int m, bool combine) {
     const metasd_model_desc& d = M.d;
     const size_t plane = (size_t)d.n_kv_heads * c->cfg.max_ctx * HD;
     const T* kc = (const T*)M.kv + (size_t)L * 2 * plane;
@@ -635,15 +642,26 @@ int attention_hd(metasd_ctx* c, const Model& M, int L, int pos0, int m) {
                                                                  (double)m * d.n_heads * HD * 4);
     hipEvent_t ea = pr ? pr->a : nullptr, eb = pr ? pr->b : nullptr;
     if constexpr (sizeof(T) == 2 && HD >= 64) {
-        hipExtLaunchKernelGGL((attn_partial_mfma_kernel<HD>), dim3(nchunks, d.n_heads), dim3(256), 0u, c->stream, ea, eb, 0u,
-                              (const float*)c->d_q(), kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale,
-                              c->d_apart(), nchunks);
+        if (c->tree)
+            hipExtLaunchKernelGGL((attn_partial_mfma_tree_kernel<HD>), dim3(nchunks, d.n_heads), dim3(256), 0u, c->stream, ea, eb, 0u,
+                                  (const float*)c->d_q(), kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale,
+                                  c->d_apart(), nchunks, *c->tree);
+        else
+            hipExtLaunchKernelGGL((attn_partial_mfma_kernel<HD>), dim3(nchunks, d.n_heads), dim3(256), 0u, c->stream, ea, eb, 0u,
+                                  (const float*)c->d_q(), kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale,
+                                  c->d_apart(), nchunks);
     } else {
-        hipExtLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(nchunks, d.n_heads), dim3(256), 0u, c->stream, ea, eb, 0u,
-                              (const float*)c->d_q(), kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale,
-                              c->d_apart(), nchunks);
+        if (c->tree)
+            hipExtLaunchKernelGGL((attn_partial_tree_kernel<T, HD>), dim3(nchunks, d.n_heads), dim3(256), 0u, c->stream, ea, eb, 0u,
+                                  (const float*)c->d_q(), kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale,
+                                  c->d_apart(), nchunks, *c->tree);
+        else
+            hipExtLaunchKernelGGL((attn_partial_kernel<T, HD>), dim3(nchunks, d.n_heads), dim3(256), 0u, c->stream, ea, eb, 0u,
+                                  (const float*)c->d_q(), kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale,
+                                  c->d_apart(), nchunks);
     }
     LAUNCH_CHECK(c, "attn_partial");
+    if (!combine) return 0;
     hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3(d.n_heads, m), dim3(HD), 0, c->stream, c->d_apart(), nchunks,
                        d.n_heads, (float*)c->d_ao(), sizeof(T) == 2 ? 1 : 0);
     LAUNCH_CHECK(c, "attn_combine");
@@ -651,12 +669,12 @@ int attention_hd(metasd_ctx* c, const Model& M, int L, int pos0, int m) {
 }
 
 template <typename T>
-int attention(metasd_ctx* c, const Model& M, int L, int pos0, int m) {
+int attention(metasd_ctx* c, const Model& M, int L, int pos0, int m, bool combine = true) {
     switch (M.hd) {
-        case 32: return attention_hd<T, 32>(c, M, L, pos0, m);
-        case 64: return attention_hd<T, 64>(c, M, L, pos0, m);
+        case 32: return attention_hd<T, 32>(c, M, L, pos0, m, combine);
+        case 64: return attention_hd<T, 64>(c, M, L, pos0, m, combine);
         default:
-            if constexpr (sizeof(T) == 2) return attention_hd<T, 128>(c, M, L, pos0, m);
+            if constexpr (sizeof(T) == 2) return attention_hd<T, 128>(c, M, L, pos0, m, combine);
             return c->fail(METASD_E_INVALID, "fp32 head_dim 128 unsupported");
     }
 }
@@ -676,7 +694,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
     int ns = 0, rc;
     constexpr int split = sizeof(T) == 2 ? 1 : 0;   // bf16 models: activations for the GEMM are stored as two bf16 arrays
     hipLaunchKernelGGL(embed_rope_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, h, pos0, hd, d.rope_theta,
-                       c->d_rope());
+                       c->d_rope(), c->tree ? *c->tree : TreeBlk{});
     LAUNCH_CHECK(c, "embed + rope table");
     for (int L = 0; L < d.n_layers; ++L) {
         // h += previous FFN output (split partials); xn = norm(h)
@@ -737,7 +755,7 @@ int forward_rows_residual(metasd_ctx* c, Model& M, int pos0, int m, float* logit
     int ns = 0, rc, ntg = 0;
     c->cur_eps = d.rms_eps;
     hipLaunchKernelGGL(embed_rope_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, h, pos0, hd, d.rope_theta,
-                       c->d_rope());
+                       c->d_rope(), c->tree ? *c->tree : TreeBlk{});
     LAUNCH_CHECK(c, "embed + rope table");
     // first norm: a plain RMSNorm of the embedding rows (normalised x, no scaling downstream)
     hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, 0, (size_t)m * D, D, (const T*)M.layer_w(0, 0), d.rms_eps,
@@ -800,7 +818,7 @@ int forward_rows_fused(metasd_ctx* c, Model& M, int pos0, int m, float* logits, 
     hipStream_t st = c->stream;
     int hp = 0, pp = 0, ns = 0, rc;     // current residual buffer, current partials buffer, partials in it
     hipLaunchKernelGGL(embed_rope_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, c->d_h_pp(0), pos0, hd,
-                       d.rope_theta, c->d_rope());
+                       d.rope_theta, c->d_rope(), c->tree ? *c->tree : TreeBlk{});
     LAUNCH_CHECK(c, "embed + rope table");
     auto norm_pro = [&](const void* gain, int row0) {
         GemmPro p{};
@@ -824,18 +842,7 @@ int forward_rows_fused(metasd_ctx* c, Model& M, int pos0, int m, float* logits, 
         hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, c->d_part_pp(pp), ns, (size_t)m * NQKV, NQKV, pos0, H,
                            KH, hd, (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, 1, 1, (const float*)nullptr);
         LAUNCH_CHECK(c, "rope_kv");
-        {
-            const float scale = 1.0f / sqrtf((float)hd);
-            metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_ATTN, 2.0 * KH * (double)(pos0 + m) * hd * 2 + (double)m * H * hd * 4);
-            hipEvent_t ea = pr ? pr->a : nullptr, eb = pr ? pr->b : nullptr;
-            if (hd == 64)
-                hipExtLaunchKernelGGL((attn_partial_mfma_kernel<64>), dim3(nchunks, H), dim3(256), 0u, st, ea, eb, 0u, (const float*)c->d_q(),
-                                      (const T*)kc, (const T*)(kc + plane), m, pos0, H, KH, c->cfg.max_ctx, scale, c->d_apart(), nchunks);
-            else
-                hipExtLaunchKernelGGL((attn_partial_mfma_kernel<128>), dim3(nchunks, H), dim3(256), 0u, st, ea, eb, 0u, (const float*)c->d_q(),
-                                      (const T*)kc, (const T*)(kc + plane), m, pos0, H, KH, c->cfg.max_ctx, scale, c->d_apart(), nchunks);
-            LAUNCH_CHECK(c, "attn_partial");
-        }
+        if ((rc = attention<T>(c, M, L, pos0, m, false))) return rc;
         // output projection of the merged attention output
         {
             GemmPro p{};
@@ -1471,6 +1478,19 @@ int accept_batch(metasd_ctx* c, int gamma, int32_t* n_acc_out, int32_t* token_ou
 
 }  // namespace
 
+namespace {
+template <typename T>
+int compact_kv(metasd_ctx* c, Model& M, int base, int limit) {
+    const int planes = M.d.n_layers * 2 * M.d.n_kv_heads;
+    const size_t total = (size_t)planes * M.hd;
+    hipLaunchKernelGGL(kv_compact_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, c->stream, (T*)M.kv, planes, c->cfg.max_ctx, M.hd,
+                       base, (const int32_t*)c->d_res(), limit, c->tshape.n);
+    LAUNCH_CHECK(c, "kv_compact");
+    return 0;
+}
+
+}  // namespace
+
 // ================================================================================================ C ABI
 
 extern "C" {
@@ -1662,7 +1682,7 @@ int32_t metasd_set_context(metasd_ctx* c, int32_t seq, const int32_t* tokens, in
     if (n + c->cfg.gamma_max + 1 > c->cfg.max_ctx) return c->fail(METASD_E_OVERFLOW, "set_context: n + gamma_max + 1 = %d exceeds max_ctx %d", n + c->cfg.gamma_max + 1, c->cfg.max_ctx);
     for (int i = 0; i < n; ++i)
         if (tokens[i] < 0 || tokens[i] >= c->target.d.vocab) return c->fail(METASD_E_INVALID, "set_context: token %d out of range at %d", tokens[i], i);
-    if (c->phase == PH_DRAFTED || c->phase == PH_VERIFIED)
+    if (c->phase == PH_DRAFTED || c->phase == PH_VERIFIED || c->phase == PH_TREE_DRAFTED || c->phase == PH_TREE_VERIFIED)
         return c->fail(METASD_E_ORDER, "set_context: a round is in flight (finish it with metasd_accept first)");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     metasd_ctx::SeqState& S = c->sq[seq];
@@ -1822,6 +1842,125 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
         for (int j = 0; j < gamma; ++j) s += hbd[j];
         *bd_out = s / (double)gamma;
     }
+    return METASD_OK;
+}
+
+// ---- token trees (greedy): draft a tree of candidates, verify it in one pass with tree attention, accept the longest
+// path that the target's own greedy choices follow
+
+int32_t metasd_draft_tree(metasd_ctx* c, int32_t k, const metasd_tree* tree) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (c->cfg.batch != 1) return c->fail(METASD_E_INVALID, "draft_tree: contexts with one sequence only");
+    if (c->cfg.temperature != 0.f) return c->fail(METASD_E_INVALID, "draft_tree: greedy contexts only (temperature 0): the paper states no acceptance rule for sampled trees");
+    if (k < 0 || k >= c->cfg.K || !tree) return c->fail(METASD_E_INVALID, "draft_tree: bad drafter index or NULL tree");
+    if (c->phase != PH_READY) return c->fail(METASD_E_ORDER, "draft_tree: call set_context first / finish the previous round");
+    const int n = tree->n;
+    if (n < 2 || n > TREE_MAX || n > c->cfg.gamma_max + 1) return c->fail(METASD_E_INVALID, "draft_tree: tree of %d nodes; 2 .. min(%d, gamma_max + 1) supported", n, TREE_MAX);
+    TreeShape ts{};
+    ts.n = n;
+    ts.parent[0] = -1;
+    c->tdepth[0] = 0;
+    c->tanc[0] = 1;
+    for (int i = 1; i < n; ++i) {
+        const int p = tree->parent[i], r = tree->rank[i];
+        if (p < 0 || p >= i || r < 0 || r >= TREE_RANKS) return c->fail(METASD_E_INVALID, "draft_tree: node %d: parent must be an earlier node, rank 0..%d", i, TREE_RANKS - 1);
+        c->tdepth[i] = c->tdepth[p] + 1;
+        if (c->tdepth[i] < c->tdepth[i - 1]) return c->fail(METASD_E_INVALID, "draft_tree: nodes must come in breadth-first order (depth never decreases)");
+        for (int j = 1; j < i; ++j)
+            if (tree->parent[j] == p && tree->rank[j] == r) return c->fail(METASD_E_INVALID, "draft_tree: nodes %d and %d are the same child of node %d", j, i, p);
+        ts.parent[i] = (int8_t)p;
+        ts.rank[i] = (int8_t)r;
+        c->tanc[i] = (uint16_t)(c->tanc[p] | (1u << i));
+    }
+    c->tmaxdepth = c->tdepth[n - 1];
+    for (int d = 0, i = 0; d <= c->tmaxdepth + 1; ++d) {
+        while (i < n && c->tdepth[i] < d) ++i;
+        c->tlevel[d] = i;
+    }
+    if (c->tlevel[c->tmaxdepth] > c->cfg.gamma_max) return c->fail(METASD_E_INVALID, "draft_tree: %d nodes above the deepest level exceed gamma_max %d", c->tlevel[c->tmaxdepth], c->cfg.gamma_max);
+    const int l = c->sq[0].l, base = l - 1;
+    if (l + n + 1 > c->cfg.max_ctx) return c->fail(METASD_E_OVERFLOW, "draft_tree: l + nodes + 1 = %d exceeds max_ctx %d", l + n + 1, c->cfg.max_ctx);
+    sync_shared_kv(c);
+    Model& D = c->drafters[k];
+    const int V = D.d.vocab;
+    TreeBlk tb{};
+    tb.on = 1; tb.base = base;
+    for (int i = 0; i < n; ++i) { tb.anc[i] = c->tanc[i]; tb.depth[i] = (uint8_t)c->tdepth[i]; }
+    for (int d = 0; d < c->tmaxdepth; ++d) {
+        const int i0 = c->tlevel[d], m = c->tlevel[d + 1] - i0;
+        float* Qd = c->d_Q() + (size_t)i0 * V;
+        int rc;
+        if (d == 0) rc = forward(c, D, D.kvl[0], l - D.kvl[0], Qd, false);      // the committed backlog, ending with the root
+        else {
+            tb.i0 = i0;
+            c->tree = &tb;
+            rc = forward(c, D, base + i0, m, Qd, true);
+            c->tree = nullptr;
+        }
+        if (rc) return rc;
+        hipLaunchKernelGGL(tree_children_kernel, dim3(m), dim3(AK_NT), 0, c->stream, (const float*)Qd, V, ts, i0, c->d_hist() + base, c->d_draft());
+        LAUNCH_CHECK(c, "tree_children");
+    }
+    c->tshape = ts;
+    c->sq[0].cur_k = k;
+    c->phase = PH_TREE_DRAFTED;
+    return METASD_OK;
+}
+
+int32_t metasd_verify_tree(metasd_ctx* c) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (c->phase != PH_TREE_DRAFTED) return c->fail(METASD_E_ORDER, "verify_tree: draft_tree has not been run for this round");
+    const int n = c->tshape.n, base = c->sq[0].l - 1;
+    TreeBlk tb{};
+    tb.on = 1; tb.base = base; tb.i0 = 0;
+    for (int i = 0; i < n; ++i) { tb.anc[i] = c->tanc[i]; tb.depth[i] = (uint8_t)c->tdepth[i]; }
+    c->tree = &tb;
+    const int rc = forward(c, c->target, base, n, c->d_P(), true);
+    c->tree = nullptr;
+    if (rc) return rc;
+    c->phase = PH_TREE_VERIFIED;
+    return METASD_OK;
+}
+
+int32_t metasd_accept_tree(metasd_ctx* c, int32_t* n_acc_out, int32_t* token_out, int32_t* path_out) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (c->phase != PH_TREE_VERIFIED) return c->fail(METASD_E_ORDER, "accept_tree: verify_tree has not been run for this round");
+    const int n = c->tshape.n, V = c->target.d.vocab, l = c->sq[0].l, base = l - 1;
+    int32_t* amax = reinterpret_cast<int32_t*>(c->d_cand());
+    if (launch_sample(c->stream, c->d_P(), n, V, 0.f, c->cfg.seed, 0u, 0u, 0u, amax, 1, nullptr)) return c->fail(METASD_E_HIP, "launch argmax failed");
+    hipLaunchKernelGGL(accept_tree_kernel, dim3(1), dim3(64), 0, c->stream, (const int32_t*)amax, (const int32_t*)c->d_draft(), c->tshape, c->d_res(),
+                       c->d_hist() + base);
+    LAUNCH_CHECK(c, "accept_tree");
+    Model& D = c->drafters[c->sq[0].cur_k];
+    int rc = c->target.d.dtype == METASD_BF16 ? compact_kv<bf16_t>(c, c->target, base, TREE_MAX) : compact_kv<float>(c, c->target, base, TREE_MAX);
+    if (!rc && !D.shared_kv)
+        rc = D.d.dtype == METASD_BF16 ? compact_kv<bf16_t>(c, D, base, c->tmaxdepth - 1) : compact_kv<float>(c, D, base, c->tmaxdepth - 1);
+    if (rc) return rc;
+    if ((rc = c->fetch_results())) return rc;
+    if (c->mirror<GridBar>(c->lay.bar)->abort) {
+        (void)hipMemsetAsync(c->d_bar(), 0, sizeof(GridBar), c->stream);
+        c->phase = PH_NONE;
+        return c->fail(METASD_E_HIP, "a bounded device-side wait between workgroups timed out (split-K reduction); call metasd_set_context to start over");
+    }
+    const int32_t* hres = c->mirror<int32_t>(c->lay.res);
+    const int32_t* htok = c->mirror<int32_t>(c->lay.draft);
+    const int na = hres[0], token = hres[1];
+    if (na < 0 || na > c->tmaxdepth || token < 0 || token >= V) return c->fail(METASD_E_HIP, "accept_tree: device returned n_acc %d token %d", na, token);
+    for (int j = 0; j < na; ++j) {
+        const int node = hres[2 + j];
+        if (node < 1 || node >= n) return c->fail(METASD_E_HIP, "accept_tree: device returned path node %d", node);
+        c->sq[0].hist[l + j] = htok[node];
+        if (path_out) path_out[j] = node;
+    }
+    c->sq[0].hist[l + na] = token;
+    c->sq[0].l = l + na + 1;
+    c->target.kvl[0] = l + na;
+    D.kvl[0] = std::min(l + na, l + c->tmaxdepth - 1);
+    c->sq[0].round += 1;
+    sync_shared_kv(c);
+    c->phase = PH_READY;
+    if (n_acc_out) *n_acc_out = na;
+    if (token_out) *token_out = token;
     return METASD_OK;
 }
 
@@ -1988,7 +2127,7 @@ int32_t metasd_peek(metasd_ctx* c, int32_t what, void** dev_ptr_out, size_t* byt
         case METASD_PEEK_Q: *dev_ptr_out = c->d_Q(); *bytes_out = (size_t)c->cfg.batch * c->cfg.gamma_max * V * 4; break;
         case METASD_PEEK_HIST: *dev_ptr_out = c->d_hist(); *bytes_out = (size_t)c->cfg.batch * c->cfg.max_ctx * 4; break;
         case METASD_PEEK_BD: *dev_ptr_out = c->d_bd(); *bytes_out = (size_t)c->cfg.batch * c->cfg.gamma_max * 8; break;
-        case METASD_PEEK_DRAFT: *dev_ptr_out = c->d_draft(); *bytes_out = (size_t)c->cfg.batch * c->cfg.gamma_max * 4; break;
+        case METASD_PEEK_DRAFT: *dev_ptr_out = c->d_draft(); *bytes_out = (size_t)c->cfg.batch * (c->cfg.gamma_max + 1) * 4; break;
         default: return c->fail(METASD_E_INVALID, "peek: unknown buffer %d", what);
     }
     return METASD_OK;

@@ -1,0 +1,212 @@
+"""GPU parity of multi-candidate (tree) rounds in greedy mode against the oracle: the drafter fills a tree of candidates
+level by level with tree attention, the target verifies all nodes in one pass, the longest path of the target's own
+greedy choices is accepted, the K/V of the accepted nodes move to their positions.  Every round is compared:
+  - the children the GPU gave every node are the drafter's most likely tokens by the GPU's own logits (exact);
+  - drafter logits at every node above the deepest level and target logits at every node, against the oracle run on
+    the GPU's tokens (tolerance);
+  - the accepted path and the emitted token are the walk on the GPU's own target logits (exact), and the oracle's own
+    outcome (exact for fp32; bf16: differences only where the top-2 gap is inside twice the logit tolerance);
+  - committed history, lengths and KV lengths; later rounds run on the compacted caches, so a wrong move shows up as
+    a logit mismatch.
+For the fp32 configuration the whole output equals the oracle's target-only greedy decoding token for token."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2604_05417_amd as M
+import workloads as W
+from lockstep import top2_gap
+from oracle.tree import Tree, ranked_tokens
+from test_gpu_bf16 import SMALL, TOL, fill_kv, oracle_models
+
+pytestmark = pytest.mark.gpu
+
+
+class TreeLockStep:
+    def __init__(self, gpu, target, drafters, prompt, tree, beta, tol, kv_prefilled=False):
+        self.g, self.T, self.D, self.tree, self.tol = gpu, target, drafters, tree, tol
+        hist = np.zeros(target.max_ctx, np.int32)
+        hist[: len(prompt)] = prompt
+        self.st = oracle.SdState(hist=hist, l=len(prompt), c=[len(prompt) - 1 if kv_prefilled else 0] * len(drafters))
+        if not kv_prefilled and len(prompt) > 1:
+            target.forward(prompt[:-1], 0, None)
+        self.bandit = oracle.Ucb(len(drafters), beta)
+        self.stats = dict(rounds=0, max_dp=0.0, max_dq=0.0, ties=0, n_acc=[], branch=0)
+
+    def round(self, force_k=None):
+        g, t, st, tol = self.g, self.tree, self.st, self.tol
+        k_gpu, k_or = g.bandit_select(), self.bandit.select()
+        assert k_gpu == k_or
+        k = k_gpu if force_k is None else force_k
+        l = st.l
+        g.draft_tree(k, t.parent, t.rank)
+        g.verify_tree()
+        n, token, path = g.accept_tree()
+        Pg = g.peek("P")[: t.n].cpu().numpy()
+        Qg = g.peek("Q")[: t.n - 1].cpu().numpy() if t.n - 1 <= g.gamma_max else None
+        tok = g.peek("draft")[: t.n].cpu().numpy().copy()
+        hist = g.peek("hist")[l: l + n + 1].cpu().numpy()
+        inner = [i for i in range(t.n) if t.depth[i] < t.max_depth]
+        exact = tol <= 1e-3
+        # children by the GPU's own drafter logits
+        for i in inner:
+            ch = t.children(i)
+            if ch:
+                best = ranked_tokens(Qg[i], max(t.rank[j] for j in ch) + 1)
+                for j in ch:
+                    if tok[j] != best[t.rank[j]]:
+                        srt = np.sort(Qg[i])[::-1]
+                        assert np.min(np.abs(np.diff(srt[: t.rank[j] + 2]))) < 1e-6, f"node {j}: token {tok[j]} is not rank {t.rank[j]} of its parent's logits"
+                        self.stats["ties"] += 1
+        # the walk on the GPU's own target logits
+        amax = [int(np.argmax(Pg[i])) for i in range(t.n)]
+        cur, walk = 0, []
+        while True:
+            nxt = [j for j in t.children(cur) if tok[j] == amax[cur]]
+            if not nxt:
+                break
+            cur = nxt[0]
+            walk.append(cur)
+        if (walk, amax[cur]) != (path, token):
+            assert any(top2_gap(Pg[i]) < 1e-6 for i in [0] + walk), f"round {st.t}: GPU path {path} token {token}, walk on its own logits {walk} {amax[cur]}"
+            self.stats["ties"] += 1
+        assert (hist[:n] == tok[path]).all() and hist[n] == token
+        # the oracle on the GPU's tokens, committing the GPU's outcome
+        r = oracle.tree_round(self.T, self.D[k], k, st, t, tokens=tok, outcome=(path, token))
+        dq = float(np.abs(r["Q"][inner] - Qg[inner]).max())
+        dp = float(np.abs(r["P"] - Pg).max())
+        self.stats["max_dq"], self.stats["max_dp"] = max(self.stats["max_dq"], dq), max(self.stats["max_dp"], dp)
+        assert dq <= tol and dp <= tol, f"round {st.t - 1}: logits differ by {dq} (drafter) / {dp} (target)"
+        same_tokens = np.array_equal(r["own_tok"][1:], tok[1:])        # entry 0 is the root: not a draft token
+        if (r["own_path"], r["own_token"]) != (path, token) or not same_tokens:
+            tie = any(top2_gap(r["P"][i]) < 2 * tol for i in range(t.n)) or not same_tokens
+            assert tie and not exact, (f"round {st.t - 1}: oracle outcome {r['own_path']} {r['own_token']} vs GPU {path} {token}; "
+                                       f"oracle tokens {r['own_tok'].tolist()} vs GPU {tok.tolist()}")
+            self.stats["ties"] += 1
+        self.bandit.update(k, oracle.reward_be(n, t.max_depth))
+        g.bandit_update(k, n, t.max_depth)
+        lg, kvg, rg = g.state(-1)
+        assert (lg, kvg, rg) == (st.l, st.l - 1, st.t)
+        assert g.state(k)[1] == st.c[k]
+        self.stats["rounds"] += 1
+        self.stats["n_acc"].append(n)
+        self.stats["branch"] += sum(1 for i in path if t.rank[i] > 0)
+        return n, token
+
+
+def make(cfg, tree, tol, share_kv=False, kv_prefilled=False, device="cpu"):
+    td, tw = cfg["target"]
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=15, max_ctx=cfg["max_ctx"], temperature=0.0, seed=cfg["seed"], ucb_beta=cfg["beta"],
+                 share_target_kv=share_kv)
+    ot, od = oracle_models(cfg, share_kv)
+    if kv_prefilled:
+        fill_kv(cfg, g, ot, od, len(cfg["prompt"]) - 1, device)
+    g.set_context(cfg["prompt"], kv_prefilled=kv_prefilled)
+    return g, TreeLockStep(g, ot, od, cfg["prompt"], tree, cfg["beta"], tol, kv_prefilled=kv_prefilled)
+
+
+@pytest.mark.parametrize("kind", ["wide", "bushy", "chain5"])
+def test_fp32_tree_rounds_are_lossless(kind):
+    """Tiny fp32 configuration (head_dim 32: the plain attention kernel), drafters = the target's layers with noisy heads;
+    64 new tokens; the output is the oracle's target-only greedy decoding token for token."""
+    cfg = W.config1_tree()
+    tree = Tree(**W.draft_tree(kind))
+    g, ls = make(cfg, tree, 1e-4)
+    l0 = len(cfg["prompt"])
+    while ls.st.l < l0 + 64:
+        ls.round()
+    ref = oracle.ar_decode(oracle.Model(cfg["target"][0], W.to_numpy(cfg["target"][1]), cfg["max_ctx"]), cfg["prompt"], 64, T=0.0)
+    assert np.array_equal(ls.st.hist[l0: l0 + 64], ref)
+    out = g.peek("hist")[l0: l0 + 64].cpu().numpy()
+    assert np.array_equal(out, ref)
+    st = ls.stats
+    assert st["ties"] == 0 and max(st["n_acc"]) >= 3 and (kind == "chain5" or st["branch"] >= 1), st
+    g.close()
+
+
+@pytest.mark.parametrize("i,share", [(0, False), (2, False), (0, True)])
+def test_bf16_tree_rounds(i, share):
+    """Small bf16 targets (head_dim 64 and 128: the MFMA attention kernel with the tree mask), prompts spanning several
+    attention chunks with a ragged tail, drafters = the target's first layers (all of them, or all but one) with a noisy head,
+    with caches of their own or on the target's; arms forced so that a drafter returns after sitting out."""
+    s = SMALL[i]
+    td = W.model_desc(s["n_layers"], s["d_model"], s["n_heads"], s["n_heads"], s["d_ffn"], s["vocab"], W.SWIGLU, W.BF16)
+    tw = W.gen_weights(td, 0)
+    drafters = [W.early_exit_drafter(td, tw, e, sg, 300 + k) for k, (e, sg) in enumerate(((s["n_layers"], 0.0), (s["n_layers"], 0.004), (s["n_layers"] - 1, 0.0)))]
+    cfg = dict(target=(td, tw), drafters=drafters, prompt=W.prompt_tokens(s["prompt"], s["vocab"], 3), beta=1.0, seed=1, max_ctx=s["prompt"] + 100)
+    g, ls = make(cfg, Tree(**W.draft_tree("wide")), TOL, share_kv=share)
+    for k in (None, None, None, 1, 0, 1, 2, 0):
+        ls.round(k)
+    st = ls.stats
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties"] <= 2 and max(st["n_acc"]) >= 3, st
+    g.close()
+
+
+def test_tree_round_with_separate_drafters_and_backlog():
+    """Drafters with weights and caches of their own (two layers, narrower than the target): the first pass of a tree
+    round consumes the drafter's backlog of committed tokens as a chain, later levels are tree blocks; bushy tree."""
+    s = SMALL[0]
+    cfg = W.config4(n_layers=s["n_layers"], ctx=s["prompt"], n_new=64, K=2, d_model=s["d_model"], n_heads=s["n_heads"], d_ffn=s["d_ffn"],
+                    vocab=s["vocab"], dd_model=s["dd_model"], dn_heads=s["dn_heads"], dd_ffn=s["dd_ffn"])
+    cfg["max_ctx"] = s["prompt"] + 100
+    g, ls = make(cfg, Tree(**W.draft_tree("bushy")), TOL)
+    for k in (None, None, 0, 0, 1, 0):
+        ls.round(k)
+    st = ls.stats
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties"] <= 2, st
+    g.close()
+
+
+def test_tree_rounds_need_a_greedy_single_sequence_context_and_a_valid_tree():
+    cfg = W.config1_tree()
+    td, tw = cfg["target"]
+    t = W.draft_tree("wide")
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=15, max_ctx=cfg["max_ctx"], temperature=1.0, seed=1)
+    g.set_context(cfg["prompt"])
+    with pytest.raises(M.MetaSDError) as e:                 # sampling: no acceptance rule for trees
+        g.draft_tree(0, t["parent"], t["rank"])
+    assert e.value.code == -1
+    g.close()
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=15, max_ctx=cfg["max_ctx"], temperature=0.0, seed=1)
+    with pytest.raises(M.MetaSDError) as e:                 # no context yet
+        g.draft_tree(0, t["parent"], t["rank"])
+    assert e.value.code == -3
+    g.set_context(cfg["prompt"])
+    with pytest.raises(M.MetaSDError):                      # a child before its parent
+        g.draft_tree(0, [-1, 2, 0], [0, 0, 0])
+    with pytest.raises(M.MetaSDError):                      # not breadth-first
+        g.draft_tree(0, [-1, 0, 1, 0], [0, 0, 0, 1])
+    with pytest.raises(M.MetaSDError):                      # the same child twice
+        g.draft_tree(0, [-1, 0, 0], [0, 1, 1])
+    with pytest.raises(M.MetaSDError) as e:                 # verify before draft
+        g.verify_tree()
+    assert e.value.code == -3
+    g.draft_tree(0, t["parent"], t["rank"])
+    with pytest.raises(M.MetaSDError) as e:                 # a chain round's verify does not follow a tree draft
+        g.verify(5)
+    assert e.value.code == -3
+    g.verify_tree()
+    n, tok, path = g.accept_tree()
+    assert 0 <= n <= 5 and len(path) == n
+    k = g.bandit_select()
+    g.draft(k, 4)                                           # chain rounds and tree rounds mix freely
+    g.verify(4)
+    g.accept(4)
+    g.close()
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=5, max_ctx=cfg["max_ctx"], temperature=0.0, seed=1)
+    g.set_context(cfg["prompt"])
+    with pytest.raises(M.MetaSDError):                      # 13 nodes need gamma_max >= 12
+        g.draft_tree(0, t["parent"], t["rank"])
+    g.close()
+
+
+def test_config4_7b_shape_tree_round_full_size():
+    """7B-shape target at full size, KV context 2048 (synthetic prefix), separate two-layer drafters: two greedy tree rounds
+    (13 nodes: a 13-row verification block with the tree mask across 17 attention chunks), every logit compared."""
+    cfg = W.config4(device="cuda")
+    g, ls = make(cfg, Tree(**W.draft_tree("wide")), TOL, kv_prefilled=True, device="cuda")
+    for _ in range(2):
+        ls.round()
+    st = ls.stats
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties"] <= 1, st
+    g.close()

@@ -175,3 +175,28 @@ def config4(device: str = "cpu", n_layers: int = 32, ctx: int = 2048, n_new: int
     return dict(name="C4", target=(td, tw), drafters=drafters, heads=heads, seg_len=seg_len, gamma=5,
                 prompt=prompt_tokens(ctx, vocab, 3), n_new=n_new, beta=1.0, seed=1, ctx=ctx,
                 max_ctx=ctx + n_new + 16, T=1.0, kv_seed=7)
+
+
+def draft_tree(kind: str = "wide") -> dict:
+    """Shapes of draft trees for multi-candidate rounds (parent, rank per node; node 0 the root; breadth-first order).
+    'wide': 13 nodes, depth 5 - three candidates after the root, two after the likeliest nodes of the next levels, the
+    likeliest path kept to depth 5 (a small stand-in for the static trees of the multi-draft methods the paper cites;
+    it gives no tree of its own).  'chain5': ordinary speculation with gamma = 5 written as a tree."""
+    if kind == "chain5":
+        return dict(parent=[-1, 0, 1, 2, 3, 4], rank=[0] * 6)
+    if kind == "bushy":          # 16 nodes, depth 3: many siblings per level (ranks up to 4)
+        return dict(parent=[-1, 0, 0, 0, 0, 0, 1, 1, 1, 2, 2, 3, 6, 6, 7, 9], rank=[0, 0, 1, 2, 3, 4, 0, 1, 2, 0, 1, 0, 0, 1, 0, 0])
+    return dict(parent=[-1, 0, 0, 0, 1, 1, 2, 4, 4, 5, 7, 7, 10], rank=[0, 0, 1, 2, 0, 1, 0, 0, 1, 0, 0, 1, 0])
+
+
+def config1_tree(device: str = "cpu") -> dict:
+    """The tiny fp32 configuration for multi-candidate (tree) rounds, greedy mode.  With random weights an early exit
+    after layer 1 almost never shares the target's argmax, so depth would never be exercised; the drafters here run all
+    of the target's layers and differ by the noise on their LM head, sigma = (0, 0.005, 0.02): always / often / rarely
+    the target's choice, often as a second candidate."""
+    cfg = config1(device)
+    td, tw = cfg["target"]
+    cfg["drafters"] = [early_exit_drafter(td, tw, td["n_layers"], s, 200 + k) for k, s in enumerate((0.0, 0.005, 0.02))]
+    cfg["name"] = "C1-tree"
+    cfg["max_ctx"] = 16 + 64 + 32
+    return cfg
