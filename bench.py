@@ -137,13 +137,15 @@ def main():
 
     # ---- phase pass: the same kind of steps with events between the three phases (no per-launch timing)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K_steps)]
+    host = np.zeros((K_steps, 2))                 # seconds the host spends inside the draft and verify calls (enqueueing their launches)
     for i in range(K_steps):
         k = g.bandit_select()
-        ev[i][0].record(); g.draft(k, gamma)
-        ev[i][1].record(); g.verify(gamma)
+        ev[i][0].record(); h0 = time.perf_counter(); g.draft(k, gamma); h1 = time.perf_counter()
+        ev[i][1].record(); h2 = time.perf_counter(); g.verify(gamma); h3 = time.perf_counter()
         ev[i][2].record(); n, tok, mask, bd = g.accept(gamma)
         ev[i][3].record()
         g.bandit_update(k, n, gamma, bd)
+        host[i] = (h1 - h0, h3 - h2)
     torch.cuda.synchronize()
     phase_all = np.array([[ev[i][j].elapsed_time(ev[i][j + 1]) for j in range(3)] for i in range(K_steps)])
     phase = [float(np.median(phase_all[:, j])) for j in range(3)]
@@ -180,6 +182,9 @@ def main():
     verify_bytes = n_params * 2 + kv_tok * l_mid + kv_tok * (gamma + 1) + (gamma + 1) * td["vocab"] * 4
     extra = {
         "verify_ms": phase[1], "draft_ms": phase[0], "accept_ms": phase[2],
+        # host time inside the two asynchronous calls (median): below the GPU time of the phase means the GPU, not the host's
+        # launch rate, bounds the phase
+        "draft_host_ms": float(np.median(host[:, 0]) * 1e3), "verify_host_ms": float(np.median(host[:, 1]) * 1e3),
         "phase_ms_p10_p90": {"draft": phase_p10_p90[0], "verify": phase_p10_p90[1], "accept": phase_p10_p90[2]},
         "verify_hbm_frac": verify_bytes / (phase[1] * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "verify_algorithmic_GB": verify_bytes / 1e9,
