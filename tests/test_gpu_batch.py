@@ -345,3 +345,20 @@ def test_config5_full_size_sampled_sequences():
         print("C5 sampled sequence", ls.seq, {k: st[k] for k in ("max_dp", "max_dq", "ties_shared", "ties_own", "mismatch_own")})
         assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
     g.close()
+
+
+def test_largest_batch_and_draft_length():
+    """The upper ends of the ranges at a shape the oracle follows in seconds: 32 sequences (METASD_MAX_BATCH) with
+    gamma = 15 (METASD_MAX_GAMMA): 512 verification rows - two passes of the many-row GEMM - ragged prompts, every
+    sequence followed by its own oracle for three rounds, the third with three different arms in flight."""
+    cfg = W.config4(n_layers=2, ctx=40, n_new=64, K=3, d_model=256, n_heads=4, d_ffn=512, vocab=1024, dd_model=128, dn_heads=2, dd_ffn=256)
+    cfg["gamma"], cfg["max_ctx"] = 15, 40 + 64
+    prompts = [W.prompt_tokens(40 - b, 1024, 90 + b) for b in range(32)]
+    g, seqs = batch_pair(cfg, 1.0, prompts, TOL)
+    bl = make_lockstep(g, cfg, seqs, prompts, 1.0, TOL)
+    for r in range(3):
+        bl.round(None if r < 2 else [(b + r) % 3 for b in range(32)])
+    for ls in bl.seqs:
+        st = ls.stats
+        assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+    g.close()

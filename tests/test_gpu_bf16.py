@@ -139,10 +139,12 @@ def test_shared_cache_needs_the_targets_own_layers():
 
 
 def test_config3_1b_shape_shared_cache():
-    """1B-shape configuration at full size with the four early-exit drafters on the target's cache; real 512-token prefill
-    (by the target alone: the drafters have nothing to prefill), 4 rounds at T = 1, one per drafter."""
+    """1B-shape configuration at full size with the four early-exit drafters on the target's cache (512-position synthetic
+    prefix in the target's cache only: the drafters have none of their own), 5 rounds at T = 1: one per drafter and a
+    return to the first."""
     cfg = W.config3(device="cuda")
-    st = run_lockstep(cfg, 1.0, rounds=4, kv_prefilled=False, device="cuda", share_kv=True)
+    cfg["kv_seed"] = 7
+    st = run_lockstep(cfg, 1.0, rounds=5, kv_prefilled=True, device="cuda", share_kv=True)
     assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
 
 

@@ -94,3 +94,22 @@ def test_runs_out_of_context_cleanly():
             g.round(4)
     assert e.value.code == -2
     g.close()
+
+
+@pytest.mark.parametrize("T", [0.0, 1.0])
+def test_smallest_sizes_one_drafter_one_draft_one_prompt_token(T):
+    """The degenerate ends of the ranges: K = 1 (Alg. 2's index then only ever has one arm; its bonus term is finite
+    from the first decision on), gamma = 1 (a two-row verification block), a one-token prompt (nothing to prefill);
+    20 rounds in lock-step with the oracle."""
+    cfg = W.config1()
+    cfg["drafters"] = cfg["drafters"][:1]
+    cfg["prompt"] = cfg["prompt"][:1]
+    g, ot, od = build_pair(cfg, T, gamma=1)
+    g.set_context(cfg["prompt"])
+    ls = LockStep(g, ot, od, cfg["prompt"], 1, T, cfg["seed"], cfg["beta"], logit_tol=1e-4)
+    for _ in range(20):
+        ls.round()
+    st = ls.stats
+    assert st["mismatch_own"] == 0 and st["ties_own"] + st["ties_shared"] <= 1 and st["max_dp"] <= 1e-4 and st["max_dq"] <= 1e-4, st
+    assert set(st["arms"]) == {0}
+    g.close()
