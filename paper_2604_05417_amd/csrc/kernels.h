@@ -1024,7 +1024,7 @@ __device__ __forceinline__ bool tree_allowed(const TreeBlk& tb, int p, int row) 
 // RoPE (rotate-half pairing, angle = pos * theta^(-2i/hd)) on q and k, K/V cache append.
 //   part: split-K partials of the fused q|k|v projection, [s][r][N], N = (H + 2 KH) * hd.
 //   q out fp32 [m][H*hd] (q_split: as two bf16 arrays, see below); cache planes (type T) [kv_head][max_ctx][hd].
-//   grid (H + 2KH, m), block 64
+//   grid (ceil((H + 2KH) / k), m), block 64 k
 
 // The rotation table of a forward block, tab[r][i] = (cos, sin)((pos0 + r) * theta^(-2i/hd)) in fp64 (the rotation is
 // applied in fp64 and rounded once), is built once per forward by embed_rope_kernel and used by every layer.
@@ -1035,8 +1035,9 @@ __device__ __forceinline__ void rope_kv_body(const float* __restrict__ part, int
                                              int KH, int hd, const double2* __restrict__ tab, float* __restrict__ q,
                                              T* __restrict__ kc, T* __restrict__ vc, int max_ctx, int interleaved, int q_split,
                                              const float* __restrict__ inv, bool write_kv) {
-    const int head = blockIdx.x, r = blockIdx.y, i = threadIdx.x, half = hd >> 1;
-    if (i >= half) return;
+    // 64 threads per head; a workgroup of 64 k threads takes k consecutive heads
+    const int head = (int)blockIdx.x * ((int)blockDim.x >> 6) + ((int)threadIdx.x >> 6), r = blockIdx.y, i = threadIdx.x & 63, half = hd >> 1;
+    if (i >= half || head >= H + 2 * KH) return;
     // interleaved (rope-ordered packed weights): q / k columns hold the pair (i, i + half) at 16(i/8) + 2(i%8), +1
     const bool il = interleaved && head < H + KH;
     const size_t base = (size_t)r * N + (size_t)head * hd;
@@ -1465,6 +1466,29 @@ __device__ __forceinline__ void attn_combine_body(const float* __restrict__ part
     const int col = threadIdx.x;
     const float* base = part + ((size_t)h * nch_stride * 16 + r) * (HD + 2);
     const size_t cs = (size_t)16 * (HD + 2);
+    if (nchunks <= 24) {
+        // up to 24 records (3072 positions): everything is requested at once - one trip to memory instead of one per group
+        // of eight and pass (records past the end re-read the last one and get weight zero)
+        float mc[24], lc[24], oc[24];
+#pragma unroll
+        for (int u = 0; u < 24; ++u) {
+            const float* rec = base + (size_t)min(u, nchunks - 1) * cs;
+            mc[u] = rec[HD]; lc[u] = rec[HD + 1]; oc[u] = rec[col];
+        }
+        float M = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 24; ++u) M = fmaxf(M, u < nchunks ? mc[u] : -INFINITY);
+        float Lsum = 0.f, o = 0.f;
+#pragma unroll
+        for (int u = 0; u < 24; ++u) {                   // same order and arithmetic as the general loop below
+            const float w = (u >= nchunks || mc[u] == -INFINITY) ? 0.f : expf(mc[u] - M);
+            Lsum += lc[u] * w;
+            o += oc[u] * w;
+        }
+        if (split) store_split1(out, lo_off, (size_t)r_out * H * HD + (size_t)h * HD + col, o / Lsum);
+        else out[(size_t)r_out * H * HD + (size_t)h * HD + col] = o / Lsum;
+        return;
+    }
     float M = -INFINITY;
     for (int c0 = 0; c0 < nchunks; c0 += 8) {           // eight chunk records in flight
         float mc[8];
@@ -1503,6 +1527,36 @@ __global__ void attn_combine_kernel(const float* __restrict__ part, int nchunks,
 // ------------------------------------------------------------------------------------------
 // FFN activation on split-K partials:  SwiGLU  out = silu(gate) * up  (part columns: gate | up),
 //                                      GELU    out = 0.5 u (1 + erf(u / sqrt 2)).
+
+// Four consecutive columns per thread (f % 4 == 0), the same arithmetic per element as ffn_act_kernel.   grid ceil(m f / 1024), block 256
+__global__ void ffn_act4_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int m, int f, int act,
+                                float* __restrict__ out, int split, const float* __restrict__ inv) {
+    const size_t idx = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (idx >= (size_t)m * f) return;
+    const int r = (int)(idx / f), i = (int)(idx - (size_t)r * f);
+    const size_t cg = (size_t)r * (act == 1 ? 2 : 1) * f + i, cu = cg + f;
+    float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
+    for (int s0 = 0; s0 < nsplit; s0 += 4) {            // four partials in flight, added in order
+        float4 pg[4], pu[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const bool ok = s0 + k < nsplit;
+            pg[k] = ok ? *reinterpret_cast<const float4*>(part + (size_t)(s0 + k) * sstride + cg) : make_float4(0.f, 0.f, 0.f, 0.f);
+            pu[k] = (ok && act == 1) ? *reinterpret_cast<const float4*>(part + (size_t)(s0 + k) * sstride + cu) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (s0 + k < nsplit) {
+                g.x += pg[k].x; g.y += pg[k].y; g.z += pg[k].z; g.w += pg[k].w;
+                u.x += pu[k].x; u.y += pu[k].y; u.z += pu[k].z; u.w += pu[k].w;
+            }
+    }
+    if (inv) { const float sc = inv[r]; g.x *= sc; g.y *= sc; g.z *= sc; g.w *= sc; u.x *= sc; u.y *= sc; u.z *= sc; u.w *= sc; }
+    auto f1 = [&](float gg, float uu) { return act == 1 ? gg / (1.0f + expf(-gg)) * uu : 0.5f * gg * (1.0f + erff(gg * 0.70710678118654752f)); };
+    const float4 y = make_float4(f1(g.x, u.x), f1(g.y, u.y), f1(g.z, u.z), f1(g.w, u.w));
+    if (split) store_split4(out, (size_t)m * f, idx, y);
+    else *reinterpret_cast<float4*>(out + idx) = y;
+}
 
 __global__ void ffn_act_kernel(const float* __restrict__ part, int nsplit, size_t sstride, int m, int f, int act,
                                float* __restrict__ out, int split, const float* __restrict__ inv) {

@@ -705,7 +705,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         const int NQKV = DQ + 2 * DKV;
         const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
-        hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, part, ns, (size_t)m * NQKV, NQKV, pos0, H, KH,
+        hipLaunchKernelGGL(rope_kv_kernel<T>, dim3((H + 2 * KH + 3) / 4, m), dim3(256), 0, st, part, ns, (size_t)m * NQKV, NQKV, pos0, H, KH,
                            hd, (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, sizeof(T) == 2 ? 1 : 0,
                            (sizeof(T) == 2 && hd >= 64) ? 1 : 0, (const float*)nullptr);
         LAUNCH_CHECK(c, "rope_kv");
@@ -721,7 +721,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         }
         const size_t nact = (size_t)m * F;
         const int NF = (d.act == METASD_SWIGLU ? 2 : 1) * F;
-        hipLaunchKernelGGL(ffn_act_kernel, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)m * NF, m, F,
+        hipLaunchKernelGGL(ffn_act4_kernel, dim3((unsigned)((nact / 4 + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)m * NF, m, F,
                            d.act, (float*)c->d_act(), split, (const float*)nullptr);
         LAUNCH_CHECK(c, "ffn_act");
         if ((rc = gemm<T>(c, c->d_act(), F, m, F, M.layer_w(L, 8), D, nullptr, 0, nullptr, 0, nullptr, &ns, (size_t)m * F))) return rc;
@@ -767,7 +767,7 @@ int forward_rows_residual(metasd_ctx* c, Model& M, int pos0, int m, float* logit
                           scaled ? ssq : nullptr, ntg, inv, 0))) return rc;
         const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
-        hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, part, ns, (size_t)m * NQKV, NQKV, pos0, H, KH, hd,
+        hipLaunchKernelGGL(rope_kv_kernel<T>, dim3((H + 2 * KH + 3) / 4, m), dim3(256), 0, st, part, ns, (size_t)m * NQKV, NQKV, pos0, H, KH, hd,
                            (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, 1, hd >= 64 ? 1 : 0,
                            scaled ? (const float*)inv : nullptr);
         LAUNCH_CHECK(c, "rope_kv");
@@ -780,7 +780,7 @@ int forward_rows_residual(metasd_ctx* c, Model& M, int pos0, int m, float* logit
         }
         const size_t nact = (size_t)m * F;
         const int NF = (d.act == METASD_SWIGLU ? 2 : 1) * F;
-        hipLaunchKernelGGL(ffn_act_kernel, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)m * NF, m, F, d.act,
+        hipLaunchKernelGGL(ffn_act4_kernel, dim3((unsigned)((nact / 4 + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)m * NF, m, F, d.act,
                            (float*)c->d_act(), 1, (const float*)inv);
         LAUNCH_CHECK(c, "ffn_act");
         const void* gain_next = L + 1 < d.n_layers ? M.layer_w(L + 1, 0) : M.final_norm();
@@ -839,7 +839,7 @@ int forward_rows_fused(metasd_ctx* c, Model& M, int pos0, int m, float* logits, 
         hp ^= 1; pp ^= 1;
         const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
-        hipLaunchKernelGGL(rope_kv_kernel<T>, dim3(H + 2 * KH, m), dim3(64), 0, st, c->d_part_pp(pp), ns, (size_t)m * NQKV, NQKV, pos0, H,
+        hipLaunchKernelGGL(rope_kv_kernel<T>, dim3((H + 2 * KH + 3) / 4, m), dim3(256), 0, st, c->d_part_pp(pp), ns, (size_t)m * NQKV, NQKV, pos0, H,
                            KH, hd, (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, 1, 1, (const float*)nullptr);
         LAUNCH_CHECK(c, "rope_kv");
         if ((rc = attention<T>(c, M, L, pos0, m, false))) return rc;
@@ -1078,7 +1078,7 @@ int forward_segs_t(metasd_ctx* c, Model& M, const Segs& sg, float* logits, int o
         }
         const size_t nact = (size_t)R * F;
         const int NF = (d.act == METASD_SWIGLU ? 2 : 1) * F;
-        hipLaunchKernelGGL(ffn_act_kernel, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)R * NF, R, F, d.act,
+        hipLaunchKernelGGL(ffn_act4_kernel, dim3((unsigned)((nact / 4 + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)R * NF, R, F, d.act,
                            (float*)c->d_act(), split, (const float*)nullptr);
         LAUNCH_CHECK(c, "ffn_act");
         if ((rc = gemm_rows<T>(c, c->d_act(), F, R, F, M.layer_w(L, 8), D, nullptr, 0, nullptr, 0, &ns))) return rc;
@@ -1237,7 +1237,7 @@ int forward_step_grouped(metasd_ctx* c, const Segs& sg, const int* arm, float* l
         }
         const size_t nact = (size_t)R * F;
         const int NF = (d.act == METASD_SWIGLU ? 2 : 1) * F;
-        hipLaunchKernelGGL(ffn_act_kernel, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)R * NF, R, F, d.act,
+        hipLaunchKernelGGL(ffn_act4_kernel, dim3((unsigned)((nact / 4 + 255) / 256)), dim3(256), 0, st, part, ns, (size_t)R * NF, R, F, d.act,
                            (float*)c->d_act(), 1, (const float*)nullptr);
         LAUNCH_CHECK(c, "ffn_act");
         if ((rc = gemm_rows_grouped(c, c->d_act(), F, R, F, weights(L, 8, -1, -1), D, 0, 0, &ns))) return rc;
