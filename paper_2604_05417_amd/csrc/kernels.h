@@ -1043,6 +1043,7 @@ __device__ __forceinline__ void rope_kv_body(const float* __restrict__ part, int
     const size_t base = (size_t)r * N + (size_t)head * hd;
     const size_t ca = base + (il ? 16 * (i >> 3) + 2 * (i & 7) : i), cb = il ? ca + 1 : ca + half;
     const double2 cssn = tab[r * half + i];
+    const float sc = inv ? inv[r] : 1.f;               // requested with the partials, not after them
     float a = 0.f, b = 0.f;
     for (int s0 = 0; s0 < nsplit; s0 += 8) {          // eight partials in flight, added in order
         float pa[8], pb[8];
@@ -1056,7 +1057,7 @@ __device__ __forceinline__ void rope_kv_body(const float* __restrict__ part, int
         for (int u = 0; u < 8; ++u)
             if (s0 + u < nsplit) { a += pa[u]; b += pb[u]; }
     }
-    if (inv) { const float sc = inv[r]; a *= sc; b *= sc; }   // 1/rms of the input row (the projection ran on h * gain)
+    if (inv) { a *= sc; b *= sc; }                      // 1/rms of the input row (the projection ran on h * gain)
     if (head < H + KH) {
         const double cs = cssn.x, sn = cssn.y;
         const float ra = (float)((double)a * cs - (double)b * sn);
@@ -1253,6 +1254,21 @@ __global__ __launch_bounds__(256) void attn_partial_tree_kernel(const float* __r
     attn_partial_body<T, HD>(q, kc, vc, m, pos0, H, KH, max_ctx, scale, part, nchunks, (int)blockIdx.x, (int)blockIdx.y, &tb);
 }
 
+// Source of a block's fresh q / k / v when the attention kernel forms them itself (no rope_kv_kernel launch): the split-K
+// partial sums of the QKV projection (rope-ordered q and k columns: pair (i, i + hd/2) of a head at columns 16(i/8) + 2(i%8), +1),
+// the rotation table of the block, the optional 1/rms per row, and where the new K / V rows go.  The arithmetic per element is
+// rope_kv_body's: partials added in order from zero, scaled, rotated in fp64, rounded once.
+struct QkvIn {
+    const float* part;     // [nsplit][m][N]
+    int nsplit;
+    size_t sstride;        // m * N
+    int N;                 // (H + 2 KH) * hd
+    const double2* tab;    // [m][hd/2] (cos, sin)
+    const float* inv;      // [m] or nullptr
+    bf16_t* kc;            // cache planes of this layer, written for positions pos0 .. pos0+m-1
+    bf16_t* vc;
+};
+
 // bf16-cache variant on MFMA.  One workgroup (4 wavefronts) per (chunk of 128 positions, query head):
 //   S^T[pos][row] = K[pos][:] . q[row][:]   A = K rows straight from global (16 B per lane, no LDS),
 //                                           B = q as two bf16 terms (hi + lo); wavefront w owns
@@ -1267,11 +1283,19 @@ __global__ __launch_bounds__(256) void attn_partial_tree_kernel(const float* __r
 // MULTI: the workgroup walks cpw consecutive chunks starting at chunk c and keeps a running (max, sum, O) per row
 // (each new chunk rescales what is there by exp(old max - new max)); it writes one record, number rec of head h,
 // so the records written and merged later shrink by the factor cpw.  Without MULTI: one chunk, record c.
-template <int HD, bool MULTI = false>
+// QKV (one chunk per workgroup only): q, and the K / V rows of the block's own positions, are formed here from the QKV
+// projection's partial sums instead of being read (see QkvIn).  The pieces (four consecutive columns of one row: all of q of
+// this head, and the new K and V rows that fall into this chunk) are dealt out over the 256 threads and requested before the
+// cache loads, so they arrive in the same trip to memory; q and the new K rows pass through LDS into the MFMA fragment layout,
+// the new V rows go straight into the staged V chunk.  The first query head of each KV head also writes the new rows to the
+// cache.  Every workgroup forms the new rows it needs itself: nothing in this launch reads what another workgroup writes.
+template <int HD, bool MULTI = false, bool QKV = false>
 __device__ __forceinline__ void attn_partial_mfma_body(const float* __restrict__ q, const bf16_t* __restrict__ kc,
                                                        const bf16_t* __restrict__ vc, int m, int pos0, int H, int KH,
                                                        int max_ctx, float scale, float* __restrict__ part, int nchunks, int c,
-                                                       int h, size_t q_lo_off, int cpw = 1, int rec = 0, const TreeBlk* tb = nullptr) {
+                                                       int h, size_t q_lo_off, int cpw = 1, int rec = 0, const TreeBlk* tb = nullptr,
+                                                       const QkvIn* qi = nullptr) {
+    static_assert(!(MULTI && QKV), "fresh q/k/v are formed for a single chunk per workgroup");
     constexpr int RS = HD + 8;                 // padded LDS row stride of the V chunk (elements)
     constexpr int VPR = HD / 8;                // 16-byte pieces per row
     constexpr int PS = ATT_CH + 8;             // padded row stride of P (elements)
@@ -1296,13 +1320,16 @@ __device__ __forceinline__ void attn_partial_mfma_body(const float* __restrict__
     for (int k = 0; k < KC; ++k) {
         qh[k] = make_uint4(0, 0, 0, 0);
         ql[k] = make_uint4(0, 0, 0, 0);
-        if (rowok) {
+        if (!QKV && rowok) {
             const bf16_t* src = reinterpret_cast<const bf16_t*>(q) + (size_t)row * H * HD + (size_t)h * HD + k * 32 + g * 8;
             qh[k] = *reinterpret_cast<const uint4*>(src);
             ql[k] = *reinterpret_cast<const uint4*>(src + q_lo_off);
         }
     }
     const bf16_t* kbase = kc + (size_t)kh * max_ctx * HD;
+    constexpr int QS = HD + 8;                 // padded row stride (elements) of q and of the new K rows in LDS
+    constexpr int C4 = HD / 4;                 // four-column pieces per row
+    constexpr int half = HD / 2;
     // running state of this lane's query row (MULTI): maximum, sum, and this wavefront's O^T tiles
     float run_max = -INFINITY, run_sum = 0.f;
     f32x4 orun[NTW];
@@ -1314,30 +1341,155 @@ __device__ __forceinline__ void attn_partial_mfma_body(const float* __restrict__
         const int p0 = (c + ci) * ATT_CH;
         if (MULTI && p0 >= L) break;               // workgroup-uniform
         const int np = min(ATT_CH, L - p0);
-        // ---- issue the V chunk loads first (consumed last), rows beyond the ragged end are zero
+        // the block's own rows that fall into this chunk: rows r_lo .. r_lo + nnew - 1
+        const int r_lo = max(0, p0 - pos0), nnew = QKV ? max(0, min(m, p0 + ATT_CH - pos0) - r_lo) : 0;
+        // ---- fresh q / k / v: the pieces of this thread (piece number tid + 256 j), two per trip.  Requests are unconditional
+        // (clamped to valid addresses, unused values dropped later) so that the code up to the first use is one straight line
+        // and the wait for the pieces does not have to wait for the cache rows requested after them.
+        constexpr int GRP = 2;
+        const int n_q = m * C4, n_kv = nnew * C4, n_items = QKV ? n_q + 2 * n_kv : 0;
+        float4 raw[GRP][4];
+        double2 rot[GRP][2];
+        float rsc[GRP];
+        auto item_at = [&](int idx, int& kind, int& r, int& cc) {      // idx < n_items; kinds: 0 q, 1 K, 2 V
+            const int k1 = idx - n_q, k2 = k1 - n_kv;
+            kind = idx < n_q ? 0 : (k2 < 0 ? 1 : 2);
+            const int loc = kind == 0 ? idx : (kind == 1 ? k1 : k2);
+            const int rr = loc / C4;
+            cc = loc - rr * C4;
+            r = kind == 0 ? rr : r_lo + rr;
+        };
+        auto item_src = [&](int kind, int r, int cc) {
+            const size_t col = kind == 0 ? (size_t)h * HD : kind == 1 ? (size_t)(H + kh) * HD : (size_t)(H + KH + kh) * HD;
+            return qi->part + (size_t)r * qi->N + col + 4 * cc;
+        };
+        auto item_request = [&](int j0) {
+            const int ns1 = qi->nsplit - 1;
+#pragma unroll
+            for (int j = 0; j < GRP; ++j) {
+                const int idx = min(tid + 256 * (j0 + j), n_items - 1);
+                int kind, r, cc;
+                item_at(idx, kind, r, cc);
+                const float* src = item_src(kind, r, cc);
+#pragma unroll
+                for (int s = 0; s < 4; ++s) raw[j][s] = *reinterpret_cast<const float4*>(src + (size_t)min(s, ns1) * qi->sstride);
+                const double2* t = qi->tab + (size_t)r * half + 8 * (cc >> 2) + 2 * (cc & 3);   // pairs i, i + 1 of columns 4 cc ..
+                rot[j][0] = t[0]; rot[j][1] = t[1];
+                rsc[j] = *(qi->inv ? qi->inv + r : reinterpret_cast<const float*>(qi->tab));
+            }
+        };
+        if constexpr (QKV) {
+            item_request(0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // ---- issue the V chunk loads (consumed last); rows beyond the ragged end re-read the last row and are zeroed when staged
         const bf16_t* vbase = vc + ((size_t)kh * max_ctx + p0) * HD;
         uint4 vreg[VIT];
 #pragma unroll
         for (int it = 0; it < VIT; ++it) {
             const int idx = tid + it * 256;
             const int p = idx / VPR, v = idx - p * VPR;
-            vreg[it] = (p < np) ? *reinterpret_cast<const uint4*>(vbase + (size_t)p * HD + v * 8) : make_uint4(0, 0, 0, 0);
+            vreg[it] = *reinterpret_cast<const uint4*>(vbase + (size_t)min(p, np - 1) * HD + v * 8);
         }
-        // ---- scores of this wavefront's 32 positions: two 16-position tiles
-        f32x4 sacc[2];
+        // ---- K rows of this wavefront's 32 positions: two 16-position tiles (A operand straight from the cache)
+        u32x4 kf[2][KC];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int pl = wave * 32 + t * 16 + row;                       // this lane's K row within the chunk
-            const int pg = min(p0 + pl, L - 1);                            // clamp: stays inside the valid cache
+            const int pg = min(p0 + pl, L - 1);                            // clamp: stays inside the cache
             const u32x4* kp = reinterpret_cast<const u32x4*>(kbase + (size_t)pg * HD + g * 8);
-            u32x4 kf[KC];
 #pragma unroll
-            for (int k = 0; k < KC; ++k) kf[k] = kp[k * 4];                // +32 elements = 4 x 16 bytes
+            for (int k = 0; k < KC; ++k) kf[t][k] = kp[k * 4];             // +32 elements = 4 x 16 bytes
+        }
+        if constexpr (QKV) {
+            __builtin_amdgcn_sched_barrier(0);
+            __shared__ __align__(16) bf16_t kn[16 * QS];                   // the new K rows of this chunk, rotated
+            bf16_t* qs_hi = phi;                                            // q as two bf16 terms: phi / plo are free until the scores exist
+            bf16_t* qs_lo = plo;
+            const bool kv_writer = h % (H / KH) == 0;
+            auto item_finish = [&](int j0) {
+#pragma unroll
+                for (int j = 0; j < GRP; ++j) {
+                    const int idx = tid + 256 * (j0 + j);
+                    float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) {
+                        const float w = s < qi->nsplit ? 1.f : 0.f;      // a repeated request counts as + 0 (the sums stay the ordered ones)
+                        f.x += w * raw[j][s].x; f.y += w * raw[j][s].y; f.z += w * raw[j][s].z; f.w += w * raw[j][s].w;
+                    }
+                    if (idx < n_items) {
+                        int kind, r, cc;
+                        item_at(idx, kind, r, cc);
+                        if (qi->nsplit > 4) {                               // more than four partials: the rest one by one
+                            const float* src = item_src(kind, r, cc);
+                            for (int s = 4; s < qi->nsplit; ++s) {
+                                const float4 x = *reinterpret_cast<const float4*>(src + (size_t)s * qi->sstride);
+                                f.x += x.x; f.y += x.y; f.z += x.z; f.w += x.w;
+                            }
+                        }
+                        if (qi->inv) { const float sc = rsc[j]; f.x *= sc; f.y *= sc; f.z *= sc; f.w *= sc; }
+                        if (kind == 2) {
+                            const uint2 pk = make_uint2(pack_bf16x2(f2bf(f.x), f2bf(f.y)), pack_bf16x2(f2bf(f.z), f2bf(f.w)));
+                            *reinterpret_cast<uint2*>(vs + (pos0 + r - p0) * RS + 4 * cc) = pk;
+                            if (kv_writer) *reinterpret_cast<uint2*>(qi->vc + ((size_t)kh * max_ctx + pos0 + r) * HD + 4 * cc) = pk;
+                        } else {
+                            // columns 4 cc .. + 3 hold (a_i, b_i, a_{i+1}, b_{i+1}): elements i, i + 1 and their partners hd/2 further on
+                            const int i = 8 * (cc >> 2) + 2 * (cc & 3);
+                            const float a0 = (float)((double)f.x * rot[j][0].x - (double)f.y * rot[j][0].y);
+                            const float b0 = (float)((double)f.x * rot[j][0].y + (double)f.y * rot[j][0].x);
+                            const float a1 = (float)((double)f.z * rot[j][1].x - (double)f.w * rot[j][1].y);
+                            const float b1 = (float)((double)f.z * rot[j][1].y + (double)f.w * rot[j][1].x);
+                            const bf16_t a0h = f2bf(a0), a1h = f2bf(a1), b0h = f2bf(b0), b1h = f2bf(b1);
+                            if (kind == 0) {
+                                *reinterpret_cast<uint32_t*>(qs_hi + r * QS + i) = pack_bf16x2(a0h, a1h);
+                                *reinterpret_cast<uint32_t*>(qs_hi + r * QS + i + half) = pack_bf16x2(b0h, b1h);
+                                *reinterpret_cast<uint32_t*>(qs_lo + r * QS + i) = pack_bf16x2(f2bf(a0 - bf2f(a0h)), f2bf(a1 - bf2f(a1h)));
+                                *reinterpret_cast<uint32_t*>(qs_lo + r * QS + i + half) = pack_bf16x2(f2bf(b0 - bf2f(b0h)), f2bf(b1 - bf2f(b1h)));
+                            } else {
+                                *reinterpret_cast<uint32_t*>(kn + (r - r_lo) * QS + i) = pack_bf16x2(a0h, a1h);
+                                *reinterpret_cast<uint32_t*>(kn + (r - r_lo) * QS + i + half) = pack_bf16x2(b0h, b1h);
+                            }
+                        }
+                    }
+                }
+            };
+            item_finish(0);
+            for (int j0 = GRP; j0 * 256 < n_items; j0 += GRP) {           // more than two pieces per thread: further trips
+                item_request(j0);
+                item_finish(j0);
+            }
+            __syncthreads();
+            if (rowok) {
+#pragma unroll
+                for (int k = 0; k < KC; ++k) {
+                    qh[k] = *reinterpret_cast<const uint4*>(qs_hi + row * QS + k * 32 + g * 8);
+                    ql[k] = *reinterpret_cast<const uint4*>(qs_lo + row * QS + k * 32 + g * 8);
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int pg = min(p0 + wave * 32 + t * 16 + row, L - 1);
+                if (pg >= pos0) {                                          // what was read from the cache there is not written yet
+#pragma unroll
+                    for (int k = 0; k < KC; ++k)
+                        kf[t][k] = __builtin_bit_cast(u32x4, *reinterpret_cast<const uint4*>(kn + (pg - pos0 - r_lo) * QS + k * 32 + g * 8));
+                }
+            }
+            if (kv_writer && tid < nnew * VPR) {                           // the new K rows to the cache, 16 bytes per thread
+                const int rr = tid / VPR, v = tid - rr * VPR;
+                *reinterpret_cast<uint4*>(qi->kc + ((size_t)kh * max_ctx + pos0 + r_lo + rr) * HD + v * 8) =
+                    *reinterpret_cast<const uint4*>(kn + rr * QS + v * 8);
+            }
+        }
+        // ---- scores
+        f32x4 sacc[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f}, acl = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int k = 0; k < KC; ++k) {
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[k]), __builtin_bit_cast(bf16x8, qh[k]), acc, 0, 0, 0);
-                acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[k]), __builtin_bit_cast(bf16x8, ql[k]), acl, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[t][k]), __builtin_bit_cast(bf16x8, qh[k]), acc, 0, 0, 0);
+                acl = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[t][k]), __builtin_bit_cast(bf16x8, ql[k]), acl, 0, 0, 0);
             }
             sacc[t] = acc + acl;
         }
@@ -1363,7 +1515,8 @@ __device__ __forceinline__ void attn_partial_mfma_body(const float* __restrict__
         for (int it = 0; it < VIT; ++it) {
             const int idx = tid + it * 256;
             const int p = idx / VPR, v = idx - p * VPR;
-            *reinterpret_cast<uint4*>(vs + p * RS + v * 8) = vreg[it];
+            if (!(QKV && p < np && p0 + p >= pos0))                       // the block's own rows are in place already
+                *reinterpret_cast<uint4*>(vs + p * RS + v * 8) = p < np ? vreg[it] : make_uint4(0, 0, 0, 0);
         }
         __syncthreads();
         const float cmx = fmaxf(fmaxf(wmax[0][row], wmax[1][row]), fmaxf(wmax[2][row], wmax[3][row]));
@@ -1448,6 +1601,14 @@ __global__ __launch_bounds__(256) void attn_partial_mfma_kernel(const float* __r
                                                                 int max_ctx, float scale, float* __restrict__ part, int nchunks) {
     attn_partial_mfma_body<HD>(q, kc, vc, m, pos0, H, KH, max_ctx, scale, part, nchunks, (int)blockIdx.x, (int)blockIdx.y,
                                (size_t)m * H * HD);
+}
+// The same with q and the block's own K / V rows formed from the QKV projection's partial sums (tb.on selects the tree mask).
+template <int HD>
+__global__ __launch_bounds__(256, 3) void attn_partial_mfma_qkv_kernel(QkvIn qi, const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
+                                                                    int m, int pos0, int H, int KH, int max_ctx, float scale,
+                                                                    float* __restrict__ part, int nchunks, TreeBlk tb) {
+    attn_partial_mfma_body<HD, false, true>(nullptr, kc, vc, m, pos0, H, KH, max_ctx, scale, part, nchunks, (int)blockIdx.x,
+                                            (int)blockIdx.y, 0, 1, 0, tb.on ? &tb : nullptr, &qi);
 }
 template <int HD>
 __global__ __launch_bounds__(256) void attn_partial_mfma_tree_kernel(const float* __restrict__ q, const bf16_t* __restrict__ kc,
@@ -1536,6 +1697,7 @@ __global__ void ffn_act4_kernel(const float* __restrict__ part, int nsplit, size
     const int r = (int)(idx / f), i = (int)(idx - (size_t)r * f);
     const size_t cg = (size_t)r * (act == 1 ? 2 : 1) * f + i, cu = cg + f;
     float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
+    const float sc = inv ? inv[r] : 1.f;               // requested with the partials, not after them
     for (int s0 = 0; s0 < nsplit; s0 += 4) {            // four partials in flight, added in order
         float4 pg[4], pu[4];
 #pragma unroll
@@ -1551,7 +1713,7 @@ __global__ void ffn_act4_kernel(const float* __restrict__ part, int nsplit, size
                 u.x += pu[k].x; u.y += pu[k].y; u.z += pu[k].z; u.w += pu[k].w;
             }
     }
-    if (inv) { const float sc = inv[r]; g.x *= sc; g.y *= sc; g.z *= sc; g.w *= sc; u.x *= sc; u.y *= sc; u.z *= sc; u.w *= sc; }
+    if (inv) { g.x *= sc; g.y *= sc; g.z *= sc; g.w *= sc; u.x *= sc; u.y *= sc; u.z *= sc; u.w *= sc; }
     auto f1 = [&](float gg, float uu) { return act == 1 ? gg / (1.0f + expf(-gg)) * uu : 0.5f * gg * (1.0f + erff(gg * 0.70710678118654752f)); };
     const float4 y = make_float4(f1(g.x, u.x), f1(g.y, u.y), f1(g.z, u.z), f1(g.w, u.w));
     if (split) store_split4(out, (size_t)m * f, idx, y);

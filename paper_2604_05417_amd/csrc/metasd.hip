@@ -629,8 +629,10 @@ int gemm_pro(metasd_ctx* c, const GemmPro& pro, int m, int K, const void* W0, in
 }
 
 // combine == false: only the per-chunk records (the consumer merges them itself)
+// qi (bf16 caches, head_dim >= 64 only): q and the block's own K / V rows come from the QKV projection's partial sums inside
+// the attention kernel (no separate rope launch)
 template <typename T, int HD>
-int attention_hd(metasd_ctx* c, const Model& M, int L, int pos0, int m, bool combine) {
+int attention_hd(metasd_ctx* c, const Model& M, int L, int pos0, int m, bool combine, const QkvIn* qi) {
     const metasd_model_desc& d = M.d;
     const size_t plane = (size_t)d.n_kv_heads * c->cfg.max_ctx * HD;
     const T* kc = (const T*)M.kv + (size_t)L * 2 * plane;
@@ -642,7 +644,11 @@ int attention_hd(metasd_ctx* c, const Model& M, int L, int pos0, int m, bool com
                                                                  (double)m * d.n_heads * HD * 4);
     hipEvent_t ea = pr ? pr->a : nullptr, eb = pr ? pr->b : nullptr;
     if constexpr (sizeof(T) == 2 && HD >= 64) {
-        if (c->tree)
+        if (qi)
+            hipExtLaunchKernelGGL((attn_partial_mfma_qkv_kernel<HD>), dim3(nchunks, d.n_heads), dim3(256), 0u, c->stream, ea, eb, 0u, *qi,
+                                  kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale, c->d_apart(), nchunks,
+                                  c->tree ? *c->tree : TreeBlk{});
+        else if (c->tree)
             hipExtLaunchKernelGGL((attn_partial_mfma_tree_kernel<HD>), dim3(nchunks, d.n_heads), dim3(256), 0u, c->stream, ea, eb, 0u,
                                   (const float*)c->d_q(), kc, vc, m, pos0, d.n_heads, d.n_kv_heads, c->cfg.max_ctx, scale,
                                   c->d_apart(), nchunks, *c->tree);
@@ -669,12 +675,13 @@ int attention_hd(metasd_ctx* c, const Model& M, int L, int pos0, int m, bool com
 }
 
 template <typename T>
-int attention(metasd_ctx* c, const Model& M, int L, int pos0, int m, bool combine = true) {
+int attention(metasd_ctx* c, const Model& M, int L, int pos0, int m, bool combine = true, const QkvIn* qi = nullptr) {
+    if (qi && (sizeof(T) != 2 || M.hd < 64)) return c->fail(METASD_E_INVALID, "attention: fused q/k/v needs a bf16 cache and head_dim >= 64");
     switch (M.hd) {
-        case 32: return attention_hd<T, 32>(c, M, L, pos0, m, combine);
-        case 64: return attention_hd<T, 64>(c, M, L, pos0, m, combine);
+        case 32: return attention_hd<T, 32>(c, M, L, pos0, m, combine, nullptr);
+        case 64: return attention_hd<T, 64>(c, M, L, pos0, m, combine, qi);
         default:
-            if constexpr (sizeof(T) == 2) return attention_hd<T, 128>(c, M, L, pos0, m, combine);
+            if constexpr (sizeof(T) == 2) return attention_hd<T, 128>(c, M, L, pos0, m, combine, qi);
             return c->fail(METASD_E_INVALID, "fp32 head_dim 128 unsupported");
     }
 }
@@ -767,6 +774,8 @@ int forward_rows_residual(metasd_ctx* c, Model& M, int pos0, int m, float* logit
                           scaled ? ssq : nullptr, ntg, inv, 0))) return rc;
         const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
+        // (forming q / k / v inside the attention kernel, as the short-block path below does, was measured here and is slower
+        // at the 7B shape: 3.32 against 3.29 ms per pass - the wider kernel loses what the launch saves)
         hipLaunchKernelGGL(rope_kv_kernel<T>, dim3((H + 2 * KH + 3) / 4, m), dim3(256), 0, st, part, ns, (size_t)m * NQKV, NQKV, pos0, H, KH, hd,
                            (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, 1, hd >= 64 ? 1 : 0,
                            scaled ? (const float*)inv : nullptr);
@@ -798,7 +807,7 @@ int forward_rows_residual(metasd_ctx* c, Model& M, int pos0, int m, float* logit
 
 // Short blocks of narrow bf16 models (drafter steps; d_model <= 2048, METASD_FUSE_DMAX): the same forward with the add+norm, the FFN
 // activation and the attention combine folded into the prologue of the GEMM that consumes them -
-// 6 launches per layer instead of 10.  The residual stream and the partials ping-pong between two
+// 5 launches per layer instead of 10 (q / k / v are formed inside the attention kernel).  The residual stream and the partials ping-pong between two
 // buffers, because a GEMM's workgroups read the old ones while others already write the new ones.
 constexpr int fused_max_rows() { return 4; }
 bool fused_small_ok(const Model& M, int m) {
@@ -839,10 +848,11 @@ int forward_rows_fused(metasd_ctx* c, Model& M, int pos0, int m, float* logits, 
         hp ^= 1; pp ^= 1;
         const size_t plane = (size_t)KH * c->cfg.max_ctx * hd;
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
-        hipLaunchKernelGGL(rope_kv_kernel<T>, dim3((H + 2 * KH + 3) / 4, m), dim3(256), 0, st, c->d_part_pp(pp), ns, (size_t)m * NQKV, NQKV, pos0, H,
-                           KH, hd, (const double2*)c->d_rope(), (float*)c->d_q(), kc, kc + plane, c->cfg.max_ctx, 1, 1, (const float*)nullptr);
-        LAUNCH_CHECK(c, "rope_kv");
-        if ((rc = attention<T>(c, M, L, pos0, m, false))) return rc;
+        // q, and the new K / V rows, are summed and rotated inside the attention kernel (no rope launch)
+        {
+            const QkvIn qi{c->d_part_pp(pp), ns, (size_t)m * NQKV, NQKV, (const double2*)c->d_rope(), nullptr, kc, kc + plane};
+            if ((rc = attention<T>(c, M, L, pos0, m, false, &qi))) return rc;
+        }
         // output projection of the merged attention output
         {
             GemmPro p{};
