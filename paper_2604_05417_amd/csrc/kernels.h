@@ -6,6 +6,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace msd {
 
@@ -1627,29 +1628,31 @@ __device__ __forceinline__ void attn_combine_body(const float* __restrict__ part
     const int col = threadIdx.x;
     const float* base = part + ((size_t)h * nch_stride * 16 + r) * (HD + 2);
     const size_t cs = (size_t)16 * (HD + 2);
-    if (nchunks <= 24) {
-        // up to 24 records (3072 positions): everything is requested at once - one trip to memory instead of one per group
-        // of eight and pass (records past the end re-read the last one and get weight zero)
-        float mc[24], lc[24], oc[24];
+    // up to 24 records (3072 positions): everything is requested at once - one trip to memory instead of one per group of
+    // eight and pass (slots past the end re-read the last record and get weight zero; 8 slots when that is enough)
+    auto merge_all = [&](auto slots) {
+        constexpr int NS = decltype(slots)::value;
+        float mc[NS], lc[NS], oc[NS];
 #pragma unroll
-        for (int u = 0; u < 24; ++u) {
+        for (int u = 0; u < NS; ++u) {
             const float* rec = base + (size_t)min(u, nchunks - 1) * cs;
             mc[u] = rec[HD]; lc[u] = rec[HD + 1]; oc[u] = rec[col];
         }
         float M = -INFINITY;
 #pragma unroll
-        for (int u = 0; u < 24; ++u) M = fmaxf(M, u < nchunks ? mc[u] : -INFINITY);
+        for (int u = 0; u < NS; ++u) M = fmaxf(M, u < nchunks ? mc[u] : -INFINITY);
         float Lsum = 0.f, o = 0.f;
 #pragma unroll
-        for (int u = 0; u < 24; ++u) {                   // same order and arithmetic as the general loop below
+        for (int u = 0; u < NS; ++u) {                   // same order and arithmetic as the general loop below
             const float w = (u >= nchunks || mc[u] == -INFINITY) ? 0.f : expf(mc[u] - M);
             Lsum += lc[u] * w;
             o += oc[u] * w;
         }
         if (split) store_split1(out, lo_off, (size_t)r_out * H * HD + (size_t)h * HD + col, o / Lsum);
         else out[(size_t)r_out * H * HD + (size_t)h * HD + col] = o / Lsum;
-        return;
-    }
+    };
+    if (nchunks <= 8) { merge_all(std::integral_constant<int, 8>{}); return; }
+    if (nchunks <= 24) { merge_all(std::integral_constant<int, 24>{}); return; }
     float M = -INFINITY;
     for (int c0 = 0; c0 < nchunks; c0 += 8) {           // eight chunk records in flight
         float mc[8];
