@@ -12,6 +12,18 @@ most likely next token after node parent[i] according to the drafter (0 = most l
 in breadth-first order.  Node i is held in cache slot l - 1 + i, rotated for position l - 1 + depth(i), and attends to
 the committed positions, its ancestors and itself; after acceptance the K/V of the accepted nodes move to the slots of
 their positions.
+
+With a temperature (T > 0) the same tree is filled and verified by sampling.  The paper says nothing here either; what is
+used is the published rule that keeps the output exactly the target's: recursive rejection sampling with draws without
+replacement (Jeon et al., "Recursive speculative decoding", 2024; for one child per node it is Alg. 3 itself).
+  drafting:  the children of a node, in ascending rank, are successive draws from q = softmax(Q_node / T) without
+             replacement - the i-th draw by inverse CDF (ascending token index) over q with the earlier draws removed;
+  verifying: at the current node with target p = softmax(P_node / T): for each child in rank order with token x,
+             accept it with probability min(1, p(x) / q(x)) and move there; on a rejection p <- norm(max(0, p - q)) and
+             q <- q with q(x) = 0, renormalised.  When no child is accepted (or the node is a leaf) the emitted token is
+             drawn from the current p.
+Uniforms: child node v uses position v - 1 (draft stream for its draw, accept stream for its test), the emitted token
+position 0 of the residual stream - so a chain-shaped tree consumes exactly the counters of a chain round.
 """
 from __future__ import annotations
 
@@ -55,6 +67,70 @@ def ranked_tokens(logits: np.ndarray, r: int) -> np.ndarray:
     return np.argsort(-logits.astype(np.float64), kind="stable")[:r]
 
 
+def softmax64(logits: np.ndarray, T: float) -> np.ndarray:
+    x = logits.astype(np.float64) / T
+    e = np.exp(x - x.max())
+    return e / e.sum()
+
+
+def inv_cdf(w: np.ndarray, u: float):
+    """Smallest v with sum_{i<=v} w_i > u * sum(w) (ascending index; the last index with weight if rounding leaves none);
+    also the distance of u * sum(w) to the nearest CDF step, relative to sum(w)."""
+    c = np.cumsum(w)
+    Z = c[-1]
+    t = float(u) * Z
+    v = int(np.searchsorted(c, t, side="right"))
+    if v >= len(w):
+        v = int(np.nonzero(w > 0)[0][-1])
+    lo = c[v - 1] if v > 0 else 0.0
+    return v, float(min(abs(c[v] - t), abs(t - lo)) / Z)
+
+
+def draw_children(logits: np.ndarray, T: float, us) -> tuple:
+    """Successive draws without replacement from softmax(logits / T); returns (tokens, margins)."""
+    q = softmax64(logits, T)
+    toks, mgs = [], []
+    for u in us:
+        v, mg = inv_cdf(q, u)
+        toks.append(v)
+        mgs.append(mg)
+        q[v] = 0.0
+    return toks, mgs
+
+
+def walk_sampled(P: np.ndarray, Q: np.ndarray, tok, tree: Tree, T: float, u_acc, u_res: float) -> dict:
+    """The acceptance walk over a verified tree (see the module docstring).  u_acc[v] = the uniform of child node v.
+    Returns path, token and, for the near-tie bookkeeping of lock-step tests, the smallest |u - ratio| met and the margin
+    of the final draw."""
+    cur, path, gap = 0, [], np.inf
+    while True:
+        ch = sorted(tree.children(cur), key=lambda j: tree.rank[j])
+        p = softmax64(P[cur], T)
+        nxt = None
+        if ch:
+            q = softmax64(Q[cur], T)
+            for j in ch:
+                x = int(tok[j])
+                ratio = p[x] / q[x] if q[x] > 0.0 else np.inf
+                gap = min(gap, abs(float(u_acc[j]) - min(1.0, ratio)))
+                if float(u_acc[j]) < min(1.0, ratio):
+                    nxt = j
+                    break
+                r = np.maximum(p - q, 0.0)
+                Z = r.sum()
+                if Z > 0.0:
+                    p = r / Z
+                q[x] = 0.0
+                sq = q.sum()
+                if sq > 0.0:
+                    q = q / sq
+        if nxt is None:
+            token, mg = inv_cdf(p, u_res)
+            return dict(path=path, token=int(token), gap=float(gap), margin=mg)
+        path.append(nxt)
+        cur = nxt
+
+
 def _allow(model, tree: Tree, base: int, nodes: list) -> np.ndarray:
     al = np.zeros((len(nodes), model.max_ctx), np.uint8)
     for r, i in enumerate(nodes):
@@ -71,10 +147,13 @@ def move_accepted(model, base: int, path: list):
             kv[:, :, base + 1 + j] = kv[:, :, base + node]
 
 
-def tree_round(target, drafter, k: int, st, tree: Tree, tokens=None, outcome=None) -> dict:
-    """One greedy round with a draft tree; commits the result.  For lock-step tests: tokens = node tokens to use instead
-    of the drafter's own choices (the drafter is run all the same; its own choices are returned as own_tok), outcome =
-    (path, token) to commit instead of the walk on this side's logits (returned as path / token all the same)."""
+def tree_round(target, drafter, k: int, st, tree: Tree, tokens=None, outcome=None, T: float = 0.0, seed: int = 0, seq: int = 0) -> dict:
+    """One round with a draft tree (greedy for T = 0, sampled otherwise); commits the result.  For lock-step tests:
+    tokens = node tokens to use instead of the drafter's own choices (the drafter is run all the same; its own choices are
+    returned as own_tok), outcome = (path, token) to commit instead of the walk on this side's logits (returned as
+    own_path / own_token all the same)."""
+    from . import STREAM_ACCEPT, STREAM_DRAFT, STREAM_RESIDUAL, uniform
+
     l = st.l
     base = l - 1
     V = target.desc["vocab"]
@@ -82,6 +161,7 @@ def tree_round(target, drafter, k: int, st, tree: Tree, tokens=None, outcome=Non
     tok[0] = st.hist[base]
     own_tok = tok.copy()
     Q = np.zeros((tree.n, V), np.float32)               # drafter logits at the nodes above the deepest level
+    draw_margin = np.full(tree.n, np.inf)
     if getattr(drafter, "shares_kv", False):
         st.c[k] = base
     for d in range(tree.max_depth):
@@ -93,7 +173,14 @@ def tree_round(target, drafter, k: int, st, tree: Tree, tokens=None, outcome=Non
                                             _allow(drafter, tree, base, nodes))
         for i in nodes:
             ch = tree.children(i)
-            if ch:
+            if ch and T > 0.0:
+                ch = sorted(ch, key=lambda j: tree.rank[j])
+                drawn, mgs = draw_children(Q[i], T, [uniform(seed, seq, st.t, j - 1, STREAM_DRAFT) for j in ch])
+                for j, v, mg in zip(ch, drawn, mgs):
+                    own_tok[j] = v
+                    draw_margin[j] = mg
+                    tok[j] = own_tok[j] if tokens is None else tokens[j]
+            elif ch:
                 best = ranked_tokens(Q[i], max(tree.rank[j] for j in ch) + 1)
                 for j in ch:
                     own_tok[j] = best[tree.rank[j]]
@@ -101,17 +188,26 @@ def tree_round(target, drafter, k: int, st, tree: Tree, tokens=None, outcome=Non
     # verify: every node in one pass
     nodes = list(range(tree.n))
     P = target.forward_rows(tok, [base + i for i in nodes], [base + tree.depth[i] for i in nodes], _allow(target, tree, base, nodes))
-    # accept: follow the target's own greedy choices
     amax = [int(np.argmax(P[i])) for i in nodes]        # numpy's argmax: first maximum = lowest token on ties
-    cur, path = 0, []
-    while True:
-        nxt = [j for j in tree.children(cur) if tok[j] == amax[cur]]
-        if not nxt:
-            break
-        cur = nxt[0]
-        path.append(cur)
-    own = (list(path), amax[cur])
-    token = amax[cur]
+    walk = None
+    if T > 0.0:
+        # accept: recursive rejection sampling down the tree
+        u_acc = np.zeros(tree.n, np.float32)
+        for j in range(1, tree.n):
+            u_acc[j] = uniform(seed, seq, st.t, j - 1, STREAM_ACCEPT)
+        walk = walk_sampled(P, Q, tok, tree, T, u_acc, uniform(seed, seq, st.t, 0, STREAM_RESIDUAL))
+        path, token = list(walk["path"]), walk["token"]
+    else:
+        # accept: follow the target's own greedy choices
+        cur, path = 0, []
+        while True:
+            nxt = [j for j in tree.children(cur) if tok[j] == amax[cur]]
+            if not nxt:
+                break
+            cur = nxt[0]
+            path.append(cur)
+        token = amax[cur]
+    own = (list(path), token)
     if outcome is not None:
         path, token = list(outcome[0]), int(outcome[1])
     n = len(path)
@@ -123,13 +219,13 @@ def tree_round(target, drafter, k: int, st, tree: Tree, tokens=None, outcome=Non
     st.l = l + n + 1
     st.c[k] = st.l - 1 if getattr(drafter, "shares_kv", False) else min(l + n, l + tree.max_depth - 1)
     out = dict(k=k, round=st.t, l_before=l, tok=tok, own_tok=own_tok, P=P, Q=Q, amax=amax, path=path, n_acc=n, token=token,
-               own_path=own[0], own_token=own[1])
+               own_path=own[0], own_token=own[1], walk=walk, draw_margin=draw_margin)
     st.t += 1
     return out
 
 
-def generate_tree(target, drafters, prompt, n_new: int, tree: Tree, beta: float, policy=None) -> dict:
-    """Greedy MetaSD-UCB generation with tree rounds; reward = N_acc / depth of the tree (Def. 1 with N_max = depth)."""
+def generate_tree(target, drafters, prompt, n_new: int, tree: Tree, beta: float, policy=None, T: float = 0.0, seed: int = 0) -> dict:
+    """MetaSD-UCB generation with tree rounds; reward = N_acc / depth of the tree (Def. 1 with N_max = depth)."""
     from . import SdState, Ucb, reward_be
 
     prompt = np.asarray(prompt, np.int32)
@@ -146,7 +242,7 @@ def generate_tree(target, drafters, prompt, n_new: int, tree: Tree, beta: float,
         k = bandit.select()
         if policy is not None:
             k = int(policy(st.t))
-        r = tree_round(target, drafters[k], k, st, tree)
+        r = tree_round(target, drafters[k], k, st, tree, T=T, seed=seed)
         bandit.update(k, reward_be(r["n_acc"], tree.max_depth))
         rounds.append(r)
     return dict(tokens=st.hist[l0:B].copy(), total_len=st.l, rounds=rounds, state=st)

@@ -128,3 +128,114 @@ def test_a_tree_accepts_at_least_what_its_likeliest_path_accepts(c1):
             assert res[1] >= res[0]
             gains += res[1] > res[0]
     assert gains >= 1
+
+
+# ---------------------------------------------------------------- sampled trees (T > 0)
+
+def test_sampled_chain_tree_is_alg3(c1):
+    """One child per node: drawing without replacement is drawing, and recursive rejection sampling is Alg. 3 - with
+    the same counters a chain-shaped tree reproduces the chain rounds of the (separately pinned) accept step exactly."""
+    t = Tree(**W.draft_tree("chain5"))
+    for arm, temp in ((0, 1.0), (2, 0.7)):
+        T, D = models(c1)
+        a = oracle.generate(T, D, c1["prompt"], c1["n_new"], 5, temp, c1["seed"], c1["beta"], policy=lambda r, a=arm: a)
+        T, D = models(c1)
+        b = oracle.generate_tree(T, D, c1["prompt"], c1["n_new"], t, c1["beta"], policy=lambda r, a=arm: a, T=temp, seed=c1["seed"])
+        assert np.array_equal(a["tokens"], b["tokens"])
+        assert [r["n_acc"] for r in a["rounds"]] == [r["n_acc"] for r in b["rounds"]]
+        for ra, rb in zip(a["rounds"], b["rounds"]):
+            assert np.array_equal(ra["d"], rb["tok"][1:])
+        assert max(r["n_acc"] for r in b["rounds"]) >= 2
+
+
+def _toy_round(rng, tree, ptab, qtab, temp=1.0):
+    """One sampled round on a toy in which the target's and the drafter's next-token laws depend on the last token only
+    (ptab[x], qtab[x] = logits after token x; the root's token is 0): draws the children, walks, returns the emitted
+    tokens of the round in order."""
+    from oracle.tree import draw_children, walk_sampled
+    tok = np.zeros(tree.n, np.int64)
+    for i in range(tree.n):
+        ch = sorted(tree.children(i), key=lambda j: tree.rank[j])
+        if ch:
+            drawn, _ = draw_children(qtab[tok[i]], temp, rng.random(len(ch)))
+            for j, v in zip(ch, drawn):
+                tok[j] = v
+    w = walk_sampled(ptab[tok], qtab[tok], tok, tree, temp, rng.random(tree.n), rng.random())
+    return [int(tok[j]) for j in w["path"]] + [w["token"]]
+
+
+@pytest.mark.parametrize("temp", [1.0, 0.6])
+def test_sampled_tree_is_lossless_on_a_toy(temp):
+    """Losslessness (the paragraph after Alg. 3), which is all the paper fixes for multi-draft rounds: whatever the
+    drafter and the tree, the tokens a round emits are distributed as the target's own sampling.  V = 4, a tree with
+    three children at the root and two below the first of them; 200k rounds: the law of the first emitted token is
+    p(. | root), and the joint law of the first two (when a second one exists it was either an accepted grandchild or
+    the residual / bonus draw after an accepted child) is p(x1 | root) p(x2 | x1) restricted to rounds that emit two -
+    compared through the unconditional law of the first token and the conditional law of the second given the first and
+    given that the first was an accepted draft (that event depends on x1 only through independent randomness)."""
+    rng = np.random.default_rng(11)
+    V = 4
+    ptab = rng.normal(0, 1.5, (V, V))
+    qtab = ptab + rng.normal(0, 1.0, (V, V))
+    tree = Tree([-1, 0, 0, 0, 1, 1, 2], [0, 0, 1, 2, 0, 1, 0])
+    from oracle.tree import softmax64
+    n = 200_000
+    first = np.zeros(V)
+    second = np.zeros((V, V))
+    for _ in range(n):
+        out = _toy_round(rng, tree, ptab, qtab, temp)
+        first[out[0]] += 1
+        if len(out) >= 2:
+            second[out[0], out[1]] += 1
+    p0 = softmax64(ptab[0], temp)
+    sd = np.sqrt(p0 * (1 - p0) / n)
+    assert (np.abs(first / n - p0) < 4.5 * sd).all(), (first / n, p0)
+    for x in range(V):
+        m = second[x].sum()
+        if m < 2000:
+            continue
+        px = softmax64(ptab[x], temp)
+        sdx = np.sqrt(px * (1 - px) / m)
+        assert (np.abs(second[x] / m - px) < 4.5 * sdx).all(), (x, second[x] / m, px)
+
+
+def test_sampled_tree_special_cases():
+    """q = p: every first child is accepted (ratio 1 > u); disjoint supports: nothing is accepted and the emitted token
+    is a draw from p; draws without replacement never repeat a token and follow the renormalised law."""
+    from oracle.tree import draw_children, softmax64, walk_sampled
+    rng = np.random.default_rng(5)
+    V = 16
+    tree = Tree(**W.draft_tree("wide"))
+    P = rng.normal(0, 2, (tree.n, V)).astype(np.float32)
+    tok = rng.integers(0, V, tree.n)
+    w = walk_sampled(P, P.copy(), tok, tree, 1.0, rng.random(tree.n) * 0.999, 0.3)
+    cur, want = 0, []
+    while tree.children(cur):
+        cur = min(tree.children(cur), key=lambda j: tree.rank[j])
+        want.append(cur)
+    assert w["path"] == want
+    Pd, Qd = P.copy(), P.copy()
+    Pd[:, : V // 2] = -1e9
+    Qd[:, V // 2:] = -1e9
+    tokq = rng.integers(0, V // 2, tree.n)
+    w = walk_sampled(Pd, Qd, tokq, tree, 1.0, rng.random(tree.n), 0.37)
+    assert w["path"] == [] and w["token"] >= V // 2
+    p = softmax64(Pd[0], 1.0)
+    c = np.cumsum(p)
+    assert c[w["token"]] > 0.37 >= (c[w["token"] - 1] if w["token"] else 0.0)
+    # without replacement: second draw follows q with the first removed
+    logits = rng.normal(0, 1, 6)
+    q = softmax64(logits, 1.0)
+    cnt = np.zeros((6, 6))
+    m = 60_000
+    for _ in range(m):
+        a, b = draw_children(logits, 1.0, rng.random(2))[0]
+        assert a != b
+        cnt[a, b] += 1
+    for a in range(6):
+        na = cnt[a].sum()
+        want2 = q.copy()
+        want2[a] = 0
+        want2 /= want2.sum()
+        assert abs(na / m - q[a]) < 4.5 * np.sqrt(q[a] * (1 - q[a]) / m)
+        assert (np.abs(cnt[a] / na - want2) < 4.5 * np.sqrt(want2 * (1 - want2) / na) + 1e-12).all()
