@@ -203,15 +203,27 @@ int32_t metasd_accept(metasd_ctx*, int32_t gamma, int32_t* n_acc_out, int32_t* t
                       double* bd_out);
 
 /* ---- multi-candidate rounds: a tree of draft tokens verified in one pass with tree attention -----------------------
- * (the white-box setting of the paper's Sec. 4, "Number of drafts": multi-draft methods verify a token tree; greedy
- * decoding only - for T = 0 the acceptance rule follows from losslessness (the paragraph after Alg. 3): the output must
- * be the target's own greedy continuation, so the accepted nodes are the longest path from the root on which every
- * token is the target's most likely next token; the paper states no rule for sampled trees).
+ * (the white-box setting of the paper's Sec. 4, "Number of drafts": multi-draft methods verify a token tree).  The paper
+ * states no rule for trees; what it fixes is losslessness (the paragraph after Alg. 3), and the rules here are the ones
+ * that keep it:
+ *   T = 0: the output must be the target's own greedy continuation, so the children of a node are the drafter's most
+ *          likely next tokens and the accepted nodes are the longest path from the root on which every token is the
+ *          target's most likely next token;
+ *   T > 0: the children of a node, in ascending rank, are successive draws WITHOUT replacement from
+ *          q = softmax(Q_node / T); verification is recursive rejection sampling (Jeon et al., "Recursive speculative
+ *          decoding", 2024): at the current node with p = softmax(P_node / T), for each child in rank order with token
+ *          x: accept with probability min(1, p(x) / q(x)) and move there; on a rejection p <- norm(max(0, p - q)) and
+ *          q <- q with q(x) = 0, renormalised; when no child is accepted (or at a leaf) the emitted token is a draw
+ *          from the current p.  With one child per node this is Alg. 3.  Philox counters: child node v uses position
+ *          v - 1 (stream 2 for its draw, stream 0 for its test), the emitted token position 0 of stream 1 - a
+ *          chain-shaped tree consumes exactly the counters of metasd_draft / metasd_accept.
  *
- * The tree's SHAPE is the caller's: node 0 is the root (the last committed token); node i > 0 is the rank[i]-th most
- * likely next token (by the drafter's logits; 0 = most likely, ties to the lower token) after node parent[i] < i.
- * Nodes come in breadth-first order (depth never decreases), 2 <= n <= min(16, gamma_max + 1), and the nodes above
- * the deepest level number at most gamma_max.  A chain (parent[i] = i - 1, rank 0) is ordinary greedy speculation. */
+ * The tree's SHAPE is the caller's: node 0 is the root (the last committed token); node i > 0 is a child of node
+ * parent[i] < i with rank rank[i]: for T = 0 the rank[i]-th most likely next token by the drafter's logits (0 = most
+ * likely, ties to the lower token), for T > 0 the children of a node are drawn in ascending rank (only the order of the
+ * ranks matters).  Nodes come in breadth-first order (depth never decreases), 2 <= n <= min(16, gamma_max + 1), and
+ * the nodes above the deepest level number at most gamma_max.  A chain (parent[i] = i - 1, rank 0) is ordinary
+ * speculation. */
 #define METASD_MAX_TREE 16
 typedef struct {
     int32_t n;
@@ -222,14 +234,15 @@ typedef struct {
 /* Drafter k fills the tree level by level: one forward pass per level over that level's nodes (each node attends to
  * the committed tokens and to its own ancestors, and is rotated for position l - 1 + depth), then the children of
  * every node of the level get their tokens.  The first pass consumes the drafter's backlog of committed tokens as in
- * metasd_draft.  Contexts with batch == 1 and temperature == 0 only.
- * Errors: INVALID (shape, k, not greedy, batch > 1), OVERFLOW, ORDER, HIP. */
+ * metasd_draft.  Contexts with batch == 1 only.
+ * Errors: INVALID (shape, k, batch > 1), OVERFLOW, ORDER, HIP. */
 int32_t metasd_draft_tree(metasd_ctx*, int32_t k, const metasd_tree* tree);
 /* One target pass over all n nodes with the same tree attention; node i's K/V go to cache slot l - 1 + i for now;
  * fp32 logits [n][V] on the device (METASD_PEEK_P).  Errors: ORDER, HIP. */
 int32_t metasd_verify_tree(metasd_ctx*);
-/* Greedy acceptance: from the root, step to the child that carries the target's most likely token, as long as there is
- * one; N_acc = steps taken, emitted token = the target's most likely token at the last node reached.  The K/V of the
+/* Acceptance.  T = 0: from the root, step to the child that carries the target's most likely token, as long as there is
+ * one; N_acc = steps taken, emitted token = the target's most likely token at the last node reached.  T > 0: the walk
+ * described above (one workgroup holds p and q of the current node in registers).  The K/V of the
  * accepted nodes are moved from their tree slots to their positions (target and drafter caches), history, KV lengths
  * and round counter are committed.  path_out (host, may be NULL): the accepted nodes, N_acc entries.  The BE reward of
  * the round is N_acc / (depth of the tree): pass that depth as `gamma` to metasd_bandit_update.

@@ -270,7 +270,7 @@ class MetaSD:
             return int(n[0]), int(tok[0]), int(mask[0]), float(bd[0])
         return n, tok, mask, bd
 
-    # ---- tree rounds (greedy contexts): parent[i], rank[i] per node, node 0 the root
+    # ---- tree rounds (greedy for temperature 0, sampled otherwise): parent[i], rank[i] per node, node 0 the root
     def draft_tree(self, k: int, parent, rank):
         n = len(parent)
         assert len(rank) == n and n <= 16

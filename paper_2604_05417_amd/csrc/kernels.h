@@ -2553,6 +2553,207 @@ __global__ void accept_tree_kernel(const int32_t* __restrict__ amax, const int32
     hist_base[1 + n] = token;
 }
 
+// ------------------------------------------------------------------------------------------
+// Sampled draft trees (T > 0): the children of a node, in ascending rank, are successive draws without replacement from
+// q = softmax(logits / T); the walk over the verified tree is recursive rejection sampling (Jeon et al., "Recursive
+// speculative decoding", 2024 - for one child per node it is the accept step of the chain).  Uniforms: child node v uses
+// position v - 1 (draft stream for its draw, accept stream for its test), the emitted token position 0 of the residual
+// stream, so a chain-shaped tree uses exactly the counters of a chain round.
+
+// the children of `node` in ascending rank; returns how many
+__device__ __forceinline__ int tree_children_of(const TreeShape& ts, int node, int (&ch)[TREE_RANKS]) {
+    int n = 0;
+    for (int r = 0; r < TREE_RANKS; ++r)
+        for (int i = node + 1; i < ts.n; ++i)
+            if (ts.parent[i] == node && ts.rank[i] == r && n < TREE_RANKS) ch[n++] = i;
+    return n;
+}
+
+// this thread's sum of its 64 values, in the order of ak_exp_inplace
+__device__ __forceinline__ float ak_thread_sum(const float (&x)[AK_CH][4]) {
+    float s = 0.f;
+#pragma unroll
+    for (int c = 0; c < AK_CH; ++c) s += (x[c][0] + x[c][1]) + (x[c][2] + x[c][3]);
+    return s;
+}
+
+// sm.dz[which][wave] <- the wavefront totals of x; returns their sum (every thread).  Two barriers.
+__device__ __forceinline__ double ak_totals(const float (&x)[AK_CH][4], AkShared& sm, int which, int wave, int lane) {
+    const double a = wave_sum((double)ak_thread_sum(x));
+    __syncthreads();                                   // earlier readers of sm.dz are done
+    if (lane == 0) sm.dz[which][wave] = a;
+    __syncthreads();
+    double Z = 0.0;
+#pragma unroll
+    for (int k = 0; k < AK_WAVES; ++k) Z += sm.dz[which][k];
+    return Z;
+}
+
+// element `idx` of the vocabulary as held in x: the value (0 elsewhere); with zero = true the owner also clears it
+__device__ __forceinline__ float ak_take(float (&x)[AK_CH][4], int idx, int wave, int lane, bool zero) {
+    float v = 0.f;
+    const int off = idx - wave * AK_SEG - lane * 4;     // = 256 c + e for the owner
+    if (off >= 0 && off < AK_SEG && (off & 255) < 4) {
+        const int cd = off >> 8, ed = off & 3;
+#pragma unroll
+        for (int c = 0; c < AK_CH; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (c == cd && e == ed) { v = x[c][e]; if (zero) x[c][e] = 0.f; }
+    }
+    return v;
+}
+
+// Row r holds the drafter's logits at node node0 + r; every child of the node gets its token:
+// hist[base + i] = tok[i] = the draw.   grid (rows), block 512
+template <bool UNIT_T>
+__device__ __forceinline__ void tree_children_sample_body(const float* __restrict__ logits, int V, float T, uint64_t seed, uint32_t seq,
+                                                          uint32_t round, const TreeShape& ts, int node0,
+                                                          int32_t* __restrict__ hist_base, int32_t* __restrict__ tok, AkShared& sm) {
+    const int node = node0 + (int)blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int ch[TREE_RANKS];
+    const int nch = tree_children_of(ts, node, ch);
+    if (nch == 0) return;                              // workgroup-uniform
+    float x[AK_CH][4];
+    ak_load(logits + (size_t)blockIdx.x * V, V, wave, lane, x);
+    const float a = wave_max(ak_thread_max(x));
+    if (lane == 0) sm.fmx[0][wave] = a;
+    __syncthreads();
+    float mx = sm.fmx[0][0];
+#pragma unroll
+    for (int k = 1; k < AK_WAVES; ++k) mx = fmaxf(mx, sm.fmx[0][k]);
+    ak_exp_inplace<UNIT_T>(x, mx, 1.0 / (double)T);
+    for (int c = 0; c < nch; ++c) {
+        const double Z = ak_totals(x, sm, 0, wave, lane);
+        const float u = philox_uniform(seed, seq, round, (uint32_t)(ch[c] - 1), 2u);
+        ak_search(x, sm.dz[0], Z, u, V, sm, wave, lane);
+        __syncthreads();
+        const int t = sm.token;
+        if (threadIdx.x == 0) { hist_base[ch[c]] = t; tok[ch[c]] = t; }
+        ak_take(x, t, wave, lane, true);               // drawn: out of the urn
+    }
+}
+
+__global__ __launch_bounds__(AK_NT) void tree_children_sample_kernel(const float* __restrict__ logits, int V, float T, uint64_t seed,
+                                                                     uint32_t seq, uint32_t round, TreeShape ts, int node0,
+                                                                     int32_t* __restrict__ hist_base, int32_t* __restrict__ tok) {
+    __shared__ AkShared sm;
+    if (T == 1.0f) tree_children_sample_body<true>(logits, V, T, seed, seq, round, ts, node0, hist_base, tok, sm);
+    else tree_children_sample_body<false>(logits, V, T, seed, seq, round, ts, node0, hist_base, tok, sm);
+}
+
+// x *= 1 / Z (1/Z applied as two floats)
+__device__ __forceinline__ void ak_scale(float (&x)[AK_CH][4], double Z) {
+    const double iz = 1.0 / Z;
+    const float hi = (float)iz, lo = (float)(iz - (double)hi);
+#pragma unroll
+    for (int c = 0; c < AK_CH; ++c)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[c][e] = fmaf(x[c][e], lo, x[c][e] * hi);
+}
+
+// x <- softmax(row / T) as fp32 probabilities
+template <bool UNIT_T>
+__device__ __forceinline__ void ak_normalised(const float* __restrict__ row, int V, double invT, float (&x)[AK_CH][4], AkShared& sm, int wave,
+                                              int lane) {
+    ak_load(row, V, wave, lane, x);
+    const float a = wave_max(ak_thread_max(x));
+    __syncthreads();
+    if (lane == 0) sm.fmx[0][wave] = a;
+    __syncthreads();
+    float mx = sm.fmx[0][0];
+#pragma unroll
+    for (int k = 1; k < AK_WAVES; ++k) mx = fmaxf(mx, sm.fmx[0][k]);
+    ak_exp_inplace<UNIT_T>(x, mx, invT);
+    ak_scale(x, ak_totals(x, sm, 0, wave, lane));
+}
+
+// The walk.  P[i], Q[i]: target / drafter logits at node i (Q only for nodes with children); tok[i]: the node's token.
+// One workgroup holds the two distributions of the current node in registers as probabilities and updates them in
+// place after every rejection.  res and hist as accept_tree_kernel.     grid (1), block 512
+template <bool UNIT_T>
+__device__ __forceinline__ void accept_tree_sample_body(const float* __restrict__ P, const float* __restrict__ Q,
+                                                        const int32_t* __restrict__ tok, int V, float T, uint64_t seed, uint32_t seq,
+                                                        uint32_t round, const TreeShape& ts, int32_t* __restrict__ res,
+                                                        int32_t* __restrict__ hist_base, AkShared& sm, float* pick, int* spath) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const double invT = 1.0 / (double)T;
+    int cur = 0, npath = 0, token = -1;
+    float xp[AK_CH][4], xq[AK_CH][4];
+    for (;;) {
+        int ch[TREE_RANKS];
+        const int nch = tree_children_of(ts, cur, ch);
+        ak_normalised<UNIT_T>(P + (size_t)cur * V, V, invT, xp, sm, wave, lane);
+        if (nch > 0) ak_normalised<UNIT_T>(Q + (size_t)cur * V, V, invT, xq, sm, wave, lane);
+        int next = -1;
+#pragma unroll 1
+        for (int c = 0; c < nch; ++c) {
+            int child = ch[0];
+#pragma unroll
+            for (int i = 1; i < TREE_RANKS; ++i) child = c == i ? ch[i] : child;
+            const int x = min(max(tok[child], 0), V - 1);          // clamped: stays in bounds for any input
+            const int off = x - wave * AK_SEG - lane * 4;
+            const bool owner = off >= 0 && off < AK_SEG && (off & 255) < 4;
+            const float pv = ak_take(xp, x, wave, lane, false), qv = ak_take(xq, x, wave, lane, true);   // q(x) leaves the urn either way
+            __syncthreads();
+            if (owner) { pick[0] = pv; pick[1] = qv; }
+            __syncthreads();
+            const double pd = (double)pick[0], qd = (double)pick[1];
+            bool acc = true;
+            if (qd > 0.0) {
+                const double ratio = pd / qd;
+                const float u = philox_uniform(seed, seq, round, (uint32_t)(child - 1), 0u);
+                acc = (double)u < (ratio < 1.0 ? ratio : 1.0);
+            }
+            if (acc) { next = child; break; }
+            // rejected: p <- norm(max(0, p - q)) with q still counting q(x); q <- q without x, renormalised
+#pragma unroll
+            for (int cc = 0; cc < AK_CH; ++cc)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float qe = (owner && cc == (off >> 8) && e == (off & 3)) ? qv : xq[cc][e];
+                    xp[cc][e] = fmaxf(xp[cc][e] - qe, 0.f);
+                }
+            const double Zr = ak_totals(xp, sm, 0, wave, lane);
+            if (Zr > 0.0) ak_scale(xp, Zr);
+            else ak_normalised<UNIT_T>(P + (size_t)cur * V, V, invT, xp, sm, wave, lane);   // p == q to rounding: a rejection has probability 0; keep p
+            const double Sq = ak_totals(xq, sm, 1, wave, lane);
+            if (Sq > 0.0) ak_scale(xq, Sq);
+        }
+        if (next < 0) {
+            const double Z = ak_totals(xp, sm, 0, wave, lane);
+            const float u = philox_uniform(seed, seq, round, 0u, 1u);
+            ak_search(xp, sm.dz[0], Z, u, V, sm, wave, lane);
+            __syncthreads();
+            token = sm.token;
+            break;
+        }
+        if (threadIdx.x == 0) spath[npath] = next;
+        ++npath;
+        cur = next;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        res[0] = npath;
+        res[1] = token;
+        for (int j = 0; j < npath; ++j) res[2 + j] = spath[j];
+        for (int j = 0; j < npath; ++j) hist_base[1 + j] = tok[spath[j]];     // path[j] >= j + 1: reads from tok, a separate array
+        hist_base[1 + npath] = token;
+    }
+}
+
+__global__ __launch_bounds__(AK_NT) void accept_tree_sample_kernel(const float* __restrict__ P, const float* __restrict__ Q,
+                                                                   const int32_t* __restrict__ tok, int V, float T, uint64_t seed,
+                                                                   uint32_t seq, uint32_t round, TreeShape ts, int32_t* __restrict__ res,
+                                                                   int32_t* __restrict__ hist_base) {
+    __shared__ AkShared sm;
+    __shared__ float pick[2];
+    __shared__ int spath[TREE_MAX];
+    if (T == 1.0f) accept_tree_sample_body<true>(P, Q, tok, V, T, seed, seq, round, ts, res, hist_base, sm, pick, spath);
+    else accept_tree_sample_body<false>(P, Q, tok, V, T, seed, seq, round, ts, res, hist_base, sm, pick, spath);
+}
+
 // After acceptance the K/V of the accepted nodes move from their tree slots to the positions they were rotated for:
 // slot base + path[j] -> base + 1 + j for j < n (path[j] >= j + 1 and ascending, so a thread that owns one element
 // offset and walks j upwards never overwrites a source it still needs).   grid (ceil(planes * hd / 256)), block 256

@@ -1861,7 +1861,6 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
 int32_t metasd_draft_tree(metasd_ctx* c, int32_t k, const metasd_tree* tree) {
     if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
     if (c->cfg.batch != 1) return c->fail(METASD_E_INVALID, "draft_tree: contexts with one sequence only");
-    if (c->cfg.temperature != 0.f) return c->fail(METASD_E_INVALID, "draft_tree: greedy contexts only (temperature 0): the paper states no acceptance rule for sampled trees");
     if (k < 0 || k >= c->cfg.K || !tree) return c->fail(METASD_E_INVALID, "draft_tree: bad drafter index or NULL tree");
     if (c->phase != PH_READY) return c->fail(METASD_E_ORDER, "draft_tree: call set_context first / finish the previous round");
     const int n = tree->n;
@@ -1908,7 +1907,11 @@ int32_t metasd_draft_tree(metasd_ctx* c, int32_t k, const metasd_tree* tree) {
             c->tree = nullptr;
         }
         if (rc) return rc;
-        hipLaunchKernelGGL(tree_children_kernel, dim3(m), dim3(AK_NT), 0, c->stream, (const float*)Qd, V, ts, i0, c->d_hist() + base, c->d_draft());
+        if (c->cfg.temperature > 0.f)
+            hipLaunchKernelGGL(tree_children_sample_kernel, dim3(m), dim3(AK_NT), 0, c->stream, (const float*)Qd, V, c->cfg.temperature, c->cfg.seed,
+                               0u, (uint32_t)c->sq[0].round, ts, i0, c->d_hist() + base, c->d_draft());
+        else
+            hipLaunchKernelGGL(tree_children_kernel, dim3(m), dim3(AK_NT), 0, c->stream, (const float*)Qd, V, ts, i0, c->d_hist() + base, c->d_draft());
         LAUNCH_CHECK(c, "tree_children");
     }
     c->tshape = ts;
@@ -1936,10 +1939,16 @@ int32_t metasd_accept_tree(metasd_ctx* c, int32_t* n_acc_out, int32_t* token_out
     if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
     if (c->phase != PH_TREE_VERIFIED) return c->fail(METASD_E_ORDER, "accept_tree: verify_tree has not been run for this round");
     const int n = c->tshape.n, V = c->target.d.vocab, l = c->sq[0].l, base = l - 1;
-    int32_t* amax = reinterpret_cast<int32_t*>(c->d_cand());
-    if (launch_sample(c->stream, c->d_P(), n, V, 0.f, c->cfg.seed, 0u, 0u, 0u, amax, 1, nullptr)) return c->fail(METASD_E_HIP, "launch argmax failed");
-    hipLaunchKernelGGL(accept_tree_kernel, dim3(1), dim3(64), 0, c->stream, (const int32_t*)amax, (const int32_t*)c->d_draft(), c->tshape, c->d_res(),
-                       c->d_hist() + base);
+    if (c->cfg.temperature > 0.f) {
+        hipLaunchKernelGGL(accept_tree_sample_kernel, dim3(1), dim3(AK_NT), 0, c->stream, (const float*)c->d_P(), (const float*)c->d_Q(),
+                           (const int32_t*)c->d_draft(), V, c->cfg.temperature, c->cfg.seed, 0u, (uint32_t)c->sq[0].round, c->tshape, c->d_res(),
+                           c->d_hist() + base);
+    } else {
+        int32_t* amax = reinterpret_cast<int32_t*>(c->d_cand());
+        if (launch_sample(c->stream, c->d_P(), n, V, 0.f, c->cfg.seed, 0u, 0u, 0u, amax, 1, nullptr)) return c->fail(METASD_E_HIP, "launch argmax failed");
+        hipLaunchKernelGGL(accept_tree_kernel, dim3(1), dim3(64), 0, c->stream, (const int32_t*)amax, (const int32_t*)c->d_draft(), c->tshape, c->d_res(),
+                           c->d_hist() + base);
+    }
     LAUNCH_CHECK(c, "accept_tree");
     Model& D = c->drafters[c->sq[0].cur_k];
     int rc = c->target.d.dtype == METASD_BF16 ? compact_kv<bf16_t>(c, c->target, base, TREE_MAX) : compact_kv<float>(c, c->target, base, TREE_MAX);

@@ -1,4 +1,5 @@
-"""GPU parity of multi-candidate (tree) rounds in greedy mode against the oracle: the drafter fills a tree of candidates
+"""GPU parity of multi-candidate (tree) rounds against the oracle, greedy (T = 0) and sampled (T > 0; the additions for
+it are described at TreeLockStep.round).  In greedy mode: the drafter fills a tree of candidates
 level by level with tree attention, the target verifies all nodes in one pass, the longest path of the target's own
 greedy choices is accepted, the K/V of the accepted nodes move to their positions.  Every round is compared:
   - the children the GPU gave every node are the drafter's most likely tokens by the GPU's own logits (exact);
@@ -23,8 +24,9 @@ pytestmark = pytest.mark.gpu
 
 
 class TreeLockStep:
-    def __init__(self, gpu, target, drafters, prompt, tree, beta, tol, kv_prefilled=False):
+    def __init__(self, gpu, target, drafters, prompt, tree, beta, tol, kv_prefilled=False, temp=0.0, seed=0):
         self.g, self.T, self.D, self.tree, self.tol = gpu, target, drafters, tree, tol
+        self.temp, self.seed = temp, seed
         hist = np.zeros(target.max_ctx, np.int32)
         hist[: len(prompt)] = prompt
         self.st = oracle.SdState(hist=hist, l=len(prompt), c=[len(prompt) - 1 if kv_prefilled else 0] * len(drafters))
@@ -34,6 +36,13 @@ class TreeLockStep:
         self.stats = dict(rounds=0, max_dp=0.0, max_dq=0.0, ties=0, n_acc=[], branch=0)
 
     def round(self, force_k=None):
+        """Sampled rounds (temp > 0) are checked in the same stages, with the sampling rules in place of the greedy ones:
+        the children of a node are the oracle's draws without replacement on the GPU's own drafter logits with the same
+        uniforms, and the accepted path and emitted token are the oracle's walk (recursive rejection sampling) on the
+        GPU's own logits and tokens - exactly, except inside the near-tie windows of the chain protocol (a CDF step
+        within 1e-6 of the target, |u - ratio| < 1e-3), which are counted."""
+        if self.temp > 0.0:
+            return self.round_sampled(force_k)
         g, t, st, tol = self.g, self.tree, self.st, self.tol
         k_gpu, k_or = g.bandit_select(), self.bandit.select()
         assert k_gpu == k_or
@@ -94,15 +103,74 @@ class TreeLockStep:
         return n, token
 
 
-def make(cfg, tree, tol, share_kv=False, kv_prefilled=False, device="cpu"):
+    def round_sampled(self, force_k=None):
+        from oracle.tree import draw_children, walk_sampled
+        g, t, st, tol, T, seed = self.g, self.tree, self.st, self.tol, self.temp, self.seed
+        k_gpu, k_or = g.bandit_select(), self.bandit.select()
+        assert k_gpu == k_or
+        k = k_gpu if force_k is None else force_k
+        l, rnd = st.l, st.t
+        g.draft_tree(k, t.parent, t.rank)
+        g.verify_tree()
+        n, token, path = g.accept_tree()
+        Pg = g.peek("P")[: t.n].cpu().numpy()
+        Qg = np.zeros_like(Pg)
+        Qg[: t.n - 1] = g.peek("Q")[: t.n - 1].cpu().numpy()
+        tok = g.peek("draft")[: t.n].cpu().numpy().copy()
+        tok[0] = st.hist[l - 1]
+        hist = g.peek("hist")[l: l + n + 1].cpu().numpy()
+        inner = [i for i in range(t.n) if t.depth[i] < t.max_depth]
+        # children: the oracle's draws on the GPU's own drafter logits
+        for i in inner:
+            ch = sorted(t.children(i), key=lambda j: t.rank[j])
+            if ch:
+                drawn, mgs = draw_children(Qg[i], T, [oracle.uniform(seed, 0, rnd, j - 1, oracle.STREAM_DRAFT) for j in ch])
+                for j, v, mg in zip(ch, drawn, mgs):
+                    if tok[j] != v:
+                        assert mg < 1e-6, f"round {rnd}: node {j}: GPU drew {tok[j]}, the oracle {v} on the same logits (margin {mg})"
+                        self.stats["ties"] += 1
+                        break                      # later draws of this node start from another urn
+        # the walk on the GPU's own logits and tokens
+        u_acc = np.zeros(t.n, np.float32)
+        for j in range(1, t.n):
+            u_acc[j] = oracle.uniform(seed, 0, rnd, j - 1, oracle.STREAM_ACCEPT)
+        w = walk_sampled(Pg, Qg, tok, t, T, u_acc, oracle.uniform(seed, 0, rnd, 0, oracle.STREAM_RESIDUAL))
+        if (w["path"], w["token"]) != (path, token):
+            assert w["gap"] < 1e-3 or w["margin"] < 1e-6, (f"round {rnd}: GPU path {path} token {token}, the oracle's walk on the same logits "
+                                                            f"{w['path']} {w['token']} (gap {w['gap']}, margin {w['margin']})")
+            self.stats["ties"] += 1
+        assert (hist[:n] == tok[path]).all() and hist[n] == token
+        # the oracle on the GPU's tokens, committing the GPU's outcome
+        r = oracle.tree_round(self.T, self.D[k], k, st, t, tokens=tok, outcome=(path, token), T=T, seed=seed)
+        dq = float(np.abs(r["Q"][inner] - Qg[inner]).max())
+        dp = float(np.abs(r["P"] - Pg).max())
+        self.stats["max_dq"], self.stats["max_dp"] = max(self.stats["max_dq"], dq), max(self.stats["max_dp"], dp)
+        assert dq <= tol and dp <= tol, f"round {rnd}: logits differ by {dq} (drafter) / {dp} (target)"
+        if tol <= 1e-3 and ((r["own_path"], r["own_token"]) != (path, token) or not np.array_equal(r["own_tok"][1:], tok[1:])):
+            # fp32: the oracle's own round is the GPU's, outside the near-tie windows
+            assert r["walk"]["gap"] < 1e-3 or r["walk"]["margin"] < 1e-5 or r["draw_margin"].min() < 1e-5, \
+                f"round {rnd}: oracle outcome {r['own_path']} {r['own_token']} vs GPU {path} {token}"
+            self.stats["ties"] += 1
+        self.bandit.update(k, oracle.reward_be(n, t.max_depth))
+        g.bandit_update(k, n, t.max_depth)
+        lg, kvg, rg = g.state(-1)
+        assert (lg, kvg, rg) == (st.l, st.l - 1, st.t)
+        assert g.state(k)[1] == st.c[k]
+        self.stats["rounds"] += 1
+        self.stats["n_acc"].append(n)
+        self.stats["branch"] += sum(1 for i in path if t.rank[i] > 0)
+        return n, token
+
+
+def make(cfg, tree, tol, share_kv=False, kv_prefilled=False, device="cpu", temp=0.0):
     td, tw = cfg["target"]
-    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=15, max_ctx=cfg["max_ctx"], temperature=0.0, seed=cfg["seed"], ucb_beta=cfg["beta"],
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=15, max_ctx=cfg["max_ctx"], temperature=temp, seed=cfg["seed"], ucb_beta=cfg["beta"],
                  share_target_kv=share_kv)
     ot, od = oracle_models(cfg, share_kv)
     if kv_prefilled:
         fill_kv(cfg, g, ot, od, len(cfg["prompt"]) - 1, device)
     g.set_context(cfg["prompt"], kv_prefilled=kv_prefilled)
-    return g, TreeLockStep(g, ot, od, cfg["prompt"], tree, cfg["beta"], tol, kv_prefilled=kv_prefilled)
+    return g, TreeLockStep(g, ot, od, cfg["prompt"], tree, cfg["beta"], tol, kv_prefilled=kv_prefilled, temp=temp, seed=cfg["seed"])
 
 
 @pytest.mark.parametrize("kind", ["wide", "bushy", "chain5"])
@@ -157,16 +225,10 @@ def test_tree_round_with_separate_drafters_and_backlog():
     g.close()
 
 
-def test_tree_rounds_need_a_greedy_single_sequence_context_and_a_valid_tree():
+def test_tree_rounds_need_a_single_sequence_context_and_a_valid_tree():
     cfg = W.config1_tree()
     td, tw = cfg["target"]
     t = W.draft_tree("wide")
-    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=15, max_ctx=cfg["max_ctx"], temperature=1.0, seed=1)
-    g.set_context(cfg["prompt"])
-    with pytest.raises(M.MetaSDError) as e:                 # sampling: no acceptance rule for trees
-        g.draft_tree(0, t["parent"], t["rank"])
-    assert e.value.code == -1
-    g.close()
     g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=15, max_ctx=cfg["max_ctx"], temperature=0.0, seed=1)
     with pytest.raises(M.MetaSDError) as e:                 # no context yet
         g.draft_tree(0, t["parent"], t["rank"])
@@ -200,13 +262,55 @@ def test_tree_rounds_need_a_greedy_single_sequence_context_and_a_valid_tree():
     g.close()
 
 
-def test_config4_7b_shape_tree_round_full_size():
-    """7B-shape target at full size, KV context 2048 (synthetic prefix), separate two-layer drafters: two greedy tree rounds
-    (13 nodes: a 13-row verification block with the tree mask across 17 attention chunks), every logit compared."""
+@pytest.mark.parametrize("temp", [0.0, 1.0])
+def test_config4_7b_shape_tree_round_full_size(temp):
+    """7B-shape target at full size, KV context 2048 (synthetic prefix), separate two-layer drafters: two tree rounds, greedy
+    and sampled (13 nodes: a 13-row verification block with the tree mask across 17 attention chunks; vocabulary 32000: draws
+    and walk over all eight wavefront segments), every logit compared."""
     cfg = W.config4(device="cuda")
-    g, ls = make(cfg, Tree(**W.draft_tree("wide")), TOL, kv_prefilled=True, device="cuda")
+    g, ls = make(cfg, Tree(**W.draft_tree("wide")), TOL, kv_prefilled=True, device="cuda", temp=temp)
     for _ in range(2):
         ls.round()
     st = ls.stats
     assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties"] <= 1, st
+    g.close()
+
+
+@pytest.mark.parametrize("kind,temp", [("wide", 1.0), ("bushy", 0.7), ("chain5", 1.0)])
+def test_fp32_sampled_tree_rounds(kind, temp):
+    """Sampled tree rounds on the tiny fp32 configuration: every stage of every round against the oracle (children drawn
+    without replacement, the rejection-sampling walk, logits, commits, compacted caches), 64 new tokens; the whole output
+    is the oracle's own sampled-tree generation with the same seed token for token (no near-tie on the way); a
+    chain-shaped tree gives the tokens of ordinary sampled speculation (the chain loop of the library, same seed)."""
+    cfg = W.config1_tree(sigmas=(0.0, 0.05, 0.15))
+    tree = Tree(**W.draft_tree(kind))
+    g, ls = make(cfg, tree, 1e-4, temp=temp)
+    l0 = len(cfg["prompt"])
+    while ls.st.l < l0 + 64:
+        ls.round(ls.st.t % 3)                      # every arm in turn: the exact drafter accepts everything, the noisy ones branch
+    st = ls.stats
+    assert st["ties"] == 0 and max(st["n_acc"]) >= 2 and min(st["n_acc"]) < tree.max_depth and (kind == "chain5" or st["branch"] >= 1), st
+    tw_np = W.to_numpy(cfg["target"][1])
+    T2 = oracle.Model(cfg["target"][0], tw_np, cfg["max_ctx"])
+    D2 = [oracle.Model(dd, W.to_numpy(dw), cfg["max_ctx"]) for dd, dw in cfg["drafters"]]
+    ref = oracle.generate_tree(T2, D2, cfg["prompt"], 64, tree, cfg["beta"], policy=lambda r: r % 3, T=temp, seed=cfg["seed"])
+    out = g.peek("hist")[l0: l0 + 64].cpu().numpy()
+    assert np.array_equal(out, ref["tokens"])
+    g.close()
+
+
+def test_bf16_sampled_tree_rounds():
+    """Sampled tree rounds on a small bf16 target (head_dim 128: the MFMA attention kernel with the tree mask): the GPU's
+    draws and walk are the oracle's on the GPU's own logits, logits within the bf16 tolerance, arms forced so that a
+    drafter returns after sitting out."""
+    s = SMALL[2]
+    td = W.model_desc(s["n_layers"], s["d_model"], s["n_heads"], s["n_heads"], s["d_ffn"], s["vocab"], W.SWIGLU, W.BF16)
+    tw = W.gen_weights(td, 0)
+    drafters = [W.early_exit_drafter(td, tw, e, sg, 300 + k) for k, (e, sg) in enumerate(((s["n_layers"], 0.0), (s["n_layers"], 0.004), (s["n_layers"] - 1, 0.0)))]
+    cfg = dict(target=(td, tw), drafters=drafters, prompt=W.prompt_tokens(s["prompt"], s["vocab"], 3), beta=1.0, seed=1, max_ctx=s["prompt"] + 100)
+    g, ls = make(cfg, Tree(**W.draft_tree("wide")), TOL, temp=1.0)
+    for k in (None, None, None, 1, 0, 1, 2, 0):
+        ls.round(k)
+    st = ls.stats
+    assert st["ties"] <= 1 and st["rounds"] == 8, st
     g.close()
