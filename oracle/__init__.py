@@ -131,9 +131,11 @@ class Model:
     early-exit drafter.  The new model then keeps no cache of its own: it reads and writes the owner's (the
     no-recomputation strategy for drafter switches, cf. the paper's appendix on switching costs); ``shares_kv`` is set."""
 
-    def __init__(self, desc: dict, weights: list, max_ctx: int, share_kv_with: "Model | None" = None):
+    def __init__(self, desc: dict, weights: list, max_ctx: int, share_kv_with: "Model | None" = None, stream=None):
         self.desc = dict(desc)
         self.max_ctx = int(max_ctx)
+        self.stream = None if stream is None else (int(stream[0]), int(stream[1]))   # (sinks, window) of a streaming drafter cache
+        assert self.stream is None or (share_kv_with is None and self.stream[0] >= 0 and self.stream[1] >= 1)
         self.shares_kv = share_kv_with is not None
         self._owner = share_kv_with                  # keeps the owner (and its arrays) alive
         want = np.uint16 if desc["dtype"] == 1 else np.float32

@@ -11,6 +11,14 @@ the missing KV entries are recomputed when a drafter is switched in).  An early-
 shares the target's cache (``Model(..., share_kv_with=target)``) has nothing to consume: the
 target's cache already holds the K/V of its layers at every committed position but the last, so
 for it ``c[k] = l-1`` at the start of every round.
+
+Streaming drafter caches (the paper's appendix "MetaEagle-UCB with efficient KV cache strategies" replaces the
+recomputation on a drafter switch by the StreamingLLM technique and states neither sink nor window size).  Reading used
+here: a drafter with ``stream = (S, W)`` attends, at position p, to the first S positions (the attention sinks) and to the
+last W positions up to p, at their original positions; when it is switched in it therefore needs, besides the sinks, only
+the last W committed tokens, and that is all it consumes - a longer backlog is skipped, and ``a[k]`` remembers where the
+contiguous tail of its cache starts so that nothing skipped is ever attended to.  (The drafter's distribution changes;
+the output law does not: Alg. 3 is exact for any drafter.)
 """
 from __future__ import annotations
 
@@ -26,6 +34,44 @@ class SdState:
     c: list                          # per-drafter number of positions already in its KV cache
     t: int = 0                       # completed rounds (Alg. 2's t)
     log: list = field(default_factory=list)
+    a: list = None                   # streaming drafters: first position of the contiguous tail of the cache (0: no gap)
+
+
+def stream_allow(max_ctx: int, positions, S: int, W: int, a: int) -> np.ndarray:
+    """allow[r, p] = 1 iff row r (at positions[r]) attends to cache position p: a sink (p < S) or one of the last W positions
+    up to its own that belong to the contiguous tail starting at a."""
+    al = np.zeros((len(positions), max_ctx), np.uint8)
+    for r, pr in enumerate(positions):
+        al[r, : min(S, pr + 1)] = 1
+        al[r, max(a, pr - W + 1): pr + 1] = 1
+    return al
+
+
+def stream_forward(drafter, hist, lo: int, hi: int, a: int):
+    """Feed positions lo .. hi-1 to a streaming drafter (blocks of <= 16 rows); returns the last row's logits."""
+    S, W = drafter.stream
+    out = None
+    for b0 in range(lo, hi, 16):
+        pos = list(range(b0, min(b0 + 16, hi)))
+        out = drafter.forward_rows(hist[pos[0]: pos[-1] + 1], pos, pos, stream_allow(drafter.max_ctx, pos, S, W, a))
+    return None if out is None else out[-1]
+
+
+def stream_catch_up(drafter, hist, c: int, l: int, a: int):
+    """What a streaming drafter consumes when it is switched in with c positions cached and l tokens committed: the
+    sinks it has not seen, then the last W committed tokens (a longer backlog is skipped and the tail restarts there).
+    Returns (logits after the last committed token, new tail start)."""
+    S, W = drafter.stream
+    q = None
+    if c < min(S, l):
+        q = stream_forward(drafter, hist, c, min(S, l), a)
+        c = min(S, l)
+    start = max(c, l - W)
+    if start > c:
+        a = start
+    if start < l:
+        q = stream_forward(drafter, hist, start, l, a)
+    return q, a
 
 
 def sd_round(target, drafter, k: int, st: SdState, gamma: int, T: float, seed: int, seq: int = 0) -> dict:
@@ -40,9 +86,17 @@ def sd_round(target, drafter, k: int, st: SdState, gamma: int, T: float, seed: i
     # --- draft: catch-up block (ends with the last committed token), then gamma-1 single steps
     if getattr(drafter, "shares_kv", False):
         st.c[k] = l - 1
-    Q[0] = drafter.forward(st.hist[st.c[k]: l], st.c[k], "last")
+    stream = getattr(drafter, "stream", None)
+    if stream is not None:
+        if st.a is None:
+            st.a = [0] * len(st.c)
+        Q[0], st.a[k] = stream_catch_up(drafter, st.hist, st.c[k], l, st.a[k])
+    else:
+        Q[0] = drafter.forward(st.hist[st.c[k]: l], st.c[k], "last")
     for j in range(gamma):
-        if j > 0:
+        if j > 0 and stream is not None:
+            Q[j] = stream_forward(drafter, st.hist, l + j - 1, l + j, st.a[k])
+        elif j > 0:
             Q[j] = drafter.forward(st.hist[l + j - 1: l + j], l + j - 1, "last")
         u = uniform(seed, seq, st.t, j, STREAM_DRAFT)
         d[j], draft_margin[j] = sample(Q[j], T, u, with_margin=True)

@@ -114,3 +114,66 @@ def test_shared_cache_greedy_is_lossless(c1):
         T, D = shared_models(c1)
         out = oracle.generate(T, D, c1["prompt"], c1["n_new"], c1["gamma"], 0.0, c1["seed"], c1["beta"], policy=lambda t, a=arm: a)
         assert np.array_equal(out["tokens"], ref)
+
+
+# ---------------------------------------------------------------- streaming drafter caches (sinks + window)
+
+def _stream_models(cfg, stream, share=False):
+    T = oracle.Model(cfg["target"][0], W.to_numpy(cfg["target"][1]), cfg["max_ctx"])
+    D = [oracle.Model(dd, W.to_numpy(dw), cfg["max_ctx"], stream=stream) for dd, dw in cfg["drafters"]]
+    return T, D
+
+
+def test_streaming_cache_with_a_window_as_long_as_the_text_is_the_plain_cache():
+    """Sinks + window covering everything: the mask is the causal mask and nothing is skipped, so the rounds are those of
+    drafters with full caches, logit for logit."""
+    cfg = W.config1()
+    T, D = _stream_models(cfg, None)
+    a = oracle.generate(T, D, cfg["prompt"], 40, cfg["gamma"], 1.0, cfg["seed"], cfg["beta"], keep_logits=True)
+    T, D = _stream_models(cfg, (3, cfg["max_ctx"]))
+    b = oracle.generate(T, D, cfg["prompt"], 40, cfg["gamma"], 1.0, cfg["seed"], cfg["beta"], keep_logits=True)
+    assert np.array_equal(a["tokens"], b["tokens"])
+    for ra, rb in zip(a["rounds"], b["rounds"]):
+        assert np.array_equal(ra["Q"], rb["Q"]) and np.array_equal(ra["P"], rb["P"])
+
+
+def test_streaming_row_sees_sinks_and_window_only():
+    """The logits of a streaming drafter at position p are those of a fresh model that was fed only the sink tokens and
+    the window's tokens, each at its original position (compact cache slots, same rotations) - attention over the visible
+    set, computed the other way round."""
+    from oracle.loop import stream_catch_up
+    cfg = W.config1()
+    dd, dw = cfg["drafters"][1]
+    S, Wn = 2, 5
+    rng = np.random.default_rng(4)
+    toks = rng.integers(0, 512, 40).astype(np.int32)
+    A = oracle.Model(dd, W.to_numpy(dw), cfg["max_ctx"], stream=(S, Wn))
+    for l in (1, 2, 4, 9, 23, 40):                       # shorter than the sinks, inside the window, far beyond it
+        A2 = oracle.Model(dd, W.to_numpy(dw), cfg["max_ctx"], stream=(S, Wn))
+        q, a = stream_catch_up(A2, toks, 0, l, 0)
+        vis = sorted(set(range(min(S, l))) | set(range(max(0, l - Wn), l)))
+        assert a == (max(min(S, l), l - Wn) if l - Wn > min(S, l) else 0)
+        B = oracle.Model(dd, W.to_numpy(dw), cfg["max_ctx"])
+        allow = np.zeros((len(vis), B.max_ctx), np.uint8)
+        for r, p in enumerate(vis):
+            lo = max(a, p - Wn + 1) if p >= S else 0
+            for r2, p2 in enumerate(vis[: r + 1]):
+                if p2 < S or p2 >= lo:
+                    allow[r, r2] = 1
+        ref = B.forward_rows(toks[vis], np.arange(len(vis)), vis, allow)[-1]
+        assert np.array_equal(q, ref), l
+    del A
+
+
+@pytest.mark.parametrize("stream", [(2, 6), (0, 3), (4, 12)])
+def test_streaming_caches_keep_greedy_decoding_lossless(stream):
+    """Whatever the drafters' cache strategy, greedy MetaSD emits the target's own greedy continuation; arms forced so that
+    every drafter sits out longer than its window and comes back (the skipped backlog must never be attended to)."""
+    cfg = W.config1()
+    T, D = _stream_models(cfg, stream)
+    order = [0, 0, 1, 1, 1, 1, 2, 2, 2, 2, 0, 1, 2, 0, 0, 0, 1]
+    out = oracle.generate(T, D, cfg["prompt"], cfg["n_new"], cfg["gamma"], 0.0, cfg["seed"], cfg["beta"], policy=lambda r: order[r % len(order)])
+    ref = oracle.ar_decode(oracle.Model(cfg["target"][0], W.to_numpy(cfg["target"][1]), cfg["max_ctx"]), cfg["prompt"], cfg["n_new"], T=0.0)
+    assert np.array_equal(out["tokens"], ref)
+    st = out["state"]
+    assert st.a is not None and max(st.a) > 0                # some backlog was skipped
