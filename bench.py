@@ -54,6 +54,9 @@ def main():
                          "c3: the 1B-shape GQA target with four early-exit drafters, real 512-token prefill; "
                          "c2: the accept kernel alone (64 rows x gamma 5 x vocab 32000); c5, c3 and c2 are side measurements")
     ap.add_argument("--batch", type=int, default=32, help="sequences of the c5 workload")
+    ap.add_argument("--stream-cache", default=None, metavar="SINKS,WINDOW",
+                    help="c4 / c3 (with --own-kv): drafters keep a streaming cache (attention sinks + window; metasd_config.stream_*) "
+                         "- a side measurement, not the default workload")
     ap.add_argument("--own-kv", action="store_true", help="c3: give every early-exit drafter a KV cache of its own (recomputed when it is "
                                                            "switched in) instead of letting it read the target's")
     args = ap.parse_args()
@@ -81,8 +84,9 @@ def main():
     total_rounds = 3 * K_steps + Wm                              # timed pass + phase pass + per-launch pass
     cfg["max_ctx"] = args.ctx + (gamma + 1) * total_rounds + 16
     td, tw = cfg["target"]
+    stream = tuple(int(v) for v in args.stream_cache.split(",")) if args.stream_cache else None
     g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=gamma, max_ctx=cfg["max_ctx"], temperature=cfg["T"],
-                 seed=cfg["seed"], ucb_beta=cfg["beta"])
+                 seed=cfg["seed"], ucb_beta=cfg["beta"], stream=stream)
     heads = [[M.pack_weight(h.contiguous()) for h in hk] for hk in cfg["heads"]]
     head_index = 2 + 9 * cfg["drafters"][0][0]["n_layers"]
 
@@ -224,7 +228,8 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"C4: 7B-shape bf16 target ({td['n_layers']} layers, d {td['d_model']}, FFN {td['d_ffn']}, "
                                f"vocab {td['vocab']}), KV context {args.ctx}, K=5 two-layer d=768 drafters with "
-                               "segment-switching heads, gamma=5, batch 1, T=1, UCB beta=1, BE reward",
+                               "segment-switching heads, gamma=5, batch 1, T=1, UCB beta=1, BE reward" +
+                               (f"; side measurement: streaming drafter caches ({args.stream_cache} sinks,window)" if args.stream_cache else ""),
                    "gamma": gamma, "batch": 1, "ctx": args.ctx, "K": g.K},
         "roofline": roofline, "cpu_baseline": cpu, "detail": extra,
     }
@@ -344,7 +349,8 @@ def bench_c3(args):
     cfg["max_ctx"] = len(cfg["prompt"]) + (gamma + 1) * total + 16
     td, tw = cfg["target"]
     g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=gamma, max_ctx=cfg["max_ctx"], temperature=cfg["T"], seed=cfg["seed"],
-                 ucb_beta=cfg["beta"], share_target_kv=not args.own_kv)
+                 ucb_beta=cfg["beta"], share_target_kv=not args.own_kv,
+                 stream=tuple(int(v) for v in args.stream_cache.split(",")) if args.stream_cache else None)
     g.set_context(cfg["prompt"], kv_prefilled=False)
 
     def one_round():
@@ -392,6 +398,7 @@ def bench_c3(args):
            "dtype": "bf16", "data": "synthetic",
            "config": {"workload": "C3: 1B-shape bf16 target (16 layers, d 2048, 32/8 heads, FFN 8192, vocab 32000), K=4 early-exit drafters "
                                   "at layers 2/4/6/8" + (" with KV caches of their own" if args.own_kv else " reading the target's KV cache") +
+                                  (f" (streaming: {args.stream_cache} sinks,window)" if args.stream_cache else "") +
                                   ", 512-token prompt prefilled on the GPU, gamma=5, T=1", "gamma": gamma, "batch": 1, "K": g.K},
            "roofline": {"bound": "hbm", "kernel": "weight-streaming GEMMs (target and drafters)", "achieved": gbs, "peak": HBM_PEAK_GBS,
                         "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None},

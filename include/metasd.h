@@ -105,6 +105,15 @@ typedef struct {
     int32_t policy;        /* METASD_POLICY_*; 0 (UCB) for a zero-initialised tail */
     int32_t policy_window; /* SWUCB: window; SH: exploration budget in rounds; else ignored */
     double policy_param;   /* DUCB: discount; EXP3: gamma; else ignored */
+    /* Streaming drafter caches (the KV strategy of the paper's appendix "MetaEagle-UCB with efficient KV cache strategies",
+     * which names the StreamingLLM technique and gives no sizes).  stream_window == 0: off - a drafter that is switched in
+     * recomputes the K/V of every committed token it has not seen.  stream_window = W > 0 (batch == 1 only): every drafter
+     * with a cache of its own attends, at position p, to the first stream_sink positions and to the last W positions up to
+     * p, at their original positions; when it is switched in it consumes the sinks it has not seen and the last W
+     * committed tokens only - a longer backlog is skipped and never attended to.  The drafter's distribution changes, the
+     * output law does not (Alg. 3 is exact for any drafter). */
+    int32_t stream_sink;
+    int32_t stream_window;
 } metasd_config;
 
 /* ---- sizes -------------------------------------------------------------------------------- */

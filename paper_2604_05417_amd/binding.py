@@ -32,7 +32,8 @@ class _Desc(C.Structure):
 class _Config(C.Structure):
     _fields_ = [("K", C.c_int32), ("gamma_max", C.c_int32), ("batch", C.c_int32), ("max_ctx", C.c_int32),
                 ("temperature", C.c_float), ("reward", C.c_int32), ("ucb_beta", C.c_double), ("seed", C.c_uint64),
-                ("policy", C.c_int32), ("policy_window", C.c_int32), ("policy_param", C.c_double)]
+                ("policy", C.c_int32), ("policy_window", C.c_int32), ("policy_param", C.c_double),
+                ("stream_sink", C.c_int32), ("stream_window", C.c_int32)]
 
 
 class _Tree(C.Structure):
@@ -136,7 +137,9 @@ class MetaSD:
 
     def __init__(self, target, drafters, gamma_max: int, max_ctx: int, temperature: float, seed: int,
                  ucb_beta: float = 1.0, reward: str = "BE", device: str = "cuda:0", policy: str = "ucb",
-                 policy_param: float = 0.0, policy_window: int = 0, batch: int = 1, share_target_kv: bool = False):
+                 policy_param: float = 0.0, policy_window: int = 0, batch: int = 1, share_target_kv: bool = False,
+                 stream=None):
+        """stream = (sinks, window): drafters with caches of their own keep a streaming cache (metasd_config.stream_*)."""
         _require_gpu()
         self.L = load_library()
         self.device = torch.device(device)
@@ -150,7 +153,8 @@ class MetaSD:
         self.tdesc = dict(tdesc)
         self.ddescs = [dict(d) for d, _ in drafters]
         self.cfg = _Config(self.K, gamma_max, batch, max_ctx, temperature, 1 if reward == "BD" else 0, ucb_beta, seed,
-                           POLICIES[policy], policy_window, policy_param)
+                           POLICIES[policy], policy_window, policy_param, 0 if stream is None else int(stream[0]),
+                           0 if stream is None else int(stream[1]))
         self._tdesc_c = _desc(tdesc)
         self._ddesc_c = (_Desc * self.K)(*[_desc(d) for d in self.ddescs])
         self._tw = self._table(tdesc, tw)

@@ -1010,15 +1010,27 @@ __global__ void pack_weight_kernel(const uint4* __restrict__ src, uint4* __restr
 // and position `base`), node i > 0 hangs under a node with a lower index.  Node i lives in cache slot base + i, is rotated
 // for position base + depth(i), and attends to every committed position (< base) and to its ancestors and itself.
 // Block row r is node i0 + r.  on == 0: an ordinary causal block (row r at slot = position pos0 + r).
+// on == 2: not a tree but the streaming cache of a drafter (the StreamingLLM strategy of the paper's appendix on KV cache
+// strategies): an ordinary block whose row at position p attends to the first `sink` positions and to the last `i0`
+// positions up to p that are not below `base`, the start of the contiguous tail of the cache (what lies between the
+// sinks and the tail was skipped when the drafter was switched in and holds nothing).
 constexpr int TREE_MAX = 16;
 struct TreeBlk {
-    int on, base, i0;
+    int on, base, i0, sink;
     uint16_t anc[TREE_MAX];    // bit j: node j is this node or one of its ancestors
     uint8_t depth[TREE_MAX];
 };
-__device__ __forceinline__ bool tree_allowed(const TreeBlk& tb, int p, int row) {
+__device__ __forceinline__ bool tree_allowed(const TreeBlk& tb, int p, int row, int pos0) {
+    if (tb.on == 2) {
+        const int pr = pos0 + row;
+        return p <= pr && (p < tb.sink || p >= max(tb.base, pr - tb.i0 + 1));
+    }
     const int j = p - tb.base;
     return j < 0 || (j < TREE_MAX && ((tb.anc[tb.i0 + row] >> j) & 1));
+}
+// streaming cache: no row of the block (positions pos0 ..) attends to anything in positions [p0, p0 + n)
+__device__ __forceinline__ bool stream_skips(const TreeBlk& tb, int p0, int n, int pos0) {
+    return tb.on == 2 && p0 >= tb.sink && p0 + n <= max(tb.base, pos0 - tb.i0 + 1);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1097,7 +1109,7 @@ __global__ void embed_rope_kernel(const int32_t* __restrict__ tok, const T* __re
     for (int k = i; k < d; k += blockDim.x) h[(size_t)r * d + k] = El<T>::ld(E[t * d + k]);
     if (i < half) {
         const double freq = pow((double)theta, -2.0 * (double)i / (double)hd);
-        const int pos = tb.on ? tb.base + (int)tb.depth[tb.i0 + r] : pos0 + r;     // a tree node is rotated for its depth, not its slot
+        const int pos = tb.on == 1 ? tb.base + (int)tb.depth[tb.i0 + r] : pos0 + r;     // a tree node is rotated for its depth, not its slot
         double sn, cs;
         sincos((double)pos * freq, &sn, &cs);
         tab[r * half + i] = make_double2(cs, sn);
@@ -1180,7 +1192,7 @@ __device__ __forceinline__ void attn_partial_body(const float* __restrict__ q, c
             for (int j = 0; j < 8; ++j) {
                 const int r = rbeg + j;
                 if (r < m) {
-                    const bool see = tb ? tree_allowed(*tb, p0 + p, r) : (p0 + p <= pos0 + r);
+                    const bool see = tb ? tree_allowed(*tb, p0 + p, r, pos0) : (p0 + p <= pos0 + r);
                     ss[r * ATT_CH + p] = (p < np && see) ? acc[j] * scale : -INFINITY;
                 }
             }
@@ -1342,6 +1354,12 @@ __device__ __forceinline__ void attn_partial_mfma_body(const float* __restrict__
         const int p0 = (c + ci) * ATT_CH;
         if (MULTI && p0 >= L) break;               // workgroup-uniform
         const int np = min(ATT_CH, L - p0);
+        if (!MULTI && tb && stream_skips(*tb, p0, ATT_CH, pos0)) {
+            // a streaming cache holds nothing any row attends to in this chunk: an empty record (weight zero in the merge)
+            float* dst = part + ((size_t)h * nchunks + c) * 16 * (HD + 2);
+            for (int i = tid; i < m * (HD + 2); i += 256) dst[i] = (i % (HD + 2)) == HD ? -INFINITY : 0.f;
+            return;
+        }
         // the block's own rows that fall into this chunk: rows r_lo .. r_lo + nnew - 1
         const int r_lo = max(0, p0 - pos0), nnew = QKV ? max(0, min(m, p0 + ATT_CH - pos0) - r_lo) : 0;
         // ---- fresh q / k / v: the pieces of this thread (piece number tid + 256 j), two per trip.  Requests are unconditional
@@ -1502,7 +1520,7 @@ __device__ __forceinline__ void attn_partial_mfma_body(const float* __restrict__
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int pl = wave * 32 + t * 16 + g * 4 + v;
-                const bool see = tb ? tree_allowed(*tb, p0 + pl, rowok ? row : 0) : (p0 + pl) <= pos0 + row;
+                const bool see = tb ? tree_allowed(*tb, p0 + pl, rowok ? row : 0, pos0) : (p0 + pl) <= pos0 + row;
                 const bool ok = rowok && pl < np && see;
                 const float x = ok ? sacc[t][v] * scale : -INFINITY;
                 sv[t * 4 + v] = x;

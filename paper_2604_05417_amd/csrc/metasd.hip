@@ -59,6 +59,8 @@ struct Model {
     int kv_layers = 0;       // layers of the cache buffer behind kv (the target's count for a shared cache): sequence stride
     int hd = 0;
     std::vector<int> kvl;   // positions valid in the KV cache, per sequence
+    bool stream = false;    // a drafter with a streaming cache (cfg.stream_sink, cfg.stream_window): see forward()
+    int tail = 0;           // streaming cache: first position of the contiguous tail (what lies between the sinks and it was skipped)
     const void** d_table = nullptr;   // device copy of w
     const void* layer_w(int L, int i) const { return w[1 + PER_LAYER * L + i]; }
     const void* final_norm() const { return w[1 + PER_LAYER * d.n_layers]; }
@@ -894,7 +896,21 @@ int upload_table(metasd_ctx* c, Model& M) {
 // earlier ones).  logits (optional): want_all ? all n rows (n <= 16) : the last row only.
 int model_index(const metasd_ctx* c, const Model& M) { return &M == &c->target ? -1 : (int)(&M - c->drafters.data()); }
 
+int forward_blocks(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool want_all);
+
+// A drafter with a streaming cache attends to the sinks and to the last stream_window positions of its cache's tail: the
+// block mask of the attention kernels (TreeBlk, on == 2) carries that for the duration of its forward passes.
 int forward(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool want_all) {
+    if (!M.stream || c->tree) return forward_blocks(c, M, pos0, n, logits, want_all);
+    TreeBlk wb{};
+    wb.on = 2; wb.base = M.tail; wb.i0 = c->cfg.stream_window; wb.sink = c->cfg.stream_sink;
+    c->tree = &wb;
+    const int rc = forward_blocks(c, M, pos0, n, logits, want_all);
+    c->tree = nullptr;
+    return rc;
+}
+
+int forward_blocks(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool want_all) {
     c->cur_model = model_index(c, M);
     if (pos0 + n > c->cfg.max_ctx) return c->fail(METASD_E_OVERFLOW, "positions %d..%d exceed max_ctx %d", pos0, pos0 + n, c->cfg.max_ctx);
     int done = 0;
@@ -1534,6 +1550,8 @@ static int check_config(const metasd_config* cfg, const metasd_model_desc* targe
             break;
         default: return fail_global(METASD_E_INVALID, "unknown policy %d", cfg->policy);
     }
+    if (cfg->stream_window < 0 || cfg->stream_sink < 0) return fail_global(METASD_E_INVALID, "stream_sink and stream_window must be >= 0");
+    if (cfg->stream_window > 0 && cfg->batch > 1) return fail_global(METASD_E_INVALID, "streaming drafter caches: contexts with one sequence only");
     char buf[256];
     if (const char* e = check_model(*target, "target", buf, sizeof buf)) return fail_global(METASD_E_INVALID, "%s", e);
     for (int k = 0; k < cfg->K; ++k) {
@@ -1618,6 +1636,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
                 D.shared_kv = true;
                 D.kv_layers = b.n_layers;
             }
+            if (!rc) c->drafters[k].stream = cfg->stream_window > 0 && !c->drafters[k].shared_kv;
         }
     }
     if (rc) { delete c; return rc; }
@@ -1707,7 +1726,7 @@ int32_t metasd_set_context(metasd_ctx* c, int32_t seq, const int32_t* tokens, in
     for (const auto& q : c->sq) all = all && q.ready;
     c->phase = all ? PH_READY : PH_NONE;
     c->target.kvl[seq] = kv_prefilled ? n - 1 : 0;
-    for (auto& d : c->drafters) d.kvl[seq] = (kv_prefilled || d.shared_kv) ? n - 1 : 0;
+    for (auto& d : c->drafters) { d.kvl[seq] = (kv_prefilled || d.shared_kv) ? n - 1 : 0; d.tail = 0; }
     if (!kv_prefilled && n > 1) {
         if (c->cfg.batch == 1) { if (int rc = forward(c, c->target, 0, n - 1, nullptr, false)) return rc; }
         else if (int rc = catch_up(c, c->target, std::vector<int>{seq}, std::vector<int>{n - 1}, nullptr, 0, 0)) return rc;
@@ -1778,7 +1797,16 @@ int32_t metasd_draft(metasd_ctx* c, const int32_t* k, int32_t gamma) {
     for (int j = 0; j < gamma; ++j) {
         float* Qj = c->d_Q() + (size_t)j * V;
         int rc;
-        if (j == 0) rc = forward(c, D, D.kvl[0], l - D.kvl[0], Qj, false);   // catch-up, ends with the last committed token
+        if (j == 0 && D.stream) {
+            // switched in: the sinks it has not seen, then the last stream_window committed tokens; a longer backlog is skipped
+            const int S = std::min(c->cfg.stream_sink, l);
+            int have = D.kvl[0];
+            rc = 0;
+            if (have < S) { rc = forward(c, D, have, S - have, S == l ? Qj : nullptr, false); have = S; }
+            const int start = std::max(have, l - c->cfg.stream_window);
+            if (start > have) D.tail = start;
+            if (!rc && start < l) rc = forward(c, D, start, l - start, Qj, false);
+        } else if (j == 0) rc = forward(c, D, D.kvl[0], l - D.kvl[0], Qj, false);   // catch-up, ends with the last committed token
         else rc = forward(c, D, l + j - 1, 1, Qj, false);
         if (rc) return rc;
         if (launch_sample(c->stream, Qj, 1, V, T, c->cfg.seed, (uint32_t)c->sq[0].round, (uint32_t)j, 0u, c->d_hist() + l + j, 1,
@@ -1862,6 +1890,7 @@ int32_t metasd_draft_tree(metasd_ctx* c, int32_t k, const metasd_tree* tree) {
     if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
     if (c->cfg.batch != 1) return c->fail(METASD_E_INVALID, "draft_tree: contexts with one sequence only");
     if (k < 0 || k >= c->cfg.K || !tree) return c->fail(METASD_E_INVALID, "draft_tree: bad drafter index or NULL tree");
+    if (c->drafters[k].stream) return c->fail(METASD_E_INVALID, "draft_tree: drafters with a streaming cache draft chains only");
     if (c->phase != PH_READY) return c->fail(METASD_E_ORDER, "draft_tree: call set_context first / finish the previous round");
     const int n = tree->n;
     if (n < 2 || n > TREE_MAX || n > c->cfg.gamma_max + 1) return c->fail(METASD_E_INVALID, "draft_tree: tree of %d nodes; 2 .. min(%d, gamma_max + 1) supported", n, TREE_MAX);

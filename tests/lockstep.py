@@ -36,6 +36,7 @@ class LockStep:
         self.l = len(prompt)
         self.hist[: self.l] = prompt
         self.c = [self.l - 1 if kv_prefilled else 0] * len(drafters)
+        self.a = [0] * len(drafters)                     # streaming drafter caches: start of the contiguous tail
         self.t = 0
         self.bandit = oracle.Ucb(len(drafters), beta)
         self.stats = dict(rounds=0, max_dq=0.0, max_dp=0.0, ties_shared=0, ties_own=0, mismatch_own=0, n_acc=[], arms=[],
@@ -74,7 +75,12 @@ class LockStep:
         if getattr(D, "shares_kv", False):               # reads the target's cache: never a backlog
             self.c[k] = l - 1
         Qo = np.empty((gamma, V), np.float32)
-        Qo[0] = D.forward(self.hist[self.c[k]: l], self.c[k], "last")
+        stream = getattr(D, "stream", None)
+        if stream is not None:                           # sinks not seen yet + the last `window` committed tokens
+            from oracle.loop import stream_catch_up, stream_forward
+            Qo[0], self.a[k] = stream_catch_up(D, self.hist, self.c[k], l, self.a[k])
+        else:
+            Qo[0] = D.forward(self.hist[self.c[k]: l], self.c[k], "last")
         u_d = [oracle.uniform(seed, sq, t, j, oracle.STREAM_DRAFT) for j in range(gamma)]
         for j in range(gamma):       # stage B for the draft: the oracle's draw on the GPU's own logits
             tj, mg = oracle.sample(Qg[j], T, u_d[j], with_margin=True)
@@ -85,7 +91,10 @@ class LockStep:
         for j in range(gamma):
             if j > 0:
                 self.hist[l + j - 1] = d[j - 1]
-                Qo[j] = D.forward(self.hist[l + j - 1: l + j], l + j - 1, "last")
+                if stream is not None:
+                    Qo[j] = stream_forward(D, self.hist, l + j - 1, l + j, self.a[k])
+                else:
+                    Qo[j] = D.forward(self.hist[l + j - 1: l + j], l + j - 1, "last")
             tj, mg = oracle.sample(Qo[j], T, u_d[j], with_margin=True)
             if tj != d[j]:
                 tie = (mg < CDF_TIE) if T > 0 else top2_gap(Qo[j]) < 2 * self.tol

@@ -14,8 +14,9 @@ pytestmark = pytest.mark.gpu
 TOL = 3e-2
 
 
-def oracle_models(cfg, share_kv=False):
-    """share_kv: early-exit drafters (their layer tensors are the target's) read the target's cache on the oracle side too."""
+def oracle_models(cfg, share_kv=False, stream=None):
+    """share_kv: early-exit drafters (their layer tensors are the target's) read the target's cache on the oracle side too.
+    stream = (sinks, window): drafters with caches of their own keep a streaming cache."""
     td, tw = cfg["target"]
     tw_np = W.to_numpy(tw)
     cache = {id(t): a for t, a in zip(tw, tw_np) if t is not None}
@@ -24,7 +25,8 @@ def oracle_models(cfg, share_kv=False):
     for dd, dw in cfg["drafters"]:
         arrs = [None if t is None else (cache[id(t)] if id(t) in cache else W.to_numpy([t])[0]) for t in dw]
         early_exit = all(a is b for a, b in zip(dw[: 1 + 9 * dd["n_layers"]], tw))
-        od.append(oracle.Model(dd, arrs, cfg["max_ctx"], share_kv_with=ot if (share_kv and early_exit) else None))
+        shared = share_kv and early_exit
+        od.append(oracle.Model(dd, arrs, cfg["max_ctx"], share_kv_with=ot if shared else None, stream=None if shared else stream))
     return ot, od
 
 
@@ -40,11 +42,11 @@ def fill_kv(cfg, g, ot, od, ctx, device):
         om.kv(1)[:, :, :ctx] = v.float().cpu().numpy()
 
 
-def run_lockstep(cfg, T, rounds, kv_prefilled, device="cpu", swap_heads=False, share_kv=False, force_arms=None):
+def run_lockstep(cfg, T, rounds, kv_prefilled, device="cpu", swap_heads=False, share_kv=False, force_arms=None, stream=None):
     td, tw = cfg["target"]
     g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=cfg["gamma"], max_ctx=cfg["max_ctx"], temperature=T, seed=cfg["seed"],
-                 ucb_beta=cfg["beta"], share_target_kv=share_kv)
-    ot, od = oracle_models(cfg, share_kv)
+                 ucb_beta=cfg["beta"], share_target_kv=share_kv, stream=stream)
+    ot, od = oracle_models(cfg, share_kv, stream)
     if kv_prefilled:
         fill_kv(cfg, g, ot, od, len(cfg["prompt"]) - 1, device)
     g.set_context(cfg["prompt"], kv_prefilled=kv_prefilled)
@@ -314,3 +316,41 @@ def test_wide_shallow_target_residual_projections(gamma, roll, monkeypatch):
     cfg["max_ctx"] = 70 + 64
     st = run_lockstep(cfg, 1.0, rounds=3, kv_prefilled=False)
     assert st["max_dp"] <= TOL and st["max_dq"] <= TOL and st["ties_shared"] <= 1, st
+
+
+# ---------------------------------------------------------------- streaming drafter caches (sinks + window)
+
+@pytest.mark.parametrize("i,stream,prompt", [(0, (4, 16), None), (1, (0, 40), None), (2, (3, 100), None), (2, (130, 20), None), (2, (3, 50), 420), (0, (1, 30), 300)])
+@pytest.mark.parametrize("T", [0.0, 1.0])
+def test_small_bf16_streaming_drafter_caches(i, stream, prompt, T):
+    """Drafters that attend to their first `sinks` positions and the last `window` positions only, and consume no more than
+    that when they are switched in (real prefill: the first switch-in skips most of the prompt; arms forced so that each
+    drafter sits out longer than its window and returns).  head_dim 64 / 32 / 128: the MFMA attention kernels with empty
+    chunks skipped and the plain kernel; sinks inside the first chunk and reaching into the second; with the longer prompts
+    one or two whole chunks lie between the sinks and the window.  Every drafter logit is
+    compared with the oracle's, which masks the same way; the rest of the round as in the other lock-step tests."""
+    s = dict(SMALL[i])
+    if prompt:
+        s["prompt"] = prompt
+    cfg = W.config4(n_layers=s["n_layers"], ctx=s["prompt"], n_new=64, K=2, d_model=s["d_model"], n_heads=s["n_heads"],
+                    d_ffn=s["d_ffn"], vocab=s["vocab"], dd_model=s["dd_model"], dn_heads=s["dn_heads"], dd_ffn=s["dd_ffn"])
+    cfg["gamma"] = s["gamma"]
+    cfg["max_ctx"] = s["prompt"] + 120
+    st = run_lockstep(cfg, T, rounds=12, kv_prefilled=False, stream=stream, force_arms=[0, 0, 1, 1, 1, 1, 1, 1, 0, 0, 1, 0])
+    assert st["max_dp"] <= TOL and st["max_dq"] <= TOL, st
+    assert st["ties_shared"] <= 1, st
+
+
+def test_streaming_caches_are_refused_for_batches_and_trees():
+    cfg = W.config1_tree()
+    td, tw = cfg["target"]
+    with pytest.raises(M.MetaSDError) as e:
+        M.MetaSD((td, tw), cfg["drafters"], gamma_max=4, max_ctx=cfg["max_ctx"], temperature=0.0, seed=1, batch=2, stream=(2, 8))
+    assert e.value.code == -1
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=15, max_ctx=cfg["max_ctx"], temperature=0.0, seed=1, stream=(2, 8))
+    g.set_context(cfg["prompt"])
+    t = W.draft_tree("wide")
+    with pytest.raises(M.MetaSDError) as e:
+        g.draft_tree(0, t["parent"], t["rank"])
+    assert e.value.code == -1
+    g.close()

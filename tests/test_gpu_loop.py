@@ -12,11 +12,11 @@ from lockstep import LockStep
 pytestmark = pytest.mark.gpu
 
 
-def build_pair(cfg, T, reward="BE", gamma=None, device="cuda"):
+def build_pair(cfg, T, reward="BE", gamma=None, device="cuda", stream=None):
     td, tw = cfg["target"]
     gamma = gamma or cfg["gamma"]
     g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=gamma, max_ctx=cfg["max_ctx"], temperature=T, seed=cfg["seed"],
-                 ucb_beta=cfg["beta"], reward=reward)
+                 ucb_beta=cfg["beta"], reward=reward, stream=stream)
     tw_np = W.to_numpy(tw)
     cache = {id(t): a for t, a in zip(tw, tw_np) if t is not None}
     ot = oracle.Model(td, tw_np, cfg["max_ctx"])
@@ -24,7 +24,7 @@ def build_pair(cfg, T, reward="BE", gamma=None, device="cuda"):
     for dd, dw in cfg["drafters"]:
         arrs = [None if t is None else cache.get(id(t)) for t in dw]
         arrs = [a if (a is not None or t is None) else W.to_numpy([t])[0] for a, t in zip(arrs, dw)]
-        od.append(oracle.Model(dd, arrs, cfg["max_ctx"]))
+        od.append(oracle.Model(dd, arrs, cfg["max_ctx"], stream=stream))
     return g, ot, od
 
 
@@ -112,4 +112,28 @@ def test_smallest_sizes_one_drafter_one_draft_one_prompt_token(T):
     st = ls.stats
     assert st["mismatch_own"] == 0 and st["ties_own"] + st["ties_shared"] <= 1 and st["max_dp"] <= 1e-4 and st["max_dq"] <= 1e-4, st
     assert set(st["arms"]) == {0}
+    g.close()
+
+
+@pytest.mark.parametrize("T", [0.0, 1.0])
+@pytest.mark.parametrize("stream", [(2, 6), (0, 3)])
+def test_config1_streaming_drafter_caches(T, stream):
+    """The tiny fp32 loop with streaming drafter caches (the plain attention kernel with the sink + window mask): 64 new
+    tokens in lock-step, arms forced so that drafters sit out longer than their window; greedy: the target's own greedy
+    continuation."""
+    cfg = W.config1()
+    g, ot, od = build_pair(cfg, T, stream=stream)
+    g.set_context(cfg["prompt"])
+    ls = LockStep(g, ot, od, cfg["prompt"], cfg["gamma"], T, cfg["seed"], cfg["beta"], logit_tol=1e-4)
+    B = len(cfg["prompt"]) + cfg["n_new"]
+    order = [0, 0, 1, 1, 1, 1, 2, 2, 2, 2, 0, 1, 2, 0, 0, 0, 1]
+    while ls.l < B:
+        ls.round(order[ls.t % len(order)])
+    st = ls.stats
+    assert st["mismatch_own"] == 0 and st["ties_own"] + st["ties_shared"] <= 1, st
+    assert st["max_dp"] <= 1e-4 and st["max_dq"] <= 1e-4 and max(ls.a) > 0
+    if T == 0.0:
+        ref = oracle.ar_decode(oracle.Model(cfg["target"][0], W.to_numpy(cfg["target"][1]), cfg["max_ctx"]),
+                               cfg["prompt"], cfg["n_new"], T=0.0)
+        assert np.array_equal(ls.hist[len(cfg["prompt"]): B], ref)
     g.close()
