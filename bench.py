@@ -49,10 +49,13 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="target layers (32 = the 7B shape; fewer is NOT the benchmark)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rounds", type=int, default=8)
-    ap.add_argument("--workload", default="c4", choices=["c4", "c5", "c3", "c2"],
+    ap.add_argument("--workload", default="c4", choices=["c4", "c5", "c3", "c2", "c4tree"],
                     help="c4 (default): the headline benchmark; c5: the batched configuration (32 sequences, gamma 7, KV context 4096); "
                          "c3: the 1B-shape GQA target with four early-exit drafters, real 512-token prefill; "
-                         "c2: the accept kernel alone (64 rows x gamma 5 x vocab 32000); c5, c3 and c2 are side measurements")
+                         "c2: the accept kernel alone (64 rows x gamma 5 x vocab 32000); c4tree: the C4 models with multi-candidate "
+                         "(tree) rounds next to chain rounds of the same depth; all but c4 are side measurements")
+    ap.add_argument("--tree", default="wide", choices=["wide", "bushy"], help="c4tree: the draft tree (workloads.draft_tree)")
+    ap.add_argument("--temperature", type=float, default=1.0, help="c4tree: 0 = greedy trees, otherwise sampled trees")
     ap.add_argument("--batch", type=int, default=32, help="sequences of the c5 workload")
     ap.add_argument("--stream-cache", default=None, metavar="SINKS,WINDOW",
                     help="c4 / c3 (with --own-kv): drafters keep a streaming cache (attention sinks + window; metasd_config.stream_*) "
@@ -68,6 +71,8 @@ def main():
         return bench_c2(args)
     if args.workload == "c3":
         return bench_c3(args)
+    if args.workload == "c4tree":
+        return bench_c4_tree(args)
 
     import numpy as np
     import torch
@@ -410,6 +415,98 @@ def bench_c3(args):
                       "arm_counts": [int(x) for x in np.bincount(arms, minlength=g.K)]}}
     g.close()
     print(json.dumps(out), flush=True)
+
+
+def bench_c4_tree(args):
+    """Side measurement: the C4 models (7B-shape target, five two-layer drafters, KV context 2048, heads switching per segment)
+    with multi-candidate rounds over a token tree, next to chain rounds of the tree's depth in the same context."""
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU available; the MetaSD library has no CPU path")
+    import paper_2604_05417_amd as M
+    import workloads as W
+    dev = "cuda:0"
+    K_steps, Wm = args.steps, max(args.warmup, 5)
+    tree = W.draft_tree(args.tree)
+    n = len(tree["parent"])
+    depth = [0] * n
+    for i in range(1, n):
+        depth[i] = depth[tree["parent"][i]] + 1
+    D = max(depth)
+    cfg = W.config4(device=dev, n_layers=args.layers, ctx=args.ctx)
+    cfg["max_ctx"] = args.ctx + (D + 1) * 2 * (K_steps + Wm + 8) + n + 16
+    td, tw = cfg["target"]
+    g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=15, max_ctx=cfg["max_ctx"], temperature=args.temperature, seed=cfg["seed"],
+                 ucb_beta=cfg["beta"])
+    heads = [[M.pack_weight(h.contiguous()) for h in hk] for hk in cfg["heads"]]
+    head_index = 2 + 9 * cfg["drafters"][0][0]["n_layers"]
+    models = [(td, g.kv_target)] + [(dd, g.kv_drafters[k]) for k, (dd, _) in enumerate(cfg["drafters"])]
+    for i, (desc, kv) in enumerate(models):
+        k, v = W.kv_fill(desc, args.ctx - 1, cfg["kv_seed"] + i, device=dev)
+        kv[:, 0, :, : args.ctx - 1] = k
+        kv[:, 1, :, : args.ctx - 1] = v
+    g.set_context(cfg["prompt"], kv_prefilled=True)
+    state = dict(seg=0, new_tokens=0)
+
+    def one_round(use_tree):
+        seg = (state["new_tokens"] // cfg["seg_len"]) % 4
+        if seg != state["seg"]:
+            for k in range(g.K):
+                g.swap_weight(k, head_index, heads[k][seg])
+            state["seg"] = seg
+        k = g.bandit_select()
+        if use_tree:
+            g.draft_tree(k, tree["parent"], tree["rank"])
+            g.verify_tree()
+            na, tok, path = g.accept_tree()
+        else:
+            g.draft(k, D)
+            g.verify(D)
+            na, tok, mask, bd = g.accept(D)
+        g.bandit_update(k, na, D)
+        state["new_tokens"] += na + 1
+        return na
+
+    res = {}
+    for name, use_tree in (("chain", False), ("tree", True)):
+        for _ in range(Wm):
+            one_round(use_tree)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        accs = [one_round(use_tree) for _ in range(K_steps)]
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t1
+        res[name] = {"tokens_per_s": (sum(accs) + len(accs)) / dt, "ms_per_round": dt / K_steps * 1e3, "mean_n_acc": float(np.mean(accs))}
+        # phases of a few more rounds (events between the calls)
+        ph = []
+        for _ in range(8):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            k = g.bandit_select()
+            ev[0].record()
+            if use_tree:
+                g.draft_tree(k, tree["parent"], tree["rank"]); ev[1].record()
+                g.verify_tree(); ev[2].record()
+                na, tok, path = g.accept_tree()
+            else:
+                g.draft(k, D); ev[1].record()
+                g.verify(D); ev[2].record()
+                na, tok, mask, bd = g.accept(D)
+            ev[3].record()
+            g.bandit_update(k, na, D)
+            torch.cuda.synchronize()
+            ph.append([ev[j].elapsed_time(ev[j + 1]) for j in range(3)])
+        med = np.median(np.array(ph), axis=0)
+        res[name].update(draft_ms=float(med[0]), verify_ms=float(med[1]), accept_ms=float(med[2]))
+    out = {"metric": "verified tokens/sec @1 GPU (7B-shape, tree rounds)", "value": res["tree"]["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
+           "steps": K_steps, "warmup": Wm, "ms_per_step": res["tree"]["ms_per_round"], "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"C4 models, KV context {args.ctx}, batch 1, T={args.temperature}: rounds over the '{args.tree}' draft tree "
+                                  f"({n} nodes, depth {D}) against chain rounds with gamma = {D}", "tree": args.tree, "nodes": n, "depth": D},
+           "roofline": None, "cpu_baseline": None, "detail": res}
+    print(json.dumps(out))
+    g.close()
+    return 0
 
 
 def bench_c2(args):

@@ -251,7 +251,8 @@ int32_t metasd_draft_tree(metasd_ctx*, int32_t k, const metasd_tree* tree);
 int32_t metasd_verify_tree(metasd_ctx*);
 /* Acceptance.  T = 0: from the root, step to the child that carries the target's most likely token, as long as there is
  * one; N_acc = steps taken, emitted token = the target's most likely token at the last node reached.  T > 0: the walk
- * described above (one workgroup holds p and q of the current node in registers).  The K/V of the
+ * described above (what happens at a node does not depend on how the walk got there: one workgroup per node decides
+ * it, a last small kernel follows the decisions from the root).  The K/V of the
  * accepted nodes are moved from their tree slots to their positions (target and drafter caches), history, KV lengths
  * and round counter are committed.  path_out (host, may be NULL): the accepted nodes, N_acc entries.  The BE reward of
  * the round is N_acc / (depth of the tree): pass that depth as `gamma` to metasd_bandit_update.

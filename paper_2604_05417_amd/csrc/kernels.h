@@ -866,8 +866,12 @@ __global__ __launch_bounds__(512) void gemm_fullk_residual_kernel(const bf16_t* 
 // buffer.  Wavefront-private, so no workgroup barrier inside the stream; LDS reduction over the eight
 // wavefronts and the residual epilogue as in gemm_fullk_residual_kernel.  No sibling workgroups.
 //   XB = ceil(m / 2): 16-byte pieces per lane, term and group.
-//   grid (ntiles), block 512, dynamic LDS 8 * 2 * 2 * m * 33 * 16 + 8 * 64 * 16 bytes.
-template <int XB>
+//   DBUF = false (9 .. 16 rows, where two buffers per wavefront no longer fit): one buffer - the next group's activations
+//   wait in registers while the current group is multiplied and are written when its LDS reads have been issued (a
+//   wavefront's LDS operations are served in order); a group is 8 KiB of weights per wavefront, so that costs nothing
+//   the stream would notice.
+//   grid (ntiles), block 512, dynamic LDS 8 * (DBUF ? 2 : 1) * 2 * m * 33 * 16 + 8 * 64 * 16 bytes.
+template <int XB, bool DBUF = true>
 __global__ __launch_bounds__(512) void gemm_fullk_roll_residual_kernel(const bf16_t* __restrict__ xh, size_t x_lo_off, int ldx, int m, int K,
                                                                        const bf16_t* __restrict__ W, int ntiles, int N,
                                                                        float* __restrict__ h, const bf16_t* __restrict__ gain,
@@ -879,8 +883,9 @@ __global__ __launch_bounds__(512) void gemm_fullk_roll_residual_kernel(const bf1
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int t = blockIdx.x;
     const int c0 = min(wave * cpw, kchunks - 1), nc = max(0, min(cpw, kchunks - wave * cpw));
-    uint4* xbuf = lds + (size_t)wave * 4 * m * RS;                         // [2 buffers][2 (hi, lo)][m][RS]
-    f32x4* red = reinterpret_cast<f32x4*>(lds + (size_t)8 * 4 * m * RS);   // [8][64]
+    constexpr int NB = DBUF ? 2 : 1, B1 = DBUF ? 1 : 0;                    // buffers per wavefront; the "other" buffer
+    uint4* xbuf = lds + (size_t)wave * NB * 2 * m * RS;                    // [NB buffers][2 (hi, lo)][m][RS]
+    f32x4* red = reinterpret_cast<f32x4*>(lds + (size_t)8 * NB * 2 * m * RS);   // [8][64]
     const u32x4* wp = reinterpret_cast<const u32x4*>(W) + ((size_t)t * kchunks + c0) * 64 + lane;
     const int ngroups = (nc + GEMM_U - 1) / GEMM_U;
     const int last = max(nc, 1) - 1;
@@ -941,18 +946,18 @@ __global__ __launch_bounds__(512) void gemm_fullk_roll_residual_kernel(const bf1
             sload(xa, xb, gi + 1);
             issue(wb, gi + 1);
             multiply(wa, 0, gi);
-            sstore(xa, xb, 1);
+            sstore(xa, xb, B1);
             sload(xa, xb, gi + 2);
             issue(wa, gi + 2);
-            multiply(wb, 1, gi + 1);
+            multiply(wb, B1, gi + 1);
             sstore(xa, xb, 0);
         }
         if (gi + 2 == ngroups) {
             sload(xa, xb, gi + 1);
             issue(wb, gi + 1);
             multiply(wa, 0, gi);
-            sstore(xa, xb, 1);
-            multiply(wb, 1, gi + 1);
+            sstore(xa, xb, B1);
+            multiply(wb, B1, gi + 1);
         } else {
             multiply(wa, 0, gi);
         }
@@ -2687,89 +2692,98 @@ __device__ __forceinline__ void ak_normalised(const float* __restrict__ row, int
     ak_scale(x, ak_totals(x, sm, 0, wave, lane));
 }
 
-// The walk.  P[i], Q[i]: target / drafter logits at node i (Q only for nodes with children); tok[i]: the node's token.
-// One workgroup holds the two distributions of the current node in registers as probabilities and updates them in
-// place after every rejection.  res and hist as accept_tree_kernel.     grid (1), block 512
+// The walk, node by node in parallel.  What happens at a node - which child is accepted, or which token is emitted when none
+// is - depends on that node's two distributions, its children's tokens and their uniforms only, not on how the walk got
+// there; so one workgroup per node decides it (P[i], Q[i]: target / drafter logits at node i, Q only for nodes with
+// children; tok[i]: the node's token; the two distributions are held in registers as probabilities and updated in place
+// after every rejection), and accept_tree_walk_kernel then follows the decisions from the root.
+//   step[i] = (accepted child or -1, token emitted if the walk ends at node i).     grid (nodes), block 512
 template <bool UNIT_T>
-__device__ __forceinline__ void accept_tree_sample_body(const float* __restrict__ P, const float* __restrict__ Q,
-                                                        const int32_t* __restrict__ tok, int V, float T, uint64_t seed, uint32_t seq,
-                                                        uint32_t round, const TreeShape& ts, int32_t* __restrict__ res,
-                                                        int32_t* __restrict__ hist_base, AkShared& sm, float* pick, int* spath) {
+__device__ __forceinline__ void accept_tree_node_body(const float* __restrict__ P, const float* __restrict__ Q,
+                                                      const int32_t* __restrict__ tok, int V, float T, uint64_t seed, uint32_t seq,
+                                                      uint32_t round, const TreeShape& ts, int2* __restrict__ step, AkShared& sm,
+                                                      float* pick) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const double invT = 1.0 / (double)T;
-    int cur = 0, npath = 0, token = -1;
+    const int cur = blockIdx.x;
     float xp[AK_CH][4], xq[AK_CH][4];
-    for (;;) {
-        int ch[TREE_RANKS];
-        const int nch = tree_children_of(ts, cur, ch);
-        ak_normalised<UNIT_T>(P + (size_t)cur * V, V, invT, xp, sm, wave, lane);
-        if (nch > 0) ak_normalised<UNIT_T>(Q + (size_t)cur * V, V, invT, xq, sm, wave, lane);
-        int next = -1;
+    int ch[TREE_RANKS];
+    const int nch = tree_children_of(ts, cur, ch);
+    ak_normalised<UNIT_T>(P + (size_t)cur * V, V, invT, xp, sm, wave, lane);
+    if (nch > 0) ak_normalised<UNIT_T>(Q + (size_t)cur * V, V, invT, xq, sm, wave, lane);
+    int next = -1;
 #pragma unroll 1
-        for (int c = 0; c < nch; ++c) {
-            int child = ch[0];
+    for (int c = 0; c < nch; ++c) {
+        int child = ch[0];
 #pragma unroll
-            for (int i = 1; i < TREE_RANKS; ++i) child = c == i ? ch[i] : child;
-            const int x = min(max(tok[child], 0), V - 1);          // clamped: stays in bounds for any input
-            const int off = x - wave * AK_SEG - lane * 4;
-            const bool owner = off >= 0 && off < AK_SEG && (off & 255) < 4;
-            const float pv = ak_take(xp, x, wave, lane, false), qv = ak_take(xq, x, wave, lane, true);   // q(x) leaves the urn either way
-            __syncthreads();
-            if (owner) { pick[0] = pv; pick[1] = qv; }
-            __syncthreads();
-            const double pd = (double)pick[0], qd = (double)pick[1];
-            bool acc = true;
-            if (qd > 0.0) {
-                const double ratio = pd / qd;
-                const float u = philox_uniform(seed, seq, round, (uint32_t)(child - 1), 0u);
-                acc = (double)u < (ratio < 1.0 ? ratio : 1.0);
+        for (int i = 1; i < TREE_RANKS; ++i) child = c == i ? ch[i] : child;
+        const int x = min(max(tok[child], 0), V - 1);          // clamped: stays in bounds for any input
+        const int off = x - wave * AK_SEG - lane * 4;
+        const bool owner = off >= 0 && off < AK_SEG && (off & 255) < 4;
+        const float pv = ak_take(xp, x, wave, lane, false), qv = ak_take(xq, x, wave, lane, true);   // q(x) leaves the urn either way
+        __syncthreads();
+        if (owner) { pick[0] = pv; pick[1] = qv; }
+        __syncthreads();
+        const double pd = (double)pick[0], qd = (double)pick[1];
+        bool acc = true;
+        if (qd > 0.0) {
+            const double ratio = pd / qd;
+            const float u = philox_uniform(seed, seq, round, (uint32_t)(child - 1), 0u);
+            acc = (double)u < (ratio < 1.0 ? ratio : 1.0);
+        }
+        if (acc) { next = child; break; }
+        // rejected: p <- norm(max(0, p - q)) with q still counting q(x); q <- q without x, renormalised
+#pragma unroll
+        for (int cc = 0; cc < AK_CH; ++cc)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float qe = (owner && cc == (off >> 8) && e == (off & 3)) ? qv : xq[cc][e];
+                xp[cc][e] = fmaxf(xp[cc][e] - qe, 0.f);
             }
-            if (acc) { next = child; break; }
-            // rejected: p <- norm(max(0, p - q)) with q still counting q(x); q <- q without x, renormalised
-#pragma unroll
-            for (int cc = 0; cc < AK_CH; ++cc)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float qe = (owner && cc == (off >> 8) && e == (off & 3)) ? qv : xq[cc][e];
-                    xp[cc][e] = fmaxf(xp[cc][e] - qe, 0.f);
-                }
-            const double Zr = ak_totals(xp, sm, 0, wave, lane);
-            if (Zr > 0.0) ak_scale(xp, Zr);
-            else ak_normalised<UNIT_T>(P + (size_t)cur * V, V, invT, xp, sm, wave, lane);   // p == q to rounding: a rejection has probability 0; keep p
-            const double Sq = ak_totals(xq, sm, 1, wave, lane);
-            if (Sq > 0.0) ak_scale(xq, Sq);
-        }
-        if (next < 0) {
-            const double Z = ak_totals(xp, sm, 0, wave, lane);
-            const float u = philox_uniform(seed, seq, round, 0u, 1u);
-            ak_search(xp, sm.dz[0], Z, u, V, sm, wave, lane);
-            __syncthreads();
-            token = sm.token;
-            break;
-        }
-        if (threadIdx.x == 0) spath[npath] = next;
-        ++npath;
-        cur = next;
+        const double Zr = ak_totals(xp, sm, 0, wave, lane);
+        if (Zr > 0.0) ak_scale(xp, Zr);
+        else ak_normalised<UNIT_T>(P + (size_t)cur * V, V, invT, xp, sm, wave, lane);   // p == q to rounding: a rejection has probability 0; keep p
+        const double Sq = ak_totals(xq, sm, 1, wave, lane);
+        if (Sq > 0.0) ak_scale(xq, Sq);
     }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        res[0] = npath;
-        res[1] = token;
-        for (int j = 0; j < npath; ++j) res[2 + j] = spath[j];
-        for (int j = 0; j < npath; ++j) hist_base[1 + j] = tok[spath[j]];     // path[j] >= j + 1: reads from tok, a separate array
-        hist_base[1 + npath] = token;
+    int token = -1;
+    if (next < 0) {
+        const double Z = ak_totals(xp, sm, 0, wave, lane);
+        const float u = philox_uniform(seed, seq, round, 0u, 1u);
+        ak_search(xp, sm.dz[0], Z, u, V, sm, wave, lane);
+        __syncthreads();
+        token = sm.token;
     }
+    if (threadIdx.x == 0) step[cur] = make_int2(next, token);
 }
 
-__global__ __launch_bounds__(AK_NT) void accept_tree_sample_kernel(const float* __restrict__ P, const float* __restrict__ Q,
-                                                                   const int32_t* __restrict__ tok, int V, float T, uint64_t seed,
-                                                                   uint32_t seq, uint32_t round, TreeShape ts, int32_t* __restrict__ res,
-                                                                   int32_t* __restrict__ hist_base) {
+__global__ __launch_bounds__(AK_NT) void accept_tree_node_kernel(const float* __restrict__ P, const float* __restrict__ Q,
+                                                                 const int32_t* __restrict__ tok, int V, float T, uint64_t seed,
+                                                                 uint32_t seq, uint32_t round, TreeShape ts, int2* __restrict__ step) {
     __shared__ AkShared sm;
     __shared__ float pick[2];
-    __shared__ int spath[TREE_MAX];
-    if (T == 1.0f) accept_tree_sample_body<true>(P, Q, tok, V, T, seed, seq, round, ts, res, hist_base, sm, pick, spath);
-    else accept_tree_sample_body<false>(P, Q, tok, V, T, seed, seq, round, ts, res, hist_base, sm, pick, spath);
+    if (T == 1.0f) accept_tree_node_body<true>(P, Q, tok, V, T, seed, seq, round, ts, step, sm, pick);
+    else accept_tree_node_body<false>(P, Q, tok, V, T, seed, seq, round, ts, step, sm, pick);
+}
+
+// Follows the nodes' decisions from the root; res and hist as accept_tree_kernel.     grid (1), block 64
+__global__ void accept_tree_walk_kernel(const int2* __restrict__ step, const int32_t* __restrict__ tok, TreeShape ts,
+                                        int32_t* __restrict__ res, int32_t* __restrict__ hist_base) {
+    if (threadIdx.x != 0) return;
+    int cur = 0, n = 0;
+    int path[TREE_MAX];
+    while (n < TREE_MAX - 1) {
+        const int next = step[cur].x;
+        if (next <= cur || next >= ts.n) break;          // -1, or anything that is not a later node
+        path[n++] = next;
+        cur = next;
+    }
+    const int token = step[cur].y;
+    res[0] = n;
+    res[1] = token;
+    for (int j = 0; j < n; ++j) res[2 + j] = path[j];
+    for (int j = 0; j < n; ++j) hist_base[1 + j] = tok[path[j]];     // path[j] >= j + 1: reads from tok, a separate array
+    hist_base[1 + n] = token;
 }
 
 // After acceptance the K/V of the accepted nodes move from their tree slots to the positions they were rotated for:

@@ -155,7 +155,7 @@ struct GridBar { int abort; int pad[3]; };
 
 // Workspace layout shared by metasd_workspace_bytes and metasd_create.
 struct Layout {
-    size_t hist, h, h2, xn, part, part2, gx, ssq, inv, q, ao, act, apart, rope, P, Q, cand, bd, res, draft, bar, xchg, tables, table_stride, total;
+    size_t hist, h, h2, xn, part, part2, gx, ssq, inv, q, ao, act, apart, rope, P, Q, cand, bd, res, draft, tstep, bar, xchg, tables, table_stride, total;
 };
 
 Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const metasd_model_desc* dr) {
@@ -213,6 +213,7 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     L.bd = take(B * c.gamma_max * sizeof(double));
     L.res = take(std::max<size_t>(128, B * 12));                   // batch 1: also the path of a tree round (2 + 15 words)
     L.draft = take(std::max<size_t>(64, B * (c.gamma_max + 1) * 4)); // chain: gamma tokens per sequence; tree: one per node
+    L.tstep = take(TREE_MAX * sizeof(int2));                       // sampled tree rounds: the decision of every node
     L.bar = take(sizeof(GridBar));
     L.xchg = take(B * (c.gamma_max + 1) * AS_XCHG_BYTES);
     int lmax = t.n_layers;
@@ -462,6 +463,7 @@ struct metasd_ctx {
     float* d_P() const { return reinterpret_cast<float*>(ws + lay.P); }
     float* d_Q() const { return reinterpret_cast<float*>(ws + lay.Q); }
     int2* d_cand() const { return reinterpret_cast<int2*>(ws + lay.cand); }
+    int2* d_tstep() const { return reinterpret_cast<int2*>(ws + lay.tstep); }
     double* d_bd() const { return reinterpret_cast<double*>(ws + lay.bd); }
     int32_t* d_res() const { return reinterpret_cast<int32_t*>(ws + lay.res); }
     int32_t* d_draft() const { return reinterpret_cast<int32_t*>(ws + lay.draft); }
@@ -570,14 +572,19 @@ int gemm_residual(metasd_ctx* c, const void* x, int ldx, int m, int K, const voi
         *ntg_out = ntiles;
         return 0;
     }
-    const size_t lds_roll = (size_t)8 * 4 * m * (GEMM_U * 4 + 1) * 16 + (size_t)8 * 64 * 16;
-    if (c->fullk && c->fullk_roll && m <= 8 && ntiles * 4 >= c->n_cu * 3 && kchunks >= 8 * GEMM_U && lds_roll <= FULLK_LDS_MAX) {
+    // up to 8 rows: two private staging buffers per wavefront; 9 .. 16 rows: one (see the kernel)
+    const size_t lds_roll = (size_t)8 * (m <= 8 ? 4 : 2) * m * (GEMM_U * 4 + 1) * 16 + (size_t)8 * 64 * 16;
+    if (c->fullk && c->fullk_roll && m <= 16 && ntiles * 4 >= c->n_cu * 3 && kchunks >= 8 * GEMM_U && lds_roll <= FULLK_LDS_MAX) {
         metasd_ctx::ProfRec* pr = c->prof_take(METASD_PROF_GEMM, (double)N * K * 2 + (double)m * K * 4 + (double)m * N * 4, N, K, m);
         hipEvent_t ea = pr ? pr->a : nullptr, eb = pr ? pr->b : nullptr;
-#define ROLL_GO(XB) hipExtLaunchKernelGGL(gemm_fullk_roll_residual_kernel<XB>, dim3(ntiles), dim3(512), (uint32_t)lds_roll, c->stream, ea, eb, 0u, \
-                                          (const bf16_t*)x, x_lo_off, ldx, m, K, (const bf16_t*)W, ntiles, N, h, (const bf16_t*)gain_next, xsplit, ssq)
-        if (m <= 6) ROLL_GO(3);
-        else ROLL_GO(4);
+#define ROLL_GO(XB, DB) hipExtLaunchKernelGGL((gemm_fullk_roll_residual_kernel<XB, DB>), dim3(ntiles), dim3(512), (uint32_t)lds_roll, c->stream, ea, eb, 0u, \
+                                              (const bf16_t*)x, x_lo_off, ldx, m, K, (const bf16_t*)W, ntiles, N, h, (const bf16_t*)gain_next, xsplit, ssq)
+        if (m <= 6) ROLL_GO(3, true);
+        else if (m <= 8) ROLL_GO(4, true);
+        else if (m <= 10) ROLL_GO(5, false);
+        else if (m <= 12) ROLL_GO(6, false);
+        else if (m <= 14) ROLL_GO(7, false);
+        else ROLL_GO(8, false);
 #undef ROLL_GO
         LAUNCH_CHECK(c, "gemm_bf16 (full-K residual, rolling staging)");
         *ntg_out = ntiles;
@@ -1668,8 +1675,12 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         if (const char* ev = getenv("METASD_ROWS_TPB")) { const int v = atoi(ev); c->rows_tpb = (v == 4 || v == 6 || v == 8) ? v : 0; }
         {
             const int roll_lds = (int)FULLK_LDS_MAX;
-            if (hipFuncSetAttribute((const void*)gemm_fullk_roll_residual_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, roll_lds) != hipSuccess ||
-                hipFuncSetAttribute((const void*)gemm_fullk_roll_residual_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, roll_lds) != hipSuccess) {
+            if (hipFuncSetAttribute((const void*)gemm_fullk_roll_residual_kernel<3, true>, hipFuncAttributeMaxDynamicSharedMemorySize, roll_lds) != hipSuccess ||
+                hipFuncSetAttribute((const void*)gemm_fullk_roll_residual_kernel<4, true>, hipFuncAttributeMaxDynamicSharedMemorySize, roll_lds) != hipSuccess ||
+                hipFuncSetAttribute((const void*)gemm_fullk_roll_residual_kernel<5, false>, hipFuncAttributeMaxDynamicSharedMemorySize, roll_lds) != hipSuccess ||
+                hipFuncSetAttribute((const void*)gemm_fullk_roll_residual_kernel<6, false>, hipFuncAttributeMaxDynamicSharedMemorySize, roll_lds) != hipSuccess ||
+                hipFuncSetAttribute((const void*)gemm_fullk_roll_residual_kernel<7, false>, hipFuncAttributeMaxDynamicSharedMemorySize, roll_lds) != hipSuccess ||
+                hipFuncSetAttribute((const void*)gemm_fullk_roll_residual_kernel<8, false>, hipFuncAttributeMaxDynamicSharedMemorySize, roll_lds) != hipSuccess) {
                 c->fullk_roll = false;
                 (void)hipGetLastError();
             }
@@ -1969,9 +1980,11 @@ int32_t metasd_accept_tree(metasd_ctx* c, int32_t* n_acc_out, int32_t* token_out
     if (c->phase != PH_TREE_VERIFIED) return c->fail(METASD_E_ORDER, "accept_tree: verify_tree has not been run for this round");
     const int n = c->tshape.n, V = c->target.d.vocab, l = c->sq[0].l, base = l - 1;
     if (c->cfg.temperature > 0.f) {
-        hipLaunchKernelGGL(accept_tree_sample_kernel, dim3(1), dim3(AK_NT), 0, c->stream, (const float*)c->d_P(), (const float*)c->d_Q(),
-                           (const int32_t*)c->d_draft(), V, c->cfg.temperature, c->cfg.seed, 0u, (uint32_t)c->sq[0].round, c->tshape, c->d_res(),
-                           c->d_hist() + base);
+        hipLaunchKernelGGL(accept_tree_node_kernel, dim3(n), dim3(AK_NT), 0, c->stream, (const float*)c->d_P(), (const float*)c->d_Q(),
+                           (const int32_t*)c->d_draft(), V, c->cfg.temperature, c->cfg.seed, 0u, (uint32_t)c->sq[0].round, c->tshape, c->d_tstep());
+        LAUNCH_CHECK(c, "accept_tree (nodes)");
+        hipLaunchKernelGGL(accept_tree_walk_kernel, dim3(1), dim3(64), 0, c->stream, (const int2*)c->d_tstep(), (const int32_t*)c->d_draft(),
+                           c->tshape, c->d_res(), c->d_hist() + base);
     } else {
         int32_t* amax = reinterpret_cast<int32_t*>(c->d_cand());
         if (launch_sample(c->stream, c->d_P(), n, V, 0.f, c->cfg.seed, 0u, 0u, 0u, amax, 1, nullptr)) return c->fail(METASD_E_HIP, "launch argmax failed");
