@@ -80,6 +80,8 @@ def lib():
         L.om_model_kv.argtypes = [C.c_void_p, C.c_int]
         L.om_forward.restype = C.c_int
         L.om_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int]
+        L.om_forward_ex.restype = C.c_int
+        L.om_forward_ex.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
         L.om_forward_rows.restype = C.c_int
         L.om_forward_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.om_philox.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p]
@@ -131,9 +133,16 @@ class Model:
     early-exit drafter.  The new model then keeps no cache of its own: it reads and writes the owner's (the
     no-recomputation strategy for drafter switches, cf. the paper's appendix on switching costs); ``shares_kv`` is set."""
 
-    def __init__(self, desc: dict, weights: list, max_ctx: int, share_kv_with: "Model | None" = None, stream=None):
+    def __init__(self, desc: dict, weights: list, max_ctx: int, share_kv_with: "Model | None" = None, stream=None, fc=None):
+        """fc (optional, [d, 2 d] in the model's dtype): the model is a drafter head on the target's hidden states - its rows start
+        from W_fc . [embedding(token) ; feature] instead of the embedding (``forward_feat``)."""
         self.desc = dict(desc)
         self.max_ctx = int(max_ctx)
+        self.fc = fc
+        self.feature_head = fc is not None
+        if fc is not None:
+            want_fc = np.uint16 if desc["dtype"] == 1 else np.float32
+            assert isinstance(fc, np.ndarray) and fc.dtype == want_fc and fc.shape == (desc["d_model"], 2 * desc["d_model"]) and fc.flags["C_CONTIGUOUS"]
         self.stream = None if stream is None else (int(stream[0]), int(stream[1]))   # (sinks, window) of a streaming drafter cache
         assert self.stream is None or (share_kv_with is None and self.stream[0] >= 0 and self.stream[1] >= 1)
         self.shares_kv = share_kv_with is not None
@@ -192,6 +201,25 @@ class Model:
             raise ValueError("om_forward: bad arguments (tokens / positions out of range)")
         return out
 
+    def forward_hidden(self, tokens, pos0: int, want: str | None = "all", feats=None):
+        """``forward`` that also returns the residual stream after the last layer of every row ([m, d]: the features of
+        those positions).  feats [m, d] (drafter heads only, ``fc`` given): row r starts from W_fc . [embedding ; feats[r]]."""
+        tok = np.ascontiguousarray(tokens, dtype=np.int32)
+        m = tok.shape[0]
+        V, D = self.desc["vocab"], self.desc["d_model"]
+        hid = np.empty((m, D), np.float32)
+        out = None if want is None else np.empty((m, V) if want == "all" else (V,), np.float32)
+        if self.feature_head:
+            f = np.ascontiguousarray(feats, np.float32)
+            assert f.shape == (m, D)
+            fcp, fp = _ptr(self.fc), _ptr(f)
+        else:
+            assert feats is None
+            fcp, fp = None, None
+        rc = lib().om_forward_ex(self._h, _ptr(tok), m, pos0, None if out is None else _ptr(out), 1 if want == "last" else 0, fcp, fp, _ptr(hid))
+        if rc != 0:
+            raise ValueError("om_forward_ex: bad arguments (tokens / positions out of range)")
+        return out, hid
 
     def forward_rows(self, tokens, slots, positions, allow, want_logits: bool = True):
         """Rows that need not form a chain (tree attention): row r writes its K/V to cache slot slots[r], is rotated for

@@ -19,6 +19,18 @@ last W positions up to p, at their original positions; when it is switched in it
 the last W committed tokens, and that is all it consumes - a longer backlog is skipped, and ``a[k]`` remembers where the
 contiguous tail of its cache starts so that nothing skipped is ever attended to.  (The drafter's distribution changes;
 the output law does not: Alg. 3 is exact for any drafter.)
+
+Drafter heads on the target's hidden states (the white-box drafters of Sec. 4: "Eagle" drafters; the paper gives no
+formulas for them).  Reading used here, after the published design it cites: the *feature* of position p, f_p, is the
+target's residual stream after its last layer at p.  A drafter head (``Model(..., fc=W_fc)``: W_fc, its own decoder
+layer(s), and the target's embedding, final norm and LM head) processes position p from the token there and the feature
+of the position before it: h = W_fc . [embedding(x_p) ; f_{p-1}] (f_{-1} = 0), then its layers with a KV cache of its own;
+what comes out is its estimate of f_p, and the target's final norm and LM head turn that into the distribution of
+x_{p+1}.  While drafting, the estimate of f_p is the feature input of the next step.  True features exist for every
+position the target has processed, i.e. up to l - 2; the verification pass yields those of the block's rows, and the
+accepted ones (positions l-1 .. l-1+n) are kept.  Whatever the head computed from estimated features is not kept: after
+a round its cache is valid up to position l_before - 1 only (``c[k] = l_before``), and the next time it is selected it
+first consumes the committed tokens since then with their true features.
 """
 from __future__ import annotations
 
@@ -35,6 +47,7 @@ class SdState:
     t: int = 0                       # completed rounds (Alg. 2's t)
     log: list = field(default_factory=list)
     a: list = None                   # streaming drafters: first position of the contiguous tail of the cache (0: no gap)
+    feat: np.ndarray = None          # [max_ctx, d] target features of the processed positions (only with drafter heads)
 
 
 def stream_allow(max_ctx: int, positions, S: int, W: int, a: int) -> np.ndarray:
@@ -87,14 +100,28 @@ def sd_round(target, drafter, k: int, st: SdState, gamma: int, T: float, seed: i
     if getattr(drafter, "shares_kv", False):
         st.c[k] = l - 1
     stream = getattr(drafter, "stream", None)
-    if stream is not None:
+    head = getattr(drafter, "feature_head", False)
+    f_est = None
+    if head:
+        # the committed tokens it has not seen, each with the true feature of the position before it
+        c = st.c[k]
+        D = st.feat.shape[1]
+        feats = np.zeros((l - c, D), np.float32)
+        lo = max(c, 1)
+        feats[lo - c:] = st.feat[lo - 1: l - 1]
+        Q[0], hid = drafter.forward_hidden(st.hist[c: l], c, "last", feats=feats)
+        f_est = hid[-1]
+    elif stream is not None:
         if st.a is None:
             st.a = [0] * len(st.c)
         Q[0], st.a[k] = stream_catch_up(drafter, st.hist, st.c[k], l, st.a[k])
     else:
         Q[0] = drafter.forward(st.hist[st.c[k]: l], st.c[k], "last")
     for j in range(gamma):
-        if j > 0 and stream is not None:
+        if j > 0 and head:
+            Q[j], hid = drafter.forward_hidden(st.hist[l + j - 1: l + j], l + j - 1, "last", feats=f_est[None])
+            f_est = hid[-1]
+        elif j > 0 and stream is not None:
             Q[j] = stream_forward(drafter, st.hist, l + j - 1, l + j, st.a[k])
         elif j > 0:
             Q[j] = drafter.forward(st.hist[l + j - 1: l + j], l + j - 1, "last")
@@ -102,7 +129,10 @@ def sd_round(target, drafter, k: int, st: SdState, gamma: int, T: float, seed: i
         d[j], draft_margin[j] = sample(Q[j], T, u, with_margin=True)
         st.hist[l + j] = d[j]
     # --- verify: one target pass over [x_last, d_1 .. d_gamma]
-    P = target.forward(st.hist[l - 1: l + gamma], l - 1, "all")
+    if st.feat is not None:
+        P, H = target.forward_hidden(st.hist[l - 1: l + gamma], l - 1, "all")
+    else:
+        P = target.forward(st.hist[l - 1: l + gamma], l - 1, "all")
     # --- accept
     u_acc = np.array([uniform(seed, seq, st.t, j, STREAM_ACCEPT) for j in range(gamma)], np.float32)
     u_res = uniform(seed, seq, st.t, 0, STREAM_RESIDUAL)
@@ -112,6 +142,10 @@ def sd_round(target, drafter, k: int, st: SdState, gamma: int, T: float, seed: i
     st.hist[l + n] = r["token"]
     st.l = l + n + 1
     st.c[k] = st.l - 1 if getattr(drafter, "shares_kv", False) else min(l + n, l + gamma - 1)
+    if st.feat is not None:
+        st.feat[l - 1: l + n] = H[: n + 1]             # the features of the committed rows of the block
+    if head:
+        st.c[k] = l                                    # what it computed from estimated features is not kept
     out = dict(k=k, round=st.t, l_before=l, d=d.copy(), P=P, Q=Q, u_acc=u_acc, u_res=u_res,
                draft_margin=draft_margin, **r)
     st.t += 1
@@ -137,10 +171,17 @@ def generate(target, drafters, prompt, n_new: int, gamma: int, T: float, seed: i
     hist = np.zeros(target.max_ctx, np.int32)
     hist[:l0] = prompt
     st = SdState(hist=hist, l=l0, c=[0] * len(drafters))
+    heads = any(getattr(dr, "feature_head", False) for dr in drafters)
+    if heads:
+        st.feat = np.zeros((target.max_ctx, target.desc["d_model"]), np.float32)
     if kv_prefilled:
+        assert not heads, "drafter heads need the features of the prefilled positions"
         st.c = [l0 - 1] * len(drafters)
     elif l0 > 1:
-        target.forward(prompt[: l0 - 1], 0, None)
+        if heads:
+            _, st.feat[: l0 - 1] = target.forward_hidden(prompt[: l0 - 1], 0, None)
+        else:
+            target.forward(prompt[: l0 - 1], 0, None)
     bandit = Ucb(len(drafters), beta)
     rounds = []
     while st.l < B:

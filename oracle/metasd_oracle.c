@@ -205,7 +205,23 @@ float *om_model_kv(om_model *m, int which) { return which ? m->vc : m->kc; }
  * 0 .. pos0+r (causal).  logits: NULL (none), or [m][V] when last_only == 0, or [V] holding the
  * last row's logits when last_only != 0.  Returns 0, or -1 on bad arguments.
  */
+/*
+ * om_forward_ex: om_forward with two optional additions used by drafters that run on the target's hidden states (the
+ * white-box drafters of Sec. 4, "Eagle"; the paper gives no formulas for them - the reading is stated in oracle/loop.py):
+ *   hidden_out [m][D]: the residual stream after the last layer of every row (the "feature" of that position);
+ *   fc, feat_in [m][D]: the rows do not start from the token embedding alone but from
+ *       h = W_fc . [embedding(token) ; feat_in[r]],   W_fc [D][2 D] row-major (no bias).
+ * With fc == NULL and hidden_out == NULL it is om_forward, step for step.
+ */
+int om_forward_ex(om_model *M, const int32_t *tokens, int m, int pos0, float *logits, int last_only,
+                  const void *fc, const float *feat_in, float *hidden_out);
+
 int om_forward(om_model *M, const int32_t *tokens, int m, int pos0, float *logits, int last_only) {
+    return om_forward_ex(M, tokens, m, pos0, logits, last_only, NULL, NULL, NULL);
+}
+
+int om_forward_ex(om_model *M, const int32_t *tokens, int m, int pos0, float *logits, int last_only,
+                  const void *fc, const float *feat_in, float *hidden_out) {
     const om_desc *d = &M->d;
     const int D = d->d_model, H = d->n_heads, KH = d->n_kv_heads, hd = M->hd, F = d->d_ffn, V = d->vocab;
     const int DQ = H * hd, DKV = KH * hd;
@@ -226,6 +242,16 @@ int om_forward(om_model *M, const int32_t *tokens, int m, int pos0, float *logit
     const void *embed = M->w[0];
     for (int r = 0; r < m; ++r)
         for (int i = 0; i < D; ++i) h[(size_t)r * D + i] = (float)wget(d, embed, (size_t)tokens[r] * D + i);
+    if (fc) {
+        /* h = W_fc . [embedding ; feature] */
+        float *cat = (float *)malloc(sizeof(float) * (size_t)m * 2 * D);
+        for (int r = 0; r < m; ++r) {
+            memcpy(cat + (size_t)r * 2 * D, h + (size_t)r * D, sizeof(float) * (size_t)D);
+            memcpy(cat + (size_t)r * 2 * D + D, feat_in + (size_t)r * D, sizeof(float) * (size_t)D);
+        }
+        matmul(d, cat, m, 2 * D, fc, D, h);
+        free(cat);
+    }
 
     for (int L = 0; L < d->n_layers; ++L) {
         const void *const *w = M->w + 1 + OM_PER_LAYER * L;
@@ -293,6 +319,7 @@ int om_forward(om_model *M, const int32_t *tokens, int m, int pos0, float *logit
         for (size_t i = 0; i < (size_t)m * D; ++i) h[i] = (float)((double)h[i] + (double)y[i]);
     }
 
+    if (hidden_out) memcpy(hidden_out, h, sizeof(float) * (size_t)m * D);
     if (logits) {
         const void *fn = M->w[1 + OM_PER_LAYER * d->n_layers];
         const void *head = M->w[2 + OM_PER_LAYER * d->n_layers];

@@ -1,5 +1,6 @@
 """The oracle's MetaSD loop (Alg. 1 / Alg. 2 around Alg. 3 rounds) on the tiny configuration."""
 import numpy as np
+import torch
 import pytest
 
 import oracle
@@ -177,3 +178,90 @@ def test_streaming_caches_keep_greedy_decoding_lossless(stream):
     assert np.array_equal(out["tokens"], ref)
     st = out["state"]
     assert st.a is not None and max(st.a) > 0                # some backlog was skipped
+
+
+# ---------------------------------------------------------------- drafter heads on the target's hidden states
+
+def _head_models(cfg, eps, layer=0):
+    T = oracle.Model(cfg["target"][0], W.to_numpy(cfg["target"][1]), cfg["max_ctx"])
+    D = []
+    for k in range(3):
+        dd, dw, fc = W.feature_head_drafter(cfg["target"][0], cfg["target"][1], layer, eps * k if eps else 0.0, 300 + k)
+        D.append(oracle.Model(dd, W.to_numpy(dw), cfg["max_ctx"], fc=W.to_numpy([fc])[0]))
+    return T, D
+
+
+def test_feature_is_the_residual_stream_before_the_final_norm():
+    """logits = LM head . RMSNorm(feature) . gain, recomputed here with numpy from the returned features."""
+    cfg = W.config1()
+    td, tw = cfg["target"]
+    T = oracle.Model(td, W.to_numpy(tw), cfg["max_ctx"])
+    P, H = T.forward_hidden(cfg["prompt"][:9], 0, "all")
+    g = tw[-2].double().numpy()
+    head = tw[-1].double().numpy()
+    x = H.astype(np.float64)
+    x = x / np.sqrt((x * x).mean(axis=1, keepdims=True) + td["rms_eps"]) * g
+    assert np.abs(x.astype(np.float32).astype(np.float64) @ head.T - P).max() < 2e-5
+    assert np.array_equal(T.forward(cfg["prompt"][9:12], 9, "all"), T.forward_hidden(cfg["prompt"][9:12], 9, "all")[0])
+
+
+def test_head_that_ignores_the_features_is_the_early_exit_drafter():
+    """W_fc = [I | 0]: the head's rows start from the token embedding, so it is the target's first layer with the target's
+    norm and LM head - the early-exit drafter after one layer, logit for logit, and the whole generation is the same (the
+    head re-reads the committed tokens of the last round, which changes nothing when the features carry no weight)."""
+    cfg = W.config1()
+    td, tw = cfg["target"]
+    T, D = _head_models(cfg, 0.0)
+    a = oracle.generate(T, D, cfg["prompt"], 48, cfg["gamma"], 1.0, cfg["seed"], cfg["beta"], keep_logits=True)
+    T2 = oracle.Model(td, W.to_numpy(tw), cfg["max_ctx"])
+    D2 = []
+    for k in range(3):
+        dd, dw = W.early_exit_drafter(td, tw, 1, 0.0, 100 + k)
+        D2.append(oracle.Model(dd, W.to_numpy(dw), cfg["max_ctx"]))
+    b = oracle.generate(T2, D2, cfg["prompt"], 48, cfg["gamma"], 1.0, cfg["seed"], cfg["beta"], keep_logits=True)
+    assert np.array_equal(a["tokens"], b["tokens"])
+    for ra, rb in zip(a["rounds"], b["rounds"]):
+        assert np.array_equal(ra["Q"], rb["Q"]) and ra["n_acc"] == rb["n_acc"]
+    assert max(r["n_acc"] for r in a["rounds"]) >= 1
+
+
+def test_head_that_passes_the_feature_through_gives_the_targets_logits_of_that_position():
+    """W_fc = [0 | I] and a layer that adds nothing (zero output projections): the head's estimate is the feature it was
+    given, so its logits at position p are the target's logits of position p - 1 - the concatenation order, the feature
+    offset and the use of the target's norm and head in one check."""
+    cfg = W.config1()
+    td, tw = cfg["target"]
+    T = oracle.Model(td, W.to_numpy(tw), cfg["max_ctx"])
+    P, H = T.forward_hidden(cfg["prompt"][:10], 0, "all")
+    dd, dw, _ = W.feature_head_drafter(td, tw, 0, 0.0, 1)
+    dw = list(dw)
+    dw[5] = torch.zeros_like(dw[5])          # wo
+    dw[9] = torch.zeros_like(dw[9])          # w_down
+    d = td["d_model"]
+    fc = torch.cat([torch.zeros(d, d), torch.eye(d)], dim=1).contiguous()
+    Hd = oracle.Model(dd, W.to_numpy(dw), cfg["max_ctx"], fc=fc.numpy())
+    feats = np.zeros((10, d), np.float32)
+    feats[1:] = H[:9]
+    Q, est = Hd.forward_hidden(cfg["prompt"][:10], 0, "all", feats=feats)
+    assert np.array_equal(est, feats)
+    assert np.array_equal(Q[1:], P[:9])
+
+
+@pytest.mark.parametrize("T", [0.0, 1.0])
+def test_generation_with_drafter_heads(T):
+    """Greedy: the target's own greedy continuation whatever the heads do; any T: the features kept along the way are the
+    target's features of the committed text (a fresh pass over it gives them again), and tokens do get accepted."""
+    cfg = W.config1()
+    td, tw = cfg["target"]
+    Tm, D = _head_models(cfg, 0.05)
+    order = [0, 1, 2, 2, 1, 0, 0, 2]
+    out = oracle.generate(Tm, D, cfg["prompt"], cfg["n_new"], cfg["gamma"], T, cfg["seed"], cfg["beta"], policy=lambda r: order[r % len(order)])
+    st = out["state"]
+    if T == 0.0:
+        ref = oracle.ar_decode(oracle.Model(td, W.to_numpy(tw), cfg["max_ctx"]), cfg["prompt"], cfg["n_new"], T=0.0)
+        assert np.array_equal(out["tokens"], ref)
+    fresh = oracle.Model(td, W.to_numpy(tw), cfg["max_ctx"])
+    _, H = fresh.forward_hidden(st.hist[: st.l - 1], 0, None)
+    assert np.array_equal(st.feat[: st.l - 1], H)
+    assert max(r["n_acc"] for r in out["rounds"]) >= 1
+    assert all(c <= st.l - 1 for c in st.c)

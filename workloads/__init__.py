@@ -85,6 +85,21 @@ def early_exit_drafter(tdesc: dict, tweights: list, n_run: int, sigma: float, se
     return desc, w
 
 
+def feature_head_drafter(tdesc: dict, tweights: list, layer: int, eps: float, seed: int):
+    """A drafter head on the target's hidden states (shape only: nothing is trained here): the target's embedding, one decoder
+    layer (the tensors of target layer `layer`, shared), the target's final norm and LM head, and W_fc = [I | eps * N(0, 1)]
+    ([d, 2 d]) mixing the token embedding with the previous position's feature.  With eps = 0 it is the early-exit drafter
+    after one layer (when layer = 0); a small eps keeps some agreement with the target while the feature path carries weight.
+    Returns (desc, weights, fc)."""
+    desc = dict(tdesc)
+    desc["n_layers"] = 1
+    d = tdesc["d_model"]
+    w = [tweights[0]] + list(tweights[1 + PER_LAYER * layer: 1 + PER_LAYER * (layer + 1)]) + [tweights[-2], tweights[-1]]
+    dev = str(tweights[0].device)
+    fc = torch.cat([torch.eye(d, device=dev), _randn((d, d), seed, dev) * eps], dim=1).to(_torch_dtype(tdesc)).contiguous()
+    return desc, w, fc
+
+
 def to_numpy(weights: list) -> list:
     """Host copies for the oracle: fp32 arrays, or uint16 bit patterns for bf16 tensors."""
     out = []
