@@ -49,7 +49,7 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="target layers (32 = the 7B shape; fewer is NOT the benchmark)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rounds", type=int, default=8)
-    ap.add_argument("--workload", default="c4", choices=["c4", "c5", "c3", "c2", "c4tree"],
+    ap.add_argument("--workload", default="c4", choices=["c4", "c5", "c3", "c2", "c4tree", "c4heads"],
                     help="c4 (default): the headline benchmark; c5: the batched configuration (32 sequences, gamma 7, KV context 4096); "
                          "c3: the 1B-shape GQA target with four early-exit drafters, real 512-token prefill; "
                          "c2: the accept kernel alone (64 rows x gamma 5 x vocab 32000); c4tree: the C4 models with multi-candidate "
@@ -71,6 +71,8 @@ def main():
         return bench_c2(args)
     if args.workload == "c3":
         return bench_c3(args)
+    if args.workload == "c4heads":
+        return bench_c4_heads(args)
     if args.workload == "c4tree":
         return bench_c4_tree(args)
 
@@ -504,6 +506,78 @@ def bench_c4_tree(args):
            "config": {"workload": f"C4 models, KV context {args.ctx}, batch 1, T={args.temperature}: rounds over the '{args.tree}' draft tree "
                                   f"({n} nodes, depth {D}) against chain rounds with gamma = {D}", "tree": args.tree, "nodes": n, "depth": D},
            "roofline": None, "cpu_baseline": None, "detail": res}
+    print(json.dumps(out))
+    g.close()
+    return 0
+
+
+def bench_c4_heads(args):
+    """Side measurement: the C4 target (7B shape, KV context 2048, gamma = 5, T = 1) with K = 5 one-layer drafter heads on its
+    hidden states (the white-box setting of the paper's Sec. 4): head k runs the tensors of target layer k behind a W_fc of
+    its own; K/V prefix and feature prefix are seeded synthetic fills."""
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU available; the MetaSD library has no CPU path")
+    import paper_2604_05417_amd as M
+    import workloads as W
+    dev = "cuda:0"
+    K_steps, Wm = args.steps, max(args.warmup, 5)
+    cfg = W.config4(device=dev, n_layers=args.layers, ctx=args.ctx, K=1)
+    gamma = cfg["gamma"]
+    cfg["max_ctx"] = args.ctx + (gamma + 1) * (K_steps + Wm + 16) + 16
+    td, tw = cfg["target"]
+    drafters, heads = [], {}
+    for k in range(5):
+        dd, dw, fc = W.feature_head_drafter(td, tw, k % td["n_layers"], 0.01 * W.c4_noise_scale(k, 0), 300 + k)
+        drafters.append((dd, dw))
+        heads[k] = fc
+    g = M.MetaSD((td, tw), drafters, gamma_max=gamma, max_ctx=cfg["max_ctx"], temperature=1.0, seed=cfg["seed"], ucb_beta=cfg["beta"],
+                 heads=heads)
+    n0 = args.ctx - 1
+    for i, (desc, kv) in enumerate([(td, g.kv_target)] + [(dd, g.kv_drafters[k]) for k, (dd, _) in enumerate(drafters)]):
+        kk, vv = W.kv_fill(desc, n0, cfg["kv_seed"] + i, device=dev)
+        kv[:, 0, :, :n0] = kk
+        kv[:, 1, :, :n0] = vv
+    g.set_context(cfg["prompt"], kv_prefilled=True)
+    gen = torch.Generator(device="cpu").manual_seed(77)
+    g.peek("feat")[:n0] = (torch.randn((n0, td["d_model"]), generator=gen) * 0.05).to(dev)
+
+    def one_round():
+        k = g.bandit_select()
+        g.draft(k, gamma)
+        g.verify(gamma)
+        na, tok, mask, bd = g.accept(gamma)
+        g.bandit_update(k, na, gamma, bd)
+        return na
+
+    for _ in range(Wm):
+        one_round()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    accs = [one_round() for _ in range(K_steps)]
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t1
+    ph = []
+    for _ in range(8):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        k = g.bandit_select()
+        ev[0].record()
+        g.draft(k, gamma); ev[1].record()
+        g.verify(gamma); ev[2].record()
+        na, tok, mask, bd = g.accept(gamma)
+        ev[3].record()
+        g.bandit_update(k, na, gamma, bd)
+        torch.cuda.synchronize()
+        ph.append([ev[j].elapsed_time(ev[j + 1]) for j in range(3)])
+    med = np.median(np.array(ph), axis=0)
+    detail = {"mean_n_acc": float(np.mean(accs)), "draft_ms": float(med[0]), "verify_ms": float(med[1]), "accept_ms": float(med[2])}
+    out = {"metric": "verified tokens/sec @1 GPU (7B-shape, drafter heads on hidden states)", "value": (sum(accs) + len(accs)) / dt,
+           "unit": "tokens/s", "n_gpus": 1, "steps": K_steps, "warmup": Wm, "ms_per_step": dt / K_steps * 1e3, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"C4 target, KV context {args.ctx}, batch 1, gamma {gamma}, T=1, K=5 one-layer heads on the target's "
+                                  "hidden states (W_fc [4096, 8192] each, layer tensors shared with the target)"},
+           "roofline": None, "cpu_baseline": None, "detail": detail}
     print(json.dumps(out))
     g.close()
     return 0

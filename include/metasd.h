@@ -114,6 +114,10 @@ typedef struct {
      * output law does not (Alg. 3 is exact for any drafter). */
     int32_t stream_sink;
     int32_t stream_window;
+    /* 1: the context keeps the target's hidden states ("features": the residual stream after the last layer) of every
+     * processed position, for drafters that run on them (metasd_set_drafter_head).  batch == 1 only; costs max_ctx *
+     * d_model * 4 bytes of workspace. */
+    int32_t feature_heads;
 } metasd_config;
 
 /* ---- sizes -------------------------------------------------------------------------------- */
@@ -210,6 +214,23 @@ int32_t metasd_verify(metasd_ctx*, int32_t gamma);
  * the round's state is lost, call metasd_set_context for every sequence to start over). */
 int32_t metasd_accept(metasd_ctx*, int32_t gamma, int32_t* n_acc_out, int32_t* token_out, uint32_t* mask_out,
                       double* bd_out);
+
+/* ---- drafter heads on the target's hidden states (the white-box drafters of the paper's Sec. 4, "Eagle") ------------
+ * The paper gives no formulas for them; the reading, after the published design it cites: the feature f_p of position p is
+ * the target's residual stream after its last layer at p.  A head processes position p from the token there and the
+ * feature of the position before:  h = W_fc . [embedding(x_p) ; f_{p-1}]  (f_{-1} = 0, no bias), then its own decoder
+ * layer(s) with a KV cache of its own; the result is its estimate of f_p, and final norm + LM head (its table entries:
+ * normally the target's tensors) turn it into the distribution of x_{p+1}.  While drafting, the estimate is the feature
+ * input of the next step; what was computed from estimates is dropped after the round, and the next time the head is
+ * selected it first consumes the committed tokens since then with the target's own features.
+ *
+ * metasd_set_drafter_head marks drafter k (same width and dtype as the target; weight table as for any model, embedding
+ * entry = the table the head embeds tokens with) as such a head.  w_fc: device pointer, [d_model][2 d_model], fp32
+ * row-major or bf16 in streaming-tile order (metasd_pack_weight(n_out = d, n_in = 2 d, rope 0)), caller-owned.  Call it
+ * after metasd_create and before the first metasd_set_context; the context must have feature_heads = 1.  With
+ * kv_prefilled contexts the caller also fills the feature table (METASD_PEEK_FEAT) for the prefilled positions.
+ * Heads draft chains (metasd_draft), not trees.  Errors: INVALID, ORDER. */
+int32_t metasd_set_drafter_head(metasd_ctx*, int32_t k, const void* w_fc);
 
 /* ---- multi-candidate rounds: a tree of draft tokens verified in one pass with tree attention -----------------------
  * (the white-box setting of the paper's Sec. 4, "Number of drafts": multi-draft methods verify a token tree).  The paper
@@ -339,6 +360,7 @@ int32_t metasd_profile_shapes(metasd_ctx*, int32_t target_only, int32_t max_rows
 #define METASD_PEEK_Q 1     /* float [gamma_max][V]    drafter logits of the last draft */
 #define METASD_PEEK_HIST 2  /* int32 [batch][max_ctx]  token history (committed + speculative) */
 #define METASD_PEEK_BD 3    /* double [gamma_max]      sum_v min(p_j, q_j) of the last accept */
+#define METASD_PEEK_FEAT 5  /* fp32 [max_ctx][d_model]   the target's features (contexts with feature_heads) */
 #define METASD_PEEK_DRAFT 4 /* int32 [gamma_max + 1]   draft tokens d_1..d_gamma of the last draft; tree rounds: the token of every node (entry 0, the root, unused) */
 /* Device pointer and byte size of an internal buffer (valid until metasd_destroy). */
 int32_t metasd_peek(metasd_ctx*, int32_t what, void** dev_ptr_out, size_t* bytes_out);

@@ -14,7 +14,7 @@ MATRIX_SLOTS = (1, 2, 3, 4, 6, 7, 8)          # wq wk wv wo w_gate w_up w_down w
 EXPORTS = ["metasd_kv_bytes", "metasd_workspace_bytes", "metasd_pack_weight", "metasd_create", "metasd_destroy",
            "metasd_set_context", "metasd_swap_weight", "metasd_bandit_select", "metasd_bandit_update",
            "metasd_bandit_state", "metasd_draft", "metasd_verify", "metasd_accept", "metasd_draft_tree", "metasd_verify_tree", "metasd_accept_tree", "metasd_accept_logits",
-           "metasd_accept_logits_noalloc", "metasd_sample_logits", "metasd_philox_words", "metasd_stream_read", "metasd_profile", "metasd_profile_read", "metasd_profile_shapes", "metasd_peek", "metasd_state", "metasd_state_seq", "metasd_accept_fallbacks", "metasd_last_error"]
+           "metasd_accept_logits_noalloc", "metasd_sample_logits", "metasd_philox_words", "metasd_stream_read", "metasd_profile", "metasd_profile_read", "metasd_profile_shapes", "metasd_peek", "metasd_state", "metasd_state_seq", "metasd_accept_fallbacks", "metasd_set_drafter_head", "metasd_last_error"]
 
 
 class MetaSDError(RuntimeError):
@@ -33,7 +33,7 @@ class _Config(C.Structure):
     _fields_ = [("K", C.c_int32), ("gamma_max", C.c_int32), ("batch", C.c_int32), ("max_ctx", C.c_int32),
                 ("temperature", C.c_float), ("reward", C.c_int32), ("ucb_beta", C.c_double), ("seed", C.c_uint64),
                 ("policy", C.c_int32), ("policy_window", C.c_int32), ("policy_param", C.c_double),
-                ("stream_sink", C.c_int32), ("stream_window", C.c_int32)]
+                ("stream_sink", C.c_int32), ("stream_window", C.c_int32), ("feature_heads", C.c_int32)]
 
 
 class _Tree(C.Structure):
@@ -69,6 +69,7 @@ def load_library():
         "metasd_bandit_select": [vp, i32, C.POINTER(i32)],
         "metasd_bandit_update": [vp, i32, i32, i32, i32, f64],
         "metasd_bandit_state": [vp, i32, vp, vp, C.POINTER(i32)],
+        "metasd_set_drafter_head": [vp, i32, vp],
         "metasd_draft": [vp, C.POINTER(i32), i32],
         "metasd_verify": [vp, i32],
         "metasd_accept": [vp, i32, vp, vp, vp, vp],
@@ -138,8 +139,9 @@ class MetaSD:
     def __init__(self, target, drafters, gamma_max: int, max_ctx: int, temperature: float, seed: int,
                  ucb_beta: float = 1.0, reward: str = "BE", device: str = "cuda:0", policy: str = "ucb",
                  policy_param: float = 0.0, policy_window: int = 0, batch: int = 1, share_target_kv: bool = False,
-                 stream=None):
-        """stream = (sinks, window): drafters with caches of their own keep a streaming cache (metasd_config.stream_*)."""
+                 stream=None, heads=None):
+        """stream = (sinks, window): drafters with caches of their own keep a streaming cache (metasd_config.stream_*).
+        heads = {k: W_fc [d, 2 d]}: drafter k is a head on the target's hidden states (metasd_set_drafter_head)."""
         _require_gpu()
         self.L = load_library()
         self.device = torch.device(device)
@@ -154,7 +156,7 @@ class MetaSD:
         self.ddescs = [dict(d) for d, _ in drafters]
         self.cfg = _Config(self.K, gamma_max, batch, max_ctx, temperature, 1 if reward == "BD" else 0, ucb_beta, seed,
                            POLICIES[policy], policy_window, policy_param, 0 if stream is None else int(stream[0]),
-                           0 if stream is None else int(stream[1]))
+                           0 if stream is None else int(stream[1]), 1 if heads else 0)
         self._tdesc_c = _desc(tdesc)
         self._ddesc_c = (_Desc * self.K)(*[_desc(d) for d in self.ddescs])
         self._tw = self._table(tdesc, tw)
@@ -179,6 +181,14 @@ class MetaSD:
                                     self.kv_target.data_ptr(), dkv, self.workspace.data_ptr(), nbytes.value,
                                     _stream_ptr(self.stream)))
         self._h = h
+        for k, fc in (heads or {}).items():
+            want = torch.bfloat16 if tdesc["dtype"] == 1 else torch.float32
+            assert fc.dtype == want and tuple(fc.shape) == (tdesc["d_model"], 2 * tdesc["d_model"])
+            t = fc.to(self.device).contiguous()
+            if tdesc["dtype"] == 1:
+                t = pack_weight(t)
+            self._keep.append(t)
+            _check(self.L.metasd_set_drafter_head(self._h, int(k), t.data_ptr()), self._h)
 
     # ---- construction helpers
     def _prepare(self, desc, index, w):
@@ -295,12 +305,14 @@ class MetaSD:
         """View of an internal device buffer: 'P' [gamma_max+1, V], 'Q' [gamma_max, V], 'hist' [max_ctx], 'bd' [gamma_max],
         'draft' [gamma_max].  batch > 1: pass the gamma of the last round; the views are P [batch, gamma+1, V],
         Q [batch, gamma, V], hist [batch, max_ctx], bd / draft [batch, gamma]."""
-        code = {"P": 0, "Q": 1, "hist": 2, "bd": 3, "draft": 4}[what]
+        code = {"P": 0, "Q": 1, "hist": 2, "bd": 3, "draft": 4, "feat": 5}[what]
         p, n = C.c_void_p(), C.c_size_t(0)
         _check(self.L.metasd_peek(self._h, code, C.byref(p), C.byref(n)), self._h)
         off = p.value - self.workspace.data_ptr()
         raw = self.workspace[off: off + n.value]
         V = self.tdesc["vocab"]
+        if what == "feat":
+            return raw.view(torch.float32).view(self.max_ctx, self.tdesc["d_model"])
         if self.batch > 1:
             B, g = self.batch, gamma
             if what == "hist":

@@ -150,6 +150,33 @@ __device__ __forceinline__ void store_split1(float* base, size_t n, size_t at, f
 }
 
 // ------------------------------------------------------------------------------------------
+// Drafter heads on the target's hidden states (the white-box drafters of the paper's Sec. 4): the input of the head's first
+// projection, x[r] = [embedding row h[r] ; feature of the position before row r], 2 d values per row.  The feature comes
+// from the table of the target's features (feat[p] = residual stream after the target's last layer at position p; row r at
+// position pos0 + r takes feat[pos0 + r - 1], zeros for position 0) or, est != nullptr, from the head's own estimate of
+// it (one row: the draft steps after the first).  split != 0: written as two bf16 arrays.     grid (m), block 256
+__global__ void feat_cat_kernel(const float* __restrict__ h, const float* __restrict__ feat, const float* __restrict__ est, int pos0, int d,
+                                float* __restrict__ out, int split) {
+    const int r = blockIdx.x;
+    const int p = pos0 + r - 1;
+    const float* f = est ? est : feat + (size_t)(p < 0 ? 0 : p) * d;
+    for (int i = threadIdx.x * 4; i < 2 * d; i += blockDim.x * 4) {
+        float4 v;
+        if (i < d) v = *reinterpret_cast<const float4*>(h + (size_t)r * d + i);
+        else if (!est && p < 0) v = make_float4(0.f, 0.f, 0.f, 0.f);
+        else v = *reinterpret_cast<const float4*>(f + (i - d));
+        if (split) store_split4(out, (size_t)gridDim.x * 2 * d, (size_t)r * 2 * d + i, v);
+        else *reinterpret_cast<float4*>(out + (size_t)r * 2 * d + i) = v;
+    }
+}
+
+// dst[0 .. n4) = src[0 .. n4) (16-byte pieces): rows of the residual stream into the feature table / the estimate
+__global__ void copy_f4_kernel(const float4* __restrict__ src, float4* __restrict__ dst, unsigned n4) {
+    const unsigned i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n4) dst[i] = src[i];
+}
+
+// ------------------------------------------------------------------------------------------
 // residual add of split-K partial sums + RMSNorm:      grid (m), block 1024, d % 4 == 0
 //   h[r] += sum_s part[s][r]   (skipped when nsplit == 0)
 //   xn[r] = h[r] / sqrt(mean(h[r]^2) + eps) * gain          (fp32; T is the type of the gain)

@@ -59,6 +59,8 @@ struct Model {
     int kv_layers = 0;       // layers of the cache buffer behind kv (the target's count for a shared cache): sequence stride
     int hd = 0;
     std::vector<int> kvl;   // positions valid in the KV cache, per sequence
+    bool head = false;      // a drafter head on the target's hidden states (metasd_set_drafter_head): see forward_rows
+    const void* fc = nullptr;   // its input projection W_fc [d][2 d]
     bool stream = false;    // a drafter with a streaming cache (cfg.stream_sink, cfg.stream_window): see forward()
     int tail = 0;           // streaming cache: first position of the contiguous tail (what lies between the sinks and it was skipped)
     const void** d_table = nullptr;   // device copy of w
@@ -155,7 +157,7 @@ struct GridBar { int abort; int pad[3]; };
 
 // Workspace layout shared by metasd_workspace_bytes and metasd_create.
 struct Layout {
-    size_t hist, h, h2, xn, part, part2, gx, ssq, inv, q, ao, act, apart, rope, P, Q, cand, bd, res, draft, tstep, bar, xchg, tables, table_stride, total;
+    size_t hist, h, h2, xn, part, part2, gx, ssq, inv, q, ao, act, apart, rope, P, Q, cand, bd, res, draft, tstep, feat, fest, bar, xchg, tables, table_stride, total;
 };
 
 Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const metasd_model_desc* dr) {
@@ -174,6 +176,9 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
         const int hd = d.d_model / d.n_heads;
         const int ns[5] = {(d.n_heads + 2 * d.n_kv_heads) * hd, d.d_model, (d.act == METASD_SWIGLU ? 2 : 1) * d.d_ffn, d.d_model, d.vocab};
         const int ks[5] = {d.d_model, d.d_model, d.d_model, d.d_ffn, d.d_model};
+        if (c.feature_heads && d.dtype == METASD_BF16)   // a drafter head's input projection: N = d, K = 2 d
+            partmax = std::max(partmax, (size_t)std::max(choose_split(MAX_ROWS, d.d_model / 16, 2 * d.d_model / 32).ksplit, ks_cap()) *
+                                            MAX_ROWS * d.d_model * sizeof(float));
         for (int i = 0; i < 5; ++i) {
             int ksplit = 1;
             if (d.dtype == METASD_BF16) ksplit = choose_split(MAX_ROWS, ns[i] / 16, ks[i] / 32).ksplit;
@@ -214,8 +219,11 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     L.res = take(std::max<size_t>(128, B * 12));                   // batch 1: also the path of a tree round (2 + 15 words)
     L.draft = take(std::max<size_t>(64, B * (c.gamma_max + 1) * 4)); // chain: gamma tokens per sequence; tree: one per node
     L.tstep = take(TREE_MAX * sizeof(int2));                       // sampled tree rounds: the decision of every node
-    L.bar = take(sizeof(GridBar));
+    L.bar = take(sizeof(GridBar));                                 // bd .. bar: the span read back after every round, kept small
     L.xchg = take(B * (c.gamma_max + 1) * AS_XCHG_BYTES);
+    // drafter heads: the target's feature of every processed position, and the head's estimate of the latest one
+    L.feat = take(c.feature_heads ? (size_t)c.max_ctx * t.d_model * 4 : 0);
+    L.fest = take(c.feature_heads ? (size_t)t.d_model * 4 : 0);
     int lmax = t.n_layers;
     for (int k = 0; k < c.K; ++k) lmax = std::max(lmax, dr[k].n_layers);
     L.table_stride = align_up((size_t)(1 + PER_LAYER * lmax + 2) * sizeof(void*));
@@ -416,6 +424,7 @@ struct metasd_ctx {
     bool fuse_small = true;          // short blocks of narrow bf16 models use the GEMMs with fused prologues (METASD_FUSE_SMALL=0: off)
     int n_cu = 0;
     const TreeBlk* tree = nullptr;   // set while a block of draft-tree nodes is being launched (positions and mask of its rows)
+    bool head_est = false;           // a drafter head's forward takes its own estimate (d_fest) as the feature input (draft steps after the first)
     TreeShape tshape{};              // the tree of the running round (metasd_draft_tree)
     int tdepth[TREE_MAX] = {};       // depth of every node, tlevel[d] = first node of depth d (tlevel[max depth + 1] = n)
     int tlevel[TREE_MAX + 2] = {};
@@ -464,6 +473,8 @@ struct metasd_ctx {
     float* d_Q() const { return reinterpret_cast<float*>(ws + lay.Q); }
     int2* d_cand() const { return reinterpret_cast<int2*>(ws + lay.cand); }
     int2* d_tstep() const { return reinterpret_cast<int2*>(ws + lay.tstep); }
+    float* d_feat() const { return reinterpret_cast<float*>(ws + lay.feat); }
+    float* d_fest() const { return reinterpret_cast<float*>(ws + lay.fest); }
     double* d_bd() const { return reinterpret_cast<double*>(ws + lay.bd); }
     int32_t* d_res() const { return reinterpret_cast<int32_t*>(ws + lay.res); }
     int32_t* d_draft() const { return reinterpret_cast<int32_t*>(ws + lay.draft); }
@@ -712,6 +723,15 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
     hipLaunchKernelGGL(embed_rope_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, h, pos0, hd, d.rope_theta,
                        c->d_rope(), c->tree ? *c->tree : TreeBlk{});
     LAUNCH_CHECK(c, "embed + rope table");
+    if (M.head) {
+        // a drafter head starts from W_fc . [embedding ; feature of the position before] instead of the embedding
+        float* cat = (float*)c->d_act();
+        hipLaunchKernelGGL(feat_cat_kernel, dim3(m), dim3(256), 0, st, (const float*)h, (const float*)c->d_feat(),
+                           c->head_est ? (const float*)c->d_fest() : (const float*)nullptr, pos0, D, cat, split);
+        LAUNCH_CHECK(c, "feat_cat");
+        int dummy;
+        if ((rc = gemm<T>(c, cat, 2 * D, m, 2 * D, M.fc, D, nullptr, 0, nullptr, 0, h, &dummy, (size_t)m * 2 * D))) return rc;
+    }
     for (int L = 0; L < d.n_layers; ++L) {
         // h += previous FFN output (split partials); xn = norm(h)
         hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.layer_w(L, 0),
@@ -742,10 +762,12 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         LAUNCH_CHECK(c, "ffn_act");
         if ((rc = gemm<T>(c, c->d_act(), F, m, F, M.layer_w(L, 8), D, nullptr, 0, nullptr, 0, nullptr, &ns, (size_t)m * F))) return rc;
     }
-    if (logits) {
+    if (logits || c->cfg.feature_heads) {          // with drafter heads the finished residual rows are wanted in any case
         hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, ns, (size_t)m * D, D, (const T*)M.final_norm(),
                            d.rms_eps, xn, split);
         LAUNCH_CHECK(c, "addnorm");
+    }
+    if (logits) {
         int dummy;
         const void* xrow = split ? (const void*)((const bf16_t*)xn + (size_t)first_row * D) : (const void*)(xn + (size_t)first_row * D);
         if ((rc = gemm<T>(c, xrow, D, m - first_row, D, M.lm_head(), V, nullptr, 0, nullptr, 0, logits, &dummy, (size_t)m * D)))
@@ -927,11 +949,27 @@ int forward_blocks(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool
         float* lg = (last && logits) ? logits : nullptr;
         const int first_row = want_all ? 0 : m - 1;
         int rc;
+        const bool is_target = &M == &c->target;
+        // the short-block path never writes the finished residual rows: not for the target when its features are wanted
+        const bool fused = c->fuse_small && fused_small_ok(M, m) && !(is_target && c->cfg.feature_heads);
         if (M.d.dtype != METASD_BF16) rc = forward_rows<float>(c, M, pos0 + done, m, lg, first_row);
-        else if (c->fuse_small && fused_small_ok(M, m)) rc = forward_rows_fused(c, M, pos0 + done, m, lg, first_row);
+        else if (M.head) rc = forward_rows<bf16_t>(c, M, pos0 + done, m, lg, first_row);     // the step-by-step path carries the head's input projection
+        else if (fused) rc = forward_rows_fused(c, M, pos0 + done, m, lg, first_row);
         else if (c->gemm_reduce) rc = forward_rows_residual(c, M, pos0 + done, m, lg, first_row);
         else rc = forward_rows<bf16_t>(c, M, pos0 + done, m, lg, first_row);
         if (rc) return rc;
+        const int D = M.d.d_model;
+        if (is_target && c->cfg.feature_heads) {        // the target's features of the block's positions
+            const unsigned n4 = (unsigned)((size_t)m * D / 4);
+            hipLaunchKernelGGL(copy_f4_kernel, dim3((n4 + 255) / 256), dim3(256), 0, c->stream, (const float4*)c->d_h(),
+                               (float4*)(c->d_feat() + (size_t)(pos0 + done) * D), n4);
+            LAUNCH_CHECK(c, "feature rows");
+        }
+        if (M.head && last) {                            // the head's estimate of the last row's feature: input of its next step
+            hipLaunchKernelGGL(copy_f4_kernel, dim3((D / 4 + 255) / 256), dim3(256), 0, c->stream,
+                               (const float4*)(c->d_h() + (size_t)(m - 1) * D), (float4*)c->d_fest(), (unsigned)(D / 4));
+            LAUNCH_CHECK(c, "feature estimate");
+        }
         done += m;
     }
     M.kvl[0] = pos0 + n;
@@ -1559,6 +1597,8 @@ static int check_config(const metasd_config* cfg, const metasd_model_desc* targe
     }
     if (cfg->stream_window < 0 || cfg->stream_sink < 0) return fail_global(METASD_E_INVALID, "stream_sink and stream_window must be >= 0");
     if (cfg->stream_window > 0 && cfg->batch > 1) return fail_global(METASD_E_INVALID, "streaming drafter caches: contexts with one sequence only");
+    if (cfg->feature_heads != 0 && cfg->feature_heads != 1) return fail_global(METASD_E_INVALID, "feature_heads must be 0 or 1");
+    if (cfg->feature_heads && cfg->batch > 1) return fail_global(METASD_E_INVALID, "drafter heads on the target's hidden states: contexts with one sequence only");
     char buf[256];
     if (const char* e = check_model(*target, "target", buf, sizeof buf)) return fail_global(METASD_E_INVALID, "%s", e);
     for (int k = 0; k < cfg->K; ++k) {
@@ -1789,6 +1829,22 @@ int32_t metasd_bandit_state(const metasd_ctx* c, int32_t seq, double* mu, int32_
 
 // ---- round
 
+int32_t metasd_set_drafter_head(metasd_ctx* c, int32_t k, const void* w_fc) {
+    if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
+    if (!c->cfg.feature_heads) return c->fail(METASD_E_INVALID, "set_drafter_head: the context was created without metasd_config.feature_heads");
+    if (k < 0 || k >= c->cfg.K || !w_fc) return c->fail(METASD_E_INVALID, "set_drafter_head: bad drafter index or NULL weight");
+    if (c->phase != PH_NONE) return c->fail(METASD_E_ORDER, "set_drafter_head: call it before the first metasd_set_context");
+    Model& D = c->drafters[k];
+    const metasd_model_desc& t = c->target.d;
+    if (D.d.d_model != t.d_model || D.d.dtype != t.dtype) return c->fail(METASD_E_INVALID, "set_drafter_head: the head must have the target's width and dtype");
+    if (D.shared_kv) return c->fail(METASD_E_INVALID, "set_drafter_head: a head keeps a cache of its own");
+    if (t.d_ffn < t.d_model) return c->fail(METASD_E_INVALID, "set_drafter_head: needs d_ffn >= d_model (the input block is staged in the FFN buffer)");
+    D.head = true;
+    D.fc = w_fc;
+    D.stream = false;
+    return METASD_OK;
+}
+
 int32_t metasd_draft(metasd_ctx* c, const int32_t* k, int32_t gamma) {
     if (!c) return fail_global(METASD_E_INVALID, "NULL ctx");
     if (!k || k[0] < 0 || k[0] >= c->cfg.K) return c->fail(METASD_E_INVALID, "draft: drafter index out of range");
@@ -1818,7 +1874,11 @@ int32_t metasd_draft(metasd_ctx* c, const int32_t* k, int32_t gamma) {
             if (start > have) D.tail = start;
             if (!rc && start < l) rc = forward(c, D, start, l - start, Qj, false);
         } else if (j == 0) rc = forward(c, D, D.kvl[0], l - D.kvl[0], Qj, false);   // catch-up, ends with the last committed token
-        else rc = forward(c, D, l + j - 1, 1, Qj, false);
+        else {
+            c->head_est = D.head;                      // a drafter head goes on from its own estimate of the last feature
+            rc = forward(c, D, l + j - 1, 1, Qj, false);
+            c->head_est = false;
+        }
         if (rc) return rc;
         if (launch_sample(c->stream, Qj, 1, V, T, c->cfg.seed, (uint32_t)c->sq[0].round, (uint32_t)j, 0u, c->d_hist() + l + j, 1,
                           c->d_draft() + j))
@@ -1880,6 +1940,9 @@ int32_t metasd_accept(metasd_ctx* c, int32_t gamma, int32_t* n_acc_out, int32_t*
     c->sq[0].l = l + n + 1;
     c->target.kvl[0] = l + n;
     c->drafters[c->sq[0].cur_k].kvl[0] = std::min(l + n, l + gamma - 1);
+    // a drafter head keeps nothing it computed from estimated features: it will re-read the committed tokens of this round with
+    // the target's own features (which the verification pass has just left in the feature table)
+    if (c->drafters[c->sq[0].cur_k].head) c->drafters[c->sq[0].cur_k].kvl[0] = l;
     c->sq[0].round += 1;
     sync_shared_kv(c);
     c->phase = PH_READY;
@@ -1902,6 +1965,7 @@ int32_t metasd_draft_tree(metasd_ctx* c, int32_t k, const metasd_tree* tree) {
     if (c->cfg.batch != 1) return c->fail(METASD_E_INVALID, "draft_tree: contexts with one sequence only");
     if (k < 0 || k >= c->cfg.K || !tree) return c->fail(METASD_E_INVALID, "draft_tree: bad drafter index or NULL tree");
     if (c->drafters[k].stream) return c->fail(METASD_E_INVALID, "draft_tree: drafters with a streaming cache draft chains only");
+    if (c->drafters[k].head) return c->fail(METASD_E_INVALID, "draft_tree: drafter heads on the target's hidden states draft chains only");
     if (c->phase != PH_READY) return c->fail(METASD_E_ORDER, "draft_tree: call set_context first / finish the previous round");
     const int n = tree->n;
     if (n < 2 || n > TREE_MAX || n > c->cfg.gamma_max + 1) return c->fail(METASD_E_INVALID, "draft_tree: tree of %d nodes; 2 .. min(%d, gamma_max + 1) supported", n, TREE_MAX);
@@ -2188,6 +2252,9 @@ int32_t metasd_peek(metasd_ctx* c, int32_t what, void** dev_ptr_out, size_t* byt
         case METASD_PEEK_Q: *dev_ptr_out = c->d_Q(); *bytes_out = (size_t)c->cfg.batch * c->cfg.gamma_max * V * 4; break;
         case METASD_PEEK_HIST: *dev_ptr_out = c->d_hist(); *bytes_out = (size_t)c->cfg.batch * c->cfg.max_ctx * 4; break;
         case METASD_PEEK_BD: *dev_ptr_out = c->d_bd(); *bytes_out = (size_t)c->cfg.batch * c->cfg.gamma_max * 8; break;
+        case METASD_PEEK_FEAT:
+            if (!c->cfg.feature_heads) return c->fail(METASD_E_INVALID, "peek: this context keeps no features (metasd_config.feature_heads)");
+            *dev_ptr_out = c->d_feat(); *bytes_out = (size_t)c->cfg.max_ctx * c->target.d.d_model * 4; break;
         case METASD_PEEK_DRAFT: *dev_ptr_out = c->d_draft(); *bytes_out = (size_t)c->cfg.batch * (c->cfg.gamma_max + 1) * 4; break;
         default: return c->fail(METASD_E_INVALID, "peek: unknown buffer %d", what);
     }

@@ -28,7 +28,9 @@ def top2_gap(x: np.ndarray) -> float:
 
 
 class LockStep:
-    def __init__(self, gpu, target, drafters, prompt, gamma, T, seed, beta, logit_tol, kv_prefilled=False, reward="BE", seq=0):
+    def __init__(self, gpu, target, drafters, prompt, gamma, T, seed, beta, logit_tol, kv_prefilled=False, reward="BE", seq=0, feat_tol=None,
+                 feat_prefill=None):
+        self.feat_tol = logit_tol if feat_tol is None else feat_tol
         self.gpu, self.target, self.drafters = gpu, target, drafters
         self.seq = seq                                   # sequence of a batched context (its Philox sequence id)
         self.gamma, self.T, self.seed, self.tol, self.reward = gamma, T, seed, logit_tol, reward
@@ -41,7 +43,15 @@ class LockStep:
         self.bandit = oracle.Ucb(len(drafters), beta)
         self.stats = dict(rounds=0, max_dq=0.0, max_dp=0.0, ties_shared=0, ties_own=0, mismatch_own=0, n_acc=[], arms=[],
                           alpha=[])
-        if not kv_prefilled and self.l > 1:
+        # drafter heads on the target's hidden states: the table of the target's features, one row per cached position
+        self.feat = None
+        if any(getattr(D, "feature_head", False) for D in drafters):
+            self.feat = np.zeros((target.max_ctx, target.desc["d_model"]), np.float32)
+            if kv_prefilled:                             # synthetic prefix: its features are given like its K/V
+                self.feat[: self.l - 1] = feat_prefill
+            elif self.l > 1:
+                _, self.feat[: self.l - 1] = target.forward_hidden(prompt[: self.l - 1], 0, None)
+        elif not kv_prefilled and self.l > 1:
             target.forward(prompt[: self.l - 1], 0, None)
 
     def select(self, force_k=None):
@@ -76,7 +86,15 @@ class LockStep:
             self.c[k] = l - 1
         Qo = np.empty((gamma, V), np.float32)
         stream = getattr(D, "stream", None)
-        if stream is not None:                           # sinks not seen yet + the last `window` committed tokens
+        head = getattr(D, "feature_head", False)
+        if head:                                         # unseen committed tokens, each with the true feature before it
+            c = self.c[k]
+            feats = np.zeros((l - c, self.feat.shape[1]), np.float32)
+            lo = max(c, 1)
+            feats[lo - c:] = self.feat[lo - 1: l - 1]
+            Qo[0], hid = D.forward_hidden(self.hist[c: l], c, "last", feats=feats)
+            f_est = hid[-1]
+        elif stream is not None:                         # sinks not seen yet + the last `window` committed tokens
             from oracle.loop import stream_catch_up, stream_forward
             Qo[0], self.a[k] = stream_catch_up(D, self.hist, self.c[k], l, self.a[k])
         else:
@@ -91,7 +109,10 @@ class LockStep:
         for j in range(gamma):
             if j > 0:
                 self.hist[l + j - 1] = d[j - 1]
-                if stream is not None:
+                if head:                                 # the head's own estimate stands in for the unknown feature
+                    Qo[j], hid = D.forward_hidden(self.hist[l + j - 1: l + j], l + j - 1, "last", feats=f_est[None])
+                    f_est = hid[-1]
+                elif stream is not None:
                     Qo[j] = stream_forward(D, self.hist, l + j - 1, l + j, self.a[k])
                 else:
                     Qo[j] = D.forward(self.hist[l + j - 1: l + j], l + j - 1, "last")
@@ -102,7 +123,10 @@ class LockStep:
                     assert tie, f"round {t} draft {j}: oracle token {tj} vs GPU {d[j]} (margin {mg})"
                 st["ties_own" if tie else "mismatch_own"] += 1
         self.hist[l + gamma - 1] = d[gamma - 1]
-        Po = self.target.forward(self.hist[l - 1: l + gamma], l - 1, "all")
+        if self.feat is not None:
+            Po, Ho = self.target.forward_hidden(self.hist[l - 1: l + gamma], l - 1, "all")
+        else:
+            Po = self.target.forward(self.hist[l - 1: l + gamma], l - 1, "all")
         dq, dp = float(np.abs(Qo - Qg).max()), float(np.abs(Po - Pg).max())
         st["max_dq"], st["max_dp"] = max(st["max_dq"], dq), max(st["max_dp"], dp)
         assert dq <= self.tol and dp <= self.tol, f"round {t}: logits differ by {dq} (drafter) / {dp} (target) > {self.tol}"
@@ -143,6 +167,14 @@ class LockStep:
         self.hist[l + n] = tok_gpu
         self.l = l + n + 1
         self.c[k] = min(l + n, l + gamma - 1)
+        if self.feat is not None:                        # features of the committed rows; estimated-feature entries go
+            self.feat[l - 1: l + n] = Ho[: n + 1]
+            fg = g.peek("feat")[: l + n].cpu().numpy()
+            df = float(np.abs(fg - self.feat[: l + n]).max())
+            st["max_df"] = max(st.get("max_df", 0.0), df)
+            assert df <= self.feat_tol, f"round {t}: feature table differs by {df} > {self.feat_tol}"
+        if head:
+            self.c[k] = l
         for i, Di in enumerate(self.drafters):
             if getattr(Di, "shares_kv", False):
                 self.c[i] = self.l - 1
