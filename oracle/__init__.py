@@ -82,6 +82,9 @@ def lib():
         L.om_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int]
         L.om_forward_ex.restype = C.c_int
         L.om_forward_ex.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.om_forward_rows_ex.restype = C.c_int
+        L.om_forward_rows_ex.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p]
         L.om_forward_rows.restype = C.c_int
         L.om_forward_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.om_philox.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p]
@@ -235,6 +238,29 @@ class Model:
         if rc != 0:
             raise ValueError("om_forward_rows: bad arguments")
         return out
+
+    def forward_rows_hidden(self, tokens, slots, positions, allow, feats=None):
+        """forward_rows that also returns the residual stream after the last layer of every row; a drafter head (fc given
+        at construction) takes feats [m, D], the feature input of every row.  Returns (logits [m, V], hidden [m, D])."""
+        tok = np.ascontiguousarray(tokens, np.int32)
+        sl = np.ascontiguousarray(slots, np.int32)
+        ps = np.ascontiguousarray(positions, np.int32)
+        al = np.ascontiguousarray(allow, np.uint8)
+        m, D = tok.shape[0], self.desc["d_model"]
+        assert sl.shape == (m,) and ps.shape == (m,) and al.shape == (m, self.max_ctx)
+        out = np.empty((m, self.desc["vocab"]), np.float32)
+        hid = np.empty((m, D), np.float32)
+        if self.feature_head:
+            f = np.ascontiguousarray(feats, np.float32)
+            assert f.shape == (m, D)
+            fcp, fp = _ptr(self.fc), _ptr(f)
+        else:
+            assert feats is None
+            fcp, fp = None, None
+        rc = lib().om_forward_rows_ex(self._h, _ptr(tok), m, _ptr(sl), _ptr(ps), _ptr(al), _ptr(out), fcp, fp, _ptr(hid))
+        if rc != 0:
+            raise ValueError("om_forward_rows_ex: bad arguments")
+        return out, hid
 
 
 # ------------------------------------------------------------------ randomness

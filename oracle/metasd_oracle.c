@@ -344,8 +344,18 @@ int om_forward_ex(om_model *M, const int32_t *tokens, int m, int pos0, float *lo
  * of the same call.  Everything else is om_forward's arithmetic, step for step; logits [m][V] (or NULL).
  * With slot[r] = pos[r] = pos0 + r and allow = (p <= pos0 + r) this IS om_forward.
  */
+int om_forward_rows_ex(om_model *M, const int32_t *tokens, int m, const int32_t *slot, const int32_t *pos,
+                       const uint8_t *allow, float *logits, const void *fc, const float *feat_in, float *hidden_out);
+
 int om_forward_rows(om_model *M, const int32_t *tokens, int m, const int32_t *slot, const int32_t *pos,
                     const uint8_t *allow, float *logits) {
+    return om_forward_rows_ex(M, tokens, m, slot, pos, allow, logits, NULL, NULL, NULL);
+}
+
+/* om_forward_rows with om_forward_ex's two optional additions (a drafter head's rows start from
+ * W_fc . [embedding ; feat_in[r]]; hidden_out receives the residual stream after the last layer of every row). */
+int om_forward_rows_ex(om_model *M, const int32_t *tokens, int m, const int32_t *slot, const int32_t *pos,
+                       const uint8_t *allow, float *logits, const void *fc, const float *feat_in, float *hidden_out) {
     const om_desc *d = &M->d;
     const int D = d->d_model, H = d->n_heads, KH = d->n_kv_heads, hd = M->hd, F = d->d_ffn, V = d->vocab;
     const int DQ = H * hd, DKV = KH * hd;
@@ -366,6 +376,16 @@ int om_forward_rows(om_model *M, const int32_t *tokens, int m, const int32_t *sl
     const void *embed = M->w[0];
     for (int r = 0; r < m; ++r)
         for (int i = 0; i < D; ++i) h[(size_t)r * D + i] = (float)wget(d, embed, (size_t)tokens[r] * D + i);
+    if (fc) {
+        /* h = W_fc . [embedding ; feature] */
+        float *cat = (float *)malloc(sizeof(float) * (size_t)m * 2 * D);
+        for (int r = 0; r < m; ++r) {
+            memcpy(cat + (size_t)r * 2 * D, h + (size_t)r * D, sizeof(float) * (size_t)D);
+            memcpy(cat + (size_t)r * 2 * D + D, feat_in + (size_t)r * D, sizeof(float) * (size_t)D);
+        }
+        matmul(d, cat, m, 2 * D, fc, D, h);
+        free(cat);
+    }
 
     for (int L = 0; L < d->n_layers; ++L) {
         const void *const *w = M->w + 1 + OM_PER_LAYER * L;
@@ -431,6 +451,7 @@ int om_forward_rows(om_model *M, const int32_t *tokens, int m, const int32_t *sl
         matmul(d, u, m, F, w[8], D, y);
         for (size_t i = 0; i < (size_t)m * D; ++i) h[i] = (float)((double)h[i] + (double)y[i]);
     }
+    if (hidden_out) memcpy(hidden_out, h, sizeof(float) * (size_t)m * D);
     if (logits) {
         rmsnorm(d, h, m, D, M->w[1 + OM_PER_LAYER * d->n_layers], a);
         matmul(d, a, m, D, M->w[2 + OM_PER_LAYER * d->n_layers], V, logits);

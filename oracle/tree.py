@@ -164,10 +164,25 @@ def tree_round(target, drafter, k: int, st, tree: Tree, tokens=None, outcome=Non
     draw_margin = np.full(tree.n, np.inf)
     if getattr(drafter, "shares_kv", False):
         st.c[k] = base
+    # a drafter head on the target's hidden states: the backlog takes the target's own features, a node below the root the
+    # head's estimate at its parent (the reading is stated in oracle/loop.py)
+    head = getattr(drafter, "feature_head", False)
+    est = np.zeros((tree.n, target.desc["d_model"]), np.float32) if head else None
     for d in range(tree.max_depth):
         nodes = tree.level(d)
-        if d == 0:
+        if d == 0 and head:
+            c = st.c[k]
+            feats = np.zeros((l - c, est.shape[1]), np.float32)
+            lo = max(c, 1)
+            feats[lo - c:] = st.feat[lo - 1: l - 1]
+            Q[0], hid = drafter.forward_hidden(st.hist[c: l], c, "last", feats=feats)
+            est[0] = hid[-1]
+        elif d == 0:
             Q[0] = drafter.forward(st.hist[st.c[k]: l], st.c[k], "last")          # the committed backlog, ending with the root
+        elif head:
+            Q[nodes], est[nodes] = drafter.forward_rows_hidden(tok[nodes], [base + i for i in nodes], [base + d] * len(nodes),
+                                                               _allow(drafter, tree, base, nodes),
+                                                               feats=est[[tree.parent[i] for i in nodes]])
         else:
             Q[nodes] = drafter.forward_rows(tok[nodes], [base + i for i in nodes], [base + d] * len(nodes),
                                             _allow(drafter, tree, base, nodes))
@@ -187,7 +202,11 @@ def tree_round(target, drafter, k: int, st, tree: Tree, tokens=None, outcome=Non
                     tok[j] = own_tok[j] if tokens is None else tokens[j]
     # verify: every node in one pass
     nodes = list(range(tree.n))
-    P = target.forward_rows(tok, [base + i for i in nodes], [base + tree.depth[i] for i in nodes], _allow(target, tree, base, nodes))
+    if getattr(st, "feat", None) is not None:
+        P, H = target.forward_rows_hidden(tok, [base + i for i in nodes], [base + tree.depth[i] for i in nodes],
+                                          _allow(target, tree, base, nodes))
+    else:
+        P = target.forward_rows(tok, [base + i for i in nodes], [base + tree.depth[i] for i in nodes], _allow(target, tree, base, nodes))
     amax = [int(np.argmax(P[i])) for i in nodes]        # numpy's argmax: first maximum = lowest token on ties
     walk = None
     if T > 0.0:
@@ -212,12 +231,18 @@ def tree_round(target, drafter, k: int, st, tree: Tree, tokens=None, outcome=Non
         path, token = list(outcome[0]), int(outcome[1])
     n = len(path)
     move_accepted(target, base, path)
-    if not getattr(drafter, "shares_kv", False):
+    if not getattr(drafter, "shares_kv", False) and not head:
         move_accepted(drafter, base, path[: tree.max_depth - 1])
     st.hist[l: l + n] = tok[path]
     st.hist[l + n] = token
     st.l = l + n + 1
     st.c[k] = st.l - 1 if getattr(drafter, "shares_kv", False) else min(l + n, l + tree.max_depth - 1)
+    if getattr(st, "feat", None) is not None:            # the target's features of the committed rows: the root and the accepted nodes
+        st.feat[base] = H[0]
+        for j, node in enumerate(path):
+            st.feat[base + 1 + j] = H[node]
+    if head:
+        st.c[k] = l                                      # what it computed from estimated features is not kept
     out = dict(k=k, round=st.t, l_before=l, tok=tok, own_tok=own_tok, P=P, Q=Q, amax=amax, path=path, n_acc=n, token=token,
                own_path=own[0], own_token=own[1], walk=walk, draw_margin=draw_margin)
     st.t += 1
@@ -234,7 +259,11 @@ def generate_tree(target, drafters, prompt, n_new: int, tree: Tree, beta: float,
     hist = np.zeros(target.max_ctx, np.int32)
     hist[:l0] = prompt
     st = SdState(hist=hist, l=l0, c=[0] * len(drafters))
-    if l0 > 1:
+    if any(getattr(dr, "feature_head", False) for dr in drafters):
+        st.feat = np.zeros((target.max_ctx, target.desc["d_model"]), np.float32)
+        if l0 > 1:
+            _, st.feat[: l0 - 1] = target.forward_hidden(prompt[: l0 - 1], 0, None)
+    elif l0 > 1:
         target.forward(prompt[: l0 - 1], 0, None)
     bandit = Ucb(len(drafters), beta)
     rounds = []

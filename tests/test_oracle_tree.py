@@ -239,3 +239,95 @@ def test_sampled_tree_special_cases():
         want2 /= want2.sum()
         assert abs(na / m - q[a]) < 4.5 * np.sqrt(q[a] * (1 - q[a]) / m)
         assert (np.abs(cnt[a] / na - want2) < 4.5 * np.sqrt(want2 * (1 - want2) / na) + 1e-12).all()
+
+
+# ---------------------------------------------------------------- drafter heads on the target's hidden states in tree rounds
+
+def _head_models(cfg, eps):
+    """Target of config1 with three heads over its first layer; head k weighs the feature input with eps * k (k = 0 ignores it)."""
+    T = oracle.Model(cfg["target"][0], cfg["tw_np"], cfg["max_ctx"])
+    D = []
+    for k in range(3):
+        dd, dw, fc = W.feature_head_drafter(cfg["target"][0], cfg["target"][1], 0, eps * k, 300 + k)
+        D.append(oracle.Model(dd, W.to_numpy(dw), cfg["max_ctx"], fc=W.to_numpy([fc])[0]))
+    return T, D
+
+
+def test_head_nodes_take_the_estimate_of_their_parent(c1):
+    """Every node of a branching tree filled by a head gets the logits of that head run as a chain over the node's own
+    root-to-node path in a fresh model - true features for the committed rows, then each step fed the estimate of the
+    step before: a node fed a sibling's or an uncle's estimate, or the true feature, fails."""
+    t = Tree(**W.draft_tree("wide"))
+    prompt = c1["prompt"]
+    T, D = _head_models(c1, 0.05)
+    hd = D[2]
+    l = 12
+    hist = np.zeros(T.max_ctx, np.int32)
+    hist[:l] = prompt[:l]
+    feat = np.zeros((T.max_ctx, T.desc["d_model"]), np.float32)
+    _, feat[: l - 1] = T.forward_hidden(prompt[: l - 1], 0, None)
+    st = oracle.SdState(hist=hist, l=l, c=[0, 0, 0], feat=feat.copy())
+    r = oracle.tree_round(T, hd, 2, st, t)
+    tok, Q = r["tok"], r["Q"]
+    fin = np.zeros((l, feat.shape[1]), np.float32)
+    fin[1:] = feat[: l - 1]
+    checked = 0
+    for i in range(t.n):
+        if not t.children(i):
+            continue                                     # logits exist for the nodes that have children
+        dd, dw, fc = W.feature_head_drafter(c1["target"][0], c1["target"][1], 0, 0.05 * 2, 302)
+        F = oracle.Model(dd, W.to_numpy(dw), c1["max_ctx"], fc=W.to_numpy([fc])[0])
+        q, hid = F.forward_hidden(hist[:l], 0, "last", feats=fin)
+        for a in t.anc[i][1:]:
+            q, hid = F.forward_hidden(tok[a: a + 1], l - 1 + t.depth[a], "last", feats=hid[-1:])
+        assert np.array_equal(q, Q[i]), i
+        checked += 1
+    assert checked >= 5
+
+
+def test_head_that_ignores_the_features_fills_the_tree_like_the_early_exit_drafter(c1):
+    """W_fc = [I | 0]: the head is the target's first layer under the target's norm and head, so its tree rounds are those
+    of that early-exit drafter - same node tokens, same paths - although it re-reads the last round's tokens every time."""
+    t = Tree(**W.draft_tree("wide"))
+    T, D = _head_models(c1, 0.0)
+    a = oracle.generate_tree(T, D, c1["prompt"], 40, t, c1["beta"], policy=lambda r: 0)
+    dd, dw, _ = W.feature_head_drafter(c1["target"][0], c1["target"][1], 0, 0.0, 300)
+    T2 = oracle.Model(c1["target"][0], c1["tw_np"], c1["max_ctx"])
+    E = oracle.Model(dd, W.to_numpy(dw), c1["max_ctx"])
+    b = oracle.generate_tree(T2, [E], c1["prompt"], 40, t, c1["beta"], policy=lambda r: 0)
+    assert np.array_equal(a["tokens"], b["tokens"])
+    for ra, rb in zip(a["rounds"], b["rounds"]):
+        assert np.array_equal(ra["tok"], rb["tok"]) and ra["path"] == rb["path"]
+        assert np.abs(ra["Q"] - rb["Q"]).max() < 1e-5
+
+
+@pytest.mark.parametrize("temp", [0.0, 1.0])
+def test_chain_tree_with_heads_is_the_chain_round_with_heads(c1, temp):
+    """A chain written as a tree: the head's estimate passes from node to child exactly as from draft step to draft step."""
+    t = Tree(**W.draft_tree("chain5"))
+    order = [2, 1, 1, 0, 2]
+    T, D = _head_models(c1, 0.05)
+    a = oracle.generate(T, D, c1["prompt"], 40, 5, temp, c1["seed"], c1["beta"], policy=lambda r: order[r % 5])
+    T, D = _head_models(c1, 0.05)
+    b = oracle.generate_tree(T, D, c1["prompt"], 40, t, c1["beta"], policy=lambda r: order[r % 5], T=temp, seed=c1["seed"])
+    assert np.array_equal(a["tokens"], b["tokens"])
+    for ra, rb in zip(a["rounds"], b["rounds"]):
+        assert np.array_equal(ra["d"], rb["tok"][1:]) and ra["n_acc"] == rb["n_acc"]
+    assert np.array_equal(a["state"].feat[: a["state"].l - 1], b["state"].feat[: b["state"].l - 1])
+
+
+def test_greedy_tree_rounds_with_heads_are_lossless_and_keep_the_targets_features(c1):
+    t = Tree(**W.draft_tree("wide"))
+    T0 = oracle.Model(c1["target"][0], c1["tw_np"], c1["max_ctx"])
+    ref = oracle.ar_decode(T0, c1["prompt"], c1["n_new"], T=0.0)
+    T, D = _head_models(c1, 0.05)
+    order = [0, 2, 1, 1, 2, 0, 0]
+    out = oracle.generate_tree(T, D, c1["prompt"], c1["n_new"], t, c1["beta"], policy=lambda r: order[r % len(order)])
+    assert np.array_equal(out["tokens"], ref)
+    st = out["state"]
+    F = oracle.Model(c1["target"][0], c1["tw_np"], c1["max_ctx"])
+    _, H = F.forward_hidden(st.hist[: st.l - 1], 0, None)
+    assert np.array_equal(st.feat[: st.l - 1], H)
+    for which in (0, 1):
+        assert np.array_equal(T.kv(which)[:, :, : st.l - 1], F.kv(which)[:, :, : st.l - 1])
+    assert sum(r["n_acc"] for r in out["rounds"]) > 0
