@@ -512,9 +512,10 @@ def bench_c4_tree(args):
 
 
 def bench_c4_heads(args):
-    """Side measurement: the C4 target (7B shape, KV context 2048, gamma = 5, T = 1) with K = 5 one-layer drafter heads on its
-    hidden states (the white-box setting of the paper's Sec. 4): head k runs the tensors of target layer k behind a W_fc of
-    its own; K/V prefix and feature prefix are seeded synthetic fills."""
+    """Side measurement: the C4 target (7B shape, KV context 2048, T = 1) with K = 5 one-layer drafter heads on its hidden states
+    (the white-box setting of the paper's Sec. 4): head k runs the tensors of target layer k behind a W_fc of its own; chain
+    rounds with gamma = 5 and rounds over the draft tree (--tree) in the same context; K/V prefix and feature prefix are seeded
+    synthetic fills."""
     import numpy as np
     import torch
     if not torch.cuda.is_available():
@@ -523,16 +524,21 @@ def bench_c4_heads(args):
     import workloads as W
     dev = "cuda:0"
     K_steps, Wm = args.steps, max(args.warmup, 5)
+    tree = W.draft_tree(args.tree)
+    n = len(tree["parent"])
+    depth = [0] * n
+    for i in range(1, n):
+        depth[i] = depth[tree["parent"][i]] + 1
+    D = max(depth)
     cfg = W.config4(device=dev, n_layers=args.layers, ctx=args.ctx, K=1)
-    gamma = cfg["gamma"]
-    cfg["max_ctx"] = args.ctx + (gamma + 1) * (K_steps + Wm + 16) + 16
+    cfg["max_ctx"] = args.ctx + (D + 1) * 2 * (K_steps + Wm + 8) + n + 16
     td, tw = cfg["target"]
     drafters, heads = [], {}
     for k in range(5):
         dd, dw, fc = W.feature_head_drafter(td, tw, k % td["n_layers"], 0.01 * W.c4_noise_scale(k, 0), 300 + k)
         drafters.append((dd, dw))
         heads[k] = fc
-    g = M.MetaSD((td, tw), drafters, gamma_max=gamma, max_ctx=cfg["max_ctx"], temperature=1.0, seed=cfg["seed"], ucb_beta=cfg["beta"],
+    g = M.MetaSD((td, tw), drafters, gamma_max=15, max_ctx=cfg["max_ctx"], temperature=1.0, seed=cfg["seed"], ucb_beta=cfg["beta"],
                  heads=heads)
     n0 = args.ctx - 1
     for i, (desc, kv) in enumerate([(td, g.kv_target)] + [(dd, g.kv_drafters[k]) for k, (dd, _) in enumerate(drafters)]):
@@ -543,41 +549,50 @@ def bench_c4_heads(args):
     gen = torch.Generator(device="cpu").manual_seed(77)
     g.peek("feat")[:n0] = (torch.randn((n0, td["d_model"]), generator=gen) * 0.05).to(dev)
 
-    def one_round():
+    def one_round(use_tree, ev=None):
         k = g.bandit_select()
-        g.draft(k, gamma)
-        g.verify(gamma)
-        na, tok, mask, bd = g.accept(gamma)
-        g.bandit_update(k, na, gamma, bd)
+        if ev: ev[0].record()
+        if use_tree:
+            g.draft_tree(k, tree["parent"], tree["rank"])
+            if ev: ev[1].record()
+            g.verify_tree()
+            if ev: ev[2].record()
+            na, tok, path = g.accept_tree()
+        else:
+            g.draft(k, D)
+            if ev: ev[1].record()
+            g.verify(D)
+            if ev: ev[2].record()
+            na, tok, mask, bd = g.accept(D)
+        if ev: ev[3].record()
+        g.bandit_update(k, na, D)
         return na
 
-    for _ in range(Wm):
-        one_round()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    accs = [one_round() for _ in range(K_steps)]
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t1
-    ph = []
-    for _ in range(8):
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-        k = g.bandit_select()
-        ev[0].record()
-        g.draft(k, gamma); ev[1].record()
-        g.verify(gamma); ev[2].record()
-        na, tok, mask, bd = g.accept(gamma)
-        ev[3].record()
-        g.bandit_update(k, na, gamma, bd)
+    res = {}
+    for name, use_tree in (("chain", False), ("tree", True)):
+        for _ in range(Wm):
+            one_round(use_tree)
         torch.cuda.synchronize()
-        ph.append([ev[j].elapsed_time(ev[j + 1]) for j in range(3)])
-    med = np.median(np.array(ph), axis=0)
-    detail = {"mean_n_acc": float(np.mean(accs)), "draft_ms": float(med[0]), "verify_ms": float(med[1]), "accept_ms": float(med[2])}
-    out = {"metric": "verified tokens/sec @1 GPU (7B-shape, drafter heads on hidden states)", "value": (sum(accs) + len(accs)) / dt,
-           "unit": "tokens/s", "n_gpus": 1, "steps": K_steps, "warmup": Wm, "ms_per_step": dt / K_steps * 1e3, "higher_is_better": True,
+        t1 = time.perf_counter()
+        accs = [one_round(use_tree) for _ in range(K_steps)]
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t1
+        ph = []
+        for _ in range(8):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            one_round(use_tree, ev)
+            torch.cuda.synchronize()
+            ph.append([ev[j].elapsed_time(ev[j + 1]) for j in range(3)])
+        med = np.median(np.array(ph), axis=0)
+        res[name] = {"tokens_per_s": (sum(accs) + len(accs)) / dt, "ms_per_round": dt / K_steps * 1e3, "mean_n_acc": float(np.mean(accs)),
+                     "draft_ms": float(med[0]), "verify_ms": float(med[1]), "accept_ms": float(med[2])}
+    out = {"metric": "verified tokens/sec @1 GPU (7B-shape, drafter heads on hidden states)", "value": res["chain"]["tokens_per_s"],
+           "unit": "tokens/s", "n_gpus": 1, "steps": K_steps, "warmup": Wm, "ms_per_step": res["chain"]["ms_per_round"], "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": f"C4 target, KV context {args.ctx}, batch 1, gamma {gamma}, T=1, K=5 one-layer heads on the target's "
-                                  "hidden states (W_fc [4096, 8192] each, layer tensors shared with the target)"},
-           "roofline": None, "cpu_baseline": None, "detail": detail}
+           "config": {"workload": f"C4 target, KV context {args.ctx}, batch 1, T=1, K=5 one-layer heads on the target's hidden states (W_fc "
+                                  f"[4096, 8192] each, layer tensors shared with the target): chain rounds with gamma = {D} (value) and rounds "
+                                  f"over the '{args.tree}' tree ({n} nodes, depth {D})"},
+           "roofline": None, "cpu_baseline": None, "detail": res}
     print(json.dumps(out))
     g.close()
     return 0

@@ -229,7 +229,8 @@ int32_t metasd_accept(metasd_ctx*, int32_t gamma, int32_t* n_acc_out, int32_t* t
  * row-major or bf16 in streaming-tile order (metasd_pack_weight(n_out = d, n_in = 2 d, rope 0)), caller-owned.  Call it
  * after metasd_create and before the first metasd_set_context; the context must have feature_heads = 1.  With
  * kv_prefilled contexts the caller also fills the feature table (METASD_PEEK_FEAT) for the prefilled positions.
- * Heads draft chains (metasd_draft), not trees.  Errors: INVALID, ORDER. */
+ * In tree rounds (metasd_draft_tree) a node takes the head's estimate at its parent; the target's features of the root and
+ * of the accepted nodes are kept.  Errors: INVALID, ORDER. */
 int32_t metasd_set_drafter_head(metasd_ctx*, int32_t k, const void* w_fc);
 
 /* ---- multi-candidate rounds: a tree of draft tokens verified in one pass with tree attention -----------------------

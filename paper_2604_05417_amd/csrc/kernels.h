@@ -154,12 +154,13 @@ __device__ __forceinline__ void store_split1(float* base, size_t n, size_t at, f
 // projection, x[r] = [embedding row h[r] ; feature of the position before row r], 2 d values per row.  The feature comes
 // from the table of the target's features (feat[p] = residual stream after the target's last layer at position p; row r at
 // position pos0 + r takes feat[pos0 + r - 1], zeros for position 0) or, est != nullptr, from the head's own estimate of
-// it (one row: the draft steps after the first).  split != 0: written as two bf16 arrays.     grid (m), block 256
-__global__ void feat_cat_kernel(const float* __restrict__ h, const float* __restrict__ feat, const float* __restrict__ est, int pos0, int d,
-                                float* __restrict__ out, int split) {
+// it (est[src.idx[r]]: one row for the draft steps of a chain after the first, the rows of a tree level take their parents').  split != 0: written as two bf16 arrays.     grid (m), block 256
+struct FeatSrc { uint8_t idx[16]; };   // estimates: the row of `est` that row r takes (chain steps: 0; tree levels: the parent node)
+__global__ void feat_cat_kernel(const float* __restrict__ h, const float* __restrict__ feat, const float* __restrict__ est, FeatSrc src,
+                                int pos0, int d, float* __restrict__ out, int split) {
     const int r = blockIdx.x;
     const int p = pos0 + r - 1;
-    const float* f = est ? est : feat + (size_t)(p < 0 ? 0 : p) * d;
+    const float* f = est ? est + (size_t)src.idx[r & 15] * d : feat + (size_t)(p < 0 ? 0 : p) * d;
     for (int i = threadIdx.x * 4; i < 2 * d; i += blockDim.x * 4) {
         float4 v;
         if (i < d) v = *reinterpret_cast<const float4*>(h + (size_t)r * d + i);

@@ -223,7 +223,7 @@ Layout make_layout(const metasd_config& c, const metasd_model_desc& t, const met
     L.xchg = take(B * (c.gamma_max + 1) * AS_XCHG_BYTES);
     // drafter heads: the target's feature of every processed position, and the head's estimate of the latest one
     L.feat = take(c.feature_heads ? (size_t)c.max_ctx * t.d_model * 4 : 0);
-    L.fest = take(c.feature_heads ? (size_t)t.d_model * 4 : 0);
+    L.fest = take(c.feature_heads ? (size_t)TREE_MAX * t.d_model * 4 : 0);   // one row per tree node (a chain uses row 0)
     int lmax = t.n_layers;
     for (int k = 0; k < c.K; ++k) lmax = std::max(lmax, dr[k].n_layers);
     L.table_stride = align_up((size_t)(1 + PER_LAYER * lmax + 2) * sizeof(void*));
@@ -424,7 +424,8 @@ struct metasd_ctx {
     bool fuse_small = true;          // short blocks of narrow bf16 models use the GEMMs with fused prologues (METASD_FUSE_SMALL=0: off)
     int n_cu = 0;
     const TreeBlk* tree = nullptr;   // set while a block of draft-tree nodes is being launched (positions and mask of its rows)
-    bool head_est = false;           // a drafter head's forward takes its own estimate (d_fest) as the feature input (draft steps after the first)
+    bool head_est = false;           // a drafter head's forward takes its own estimates (d_fest) as the feature input (draft steps after the first)
+    FeatSrc fsrc{};                  // .. row r the estimate fsrc.idx[r] (chain steps: 0; tree levels: the parent node's)
     TreeShape tshape{};              // the tree of the running round (metasd_draft_tree)
     int tdepth[TREE_MAX] = {};       // depth of every node, tlevel[d] = first node of depth d (tlevel[max depth + 1] = n)
     int tlevel[TREE_MAX + 2] = {};
@@ -727,7 +728,7 @@ int forward_rows(metasd_ctx* c, Model& M, int pos0, int m, float* logits, int fi
         // a drafter head starts from W_fc . [embedding ; feature of the position before] instead of the embedding
         float* cat = (float*)c->d_act();
         hipLaunchKernelGGL(feat_cat_kernel, dim3(m), dim3(256), 0, st, (const float*)h, (const float*)c->d_feat(),
-                           c->head_est ? (const float*)c->d_fest() : (const float*)nullptr, pos0, D, cat, split);
+                           c->head_est ? (const float*)c->d_fest() : (const float*)nullptr, c->fsrc, pos0, D, cat, split);
         LAUNCH_CHECK(c, "feat_cat");
         int dummy;
         if ((rc = gemm<T>(c, cat, 2 * D, m, 2 * D, M.fc, D, nullptr, 0, nullptr, 0, h, &dummy, (size_t)m * 2 * D))) return rc;
@@ -965,7 +966,12 @@ int forward_blocks(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool
                                (float4*)(c->d_feat() + (size_t)(pos0 + done) * D), n4);
             LAUNCH_CHECK(c, "feature rows");
         }
-        if (M.head && last) {                            // the head's estimate of the last row's feature: input of its next step
+        if (M.head && c->tree && c->tree->on == 1) {     // a tree level (one block): the estimates at its nodes, for their children
+            const unsigned n4 = (unsigned)((size_t)m * D / 4);
+            hipLaunchKernelGGL(copy_f4_kernel, dim3((n4 + 255) / 256), dim3(256), 0, c->stream, (const float4*)c->d_h(),
+                               (float4*)(c->d_fest() + (size_t)c->tree->i0 * D), n4);
+            LAUNCH_CHECK(c, "feature estimates");
+        } else if (M.head && last) {                     // the head's estimate of the last row's feature: input of its next step
             hipLaunchKernelGGL(copy_f4_kernel, dim3((D / 4 + 255) / 256), dim3(256), 0, c->stream,
                                (const float4*)(c->d_h() + (size_t)(m - 1) * D), (float4*)c->d_fest(), (unsigned)(D / 4));
             LAUNCH_CHECK(c, "feature estimate");
@@ -1965,7 +1971,6 @@ int32_t metasd_draft_tree(metasd_ctx* c, int32_t k, const metasd_tree* tree) {
     if (c->cfg.batch != 1) return c->fail(METASD_E_INVALID, "draft_tree: contexts with one sequence only");
     if (k < 0 || k >= c->cfg.K || !tree) return c->fail(METASD_E_INVALID, "draft_tree: bad drafter index or NULL tree");
     if (c->drafters[k].stream) return c->fail(METASD_E_INVALID, "draft_tree: drafters with a streaming cache draft chains only");
-    if (c->drafters[k].head) return c->fail(METASD_E_INVALID, "draft_tree: drafter heads on the target's hidden states draft chains only");
     if (c->phase != PH_READY) return c->fail(METASD_E_ORDER, "draft_tree: call set_context first / finish the previous round");
     const int n = tree->n;
     if (n < 2 || n > TREE_MAX || n > c->cfg.gamma_max + 1) return c->fail(METASD_E_INVALID, "draft_tree: tree of %d nodes; 2 .. min(%d, gamma_max + 1) supported", n, TREE_MAX);
@@ -2007,7 +2012,13 @@ int32_t metasd_draft_tree(metasd_ctx* c, int32_t k, const metasd_tree* tree) {
         else {
             tb.i0 = i0;
             c->tree = &tb;
+            if (D.head) {                                // a head's node takes the head's estimate at its parent
+                c->head_est = true;
+                for (int r = 0; r < m; ++r) c->fsrc.idx[r] = (uint8_t)ts.parent[i0 + r];
+            }
             rc = forward(c, D, base + i0, m, Qd, true);
+            c->head_est = false;
+            c->fsrc = FeatSrc{};
             c->tree = nullptr;
         }
         if (rc) return rc;
@@ -2058,9 +2069,15 @@ int32_t metasd_accept_tree(metasd_ctx* c, int32_t* n_acc_out, int32_t* token_out
     LAUNCH_CHECK(c, "accept_tree");
     Model& D = c->drafters[c->sq[0].cur_k];
     int rc = c->target.d.dtype == METASD_BF16 ? compact_kv<bf16_t>(c, c->target, base, TREE_MAX) : compact_kv<float>(c, c->target, base, TREE_MAX);
-    if (!rc && !D.shared_kv)
+    if (!rc && !D.shared_kv && !D.head)                  // a head keeps nothing of the round: no rows to move
         rc = D.d.dtype == METASD_BF16 ? compact_kv<bf16_t>(c, D, base, c->tmaxdepth - 1) : compact_kv<float>(c, D, base, c->tmaxdepth - 1);
     if (rc) return rc;
+    if (c->cfg.feature_heads) {                          // the target's features of the accepted nodes, from their slots to their positions
+        const int Dm = c->target.d.d_model;
+        hipLaunchKernelGGL(kv_compact_kernel<float>, dim3((unsigned)((Dm + 255) / 256)), dim3(256), 0, c->stream, c->d_feat(), 1, c->cfg.max_ctx, Dm,
+                           base, (const int32_t*)c->d_res(), TREE_MAX, c->tshape.n);
+        LAUNCH_CHECK(c, "feature rows of the accepted nodes");
+    }
     if ((rc = c->fetch_results())) return rc;
     if (c->mirror<GridBar>(c->lay.bar)->abort) {
         (void)hipMemsetAsync(c->d_bar(), 0, sizeof(GridBar), c->stream);
@@ -2081,6 +2098,7 @@ int32_t metasd_accept_tree(metasd_ctx* c, int32_t* n_acc_out, int32_t* token_out
     c->sq[0].l = l + na + 1;
     c->target.kvl[0] = l + na;
     D.kvl[0] = std::min(l + na, l + c->tmaxdepth - 1);
+    if (D.head) D.kvl[0] = l;                            // what a head computed from estimated features is not kept
     c->sq[0].round += 1;
     sync_shared_kv(c);
     c->phase = PH_READY;

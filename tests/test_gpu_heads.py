@@ -88,9 +88,6 @@ def test_head_validation():
     for bad in (lambda: g.L.metasd_set_drafter_head(g._h, 1, t.data_ptr()), lambda: g.L.metasd_set_drafter_head(g._h, 0, None)):
         with pytest.raises(M.MetaSDError):
             M.binding._check(bad(), g._h)
-    g.set_context(cfg["prompt"])
-    with pytest.raises(M.MetaSDError):                     # tree rounds are for drafters with plain caches
-        g.draft_tree(0, **W.draft_tree("wide"))
     g.close()
 
 

@@ -24,13 +24,19 @@ pytestmark = pytest.mark.gpu
 
 
 class TreeLockStep:
-    def __init__(self, gpu, target, drafters, prompt, tree, beta, tol, kv_prefilled=False, temp=0.0, seed=0):
+    def __init__(self, gpu, target, drafters, prompt, tree, beta, tol, kv_prefilled=False, temp=0.0, seed=0, feat_prefill=None):
         self.g, self.T, self.D, self.tree, self.tol = gpu, target, drafters, tree, tol
         self.temp, self.seed = temp, seed
         hist = np.zeros(target.max_ctx, np.int32)
         hist[: len(prompt)] = prompt
         self.st = oracle.SdState(hist=hist, l=len(prompt), c=[len(prompt) - 1 if kv_prefilled else 0] * len(drafters))
-        if not kv_prefilled and len(prompt) > 1:
+        if any(getattr(d, "feature_head", False) for d in drafters):     # drafter heads: the target's features are kept too
+            self.st.feat = np.zeros((target.max_ctx, target.desc["d_model"]), np.float32)
+            if kv_prefilled:                             # synthetic prefix: its features are given like its K/V
+                self.st.feat[: len(prompt) - 1] = feat_prefill
+            elif len(prompt) > 1:
+                _, self.st.feat[: len(prompt) - 1] = target.forward_hidden(prompt[:-1], 0, None)
+        elif not kv_prefilled and len(prompt) > 1:
             target.forward(prompt[:-1], 0, None)
         self.bandit = oracle.Ucb(len(drafters), beta)
         self.stats = dict(rounds=0, max_dp=0.0, max_dq=0.0, ties=0, n_acc=[], branch=0)
@@ -97,11 +103,22 @@ class TreeLockStep:
         lg, kvg, rg = g.state(-1)
         assert (lg, kvg, rg) == (st.l, st.l - 1, st.t)
         assert g.state(k)[1] == st.c[k]
+        self.check_features()
         self.stats["rounds"] += 1
         self.stats["n_acc"].append(n)
         self.stats["branch"] += sum(1 for i in path if t.rank[i] > 0)
         return n, token
 
+
+    def check_features(self):
+        """With drafter heads: the table of the target's features holds those of the committed rows (root and accepted nodes
+        moved from their slots to their positions)."""
+        if self.st.feat is None:
+            return
+        n = self.st.l - 1
+        df = float(np.abs(self.g.peek("feat")[:n].cpu().numpy() - self.st.feat[:n]).max())
+        self.stats["max_df"] = max(self.stats.get("max_df", 0.0), df)
+        assert df <= self.tol, f"round {self.st.t - 1}: feature table differs by {df}"
 
     def round_sampled(self, force_k=None):
         from oracle.tree import draw_children, walk_sampled
@@ -156,6 +173,7 @@ class TreeLockStep:
         lg, kvg, rg = g.state(-1)
         assert (lg, kvg, rg) == (st.l, st.l - 1, st.t)
         assert g.state(k)[1] == st.c[k]
+        self.check_features()
         self.stats["rounds"] += 1
         self.stats["n_acc"].append(n)
         self.stats["branch"] += sum(1 for i in path if t.rank[i] > 0)
@@ -313,4 +331,96 @@ def test_bf16_sampled_tree_rounds():
         ls.round(k)
     st = ls.stats
     assert st["ties"] <= 1 and st["rounds"] == 8, st
+    g.close()
+
+
+# ---------------------------------------------------------------- drafter heads on the target's hidden states filling the tree
+
+def make_heads(cfg, tree, tol, temp, eps=0.03, mixed=False):
+    """K = 3 heads over the target's first layer (feature weight eps * (k + 1)); mixed: drafter 1 stays an ordinary drafter."""
+    td, tw = cfg["target"]
+    tw_np = W.to_numpy(tw)
+    cache = {id(t): a for t, a in zip(tw, tw_np)}
+    drafters, heads, od = [], {}, []
+    for k in range(3):
+        if mixed and k == 1:
+            dd, dw = cfg["drafters"][1]
+            fc = None
+        else:
+            dd, dw, fc = W.feature_head_drafter(td, tw, 0, eps * (k + 1), 300 + k)
+            heads[k] = fc
+        drafters.append((dd, dw))
+        arrs = [cache[id(t)] if id(t) in cache else W.to_numpy([t])[0] for t in dw]
+        od.append(oracle.Model(dd, arrs, cfg["max_ctx"], fc=None if fc is None else W.to_numpy([fc])[0]))
+    g = M.MetaSD((td, tw), drafters, gamma_max=15, max_ctx=cfg["max_ctx"], temperature=temp, seed=cfg["seed"], ucb_beta=cfg["beta"], heads=heads)
+    g.set_context(cfg["prompt"])
+    return g, TreeLockStep(g, oracle.Model(td, tw_np, cfg["max_ctx"]), od, cfg["prompt"], tree, cfg["beta"], tol, temp=temp, seed=cfg["seed"])
+
+
+@pytest.mark.parametrize("temp", [0.0, 1.0])
+@pytest.mark.parametrize("kind,mixed", [("wide", False), ("bushy", True)])
+def test_config1_tree_rounds_with_drafter_heads(kind, mixed, temp):
+    """fp32: heads fill the tree (every node takes the head's estimate at its parent), the target's features of the root and
+    of the accepted nodes end up at their positions; 48 new tokens in lock-step, greedy: the target's own greedy continuation."""
+    cfg = W.config1_tree()
+    tree = Tree(**W.draft_tree(kind))
+    g, ls = make_heads(cfg, tree, 1e-4, temp, mixed=mixed)
+    order = [0, 2, 1, 1, 2, 0, 0]
+    B = len(cfg["prompt"]) + 48
+    while ls.st.l < B:
+        ls.round(order[ls.st.t % len(order)])
+    st = ls.stats
+    assert st["ties"] <= 1 and st["max_dp"] <= 1e-4 and st["max_dq"] <= 1e-4 and st["max_df"] <= 1e-4, st
+    if temp == 0.0:
+        ref = oracle.ar_decode(oracle.Model(cfg["target"][0], W.to_numpy(cfg["target"][1]), cfg["max_ctx"]), cfg["prompt"], 48, T=0.0)
+        assert np.array_equal(ls.st.hist[len(cfg["prompt"]): B], ref)
+    g.close()
+
+
+@pytest.mark.parametrize("temp", [0.0, 1.0])
+def test_small_bf16_tree_rounds_with_drafter_heads(temp):
+    """bf16 (head_dim 64, MFMA path, the 13-row verification block through the residual kernels with the features kept)."""
+    cfg = W.config4(n_layers=2, ctx=45, n_new=64, K=2, d_model=256, n_heads=4, d_ffn=736, vocab=1040, dd_model=128, dn_heads=2, dd_ffn=160)
+    cfg["max_ctx"] = 45 + 100
+    tree = Tree(**W.draft_tree("wide"))
+    g, ls = make_heads(cfg, tree, TOL, temp, eps=0.02, mixed=True)
+    order = [0, 1, 2, 2, 0]
+    for _ in range(8):
+        ls.round(order[ls.st.t % len(order)])
+    assert ls.stats["max_dp"] <= TOL and ls.stats["max_dq"] <= TOL and ls.stats["max_df"] <= TOL, ls.stats
+    g.close()
+
+
+@pytest.mark.parametrize("temp", [0.0, 1.0])
+def test_config4_7b_shape_tree_rounds_with_drafter_heads(temp):
+    """The 7B shape at full size: two one-layer heads (W_fc [4096, 8192]) fill the 13-node tree, synthetic K/V and feature
+    prefix of 2047 positions on both sides; one round per head and a return to the first."""
+    import torch
+    cfg = W.config4(device="cuda", K=1)
+    td, tw = cfg["target"]
+    n0 = len(cfg["prompt"]) - 1
+    tw_np = W.to_numpy(tw)
+    cache = {id(t): a for t, a in zip(tw, tw_np)}
+    drafters, heads, od = [], {}, []
+    for k in range(2):
+        dd, dw, fc = W.feature_head_drafter(td, tw, k, 0.01 * (k + 1), 300 + k)
+        drafters.append((dd, dw))
+        heads[k] = fc
+        od.append(oracle.Model(dd, [cache[id(t)] for t in dw], cfg["max_ctx"], fc=W.to_numpy([fc])[0]))
+    ot = oracle.Model(td, tw_np, cfg["max_ctx"])
+    g = M.MetaSD((td, tw), drafters, gamma_max=15, max_ctx=cfg["max_ctx"], temperature=temp, seed=cfg["seed"], ucb_beta=cfg["beta"], heads=heads)
+    for i, (desc, kv_gpu, om) in enumerate([(td, g.kv_target, ot)] + [(dd, g.kv_drafters[k], od[k]) for k, (dd, _) in enumerate(drafters)]):
+        kk, vv = W.kv_fill(desc, n0, cfg["kv_seed"] + i, device="cuda")
+        kv_gpu[:, 0, :, :n0] = kk
+        kv_gpu[:, 1, :, :n0] = vv
+        om.kv(0)[:, :, :n0] = kk.float().cpu().numpy()
+        om.kv(1)[:, :, :n0] = vv.float().cpu().numpy()
+    f0 = (torch.randn((n0, td["d_model"]), generator=torch.Generator(device="cpu").manual_seed(77)) * 0.05).float()
+    g.set_context(cfg["prompt"], kv_prefilled=True)
+    g.peek("feat")[:n0] = f0.cuda()
+    tree = Tree(**W.draft_tree("wide"))
+    ls = TreeLockStep(g, ot, od, cfg["prompt"], tree, cfg["beta"], TOL, kv_prefilled=True, temp=temp, seed=cfg["seed"], feat_prefill=f0.numpy())
+    for k in (0, 1, 0):
+        ls.round(k)
+    assert ls.stats["max_dp"] <= TOL and ls.stats["max_dq"] <= TOL and ls.stats["max_df"] <= TOL and ls.stats["ties"] <= 1, ls.stats
     g.close()
