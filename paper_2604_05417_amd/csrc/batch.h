@@ -202,33 +202,36 @@ __global__ void commit_tokens_kernel(const int32_t* __restrict__ n_acc, const in
 // bf16 GEMM on MFMA for blocks of more than 16 rows (verification of a batch: R = batch x (gamma + 1)).
 //   out[ks][r][n] = sum over the K-slice of x[r][k] W[n][k],  W in streaming-tile order,
 //   x as two bf16 arrays (hi at xh, lo x_lo_off elements behind), row stride ldx.
-// One workgroup of 8 wavefronts owns 2 TPQ feature tiles (TPQ = 4: 128 features) x one K-slice x all R rows:
-// wavefronts 0-3 the first TPQ tiles, 4-7 the other TPQ; within a quad wavefront w takes the
-// 16-row blocks w, w+4, ..  (RBW of them).  The K-slice advances in stages of two 32-wide chunks:
-// per stage the R x 64 activations (both terms: 128 contiguous bytes per row and term, so the
-// requests are whole cache lines) are staged in LDS, double-buffered, one workgroup barrier per
-// stage; a wavefront reads each activation fragment once and feeds it to the TPQ tiles it holds
-// in registers (2 TPQ MFMAs per LDS read pair), so LDS reads stay far below the MFMA rate.  Weights:
-// PD stages (8 KiB each per wavefront) in flight in registers; the wavefronts that share tiles
-// request the same lines (L1 / L2 hits).  Activation pieces are requested one stage ahead.
+// One workgroup of 8 wavefronts owns (8 / NRG) TPQ feature tiles x one K-slice x all R rows.  NRG = 4 (TPQ = 4: 128
+// features): wavefronts 0-3 the first TPQ tiles, 4-7 the other TPQ; within such a group wavefront w takes the
+// 16-row blocks w, w+NRG, ..  (RBW of them).  NRG = 2: four groups of two wavefronts (12 tiles with TPQ = 3) - every
+// activation byte staged serves twice the multiplies, and a weight tile is requested by two wavefronts instead of four.
+// The K-slice advances in stages of CST 32-wide chunks (2; 128 contiguous bytes per row and term, whole cache lines):
+// per stage the R x 64 activations, both terms, are staged in LDS, double-buffered, one workgroup barrier per stage; a
+// wavefront reads each activation fragment once and feeds it to the TPQ tiles it holds in registers (2 TPQ MFMAs per
+// LDS read pair).  Weights: PD stages in flight in registers; the wavefronts that share tiles request the same lines
+// (L1 / L2 hits).  DMA = false: activation pieces are requested one stage ahead into registers and written to LDS at
+// the start of the next stage.  DMA = true: they go from memory into LDS directly (see there).
 // LO = false leaves out the low-order terms of the activations (plain bf16 activations).
-//   grid (ceil(ntiles / (2 TPQ)) * ksplit), block 512, dynamic LDS 2 * (LO ? 16 : 8) * (64 RBW + 1) * 16 bytes;  R <= 64 RBW.
-template <int RBW, int PD, bool LO, int TPQ = 4>
+//   grid (ceil(ntiles / ((8 / NRG) TPQ)) * ksplit), block 512, dynamic LDS 2 * (LO ? 8 : 4) CST * 16 NRG RBW * 16 bytes;  R <= 16 NRG RBW.
+template <int RBW, int PD, bool LO, int TPQ = 4, int NRG = 4, int CST = 2, bool DMA = false>
 __device__ __forceinline__ void gemm_bf16_rows_body(const bf16_t* __restrict__ xh, size_t x_lo_off, int ldx, int R, int K,
                                                     const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
                                                     const bf16_t* __restrict__ W2, int t0, int t1, int ntiles,
                                                     float* __restrict__ out, size_t out_sstride, int N, int ksplit, int cps) {
-    extern __shared__ uint4 lds[];                 // [2 buffers][NP pieces][LR rows]
-    constexpr int R16 = 64 * RBW, LR = R16 + 1;
-    constexpr int NP = LO ? 16 : 8;                // 16-byte pieces per row and stage: 8 hi (+ 8 lo)
+    extern __shared__ uint4 lds[];                 // [2 buffers][hi | lo][R16 rows][HP pieces, swizzled]
+    constexpr int R16 = 16 * NRG * RBW;
+    constexpr int NTG = 8 / NRG;                   // groups of wavefronts with tiles of their own
+    constexpr int HP = 4 * CST;                    // 16-byte pieces per row, stage and term (a stage is CST 32-wide chunks)
+    constexpr int NP = LO ? 2 * HP : HP;           // .. per row and stage: hi (+ lo)
     constexpr int APT = R16 * NP / 512;            // pieces per thread and stage
     const int kchunks = K >> 5;
     const int ks = blockIdx.x % ksplit, tg = blockIdx.x / ksplit;
     const int c0 = ks * cps, nc = min(cps, kchunks - c0);
-    const int nst = (nc + 1) >> 1;                 // stages of two chunks
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, quad = wave >> 2, wr = wave & 3;
+    const int nst = (nc + CST - 1) / CST;          // stages of CST chunks
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, quad = wave / NRG, wr = wave % NRG;
     const int row16 = lane & 15, g = lane >> 4;
-    const int tl0 = tg * 2 * TPQ + quad * TPQ;     // this wavefront's TPQ tiles: tl0 .. tl0 + TPQ - 1
+    const int tl0 = tg * NTG * TPQ + quad * TPQ;   // this wavefront's TPQ tiles: tl0 .. tl0 + TPQ - 1
     auto tile_ptr = [&](int i) -> const u32x4* {
         const int t = min(tl0 + i, ntiles - 1);
         const bf16_t* W;
@@ -243,10 +246,10 @@ __device__ __forceinline__ void gemm_bf16_rows_body(const bf16_t* __restrict__ x
     for (int i = 0; i < TPQ; ++i) wp[i] = tile_ptr(i);
     // every load is unconditional and clamped into range: chunks past the slice's end re-read its last
     // chunk and are multiplied by zero
-    auto wload = [&](u32x4 (&dst)[2 * TPQ], int st) {
+    auto wload = [&](u32x4 (&dst)[CST * TPQ], int st) {
 #pragma unroll
-        for (int cc = 0; cc < 2; ++cc) {
-            const size_t co = (size_t)min(2 * st + cc, nc - 1) * 64;   // plain loads: the four wavefronts that share these tiles meet in L1
+        for (int cc = 0; cc < CST; ++cc) {
+            const size_t co = (size_t)min(CST * st + cc, nc - 1) * 64;   // plain loads: the four wavefronts that share these tiles meet in L1
 #pragma unroll
             for (int i = 0; i < TPQ; ++i) dst[cc * TPQ + i] = wp[i][co];
         }
@@ -255,17 +258,21 @@ __device__ __forceinline__ void gemm_bf16_rows_body(const bf16_t* __restrict__ x
 #pragma unroll
         for (int u = 0; u < APT; ++u) {
             const int idx = tid + 512 * u, row = min(idx / NP, R - 1), which = idx % NP;
-            const int c = min(2 * st + ((which & 7) >> 2), nc - 1);
-            const bf16_t* src = xh + (size_t)row * ldx + (size_t)(c0 + c) * 32 + (which & 3) * 8 + ((which >> 3) ? x_lo_off : (size_t)0);
+            const int c = min(CST * st + ((which % HP) >> 2), nc - 1);
+            const bf16_t* src = xh + (size_t)row * ldx + (size_t)(c0 + c) * 32 + (which & 3) * 8 + (which >= HP ? x_lo_off : (size_t)0);
             dst[u] = *reinterpret_cast<const u32x4*>(src);
         }
     };
+    // LDS layout of a stage: per term, rows of HP 16-byte pieces (128 or 64 bytes), piece q of row r in position q ^ swz(r):
+    // the 16 lanes that read one K sub-block of 16 consecutive rows then touch 16 different 16-byte columns of the 256-byte
+    // bank space (measured: 220 B/clk per CU against 63 without the swizzle and 120 for piece-major planes padded by one row)
+    auto swz = [](int r) { return CST == 2 ? (r >> 1) & 7 : (r >> 2) & 3; };
     auto astore = [&](const u32x4 (&src)[APT], int buf) {
-        uint4* base = lds + (size_t)buf * NP * LR;
+        uint4* base = lds + (size_t)buf * NP * R16;
 #pragma unroll
         for (int u = 0; u < APT; ++u) {
-            const int idx = tid + 512 * u;
-            base[(idx % NP) * LR + idx / NP] = __builtin_bit_cast(uint4, src[u]);
+            const int idx = tid + 512 * u, row = idx / NP, which = idx % NP, q = which % HP;
+            base[(which >= HP ? R16 * HP : 0) + row * HP + (q ^ swz(row))] = __builtin_bit_cast(uint4, src[u]);
         }
     };
     f32x4 acc[RBW][TPQ];
@@ -278,44 +285,99 @@ __device__ __forceinline__ void gemm_bf16_rows_body(const bf16_t* __restrict__ x
     // fragments instead would make every LDS read wait for its data at once.
     // The activation fragments of step k+1 (a step = one 16-row block of one chunk) are read from LDS
     // before the MFMAs of step k are issued, so the LDS latency hides behind 8 (4) MFMAs.
-    auto compute = [&](u32x4 (&w)[2 * TPQ], int buf, int st) {
-        const u32x4* base = reinterpret_cast<const u32x4*>(lds) + (size_t)buf * NP * LR;
-        const uint32_t mask0 = 2 * st < nc ? 0xffffffffu : 0u, mask1 = 2 * st + 1 < nc ? 0xffffffffu : 0u;
+    auto wmask = [&](u32x4 (&w)[CST * TPQ], int st) {
 #pragma unroll
-        for (int i = 0; i < TPQ; ++i) { w[i] &= mask0; w[TPQ + i] &= mask1; }
-        u32x4 fh[2], fl[2];
+        for (int cc = 0; cc < CST; ++cc) {
+            const uint32_t mask = CST * st + cc < nc ? 0xffffffffu : 0u;
+#pragma unroll
+            for (int i = 0; i < TPQ; ++i) w[cc * TPQ + i] &= mask;
+        }
+    };
+    auto compute = [&](u32x4 (&w)[CST * TPQ], int buf) {
+        const u32x4* base = reinterpret_cast<const u32x4*>(lds) + (size_t)buf * NP * R16;
+        constexpr int FD = 1;                   // fragments are read FD steps before their multiplies (2: measured no faster)
+        u32x4 fh[FD + 1], fl[FD + 1];
         auto fetch = [&](int k) {               // step k: chunk cc = k / RBW, row block a = k % RBW
             const int cc = k / RBW, a = k % RBW;
-            const int rowi = (wr + 4 * a) * 16 + row16;
-            fh[k & 1] = base[(cc * 4 + g) * LR + rowi];
-            if constexpr (LO) fl[k & 1] = base[(8 + cc * 4 + g) * LR + rowi];
+            const int rowi = (wr + NRG * a) * 16 + row16;
+            const int slot = rowi * HP + ((cc * 4 + g) ^ swz(rowi));
+            fh[k % (FD + 1)] = base[slot];
+            if constexpr (LO) fl[k % (FD + 1)] = base[R16 * HP + slot];
         };
-        fetch(0);
 #pragma unroll
-        for (int k = 0; k < 2 * RBW; ++k) {
-            if (k + 1 < 2 * RBW) fetch(k + 1);
+        for (int k = 0; k < FD; ++k) fetch(k);
+#pragma unroll
+        for (int k = 0; k < CST * RBW; ++k) {
+            if (k + FD < CST * RBW) fetch(k + FD);
             const int cc = k / RBW, a = k % RBW;
 #pragma unroll
             for (int i = 0; i < TPQ; ++i)
-                acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[cc * TPQ + i]), __builtin_bit_cast(bf16x8, fh[k & 1]), acc[a][i], 0, 0, 0);
+                acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[cc * TPQ + i]), __builtin_bit_cast(bf16x8, fh[k % (FD + 1)]), acc[a][i], 0, 0, 0);
             if constexpr (LO) {
 #pragma unroll
                 for (int i = 0; i < TPQ; ++i)
-                    acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[cc * TPQ + i]), __builtin_bit_cast(bf16x8, fl[k & 1]), acc[a][i], 0, 0, 0);
+                    acc[a][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w[cc * TPQ + i]), __builtin_bit_cast(bf16x8, fl[k % (FD + 1)]), acc[a][i], 0, 0, 0);
             }
         }
-        // shape of the schedule: the reads of the next step, then the MFMAs of this one
-        __builtin_amdgcn_sched_group_barrier(0x100, LO ? 2 : 1, 0);
+        // shape of the schedule: the reads of the steps ahead, then the MFMAs of this one
+        __builtin_amdgcn_sched_group_barrier(0x100, (LO ? 2 : 1) * FD, 0);
 #pragma unroll
-        for (int k = 0; k < 2 * RBW; ++k) {
-            if (k + 1 < 2 * RBW) __builtin_amdgcn_sched_group_barrier(0x100, LO ? 2 : 1, 0);
+        for (int k = 0; k < CST * RBW; ++k) {
+            if (k + FD < CST * RBW) __builtin_amdgcn_sched_group_barrier(0x100, LO ? 2 : 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, LO ? 2 * TPQ : TPQ, 0);
         }
     };
+    u32x4 w[PD][CST * TPQ];
+    if constexpr (DMA) {
+        // Activations go from memory straight into LDS (16 bytes per lane, lane i of a request to slot i of a KiB), without
+        // passing registers: one request covers 8 rows x 128 bytes of one term, the lane that fills position p of row r
+        // fetches piece p ^ swz(r).  The requests of stage st+1 are issued once this stage's weights have arrived (after the
+        // masks touched them: the waits the compiler places for the weights count the requests it knows of, and these it
+        // does not) and land while this stage is multiplied; every wavefront waits for everything it has in flight before
+        // the barrier (a count of zero: right wherever the compiler puts the weight requests), and the weights of stage
+        // st+PD are requested after the barrier, a whole stage before their use.  Nothing is outstanding when the kernel ends.
+        static_assert(!DMA || (LO && CST == 2), "direct loads: two terms, stages of two chunks");
+        constexpr int RG = R16 / 8, NI = 2 * RG / 8;             // row groups of 8; requests per wavefront and stage
+        const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) void*)lds;
+        const int rl = lane >> 3, pp = lane & 7;
+        auto dma = [&](int st, int buf) {
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int id = wave * NI + j, term = id / RG, rg = id % RG;
+                const int row = rg * 8 + rl, q = pp ^ swz(row);
+                const int c = min(CST * st + (q >> 2), nc - 1);
+                const bf16_t* src = xh + (size_t)min(row, R - 1) * ldx + (size_t)(c0 + c) * 32 + (q & 3) * 8 + (term ? x_lo_off : (size_t)0);
+                const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + (unsigned)(((buf * NP + term * HP) * R16 + rg * 64) * 16));
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
+            }
+        };
+        dma(0, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        lds_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < PD; ++u) wload(w[u], u);
+        for (int sb = 0; sb < nst; sb += PD) {
+#pragma unroll
+            for (int u = 0; u < PD; ++u) {
+                const int st = sb + u;
+                wmask(w[u], st);
+                __builtin_amdgcn_sched_barrier(0);
+                dma(st + 1, (st + 1) & 1);                 // its buffer was last read in stage st-1, before the last barrier
+                __builtin_amdgcn_sched_barrier(0);
+                compute(w[u], st & 1);
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                lds_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                wload(w[u], st + PD);
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
     // Order of the requests (a wavefront's loads return in order): the activations of stage st+1 are
     // requested before the multiplies of stage st-1 and written to LDS before those of stage st; the only
     // loads requested after them and before that write are weights the next multiplies need anyway.
-    u32x4 w[PD][2 * TPQ];
     u32x4 ar[APT];
     aload(ar, 0);
 #pragma unroll
@@ -335,14 +397,16 @@ __device__ __forceinline__ void gemm_bf16_rows_body(const bf16_t* __restrict__ x
             // activation load scheduled behind them would make the next stage's LDS write wait for weights that
             // are only needed two stages later (a full trip to HBM per stage).
             __builtin_amdgcn_sched_barrier(0);
-            compute(w[u], st & 1, st);
+            wmask(w[u], st);
+            compute(w[u], st & 1);
             wload(w[u], st + PD);
             lds_barrier();
         }
     }
+    }
 #pragma unroll
     for (int a = 0; a < RBW; ++a) {
-        const int row = (wr + 4 * a) * 16 + row16;
+        const int row = (wr + NRG * a) * 16 + row16;
         if (row < R) {
 #pragma unroll
             for (int i = 0; i < TPQ; ++i)
@@ -354,13 +418,13 @@ __device__ __forceinline__ void gemm_bf16_rows_body(const bf16_t* __restrict__ x
     }
 }
 
-template <int RBW, int PD, bool LO, int TPQ = 4>
+template <int RBW, int PD, bool LO, int TPQ = 4, int NRG = 4, int CST = 2, bool DMA = false>
 __global__ __launch_bounds__(512) void gemm_bf16_rows_kernel(const bf16_t* __restrict__ xh, size_t x_lo_off, int ldx, int R, int K,
                                                              const bf16_t* __restrict__ W0, const bf16_t* __restrict__ W1,
                                                              const bf16_t* __restrict__ W2, int t0, int t1, int ntiles,
                                                              float* __restrict__ out, size_t out_sstride, int N, int ksplit,
                                                              int cps) {
-    gemm_bf16_rows_body<RBW, PD, LO, TPQ>(xh, x_lo_off, ldx, R, K, W0, W1, W2, t0, t1, ntiles, out, out_sstride, N, ksplit, cps);
+    gemm_bf16_rows_body<RBW, PD, LO, TPQ, NRG, CST, DMA>(xh, x_lo_off, ldx, R, K, W0, W1, W2, t0, t1, ntiles, out, out_sstride, N, ksplit, cps);
 }
 
 // One launch for several row groups with weights of their own (same shapes): blockIdx.y is the group; its rows

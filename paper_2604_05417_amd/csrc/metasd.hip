@@ -106,21 +106,23 @@ Split choose_split(int m, int ntiles, int kchunks) {
     return s;
 }
 
-// Many-row GEMM (more than 16 rows): tiles per workgroup (8; for more than 128 rows also 6 or 4) and K split.
+// Many-row GEMM (more than 16 rows): tiles per workgroup (8; for more than 128 rows also 6, 4, or 12 - the form that
+// loads its activations straight into LDS) and K split.
 // A workgroup holds a CU (its LDS), so the launch runs in ceil(workgroups / 256) rounds; measured on the 7B
-// shapes at 256 rows a round costs about 0.9 / 0.75 / 0.6 us per 32-wide K chunk with 8 / 6 / 4 tiles (a fixed
-// part for staging the activations plus the multiplies), and the split-K partials are written and read once.
+// shapes at 256 rows a round costs about 0.9 / 0.75 / 0.6 / 1.28 us per 32-wide K chunk with 8 / 6 / 4 / 12 tiles (a
+// fixed part for staging the activations plus the multiplies), and the split-K partials are written and read once.
 Split choose_split_rows(int ntiles, int kchunks, int R, int forced_tpb) {
     int best = 1, best_tpb = 8;
     double best_cost = 1e30;
-    for (int tpb = 8; tpb >= 4; tpb -= 2) {
+    for (int tpb : {8, 6, 4, 12}) {
         if (tpb != 8 && (R <= 128 || (forced_tpb && tpb != forced_tpb))) continue;
         if (tpb == 8 && forced_tpb && forced_tpb != 8 && R > 128) continue;
         const int groups = (ntiles + tpb - 1) / tpb;
         for (int ks = 1; ks <= 8 && kchunks / ks >= 8; ++ks) {
             const int cps = ((kchunks + ks - 1) / ks + 3) / 4 * 4;
             const int rounds = (groups * ks + 255) / 256;
-            const double cost = (double)rounds * cps * (0.3 + 0.075 * tpb) + (ks > 1 ? (double)ks * R * ntiles * 16 * 8 / 8e6 : 0.0);   // us
+            const double per_chunk = tpb == 12 ? 1.28 : 0.3 + 0.075 * tpb;
+            const double cost = (double)rounds * cps * per_chunk + (ks > 1 ? (double)ks * R * ntiles * 16 * 8 / 8e6 : 0.0);   // us
             if (cost < best_cost) { best_cost = cost; best = ks; best_tpb = tpb; }
         }
     }
@@ -417,7 +419,7 @@ struct metasd_ctx {
     bool fullk = true;               // residual GEMMs whose input fits in LDS run without split-K (METASD_GEMM_FULLK=0: off)
     bool grouped_on = true;          // batched drafting: one forward per step for all arms (METASD_DRAFT_GROUPED=0: one per arm)
     int att_cpw = 0;                 // batched attention: chunks per workgroup, 0 = by the rule in attention_seg_hd (METASD_ATT_CPW=1..64 forces one)
-    int rows_tpb = 0;                // many-row GEMM: tiles per workgroup, 0 = by the cost model (METASD_ROWS_TPB=4|6|8 forces one)
+    int rows_tpb = 0;                // many-row GEMM: tiles per workgroup, 0 = by the cost model (METASD_ROWS_TPB=4|6|8|12 forces one)
     bool fullk_roll = true;          // .. and larger inputs with rolling private staging (METASD_GEMM_ROLL=0: sibling reduction instead)
     bool gemm_reduce = true;         // bf16 models: residual GEMMs reduce their split-K partials themselves (METASD_GEMM_REDUCE=0: off)
     float cur_eps = 1e-5f;           // rms_eps of the model whose forward is being launched
@@ -1008,18 +1010,19 @@ int gemm_rows<float>(metasd_ctx* c, const void* x, int ldx, int R, int K, const 
 }
 
 // more than 64 KiB of dynamic LDS needs the function attribute (set once per variant; harmless below the limit)
-template <int RBW, bool LO, int TPQ = 4, int PD = ROWS_PD>
+template <int RBW, bool LO, int TPQ = 4, int PD = ROWS_PD, int NRG = 4, int CST = 2, bool DMA = false>
 int launch_gemm_rows(metasd_ctx* c, const bf16_t* xh, size_t x_lo_off, int ldx, int R, int r0, int nr, int K, const void* W0,
                      const void* W1, const void* W2, int t0, int t1, int ntiles, int N, const Split& s, metasd_ctx::ProfRec* pr) {
-    const size_t lds = (size_t)2 * (LO ? 16 : 8) * (64 * RBW + 1) * 16;
+    const size_t lds = (size_t)2 * (LO ? 8 : 4) * CST * (16 * NRG * RBW) * 16;
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)gemm_bf16_rows_kernel<RBW, PD, LO, TPQ>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        if (hipFuncSetAttribute((const void*)gemm_bf16_rows_kernel<RBW, PD, LO, TPQ, NRG, CST, DMA>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return c->fail(METASD_E_HIP, "gemm_bf16_rows_kernel: cannot reserve %zu bytes of LDS", lds);
         attr_set = true;
     }
-    const int groups = (ntiles + 2 * TPQ - 1) / (2 * TPQ);
-    hipExtLaunchKernelGGL((gemm_bf16_rows_kernel<RBW, PD, LO, TPQ>), dim3(groups * s.ksplit), dim3(512), (uint32_t)lds, c->stream,
+    constexpr int TPW = (8 / NRG) * TPQ;           // tiles per workgroup
+    const int groups = (ntiles + TPW - 1) / TPW;
+    hipExtLaunchKernelGGL((gemm_bf16_rows_kernel<RBW, PD, LO, TPQ, NRG, CST, DMA>), dim3(groups * s.ksplit), dim3(512), (uint32_t)lds, c->stream,
                           pr ? pr->a : nullptr, pr ? pr->b : nullptr, 0u, xh + (size_t)r0 * ldx, x_lo_off, ldx, nr, K, (const bf16_t*)W0,
                           (const bf16_t*)W1, (const bf16_t*)W2, t0, t1, ntiles, c->d_part() + (size_t)r0 * N, (size_t)R * N, N, s.ksplit, s.cps);
     LAUNCH_CHECK(c, "gemm_bf16_rows");
@@ -1042,12 +1045,13 @@ int gemm_rows<bf16_t>(metasd_ctx* c, const void* x, int ldx, int R, int K, const
         const int nr = std::min(256, R - r0);
         metasd_ctx::ProfRec* p = r0 ? nullptr : pr;
 #define ROWS_ARGS (c, xh, x_lo_off, ldx, R, r0, nr, K, W0, W1, W2, t0, t1, ntiles, N, s, p)
-#define ROWS_GO(RBW) launch_gemm_rows<RBW, true> ROWS_ARGS
-        if (nr <= 64) rc = ROWS_GO(1);
-        else if (nr <= 128) rc = ROWS_GO(2);
-        else if (s.tpb == 4) rc = launch_gemm_rows<4, true, 2> ROWS_ARGS;
-        else if (s.tpb == 6) rc = launch_gemm_rows<4, true, 3> ROWS_ARGS;
-        else rc = ROWS_GO(4);
+#define ROWS_GO(RBW, TPQ) launch_gemm_rows<RBW, true, TPQ> ROWS_ARGS
+        if (nr <= 64) rc = ROWS_GO(1, 4);
+        else if (nr <= 128) rc = ROWS_GO(2, 4);
+        else if (s.tpb == 12) rc = launch_gemm_rows<8, true, 3, ROWS_PD, 2, 2, true> ROWS_ARGS;     // activations straight into LDS
+        else if (s.tpb == 4) rc = ROWS_GO(4, 2);
+        else if (s.tpb == 6) rc = ROWS_GO(4, 3);
+        else rc = ROWS_GO(4, 4);
 #undef ROWS_GO
 #undef ROWS_ARGS
     }
@@ -1205,7 +1209,7 @@ bool grouped_step_supported(const metasd_ctx* c) {
 template <int RBW>
 int launch_gemm_rows_grouped(metasd_ctx* c, const void* x, int ldx, int R, int K, const RowGroups& gg, int n0, int n1, int N, const Split& s,
                              metasd_ctx::ProfRec* pr) {
-    const size_t lds = (size_t)2 * 16 * (64 * RBW + 1) * 16;
+    const size_t lds = (size_t)2 * 16 * (64 * RBW) * 16;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)gemm_bf16_rows_grouped_kernel<RBW, ROWS_PD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -1718,7 +1722,7 @@ int32_t metasd_create(metasd_ctx** out, const metasd_config* cfg, const metasd_m
         if (const char* ev = getenv("METASD_GEMM_ROLL")) c->fullk_roll = ev[0] != '0';
         if (const char* ev = getenv("METASD_DRAFT_GROUPED")) c->grouped_on = ev[0] != '0';
         if (const char* ev = getenv("METASD_ATT_CPW")) { const int v = atoi(ev); c->att_cpw = (v >= 1 && v <= 64) ? v : 0; }
-        if (const char* ev = getenv("METASD_ROWS_TPB")) { const int v = atoi(ev); c->rows_tpb = (v == 4 || v == 6 || v == 8) ? v : 0; }
+        if (const char* ev = getenv("METASD_ROWS_TPB")) { const int v = atoi(ev); c->rows_tpb = (v == 4 || v == 6 || v == 8 || v == 12) ? v : 0; }
         {
             const int roll_lds = (int)FULLK_LDS_MAX;
             if (hipFuncSetAttribute((const void*)gemm_fullk_roll_residual_kernel<3, true>, hipFuncAttributeMaxDynamicSharedMemorySize, roll_lds) != hipSuccess ||

@@ -176,9 +176,9 @@ def test_bf16_wide_blocks(rows):
     g.close()
 
 
-@pytest.mark.parametrize("tpb", [4, 6])
+@pytest.mark.parametrize("tpb", [4, 6, 12])
 def test_bf16_wide_blocks_other_tile_counts(tpb, monkeypatch):
-    """The 256-row GEMM variant with 4 and 6 feature tiles per workgroup (the cost model picks them for the 7B shapes;
+    """The 256-row GEMM variant with 4, 6 and 12 feature tiles per workgroup (12: the form whose activations go straight from memory into LDS) (the cost model picks them for the 7B shapes;
     here forced at context creation): 20 x 8 = 160 rows, tile counts that are no multiple of 4 or 6 (ragged last group)."""
     monkeypatch.setenv("METASD_ROWS_TPB", str(tpb))
     s = SMALL[0]
