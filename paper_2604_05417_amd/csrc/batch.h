@@ -199,6 +199,81 @@ __global__ void commit_tokens_kernel(const int32_t* __restrict__ n_acc, const in
 }
 
 // ------------------------------------------------------------------------------------------
+// addnorm_kernel's arithmetic (same order of additions, same results) for many rows of d = 1024 COLS columns: one
+// 256-thread workgroup per row, every thread COLS float4 columns, the row of h and all partials of a group of eight
+// requested at once (up to 36 requests in flight per thread instead of 9: with one workgroup per CU the time goes with the
+// number of requests a CU keeps in flight).       grid (rows), block 256
+template <typename T, int COLS>
+__global__ __launch_bounds__(256) void addnorm_rows_kernel(float* __restrict__ h, const float* __restrict__ part, int nsplit, size_t sstride,
+                                                           const T* __restrict__ gain, float eps, float* __restrict__ xn, int split) {
+    __shared__ float red[4];
+    constexpr int d = 1024 * COLS;
+    const int r = blockIdx.x;
+    float* hr = h + (size_t)r * d;
+    const float* pr = part + (size_t)r * d;
+    float4 v[COLS], gn[COLS];
+#pragma unroll
+    for (int c = 0; c < COLS; ++c) {
+        const int i = threadIdx.x * 4 + 1024 * c;
+        v[c] = *reinterpret_cast<const float4*>(hr + i);
+        gn[c] = make_float4(El<T>::ld(gain[i]), El<T>::ld(gain[i + 1]), El<T>::ld(gain[i + 2]), El<T>::ld(gain[i + 3]));
+    }
+    if (nsplit > 0) {
+        float4 y[COLS];
+#pragma unroll
+        for (int c = 0; c < COLS; ++c) y[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s0 = 0; s0 < nsplit; s0 += 8) {
+            float4 p[8][COLS];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int c = 0; c < COLS; ++c)
+                    p[u][c] = *reinterpret_cast<const float4*>(pr + (size_t)min(s0 + u, nsplit - 1) * sstride + threadIdx.x * 4 + 1024 * c);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const bool on = s0 + u < nsplit;
+#pragma unroll
+                for (int c = 0; c < COLS; ++c) {
+                    y[c].x += on ? p[u][c].x : 0.f; y[c].y += on ? p[u][c].y : 0.f; y[c].z += on ? p[u][c].z : 0.f; y[c].w += on ? p[u][c].w : 0.f;
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < COLS; ++c) {
+            v[c].x += y[c].x; v[c].y += y[c].y; v[c].z += y[c].z; v[c].w += y[c].w;
+            *reinterpret_cast<float4*>(hr + threadIdx.x * 4 + 1024 * c) = v[c];
+        }
+    }
+    // sum of squares in addnorm_kernel's order: a thread of its 1024-thread workgroup holds one column per 4096, i.e. the
+    // columns c of this thread belong to threads tid + 256 c there - different wavefronts, summed per wavefront first
+    float tot = 0.f;
+#pragma unroll
+    for (int c = 0; c < COLS; ++c) {
+        float ss = v[c].x * v[c].x + v[c].y * v[c].y + v[c].z * v[c].z + v[c].w * v[c].w;
+        ss = wave_sum(ss);
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < 4; ++w) tot += red[w];
+    }
+    const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+    if (xn) {
+#pragma unroll
+        for (int c = 0; c < COLS; ++c) {
+            const int i = threadIdx.x * 4 + 1024 * c;
+            float4 o;
+            o.x = v[c].x * inv * gn[c].x;
+            o.y = v[c].y * inv * gn[c].y;
+            o.z = v[c].z * inv * gn[c].z;
+            o.w = v[c].w * inv * gn[c].w;
+            if (split) store_split4(xn, (size_t)gridDim.x * d, (size_t)r * d + i, o);
+            else *reinterpret_cast<float4*>(xn + (size_t)r * d + i) = o;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // bf16 GEMM on MFMA for blocks of more than 16 rows (verification of a batch: R = batch x (gamma + 1)).
 //   out[ks][r][n] = sum over the K-slice of x[r][k] W[n][k],  W in streaming-tile order,
 //   x as two bf16 arrays (hi at xh, lo x_lo_off elements behind), row stride ldx.

@@ -191,7 +191,7 @@ __device__ __forceinline__ void addnorm_body(float* __restrict__ h, const float*
     const int r = blockIdx.x;
     float* hr = h + (size_t)r * d;
     const float* pr = part + (size_t)r * d;
-    float4 keep[KEEP];
+    float4 keep[KEEP], gk[KEEP];
     float ss = 0.f;
     int k = 0;
     for (int i = threadIdx.x * 4; i < d; i += 4096, ++k) {
@@ -199,19 +199,25 @@ __device__ __forceinline__ void addnorm_body(float* __restrict__ h, const float*
         if (nsplit > 0) {
             float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
             for (int s0 = 0; s0 < nsplit; s0 += 8) {      // eight partials in flight; added in the fixed order s = 0, 1, ..
+                // every request unconditional (past the last partial: that one again, then dropped by a select): a branch
+                // around a request would make the compiler wait for all of them one by one
                 float4 p[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
-                    p[u] = (s0 + u < nsplit) ? *reinterpret_cast<const float4*>(pr + (size_t)(s0 + u) * sstride + i)
-                                             : make_float4(0.f, 0.f, 0.f, 0.f);
+                    p[u] = *reinterpret_cast<const float4*>(pr + (size_t)min(s0 + u, nsplit - 1) * sstride + i);
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    if (s0 + u < nsplit) { y.x += p[u].x; y.y += p[u].y; y.z += p[u].z; y.w += p[u].w; }
+                for (int u = 0; u < 8; ++u) {
+                    const bool on = s0 + u < nsplit;
+                    y.x += on ? p[u].x : 0.f; y.y += on ? p[u].y : 0.f; y.z += on ? p[u].z : 0.f; y.w += on ? p[u].w : 0.f;
+                }
             }
             v.x += y.x; v.y += y.y; v.z += y.z; v.w += y.w;
             *reinterpret_cast<float4*>(hr + i) = v;
         }
-        if (k < KEEP) keep[k] = v;
+        if (k < KEEP) {
+            keep[k] = v;
+            if (xn) gk[k] = make_float4(El<T>::ld(gain[i]), El<T>::ld(gain[i + 1]), El<T>::ld(gain[i + 2]), El<T>::ld(gain[i + 3]));   // requested with the row, not after the reduction
+        }
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
     ss = wave_sum(ss);
@@ -225,11 +231,13 @@ __device__ __forceinline__ void addnorm_body(float* __restrict__ h, const float*
         k = 0;
         for (int i = threadIdx.x * 4; i < d; i += 4096, ++k) {
             const float4 v = k < KEEP ? keep[k < KEEP ? k : 0] : *reinterpret_cast<const float4*>(hr + i);
+            const float4 gn = k < KEEP ? gk[k < KEEP ? k : 0]
+                                       : make_float4(El<T>::ld(gain[i]), El<T>::ld(gain[i + 1]), El<T>::ld(gain[i + 2]), El<T>::ld(gain[i + 3]));
             float4 o;
-            o.x = v.x * inv * El<T>::ld(gain[i]);
-            o.y = v.y * inv * El<T>::ld(gain[i + 1]);
-            o.z = v.z * inv * El<T>::ld(gain[i + 2]);
-            o.w = v.w * inv * El<T>::ld(gain[i + 3]);
+            o.x = v.x * inv * gn.x;
+            o.y = v.y * inv * gn.y;
+            o.z = v.z * inv * gn.z;
+            o.w = v.w * inv * gn.w;
             if (split) store_split4(xn, (size_t)gridDim.x * d, (size_t)r * d + i, o);
             else *reinterpret_cast<float4*>(xn + (size_t)r * d + i) = o;
         }

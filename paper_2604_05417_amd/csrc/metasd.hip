@@ -1116,6 +1116,18 @@ int attention_seg(metasd_ctx* c, const Model& M, int L, const Segs& sg) {
     }
 }
 
+// add the split-K partials to the residual rows and normalise: many rows of 2048 or 4096 columns go through the form that
+// keeps more requests in flight per CU (same arithmetic in the same order)
+template <typename T>
+void launch_addnorm_many(metasd_ctx* c, int R, float* h, const float* part, int ns, int D, const T* gain, float eps, float* xn, int split) {
+    if (R > MAX_ROWS && D == 4096)
+        hipLaunchKernelGGL((addnorm_rows_kernel<T, 4>), dim3(R), dim3(256), 0, c->stream, h, part, ns, (size_t)R * D, gain, eps, xn, split);
+    else if (R > MAX_ROWS && D == 2048)
+        hipLaunchKernelGGL((addnorm_rows_kernel<T, 2>), dim3(R), dim3(256), 0, c->stream, h, part, ns, (size_t)R * D, gain, eps, xn, split);
+    else
+        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(R), dim3(1024), 0, c->stream, h, part, ns, (size_t)R * D, D, gain, eps, xn, split);
+}
+
 // Forward of the block sg through model M; appends K/V of the valid rows.  logits == nullptr: none.
 // Otherwise the rows that carry logits are written to logits[(seq * out_seq_rows + out_row0 + j) * V]
 // (last_only: only the last valid row of each segment, at j = 0).
@@ -1138,8 +1150,7 @@ int forward_segs_t(metasd_ctx* c, Model& M, const Segs& sg, float* logits, int o
     hipLaunchKernelGGL(rope_table_seg_kernel, dim3(R), dim3(hd / 2), 0, st, sg, hd, d.rope_theta, c->d_rope());
     LAUNCH_CHECK(c, "rope_table (segments)");
     for (int L = 0; L < d.n_layers; ++L) {
-        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(R), dim3(1024), 0, st, h, part, ns, (size_t)R * D, D, (const T*)M.layer_w(L, 0),
-                           d.rms_eps, xn, split);
+        launch_addnorm_many<T>(c, R, h, part, ns, D, (const T*)M.layer_w(L, 0), d.rms_eps, xn, split);
         LAUNCH_CHECK(c, "addnorm");
         if ((rc = gemm_rows<T>(c, xn, D, R, D, M.layer_w(L, 1), DQ, M.layer_w(L, 2), DKV, M.layer_w(L, 3), DKV, &ns))) return rc;
         T* kc = (T*)M.kv + (size_t)L * 2 * plane;
@@ -1149,8 +1160,7 @@ int forward_segs_t(metasd_ctx* c, Model& M, const Segs& sg, float* logits, int o
         LAUNCH_CHECK(c, "rope_kv (segments)");
         if ((rc = attention_seg<T>(c, M, L, sg))) return rc;
         if ((rc = gemm_rows<T>(c, c->d_ao(), DQ, R, DQ, M.layer_w(L, 4), D, nullptr, 0, nullptr, 0, &ns))) return rc;
-        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(R), dim3(1024), 0, st, h, part, ns, (size_t)R * D, D, (const T*)M.layer_w(L, 5),
-                           d.rms_eps, xn, split);
+        launch_addnorm_many<T>(c, R, h, part, ns, D, (const T*)M.layer_w(L, 5), d.rms_eps, xn, split);
         LAUNCH_CHECK(c, "addnorm");
         if (d.act == METASD_SWIGLU) {
             if ((rc = gemm_rows<T>(c, xn, D, R, D, M.layer_w(L, 6), F, M.layer_w(L, 7), F, nullptr, 0, &ns))) return rc;
@@ -1165,8 +1175,7 @@ int forward_segs_t(metasd_ctx* c, Model& M, const Segs& sg, float* logits, int o
         if ((rc = gemm_rows<T>(c, c->d_act(), F, R, F, M.layer_w(L, 8), D, nullptr, 0, nullptr, 0, &ns))) return rc;
     }
     if (logits) {
-        hipLaunchKernelGGL(addnorm_kernel<T>, dim3(R), dim3(1024), 0, st, h, part, ns, (size_t)R * D, D, (const T*)M.final_norm(),
-                           d.rms_eps, xn, split);
+        launch_addnorm_many<T>(c, R, h, part, ns, D, (const T*)M.final_norm(), d.rms_eps, xn, split);
         LAUNCH_CHECK(c, "addnorm");
         if ((rc = gemm_rows<T>(c, xn, D, R, D, M.lm_head(), V, nullptr, 0, nullptr, 0, &ns))) return rc;
         hipLaunchKernelGGL(sum_partials_seg_kernel, dim3((V + 255) / 256, R), dim3(256), 0, st, (const float*)part, ns, (size_t)R * V, V,
