@@ -423,7 +423,7 @@ __device__ __forceinline__ void gemm_bf16_rows_body(const bf16_t* __restrict__ x
                 const int c = min(CST * st + (q >> 2), nc - 1);
                 const bf16_t* src = xh + (size_t)min(row, R - 1) * ldx + (size_t)(c0 + c) * 32 + (q & 3) * 8 + (term ? x_lo_off : (size_t)0);
                 const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + (unsigned)(((buf * NP + term * HP) * R16 + rg * 64) * 16));
-                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory", "m0");
             }
         };
         dma(0, 0);
