@@ -56,6 +56,23 @@ def test_sizes_and_validation(lib):
         bad = B._Config(3, 4, batch, 96, 1.0, 0, 1.0, 1)
         assert lib.metasd_workspace_bytes(C.byref(bad), C.byref(desc()), dr, C.byref(n)) == -1
     assert b"batch" in lib.metasd_last_error(None)
+    # drafter heads: the feature table (max_ctx x d_model fp32) and one estimate row per tree node come on top; one sequence only;
+    # streaming caches: one sequence only, sizes not negative
+    heads = B._Config(3, 4, 1, 96, 1.0, 0, 1.0, 1)
+    heads.feature_heads = 1
+    assert lib.metasd_workspace_bytes(C.byref(heads), C.byref(desc()), dr, C.byref(n)) == 0
+    d_model = desc().d_model
+    assert (96 + 16) * d_model * 4 <= n.value - one <= (96 + 16) * d_model * 4 + 2 * 256
+    heads.batch = 2
+    assert lib.metasd_workspace_bytes(C.byref(heads), C.byref(desc()), dr, C.byref(n)) == -1
+    heads.batch, heads.feature_heads = 1, 2
+    assert lib.metasd_workspace_bytes(C.byref(heads), C.byref(desc()), dr, C.byref(n)) == -1
+    stream = B._Config(3, 4, 2, 96, 1.0, 0, 1.0, 1)
+    stream.stream_window = 8
+    assert lib.metasd_workspace_bytes(C.byref(stream), C.byref(desc()), dr, C.byref(n)) == -1
+    stream.batch, stream.stream_sink = 1, -1
+    assert lib.metasd_workspace_bytes(C.byref(stream), C.byref(desc()), dr, C.byref(n)) == -1
+    assert lib.metasd_set_drafter_head(None, 0, None) == -1
     dr2 = (B._Desc * 3)(desc(n_layers=1), desc(n_layers=1, vocab=256), desc(n_layers=1))
     assert lib.metasd_workspace_bytes(C.byref(cfg), C.byref(desc()), dr2, C.byref(n)) == -1
     h = C.c_void_p()
