@@ -798,6 +798,15 @@ int forward_rows_residual(metasd_ctx* c, Model& M, int pos0, int m, float* logit
     hipLaunchKernelGGL(embed_rope_kernel<T>, dim3(m), dim3(256), 0, st, c->d_hist() + pos0, (const T*)M.w[0], D, h, pos0, hd, d.rope_theta,
                        c->d_rope(), c->tree ? *c->tree : TreeBlk{});
     LAUNCH_CHECK(c, "embed + rope table");
+    if (M.head) {
+        // a drafter head starts from W_fc . [embedding ; feature of the position before] instead of the embedding (as in forward_rows)
+        float* cat = (float*)c->d_act();
+        hipLaunchKernelGGL(feat_cat_kernel, dim3(m), dim3(256), 0, st, (const float*)h, (const float*)c->d_feat(),
+                           c->head_est ? (const float*)c->d_fest() : (const float*)nullptr, c->fsrc, pos0, D, cat, 1);
+        LAUNCH_CHECK(c, "feat_cat");
+        int dummy;
+        if ((rc = gemm<T>(c, cat, 2 * D, m, 2 * D, M.fc, D, nullptr, 0, nullptr, 0, h, &dummy, (size_t)m * 2 * D))) return rc;
+    }
     // first norm: a plain RMSNorm of the embedding rows (normalised x, no scaling downstream)
     hipLaunchKernelGGL(addnorm_kernel<T>, dim3(m), dim3(1024), 0, st, h, part, 0, (size_t)m * D, D, (const T*)M.layer_w(0, 0), d.rms_eps,
                        xn, 1);
@@ -956,7 +965,8 @@ int forward_blocks(metasd_ctx* c, Model& M, int pos0, int n, float* logits, bool
         // the short-block path never writes the finished residual rows: not for the target when its features are wanted
         const bool fused = c->fuse_small && fused_small_ok(M, m) && !(is_target && c->cfg.feature_heads);
         if (M.d.dtype != METASD_BF16) rc = forward_rows<float>(c, M, pos0 + done, m, lg, first_row);
-        else if (M.head) rc = forward_rows<bf16_t>(c, M, pos0 + done, m, lg, first_row);     // the step-by-step path carries the head's input projection
+        else if (M.head) rc = c->gemm_reduce ? forward_rows_residual(c, M, pos0 + done, m, lg, first_row)     // these two paths carry the head's
+                                             : forward_rows<bf16_t>(c, M, pos0 + done, m, lg, first_row);      // input projection
         else if (fused) rc = forward_rows_fused(c, M, pos0 + done, m, lg, first_row);
         else if (c->gemm_reduce) rc = forward_rows_residual(c, M, pos0 + done, m, lg, first_row);
         else rc = forward_rows<bf16_t>(c, M, pos0 + done, m, lg, first_row);
