@@ -49,7 +49,7 @@ def main():
     ap.add_argument("--layers", type=int, default=32, help="target layers (32 = the 7B shape; fewer is NOT the benchmark)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rounds", type=int, default=8)
-    ap.add_argument("--workload", default="c4", choices=["c4", "c5", "c3", "c2", "c4tree", "c4heads"],
+    ap.add_argument("--workload", default="c4", choices=["c4", "c5", "c3", "c2", "c4tree", "c4heads", "c4policies"],
                     help="c4 (default): the headline benchmark; c5: the batched configuration (32 sequences, gamma 7, KV context 4096); "
                          "c3: the 1B-shape GQA target with four early-exit drafters, real 512-token prefill; "
                          "c2: the accept kernel alone (64 rows x gamma 5 x vocab 32000); c4tree: the C4 models with multi-candidate "
@@ -73,6 +73,8 @@ def main():
         return bench_c3(args)
     if args.workload == "c4heads":
         return bench_c4_heads(args)
+    if args.workload == "c4policies":
+        return bench_c4_policies(args)
     if args.workload == "c4tree":
         return bench_c4_tree(args)
 
@@ -595,6 +597,76 @@ def bench_c4_heads(args):
            "roofline": None, "cpu_baseline": None, "detail": res}
     print(json.dumps(out))
     g.close()
+    return 0
+
+
+def bench_c4_policies(args):
+    """Side measurement: what the bandit is for.  The C4 workload (drafter heads exchanged every 32 generated tokens, so the
+    best drafter moves) run with every drafter fixed and with each selection policy of the library, same seed, same prompt,
+    same number of rounds: verified tokens/s and mean accepted length per policy."""
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU available; the MetaSD library has no CPU path")
+    import paper_2604_05417_amd as M
+    import workloads as W
+    dev = "cuda:0"
+    rounds = args.steps if args.steps != 64 else 192
+    cfg = W.config4(device=dev, n_layers=args.layers, ctx=args.ctx)
+    gamma = cfg["gamma"]
+    cfg["max_ctx"] = args.ctx + (gamma + 1) * (rounds + 8) + 16
+    td, tw = cfg["target"]
+    K = len(cfg["drafters"])
+    heads = [[M.pack_weight(h.contiguous()) for h in hk] for hk in cfg["heads"]]
+    head_index = 2 + 9 * cfg["drafters"][0][0]["n_layers"]
+    runs = [("fixed %d" % k, "ucb", k, {}) for k in range(K)] + [
+        ("ucb", "ucb", None, {}), ("ducb", "ducb", None, dict(policy_param=0.95)), ("swucb", "swucb", None, dict(policy_window=32)),
+        ("exp3", "exp3", None, dict(policy_param=0.1)), ("random", "random", None, {})]
+    res = {}
+    for name, policy, fixed, extra in runs:
+        g = M.MetaSD((td, tw), cfg["drafters"], gamma_max=gamma, max_ctx=cfg["max_ctx"], temperature=cfg["T"], seed=cfg["seed"],
+                     ucb_beta=cfg["beta"], policy=policy, **extra)
+        for i, (desc, kv) in enumerate([(td, g.kv_target)] + [(dd, g.kv_drafters[k]) for k, (dd, _) in enumerate(cfg["drafters"])]):
+            kk, vv = W.kv_fill(desc, args.ctx - 1, cfg["kv_seed"] + i, device=dev)
+            kv[:, 0, :, : args.ctx - 1] = kk
+            kv[:, 1, :, : args.ctx - 1] = vv
+        for k in range(K):
+            g.swap_weight(k, head_index, heads[k][0])
+        g.set_context(cfg["prompt"], kv_prefilled=True)
+        seg, new_tokens, accs, arms = 0, 0, [], [0] * K
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(rounds):
+            s_now = (new_tokens // cfg["seg_len"]) % 4
+            if s_now != seg:
+                for k in range(K):
+                    g.swap_weight(k, head_index, heads[k][s_now])
+                seg = s_now
+            k = g.bandit_select()
+            if fixed is not None:
+                k = fixed
+            g.draft(k, gamma)
+            g.verify(gamma)
+            n, tok, mask, bd = g.accept(gamma)
+            g.bandit_update(k, n, gamma, bd)
+            new_tokens += n + 1
+            accs.append(n)
+            arms[k] += 1
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t1
+        res[name] = {"tokens_per_s": new_tokens / dt, "mean_n_acc": float(np.mean(accs)), "ms_per_round": dt / rounds * 1e3, "arm_counts": arms}
+        log(f"[bench c4policies] {name:8s} {res[name]['tokens_per_s']:7.1f} tokens/s  mean N_acc {res[name]['mean_n_acc']:.3f}  arms {arms}")
+        g.close()
+        del g
+        torch.cuda.empty_cache()
+    best_fixed = max(res["fixed %d" % k]["tokens_per_s"] for k in range(K))
+    out = {"metric": "verified tokens/sec @1 GPU (7B-shape, per selection policy)", "value": res["ucb"]["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
+           "steps": rounds, "warmup": 0, "ms_per_step": res["ucb"]["ms_per_round"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"C4 models, KV context {args.ctx}, batch 1, gamma {gamma}, T={cfg['T']}, {rounds} rounds per policy from the same state; "
+                                  "drafter heads exchanged every 32 generated tokens (the best drafter moves)"},
+           "roofline": None, "cpu_baseline": None, "detail": {"per_policy": res, "best_fixed_tokens_per_s": best_fixed}}
+    print(json.dumps(out))
     return 0
 
 
