@@ -144,3 +144,26 @@ def test_config4_7b_shape_drafter_heads_full_size():
     st = ls.stats
     assert st["max_dp"] <= 3e-2 and st["max_dq"] <= 3e-2 and st["ties_shared"] <= 1, st
     g.close()
+
+
+@pytest.mark.parametrize("T", [0.0, 1.0])
+def test_head_catch_up_over_a_long_backlog(T):
+    """A head that sat out many rounds re-reads a backlog longer than one 16-row block (the feature rows of every block come
+    from the table the target's passes filled meanwhile), and a head chosen many times in a row re-reads the rows of its
+    own previous round every time; fp32, lock-step."""
+    cfg = W.config1()
+    cfg["max_ctx"] = 16 + 120
+    g, ot, od = build_heads(cfg, T, 0.03, mixed=True)
+    g.set_context(cfg["prompt"])
+    ls = LockStep(g, ot, od, cfg["prompt"], cfg["gamma"], T, cfg["seed"], cfg["beta"], logit_tol=1e-4)
+    order = [1] * 9 + [0] + [2] * 6 + [0, 0, 0, 2]
+    backlog = []
+    for k in order:
+        if k != 1:
+            backlog.append(ls.l - ls.c[k])
+        ls.round(k)
+    st = ls.stats
+    assert max(backlog) > 16, backlog
+    assert st["mismatch_own"] == 0 and st["ties_own"] + st["ties_shared"] <= 1, st
+    assert st["max_dp"] <= 1e-4 and st["max_dq"] <= 1e-4 and st["max_df"] <= 1e-4
+    g.close()
